@@ -1,0 +1,171 @@
+// C ABI (include/bpc.h): argument validation on the host, then dispatch to the kernel
+// launchers.  Nothing here allocates or synchronises.
+#include <hip/hip_runtime.h>
+#include "kernels.hpp"
+
+using namespace bpc;
+
+static thread_local int g_last_hip_error = 0;
+
+static bpc_status_t hip_status(hipError_t e) {
+  if (e == hipSuccess) return BPC_OK;
+  g_last_hip_error = (int)e;
+  return BPC_ERR_HIP;
+}
+
+static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+extern "C" {
+
+uint64_t bpc_partition_k(const bpc_params_t *params, uint64_t d) {
+  if (!params_valid(params) || d == 0) return 0;
+  if (params->kind != BPC_TOPK && params->kind != BPC_RANDK) return 0;
+  return k_rule(params->k_ratio, d);
+}
+
+size_t bpc_partition_stride(const bpc_params_t *params) {
+  if (!params_valid(params)) return 0;
+  return stride_of(params);
+}
+
+size_t bpc_payload_bytes(const bpc_params_t *params, uint64_t D) {
+  if (!params_valid(params) || D == 0) return 0;
+  return (size_t)cdiv(D, params->part_elems) * stride_of(params);
+}
+
+size_t bpc_workspace_bytes(const bpc_params_t *params, uint64_t D, int n) {
+  if (!params_valid(params) || n < 1 || n > kMaxWorkers) return 0;
+  if (D == 0) return 256;
+  return ws_layout(params, D).total;
+}
+
+static bpc_status_t check_size(uint64_t D) {
+  // element offsets inside kernels are 64 bit, tile and partition counts 32 bit
+  return D / kTile >= 0x7fffffffull ? BPC_ERR_UNSUPPORTED : BPC_OK;
+}
+
+static hipError_t encode(const Geo &g, const bpc_params_t &prm, const bpc_params_t *in_prm, const Source &src,
+                         uint8_t *payload, const Workspace &ws, hipStream_t stream) {
+  switch (prm.kind) {
+    case BPC_IDENTITY: return identity_encode(g, prm, src, payload, ws, stream);
+    case BPC_SIGN: return sign_encode(g, prm, src, payload, ws, stream);
+    case BPC_TOPK: return topk_encode(g, prm, in_prm, src, payload, ws, stream);
+    case BPC_RANDK: return randk_encode(g, prm, in_prm, src, payload, ws, stream);
+    default: return dither_encode(g, prm, src, payload, ws, stream);
+  }
+}
+
+bpc_status_t bpc_compress(const bpc_params_t *params, const void *grad, bpc_dtype_t dtype, float *residual,
+                          uint64_t D, void *payload, void *ws, size_t ws_bytes, void *hip_stream) {
+  if (!params_valid(params)) return BPC_ERR_INVALID_ARG;
+  if (dtype != BPC_F32 && dtype != BPC_F16) return BPC_ERR_INVALID_ARG;
+  if (D == 0) return BPC_OK;
+  if (!grad || !payload) return BPC_ERR_INVALID_ARG;
+  if (check_size(D) != BPC_OK) return BPC_ERR_UNSUPPORTED;
+  if (!aligned16(grad) || !aligned16(residual) || !aligned16(payload) || !aligned16(ws) ||
+      !aligned16(params->norm_override))
+    return BPC_ERR_ALIGNMENT;
+  WsLayout lay = ws_layout(params, D);
+  if (!ws || ws_bytes < lay.total) return BPC_ERR_WORKSPACE;
+  Geo g = make_geo(params, D);
+  Source src{};
+  src.grad = grad;
+  src.dtype = (int)dtype;
+  src.residual = residual;
+  Workspace w{(uint8_t *)ws, lay};
+  return hip_status(encode(g, *params, nullptr, src, (uint8_t *)payload, w, (hipStream_t)hip_stream));
+}
+
+bpc_status_t bpc_decompress(const bpc_params_t *params, const void *payload, uint64_t D, float *out,
+                            void *hip_stream) {
+  if (!params_valid(params)) return BPC_ERR_INVALID_ARG;
+  if (D == 0) return BPC_OK;
+  if (!payload || !out) return BPC_ERR_INVALID_ARG;
+  if (check_size(D) != BPC_OK) return BPC_ERR_UNSUPPORTED;
+  if (!aligned16(payload) || !aligned16(out)) return BPC_ERR_ALIGNMENT;
+  Geo g = make_geo(params, D);
+  return hip_status(decode_dense(g, *params, (const uint8_t *)payload, out, (hipStream_t)hip_stream));
+}
+
+bpc_status_t bpc_server_aggregate(const bpc_params_t *in, const void *const *payloads, int n,
+                                  const bpc_params_t *out, float *server_residual, uint64_t D,
+                                  void *out_payload, void *ws, size_t ws_bytes, void *hip_stream) {
+  if (!params_valid(out) || !in || n < 1) return BPC_ERR_INVALID_ARG;
+  if (n > kMaxWorkers) return BPC_ERR_UNSUPPORTED;
+  for (int i = 0; i < n; ++i) {
+    if (!params_valid(&in[i])) return BPC_ERR_INVALID_ARG;
+    if (in[i].kind != out->kind || in[i].part_elems != out->part_elems) return BPC_ERR_INVALID_ARG;
+    if ((out->kind == BPC_TOPK || out->kind == BPC_RANDK) && in[i].k_ratio != out->k_ratio)
+      return BPC_ERR_INVALID_ARG;
+    if (out->kind == BPC_DITHER && in[i].levels != out->levels) return BPC_ERR_INVALID_ARG;
+  }
+  if (D == 0) return BPC_OK;
+  if (!payloads || !out_payload) return BPC_ERR_INVALID_ARG;
+  for (int i = 0; i < n; ++i)
+    if (!payloads[i]) return BPC_ERR_INVALID_ARG;
+  if (check_size(D) != BPC_OK) return BPC_ERR_UNSUPPORTED;
+  if (!aligned16(server_residual) || !aligned16(out_payload) || !aligned16(ws) || !aligned16(out->norm_override))
+    return BPC_ERR_ALIGNMENT;
+  for (int i = 0; i < n; ++i)
+    if (!aligned16(payloads[i])) return BPC_ERR_ALIGNMENT;
+  WsLayout lay = ws_layout(out, D);
+  if (!ws || ws_bytes < lay.total) return BPC_ERR_WORKSPACE;
+  Geo g = make_geo(out, D);
+  Source src{};
+  src.grad = nullptr;
+  src.residual = server_residual;
+  src.msgs.n = n;
+  src.msgs.inv_n = 1.0f / (float)n;
+  for (int i = 0; i < n; ++i) {
+    src.msgs.ptr[i] = (const uint8_t *)payloads[i];
+    src.msgs.seed[i] = in[i].seed;
+    src.msgs.stream_id[i] = in[i].stream_id;
+  }
+  Workspace w{(uint8_t *)ws, lay};
+  return hip_status(encode(g, *out, in, src, (uint8_t *)out_payload, w, (hipStream_t)hip_stream));
+}
+
+bpc_status_t bpc_adaptive_update(const bpc_params_t *params, const void *payload, uint64_t D, float *param,
+                                 float *m, float *v, const bpc_opt_t *opt, void *ws, size_t ws_bytes,
+                                 void *hip_stream) {
+  if (!params_valid(params) || !opt) return BPC_ERR_INVALID_ARG;
+  if (opt->kind != BPC_OPT_LANS && opt->kind != BPC_OPT_ADAM) return BPC_ERR_INVALID_ARG;
+  if (!(opt->beta1 > 0.0f && opt->beta1 < 1.0f) || !(opt->beta2 > 0.0f && opt->beta2 < 1.0f) ||
+      !(opt->eps > 0.0f) || !(opt->bias_corr1 > 0.0f) || !(opt->bias_corr2 > 0.0f) ||
+      !(opt->phi_lo <= opt->phi_hi))
+    return BPC_ERR_INVALID_ARG;
+  if (opt->kind == BPC_OPT_LANS && opt->block_offsets && opt->n_blocks == 0) return BPC_ERR_INVALID_ARG;
+  if (D == 0) return BPC_OK;
+  if (!payload || !param || !m || !v) return BPC_ERR_INVALID_ARG;
+  if (check_size(D) != BPC_OK) return BPC_ERR_UNSUPPORTED;
+  if (!aligned16(payload) || !aligned16(param) || !aligned16(m) || !aligned16(v) || !aligned16(ws) ||
+      !aligned16(opt->block_offsets))
+    return BPC_ERR_ALIGNMENT;
+  WsLayout lay = ws_layout(params, D);
+  size_t need = lay.total;
+  if (opt->kind == BPC_OPT_LANS && opt->block_offsets) {
+    size_t with_blocks = lay.norms + sizeof(double) * 3 * (size_t)opt->n_blocks;
+    if (with_blocks > need) need = with_blocks;
+  }
+  if (!ws || ws_bytes < need) return BPC_ERR_WORKSPACE;
+  Geo g = make_geo(params, D);
+  Workspace w{(uint8_t *)ws, lay};
+  return hip_status(adaptive_update(g, *params, (const uint8_t *)payload, param, m, v, *opt, w,
+                                    (hipStream_t)hip_stream));
+}
+
+const char *bpc_status_string(bpc_status_t status) {
+  switch (status) {
+    case BPC_OK: return "ok";
+    case BPC_ERR_INVALID_ARG: return "invalid argument";
+    case BPC_ERR_UNSUPPORTED: return "unsupported configuration";
+    case BPC_ERR_WORKSPACE: return "workspace missing or too small";
+    case BPC_ERR_ALIGNMENT: return "device pointer not 16-byte aligned";
+    case BPC_ERR_HIP: return "HIP call failed";
+    default: return "unknown status";
+  }
+}
+
+int bpc_last_hip_error(void) { return g_last_hip_error; }
+
+}  // extern "C"

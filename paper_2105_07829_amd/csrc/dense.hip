@@ -1,0 +1,143 @@
+// Identity "compressor" (with it Algorithms 3 and 4 reduce to plain gradient averaging,
+// Algorithm 1), the dense decode of every message kind, and a zero-fill kernel.
+#include "sources.hpp"
+
+namespace bpc {
+
+__global__ __launch_bounds__(kThreads) void fill_zero_kernel(uint32_t *ptr, size_t n_words) {
+  size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
+  const size_t step = (size_t)gridDim.x * kThreads;
+  const size_t n16 = n_words / 4;
+  uint4 *p16 = reinterpret_cast<uint4 *>(ptr);
+  for (size_t q = i; q < n16; q += step) p16[q] = make_uint4(0, 0, 0, 0);
+  for (size_t w = n16 * 4 + i; w < n_words; w += step) ptr[w] = 0;
+}
+
+// `ptr` 16-byte aligned, `bytes` a multiple of 4; nothing past ptr + bytes is written.
+hipError_t fill_zero(void *ptr, size_t bytes, hipStream_t stream) {
+  size_t n_words = bytes / 4;
+  if (n_words == 0) return hipSuccess;
+  size_t blocks = cdiv(cdiv(n_words, 4), kThreads);
+  if (blocks > 4096) blocks = 4096;
+  fill_zero_kernel<<<(uint32_t)blocks, kThreads, 0, stream>>>((uint32_t *)ptr, n_words);
+  return hipGetLastError();
+}
+
+template <class SRC>
+__global__ __launch_bounds__(kThreads) void identity_encode_kernel(Geo g, SRC src, uint8_t *payload,
+                                                                   float *residual) {
+  __shared__ float lds[SRC::kLdsFloats];
+  const uint32_t p = blockIdx.x / g.tiles_per_part;
+  const uint32_t tile = blockIdx.x % g.tiles_per_part;
+  const uint32_t d = g.part_size(p);
+  src.begin(g, p, lds);
+  uint8_t *rec = payload + (uint64_t)p * g.stride;
+  float *vals = reinterpret_cast<float *>(rec + kHeaderBytes);
+  if (tile == 0 && threadIdx.x < 4) reinterpret_cast<uint32_t *>(rec)[threadIdx.x] = 0;
+  const uint64_t base = g.part_base(p);
+#pragma unroll
+  for (int c = 0; c < kTile / kThreads; ++c) {
+    uint32_t j = tile * kTile + c * kThreads + threadIdx.x;
+    if (j < d) {
+      float v = src.at(g, p, j, lds);
+      vals[j] = v;
+      if (residual) residual[base + j] = v - v;
+    }
+  }
+}
+
+hipError_t identity_encode(const Geo &g, const bpc_params_t &, const Source &src, uint8_t *payload,
+                           const Workspace &, hipStream_t stream) {
+  auto make_server = [&] { return IdentityMsgSource{src.msgs, src.residual, g.stride}; };
+  return with_source(src, make_server, [&](auto s) -> hipError_t {
+    identity_encode_kernel<decltype(s)><<<g.n_tiles, kThreads, 0, stream>>>(g, s, payload, src.residual);
+    return hipGetLastError();
+  });
+}
+
+// Element-wise decode of the bit-packed kinds and of the identity record.
+__global__ __launch_bounds__(kThreads) void decode_packed_kernel(Geo g, int kind, uint32_t levels,
+                                                                 const uint8_t *payload, float *out) {
+  const uint32_t p = blockIdx.x / g.tiles_per_part;
+  const uint32_t tile = blockIdx.x % g.tiles_per_part;
+  const uint32_t d = g.part_size(p);
+  const uint8_t *rec = payload + (uint64_t)p * g.stride;
+  const float scale = *reinterpret_cast<const float *>(rec);
+  const uint32_t *words = reinterpret_cast<const uint32_t *>(rec + kHeaderBytes);
+  const uint64_t base = g.part_base(p);
+#pragma unroll
+  for (int c = 0; c < kTile / kThreads; ++c) {
+    uint32_t j = tile * kTile + c * kThreads + threadIdx.x;
+    if (j >= d) continue;
+    float v;
+    if (kind == BPC_SIGN) {
+      v = ((words[j >> 5] >> (j & 31)) & 1u) ? -scale : scale;
+    } else if (kind == BPC_DITHER) {
+      uint32_t nib = (words[j >> 3] >> (4 * (j & 7))) & 15u;
+      float mag = (scale * (float)(nib & 7u)) / (float)levels;
+      v = (nib & 8u) ? -mag : mag;
+    } else {
+      v = __uint_as_float(words[j]);
+    }
+    out[base + j] = v;
+  }
+}
+
+// Top-k: out[idx_t] = val_t.  `out` was zero-filled before.
+__global__ __launch_bounds__(kThreads) void decode_topk_kernel(Geo g, const uint8_t *payload, float *out) {
+  const uint32_t p = blockIdx.y;
+  const uint32_t d = g.part_size(p);
+  const uint8_t *rec = payload + (uint64_t)p * g.stride;
+  uint32_t k = *reinterpret_cast<const uint32_t *>(rec);
+  k = k > g.k_cap ? g.k_cap : k;
+  const uint32_t *idx = reinterpret_cast<const uint32_t *>(rec + kHeaderBytes);
+  const float *val = reinterpret_cast<const float *>(rec + kHeaderBytes + 4 * ru4(g.k_cap));
+  const uint64_t base = g.part_base(p);
+  for (uint32_t t = blockIdx.x * kThreads + threadIdx.x; t < k; t += gridDim.x * kThreads) {
+    uint32_t j = idx[t];
+    if (j < d) out[base + j] = val[t];
+  }
+}
+
+// Random-k: out[idx_t] += scale * val_t with idx_t regenerated from the Philox stream.
+// Repeated indices add equal values, so the order of the atomic adds does not matter.
+__global__ __launch_bounds__(kThreads) void decode_randk_kernel(Geo g, const uint8_t *payload, float *out,
+                                                                float value_scale, uint64_t seed,
+                                                                uint64_t stream_id) {
+  const uint32_t p = blockIdx.y;
+  const uint32_t d = g.part_size(p);
+  const uint8_t *rec = payload + (uint64_t)p * g.stride;
+  uint32_t k = *reinterpret_cast<const uint32_t *>(rec);
+  k = k > g.k_cap ? g.k_cap : k;
+  const float *val = reinterpret_cast<const float *>(rec + kHeaderBytes);
+  const float scale = value_scale >= 0.0f ? value_scale : (float)d / (float)k;
+  const uint64_t base = g.part_base(p);
+  const Philox rng(seed, stream_id, p);
+  for (uint32_t t = blockIdx.x * kThreads + threadIdx.x; t < k; t += gridDim.x * kThreads) {
+    uint32_t j = (uint32_t)(((uint64_t)rng.word(t) * d) >> 32);
+    atomicAdd(out + base + j, scale * val[t]);
+  }
+}
+
+hipError_t scatter_add_sparse(const Geo &g, const bpc_params_t &prm, const uint8_t *payload, float *out,
+                              hipStream_t stream) {
+  dim3 grid((uint32_t)cdiv(g.k_cap, kThreads), g.P);
+  if (prm.kind == BPC_TOPK)
+    decode_topk_kernel<<<grid, kThreads, 0, stream>>>(g, payload, out);
+  else
+    decode_randk_kernel<<<grid, kThreads, 0, stream>>>(g, payload, out, prm.value_scale, prm.seed, prm.stream_id);
+  return hipGetLastError();
+}
+
+hipError_t decode_dense(const Geo &g, const bpc_params_t &prm, const uint8_t *payload, float *out,
+                        hipStream_t stream) {
+  if (prm.kind == BPC_TOPK || prm.kind == BPC_RANDK) {
+    hipError_t e = fill_zero(out, sizeof(float) * g.D, stream);
+    if (e != hipSuccess) return e;
+    return scatter_add_sparse(g, prm, payload, out, stream);
+  }
+  decode_packed_kernel<<<g.n_tiles, kThreads, 0, stream>>>(g, prm.kind, prm.levels, payload, out);
+  return hipGetLastError();
+}
+
+}  // namespace bpc

@@ -1,0 +1,112 @@
+// Device helpers shared by the kernels: Philox4x32-10, fixed-order reductions,
+// gradient loads with exact fp16 widening.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <stdint.h>
+
+namespace bpc {
+
+// Philox4x32-10 (Salmon et al., SC'11).  One 64-bit multiply-add yields both halves of a product.
+struct Philox {
+  uint32_t k0, k1, c1, c2, c3;
+  __device__ Philox(uint64_t seed, uint64_t stream_id, uint32_t partition)
+      : k0((uint32_t)seed), k1((uint32_t)(seed >> 32)), c1(partition), c2((uint32_t)stream_id),
+        c3((uint32_t)(stream_id >> 32)) {}
+  __device__ void block(uint32_t blk, uint32_t out[4]) const {
+    uint32_t a = blk, b = c1, c = c2, d = c3, ka = k0, kb = k1;
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+      uint64_t p0 = (uint64_t)0xD2511F53u * a;
+      uint64_t p1 = (uint64_t)0xCD9E8D57u * c;
+      uint32_t na = (uint32_t)(p1 >> 32) ^ b ^ ka;
+      uint32_t nc = (uint32_t)(p0 >> 32) ^ d ^ kb;
+      b = (uint32_t)p1;
+      d = (uint32_t)p0;
+      a = na;
+      c = nc;
+      ka += 0x9E3779B9u;
+      kb += 0xBB67AE85u;
+    }
+    out[0] = a; out[1] = b; out[2] = c; out[3] = d;
+  }
+  __device__ uint32_t word(uint32_t t) const {
+    uint32_t o[4];
+    block(t >> 2, o);
+    uint32_t s = t & 3;
+    return s == 0 ? o[0] : s == 1 ? o[1] : s == 2 ? o[2] : o[3];
+  }
+};
+
+__device__ inline float load_grad(const float *g, uint64_t i) { return g[i]; }
+__device__ inline float load_grad(const __half *g, uint64_t i) { return __half2float(g[i]); }
+
+// Sum over the 64 lanes in a fixed butterfly order (same bits on every run).
+__device__ inline double wave_sum(double x) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off, 64);
+  return x;
+}
+__device__ inline float wave_max(float x) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) x = fmaxf(x, __shfl_xor(x, off, 64));
+  return x;
+}
+__device__ inline uint32_t wave_sum_u32(uint32_t x) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off, 64);
+  return x;
+}
+
+// Workgroup sum in a fixed order; the result is valid in thread 0.  `scratch` holds one
+// double per wave.
+template <int THREADS>
+__device__ inline double block_sum(double x, double *scratch) {
+  x = wave_sum(x);
+  int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  __syncthreads();
+  if (lane == 0) scratch[wave] = x;
+  __syncthreads();
+  double t = 0.0;
+  if (threadIdx.x == 0) {
+#pragma unroll
+    for (int w = 0; w < THREADS / 64; ++w) t += scratch[w];
+  }
+  return t;
+}
+template <int THREADS>
+__device__ inline float block_max(float x, float *scratch) {
+  x = wave_max(x);
+  int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  __syncthreads();
+  if (lane == 0) scratch[wave] = x;
+  __syncthreads();
+  float t = 0.0f;
+  if (threadIdx.x == 0) {
+#pragma unroll
+    for (int w = 0; w < THREADS / 64; ++w) t = fmaxf(t, scratch[w]);
+  }
+  return t;
+}
+
+// Exclusive prefix sum over the workgroup's threads (Hillis-Steele in LDS).  Returns the
+// exclusive prefix of `x`; *total receives the sum over all threads.
+template <int THREADS>
+__device__ inline uint32_t block_exclusive_scan(uint32_t x, uint32_t *lds /*THREADS*/, uint32_t *total) {
+  int t = threadIdx.x;
+  __syncthreads();
+  lds[t] = x;
+  __syncthreads();
+  for (int off = 1; off < THREADS; off <<= 1) {
+    uint32_t add = t >= off ? lds[t - off] : 0;
+    __syncthreads();
+    lds[t] += add;
+    __syncthreads();
+  }
+  uint32_t incl = lds[t];
+  *total = lds[THREADS - 1];
+  __syncthreads();
+  return incl - x;
+}
+
+}  // namespace bpc

@@ -1,0 +1,139 @@
+// Linear dithering (the stochastic multi-level quantiser the paper cites for its "dithering"
+// compressors, Section 3.2): with a = s|v_j|/nu the level is floor(a)+1 with probability
+// a-floor(a), else floor(a).  Message: nu once, then one nibble (sign, level) per element.
+// Residual update as in Algorithm 4.  Three launches per call:
+//   reduce : per-tile partial of sum v_j^2 (f64) or max |v_j|
+//   finish : nu per partition -> record header
+//   apply  : levels from Philox draws, packed nibbles, residual_j = v_j - decode_j
+#include "sources.hpp"
+
+namespace bpc {
+
+constexpr int kPerThread = 8;                       // one message word per thread
+constexpr int kRowElems = kThreads * kPerThread;    // 2048
+constexpr int kRows = kTile / kRowElems;            // 2
+
+template <class SRC>
+__global__ __launch_bounds__(kThreads) void dither_reduce_kernel(Geo g, SRC src, double *partials, int linf) {
+  __shared__ float lds[SRC::kLdsFloats];
+  __shared__ double red[kThreads / 64];
+  __shared__ float redf[kThreads / 64];
+  const uint32_t p = blockIdx.x / g.tiles_per_part;
+  const uint32_t tile = blockIdx.x % g.tiles_per_part;
+  const uint32_t d = g.part_size(p);
+  src.begin(g, p, lds);
+  double acc = 0.0;
+  float mx = 0.0f;
+#pragma unroll
+  for (int c = 0; c < kTile / kThreads; ++c) {
+    uint32_t j = tile * kTile + c * kThreads + threadIdx.x;
+    float v = j < d ? src.at(g, p, j, lds) : 0.0f;
+    acc = fma((double)v, (double)v, acc);  // the product of two f32 is exact in f64
+    mx = fmaxf(mx, fabsf(v));
+  }
+  if (linf) {
+    float m = block_max<kThreads>(mx, redf);
+    if (threadIdx.x == 0) partials[blockIdx.x] = (double)m;
+  } else {
+    double s = block_sum<kThreads>(acc, red);
+    if (threadIdx.x == 0) partials[blockIdx.x] = s;
+  }
+}
+
+__global__ __launch_bounds__(64) void dither_finish_kernel(Geo g, const double *partials, const float *override,
+                                                           int linf, uint8_t *payload) {
+  const uint32_t p = blockIdx.x;
+  const uint32_t d = g.part_size(p);
+  const uint32_t n_tiles = (uint32_t)cdiv(d, kTile);
+  float nu;
+  if (override) {
+    nu = override[p];
+  } else if (linf) {
+    float m = 0.0f;
+    for (uint32_t t = threadIdx.x; t < n_tiles; t += 64)
+      m = fmaxf(m, (float)partials[(uint64_t)p * g.tiles_per_part + t]);
+    nu = wave_max(m);
+  } else {
+    double s = 0.0;
+    for (uint32_t t = threadIdx.x; t < n_tiles; t += 64) s += partials[(uint64_t)p * g.tiles_per_part + t];
+    s = wave_sum(s);
+    nu = (float)sqrt(s);
+  }
+  if (threadIdx.x == 0) {
+    uint32_t *hdr = reinterpret_cast<uint32_t *>(payload + (uint64_t)p * g.stride);
+    hdr[0] = __float_as_uint(nu);
+    hdr[1] = 0; hdr[2] = 0; hdr[3] = 0;
+  }
+}
+
+// Level and residual of one element; `r` is the element's random word.
+__device__ inline uint32_t dither_one(float v, float nu, uint32_t s, uint32_t r, float *resid) {
+  if (!(nu > 0.0f)) {
+    *resid = v;
+    return 0u;
+  }
+  float a = (fabsf(v) * (float)s) / nu;
+  float l = floorf(a);
+  float f = a - l;
+  float u = (float)(r >> 8) * 0x1p-24f;
+  uint32_t level = (uint32_t)l + (u < f ? 1u : 0u);
+  level = level > s ? s : level;
+  float mag = (nu * (float)level) / (float)s;
+  *resid = v - (v < 0.0f ? -mag : mag);
+  return (v < 0.0f ? 8u : 0u) | level;
+}
+
+template <class SRC>
+__global__ __launch_bounds__(kThreads) void dither_apply_kernel(Geo g, SRC src, uint8_t *payload, float *residual,
+                                                                uint32_t levels, uint64_t seed,
+                                                                uint64_t stream_id) {
+  __shared__ float lds[SRC::kLdsFloats];
+  const uint32_t p = blockIdx.x / g.tiles_per_part;
+  const uint32_t tile = blockIdx.x % g.tiles_per_part;
+  const uint32_t d = g.part_size(p);
+  src.begin(g, p, lds);
+  uint8_t *rec = payload + (uint64_t)p * g.stride;
+  const float nu = *reinterpret_cast<const float *>(rec);
+  uint32_t *nibs = reinterpret_cast<uint32_t *>(rec + kHeaderBytes);
+  const uint32_t n_words = (uint32_t)ru4(cdiv(d, 8));
+  const uint64_t base = g.part_base(p);
+  const Philox rng(seed, stream_id, p);
+#pragma unroll
+  for (int row = 0; row < kRows; ++row) {
+    const uint32_t j0 = tile * kTile + row * kRowElems + threadIdx.x * kPerThread;
+    if ((j0 >> 3) >= n_words) continue;
+    uint32_t rnd[8];
+    rng.block(j0 >> 2, rnd);
+    rng.block((j0 >> 2) + 1, rnd + 4);
+    uint32_t word = 0;
+#pragma unroll
+    for (int e = 0; e < kPerThread; ++e) {
+      uint32_t j = j0 + e;
+      if (j < d) {
+        float r;
+        float v = src.at(g, p, j, lds);
+        uint32_t nib = dither_one(v, nu, levels, rnd[e], &r);
+        word |= nib << (4 * e);
+        if (residual) residual[base + j] = r;
+      }
+    }
+    nibs[j0 >> 3] = word;
+  }
+}
+
+hipError_t dither_encode(const Geo &g, const bpc_params_t &prm, const Source &src, uint8_t *payload,
+                         const Workspace &ws, hipStream_t stream) {
+  double *partials = ws.at<double>(ws.lay.partials);
+  const int linf = prm.norm == BPC_NORM_LINF;
+  auto make_server = [&] { return DitherMsgSource{src.msgs, src.residual, g.stride, prm.levels}; };
+  return with_source(src, make_server, [&](auto s) -> hipError_t {
+    using S = decltype(s);
+    if (!prm.norm_override) dither_reduce_kernel<S><<<g.n_tiles, kThreads, 0, stream>>>(g, s, partials, linf);
+    dither_finish_kernel<<<g.P, 64, 0, stream>>>(g, partials, prm.norm_override, linf, payload);
+    dither_apply_kernel<S><<<g.n_tiles, kThreads, 0, stream>>>(g, s, payload, src.residual, prm.levels, prm.seed,
+                                                               prm.stream_id);
+    return hipGetLastError();
+  });
+}
+
+}  // namespace bpc

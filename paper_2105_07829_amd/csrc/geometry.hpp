@@ -1,0 +1,120 @@
+// Host+device description of how a flat gradient is cut into partitions and
+// how a call's device workspace is carved up.  Record format: include/bpc.h.
+#pragma once
+#include <stdint.h>
+#include <stddef.h>
+#include <math.h>
+#include "../../include/bpc.h"
+
+#if defined(__HIPCC__)
+#define BPC_HD __host__ __device__
+#else
+#define BPC_HD
+#endif
+
+namespace bpc {
+
+constexpr int kMaxWorkers = 64;      // most worker messages one aggregate call accepts
+constexpr int kTile = 4096;          // elements one workgroup handles in the streaming kernels
+constexpr int kThreads = 256;        // workgroup size of the streaming kernels
+constexpr uint32_t kHeaderBytes = 16;
+
+BPC_HD inline uint64_t ru4(uint64_t x) { return (x + 3) / 4 * 4; }
+BPC_HD inline uint64_t cdiv(uint64_t a, uint64_t b) { return (a + b - 1) / b; }
+
+// Everything a kernel needs to find partition p and its record.
+// k = max(1, floor(ratio*d)), never above d; exact in f64 for d < 2^31.
+BPC_HD inline uint64_t k_rule(double ratio, uint64_t d) {
+  if (d == 0) return 0;
+  uint64_t k = (uint64_t)floor(ratio * (double)d);
+  if (k < 1) k = 1;
+  if (k > d) k = d;
+  return k;
+}
+
+struct Geo {
+  uint64_t D;            // elements of the flat gradient
+  uint64_t part_elems;   // elements of a full partition
+  uint32_t P;            // number of partitions
+  uint32_t tiles_per_part;  // kTile-sized tiles of a full partition
+  uint32_t n_tiles;      // tiles over all partitions (last partition may have fewer)
+  uint32_t k_cap;        // kept elements of a full partition (TOPK/RANDK), else 0
+  uint64_t stride;       // bytes between records
+  double k_ratio;
+
+  BPC_HD uint64_t part_base(uint32_t p) const { return (uint64_t)p * part_elems; }
+  BPC_HD uint32_t part_size(uint32_t p) const {
+    uint64_t rest = D - (uint64_t)p * part_elems;
+    return (uint32_t)(rest < part_elems ? rest : part_elems);
+  }
+};
+
+inline bool params_valid(const bpc_params_t *p) {
+  if (!p) return false;
+  if (p->part_elems == 0 || p->part_elems % 1024 != 0 || p->part_elems > (1ull << 31)) return false;
+  switch (p->kind) {
+    case BPC_IDENTITY: case BPC_SIGN: return true;
+    case BPC_TOPK: case BPC_RANDK: return p->k_ratio > 0.0 && p->k_ratio <= 1.0;
+    case BPC_DITHER:
+      return p->levels >= 1 && p->levels <= 7 && (p->norm == BPC_NORM_L2 || p->norm == BPC_NORM_LINF);
+    default: return false;
+  }
+}
+
+inline size_t stride_of(const bpc_params_t *p) {
+  uint64_t d = p->part_elems, words = 0;
+  switch (p->kind) {
+    case BPC_IDENTITY: words = ru4(d); break;
+    case BPC_SIGN:     words = ru4(cdiv(d, 32)); break;
+    case BPC_DITHER:   words = ru4(cdiv(d, 8)); break;
+    case BPC_TOPK:     words = 2 * ru4(k_rule(p->k_ratio, d)); break;
+    case BPC_RANDK:    words = ru4(k_rule(p->k_ratio, d)); break;
+  }
+  return (size_t)(kHeaderBytes + 4 * words);
+}
+
+inline Geo make_geo(const bpc_params_t *p, uint64_t D) {
+  Geo g;
+  g.D = D;
+  g.part_elems = p->part_elems;
+  g.P = (uint32_t)cdiv(D, p->part_elems);
+  g.tiles_per_part = (uint32_t)cdiv(p->part_elems, kTile);
+  uint64_t last = D - (uint64_t)(g.P ? g.P - 1 : 0) * p->part_elems;
+  g.n_tiles = g.P ? (g.P - 1) * g.tiles_per_part + (uint32_t)cdiv(last, kTile) : 0;
+  g.k_cap = (p->kind == BPC_TOPK || p->kind == BPC_RANDK) ? (uint32_t)k_rule(p->k_ratio, p->part_elems) : 0;
+  g.stride = stride_of(p);
+  g.k_ratio = p->k_ratio;
+  return g;
+}
+
+// Device workspace of one call.  Offsets in bytes from the workspace base, each
+// a multiple of 256.  Regions a kind does not use have size 0.
+struct WsLayout {
+  size_t partials;   // double[n_tiles]: per-tile partial norms
+  size_t dense;      // float[D]: q / Delta / decoded message when no caller buffer can hold it
+  size_t hist;       // u32[P*4096]: top-k radix histograms (2048 + 1024 + 1024 bins)
+  size_t state;      // u32[P*8]: top-k selection state
+  size_t tilecnt;    // u32[2*n_tiles]: per-tile (greater, equal) counts, then offsets
+  size_t norms;      // double[3*P]: LANS block norms when blocks are the partitions
+  size_t total;
+};
+
+inline WsLayout ws_layout(const bpc_params_t *p, uint64_t D) {
+  Geo g = make_geo(p, D);
+  WsLayout w;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off += (bytes + 255) / 256 * 256; return o; };
+  bool sparse = p->kind == BPC_TOPK || p->kind == BPC_RANDK;
+  w.partials = take(sizeof(double) * (size_t)g.n_tiles);
+  w.dense = take(sparse ? sizeof(float) * (size_t)D : 0);
+  w.hist = take(p->kind == BPC_TOPK ? sizeof(uint32_t) * 4096 * (size_t)g.P : 0);
+  w.state = take(p->kind == BPC_TOPK ? sizeof(uint32_t) * 8 * (size_t)g.P : 0);
+  w.tilecnt = take(p->kind == BPC_TOPK ? sizeof(uint32_t) * 2 * (size_t)g.n_tiles : 0);
+  w.norms = take(sizeof(double) * 3 * (size_t)g.P);
+  w.total = off;
+  return w;
+}
+
+BPC_HD inline uint64_t k_of_device(const Geo &g, uint32_t p) { return k_rule(g.k_ratio, g.part_size(p)); }
+
+}  // namespace bpc

@@ -1,0 +1,60 @@
+// Launchers of the HIP kernels, one group per compressor.  Every launcher only
+// enqueues work on `stream` and returns the first HIP error it saw.
+#pragma once
+#include <hip/hip_runtime.h>
+#include "geometry.hpp"
+
+namespace bpc {
+
+// The n worker messages of an aggregate call, passed by value in the kernel arguments.
+struct WorkerMsgs {
+  const uint8_t *ptr[kMaxWorkers];
+  uint64_t seed[kMaxWorkers];
+  uint64_t stream_id[kMaxWorkers];
+  int n;
+  float inv_n;
+};
+
+// Where the worker-side q = g + e or the server-side Delta comes from.
+struct Source {
+  // worker: grad (+ residual); server: msgs (+ residual)
+  const void *grad;     // NULL on the server
+  int dtype;            // bpc_dtype_t of grad
+  float *residual;      // e (worker) or e~ (server); NULL: no error feedback
+  WorkerMsgs msgs;      // used when grad == NULL
+};
+
+struct Workspace {
+  uint8_t *base;
+  WsLayout lay;
+  template <class T> T *at(size_t off) const { return reinterpret_cast<T *>(base + off); }
+};
+
+hipError_t fill_zero(void *ptr, size_t bytes, hipStream_t stream);
+
+// C(q) and the residual update for each kind; the same entry serves worker and server.
+hipError_t sign_encode(const Geo &g, const bpc_params_t &prm, const Source &src, uint8_t *payload,
+                       const Workspace &ws, hipStream_t stream);
+hipError_t dither_encode(const Geo &g, const bpc_params_t &prm, const Source &src, uint8_t *payload,
+                         const Workspace &ws, hipStream_t stream);
+hipError_t identity_encode(const Geo &g, const bpc_params_t &prm, const Source &src, uint8_t *payload,
+                           const Workspace &ws, hipStream_t stream);
+hipError_t topk_encode(const Geo &g, const bpc_params_t &prm, const bpc_params_t *in_prm, const Source &src,
+                       uint8_t *payload, const Workspace &ws, hipStream_t stream);
+hipError_t randk_encode(const Geo &g, const bpc_params_t &prm, const bpc_params_t *in_prm, const Source &src,
+                        uint8_t *payload, const Workspace &ws, hipStream_t stream);
+
+// out[idx] += decoded sparse entries (TOPK: plain store).  `out` holds the running sum.
+hipError_t scatter_add_sparse(const Geo &g, const bpc_params_t &prm, const uint8_t *payload, float *out,
+                              hipStream_t stream);
+
+// out = decode(payload), dense.
+hipError_t decode_dense(const Geo &g, const bpc_params_t &prm, const uint8_t *payload, float *out,
+                        hipStream_t stream);
+
+// Algorithm 5 update lines fused with the decode of bit-packed messages; sparse kinds are
+// decoded into the workspace first.
+hipError_t adaptive_update(const Geo &g, const bpc_params_t &prm, const uint8_t *payload, float *x, float *m,
+                           float *v, const bpc_opt_t &opt, const Workspace &ws, hipStream_t stream);
+
+}  // namespace bpc

@@ -1,0 +1,77 @@
+"""Helpers of the GPU parity tests: move numpy inputs to the card, call the C-ABI library
+through its Python binding, bring results back."""
+import numpy as np
+import torch
+
+import paper_2105_07829_amd as bpc
+
+DEV = "cuda"
+
+KIND_B = {"identity": bpc.IDENTITY, "sign": bpc.SIGN, "topk": bpc.TOPK, "randk": bpc.RANDK, "dither": bpc.DITHER}
+
+
+def both_params(orc, kind, pe, **kw):
+    """The same compressor description for the oracle and for the library."""
+    kind_o = {"identity": orc.IDENTITY, "sign": orc.SIGN, "topk": orc.TOPK, "randk": orc.RANDK,
+              "dither": orc.DITHER}[kind]
+    return orc.make_params(kind_o, pe, **kw), bpc.make_params(KIND_B[kind], pe, **kw)
+
+
+def to_dev(a):
+    return None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def to_host(t):
+    return None if t is None else t.cpu().numpy()
+
+
+def new_ws(pb, D, n=1):
+    return torch.empty(max(bpc.workspace_bytes(pb, D, n), 256), dtype=torch.uint8, device=DEV)
+
+
+def new_payload(pb, D, fill=0xA5):
+    # filled with a pattern so that bytes the library must write cannot pass by accident
+    return torch.full((max(bpc.payload_bytes(pb, D), 16),), fill, dtype=torch.uint8, device=DEV)
+
+
+def gpu_compress(pb, grad_np, res_np):
+    D = grad_np.size
+    g = to_dev(grad_np)
+    r = to_dev(res_np)
+    payload = new_payload(pb, D)
+    bpc.bpc_compress(pb, g, r, payload, new_ws(pb, D))
+    torch.cuda.synchronize()
+    return to_host(payload)[:bpc.payload_bytes(pb, D)], to_host(r)
+
+
+def gpu_decompress(pb, payload_np, D):
+    out = torch.full((max(D, 1),), 7.0, dtype=torch.float32, device=DEV)[:D]
+    pl = to_dev(payload_np) if payload_np.size else torch.empty(16, dtype=torch.uint8, device=DEV)
+    bpc.bpc_decompress(pb, pl, out)
+    torch.cuda.synchronize()
+    return to_host(out)
+
+
+def gpu_server(in_pbs, payloads_np, out_pb, res_np, D):
+    pls = [to_dev(p) for p in payloads_np]
+    r = to_dev(res_np)
+    out_payload = new_payload(out_pb, D)
+    bpc.bpc_server_aggregate(in_pbs, pls, out_pb, r, D, out_payload, new_ws(out_pb, D, len(pls)))
+    torch.cuda.synchronize()
+    return to_host(out_payload)[:bpc.payload_bytes(out_pb, D)], to_host(r)
+
+
+def gpu_update(pb, payload_np, x_np, m_np, v_np, opt_b):
+    x, m, v = to_dev(x_np), to_dev(m_np), to_dev(v_np)
+    D = x_np.size
+    ws = torch.empty(bpc.workspace_bytes(pb, D, 1) + 24 * int(opt_b.n_blocks) + 256, dtype=torch.uint8, device=DEV)
+    bpc.bpc_adaptive_update(pb, to_dev(payload_np), x, m, v, opt_b, ws)
+    torch.cuda.synchronize()
+    return to_host(x), to_host(m), to_host(v)
+
+
+def close(a, b, rel):
+    """|a - b| <= rel * (|b| + mean|b|): relative tolerance for arrays that cross zero."""
+    a64, b64 = a.astype(np.float64), b.astype(np.float64)
+    scale = np.abs(b64) + (np.abs(b64).mean() if b64.size else 0.0)
+    return bool(np.all(np.abs(a64 - b64) <= rel * scale + 1e-45))

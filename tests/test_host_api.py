@@ -1,0 +1,136 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
+header declares, sizes agree with the format description, and every argument error is caught
+before the first HIP call."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import fmt
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def bpc():
+    import paper_2105_07829_amd as bpc
+    if not os.path.exists(bpc.LIB_PATH):
+        bpc.build()
+    bpc.lib()
+    return bpc
+
+
+def test_library_exports_every_declared_symbol(bpc):
+    header = open(os.path.join(ROOT, "include", "bpc.h")).read()
+    declared = set(re.findall(r"\b(bpc_[a-z_0-9]+)\s*\(", header))
+    declared -= {n for n in declared if n.endswith("_t")}
+    assert declared == set(bpc.EXPORTS)
+    raw = C.CDLL(bpc.LIB_PATH)
+    for name in declared:
+        assert hasattr(raw, name), name
+
+
+def test_sizes_follow_the_record_format(bpc):
+    pe = 1 << 20
+    assert bpc.partition_stride(bpc.make_params(bpc.SIGN, pe)) == fmt.stride("sign", pe)
+    assert bpc.partition_stride(bpc.make_params(bpc.DITHER, pe)) == fmt.stride("dither", pe)
+    assert bpc.partition_stride(bpc.make_params(bpc.IDENTITY, pe)) == fmt.stride("identity", pe)
+    assert bpc.partition_stride(bpc.make_params(bpc.TOPK, pe, k_ratio=0.01)) == fmt.stride("topk", pe, 0.01)
+    assert bpc.partition_stride(bpc.make_params(bpc.RANDK, pe, k_ratio=0.01)) == fmt.stride("randk", pe, 0.01)
+    p = bpc.make_params(bpc.TOPK, pe, k_ratio=0.01)
+    assert bpc.partition_k(p, pe) == 10485 and bpc.partition_k(p, 391_208) == 3912 and bpc.partition_k(p, 3) == 1
+    assert bpc.payload_bytes(p, 25_557_032) == 25 * fmt.stride("topk", pe, 0.01)
+    assert bpc.payload_bytes(p, 0) == 0
+    assert bpc.workspace_bytes(p, 25_557_032, 8) >= 4 * 25_557_032
+
+
+def test_sizes_agree_with_the_oracle(bpc, orc):
+    for kind_b, kind_o, kw in [(bpc.SIGN, orc.SIGN, {}), (bpc.DITHER, orc.DITHER, {}),
+                               (bpc.TOPK, orc.TOPK, dict(k_ratio=0.013)), (bpc.RANDK, orc.RANDK, dict(k_ratio=0.2)),
+                               (bpc.IDENTITY, orc.IDENTITY, {})]:
+        for pe in (1024, 5120, 1 << 20):
+            pb, po = bpc.make_params(kind_b, pe, **kw), orc.make_params(kind_o, pe, **kw)
+            assert bpc.partition_stride(pb) == orc.partition_stride(po)
+            for D in (1, pe - 1, pe, 3 * pe + 17):
+                assert bpc.payload_bytes(pb, D) == orc.payload_bytes(po, D)
+                d_last = D - (D - 1) // pe * pe
+                assert bpc.partition_k(pb, d_last) == orc.partition_k(po, d_last)
+
+
+def test_invalid_params_are_rejected(bpc):
+    bad = [bpc.make_params(bpc.SIGN, 0), bpc.make_params(bpc.SIGN, 1000), bpc.make_params(9, 1024),
+           bpc.make_params(bpc.TOPK, 1024, k_ratio=0.0), bpc.make_params(bpc.TOPK, 1024, k_ratio=1.5),
+           bpc.make_params(bpc.RANDK, 1024, k_ratio=-1.0), bpc.make_params(bpc.DITHER, 1024, levels=0),
+           bpc.make_params(bpc.DITHER, 1024, levels=8), bpc.make_params(bpc.DITHER, 1024, norm=5)]
+    for p in bad:
+        assert bpc.partition_stride(p) == 0
+        assert bpc.payload_bytes(p, 4096) == 0
+        assert bpc.workspace_bytes(p, 4096, 1) == 0
+        st = bpc.lib().bpc_compress(C.byref(p), 0x1000, bpc.F32, None, 4096, 0x2000, 0x3000, 1 << 30, None)
+        assert st == bpc.ERR_INVALID_ARG
+
+
+def test_argument_errors_come_before_any_device_work(bpc):
+    """Pointers below are fake addresses: every call must return before touching them."""
+    L = bpc.lib()
+    p = bpc.make_params(bpc.SIGN, 1024)
+    D = 5000
+    ws = bpc.workspace_bytes(p, D, 1)
+    G, R, PL, WS = 0x10000, 0x20000, 0x30000, 0x40000
+    assert L.bpc_compress(None, G, bpc.F32, R, D, PL, WS, ws, None) == bpc.ERR_INVALID_ARG
+    assert L.bpc_compress(C.byref(p), None, bpc.F32, R, D, PL, WS, ws, None) == bpc.ERR_INVALID_ARG
+    assert L.bpc_compress(C.byref(p), G, 7, R, D, PL, WS, ws, None) == bpc.ERR_INVALID_ARG
+    assert L.bpc_compress(C.byref(p), G, bpc.F32, R, D, None, WS, ws, None) == bpc.ERR_INVALID_ARG
+    assert L.bpc_compress(C.byref(p), G + 4, bpc.F32, R, D, PL, WS, ws, None) == bpc.ERR_ALIGNMENT
+    assert L.bpc_compress(C.byref(p), G, bpc.F32, R + 8, D, PL, WS, ws, None) == bpc.ERR_ALIGNMENT
+    assert L.bpc_compress(C.byref(p), G, bpc.F32, R, D, PL + 2, WS, ws, None) == bpc.ERR_ALIGNMENT
+    assert L.bpc_compress(C.byref(p), G, bpc.F32, R, D, PL, WS, ws - 1, None) == bpc.ERR_WORKSPACE
+    assert L.bpc_compress(C.byref(p), G, bpc.F32, R, D, PL, None, ws, None) == bpc.ERR_WORKSPACE
+    assert L.bpc_compress(C.byref(p), G, bpc.F32, R, 0, PL, WS, ws, None) == bpc.OK   # empty gradient
+    assert L.bpc_decompress(C.byref(p), None, D, R, None) == bpc.ERR_INVALID_ARG
+    assert L.bpc_decompress(C.byref(p), PL, D, R + 4, None) == bpc.ERR_ALIGNMENT
+    assert L.bpc_decompress(C.byref(p), PL, 0, R, None) == bpc.OK
+    # aggregate
+    n = 3
+    arr = (bpc.Params * n)(*[p] * n)
+    ptrs = (C.c_void_p * n)(PL, PL + 0x1000, PL + 0x2000)
+    assert L.bpc_server_aggregate(arr, ptrs, 0, C.byref(p), R, D, PL, WS, ws, None) == bpc.ERR_INVALID_ARG
+    assert L.bpc_server_aggregate(arr, ptrs, 65, C.byref(p), R, D, PL, WS, ws, None) == bpc.ERR_UNSUPPORTED
+    assert L.bpc_server_aggregate(arr, None, n, C.byref(p), R, D, PL, WS, ws, None) == bpc.ERR_INVALID_ARG
+    other = bpc.make_params(bpc.DITHER, 1024)
+    assert L.bpc_server_aggregate(arr, ptrs, n, C.byref(other), R, D, PL, WS, 1 << 30, None) == bpc.ERR_INVALID_ARG
+    ptrs_bad = (C.c_void_p * n)(PL, None, PL)
+    assert L.bpc_server_aggregate(arr, ptrs_bad, n, C.byref(p), R, D, PL, WS, ws, None) == bpc.ERR_INVALID_ARG
+    ptrs_mis = (C.c_void_p * n)(PL, PL + 4, PL)
+    assert L.bpc_server_aggregate(arr, ptrs_mis, n, C.byref(p), R, D, PL, WS, ws, None) == bpc.ERR_ALIGNMENT
+    assert L.bpc_server_aggregate(arr, ptrs, n, C.byref(p), R, D, PL, WS, 16, None) == bpc.ERR_WORKSPACE
+    assert L.bpc_server_aggregate(arr, ptrs, n, C.byref(p), R, 0, PL, WS, ws, None) == bpc.OK
+    # update
+    o = bpc.make_opt(bpc.OPT_ADAM, 1e-3, 0.9, 0.999, 1e-8, 0.01, 1)
+    X, M, V = 0x50000, 0x60000, 0x70000
+    assert L.bpc_adaptive_update(C.byref(p), PL, D, X, M, V, None, WS, ws, None) == bpc.ERR_INVALID_ARG
+    assert L.bpc_adaptive_update(C.byref(p), PL, D, None, M, V, C.byref(o), WS, ws, None) == bpc.ERR_INVALID_ARG
+    assert L.bpc_adaptive_update(C.byref(p), PL, D, X, M + 4, V, C.byref(o), WS, ws, None) == bpc.ERR_ALIGNMENT
+    assert L.bpc_adaptive_update(C.byref(p), PL, D, X, M, V, C.byref(o), WS, 8, None) == bpc.ERR_WORKSPACE
+    bad = bpc.make_opt(bpc.OPT_ADAM, 1e-3, 1.0, 0.999, 1e-8, 0.0, 1)
+    assert L.bpc_adaptive_update(C.byref(p), PL, D, X, M, V, C.byref(bad), WS, ws, None) == bpc.ERR_INVALID_ARG
+    bad = bpc.make_opt(5, 1e-3, 0.9, 0.999, 1e-8, 0.0, 1)
+    assert L.bpc_adaptive_update(C.byref(p), PL, D, X, M, V, C.byref(bad), WS, ws, None) == bpc.ERR_INVALID_ARG
+    assert L.bpc_adaptive_update(C.byref(p), PL, 0, X, M, V, C.byref(o), WS, ws, None) == bpc.OK
+
+
+def test_status_strings(bpc):
+    L = bpc.lib()
+    seen = {L.bpc_status_string(i).decode() for i in range(6)}
+    assert len(seen) == 6 and "ok" in seen
+    assert L.bpc_status_string(99).decode() == "unknown status"
+    assert L.bpc_last_hip_error() == 0
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    import paper_2105_07829_amd as bpc
+    monkeypatch.setattr(bpc, "_lib", None)
+    monkeypatch.setattr(bpc, "LIB_PATH", "/nonexistent/libbpc.so")
+    with pytest.raises(ImportError):
+        bpc.lib()
