@@ -1,0 +1,253 @@
+#!/usr/bin/env python3
+"""Throughput of the two-way error-feedback compression hot path on one MI355X.
+
+One step = one pass of the whole path over one batch of synthetic gradients:
+n x bpc_compress (worker: q = g + e, C(q), residual), 1 x bpc_server_aggregate (decode n
+messages, average, + server residual, recompress, residual), 1 x bpc_adaptive_update (decode
+the pulled message fused with the moment / parameter update).  Inputs are resident in HBM
+before the clock starts.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-others] [--no-cpu]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0      # MI355X HBM3E, vendor figure
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="bert_large")
+    ap.add_argument("--no-others", action="store_true", help="skip the secondary workloads")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--cpu-partitions", type=int, default=8, help="partitions in the CPU sample")
+    return ap.parse_args()
+
+
+def payload_bytes_per_elem(w):
+    k = w["kind"]
+    if k == "sign":
+        return 1.0 / 8
+    if k == "dither":
+        return 0.5
+    if k == "topk":
+        return 8 * w["k_ratio"]
+    if k == "randk":
+        return 4 * w["k_ratio"]
+    return 4.0
+
+
+def algorithmic_bytes_per_elem(w):
+    """Bytes the method must move per gradient element: every input read once, every output
+    written once."""
+    G = 4 if w["dtype"] == "f32" else 2
+    pl = payload_bytes_per_elem(w)
+    n = w["n_workers"]
+    return {"W": G + 8 + pl, "S": n * pl + 8 + pl, "U": pl + 24}
+
+
+class Pipeline:
+    """Device state of one workload and the three stage calls."""
+
+    def __init__(self, name, w, torch, bpc, synth):
+        self.name, self.w, self.torch, self.bpc = name, w, torch, bpc
+        dev = "cuda"
+        self.D, self.n = w["D"], w["n_workers"]
+        self.pe = synth.part_elems(w["dtype"])
+        kind = {"sign": bpc.SIGN, "topk": bpc.TOPK, "randk": bpc.RANDK, "dither": bpc.DITHER}[w["kind"]]
+        self.kw = dict(k_ratio=w.get("k_ratio", 0.01), levels=w.get("levels", 4),
+                       value_scale=w.get("value_scale", 1.0), seed=synth.BASE_SEED)
+        self.kind = kind
+        p0 = bpc.make_params(kind, self.pe, **self.kw)
+        self.grads = [synth.device_gradient(w["dist"], self.D, w["dtype"], worker=i, device=dev)
+                      for i in range(self.n)]
+        self.res = [torch.zeros(self.D, dtype=torch.float32, device=dev) for _ in range(self.n)]
+        self.sres = torch.zeros(self.D, dtype=torch.float32, device=dev)
+        pb = bpc.payload_bytes(p0, self.D)
+        self.pay = [torch.zeros(pb, dtype=torch.uint8, device=dev) for _ in range(self.n)]
+        self.pay_out = torch.zeros(pb, dtype=torch.uint8, device=dev)
+        self.ws = torch.empty(bpc.workspace_bytes(p0, self.D, self.n), dtype=torch.uint8, device=dev)
+        self.x = synth.device_params(self.D, device=dev)
+        self.m = torch.zeros(self.D, dtype=torch.float32, device=dev)
+        self.v = torch.zeros(self.D, dtype=torch.float32, device=dev)
+        self.t = 0
+
+    def params(self, role, worker):
+        return self.bpc.make_params(self.kind, self.pe, stream_id=(self.t << 32) | (role << 16) | worker, **self.kw)
+
+    def stage_w(self, i):
+        self.bpc.bpc_compress(self.params(0, i), self.grads[i], self.res[i], self.pay[i], self.ws)
+
+    def stage_s(self):
+        ins = [self.params(0, i) for i in range(self.n)]
+        self.bpc.bpc_server_aggregate(ins, self.pay, self.params(1, 0), self.sres, self.D, self.pay_out, self.ws)
+
+    def stage_u(self):
+        t = max(self.t, 1)
+        opt = self.bpc.make_opt(self.bpc.OPT_ADAM, 1e-3, 0.9, 0.999, 1e-8, 0.01, t)
+        self.bpc.bpc_adaptive_update(self.params(1, 0), self.pay_out, self.x, self.m, self.v, opt, self.ws)
+
+    def step(self):
+        self.t += 1
+        for i in range(self.n):
+            self.stage_w(i)
+        self.stage_s()
+        self.stage_u()
+
+
+def timed(torch, fn, reps):
+    """Average milliseconds of fn() over reps calls, HIP events on the stream fn launches on."""
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    a.record()
+    for _ in range(reps):
+        fn()
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) / reps
+
+
+def run_workload(name, w, steps, warmup, torch, bpc, synth):
+    pipe = Pipeline(name, w, torch, bpc, synth)
+    for _ in range(warmup):
+        pipe.step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        pipe.step()
+    torch.cuda.synchronize()
+    ms_step = (time.perf_counter() - t0) * 1e3 / steps
+    # per-stage averages, steady state (non-zero residuals)
+    reps = max(steps, 5)
+    ms_w = timed(torch, lambda: pipe.stage_w(0), reps)
+    ms_s = timed(torch, pipe.stage_s, reps)
+    ms_u = timed(torch, pipe.stage_u, reps)
+    G = 4 if w["dtype"] == "f32" else 2
+    D, n = w["D"], w["n_workers"]
+    alg = algorithmic_bytes_per_elem(w)
+    stages = {}
+    for key, ms in (("W", ms_w), ("S", ms_s), ("U", ms_u)):
+        stages[key] = {"ms": round(ms, 4), "gradient_GBps": round(D * G / ms / 1e6, 1),
+                       "algorithmic_GBps": round(D * alg[key] / ms / 1e6, 1),
+                       "frac_of_hbm_peak": round(D * alg[key] / ms / 1e6 / HBM_PEAK_GBPS, 4)}
+    out = {"workload": name, "D": D, "dtype": w["dtype"], "compressor": w["kind"], "n_workers": n,
+           "ms_per_step": round(ms_step, 4), "value_GBps": round(n * D * G / ms_step / 1e6, 1),
+           "pipeline_GBps_one_worker": round(D * G / (ms_w + ms_s + ms_u) / 1e6, 1), "stages": stages}
+    del pipe
+    torch.cuda.empty_cache()
+    return out
+
+
+def cpu_baseline(name, w, n_parts, synth):
+    """The CPU oracle as it stands, on `n_parts` full partitions of the same workload (all n
+    workers, server, update), partitions spread over the host cores with a thread pool."""
+    import numpy as np
+    from concurrent.futures import ThreadPoolExecutor
+
+    import oracle
+
+    oracle.build()
+    pe = synth.part_elems(w["dtype"])
+    n = w["n_workers"]
+    D = pe * n_parts
+    cores = min(os.cpu_count() or 1, 16)
+    kind = {"sign": oracle.SIGN, "topk": oracle.TOPK, "randk": oracle.RANDK, "dither": oracle.DITHER}[w["kind"]]
+    kw = dict(k_ratio=w.get("k_ratio", 0.01), levels=w.get("levels", 4), value_scale=w.get("value_scale", 1.0),
+              seed=synth.BASE_SEED)
+    grads = [synth.host_gradient(w["dist"], D, w["dtype"], worker=i) for i in range(n)]
+    res = [np.zeros(D, np.float32) for _ in range(n)]
+    sres = np.zeros(D, np.float32)
+    x, m, v = synth.host_params(D), np.zeros(D, np.float32), np.zeros(D, np.float32)
+    strd = None
+
+    def prm(role, worker, part):
+        return oracle.make_params(kind, pe, stream_id=(1 << 32) | (role << 16) | worker, first_partition=part, **kw)
+
+    pays = [[None] * n_parts for _ in range(n)]
+    outs = [None] * n_parts
+
+    def work_w(job):
+        i, p = job
+        sl = slice(p * pe, (p + 1) * pe)
+        pays[i][p] = oracle.compress(prm(0, i, p), grads[i][sl], res[i][sl])
+
+    def work_su(p):
+        sl = slice(p * pe, (p + 1) * pe)
+        ins = [prm(0, i, p) for i in range(n)]
+        outs[p] = oracle.server_aggregate(ins, [pays[i][p] for i in range(n)], prm(1, 0, p), sres[sl], pe)
+        opt = oracle.make_opt(oracle.OPT_ADAM, 1e-3, 0.9, 0.999, 1e-8, 0.01, 1)
+        oracle.adaptive_update(prm(1, 0, p), outs[p], pe, x[sl], m[sl], v[sl], opt)
+
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(cores) as ex:
+        list(ex.map(work_w, [(i, p) for i in range(n) for p in range(n_parts)]))
+        list(ex.map(work_su, range(n_parts)))
+    dt = time.perf_counter() - t0
+    G = 4 if w["dtype"] == "f32" else 2
+    return {"value": round(n * D * G / dt / 1e9, 4), "unit": "GB/s", "cores": cores, "kind": "oracle",
+            "sample": f"{n_parts} full partitions ({D} elements) of {name}: {n} workers compress + server "
+                      f"aggregate + update, {dt:.1f} s wall, one step"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the path has no cross-GPU part); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+
+    import paper_2105_07829_amd as bpc
+    import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    bpc.lib()   # raises if the HIP library was not built: there is no fallback
+    torch.cuda.set_device(0)
+    head = run_workload(args.workload, synth.WORKLOADS[args.workload], args.steps, args.warmup, torch, bpc, synth)
+    others = []
+    if not args.no_others:
+        for name, w in synth.WORKLOADS.items():
+            if name != args.workload:
+                others.append(run_workload(name, w, max(3, args.steps // 2), 2, torch, bpc, synth))
+    w = synth.WORKLOADS[args.workload]
+    # dominant stage of the step: the worker compress call runs n times per step
+    dom = max(("W", "S", "U"), key=lambda k: head["stages"][k]["ms"] * (w["n_workers"] if k == "W" else 1))
+    alg = algorithmic_bytes_per_elem(w)[dom]
+    ach = head["stages"][dom]["algorithmic_GBps"]
+    call = {"W": "bpc_compress", "S": "bpc_server_aggregate", "U": "bpc_adaptive_update"}[dom]
+    result = {
+        "metric": "GB/s of gradient compressed+EF+decompressed, % of HBM peak, per compressor",
+        "value": head["value_GBps"], "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": args.workload, "elements": w["D"], "gradient_dtype": w["dtype"],
+                   "compressor": w["kind"], "n_workers": w["n_workers"], "partition_bytes": synth.PART_BYTES,
+                   "error_feedback": "two-way", "update": "adam-style"},
+        "roofline": {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "kernel": f"{call} ({w['kind']})", "algorithmic_bytes_per_element": alg,
+                     "elements_per_launch": w["D"]},
+        "stages": head["stages"],
+        "pipeline_GBps_one_worker": head["pipeline_GBps_one_worker"],
+        "other_workloads": others,
+    }
+    if not args.no_cpu:
+        result["cpu_baseline"] = cpu_baseline(args.workload, w, args.cpu_partitions, synth)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -28,7 +28,7 @@ HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-ffp-contract=off"
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-fPIC", "-shared"]
 
 EXPORTS = ["bpc_partition_k", "bpc_partition_stride", "bpc_payload_bytes", "bpc_workspace_bytes",
-           "bpc_compress", "bpc_decompress", "bpc_server_aggregate", "bpc_adaptive_update",
+           "bpc_workspace_status_offset", "bpc_compress", "bpc_decompress", "bpc_server_aggregate", "bpc_adaptive_update",
            "bpc_status_string", "bpc_last_hip_error"]
 
 
@@ -88,6 +88,8 @@ def lib():
         L.bpc_payload_bytes.restype = C.c_size_t
         L.bpc_workspace_bytes.argtypes = [PP, C.c_uint64, C.c_int]
         L.bpc_workspace_bytes.restype = C.c_size_t
+        L.bpc_workspace_status_offset.argtypes = [PP, C.c_uint64]
+        L.bpc_workspace_status_offset.restype = C.c_size_t
         L.bpc_compress.argtypes = [PP, C.c_void_p, C.c_int, C.c_void_p, C.c_uint64, C.c_void_p,
                                    C.c_void_p, C.c_size_t, C.c_void_p]
         L.bpc_compress.restype = C.c_int
@@ -175,6 +177,12 @@ def payload_bytes(p: Params, D: int) -> int:
 
 def workspace_bytes(p: Params, D: int, n: int = 1) -> int:
     return int(lib().bpc_workspace_bytes(C.byref(p), D, n))
+
+
+def workspace_status(p: Params, D: int, ws) -> int:
+    """Value of the workspace status word (synchronises the device); 0 means no wait timed out."""
+    off = int(lib().bpc_workspace_status_offset(C.byref(p), D))
+    return int(ws[off:off + 4].view(dtype=__import__("torch").int32).item())
 
 
 def _dtype_code(grad):

@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include "kernels.hpp"
 
+
+
 using namespace bpc;
 
 static thread_local int g_last_hip_error = 0;
@@ -37,6 +39,12 @@ size_t bpc_workspace_bytes(const bpc_params_t *params, uint64_t D, int n) {
   if (!params_valid(params) || n < 1 || n > kMaxWorkers) return 0;
   if (D == 0) return 256;
   return ws_layout(params, D).total;
+}
+
+size_t bpc_workspace_status_offset(const bpc_params_t *params, uint64_t D) {
+  if (!params_valid(params)) return (size_t)-1;
+  if (D == 0) return 0;
+  return ws_layout(params, D).status;
 }
 
 static bpc_status_t check_size(uint64_t D) {

@@ -48,6 +48,11 @@ hipError_t randk_encode(const Geo &g, const bpc_params_t &prm, const bpc_params_
 hipError_t scatter_add_sparse(const Geo &g, const bpc_params_t &prm, const uint8_t *payload, float *out,
                               hipStream_t stream);
 
+// Single-pass (register-resident, cluster-synchronised) variants.  *used = false means the
+// shape is outside what they handle and nothing was enqueued.
+hipError_t sign_worker_single_pass(const Geo &g, const bpc_params_t &prm, const Source &src, uint8_t *payload,
+                                   const Workspace &ws, hipStream_t stream, bool *used);
+
 // out = decode(payload), dense.
 hipError_t decode_dense(const Geo &g, const bpc_params_t &prm, const uint8_t *payload, float *out,
                         hipStream_t stream);

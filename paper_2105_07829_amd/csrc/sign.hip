@@ -87,6 +87,11 @@ __global__ __launch_bounds__(kThreads) void sign_apply_kernel(Geo g, SRC src, co
 
 hipError_t sign_encode(const Geo &g, const bpc_params_t &prm, const Source &src, uint8_t *payload,
                        const Workspace &ws, hipStream_t stream) {
+  if (src.grad) {
+    bool used = false;
+    hipError_t e = sign_worker_single_pass(g, prm, src, payload, ws, stream, &used);
+    if (e != hipSuccess || used) return e;
+  }
   double *partials = ws.at<double>(ws.lay.partials);
   auto make_server = [&] { return SignMsgSource{src.msgs, src.residual, g.stride}; };
   return with_source(src, make_server, [&](auto s) -> hipError_t {

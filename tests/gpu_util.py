@@ -26,7 +26,7 @@ def to_host(t):
 
 
 def new_ws(pb, D, n=1):
-    return torch.empty(max(bpc.workspace_bytes(pb, D, n), 256), dtype=torch.uint8, device=DEV)
+    return torch.zeros(max(bpc.workspace_bytes(pb, D, n), 256), dtype=torch.uint8, device=DEV)
 
 
 def new_payload(pb, D, fill=0xA5):
@@ -39,8 +39,10 @@ def gpu_compress(pb, grad_np, res_np):
     g = to_dev(grad_np)
     r = to_dev(res_np)
     payload = new_payload(pb, D)
-    bpc.bpc_compress(pb, g, r, payload, new_ws(pb, D))
+    ws = new_ws(pb, D)
+    bpc.bpc_compress(pb, g, r, payload, ws)
     torch.cuda.synchronize()
+    assert D == 0 or bpc.workspace_status(pb, D, ws) == 0, "a device-side wait timed out"
     return to_host(payload)[:bpc.payload_bytes(pb, D)], to_host(r)
 
 
@@ -56,8 +58,11 @@ def gpu_server(in_pbs, payloads_np, out_pb, res_np, D):
     pls = [to_dev(p) for p in payloads_np]
     r = to_dev(res_np)
     out_payload = new_payload(out_pb, D)
-    bpc.bpc_server_aggregate(in_pbs, pls, out_pb, r, D, out_payload, new_ws(out_pb, D, len(pls)))
+    ws = new_ws(out_pb, D, len(pls))
+    ws[:].zero_()
+    bpc.bpc_server_aggregate(in_pbs, pls, out_pb, r, D, out_payload, ws)
     torch.cuda.synchronize()
+    assert bpc.workspace_status(out_pb, D, ws) == 0, "a device-side wait timed out"
     return to_host(out_payload)[:bpc.payload_bytes(out_pb, D)], to_host(r)
 
 

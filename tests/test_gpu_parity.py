@@ -97,6 +97,39 @@ def test_worker_stage(gu, orc, name, dtype, ef):
                 assert gu.close(res_gpu, res_ref, REL), name
 
 
+BIG_PE = 131072                          # two 65536-element register tiles per partition
+BIG_D = 2 * BIG_PE + 70000               # tail partition: one full tile and a ragged one
+
+
+@pytest.mark.parametrize("name", sorted(KW))
+@pytest.mark.parametrize("dtype", [np.float32, np.float16])
+@pytest.mark.parametrize("ef", [True, False])
+def test_worker_stage_large_partitions(gu, orc, name, dtype, ef):
+    """Same comparison on partitions that span several register-resident tiles."""
+    for D in (BIG_D, BIG_PE, 65536 + 3):
+        po, pb = gu.both_params(orc, base_kind(name), BIG_PE, **KW[name])
+        g = grads(D, dtype, 17 + D)
+        e = (rng(3 + D).standard_normal(D) * 3e-4).astype(np.float32) if ef else None
+        res_ref = None if e is None else e.copy()
+        pay_ref = orc.compress(po, g, res_ref)
+        pay_gpu, res_gpu = gu.gpu_compress(pb, g, e)
+
+        def redo(norms):
+            po2, _ = gu.both_params(orc, base_kind(name), BIG_PE, norm_override=norms, **KW[name])
+            r2 = None if e is None else e.copy()
+            out = orc.compress(po2, g, r2)
+            if r2 is not None:
+                res_ref[:] = r2
+            return out
+
+        compare_payload(gu, orc, name, po, pay_gpu, pay_ref, D, BIG_PE, redo)
+        if ef:
+            if base_kind(name) in ("identity", "topk"):
+                assert np.array_equal(res_gpu.view(np.uint32), res_ref.view(np.uint32))
+            else:
+                assert gu.close(res_gpu, res_ref, REL), name
+
+
 @pytest.mark.parametrize("name", sorted(KW))
 @pytest.mark.parametrize("ef", [True, False])
 @pytest.mark.parametrize("n", [1, 4, 16])
