@@ -248,8 +248,11 @@ static void encode_dither(const orc_params *p, uint64_t part_no, const float *q,
   for (uint64_t w = 0; w < words; ++w) put_u32(rec, 4 + w, 0);
   if (!(nu > 0.0f)) return;
   unsigned s = p->levels;
+  /* a = s|q_j|/nu is evaluated as |q_j| * (s/nu), the quotient formed once per partition;
+   * if s/nu overflows (nu below about 1e-38) the division is done per element instead. */
+  float s_over_nu = (float)s / nu;
   for (uint64_t j = 0; j < d; ++j) {
-    float a = (fabsf(q[j]) * (float)s) / nu;
+    float a = isfinite(s_over_nu) ? fabsf(q[j]) * s_over_nu : (fabsf(q[j]) * (float)s) / nu;
     float l = floorf(a);
     float f = a - l;
     float u = (float)(draw_word(p, part_no, j) >> 8) * 0x1p-24f;

@@ -1,0 +1,58 @@
+// Host-side support of the cluster kernels (see cluster.hpp).
+#include <mutex>
+#include <stdlib.h>
+#include "cluster.hpp"
+
+namespace bpc {
+
+__global__ void slots_reset_kernel(double *slots, uint32_t n, uint32_t *status) {
+  uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) slots[i] = -1.0;
+  if (i == 0) *status = 0;
+}
+
+int cluster_capacity(const void *kernel) {
+  int dev = 0, cus = 0, per_cu = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return 0;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kCThreads, 0) != hipSuccess) return 0;
+  return cus * per_cu;
+}
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_mu;
+hipEvent_t g_event[kMaxDevices];
+hipStream_t g_last_stream[kMaxDevices];
+bool g_have[kMaxDevices];
+}  // namespace
+
+hipError_t cluster_launch_begin(hipStream_t stream) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_mu);
+  if (g_have[dev] && g_last_stream[dev] != stream) return hipStreamWaitEvent(stream, g_event[dev], 0);
+  return hipSuccess;
+}
+
+hipError_t cluster_launch_end(hipStream_t stream) {
+  if (getenv("BPC_EXP_NO_EVENT")) return hipSuccess;
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_mu);
+  if (!g_event[dev]) {
+    e = hipEventCreateWithFlags(&g_event[dev], hipEventDisableTiming);
+    if (e != hipSuccess) return e;
+  }
+  e = hipEventRecord(g_event[dev], stream);
+  if (e != hipSuccess) return e;
+  g_last_stream[dev] = stream;
+  g_have[dev] = true;
+  return hipSuccess;
+}
+
+}  // namespace bpc

@@ -16,12 +16,13 @@
 #pragma once
 #include "device_utils.hpp"
 #include "geometry.hpp"
+#include <hip/hip_runtime.h>
 
 namespace bpc {
 
-constexpr int kCThreads = 1024;               // workgroup size of the cluster kernels
-constexpr int kCPerThread = 64;               // elements a thread keeps in registers
-constexpr int kCTile = kCThreads * kCPerThread;  // 65536
+constexpr int kCThreads = 1024;               // workgroup size of the cluster kernels (one per CU)
+constexpr int kCPerThread = 32;               // elements a thread keeps in registers
+constexpr int kCTile = kCThreads * kCPerThread;  // 32768
 constexpr int kSpinLimit = 1 << 22;
 
 struct ClusterGeo {
@@ -37,7 +38,18 @@ inline ClusterGeo make_cluster_geo(const Geo &g) {
   return c;
 }
 
+// Host side: cluster kernels are launched as ordinary kernels whose grid never exceeds what
+// the device can hold at once.  Two of them running concurrently (different streams) could
+// each end up partly resident and wait for each other's slots, so launches are chained:
+// every launch records an event, and a launch on another stream first waits for it.
+hipError_t cluster_launch_begin(hipStream_t stream);
+hipError_t cluster_launch_end(hipStream_t stream);
+// Number of workgroups of `kernel` (kCThreads threads, no dynamic LDS) resident at once.
+int cluster_capacity(const void *kernel);
+
 #if defined(__HIPCC__)
+__global__ void slots_reset_kernel(double *slots, uint32_t n, uint32_t *status);
+
 __device__ inline void slot_publish(double *slot, double value) {
   __hip_atomic_store(slot, value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
@@ -90,12 +102,63 @@ __device__ inline double cluster_block_reduce(double x, double *red /*kCThreads/
   if (wave == 0) {
     t = lane < kCThreads / 64 ? red[lane] : 0.0;
 #pragma unroll
-    for (int off = 8; off > 0; off >>= 1) {
+    for (int off = kCThreads / 128; off > 0; off >>= 1) {
       double o = __shfl_xor(t, off, 64);
       t = MAX ? fmax(t, o) : t + o;
     }
   }
   return t;
+}
+
+// Persistent, software-pipelined driver.  `Op` supplies:
+//   struct Raw, struct Held;                     raw loads of a tile / what is kept for phase 2
+//   uint32_t n_items() const;
+//   bool   full(item) const;                     tile completely inside its partition
+//   void   issue(item, Raw&) const;              start the loads of a full tile
+//   double phase1(item, Raw&, Held&) const;      consume the loads, return the tile's partial
+//   void   early(item, Held&) const;             stores that do not need the norm
+//   double ragged_phase1(item) const;            same for a ragged tile, nothing held
+//   void   slots_of(item, first, count, denom)   the partition's slots
+//   void   phase2(item, Held&, double total) const;   / ragged_phase2(item, total)
+//   static constexpr bool kMax;                  reduction is a maximum instead of a sum
+// While a workgroup waits for its partition's total and writes its outputs, the loads of
+// its next tile are already in flight.
+template <class Op>
+__device__ inline void cluster_run(const Op &op, double *slots, uint32_t *status) {
+  __shared__ double red[kCThreads / 64];
+  __shared__ double total_sh;
+  const uint32_t n_items = op.n_items();
+  uint32_t item = blockIdx.x;
+  if (item >= n_items) return;
+  typename Op::Raw raw;
+  bool full = op.full(item);
+  if (full) op.issue(item, raw);
+  for (;;) {
+    typename Op::Held held;
+    double part = full ? op.phase1(item, raw, held) : op.ragged_phase1(item);
+    const uint32_t next = item + gridDim.x;
+    const bool have_next = next < n_items;
+    const bool next_full = have_next && op.full(next);
+    if (next_full) op.issue(next, raw);
+    part = cluster_block_reduce<Op::kMax>(part, red);
+    if (full) op.early(item, held);
+    if (threadIdx.x < 64) {
+      uint32_t first, count;
+      op.slots_of(item, &first, &count);
+      if (op.needs_total()) {
+        if (threadIdx.x == 0) slot_publish(slots + item, part);
+        double total = slots_collect<Op::kMax>(slots + first, count, status);
+        if (threadIdx.x == 0) total_sh = total;
+      }
+    }
+    __syncthreads();
+    const double total = total_sh;
+    if (full) op.phase2(item, held, total); else op.ragged_phase2(item, total);
+    if (!have_next) break;
+    item = next;
+    full = next_full;
+    __syncthreads();
+  }
 }
 #endif
 

@@ -19,8 +19,8 @@ struct Philox {
     for (int r = 0; r < 10; ++r) {
       uint64_t p0 = (uint64_t)0xD2511F53u * a;
       uint64_t p1 = (uint64_t)0xCD9E8D57u * c;
-      uint32_t na = (uint32_t)(p1 >> 32) ^ b ^ ka;
-      uint32_t nc = (uint32_t)(p0 >> 32) ^ d ^ kb;
+      uint32_t na = (uint32_t)(p1 >> 32) ^ (b ^ ka);
+      uint32_t nc = (uint32_t)(p0 >> 32) ^ (d ^ kb);
       b = (uint32_t)p1;
       d = (uint32_t)p0;
       a = na;

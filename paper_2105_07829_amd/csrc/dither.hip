@@ -72,7 +72,8 @@ __device__ inline uint32_t dither_one(float v, float nu, uint32_t s, uint32_t r,
     *resid = v;
     return 0u;
   }
-  float a = (fabsf(v) * (float)s) / nu;
+  const float s_over_nu = (float)s / nu;   // once per partition in effect: nu and s are uniform
+  float a = s_over_nu <= 3.402823466e38f ? fabsf(v) * s_over_nu : (fabsf(v) * (float)s) / nu;
   float l = floorf(a);
   float f = a - l;
   float u = (float)(r >> 8) * 0x1p-24f;
@@ -123,6 +124,11 @@ __global__ __launch_bounds__(kThreads) void dither_apply_kernel(Geo g, SRC src, 
 
 hipError_t dither_encode(const Geo &g, const bpc_params_t &prm, const Source &src, uint8_t *payload,
                          const Workspace &ws, hipStream_t stream) {
+  if (src.grad) {
+    bool used = false;
+    hipError_t e = dither_worker_single_pass(g, prm, src, payload, ws, stream, &used);
+    if (e != hipSuccess || used) return e;
+  }
   double *partials = ws.at<double>(ws.lay.partials);
   const int linf = prm.norm == BPC_NORM_LINF;
   auto make_server = [&] { return DitherMsgSource{src.msgs, src.residual, g.stride, prm.levels}; };

@@ -1,0 +1,263 @@
+// Linear-dithering worker, single pass (Algorithm 4 worker lines with the stochastic
+// multi-level quantiser): a workgroup reads a 32768-element tile of g and e once, keeps
+// q = g + e in registers, publishes its part of ||q||_2^2 (or max |q|), waits for the
+// partition's norm, then draws the levels, writes the packed nibbles and e' = q - decode.
+#include "cluster_launch.hpp"
+
+namespace bpc {
+
+constexpr int kDRows = kCPerThread / 8;  // 4 rows of 8192 elements; a thread owns 8 consecutive per row
+
+template <class G> struct Vec8Of;
+template <> struct Vec8Of<float> { struct type { float4 a, b; }; };
+template <> struct Vec8Of<__half> { using type = uint4; };
+
+__device__ inline void widen8(const Vec8Of<float>::type &g, float out[8]) {
+  out[0] = g.a.x; out[1] = g.a.y; out[2] = g.a.z; out[3] = g.a.w;
+  out[4] = g.b.x; out[5] = g.b.y; out[6] = g.b.z; out[7] = g.b.w;
+}
+__device__ inline void widen8(const uint4 &g, float out[8]) {
+  const uint32_t w[4] = {g.x, g.y, g.z, g.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    float2 f = __half22float2(*reinterpret_cast<const __half2 *>(&w[i]));
+    out[2 * i] = f.x;
+    out[2 * i + 1] = f.y;
+  }
+}
+__device__ inline Vec8Of<float>::type load8(const float *p) {
+  const float4 *q = reinterpret_cast<const float4 *>(p);
+  return {q[0], q[1]};
+}
+__device__ inline uint4 load8(const __half *p) { return *reinterpret_cast<const uint4 *>(p); }
+
+template <class G, bool EF, bool LINF>
+struct DitherWorkerOp {
+  using GV = typename Vec8Of<G>::type;
+  struct Raw { GV g[kDRows]; float4 e[2 * kDRows]; };
+  struct Held { float q[kCPerThread]; };
+  static constexpr bool kMax = LINF;
+
+  Geo g;
+  ClusterGeo cg;
+  const G *__restrict__ grad;
+  float *__restrict__ res;
+  uint8_t *__restrict__ payload;
+  const float *__restrict__ override;
+  uint32_t levels;
+  uint64_t seed, stream_id;
+
+  __device__ uint32_t n_items() const { return cg.n_items; }
+  __device__ bool needs_total() const { return override == nullptr; }
+  __device__ uint32_t part_of(uint32_t item) const { return item / cg.tiles_per_part; }
+  __device__ uint32_t tile_off(uint32_t item) const { return (item % cg.tiles_per_part) * kCTile; }
+  __device__ bool full(uint32_t item) const { return g.part_size(part_of(item)) - tile_off(item) >= (uint32_t)kCTile; }
+  __device__ uint64_t base(uint32_t item) const { return g.part_base(part_of(item)) + tile_off(item); }
+  __device__ void slots_of(uint32_t item, uint32_t *first, uint32_t *count) const {
+    uint32_t p = part_of(item);
+    *first = p * cg.tiles_per_part;
+    *count = (uint32_t)cdiv(g.part_size(p), kCTile);
+  }
+
+  __device__ void issue(uint32_t item, Raw &raw) const {
+    const uint64_t b = base(item);
+#pragma unroll
+    for (int u = 0; u < kDRows; ++u) {
+      const uint32_t off = (u * kCThreads + threadIdx.x) * 8;
+      raw.g[u] = load8(grad + b + off);
+      if (EF) {
+        const float4 *e4 = reinterpret_cast<const float4 *>(res + b + off);
+        raw.e[2 * u] = e4[0];
+        raw.e[2 * u + 1] = e4[1];
+      }
+    }
+  }
+
+  __device__ double phase1(uint32_t, Raw &raw, Held &h) const {
+    double acc = 0.0;
+    float mx = 0.0f;
+#pragma unroll
+    for (int u = 0; u < kDRows; ++u) {
+      float w[8];
+      widen8(raw.g[u], w);
+      const float e[8] = {raw.e[2 * u].x, raw.e[2 * u].y, raw.e[2 * u].z, raw.e[2 * u].w,
+                          raw.e[2 * u + 1].x, raw.e[2 * u + 1].y, raw.e[2 * u + 1].z, raw.e[2 * u + 1].w};
+#pragma unroll
+      for (int c = 0; c < 8; ++c) {
+        float q = EF ? w[c] + e[c] : w[c];
+        h.q[8 * u + c] = q;
+        if (LINF) mx = fmaxf(mx, fabsf(q));
+        else acc = fma((double)q, (double)q, acc);
+      }
+    }
+    return LINF ? (double)mx : acc;
+  }
+  __device__ void early(uint32_t, Held &) const {}
+
+  __device__ float nu_of(uint32_t p, double total) const {
+    if (override) return override[p];
+    return LINF ? (float)total : (float)sqrt(total);
+  }
+  __device__ void header(uint32_t item, float nu) const {
+    if (tile_off(item) == 0 && threadIdx.x == 0) {
+      uint32_t *hdr = reinterpret_cast<uint32_t *>(payload + (uint64_t)part_of(item) * g.stride);
+      hdr[0] = __float_as_uint(nu);
+      hdr[1] = 0; hdr[2] = 0; hdr[3] = 0;
+    }
+  }
+
+  // Level, nibble and residual of one element.  The decoded magnitude (nu * level) / s comes
+  // from a table of the s + 1 possible values.
+  // a = s|q|/nu is |q| * (s/nu); SLOW (s/nu not finite) divides per element instead.
+  template <bool SLOW>
+  __device__ uint32_t quantise(float q, float nu, float s_over_nu, uint32_t r, const float *mag,
+                               float *resid) const {
+    const uint32_t s = levels;
+    float a = SLOW ? (fabsf(q) * (float)s) / nu : fabsf(q) * s_over_nu;
+    float l = floorf(a);
+    float f = a - l;
+    float u = (float)(r >> 8) * 0x1p-24f;
+    uint32_t level = (uint32_t)l + (u < f ? 1u : 0u);
+    level = level > s ? s : level;
+    const float m = mag[level];
+    *resid = q - (q < 0.0f ? -m : m);
+    return (q < 0.0f ? 8u : 0u) | level;
+  }
+
+  __device__ void fill_table(float nu, float *mag) const {
+    __syncthreads();
+    if (threadIdx.x < 8) mag[threadIdx.x] = (nu * (float)threadIdx.x) / (float)levels;
+    __syncthreads();
+  }
+
+  // 0: nu is not positive, everything encodes to level 0; 1: fast path; 2: per-element division
+  __device__ static int mode_of(float nu, float s_over_nu) {
+    return !(nu > 0.0f) ? 0 : s_over_nu <= 3.402823466e38f ? 1 : 2;
+  }
+
+  __device__ void phase2(uint32_t item, Held &h, double total) const {
+    __shared__ float mag[8];
+    const uint32_t p = part_of(item);
+    const float nu = nu_of(p, total);
+    header(item, nu);
+    fill_table(nu, mag);
+    const float s_over_nu = (float)levels / nu;
+    const int mode = mode_of(nu, s_over_nu);
+    if (mode == 1) phase2_body<1>(item, h, nu, s_over_nu, mag);
+    else if (mode == 2) phase2_body<2>(item, h, nu, s_over_nu, mag);
+    else phase2_body<0>(item, h, nu, s_over_nu, mag);
+  }
+
+  template <int MODE>
+  __device__ void phase2_body(uint32_t item, Held &h, float nu, float s_over_nu, const float *mag) const {
+    const uint32_t p = part_of(item);
+    const Philox rng(seed, stream_id, p);
+    const uint64_t b = base(item);
+    uint32_t *nibs = reinterpret_cast<uint32_t *>(payload + (uint64_t)p * g.stride + kHeaderBytes);
+#pragma unroll
+    for (int u = 0; u < kDRows; ++u) {
+      const uint32_t off = (u * kCThreads + threadIdx.x) * 8;  // within the tile
+      const uint32_t j0 = tile_off(item) + off;                // within the partition
+      uint32_t word = 0;
+      float r[8];
+      if (MODE == 0) {
+#pragma unroll
+        for (int c = 0; c < 8; ++c) r[c] = h.q[8 * u + c];
+      } else {
+        uint32_t rnd[8];
+        rng.block(j0 >> 2, rnd);
+        rng.block((j0 >> 2) + 1, rnd + 4);
+#pragma unroll
+        for (int c = 0; c < 8; ++c)
+          word |= quantise<MODE == 2>(h.q[8 * u + c], nu, s_over_nu, rnd[c], mag, &r[c]) << (4 * c);
+      }
+      nibs[j0 >> 3] = word;
+      if (EF) {
+        float4 *o4 = reinterpret_cast<float4 *>(res + b + off);
+        o4[0] = make_float4(r[0], r[1], r[2], r[3]);
+        o4[1] = make_float4(r[4], r[5], r[6], r[7]);
+      }
+    }
+  }
+
+  // Ragged last tile of a partition: rolled loops, nothing kept in registers, phase 2 reads
+  // g and e again (at most one such tile per call).
+  __device__ float ragged_q(uint64_t i) const {
+    float v = load_grad(grad, i);
+    return EF ? v + res[i] : v;
+  }
+  __device__ double ragged_phase1(uint32_t item) const {
+    const uint32_t n_here = g.part_size(part_of(item)) - tile_off(item);
+    const uint64_t b = base(item);
+    double acc = 0.0;
+    float mx = 0.0f;
+    for (uint32_t j = threadIdx.x; j < n_here; j += kCThreads) {
+      float q = ragged_q(b + j);
+      if (LINF) mx = fmaxf(mx, fabsf(q));
+      else acc = fma((double)q, (double)q, acc);
+    }
+    return LINF ? (double)mx : acc;
+  }
+  __device__ void ragged_phase2(uint32_t item, double total) const {
+    __shared__ float mag[8];
+    const uint32_t p = part_of(item);
+    const uint32_t d = g.part_size(p), toff = tile_off(item), n_here = d - toff;
+    const float nu = nu_of(p, total);
+    header(item, nu);
+    fill_table(nu, mag);
+    const float s_over_nu = (float)levels / nu;
+    const int mode = mode_of(nu, s_over_nu);
+    const Philox rng(seed, stream_id, p);
+    const uint64_t b = base(item);
+    uint32_t *nibs = reinterpret_cast<uint32_t *>(payload + (uint64_t)p * g.stride + kHeaderBytes);
+    const uint32_t n_words = (uint32_t)ru4(cdiv(d, 8));
+    for (uint32_t w = (toff >> 3) + threadIdx.x; w < n_words; w += kCThreads) {
+      const uint32_t j0 = w * 8;
+      uint32_t rnd[8];
+      rng.block(j0 >> 2, rnd);
+      rng.block((j0 >> 2) + 1, rnd + 4);
+      uint32_t word = 0;
+      for (int c = 0; c < 8; ++c) {
+        const uint32_t j = j0 + c;
+        if (j < d) {
+          const float q = ragged_q(g.part_base(p) + j);
+          float r = q;
+          if (mode == 1) word |= quantise<false>(q, nu, s_over_nu, rnd[c], mag, &r) << (4 * c);
+          else if (mode == 2) word |= quantise<true>(q, nu, s_over_nu, rnd[c], mag, &r) << (4 * c);
+          if (EF) res[g.part_base(p) + j] = r;
+        }
+      }
+      nibs[w] = word;
+    }
+    (void)n_here;
+    (void)b;
+  }
+};
+
+template <class G, bool EF>
+static hipError_t launch_dither(const Geo &g, const ClusterGeo &cg, const bpc_params_t &prm, const Source &src,
+                                uint8_t *payload, double *slots, uint32_t *status, hipStream_t stream,
+                                bool *used) {
+  if (prm.norm == BPC_NORM_LINF)
+    return launch_cluster(DitherWorkerOp<G, EF, true>{g, cg, (const G *)src.grad, src.residual, payload,
+                                                      prm.norm_override, prm.levels, prm.seed, prm.stream_id},
+                          cg, slots, status, stream, used);
+  return launch_cluster(DitherWorkerOp<G, EF, false>{g, cg, (const G *)src.grad, src.residual, payload,
+                                                     prm.norm_override, prm.levels, prm.seed, prm.stream_id},
+                        cg, slots, status, stream, used);
+}
+
+hipError_t dither_worker_single_pass(const Geo &g, const bpc_params_t &prm, const Source &src, uint8_t *payload,
+                                     const Workspace &ws, hipStream_t stream, bool *used) {
+  ClusterGeo cg = make_cluster_geo(g);
+  double *slots = ws.at<double>(ws.lay.slots);
+  uint32_t *status = ws.at<uint32_t>(ws.lay.status);
+  const bool f16 = src.dtype == BPC_F16;
+  if (src.residual)
+    return f16 ? launch_dither<__half, true>(g, cg, prm, src, payload, slots, status, stream, used)
+               : launch_dither<float, true>(g, cg, prm, src, payload, slots, status, stream, used);
+  return f16 ? launch_dither<__half, false>(g, cg, prm, src, payload, slots, status, stream, used)
+             : launch_dither<float, false>(g, cg, prm, src, payload, slots, status, stream, used);
+}
+
+}  // namespace bpc

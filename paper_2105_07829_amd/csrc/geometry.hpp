@@ -95,7 +95,7 @@ struct WsLayout {
   size_t hist;       // u32[P*4096]: top-k radix histograms (2048 + 1024 + 1024 bins)
   size_t state;      // u32[P*8]: top-k selection state
   size_t tilecnt;    // u32[2*n_tiles]: per-tile (greater, equal) counts, then offsets
-  size_t slots;      // double[3 * tiles of 65536]: partition-wide reductions of the single-pass kernels
+  size_t slots;      // double[3 * tiles of 32768]: partition-wide reductions of the single-pass kernels
   size_t status;     // u32[64]: word 0 is non-zero if a single-pass kernel gave up waiting
   size_t norms;      // double[3*P]: LANS block norms when blocks are the partitions
   size_t total;
@@ -112,7 +112,7 @@ inline WsLayout ws_layout(const bpc_params_t *p, uint64_t D) {
   w.hist = take(p->kind == BPC_TOPK ? sizeof(uint32_t) * 4096 * (size_t)g.P : 0);
   w.state = take(p->kind == BPC_TOPK ? sizeof(uint32_t) * 8 * (size_t)g.P : 0);
   w.tilecnt = take(p->kind == BPC_TOPK ? sizeof(uint32_t) * 2 * (size_t)g.n_tiles : 0);
-  w.slots = take(sizeof(double) * 3 * ((size_t)g.P * cdiv(g.part_elems, 65536)));
+  w.slots = take(sizeof(double) * 3 * ((size_t)g.P * cdiv(g.part_elems, 32768)));
   w.status = take(256);
   w.norms = take(sizeof(double) * 3 * (size_t)g.P);
   w.total = off;

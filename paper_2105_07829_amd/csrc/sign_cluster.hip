@@ -1,14 +1,13 @@
 // Scaled-sign worker, single pass (Algorithm 4 worker lines with C(v) = ||v||_1/d sign(v)):
-// each workgroup reads a 65536-element tile of g and e once, keeps q = g + e in registers,
+// each workgroup reads a 32768-element tile of g and e once, keeps q = g + e in registers,
 // writes the sign bits, publishes its part of ||q||_1, waits for the partition's sum and then
 // writes e' = q -+ sigma.  HBM traffic is the algorithmic minimum: g and e read once, e' and
 // the bits written once.
-#include "cluster.hpp"
-#include "kernels.hpp"
+#include "cluster_launch.hpp"
 
 namespace bpc {
 
-constexpr int kRows = kCPerThread / 4;  // 16 rows of 4096 elements; a thread owns 4 consecutive per row
+constexpr int kRows = kCPerThread / 4;  // 8 rows of 4096 elements; a thread owns 4 consecutive per row
 
 __device__ inline void widen4(const float4 &g, float out[4]) { out[0] = g.x; out[1] = g.y; out[2] = g.z; out[3] = g.w; }
 __device__ inline void widen4(const uint2 &g, float out[4]) {
@@ -22,164 +21,155 @@ template <> struct Vec4Of<__half> { using type = uint2; };
 
 // Sign bits of a row: every lane holds a nibble for its 4 elements; 8 neighbouring lanes are
 // merged into one 32-bit word which lane 8w of the wave ends up holding.
+// (DPP row_shl:n makes lane i read lane i+n of its 16-lane row; lanes past the row read 0.)
+__device__ inline uint32_t from_lane_above(uint32_t x, int n) {
+  return n == 1   ? (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x101, 0xf, 0xf, true)
+         : n == 2 ? (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x102, 0xf, 0xf, true)
+                  : (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x104, 0xf, 0xf, true);
+}
 __device__ inline uint32_t merge8(uint32_t nib) {
-  nib |= __shfl_down(nib, 1, 64) << 4;
-  nib |= __shfl_down(nib, 2, 64) << 8;
-  nib |= __shfl_down(nib, 4, 64) << 16;
+  nib |= from_lane_above(nib, 1) << 4;
+  nib |= from_lane_above(nib, 2) << 8;
+  nib |= from_lane_above(nib, 4) << 16;
   return nib;
 }
 
 template <class G, bool EF>
-__global__ __launch_bounds__(kCThreads) void sign_worker_cluster_kernel(
-    Geo g, ClusterGeo cg, const G *__restrict__ grad, float *__restrict__ res, uint8_t *__restrict__ payload,
-    double *slots, uint32_t *status, const float *__restrict__ override) {
+struct SignWorkerOp {
   using GV = typename Vec4Of<G>::type;
-  __shared__ double red[kCThreads / 64];
-  __shared__ float sigma_sh;
-  const uint32_t t = threadIdx.x;
-  for (uint32_t item = blockIdx.x; item < cg.n_items; item += gridDim.x) {
-    const uint32_t p = item / cg.tiles_per_part;
-    const uint32_t tile = item % cg.tiles_per_part;
-    const uint32_t d = g.part_size(p);
-    const uint32_t tile_off = tile * kCTile;
-    const uint32_t n_here = d - tile_off < (uint32_t)kCTile ? d - tile_off : (uint32_t)kCTile;
-    const uint64_t base = g.part_base(p) + tile_off;
-    const bool full = n_here == (uint32_t)kCTile;
-    float q[kCPerThread];
-    // ---- phase 1: q = g + e
-    if (full) {
-      const GV *g4 = reinterpret_cast<const GV *>(grad + base);
-      const float4 *e4 = reinterpret_cast<const float4 *>(res + base);
-      GV gr[kRows];
+  struct Raw { GV g[kRows]; float4 e[kRows]; };
+  struct Held { float q[kCPerThread]; };
+  static constexpr bool kMax = false;
+
+  Geo g;
+  ClusterGeo cg;
+  const G *__restrict__ grad;
+  float *__restrict__ res;
+  uint8_t *__restrict__ payload;
+  const float *__restrict__ override;
+
+  __device__ uint32_t n_items() const { return cg.n_items; }
+  __device__ bool needs_total() const { return override == nullptr; }
+  __device__ uint32_t part_of(uint32_t item) const { return item / cg.tiles_per_part; }
+  __device__ uint32_t tile_off(uint32_t item) const { return (item % cg.tiles_per_part) * kCTile; }
+  __device__ bool full(uint32_t item) const { return g.part_size(part_of(item)) - tile_off(item) >= (uint32_t)kCTile; }
+  __device__ uint64_t base(uint32_t item) const { return g.part_base(part_of(item)) + tile_off(item); }
+  __device__ void slots_of(uint32_t item, uint32_t *first, uint32_t *count) const {
+    uint32_t p = part_of(item);
+    *first = p * cg.tiles_per_part;
+    *count = (uint32_t)cdiv(g.part_size(p), kCTile);
+  }
+  __device__ uint32_t *bits_of(uint32_t p) const {
+    return reinterpret_cast<uint32_t *>(payload + (uint64_t)p * g.stride + kHeaderBytes);
+  }
+
+  __device__ void issue(uint32_t item, Raw &raw) const {
+    const uint64_t b = base(item);
+    const GV *g4 = reinterpret_cast<const GV *>(grad + b);
+    const float4 *e4 = reinterpret_cast<const float4 *>(res + b);
 #pragma unroll
-      for (int u = 0; u < kRows; ++u) gr[u] = g4[u * kCThreads + t];
-      if (EF) {
-#pragma unroll
-        for (int u = 0; u < kRows; ++u) {
-          float4 e = e4[u * kCThreads + t];
-          q[4 * u] = e.x; q[4 * u + 1] = e.y; q[4 * u + 2] = e.z; q[4 * u + 3] = e.w;
-        }
-      }
-#pragma unroll
-      for (int u = 0; u < kRows; ++u) {
-        float w[4];
-        widen4(gr[u], w);
-#pragma unroll
-        for (int c = 0; c < 4; ++c) q[4 * u + c] = EF ? w[c] + q[4 * u + c] : w[c];
-      }
+    for (int u = 0; u < kRows; ++u) {
+      raw.g[u] = g4[u * kCThreads + threadIdx.x];
+      if (EF) raw.e[u] = e4[u * kCThreads + threadIdx.x];
     }
-    // ---- sign bits and the tile's share of ||q||_1
-    uint32_t *bits = reinterpret_cast<uint32_t *>(payload + (uint64_t)p * g.stride + kHeaderBytes);
-    const uint32_t n_words = (uint32_t)ru4(cdiv(d, 32));
+  }
+
+  __device__ double phase1(uint32_t, Raw &raw, Held &h) const {
     double acc = 0.0;
-    if (full) {
 #pragma unroll
-      for (int u = 0; u < kRows; ++u) {
-        uint32_t nib = 0;
+    for (int u = 0; u < kRows; ++u) {
+      float w[4];
+      widen4(raw.g[u], w);
+      const float e[4] = {raw.e[u].x, raw.e[u].y, raw.e[u].z, raw.e[u].w};
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-          nib |= (q[4 * u + c] < 0.0f ? 1u : 0u) << c;
-          acc += (double)fabsf(q[4 * u + c]);
-        }
-        uint32_t word = merge8(nib);
-        uint32_t widx = (tile_off >> 5) + u * (kCThreads * 4 / 32) + (t >> 3);
-        if ((t & 7) == 0) bits[widx] = word;
-      }
-    } else {
-      // ragged last tile of a partition: lane-strided and rolled, nothing kept in registers;
-      // phase 2 reads g and e again (one tile per call at most)
-      const uint32_t lane = t & 63;
-      for (uint32_t c0 = (t >> 6) * 64; c0 < (uint32_t)kCTile; c0 += kCThreads) {
-        uint32_t j = c0 + lane;
-        uint32_t word = (tile_off + c0) >> 5;
-        if (word >= n_words) break;
-        float v = 0.0f;
-        if (j < n_here) {
-          v = load_grad(grad, base + j);
-          if (EF) v = v + res[base + j];
-        }
-        uint64_t mask = __ballot(v < 0.0f);
-        if (lane == 0) *reinterpret_cast<uint64_t *>(bits + word) = mask;
-        acc += (double)fabsf(v);
+      for (int c = 0; c < 4; ++c) {
+        float q = EF ? w[c] + e[c] : w[c];
+        h.q[4 * u + c] = q;
+        acc += (double)fabsf(q);
       }
     }
-    float sigma;
-    if (override) {
-      sigma = override[p];
-    } else {
-      double part = cluster_block_reduce<false>(acc, red);
-      if (t < 64) {
-        const uint32_t first = p * cg.tiles_per_part;
-        if (t == 0) slot_publish(slots + item, part);
-        double total = slots_collect<false>(slots + first, (uint32_t)cdiv(d, kCTile), status);
-        if (t == 0) sigma_sh = (float)(total / (double)d);
-      }
-      __syncthreads();
-      sigma = sigma_sh;
+    return acc;
+  }
+
+  __device__ void early(uint32_t item, Held &h) const {
+    uint32_t *bits = bits_of(part_of(item));
+    const uint32_t t = threadIdx.x;
+#pragma unroll
+    for (int u = 0; u < kRows; ++u) {
+      uint32_t nib = 0;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) nib |= (h.q[4 * u + c] < 0.0f ? 1u : 0u) << c;
+      uint32_t word = merge8(nib);
+      uint32_t widx = (tile_off(item) >> 5) + u * (kCThreads * 4 / 32) + (t >> 3);
+      if ((t & 7) == 0) bits[widx] = word;
     }
-    if (tile == 0 && t == 0) {
-      uint32_t *hdr = reinterpret_cast<uint32_t *>(payload + (uint64_t)p * g.stride);
+  }
+
+  __device__ float sigma_of(uint32_t p, double total) const {
+    return override ? override[p] : (float)(total / (double)g.part_size(p));
+  }
+  __device__ void header(uint32_t item, float sigma) const {
+    if (tile_off(item) == 0 && threadIdx.x == 0) {
+      uint32_t *hdr = reinterpret_cast<uint32_t *>(payload + (uint64_t)part_of(item) * g.stride);
       hdr[0] = __float_as_uint(sigma);
       hdr[1] = 0; hdr[2] = 0; hdr[3] = 0;
     }
-    // ---- phase 2: e' = q - C(q)
-    if (EF) {
-      if (full) {
-        float4 *o4 = reinterpret_cast<float4 *>(res + base);
-#pragma unroll
-        for (int u = 0; u < kRows; ++u) {
-          float4 o;
-          o.x = q[4 * u] - (q[4 * u] < 0.0f ? -sigma : sigma);
-          o.y = q[4 * u + 1] - (q[4 * u + 1] < 0.0f ? -sigma : sigma);
-          o.z = q[4 * u + 2] - (q[4 * u + 2] < 0.0f ? -sigma : sigma);
-          o.w = q[4 * u + 3] - (q[4 * u + 3] < 0.0f ? -sigma : sigma);
-          o4[u * kCThreads + t] = o;
-        }
-      } else {
-        for (uint32_t j = t; j < n_here; j += kCThreads) {
-          float v = load_grad(grad, base + j) + res[base + j];
-          res[base + j] = v - (v < 0.0f ? -sigma : sigma);
-        }
-      }
-    }
-    __syncthreads();  // red / sigma_sh are reused by the next item
   }
-}
 
-__global__ void slots_reset_kernel(double *slots, uint32_t n, uint32_t *status) {
-  uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) slots[i] = -1.0;
-  if (i == 0) *status = 0;
-}
+  __device__ void phase2(uint32_t item, Held &h, double total) const {
+    const float sigma = sigma_of(part_of(item), total);
+    header(item, sigma);
+    if (!EF) return;
+    float4 *o4 = reinterpret_cast<float4 *>(res + base(item));
+#pragma unroll
+    for (int u = 0; u < kRows; ++u) {
+      float4 o;
+      o.x = h.q[4 * u] - (h.q[4 * u] < 0.0f ? -sigma : sigma);
+      o.y = h.q[4 * u + 1] - (h.q[4 * u + 1] < 0.0f ? -sigma : sigma);
+      o.z = h.q[4 * u + 2] - (h.q[4 * u + 2] < 0.0f ? -sigma : sigma);
+      o.w = h.q[4 * u + 3] - (h.q[4 * u + 3] < 0.0f ? -sigma : sigma);
+      o4[u * kCThreads + threadIdx.x] = o;
+    }
+  }
 
-// Number of workgroups of `kernel` that can be resident at once on the current device.
-static int resident_capacity(const void *kernel) {
-  int dev = 0, cus = 0, per_cu = 0;
-  if (hipGetDevice(&dev) != hipSuccess) return 0;
-  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
-  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kCThreads, 0) != hipSuccess) return 0;
-  return cus * per_cu;
-}
-
-template <class G, bool EF>
-static hipError_t launch_sign_worker(const Geo &g, const ClusterGeo &cg, const void *grad, float *res,
-                                     uint8_t *payload, double *slots, uint32_t *status, const float *override,
-                                     hipStream_t stream, bool *used) {
-  const void *fn = reinterpret_cast<const void *>(&sign_worker_cluster_kernel<G, EF>);
-  static int capacity = 0;  // per kernel instantiation; a property of the device and the code object
-  if (capacity == 0) capacity = resident_capacity(fn);
-  *used = false;
-  if (capacity <= 0) return hipSuccess;
-  uint32_t grid = cg.n_items < (uint32_t)capacity ? cg.n_items : (uint32_t)capacity;
-  if (cg.tiles_per_part > grid) return hipSuccess;  // a partition must fit in the resident grid
-  slots_reset_kernel<<<(uint32_t)cdiv(cg.n_items, 256), 256, 0, stream>>>(slots, cg.n_items, status);
-  Geo g_ = g;
-  ClusterGeo cg_ = cg;
-  const G *grad_ = (const G *)grad;
-  void *args[] = {&g_, &cg_, &grad_, &res, &payload, &slots, &status, &override};
-  *used = true;
-  return hipLaunchCooperativeKernel(fn, dim3(grid), dim3(kCThreads), args, 0, stream);
-}
+  // Ragged last tile of a partition: lane-strided and rolled, nothing kept in registers;
+  // phase 2 reads g and e again (at most one such tile per call).
+  __device__ double ragged_phase1(uint32_t item) const {
+    const uint32_t p = part_of(item), toff = tile_off(item);
+    const uint32_t d = g.part_size(p), n_here = d - toff;
+    const uint64_t b = base(item);
+    uint32_t *bits = bits_of(p);
+    const uint32_t n_words = (uint32_t)ru4(cdiv(d, 32));
+    const uint32_t lane = threadIdx.x & 63;
+    double acc = 0.0;
+    for (uint32_t c0 = (threadIdx.x >> 6) * 64; c0 < (uint32_t)kCTile; c0 += kCThreads) {
+      uint32_t j = c0 + lane;
+      uint32_t word = (toff + c0) >> 5;
+      if (word >= n_words) break;
+      float v = 0.0f;
+      if (j < n_here) {
+        v = load_grad(grad, b + j);
+        if (EF) v = v + res[b + j];
+      }
+      uint64_t mask = __ballot(v < 0.0f);
+      if (lane == 0) *reinterpret_cast<uint64_t *>(bits + word) = mask;
+      acc += (double)fabsf(v);
+    }
+    return acc;
+  }
+  __device__ void ragged_phase2(uint32_t item, double total) const {
+    const uint32_t p = part_of(item);
+    const float sigma = sigma_of(p, total);
+    header(item, sigma);
+    if (!EF) return;
+    const uint32_t n_here = g.part_size(p) - tile_off(item);
+    const uint64_t b = base(item);
+    for (uint32_t j = threadIdx.x; j < n_here; j += kCThreads) {
+      float v = load_grad(grad, b + j) + res[b + j];
+      res[b + j] = v - (v < 0.0f ? -sigma : sigma);
+    }
+  }
+};
 
 // Returns hipSuccess with *used = false when the single-pass kernel cannot run this shape
 // (the caller then takes the multi-pass path).
@@ -190,15 +180,17 @@ hipError_t sign_worker_single_pass(const Geo &g, const bpc_params_t &prm, const 
   uint32_t *status = ws.at<uint32_t>(ws.lay.status);
   const bool f16 = src.dtype == BPC_F16;
   if (src.residual) {
-    return f16 ? launch_sign_worker<__half, true>(g, cg, src.grad, src.residual, payload, slots, status,
-                                                  prm.norm_override, stream, used)
-               : launch_sign_worker<float, true>(g, cg, src.grad, src.residual, payload, slots, status,
-                                                 prm.norm_override, stream, used);
+    if (f16)
+      return launch_cluster(SignWorkerOp<__half, true>{g, cg, (const __half *)src.grad, src.residual, payload, prm.norm_override},
+                            cg, slots, status, stream, used);
+    return launch_cluster(SignWorkerOp<float, true>{g, cg, (const float *)src.grad, src.residual, payload, prm.norm_override},
+                          cg, slots, status, stream, used);
   }
-  return f16 ? launch_sign_worker<__half, false>(g, cg, src.grad, nullptr, payload, slots, status,
-                                                 prm.norm_override, stream, used)
-             : launch_sign_worker<float, false>(g, cg, src.grad, nullptr, payload, slots, status,
-                                                prm.norm_override, stream, used);
+  if (f16)
+    return launch_cluster(SignWorkerOp<__half, false>{g, cg, (const __half *)src.grad, nullptr, payload, prm.norm_override},
+                          cg, slots, status, stream, used);
+  return launch_cluster(SignWorkerOp<float, false>{g, cg, (const float *)src.grad, nullptr, payload, prm.norm_override},
+                        cg, slots, status, stream, used);
 }
 
 }  // namespace bpc

@@ -283,7 +283,7 @@ def test_dither_uses_one_draw_per_element_in_index_order(orc):
     for j in range(d):
         blk = orc.philox4x32_10([j // 4, part_no, stream & 0xFFFFFFFF, stream >> 32], [seed, 0])
         u = np.float32(int(blk[j % 4]) >> 8) * np.float32(2.0 ** -24)
-        a = np.float32(np.float32(abs(x[j])) * np.float32(s)) / np.float32(nu)
+        a = np.float32(abs(x[j])) * (np.float32(s) / np.float32(nu))      # |x| * (s / nu), float32
         l = np.floor(a)
         exp = min(s, int(l) + int(u < np.float32(a - l)))
         assert lvl[j] == exp
