@@ -114,34 +114,44 @@ __device__ inline double cluster_block_reduce(double x, double *red /*kCThreads/
 //   struct Raw, struct Held;                     raw loads of a tile / what is kept for phase 2
 //   uint32_t n_items() const;
 //   bool   full(item) const;                     tile completely inside its partition
-//   void   issue(item, Raw&) const;              start the loads of a full tile
+//   void   issue_row(item, row, Raw&) const;     start the loads of one row of a full tile
 //   double phase1(item, Raw&, Held&) const;      consume the loads, return the tile's partial
 //   void   early(item, Held&) const;             stores that do not need the norm
-//   double ragged_phase1(item) const;            same for a ragged tile, nothing held
-//   void   slots_of(item, first, count, denom)   the partition's slots
-//   void   phase2(item, Held&, double total) const;   / ragged_phase2(item, total)
-//   static constexpr bool kMax;                  reduction is a maximum instead of a sum
-// While a workgroup waits for its partition's total and writes its outputs, the loads of
-// its next tile are already in flight.
+//   void   begin2(item, total) / row2(item, row, Held&) const;   outputs of one row
+//   double ragged_phase1(item) / ragged_phase2(item, total);     rolled path, nothing held
+//   void   slots_of(item, first, count)          the partition's slots
+//   static constexpr int kRowsPerTile; static constexpr bool kMax (maximum instead of sum)
+//   static constexpr bool kPrefetchEarly
+// The loads of a workgroup's next tile are in flight while it waits for its partition's total
+// and writes its outputs: either all issued right after phase 1 (kPrefetchEarly; best when
+// phase 2 is little more than stores) or row by row between the rows of output (best when
+// phase 2 is arithmetic-heavy, so that loads, arithmetic and stores of the CU interleave).
 template <class Op>
 __device__ inline void cluster_run(const Op &op, double *slots, uint32_t *status) {
   __shared__ double red[kCThreads / 64];
   __shared__ double total_sh;
   const uint32_t n_items = op.n_items();
-  uint32_t item = blockIdx.x;
+  // item numbers are the same for every lane: keeping them in scalar registers makes all
+  // tile addresses scalar base + per-thread offset
+  uint32_t item = __builtin_amdgcn_readfirstlane(blockIdx.x);
   if (item >= n_items) return;
   typename Op::Raw raw;
   bool full = op.full(item);
-  if (full) op.issue(item, raw);
+  if (full) {
+#pragma unroll
+    for (int u = 0; u < Op::kRowsPerTile; ++u) op.issue_row(item, u, raw);
+  }
   for (;;) {
     typename Op::Held held;
     double part = full ? op.phase1(item, raw, held) : op.ragged_phase1(item);
-    const uint32_t next = item + gridDim.x;
+    const uint32_t next = __builtin_amdgcn_readfirstlane(item + gridDim.x);
     const bool have_next = next < n_items;
     const bool next_full = have_next && op.full(next);
-    if (next_full) op.issue(next, raw);
+    if (Op::kPrefetchEarly && next_full) {
+#pragma unroll
+      for (int u = 0; u < Op::kRowsPerTile; ++u) op.issue_row(next, u, raw);
+    }
     part = cluster_block_reduce<Op::kMax>(part, red);
-    if (full) op.early(item, held);
     if (threadIdx.x < 64) {
       uint32_t first, count;
       op.slots_of(item, &first, &count);
@@ -151,9 +161,23 @@ __device__ inline void cluster_run(const Op &op, double *slots, uint32_t *status
         if (threadIdx.x == 0) total_sh = total;
       }
     }
+    if (full) op.early(item, held);
     __syncthreads();
     const double total = total_sh;
-    if (full) op.phase2(item, held, total); else op.ragged_phase2(item, total);
+    if (full) {
+      op.begin2(item, total);
+#pragma unroll
+      for (int u = 0; u < Op::kRowsPerTile; ++u) {
+        op.row2(item, u, held);
+        if (!Op::kPrefetchEarly && next_full) op.issue_row(next, u, raw);
+      }
+    } else {
+      op.ragged_phase2(item, total);
+      if (!Op::kPrefetchEarly && next_full) {
+#pragma unroll
+        for (int u = 0; u < Op::kRowsPerTile; ++u) op.issue_row(next, u, raw);
+      }
+    }
     if (!have_next) break;
     item = next;
     full = next_full;

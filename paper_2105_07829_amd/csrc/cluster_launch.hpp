@@ -7,6 +7,8 @@ namespace bpc {
 
 template <class Op>
 __global__ __launch_bounds__(kCThreads, 4) void cluster_kernel(Op op, double *slots, uint32_t *status) {
+  __shared__ float table[Op::kTableFloats];
+  op.set_table(table);
   cluster_run(op, slots, status);
 }
 

@@ -38,6 +38,15 @@ struct Philox {
   }
 };
 
+// Marks an element offset that is the same in every lane as such, so that `base + offset`
+// stays a scalar and accesses take the "scalar base + 32-bit lane offset" addressing form
+// instead of needing a 64-bit address register pair per access.
+__device__ inline uint64_t uniform_off(uint64_t v) {
+  uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+  uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+  return ((uint64_t)hi << 32) | lo;
+}
+
 __device__ inline float load_grad(const float *g, uint64_t i) { return g[i]; }
 __device__ inline float load_grad(const __half *g, uint64_t i) { return __half2float(g[i]); }
 

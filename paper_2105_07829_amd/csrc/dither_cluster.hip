@@ -37,6 +37,10 @@ struct DitherWorkerOp {
   struct Raw { GV g[kDRows]; float4 e[2 * kDRows]; };
   struct Held { float q[kCPerThread]; };
   static constexpr bool kMax = LINF;
+  static constexpr int kRowsPerTile = kDRows;
+  static constexpr int kTableFloats = 8;
+  static constexpr bool kPrefetchEarly = false;
+  __device__ void set_table(float *t) { mag = t; }
 
   Geo g;
   ClusterGeo cg;
@@ -46,6 +50,9 @@ struct DitherWorkerOp {
   const float *__restrict__ override;
   uint32_t levels;
   uint64_t seed, stream_id;
+  float *mag;            // LDS table of the s + 1 decoded magnitudes (set by the kernel wrapper)
+  mutable float nu, s_over_nu;   // of the tile being written (set by begin2)
+  mutable int mode;
 
   __device__ uint32_t n_items() const { return cg.n_items; }
   __device__ bool needs_total() const { return override == nullptr; }
@@ -59,17 +66,13 @@ struct DitherWorkerOp {
     *count = (uint32_t)cdiv(g.part_size(p), kCTile);
   }
 
-  __device__ void issue(uint32_t item, Raw &raw) const {
-    const uint64_t b = base(item);
-#pragma unroll
-    for (int u = 0; u < kDRows; ++u) {
-      const uint32_t off = (u * kCThreads + threadIdx.x) * 8;
-      raw.g[u] = load8(grad + b + off);
-      if (EF) {
-        const float4 *e4 = reinterpret_cast<const float4 *>(res + b + off);
-        raw.e[2 * u] = e4[0];
-        raw.e[2 * u + 1] = e4[1];
-      }
+  __device__ void issue_row(uint32_t item, int u, Raw &raw) const {
+    const uint64_t b = uniform_off(base(item) + (uint32_t)u * (kCThreads * 8));
+    raw.g[u] = load8(grad + b + threadIdx.x * 8);
+    if (EF) {
+      const float4 *e4 = reinterpret_cast<const float4 *>(res + b) + threadIdx.x * 2;
+      raw.e[2 * u] = e4[0];
+      raw.e[2 * u + 1] = e4[1];
     }
   }
 
@@ -135,48 +138,46 @@ struct DitherWorkerOp {
     return !(nu > 0.0f) ? 0 : s_over_nu <= 3.402823466e38f ? 1 : 2;
   }
 
-  __device__ void phase2(uint32_t item, Held &h, double total) const {
-    __shared__ float mag[8];
+  __device__ void begin2(uint32_t item, double total) const {
     const uint32_t p = part_of(item);
-    const float nu = nu_of(p, total);
+    nu = nu_of(p, total);
     header(item, nu);
     fill_table(nu, mag);
-    const float s_over_nu = (float)levels / nu;
-    const int mode = mode_of(nu, s_over_nu);
-    if (mode == 1) phase2_body<1>(item, h, nu, s_over_nu, mag);
-    else if (mode == 2) phase2_body<2>(item, h, nu, s_over_nu, mag);
-    else phase2_body<0>(item, h, nu, s_over_nu, mag);
+    s_over_nu = (float)levels / nu;
+    mode = mode_of(nu, s_over_nu);
+  }
+  __device__ void row2(uint32_t item, int u, Held &h) const {
+    if (mode == 1) row2_body<1>(item, u, h);
+    else if (mode == 2) row2_body<2>(item, u, h);
+    else row2_body<0>(item, u, h);
   }
 
   template <int MODE>
-  __device__ void phase2_body(uint32_t item, Held &h, float nu, float s_over_nu, const float *mag) const {
+  __device__ void row2_body(uint32_t item, int u, Held &h) const {
     const uint32_t p = part_of(item);
     const Philox rng(seed, stream_id, p);
     const uint64_t b = base(item);
     uint32_t *nibs = reinterpret_cast<uint32_t *>(payload + (uint64_t)p * g.stride + kHeaderBytes);
+    const uint32_t off = (u * kCThreads + threadIdx.x) * 8;  // within the tile
+    const uint32_t j0 = tile_off(item) + off;                // within the partition
+    uint32_t word = 0;
+    float r[8];
+    if (MODE == 0) {
 #pragma unroll
-    for (int u = 0; u < kDRows; ++u) {
-      const uint32_t off = (u * kCThreads + threadIdx.x) * 8;  // within the tile
-      const uint32_t j0 = tile_off(item) + off;                // within the partition
-      uint32_t word = 0;
-      float r[8];
-      if (MODE == 0) {
+      for (int c = 0; c < 8; ++c) r[c] = h.q[8 * u + c];
+    } else {
+      uint32_t rnd[8];
+      rng.block(j0 >> 2, rnd);
+      rng.block((j0 >> 2) + 1, rnd + 4);
 #pragma unroll
-        for (int c = 0; c < 8; ++c) r[c] = h.q[8 * u + c];
-      } else {
-        uint32_t rnd[8];
-        rng.block(j0 >> 2, rnd);
-        rng.block((j0 >> 2) + 1, rnd + 4);
-#pragma unroll
-        for (int c = 0; c < 8; ++c)
-          word |= quantise<MODE == 2>(h.q[8 * u + c], nu, s_over_nu, rnd[c], mag, &r[c]) << (4 * c);
-      }
-      nibs[j0 >> 3] = word;
-      if (EF) {
-        float4 *o4 = reinterpret_cast<float4 *>(res + b + off);
-        o4[0] = make_float4(r[0], r[1], r[2], r[3]);
-        o4[1] = make_float4(r[4], r[5], r[6], r[7]);
-      }
+      for (int c = 0; c < 8; ++c)
+        word |= quantise<MODE == 2>(h.q[8 * u + c], nu, s_over_nu, rnd[c], mag, &r[c]) << (4 * c);
+    }
+    (nibs + uniform_off((tile_off(item) + u * (kCThreads * 8)) >> 3))[threadIdx.x] = word;
+    if (EF) {
+      float4 *o4 = reinterpret_cast<float4 *>(res + uniform_off(b + (uint32_t)u * (kCThreads * 8))) + threadIdx.x * 2;
+      o4[0] = make_float4(r[0], r[1], r[2], r[3]);
+      o4[1] = make_float4(r[4], r[5], r[6], r[7]);
     }
   }
 
@@ -199,14 +200,9 @@ struct DitherWorkerOp {
     return LINF ? (double)mx : acc;
   }
   __device__ void ragged_phase2(uint32_t item, double total) const {
-    __shared__ float mag[8];
     const uint32_t p = part_of(item);
     const uint32_t d = g.part_size(p), toff = tile_off(item), n_here = d - toff;
-    const float nu = nu_of(p, total);
-    header(item, nu);
-    fill_table(nu, mag);
-    const float s_over_nu = (float)levels / nu;
-    const int mode = mode_of(nu, s_over_nu);
+    begin2(item, total);
     const Philox rng(seed, stream_id, p);
     const uint64_t b = base(item);
     uint32_t *nibs = reinterpret_cast<uint32_t *>(payload + (uint64_t)p * g.stride + kHeaderBytes);
@@ -240,10 +236,10 @@ static hipError_t launch_dither(const Geo &g, const ClusterGeo &cg, const bpc_pa
                                 bool *used) {
   if (prm.norm == BPC_NORM_LINF)
     return launch_cluster(DitherWorkerOp<G, EF, true>{g, cg, (const G *)src.grad, src.residual, payload,
-                                                      prm.norm_override, prm.levels, prm.seed, prm.stream_id},
+                                                      prm.norm_override, prm.levels, prm.seed, prm.stream_id, nullptr, 0.0f, 0.0f, 0},
                           cg, slots, status, stream, used);
   return launch_cluster(DitherWorkerOp<G, EF, false>{g, cg, (const G *)src.grad, src.residual, payload,
-                                                     prm.norm_override, prm.levels, prm.seed, prm.stream_id},
+                                                     prm.norm_override, prm.levels, prm.seed, prm.stream_id, nullptr, 0.0f, 0.0f, 0},
                         cg, slots, status, stream, used);
 }
 

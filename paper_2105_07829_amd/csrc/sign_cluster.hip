@@ -40,6 +40,10 @@ struct SignWorkerOp {
   struct Raw { GV g[kRows]; float4 e[kRows]; };
   struct Held { float q[kCPerThread]; };
   static constexpr bool kMax = false;
+  static constexpr int kRowsPerTile = kRows;
+  static constexpr int kTableFloats = 1;
+  static constexpr bool kPrefetchEarly = true;
+  __device__ void set_table(float *) {}
 
   Geo g;
   ClusterGeo cg;
@@ -47,6 +51,7 @@ struct SignWorkerOp {
   float *__restrict__ res;
   uint8_t *__restrict__ payload;
   const float *__restrict__ override;
+  mutable float sigma;   // of the tile being written (set by begin2)
 
   __device__ uint32_t n_items() const { return cg.n_items; }
   __device__ bool needs_total() const { return override == nullptr; }
@@ -63,15 +68,10 @@ struct SignWorkerOp {
     return reinterpret_cast<uint32_t *>(payload + (uint64_t)p * g.stride + kHeaderBytes);
   }
 
-  __device__ void issue(uint32_t item, Raw &raw) const {
-    const uint64_t b = base(item);
-    const GV *g4 = reinterpret_cast<const GV *>(grad + b);
-    const float4 *e4 = reinterpret_cast<const float4 *>(res + b);
-#pragma unroll
-    for (int u = 0; u < kRows; ++u) {
-      raw.g[u] = g4[u * kCThreads + threadIdx.x];
-      if (EF) raw.e[u] = e4[u * kCThreads + threadIdx.x];
-    }
+  __device__ void issue_row(uint32_t item, int u, Raw &raw) const {
+    const uint64_t b = uniform_off(base(item) + (uint32_t)u * (kCThreads * 4));
+    raw.g[u] = reinterpret_cast<const GV *>(grad + b)[threadIdx.x];
+    if (EF) raw.e[u] = reinterpret_cast<const float4 *>(res + b)[threadIdx.x];
   }
 
   __device__ double phase1(uint32_t, Raw &raw, Held &h) const {
@@ -100,8 +100,8 @@ struct SignWorkerOp {
 #pragma unroll
       for (int c = 0; c < 4; ++c) nib |= (h.q[4 * u + c] < 0.0f ? 1u : 0u) << c;
       uint32_t word = merge8(nib);
-      uint32_t widx = (tile_off(item) >> 5) + u * (kCThreads * 4 / 32) + (t >> 3);
-      if ((t & 7) == 0) bits[widx] = word;
+      uint32_t *row_words = bits + uniform_off((tile_off(item) >> 5) + u * (kCThreads * 4 / 32));
+      if ((t & 7) == 0) row_words[t >> 3] = word;
     }
   }
 
@@ -116,20 +116,19 @@ struct SignWorkerOp {
     }
   }
 
-  __device__ void phase2(uint32_t item, Held &h, double total) const {
-    const float sigma = sigma_of(part_of(item), total);
+  __device__ void begin2(uint32_t item, double total) const {
+    sigma = sigma_of(part_of(item), total);
     header(item, sigma);
+  }
+  __device__ void row2(uint32_t item, int u, Held &h) const {
     if (!EF) return;
-    float4 *o4 = reinterpret_cast<float4 *>(res + base(item));
-#pragma unroll
-    for (int u = 0; u < kRows; ++u) {
-      float4 o;
-      o.x = h.q[4 * u] - (h.q[4 * u] < 0.0f ? -sigma : sigma);
-      o.y = h.q[4 * u + 1] - (h.q[4 * u + 1] < 0.0f ? -sigma : sigma);
-      o.z = h.q[4 * u + 2] - (h.q[4 * u + 2] < 0.0f ? -sigma : sigma);
-      o.w = h.q[4 * u + 3] - (h.q[4 * u + 3] < 0.0f ? -sigma : sigma);
-      o4[u * kCThreads + threadIdx.x] = o;
-    }
+    float4 *o4 = reinterpret_cast<float4 *>(res + uniform_off(base(item) + (uint32_t)u * (kCThreads * 4)));
+    float4 o;
+    o.x = h.q[4 * u] - (h.q[4 * u] < 0.0f ? -sigma : sigma);
+    o.y = h.q[4 * u + 1] - (h.q[4 * u + 1] < 0.0f ? -sigma : sigma);
+    o.z = h.q[4 * u + 2] - (h.q[4 * u + 2] < 0.0f ? -sigma : sigma);
+    o.w = h.q[4 * u + 3] - (h.q[4 * u + 3] < 0.0f ? -sigma : sigma);
+    o4[threadIdx.x] = o;
   }
 
   // Ragged last tile of a partition: lane-strided and rolled, nothing kept in registers;
@@ -181,15 +180,15 @@ hipError_t sign_worker_single_pass(const Geo &g, const bpc_params_t &prm, const 
   const bool f16 = src.dtype == BPC_F16;
   if (src.residual) {
     if (f16)
-      return launch_cluster(SignWorkerOp<__half, true>{g, cg, (const __half *)src.grad, src.residual, payload, prm.norm_override},
+      return launch_cluster(SignWorkerOp<__half, true>{g, cg, (const __half *)src.grad, src.residual, payload, prm.norm_override, 0.0f},
                             cg, slots, status, stream, used);
-    return launch_cluster(SignWorkerOp<float, true>{g, cg, (const float *)src.grad, src.residual, payload, prm.norm_override},
+    return launch_cluster(SignWorkerOp<float, true>{g, cg, (const float *)src.grad, src.residual, payload, prm.norm_override, 0.0f},
                           cg, slots, status, stream, used);
   }
   if (f16)
-    return launch_cluster(SignWorkerOp<__half, false>{g, cg, (const __half *)src.grad, nullptr, payload, prm.norm_override},
+    return launch_cluster(SignWorkerOp<__half, false>{g, cg, (const __half *)src.grad, nullptr, payload, prm.norm_override, 0.0f},
                           cg, slots, status, stream, used);
-  return launch_cluster(SignWorkerOp<float, false>{g, cg, (const float *)src.grad, nullptr, payload, prm.norm_override},
+  return launch_cluster(SignWorkerOp<float, false>{g, cg, (const float *)src.grad, nullptr, payload, prm.norm_override, 0.0f},
                         cg, slots, status, stream, used);
 }
 
