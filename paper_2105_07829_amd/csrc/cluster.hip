@@ -11,11 +11,11 @@ __global__ void slots_reset_kernel(double *slots, uint32_t n, uint32_t *status) 
   if (i == 0) *status = 0;
 }
 
-int cluster_capacity(const void *kernel) {
+int cluster_capacity(const void *kernel, size_t dyn_lds) {
   int dev = 0, cus = 0, per_cu = 0;
   if (hipGetDevice(&dev) != hipSuccess) return 0;
   if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
-  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kCThreads, 0) != hipSuccess) return 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kCThreads, dyn_lds) != hipSuccess) return 0;
   return cus * per_cu;
 }
 

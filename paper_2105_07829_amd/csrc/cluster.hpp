@@ -44,8 +44,8 @@ inline ClusterGeo make_cluster_geo(const Geo &g) {
 // every launch records an event, and a launch on another stream first waits for it.
 hipError_t cluster_launch_begin(hipStream_t stream);
 hipError_t cluster_launch_end(hipStream_t stream);
-// Number of workgroups of `kernel` (kCThreads threads, no dynamic LDS) resident at once.
-int cluster_capacity(const void *kernel);
+// Number of workgroups of `kernel` (kCThreads threads, `dyn_lds` bytes of dynamic LDS) resident at once.
+int cluster_capacity(const void *kernel, size_t dyn_lds = 0);
 
 #if defined(__HIPCC__)
 __global__ void slots_reset_kernel(double *slots, uint32_t n, uint32_t *status);
@@ -117,17 +117,25 @@ __device__ inline double cluster_block_reduce(double x, double *red /*kCThreads/
 //   void   issue_row(item, row, Raw&) const;     start the loads of one row of a full tile
 //   double phase1(item, Raw&, Held&) const;      consume the loads, return the tile's partial
 //   void   early(item, Held&) const;             stores that do not need the norm
-//   void   begin2(item, total) / row2(item, row, Held&) const;   outputs of one row
+//   Ctx    begin2(item, total, table) / row2(item, row, Held&, Ctx) const;   outputs of one row
 //   double ragged_phase1(item) / ragged_phase2(item, total);     rolled path, nothing held
 //   void   slots_of(item, first, count)          the partition's slots
 //   static constexpr int kRowsPerTile; static constexpr bool kMax (maximum instead of sum)
-//   static constexpr bool kPrefetchEarly
-// The loads of a workgroup's next tile are in flight while it waits for its partition's total
-// and writes its outputs: either all issued right after phase 1 (kPrefetchEarly; best when
-// phase 2 is little more than stores) or row by row between the rows of output (best when
-// phase 2 is arithmetic-heavy, so that loads, arithmetic and stores of the CU interleave).
+//   static constexpr Prefetch kPrefetch; static constexpr int kTableFloats (LDS scratch, `table`)
+// The operator is passed by value in the kernel arguments and never modified, so it stays in
+// the kernel-argument segment (a modified copy would live in scratch memory).
+// The loads of a workgroup's next tile overlap its work on the current one (see Prefetch).
+// When a tile's loads are issued relative to the work on the previous tile.
+enum class Prefetch {
+  kEarly,        // all of them right after phase 1 of the previous tile (phase 2 is mostly stores)
+  kInterleaved,  // row by row between the rows of output of the previous tile (phase 2 is
+                 // arithmetic-heavy: loads, arithmetic and stores of the CU interleave)
+  kNone          // not ahead of time: phase 1 issues its own loads and hides them behind its
+                 // arithmetic
+};
+
 template <class Op>
-__device__ inline void cluster_run(const Op &op, double *slots, uint32_t *status) {
+__device__ inline void cluster_run(const Op &op, float *table, double *slots, uint32_t *status) {
   __shared__ double red[kCThreads / 64];
   __shared__ double total_sh;
   const uint32_t n_items = op.n_items();
@@ -137,17 +145,17 @@ __device__ inline void cluster_run(const Op &op, double *slots, uint32_t *status
   if (item >= n_items) return;
   typename Op::Raw raw;
   bool full = op.full(item);
-  if (full) {
+  if (full && Op::kPrefetch != Prefetch::kNone) {
 #pragma unroll
     for (int u = 0; u < Op::kRowsPerTile; ++u) op.issue_row(item, u, raw);
   }
   for (;;) {
     typename Op::Held held;
-    double part = full ? op.phase1(item, raw, held) : op.ragged_phase1(item);
+    double part = full ? op.phase1(item, raw, held, table) : op.ragged_phase1(item, table);
     const uint32_t next = __builtin_amdgcn_readfirstlane(item + gridDim.x);
     const bool have_next = next < n_items;
     const bool next_full = have_next && op.full(next);
-    if (Op::kPrefetchEarly && next_full) {
+    if (Op::kPrefetch == Prefetch::kEarly && next_full) {
 #pragma unroll
       for (int u = 0; u < Op::kRowsPerTile; ++u) op.issue_row(next, u, raw);
     }
@@ -165,15 +173,15 @@ __device__ inline void cluster_run(const Op &op, double *slots, uint32_t *status
     __syncthreads();
     const double total = total_sh;
     if (full) {
-      op.begin2(item, total);
+      const typename Op::Ctx ctx = op.begin2(item, total, table);
 #pragma unroll
       for (int u = 0; u < Op::kRowsPerTile; ++u) {
-        op.row2(item, u, held);
-        if (!Op::kPrefetchEarly && next_full) op.issue_row(next, u, raw);
+        op.row2(item, u, held, ctx);
+        if (Op::kPrefetch == Prefetch::kInterleaved && next_full) op.issue_row(next, u, raw);
       }
     } else {
-      op.ragged_phase2(item, total);
-      if (!Op::kPrefetchEarly && next_full) {
+      op.ragged_phase2(item, total, table);
+      if (Op::kPrefetch == Prefetch::kInterleaved && next_full) {
 #pragma unroll
         for (int u = 0; u < Op::kRowsPerTile; ++u) op.issue_row(next, u, raw);
       }

@@ -6,18 +6,31 @@
 namespace bpc {
 
 template <class Op>
-__global__ __launch_bounds__(kCThreads, 4) void cluster_kernel(Op op, double *slots, uint32_t *status) {
+__global__ __launch_bounds__(kCThreads, 4) void cluster_kernel(const Op op, double *slots, uint32_t *status) {
   __shared__ float table[Op::kTableFloats];
-  op.set_table(table);
-  cluster_run(op, slots, status);
+  cluster_run(op, table, slots, status);
+}
+
+// Same, with the operator's LDS scratch allocated at launch (sizes above the static limit).
+template <class Op>
+__global__ __launch_bounds__(kCThreads, 4) void cluster_kernel_dyn(const Op op, double *slots, uint32_t *status) {
+  extern __shared__ float dyn_table[];
+  cluster_run(op, dyn_table, slots, status);
 }
 
 template <class Op>
 static hipError_t launch_cluster(const Op &op, const ClusterGeo &cg, double *slots, uint32_t *status,
-                                 hipStream_t stream, bool *used) {
-  const void *fn = reinterpret_cast<const void *>(&cluster_kernel<Op>);
+                                 hipStream_t stream, bool *used, size_t dyn_lds = 0) {
+  const void *fn = dyn_lds ? reinterpret_cast<const void *>(&cluster_kernel_dyn<Op>)
+                           : reinterpret_cast<const void *>(&cluster_kernel<Op>);
   static int capacity = 0;  // per kernel instantiation; a property of the device and the code object
-  if (capacity == 0) capacity = cluster_capacity(fn);
+  if (capacity == 0) {
+    if (dyn_lds && hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)Op::kMaxDynLds) != hipSuccess) {
+      *used = false;
+      return hipSuccess;
+    }
+    capacity = cluster_capacity(fn, dyn_lds ? Op::kMaxDynLds : 0);
+  }
   *used = false;
   if (capacity <= 0) return hipSuccess;
   uint32_t grid = cg.n_items < (uint32_t)capacity ? cg.n_items : (uint32_t)capacity;
@@ -26,7 +39,8 @@ static hipError_t launch_cluster(const Op &op, const ClusterGeo &cg, double *slo
   hipError_t e = cluster_launch_begin(stream);
   if (e != hipSuccess) return e;
   slots_reset_kernel<<<(uint32_t)cdiv(cg.n_items, 256), 256, 0, stream>>>(slots, cg.n_items, status);
-  cluster_kernel<Op><<<grid, kCThreads, 0, stream>>>(op, slots, status);
+  if (dyn_lds) cluster_kernel_dyn<Op><<<grid, kCThreads, dyn_lds, stream>>>(op, slots, status);
+  else cluster_kernel<Op><<<grid, kCThreads, 0, stream>>>(op, slots, status);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   return cluster_launch_end(stream);

@@ -39,8 +39,9 @@ struct DitherWorkerOp {
   static constexpr bool kMax = LINF;
   static constexpr int kRowsPerTile = kDRows;
   static constexpr int kTableFloats = 8;
-  static constexpr bool kPrefetchEarly = false;
-  __device__ void set_table(float *t) { mag = t; }
+  static constexpr size_t kMaxDynLds = 0;
+  static constexpr Prefetch kPrefetch = Prefetch::kInterleaved;
+  struct Ctx { float nu, s_over_nu; int mode; const float *mag; };
 
   Geo g;
   ClusterGeo cg;
@@ -50,9 +51,6 @@ struct DitherWorkerOp {
   const float *__restrict__ override;
   uint32_t levels;
   uint64_t seed, stream_id;
-  float *mag;            // LDS table of the s + 1 decoded magnitudes (set by the kernel wrapper)
-  mutable float nu, s_over_nu;   // of the tile being written (set by begin2)
-  mutable int mode;
 
   __device__ uint32_t n_items() const { return cg.n_items; }
   __device__ bool needs_total() const { return override == nullptr; }
@@ -76,7 +74,7 @@ struct DitherWorkerOp {
     }
   }
 
-  __device__ double phase1(uint32_t, Raw &raw, Held &h) const {
+  __device__ double phase1(uint32_t, Raw &raw, Held &h, float *) const {
     double acc = 0.0;
     float mx = 0.0f;
 #pragma unroll
@@ -138,22 +136,24 @@ struct DitherWorkerOp {
     return !(nu > 0.0f) ? 0 : s_over_nu <= 3.402823466e38f ? 1 : 2;
   }
 
-  __device__ void begin2(uint32_t item, double total) const {
+  __device__ Ctx begin2(uint32_t item, double total, float *mag) const {
     const uint32_t p = part_of(item);
-    nu = nu_of(p, total);
+    const float nu = nu_of(p, total);
     header(item, nu);
     fill_table(nu, mag);
-    s_over_nu = (float)levels / nu;
-    mode = mode_of(nu, s_over_nu);
+    const float s_over_nu = (float)levels / nu;
+    return Ctx{nu, s_over_nu, mode_of(nu, s_over_nu), mag};
   }
-  __device__ void row2(uint32_t item, int u, Held &h) const {
-    if (mode == 1) row2_body<1>(item, u, h);
-    else if (mode == 2) row2_body<2>(item, u, h);
-    else row2_body<0>(item, u, h);
+  __device__ void row2(uint32_t item, int u, Held &h, const Ctx &ctx) const {
+    if (ctx.mode == 1) row2_body<1>(item, u, h, ctx);
+    else if (ctx.mode == 2) row2_body<2>(item, u, h, ctx);
+    else row2_body<0>(item, u, h, ctx);
   }
 
   template <int MODE>
-  __device__ void row2_body(uint32_t item, int u, Held &h) const {
+  __device__ void row2_body(uint32_t item, int u, Held &h, const Ctx &ctx) const {
+    const float nu = ctx.nu, s_over_nu = ctx.s_over_nu;
+    const float *mag = ctx.mag;
     const uint32_t p = part_of(item);
     const Philox rng(seed, stream_id, p);
     const uint64_t b = base(item);
@@ -187,11 +187,12 @@ struct DitherWorkerOp {
     float v = load_grad(grad, i);
     return EF ? v + res[i] : v;
   }
-  __device__ double ragged_phase1(uint32_t item) const {
+  __device__ double ragged_phase1(uint32_t item, float *) const {
     const uint32_t n_here = g.part_size(part_of(item)) - tile_off(item);
     const uint64_t b = base(item);
     double acc = 0.0;
     float mx = 0.0f;
+#pragma unroll 4
     for (uint32_t j = threadIdx.x; j < n_here; j += kCThreads) {
       float q = ragged_q(b + j);
       if (LINF) mx = fmaxf(mx, fabsf(q));
@@ -199,14 +200,18 @@ struct DitherWorkerOp {
     }
     return LINF ? (double)mx : acc;
   }
-  __device__ void ragged_phase2(uint32_t item, double total) const {
+  __device__ void ragged_phase2(uint32_t item, double total, float *table) const {
     const uint32_t p = part_of(item);
     const uint32_t d = g.part_size(p), toff = tile_off(item), n_here = d - toff;
-    begin2(item, total);
+    const Ctx ctx = begin2(item, total, table);
+    const float nu = ctx.nu, s_over_nu = ctx.s_over_nu;
+    const int mode = ctx.mode;
+    const float *mag = ctx.mag;
     const Philox rng(seed, stream_id, p);
     const uint64_t b = base(item);
     uint32_t *nibs = reinterpret_cast<uint32_t *>(payload + (uint64_t)p * g.stride + kHeaderBytes);
     const uint32_t n_words = (uint32_t)ru4(cdiv(d, 8));
+#pragma unroll 2
     for (uint32_t w = (toff >> 3) + threadIdx.x; w < n_words; w += kCThreads) {
       const uint32_t j0 = w * 8;
       uint32_t rnd[8];
@@ -236,10 +241,10 @@ static hipError_t launch_dither(const Geo &g, const ClusterGeo &cg, const bpc_pa
                                 bool *used) {
   if (prm.norm == BPC_NORM_LINF)
     return launch_cluster(DitherWorkerOp<G, EF, true>{g, cg, (const G *)src.grad, src.residual, payload,
-                                                      prm.norm_override, prm.levels, prm.seed, prm.stream_id, nullptr, 0.0f, 0.0f, 0},
+                                                      prm.norm_override, prm.levels, prm.seed, prm.stream_id},
                           cg, slots, status, stream, used);
   return launch_cluster(DitherWorkerOp<G, EF, false>{g, cg, (const G *)src.grad, src.residual, payload,
-                                                     prm.norm_override, prm.levels, prm.seed, prm.stream_id, nullptr, 0.0f, 0.0f, 0},
+                                                     prm.norm_override, prm.levels, prm.seed, prm.stream_id},
                         cg, slots, status, stream, used);
 }
 

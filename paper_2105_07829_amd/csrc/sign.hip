@@ -87,9 +87,10 @@ __global__ __launch_bounds__(kThreads) void sign_apply_kernel(Geo g, SRC src, co
 
 hipError_t sign_encode(const Geo &g, const bpc_params_t &prm, const Source &src, uint8_t *payload,
                        const Workspace &ws, hipStream_t stream) {
-  if (src.grad) {
+  {
     bool used = false;
-    hipError_t e = sign_worker_single_pass(g, prm, src, payload, ws, stream, &used);
+    hipError_t e = src.grad ? sign_worker_single_pass(g, prm, src, payload, ws, stream, &used)
+                            : sign_server_single_pass(g, prm, src, payload, ws, stream, &used);
     if (e != hipSuccess || used) return e;
   }
   double *partials = ws.at<double>(ws.lay.partials);

@@ -42,8 +42,9 @@ struct SignWorkerOp {
   static constexpr bool kMax = false;
   static constexpr int kRowsPerTile = kRows;
   static constexpr int kTableFloats = 1;
-  static constexpr bool kPrefetchEarly = true;
-  __device__ void set_table(float *) {}
+  static constexpr size_t kMaxDynLds = 0;
+  static constexpr Prefetch kPrefetch = Prefetch::kEarly;
+  struct Ctx { float sigma; };
 
   Geo g;
   ClusterGeo cg;
@@ -51,7 +52,6 @@ struct SignWorkerOp {
   float *__restrict__ res;
   uint8_t *__restrict__ payload;
   const float *__restrict__ override;
-  mutable float sigma;   // of the tile being written (set by begin2)
 
   __device__ uint32_t n_items() const { return cg.n_items; }
   __device__ bool needs_total() const { return override == nullptr; }
@@ -74,7 +74,7 @@ struct SignWorkerOp {
     if (EF) raw.e[u] = reinterpret_cast<const float4 *>(res + b)[threadIdx.x];
   }
 
-  __device__ double phase1(uint32_t, Raw &raw, Held &h) const {
+  __device__ double phase1(uint32_t, Raw &raw, Held &h, float *) const {
     double acc = 0.0;
 #pragma unroll
     for (int u = 0; u < kRows; ++u) {
@@ -116,12 +116,14 @@ struct SignWorkerOp {
     }
   }
 
-  __device__ void begin2(uint32_t item, double total) const {
-    sigma = sigma_of(part_of(item), total);
+  __device__ Ctx begin2(uint32_t item, double total, float *) const {
+    const float sigma = sigma_of(part_of(item), total);
     header(item, sigma);
+    return Ctx{sigma};
   }
-  __device__ void row2(uint32_t item, int u, Held &h) const {
+  __device__ void row2(uint32_t item, int u, Held &h, const Ctx &ctx) const {
     if (!EF) return;
+    const float sigma = ctx.sigma;
     float4 *o4 = reinterpret_cast<float4 *>(res + uniform_off(base(item) + (uint32_t)u * (kCThreads * 4)));
     float4 o;
     o.x = h.q[4 * u] - (h.q[4 * u] < 0.0f ? -sigma : sigma);
@@ -133,7 +135,7 @@ struct SignWorkerOp {
 
   // Ragged last tile of a partition: lane-strided and rolled, nothing kept in registers;
   // phase 2 reads g and e again (at most one such tile per call).
-  __device__ double ragged_phase1(uint32_t item) const {
+  __device__ double ragged_phase1(uint32_t item, float *) const {
     const uint32_t p = part_of(item), toff = tile_off(item);
     const uint32_t d = g.part_size(p), n_here = d - toff;
     const uint64_t b = base(item);
@@ -141,6 +143,7 @@ struct SignWorkerOp {
     const uint32_t n_words = (uint32_t)ru4(cdiv(d, 32));
     const uint32_t lane = threadIdx.x & 63;
     double acc = 0.0;
+#pragma unroll 4
     for (uint32_t c0 = (threadIdx.x >> 6) * 64; c0 < (uint32_t)kCTile; c0 += kCThreads) {
       uint32_t j = c0 + lane;
       uint32_t word = (toff + c0) >> 5;
@@ -156,13 +159,14 @@ struct SignWorkerOp {
     }
     return acc;
   }
-  __device__ void ragged_phase2(uint32_t item, double total) const {
+  __device__ void ragged_phase2(uint32_t item, double total, float *) const {
     const uint32_t p = part_of(item);
     const float sigma = sigma_of(p, total);
     header(item, sigma);
     if (!EF) return;
     const uint32_t n_here = g.part_size(p) - tile_off(item);
     const uint64_t b = base(item);
+#pragma unroll 4
     for (uint32_t j = threadIdx.x; j < n_here; j += kCThreads) {
       float v = load_grad(grad, b + j) + res[b + j];
       res[b + j] = v - (v < 0.0f ? -sigma : sigma);
@@ -180,15 +184,15 @@ hipError_t sign_worker_single_pass(const Geo &g, const bpc_params_t &prm, const 
   const bool f16 = src.dtype == BPC_F16;
   if (src.residual) {
     if (f16)
-      return launch_cluster(SignWorkerOp<__half, true>{g, cg, (const __half *)src.grad, src.residual, payload, prm.norm_override, 0.0f},
+      return launch_cluster(SignWorkerOp<__half, true>{g, cg, (const __half *)src.grad, src.residual, payload, prm.norm_override},
                             cg, slots, status, stream, used);
-    return launch_cluster(SignWorkerOp<float, true>{g, cg, (const float *)src.grad, src.residual, payload, prm.norm_override, 0.0f},
+    return launch_cluster(SignWorkerOp<float, true>{g, cg, (const float *)src.grad, src.residual, payload, prm.norm_override},
                           cg, slots, status, stream, used);
   }
   if (f16)
-    return launch_cluster(SignWorkerOp<__half, false>{g, cg, (const __half *)src.grad, nullptr, payload, prm.norm_override, 0.0f},
+    return launch_cluster(SignWorkerOp<__half, false>{g, cg, (const __half *)src.grad, nullptr, payload, prm.norm_override},
                           cg, slots, status, stream, used);
-  return launch_cluster(SignWorkerOp<float, false>{g, cg, (const float *)src.grad, nullptr, payload, prm.norm_override, 0.0f},
+  return launch_cluster(SignWorkerOp<float, false>{g, cg, (const float *)src.grad, nullptr, payload, prm.norm_override},
                         cg, slots, status, stream, used);
 }
 

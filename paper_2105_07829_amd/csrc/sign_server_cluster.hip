@@ -1,0 +1,289 @@
+// Scaled-sign server, single pass (Algorithm 4 server lines): Delta = mean of the n decoded
+// worker messages + e~, p = C(Delta), e~' = Delta - p.  A workgroup reads a 32768-element
+// tile of e~ and the matching bits of the n messages once, keeps Delta in registers, writes
+// the sign bits of Delta, exchanges its part of ||Delta||_1 and writes e~' = Delta -+ sigma.
+//
+// A thread owns 8 consecutive elements per row (4 rows of 8192 elements per tile), i.e. one
+// byte of every worker's sign bits per row; shifting a bit to the sign position and merging it
+// into |sigma_i| gives +-sigma_i in two instructions.
+#include "cluster_launch.hpp"
+#include "sources.hpp"
+
+namespace bpc {
+
+constexpr int kSRows = kCPerThread / 8;   // 4
+
+// Just the message pointers (the random-stream fields of WorkerMsgs are not needed here).
+struct MsgPtrs {
+  const uint8_t *ptr[kMaxWorkers];
+  int n;
+  float inv_n;
+};
+inline MsgPtrs msg_ptrs(const WorkerMsgs &m) {
+  MsgPtrs r;
+  for (int i = 0; i < kMaxWorkers; ++i) r.ptr[i] = i < m.n ? m.ptr[i] : nullptr;
+  r.n = m.n;
+  r.inv_n = m.inv_n;
+  return r;
+}
+
+// -|sigma| if bit C of `byte` is set, else +|sigma|: the bit is shifted to the sign position
+// and merged into the magnitude (`mag` has a clear sign bit).
+template <int C>
+__device__ inline float pick_sign(uint32_t byte, uint32_t mag) {
+  return __uint_as_float(((byte << (31 - C)) & 0x80000000u) | mag);
+}
+
+// NW > 0: the number of workers is known at compile time and the worker loop is unrolled, so
+// the byte loads can be scheduled ahead of their use; NW == 0: any number, rolled loop.
+template <bool EF, int NW>
+struct SignServerOp {
+  struct Raw { float4 e[2 * kSRows]; };
+  struct Held { float delta[kCPerThread]; };
+  static constexpr bool kMax = false;
+  static constexpr int kRowsPerTile = kSRows;
+  static constexpr int kTableFloats = kMaxWorkers;
+  static constexpr Prefetch kPrefetch = Prefetch::kNone;
+  static constexpr size_t kMaxDynLds = 0;
+  struct Ctx { float sigma; };
+
+  Geo g;
+  ClusterGeo cg;
+  MsgPtrs msgs;
+  float *__restrict__ res;
+  uint8_t *__restrict__ payload;
+  const float *__restrict__ override;
+
+  __device__ uint32_t n_items() const { return cg.n_items; }
+  __device__ bool needs_total() const { return override == nullptr; }
+  __device__ uint32_t part_of(uint32_t item) const { return item / cg.tiles_per_part; }
+  __device__ uint32_t tile_off(uint32_t item) const { return (item % cg.tiles_per_part) * kCTile; }
+  __device__ bool full(uint32_t item) const { return g.part_size(part_of(item)) - tile_off(item) >= (uint32_t)kCTile; }
+  __device__ uint64_t base(uint32_t item) const { return g.part_base(part_of(item)) + tile_off(item); }
+  __device__ void slots_of(uint32_t item, uint32_t *first, uint32_t *count) const {
+    uint32_t p = part_of(item);
+    *first = p * cg.tiles_per_part;
+    *count = (uint32_t)cdiv(g.part_size(p), kCTile);
+  }
+  __device__ static uint32_t lane() { return threadIdx.x & 63; }
+
+  __device__ void issue_row(uint32_t item, int u, Raw &raw) const {
+    if (!EF) return;
+    const uint64_t b = uniform_off(base(item) + (uint32_t)u * (kCThreads * 8));
+    const float4 *e4 = reinterpret_cast<const float4 *>(res + b) + threadIdx.x * 2;
+    raw.e[2 * u] = e4[0];
+    raw.e[2 * u + 1] = e4[1];
+  }
+
+  // The byte of worker i's sign bits that covers this thread's 8 elements of each row.
+  __device__ void load_bytes(uint32_t item, int i, uint32_t out[kSRows]) const {
+    const uint8_t *bits = msgs.ptr[i] + uniform_off((uint64_t)part_of(item) * g.stride + kHeaderBytes + (tile_off(item) >> 3));
+#pragma unroll
+    for (int u = 0; u < kSRows; ++u) out[u] = bits[u * kCThreads + threadIdx.x];
+  }
+
+  __device__ void add_worker(const uint32_t byte[kSRows], float sigma_i, float acc[kCPerThread]) const {
+    // decode is bit ? -sigma : sigma.  With |sigma| and, for a negative sigma, inverted bits
+    // this is bit' ? -|sigma| : |sigma| for every finite sigma.
+    const uint32_t raw_sigma = __float_as_uint(sigma_i);
+    const uint32_t mag = raw_sigma & 0x7fffffffu;
+    const uint32_t flip = (raw_sigma >> 31) ? 0xffu : 0u;
+#pragma unroll
+    for (int u = 0; u < kSRows; ++u) {
+      const uint32_t b = byte[u] ^ flip;
+      acc[8 * u + 0] = acc[8 * u + 0] + pick_sign<0>(b, mag);
+      acc[8 * u + 1] = acc[8 * u + 1] + pick_sign<1>(b, mag);
+      acc[8 * u + 2] = acc[8 * u + 2] + pick_sign<2>(b, mag);
+      acc[8 * u + 3] = acc[8 * u + 3] + pick_sign<3>(b, mag);
+      acc[8 * u + 4] = acc[8 * u + 4] + pick_sign<4>(b, mag);
+      acc[8 * u + 5] = acc[8 * u + 5] + pick_sign<5>(b, mag);
+      acc[8 * u + 6] = acc[8 * u + 6] + pick_sign<6>(b, mag);
+      acc[8 * u + 7] = acc[8 * u + 7] + pick_sign<7>(b, mag);
+    }
+  }
+
+  __device__ double phase1(uint32_t item, Raw &raw, Held &h, float *sig) const {
+    const uint32_t p = part_of(item);
+    // the tile's own e~ loads go out first and land while the worker sums are formed
+#pragma unroll
+    for (int u = 0; u < kSRows; ++u) issue_row(item, u, raw);
+    __syncthreads();
+    if ((int)threadIdx.x < msgs.n)
+      sig[threadIdx.x] = *reinterpret_cast<const float *>(msgs.ptr[threadIdx.x] + (uint64_t)p * g.stride);
+    __syncthreads();
+    float acc[kCPerThread];
+#pragma unroll
+    for (int k = 0; k < kCPerThread; ++k) acc[k] = 0.0f;
+    if (NW > 0) {
+      // groups of 8 workers: 32 byte loads in flight, consumed in order as they land
+      constexpr int kGroup = NW == 0 ? 1 : NW < 4 ? NW : 4;
+#pragma unroll
+      for (int i0 = 0; i0 < NW; i0 += kGroup) {
+        uint32_t byte[kGroup][kSRows];
+#pragma unroll
+        for (int k = 0; k < kGroup; ++k) load_bytes(item, i0 + k, byte[k]);
+#pragma unroll
+        for (int k = 0; k < kGroup; ++k) add_worker(byte[k], sig[i0 + k], acc);
+      }
+    } else {
+      for (int i = 0; i < msgs.n; ++i) {
+        uint32_t byte[kSRows];
+        load_bytes(item, i, byte);
+        add_worker(byte, sig[i], acc);
+      }
+    }
+    double sum = 0.0;
+#pragma unroll
+    for (int u = 0; u < kSRows; ++u) {
+      const float e[8] = {raw.e[2 * u].x, raw.e[2 * u].y, raw.e[2 * u].z, raw.e[2 * u].w,
+                          raw.e[2 * u + 1].x, raw.e[2 * u + 1].y, raw.e[2 * u + 1].z, raw.e[2 * u + 1].w};
+#pragma unroll
+      for (int c = 0; c < 8; ++c) {
+        float mean = acc[8 * u + c] * msgs.inv_n;
+        float d = EF ? mean + e[c] : mean;
+        h.delta[8 * u + c] = d;
+        sum += (double)fabsf(d);
+      }
+    }
+    return sum;
+  }
+
+  // Sign bits of Delta: a byte per thread and row, four neighbouring threads make a word.
+  __device__ void early(uint32_t item, Held &h) const {
+    uint32_t *bits = reinterpret_cast<uint32_t *>(payload + (uint64_t)part_of(item) * g.stride + kHeaderBytes);
+#pragma unroll
+    for (int u = 0; u < kSRows; ++u) {
+      uint32_t byte = 0;
+#pragma unroll
+      for (int c = 0; c < 8; ++c) byte |= (h.delta[8 * u + c] < 0.0f ? 1u : 0u) << c;
+      // DPP row_shl:n reads lane i+n of the 16-lane row (0 past its end)
+      byte |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)byte, 0x101, 0xf, 0xf, true) << 8;
+      byte |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)byte, 0x102, 0xf, 0xf, true) << 16;
+      uint32_t *row_words = bits + uniform_off((tile_off(item) >> 5) + u * (kCThreads * 8 / 32));
+      if ((threadIdx.x & 3) == 0) row_words[threadIdx.x >> 2] = byte;
+    }
+  }
+
+  __device__ float sigma_of(uint32_t p, double total) const {
+    return override ? override[p] : (float)(total / (double)g.part_size(p));
+  }
+  __device__ void header(uint32_t item, float s) const {
+    if (tile_off(item) == 0 && threadIdx.x == 0) {
+      uint32_t *hdr = reinterpret_cast<uint32_t *>(payload + (uint64_t)part_of(item) * g.stride);
+      hdr[0] = __float_as_uint(s);
+      hdr[1] = 0; hdr[2] = 0; hdr[3] = 0;
+    }
+  }
+  __device__ Ctx begin2(uint32_t item, double total, float *) const {
+    const float sigma = sigma_of(part_of(item), total);
+    header(item, sigma);
+    return Ctx{sigma};
+  }
+  __device__ void row2(uint32_t item, int u, Held &h, const Ctx &ctx) const {
+    if (!EF) return;
+    const float sigma = ctx.sigma;
+    const uint64_t b = uniform_off(base(item) + (uint32_t)u * (kCThreads * 8));
+    float4 *o4 = reinterpret_cast<float4 *>(res + b) + threadIdx.x * 2;
+    float r[8];
+#pragma unroll
+    for (int c = 0; c < 8; ++c) r[c] = h.delta[8 * u + c] - (h.delta[8 * u + c] < 0.0f ? -sigma : sigma);
+    o4[0] = make_float4(r[0], r[1], r[2], r[3]);
+    o4[1] = make_float4(r[4], r[5], r[6], r[7]);
+  }
+
+  // Ragged last tile of a partition (at most one per call): not kept in registers, phase 2
+  // recomputes Delta.  A thread takes kBatch elements per step so that kBatch * n independent
+  // loads are in flight; the functions are not inlined to keep them out of the register
+  // budget of the main path.
+  static constexpr int kBatch = 4;
+  __device__ void ragged_deltas(uint32_t p, uint32_t d, uint32_t j0, float out[kBatch]) const {
+    float acc[kBatch];
+    uint32_t jc[kBatch];
+#pragma unroll
+    for (int k = 0; k < kBatch; ++k) {
+      acc[k] = 0.0f;
+      const uint32_t j = j0 + k * kCThreads;
+      jc[k] = j < d ? j : d - 1;  // clamped: always a valid element
+    }
+    const int n = NW > 0 ? NW : msgs.n;
+#pragma unroll 4
+    for (int i = 0; i < n; ++i) {
+      const uint8_t *rec = msgs.ptr[i] + (uint64_t)p * g.stride;
+      const float s = *reinterpret_cast<const float *>(rec);
+      const uint32_t *words = reinterpret_cast<const uint32_t *>(rec + kHeaderBytes);
+#pragma unroll
+      for (int k = 0; k < kBatch; ++k) {
+        const uint32_t w = words[jc[k] >> 5];
+        acc[k] = acc[k] + (((w >> (jc[k] & 31)) & 1u) ? -s : s);
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < kBatch; ++k) {
+      const float mean = acc[k] * msgs.inv_n;
+      const float v = EF ? mean + res[g.part_base(p) + jc[k]] : mean;
+      out[k] = j0 + k * kCThreads < d ? v : 0.0f;
+    }
+  }
+  __device__ double ragged_phase1(uint32_t item, float *) const {
+    const uint32_t p = part_of(item), toff = tile_off(item);
+    const uint32_t d = g.part_size(p);
+    uint32_t *bits = reinterpret_cast<uint32_t *>(payload + (uint64_t)p * g.stride + kHeaderBytes);
+    const uint32_t n_words = (uint32_t)ru4(cdiv(d, 32));
+    double acc = 0.0;
+    // element j0 + k*kCThreads: lane-strided, a wave's 64 elements are two consecutive words
+    for (uint32_t c0 = 0; c0 < (uint32_t)kCTile; c0 += kBatch * kCThreads) {
+      const uint32_t j0 = toff + c0 + threadIdx.x;
+      if (((toff + c0) >> 5) >= n_words) break;
+      float v[kBatch];
+      ragged_deltas(p, d, j0, v);
+#pragma unroll
+      for (int k = 0; k < kBatch; ++k) {
+        const uint32_t word = (toff + c0 + k * kCThreads + (threadIdx.x & ~63u)) >> 5;
+        const uint64_t mask = __ballot(v[k] < 0.0f);
+        if (lane() == 0 && word < n_words) *reinterpret_cast<uint64_t *>(bits + word) = mask;
+        acc += (double)fabsf(v[k]);
+      }
+    }
+    return acc;
+  }
+  __device__ void ragged_phase2(uint32_t item, double total, float *table) const {
+    const float sigma = begin2(item, total, table).sigma;
+    if (!EF) return;
+    const uint32_t p = part_of(item);
+    const uint32_t d = g.part_size(p);
+    for (uint32_t j0 = tile_off(item) + threadIdx.x; j0 < d; j0 += kBatch * kCThreads) {
+      float v[kBatch];
+      ragged_deltas(p, d, j0, v);
+#pragma unroll
+      for (int k = 0; k < kBatch; ++k) {
+        const uint32_t j = j0 + k * kCThreads;
+        if (j < d) res[g.part_base(p) + j] = v[k] - (v[k] < 0.0f ? -sigma : sigma);
+      }
+    }
+  }
+};
+
+template <bool EF>
+static hipError_t launch_sign_server(const Geo &g, const ClusterGeo &cg, const bpc_params_t &prm, const Source &src,
+                                     uint8_t *payload, double *slots, uint32_t *status, hipStream_t stream,
+                                     bool *used) {
+  const MsgPtrs mp = msg_ptrs(src.msgs);
+  float *res = src.residual;
+  switch (mp.n) {
+    case 4: return launch_cluster(SignServerOp<EF, 4>{g, cg, mp, res, payload, prm.norm_override}, cg, slots, status, stream, used);
+    case 8: return launch_cluster(SignServerOp<EF, 8>{g, cg, mp, res, payload, prm.norm_override}, cg, slots, status, stream, used);
+    case 16: return launch_cluster(SignServerOp<EF, 16>{g, cg, mp, res, payload, prm.norm_override}, cg, slots, status, stream, used);
+    default: return launch_cluster(SignServerOp<EF, 0>{g, cg, mp, res, payload, prm.norm_override}, cg, slots, status, stream, used);
+  }
+}
+
+hipError_t sign_server_single_pass(const Geo &g, const bpc_params_t &prm, const Source &src, uint8_t *payload,
+                                   const Workspace &ws, hipStream_t stream, bool *used) {
+  ClusterGeo cg = make_cluster_geo(g);
+  double *slots = ws.at<double>(ws.lay.slots);
+  uint32_t *status = ws.at<uint32_t>(ws.lay.status);
+  if (src.residual) return launch_sign_server<true>(g, cg, prm, src, payload, slots, status, stream, used);
+  return launch_sign_server<false>(g, cg, prm, src, payload, slots, status, stream, used);
+}
+
+}  // namespace bpc
