@@ -124,9 +124,10 @@ __global__ __launch_bounds__(kThreads) void dither_apply_kernel(Geo g, SRC src, 
 
 hipError_t dither_encode(const Geo &g, const bpc_params_t &prm, const Source &src, uint8_t *payload,
                          const Workspace &ws, hipStream_t stream) {
-  if (src.grad) {
+  {
     bool used = false;
-    hipError_t e = dither_worker_single_pass(g, prm, src, payload, ws, stream, &used);
+    hipError_t e = src.grad ? dither_worker_single_pass(g, prm, src, payload, ws, stream, &used)
+                            : dither_server_single_pass(g, prm, src, payload, ws, stream, &used);
     if (e != hipSuccess || used) return e;
   }
   double *partials = ws.at<double>(ws.lay.partials);

@@ -1,0 +1,278 @@
+// Linear-dithering server, single pass (Algorithm 4 server lines): Delta = mean of the n
+// decoded worker messages + e~, p = C(Delta) with fresh stochastic levels, e~' = Delta - p.
+// A workgroup reads a 32768-element tile of e~ and the matching nibbles of the n messages
+// once, keeps Delta in registers, exchanges its part of ||Delta||_2^2 (or max |Delta|) and
+// then writes the packed levels and e~'.
+//
+// A thread owns 8 consecutive elements per row (4 rows of 8192 elements), i.e. one 32-bit word
+// of every worker's nibbles per row.  A nibble indexes a 16-entry LDS table per worker that
+// holds the decoded values +-(nu_i * level) / s.
+#include "dither_common.hpp"
+#include "sources.hpp"
+
+namespace bpc {
+
+constexpr int kDSRows = kCPerThread / 8;   // 4
+
+struct DMsgPtrs {
+  const uint8_t *ptr[kMaxWorkers];
+  int n;
+  float inv_n;
+};
+inline DMsgPtrs dmsg_ptrs(const WorkerMsgs &m) {
+  DMsgPtrs r;
+  for (int i = 0; i < kMaxWorkers; ++i) r.ptr[i] = i < m.n ? m.ptr[i] : nullptr;
+  r.n = m.n;
+  r.inv_n = m.inv_n;
+  return r;
+}
+
+// NW > 0: number of workers known at compile time (unrolled); NW == 0: rolled loop.
+template <bool EF, bool LINF, int NW>
+struct DitherServerOp {
+  struct Raw { float4 e[2 * kDSRows]; };
+  struct Held { float delta[kCPerThread]; };
+  struct Ctx { float nu, s_over_nu; int mode; const float *mag; };
+  static constexpr bool kMax = LINF;
+  static constexpr int kRowsPerTile = kDSRows;
+  static constexpr int kTableFloats = kMaxWorkers * 16 + 8;   // decode tables, then the 8 output magnitudes
+  static constexpr size_t kMaxDynLds = 0;
+  static constexpr Prefetch kPrefetch = Prefetch::kNone;
+
+  Geo g;
+  ClusterGeo cg;
+  DMsgPtrs msgs;
+  float *__restrict__ res;
+  uint8_t *__restrict__ payload;
+  const float *__restrict__ override;
+  uint32_t levels;
+  uint64_t seed, stream_id;
+
+  __device__ uint32_t n_items() const { return cg.n_items; }
+  __device__ bool needs_total() const { return override == nullptr; }
+  __device__ uint32_t part_of(uint32_t item) const { return item / cg.tiles_per_part; }
+  __device__ uint32_t tile_off(uint32_t item) const { return (item % cg.tiles_per_part) * kCTile; }
+  __device__ bool full(uint32_t item) const { return g.part_size(part_of(item)) - tile_off(item) >= (uint32_t)kCTile; }
+  __device__ uint64_t base(uint32_t item) const { return g.part_base(part_of(item)) + tile_off(item); }
+  __device__ void slots_of(uint32_t item, uint32_t *first, uint32_t *count) const {
+    uint32_t p = part_of(item);
+    *first = p * cg.tiles_per_part;
+    *count = (uint32_t)cdiv(g.part_size(p), kCTile);
+  }
+
+  __device__ void issue_row(uint32_t item, int u, Raw &raw) const {
+    if (!EF) return;
+    const uint64_t b = uniform_off(base(item) + (uint32_t)u * (kCThreads * 8));
+    const float4 *e4 = reinterpret_cast<const float4 *>(res + b) + threadIdx.x * 2;
+    raw.e[2 * u] = e4[0];
+    raw.e[2 * u + 1] = e4[1];
+  }
+
+  // Decode tables of all workers for partition p: lut[i*16 + nibble].
+  __device__ void fill_luts(uint32_t p, float *lut) const {
+    __syncthreads();
+    for (int e = threadIdx.x; e < msgs.n * 16; e += kCThreads) {
+      const int i = e >> 4, nib = e & 15;
+      const float nu = *reinterpret_cast<const float *>(msgs.ptr[i] + (uint64_t)p * g.stride);
+      const float mag = (nu * (float)(nib & 7)) / (float)levels;
+      lut[e] = (nib & 8) ? -mag : mag;
+    }
+    __syncthreads();
+  }
+
+  // The word of worker i's nibbles that covers this thread's 8 elements of each row.
+  __device__ void load_words(uint32_t item, int i, uint32_t out[kDSRows]) const {
+    const uint32_t *nibs = reinterpret_cast<const uint32_t *>(
+        msgs.ptr[i] + uniform_off((uint64_t)part_of(item) * g.stride + kHeaderBytes + (tile_off(item) >> 1)));
+#pragma unroll
+    for (int u = 0; u < kDSRows; ++u) out[u] = nibs[u * kCThreads + threadIdx.x];
+  }
+
+  __device__ static void add_worker(const uint32_t word[kDSRows], const float *lut_i, float acc[kCPerThread]) {
+#pragma unroll
+    for (int u = 0; u < kDSRows; ++u) {
+#pragma unroll
+      for (int c = 0; c < 8; ++c) acc[8 * u + c] = acc[8 * u + c] + lut_i[(word[u] >> (4 * c)) & 15u];
+    }
+  }
+
+  __device__ double phase1(uint32_t item, Raw &raw, Held &h, float *table) const {
+    const uint32_t p = part_of(item);
+#pragma unroll
+    for (int u = 0; u < kDSRows; ++u) issue_row(item, u, raw);
+    fill_luts(p, table);
+    float acc[kCPerThread];
+#pragma unroll
+    for (int k = 0; k < kCPerThread; ++k) acc[k] = 0.0f;
+    if (NW > 0) {
+      constexpr int kGroup = NW == 0 ? 1 : NW < 4 ? NW : 4;
+#pragma unroll
+      for (int i0 = 0; i0 < NW; i0 += kGroup) {
+        uint32_t word[kGroup][kDSRows];
+#pragma unroll
+        for (int k = 0; k < kGroup; ++k) load_words(item, i0 + k, word[k]);
+#pragma unroll
+        for (int k = 0; k < kGroup; ++k) add_worker(word[k], table + (i0 + k) * 16, acc);
+      }
+    } else {
+      for (int i = 0; i < msgs.n; ++i) {
+        uint32_t word[kDSRows];
+        load_words(item, i, word);
+        add_worker(word, table + i * 16, acc);
+      }
+    }
+    double sum = 0.0;
+    float mx = 0.0f;
+#pragma unroll
+    for (int u = 0; u < kDSRows; ++u) {
+      const float e[8] = {raw.e[2 * u].x, raw.e[2 * u].y, raw.e[2 * u].z, raw.e[2 * u].w,
+                          raw.e[2 * u + 1].x, raw.e[2 * u + 1].y, raw.e[2 * u + 1].z, raw.e[2 * u + 1].w};
+#pragma unroll
+      for (int c = 0; c < 8; ++c) {
+        float mean = acc[8 * u + c] * msgs.inv_n;
+        float d = EF ? mean + e[c] : mean;
+        h.delta[8 * u + c] = d;
+        if (LINF) mx = fmaxf(mx, fabsf(d));
+        else sum = fma((double)d, (double)d, sum);
+      }
+    }
+    return LINF ? (double)mx : sum;
+  }
+  __device__ void early(uint32_t, Held &) const {}
+
+  __device__ float nu_of(uint32_t p, double total) const {
+    if (override) return override[p];
+    return LINF ? (float)total : (float)sqrt(total);
+  }
+  __device__ Ctx begin2(uint32_t item, double total, float *table) const {
+    const uint32_t p = part_of(item);
+    const float nu = nu_of(p, total);
+    if (tile_off(item) == 0 && threadIdx.x == 0) {
+      uint32_t *hdr = reinterpret_cast<uint32_t *>(payload + (uint64_t)p * g.stride);
+      hdr[0] = __float_as_uint(nu);
+      hdr[1] = 0; hdr[2] = 0; hdr[3] = 0;
+    }
+    float *mag = table + kMaxWorkers * 16;
+    dither_fill_table(nu, levels, mag);
+    const float s_over_nu = (float)levels / nu;
+    return Ctx{nu, s_over_nu, dither_mode(nu, s_over_nu), mag};
+  }
+
+  template <int MODE>
+  __device__ void row2_body(uint32_t item, int u, Held &h, const Ctx &ctx) const {
+    const uint32_t p = part_of(item);
+    const Philox rng(seed, stream_id, p);
+    const uint32_t j0 = tile_off(item) + (u * kCThreads + threadIdx.x) * 8;
+    float r[8];
+    const uint32_t word = dither_row<MODE>(&h.delta[8 * u], ctx.nu, ctx.s_over_nu, levels, rng, j0, ctx.mag, r);
+    uint32_t *nibs = reinterpret_cast<uint32_t *>(payload + (uint64_t)p * g.stride + kHeaderBytes);
+    (nibs + uniform_off((tile_off(item) + u * (kCThreads * 8)) >> 3))[threadIdx.x] = word;
+    if (EF) {
+      float4 *o4 = reinterpret_cast<float4 *>(res + uniform_off(base(item) + (uint32_t)u * (kCThreads * 8))) + threadIdx.x * 2;
+      o4[0] = make_float4(r[0], r[1], r[2], r[3]);
+      o4[1] = make_float4(r[4], r[5], r[6], r[7]);
+    }
+  }
+  __device__ void row2(uint32_t item, int u, Held &h, const Ctx &ctx) const {
+    if (ctx.mode == 1) row2_body<1>(item, u, h, ctx);
+    else if (ctx.mode == 2) row2_body<2>(item, u, h, ctx);
+    else row2_body<0>(item, u, h, ctx);
+  }
+
+  // Ragged last tile of a partition (at most one per call): nothing kept in registers, phase 2
+  // recomputes Delta.  One word (8 elements) of every worker per thread and step.
+  __device__ void ragged_deltas(uint32_t p, uint32_t d, uint32_t w, const float *lut, float out[8]) const {
+    float acc[8];
+#pragma unroll
+    for (int c = 0; c < 8; ++c) acc[c] = 0.0f;
+    const int n = NW > 0 ? NW : msgs.n;
+    for (int i = 0; i < n; ++i) {
+      const uint32_t word = reinterpret_cast<const uint32_t *>(msgs.ptr[i] + (uint64_t)p * g.stride + kHeaderBytes)[w];
+#pragma unroll
+      for (int c = 0; c < 8; ++c) acc[c] = acc[c] + lut[i * 16 + ((word >> (4 * c)) & 15u)];
+    }
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+      const uint32_t j = w * 8 + c;
+      const float mean = acc[c] * msgs.inv_n;
+      out[c] = j < d ? (EF ? mean + res[g.part_base(p) + j] : mean) : 0.0f;
+    }
+  }
+  __device__ double ragged_phase1(uint32_t item, float *table) const {
+    const uint32_t p = part_of(item), toff = tile_off(item);
+    const uint32_t d = g.part_size(p);
+    fill_luts(p, table);
+    const uint32_t n_words = (uint32_t)cdiv(d, 8);
+    double sum = 0.0;
+    float mx = 0.0f;
+    for (uint32_t w = (toff >> 3) + threadIdx.x; w < n_words; w += kCThreads) {
+      float v[8];
+      ragged_deltas(p, d, w, table, v);
+#pragma unroll
+      for (int c = 0; c < 8; ++c) {
+        if (LINF) mx = fmaxf(mx, fabsf(v[c]));
+        else sum = fma((double)v[c], (double)v[c], sum);
+      }
+    }
+    return LINF ? (double)mx : sum;
+  }
+  __device__ void ragged_phase2(uint32_t item, double total, float *table) const {
+    const uint32_t p = part_of(item), toff = tile_off(item);
+    const uint32_t d = g.part_size(p);
+    const Ctx ctx = begin2(item, total, table);
+    const Philox rng(seed, stream_id, p);
+    uint32_t *nibs = reinterpret_cast<uint32_t *>(payload + (uint64_t)p * g.stride + kHeaderBytes);
+    const uint32_t n_data = (uint32_t)cdiv(d, 8), n_words = (uint32_t)ru4(n_data);
+    for (uint32_t w = (toff >> 3) + threadIdx.x; w < n_words; w += kCThreads) {
+      uint32_t word = 0;
+      if (w < n_data) {
+        float v[8], r[8];
+        ragged_deltas(p, d, w, table, v);
+        if (ctx.mode == 1) word = dither_row<1>(v, ctx.nu, ctx.s_over_nu, levels, rng, w * 8, ctx.mag, r);
+        else if (ctx.mode == 2) word = dither_row<2>(v, ctx.nu, ctx.s_over_nu, levels, rng, w * 8, ctx.mag, r);
+        else word = dither_row<0>(v, ctx.nu, ctx.s_over_nu, levels, rng, w * 8, ctx.mag, r);
+        // elements past d are zero and quantise to nibble 0
+        if (EF) {
+#pragma unroll
+          for (int c = 0; c < 8; ++c)
+            if (w * 8 + c < d) res[g.part_base(p) + w * 8 + c] = r[c];
+        }
+      }
+      nibs[w] = word;
+    }
+  }
+};
+
+template <bool EF, bool LINF>
+static hipError_t launch_dither_server(const Geo &g, const ClusterGeo &cg, const bpc_params_t &prm,
+                                       const Source &src, uint8_t *payload, double *slots, uint32_t *status,
+                                       hipStream_t stream, bool *used) {
+  const DMsgPtrs mp = dmsg_ptrs(src.msgs);
+  float *res = src.residual;
+#define BPC_DS(NW)                                                                                          \
+  return launch_cluster(DitherServerOp<EF, LINF, NW>{g, cg, mp, res, payload, prm.norm_override, prm.levels, \
+                                                     prm.seed, prm.stream_id},                              \
+                        cg, slots, status, stream, used)
+  switch (mp.n) {
+    case 4: BPC_DS(4);
+    case 8: BPC_DS(8);
+    case 16: BPC_DS(16);
+    default: BPC_DS(0);
+  }
+#undef BPC_DS
+}
+
+hipError_t dither_server_single_pass(const Geo &g, const bpc_params_t &prm, const Source &src, uint8_t *payload,
+                                     const Workspace &ws, hipStream_t stream, bool *used) {
+  ClusterGeo cg = make_cluster_geo(g);
+  double *slots = ws.at<double>(ws.lay.slots);
+  uint32_t *status = ws.at<uint32_t>(ws.lay.status);
+  const bool linf = prm.norm == BPC_NORM_LINF;
+  if (src.residual)
+    return linf ? launch_dither_server<true, true>(g, cg, prm, src, payload, slots, status, stream, used)
+                : launch_dither_server<true, false>(g, cg, prm, src, payload, slots, status, stream, used);
+  return linf ? launch_dither_server<false, true>(g, cg, prm, src, payload, slots, status, stream, used)
+              : launch_dither_server<false, false>(g, cg, prm, src, payload, slots, status, stream, used);
+}
+
+}  // namespace bpc

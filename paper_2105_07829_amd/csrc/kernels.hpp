@@ -55,6 +55,8 @@ hipError_t sign_worker_single_pass(const Geo &g, const bpc_params_t &prm, const 
 
 hipError_t sign_server_single_pass(const Geo &g, const bpc_params_t &prm, const Source &src, uint8_t *payload,
                                    const Workspace &ws, hipStream_t stream, bool *used);
+hipError_t dither_server_single_pass(const Geo &g, const bpc_params_t &prm, const Source &src, uint8_t *payload,
+                                     const Workspace &ws, hipStream_t stream, bool *used);
 hipError_t dither_worker_single_pass(const Geo &g, const bpc_params_t &prm, const Source &src, uint8_t *payload,
                                      const Workspace &ws, hipStream_t stream, bool *used);
 
