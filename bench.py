@@ -32,6 +32,9 @@ def parse():
     ap.add_argument("--no-others", action="store_true", help="skip the secondary workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--cpu-partitions", type=int, default=8, help="partitions in the CPU sample")
+    ap.add_argument("--cpu-steps", type=int, default=6, help="pipeline steps the CPU sample runs")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device copy a few times (reference for hardware counters)")
     return ap.parse_args()
 
 
@@ -149,9 +152,10 @@ def run_workload(name, w, steps, warmup, torch, bpc, synth):
     return out
 
 
-def cpu_baseline(name, w, n_parts, synth):
+def cpu_baseline(name, w, n_parts, n_steps, synth):
     """The CPU oracle as it stands, on `n_parts` full partitions of the same workload (all n
-    workers, server, update), partitions spread over the host cores with a thread pool."""
+    workers, server, update) for `n_steps` steps, partitions spread over the host cores with a
+    thread pool."""
     import numpy as np
     from concurrent.futures import ThreadPoolExecutor
 
@@ -171,8 +175,11 @@ def cpu_baseline(name, w, n_parts, synth):
     x, m, v = synth.host_params(D), np.zeros(D, np.float32), np.zeros(D, np.float32)
     strd = None
 
+    step = [1]
+
     def prm(role, worker, part):
-        return oracle.make_params(kind, pe, stream_id=(1 << 32) | (role << 16) | worker, first_partition=part, **kw)
+        return oracle.make_params(kind, pe, stream_id=(step[0] << 32) | (role << 16) | worker,
+                                  first_partition=part, **kw)
 
     pays = [[None] * n_parts for _ in range(n)]
     outs = [None] * n_parts
@@ -186,18 +193,20 @@ def cpu_baseline(name, w, n_parts, synth):
         sl = slice(p * pe, (p + 1) * pe)
         ins = [prm(0, i, p) for i in range(n)]
         outs[p] = oracle.server_aggregate(ins, [pays[i][p] for i in range(n)], prm(1, 0, p), sres[sl], pe)
-        opt = oracle.make_opt(oracle.OPT_ADAM, 1e-3, 0.9, 0.999, 1e-8, 0.01, 1)
+        opt = oracle.make_opt(oracle.OPT_ADAM, 1e-3, 0.9, 0.999, 1e-8, 0.01, step[0])
         oracle.adaptive_update(prm(1, 0, p), outs[p], pe, x[sl], m[sl], v[sl], opt)
 
     t0 = time.perf_counter()
     with ThreadPoolExecutor(cores) as ex:
-        list(ex.map(work_w, [(i, p) for i in range(n) for p in range(n_parts)]))
-        list(ex.map(work_su, range(n_parts)))
+        for t in range(1, n_steps + 1):
+            step[0] = t
+            list(ex.map(work_w, [(i, p) for i in range(n) for p in range(n_parts)]))
+            list(ex.map(work_su, range(n_parts)))
     dt = time.perf_counter() - t0
     G = 4 if w["dtype"] == "f32" else 2
-    return {"value": round(n * D * G / dt / 1e9, 4), "unit": "GB/s", "cores": cores, "kind": "oracle",
-            "sample": f"{n_parts} full partitions ({D} elements) of {name}: {n} workers compress + server "
-                      f"aggregate + update, {dt:.1f} s wall, one step"}
+    return {"value": round(n_steps * n * D * G / dt / 1e9, 4), "unit": "GB/s", "cores": cores, "kind": "oracle",
+            "sample": f"{n_steps} steps on {n_parts} full partitions ({D} elements) of {name}: {n} workers "
+                      f"compress + server aggregate + update per step, {dt:.1f} s wall on {cores} threads"}
 
 
 def main():
@@ -244,8 +253,15 @@ def main():
         "pipeline_GBps_one_worker": head["pipeline_GBps_one_worker"],
         "other_workloads": others,
     }
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        result["copy_calibration"] = {"bytes_read": src.numel() * 4, "bytes_written": src.numel() * 4, "launches": 3}
     if not args.no_cpu:
-        result["cpu_baseline"] = cpu_baseline(args.workload, w, args.cpu_partitions, synth)
+        result["cpu_baseline"] = cpu_baseline(args.workload, w, args.cpu_partitions, args.cpu_steps, synth)
     print(json.dumps(result))
 
 
