@@ -209,6 +209,20 @@ def cpu_baseline(name, w, n_parts, n_steps, synth):
                       f"compress + server aggregate + update per step, {dt:.1f} s wall on {cores} threads"}
 
 
+def recorded_traffic(workload, stage):
+    """HBM bytes per launch of a stage as measured with rocprofv3 counters (profiles/), or None."""
+    path = os.path.join(ROOT, "profiles", f"bench_{workload}_dither.txt" if workload == "bert_large"
+                        else f"bench_{workload}.txt")
+    try:
+        for line in open(path):
+            f = line.split()
+            if len(f) >= 9 and f[0] == "TRAFFIC" and f[1] == workload and f[2] == stage:
+                return float(f[f.index("total_bytes") + 1])
+    except OSError:
+        pass
+    return None
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -246,7 +260,7 @@ def main():
                    "compressor": w["kind"], "n_workers": w["n_workers"], "partition_bytes": synth.PART_BYTES,
                    "error_feedback": "two-way", "update": "adam-style"},
         "roofline": {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": recorded_traffic(args.workload, dom),
                      "kernel": f"{call} ({w['kind']})", "algorithmic_bytes_per_element": alg,
                      "elements_per_launch": w["D"]},
         "stages": head["stages"],
