@@ -54,10 +54,10 @@ struct DitherWorkerOp {
 
   __device__ uint32_t n_items() const { return cg.n_items; }
   __device__ bool needs_total() const { return override == nullptr; }
-  __device__ uint32_t part_of(uint32_t item) const { return item / cg.tiles_per_part; }
-  __device__ uint32_t tile_off(uint32_t item) const { return (item % cg.tiles_per_part) * kCTile; }
+  __device__ uint32_t part_of(uint32_t item) const { return __builtin_amdgcn_readfirstlane(item / cg.tiles_per_part); }
+  __device__ uint32_t tile_off(uint32_t item) const { return __builtin_amdgcn_readfirstlane((item % cg.tiles_per_part) * kCTile); }
   __device__ bool full(uint32_t item) const { return g.part_size(part_of(item)) - tile_off(item) >= (uint32_t)kCTile; }
-  __device__ uint64_t base(uint32_t item) const { return g.part_base(part_of(item)) + tile_off(item); }
+  __device__ uint64_t base(uint32_t item) const { return uniform_off(g.part_base(part_of(item)) + tile_off(item)); }
   __device__ void slots_of(uint32_t item, uint32_t *first, uint32_t *count) const {
     uint32_t p = part_of(item);
     *first = p * cg.tiles_per_part;
