@@ -38,7 +38,6 @@ hipError_t cluster_launch_begin(hipStream_t stream) {
 }
 
 hipError_t cluster_launch_end(hipStream_t stream) {
-  if (getenv("BPC_EXP_NO_EVENT")) return hipSuccess;
   int dev = 0;
   hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return e;

@@ -30,12 +30,35 @@ struct ClusterGeo {
   uint32_t n_items;         // tiles over all partitions
 };
 
+// `g` must describe full partitions only, each a whole number of tiles.
 inline ClusterGeo make_cluster_geo(const Geo &g) {
   ClusterGeo c;
-  c.tiles_per_part = (uint32_t)cdiv(g.part_elems, kCTile);
-  uint64_t last = g.D - (uint64_t)(g.P - 1) * g.part_elems;
-  c.n_items = (g.P - 1) * c.tiles_per_part + (uint32_t)cdiv(last, kCTile);
+  c.tiles_per_part = (uint32_t)(g.part_elems / kCTile);
+  c.n_items = g.P * c.tiles_per_part;
   return c;
+}
+
+// Splits a gradient into the part the single-pass kernels take (whole partitions that are a
+// whole number of tiles) and the ragged last partition, if any.
+struct SplitGeo {
+  bool single_pass;   // false: the partition size is not a multiple of the tile
+  Geo head;           // the full partitions (head.D may be 0)
+  Geo tail;           // the last, shorter partition as a one-partition gradient (tail.D may be 0)
+};
+inline SplitGeo split_geo(const Geo &g) {
+  SplitGeo s;
+  s.single_pass = g.part_elems % kCTile == 0;
+  const uint32_t p_full = (uint32_t)(g.D / g.part_elems);
+  s.head = g;
+  s.head.D = (uint64_t)p_full * g.part_elems;
+  s.head.P = p_full;
+  s.head.n_tiles = p_full * g.tiles_per_part;
+  s.tail = g;
+  s.tail.D = g.D - s.head.D;
+  s.tail.P = s.tail.D ? 1 : 0;
+  s.tail.n_tiles = (uint32_t)cdiv(s.tail.D, kTile);
+  s.tail.part0 = g.part0 + p_full;
+  return s;
 }
 
 // Host side: cluster kernels are launched as ordinary kernels whose grid never exceeds what
@@ -110,15 +133,14 @@ __device__ inline double cluster_block_reduce(double x, double *red /*kCThreads/
   return t;
 }
 
-// Persistent, software-pipelined driver.  `Op` supplies:
-//   struct Raw, struct Held;                     raw loads of a tile / what is kept for phase 2
+// Persistent, software-pipelined driver over the tiles of the full partitions (a ragged last
+// partition is left to the multi-pass kernels).  `Op` supplies:
+//   struct Raw, struct Held, struct Ctx;         raw loads of a tile / what is kept for phase 2
 //   uint32_t n_items() const;
-//   bool   full(item) const;                     tile completely inside its partition
-//   void   issue_row(item, row, Raw&) const;     start the loads of one row of a full tile
-//   double phase1(item, Raw&, Held&) const;      consume the loads, return the tile's partial
+//   void   issue_row(item, row, Raw&) const;     start the loads of one row of a tile
+//   double phase1(item, Raw&, Held&, table) const;   consume the loads, return the tile's partial
 //   void   early(item, Held&) const;             stores that do not need the norm
 //   Ctx    begin2(item, total, table) / row2(item, row, Held&, Ctx) const;   outputs of one row
-//   double ragged_phase1(item) / ragged_phase2(item, total);     rolled path, nothing held
 //   void   slots_of(item, first, count)          the partition's slots
 //   static constexpr int kRowsPerTile; static constexpr bool kMax (maximum instead of sum)
 //   static constexpr Prefetch kPrefetch; static constexpr int kTableFloats (LDS scratch, `table`)
@@ -140,22 +162,20 @@ __device__ inline void cluster_run(const Op &op, float *table, double *slots, ui
   __shared__ double total_sh;
   const uint32_t n_items = op.n_items();
   // item numbers are the same for every lane: keeping them in scalar registers makes all
-  // tile addresses scalar base + per-thread offset
+  // tile addresses scalar
   uint32_t item = __builtin_amdgcn_readfirstlane(blockIdx.x);
   if (item >= n_items) return;
   typename Op::Raw raw;
-  bool full = op.full(item);
-  if (full && Op::kPrefetch != Prefetch::kNone) {
+  if (Op::kPrefetch != Prefetch::kNone) {
 #pragma unroll
     for (int u = 0; u < Op::kRowsPerTile; ++u) op.issue_row(item, u, raw);
   }
   for (;;) {
     typename Op::Held held;
-    double part = full ? op.phase1(item, raw, held, table) : op.ragged_phase1(item, table);
+    double part = op.phase1(item, raw, held, table);
     const uint32_t next = __builtin_amdgcn_readfirstlane(item + gridDim.x);
     const bool have_next = next < n_items;
-    const bool next_full = have_next && op.full(next);
-    if (Op::kPrefetch == Prefetch::kEarly && next_full) {
+    if (Op::kPrefetch == Prefetch::kEarly && have_next) {
 #pragma unroll
       for (int u = 0; u < Op::kRowsPerTile; ++u) op.issue_row(next, u, raw);
     }
@@ -169,26 +189,17 @@ __device__ inline void cluster_run(const Op &op, float *table, double *slots, ui
         if (threadIdx.x == 0) total_sh = total;
       }
     }
-    if (full) op.early(item, held);
+    op.early(item, held);
     __syncthreads();
     const double total = total_sh;
-    if (full) {
-      const typename Op::Ctx ctx = op.begin2(item, total, table);
+    const typename Op::Ctx ctx = op.begin2(item, total, table);
 #pragma unroll
-      for (int u = 0; u < Op::kRowsPerTile; ++u) {
-        op.row2(item, u, held, ctx);
-        if (Op::kPrefetch == Prefetch::kInterleaved && next_full) op.issue_row(next, u, raw);
-      }
-    } else {
-      op.ragged_phase2(item, total, table);
-      if (Op::kPrefetch == Prefetch::kInterleaved && next_full) {
-#pragma unroll
-        for (int u = 0; u < Op::kRowsPerTile; ++u) op.issue_row(next, u, raw);
-      }
+    for (int u = 0; u < Op::kRowsPerTile; ++u) {
+      op.row2(item, u, held, ctx);
+      if (Op::kPrefetch == Prefetch::kInterleaved && have_next) op.issue_row(next, u, raw);
     }
     if (!have_next) break;
     item = next;
-    full = next_full;
     __syncthreads();
   }
 }

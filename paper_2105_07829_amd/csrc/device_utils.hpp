@@ -47,6 +47,44 @@ __device__ inline uint64_t uniform_off(uint64_t v) {
   return ((uint64_t)hi << 32) | lo;
 }
 
+// A window of memory addressed through a buffer descriptor: accesses are "descriptor (scalar
+// registers) + 32-bit lane offset + scalar offset", so a tile's rows need no per-row address
+// registers.  `base` must be the same in every lane; `bytes` bounds the window (reads past it
+// return 0 and writes past it are dropped by the hardware, which the callers never rely on).
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+struct TileBuf {
+  __amdgpu_buffer_rsrc_t r;
+  __device__ TileBuf(const void *base, uint32_t bytes)
+      : r(__builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000)) {}
+  __device__ u32x4 load16(uint32_t lane_off, uint32_t row_off) const {
+    return __builtin_amdgcn_raw_buffer_load_b128(r, (int)lane_off, (int)row_off, 0);
+  }
+  __device__ u32x2 load8(uint32_t lane_off, uint32_t row_off) const {
+    return __builtin_amdgcn_raw_buffer_load_b64(r, (int)lane_off, (int)row_off, 0);
+  }
+  __device__ uint32_t load4(uint32_t lane_off, uint32_t row_off) const {
+    return __builtin_amdgcn_raw_buffer_load_b32(r, (int)lane_off, (int)row_off, 0);
+  }
+  __device__ uint32_t load1(uint32_t lane_off, uint32_t row_off) const {
+    return (uint32_t)__builtin_amdgcn_raw_buffer_load_b8(r, (int)lane_off, (int)row_off, 0);
+  }
+  // 16-byte stores take no scalar offset: with one, the hardware was seen to pick up a data
+  // register that the next instruction overwrites (the compiler only spaces the two apart
+  // when the offset field is a constant).  Callers put the row into the descriptor's base.
+  __device__ void store16(u32x4 v, uint32_t lane_off) const {
+    __builtin_amdgcn_raw_buffer_store_b128(v, r, (int)lane_off, 0, 0);
+  }
+  __device__ void store4(uint32_t v, uint32_t lane_off, uint32_t row_off) const {
+    __builtin_amdgcn_raw_buffer_store_b32(v, r, (int)lane_off, (int)row_off, 0);
+  }
+};
+__device__ inline u32x4 as_u32x4(float a, float b, float c, float d) {
+  u32x4 v;
+  v.x = __float_as_uint(a); v.y = __float_as_uint(b); v.z = __float_as_uint(c); v.w = __float_as_uint(d);
+  return v;
+}
+
 __device__ inline float load_grad(const float *g, uint64_t i) { return g[i]; }
 __device__ inline float load_grad(const __half *g, uint64_t i) { return __half2float(g[i]); }
 

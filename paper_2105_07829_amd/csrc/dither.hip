@@ -5,6 +5,7 @@
 //   reduce : per-tile partial of sum v_j^2 (f64) or max |v_j|
 //   finish : nu per partition -> record header
 //   apply  : levels from Philox draws, packed nibbles, residual_j = v_j - decode_j
+#include "cluster.hpp"
 #include "sources.hpp"
 
 namespace bpc {
@@ -98,7 +99,7 @@ __global__ __launch_bounds__(kThreads) void dither_apply_kernel(Geo g, SRC src, 
   uint32_t *nibs = reinterpret_cast<uint32_t *>(rec + kHeaderBytes);
   const uint32_t n_words = (uint32_t)ru4(cdiv(d, 8));
   const uint64_t base = g.part_base(p);
-  const Philox rng(seed, stream_id, p);
+  const Philox rng(seed, stream_id, p + g.part0);
 #pragma unroll
   for (int row = 0; row < kRows; ++row) {
     const uint32_t j0 = tile * kTile + row * kRowElems + threadIdx.x * kPerThread;
@@ -122,13 +123,24 @@ __global__ __launch_bounds__(kThreads) void dither_apply_kernel(Geo g, SRC src, 
   }
 }
 
-hipError_t dither_encode(const Geo &g, const bpc_params_t &prm, const Source &src, uint8_t *payload,
+hipError_t dither_encode(const Geo &g_in, const bpc_params_t &prm_in, const Source &src_in, uint8_t *payload,
                          const Workspace &ws, hipStream_t stream) {
-  {
+  // Full partitions that are a whole number of register tiles go to the single-pass kernel,
+  // a ragged last partition (or everything, if the shape does not fit) to the passes below.
+  const SplitGeo sp = split_geo(g_in);
+  Geo g = g_in;
+  Source src = src_in;
+  bpc_params_t prm = prm_in;
+  if (sp.single_pass && sp.head.P > 0) {
     bool used = false;
-    hipError_t e = src.grad ? dither_worker_single_pass(g, prm, src, payload, ws, stream, &used)
-                            : dither_server_single_pass(g, prm, src, payload, ws, stream, &used);
-    if (e != hipSuccess || used) return e;
+    hipError_t e = src.grad ? dither_worker_single_pass(sp.head, prm, src, payload, ws, stream, &used)
+                            : dither_server_single_pass(sp.head, prm, src, payload, ws, stream, &used);
+    if (e != hipSuccess) return e;
+    if (used) {
+      if (sp.tail.D == 0) return hipSuccess;
+      advance_to_tail(sp.head.P, g_in, &src, &payload, &prm);
+      g = sp.tail;
+    }
   }
   double *partials = ws.at<double>(ws.lay.partials);
   const int linf = prm.norm == BPC_NORM_LINF;

@@ -8,15 +8,16 @@ namespace bpc {
 
 constexpr int kDRows = kCPerThread / 8;  // 4 rows of 8192 elements; a thread owns 8 consecutive per row
 
+struct F32x8 { u32x4 a, b; };
 template <class G> struct Vec8Of;
-template <> struct Vec8Of<float> { struct type { float4 a, b; }; };
-template <> struct Vec8Of<__half> { using type = uint4; };
+template <> struct Vec8Of<float> { using type = F32x8; };
+template <> struct Vec8Of<__half> { using type = u32x4; };
 
-__device__ inline void widen8(const Vec8Of<float>::type &g, float out[8]) {
-  out[0] = g.a.x; out[1] = g.a.y; out[2] = g.a.z; out[3] = g.a.w;
-  out[4] = g.b.x; out[5] = g.b.y; out[6] = g.b.z; out[7] = g.b.w;
+__device__ inline void widen8(const F32x8 &g, float out[8]) {
+  out[0] = __uint_as_float(g.a.x); out[1] = __uint_as_float(g.a.y); out[2] = __uint_as_float(g.a.z); out[3] = __uint_as_float(g.a.w);
+  out[4] = __uint_as_float(g.b.x); out[5] = __uint_as_float(g.b.y); out[6] = __uint_as_float(g.b.z); out[7] = __uint_as_float(g.b.w);
 }
-__device__ inline void widen8(const uint4 &g, float out[8]) {
+__device__ inline void widen8(const u32x4 &g, float out[8]) {
   const uint32_t w[4] = {g.x, g.y, g.z, g.w};
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
@@ -25,16 +26,18 @@ __device__ inline void widen8(const uint4 &g, float out[8]) {
     out[2 * i + 1] = f.y;
   }
 }
-__device__ inline Vec8Of<float>::type load8(const float *p) {
-  const float4 *q = reinterpret_cast<const float4 *>(p);
-  return {q[0], q[1]};
+// 8 consecutive gradient elements of thread t in row u of a tile window
+__device__ inline F32x8 tile_load8(const TileBuf &b, int u, const float *) {
+  return {b.load16(threadIdx.x * 32, u * (kCThreads * 32)), b.load16(threadIdx.x * 32 + 16, u * (kCThreads * 32))};
 }
-__device__ inline uint4 load8(const __half *p) { return *reinterpret_cast<const uint4 *>(p); }
+__device__ inline u32x4 tile_load8(const TileBuf &b, int u, const __half *) {
+  return b.load16(threadIdx.x * 16, u * (kCThreads * 16));
+}
 
 template <class G, bool EF, bool LINF>
 struct DitherWorkerOp {
   using GV = typename Vec8Of<G>::type;
-  struct Raw { GV g[kDRows]; float4 e[2 * kDRows]; };
+  struct Raw { GV g[kDRows]; F32x8 e[kDRows]; };
   struct Held { float q[kCPerThread]; };
   static constexpr bool kMax = LINF;
   static constexpr int kRowsPerTile = kDRows;
@@ -56,7 +59,6 @@ struct DitherWorkerOp {
   __device__ bool needs_total() const { return override == nullptr; }
   __device__ uint32_t part_of(uint32_t item) const { return __builtin_amdgcn_readfirstlane(item / cg.tiles_per_part); }
   __device__ uint32_t tile_off(uint32_t item) const { return __builtin_amdgcn_readfirstlane((item % cg.tiles_per_part) * kCTile); }
-  __device__ bool full(uint32_t item) const { return g.part_size(part_of(item)) - tile_off(item) >= (uint32_t)kCTile; }
   __device__ uint64_t base(uint32_t item) const { return uniform_off(g.part_base(part_of(item)) + tile_off(item)); }
   __device__ void slots_of(uint32_t item, uint32_t *first, uint32_t *count) const {
     uint32_t p = part_of(item);
@@ -65,13 +67,9 @@ struct DitherWorkerOp {
   }
 
   __device__ void issue_row(uint32_t item, int u, Raw &raw) const {
-    const uint64_t b = uniform_off(base(item) + (uint32_t)u * (kCThreads * 8));
-    raw.g[u] = load8(grad + b + threadIdx.x * 8);
-    if (EF) {
-      const float4 *e4 = reinterpret_cast<const float4 *>(res + b) + threadIdx.x * 2;
-      raw.e[2 * u] = e4[0];
-      raw.e[2 * u + 1] = e4[1];
-    }
+    const uint64_t b = base(item);
+    raw.g[u] = tile_load8(TileBuf(grad + b, kCTile * sizeof(G)), u, grad);
+    if (EF) raw.e[u] = tile_load8(TileBuf(res + b, kCTile * 4), u, (const float *)nullptr);
   }
 
   __device__ double phase1(uint32_t, Raw &raw, Held &h, float *) const {
@@ -81,8 +79,8 @@ struct DitherWorkerOp {
     for (int u = 0; u < kDRows; ++u) {
       float w[8];
       widen8(raw.g[u], w);
-      const float e[8] = {raw.e[2 * u].x, raw.e[2 * u].y, raw.e[2 * u].z, raw.e[2 * u].w,
-                          raw.e[2 * u + 1].x, raw.e[2 * u + 1].y, raw.e[2 * u + 1].z, raw.e[2 * u + 1].w};
+      float e[8];
+      widen8(raw.e[u], e);
 #pragma unroll
       for (int c = 0; c < 8; ++c) {
         float q = EF ? w[c] + e[c] : w[c];
@@ -173,66 +171,14 @@ struct DitherWorkerOp {
       for (int c = 0; c < 8; ++c)
         word |= quantise<MODE == 2>(h.q[8 * u + c], nu, s_over_nu, rnd[c], mag, &r[c]) << (4 * c);
     }
-    (nibs + uniform_off((tile_off(item) + u * (kCThreads * 8)) >> 3))[threadIdx.x] = word;
+    TileBuf(nibs + (tile_off(item) >> 3), kCTile / 2).store4(word, threadIdx.x * 4, u * (kCThreads * 4));
     if (EF) {
-      float4 *o4 = reinterpret_cast<float4 *>(res + uniform_off(b + (uint32_t)u * (kCThreads * 8))) + threadIdx.x * 2;
-      o4[0] = make_float4(r[0], r[1], r[2], r[3]);
-      o4[1] = make_float4(r[4], r[5], r[6], r[7]);
+      const TileBuf ob(res + b + u * (kCThreads * 8), kCThreads * 32);
+      ob.store16(as_u32x4(r[0], r[1], r[2], r[3]), threadIdx.x * 32);
+      ob.store16(as_u32x4(r[4], r[5], r[6], r[7]), threadIdx.x * 32 + 16);
     }
   }
 
-  // Ragged last tile of a partition: rolled loops, nothing kept in registers, phase 2 reads
-  // g and e again (at most one such tile per call).
-  __device__ float ragged_q(uint64_t i) const {
-    float v = load_grad(grad, i);
-    return EF ? v + res[i] : v;
-  }
-  __device__ double ragged_phase1(uint32_t item, float *) const {
-    const uint32_t n_here = g.part_size(part_of(item)) - tile_off(item);
-    const uint64_t b = base(item);
-    double acc = 0.0;
-    float mx = 0.0f;
-#pragma unroll 4
-    for (uint32_t j = threadIdx.x; j < n_here; j += kCThreads) {
-      float q = ragged_q(b + j);
-      if (LINF) mx = fmaxf(mx, fabsf(q));
-      else acc = fma((double)q, (double)q, acc);
-    }
-    return LINF ? (double)mx : acc;
-  }
-  __device__ void ragged_phase2(uint32_t item, double total, float *table) const {
-    const uint32_t p = part_of(item);
-    const uint32_t d = g.part_size(p), toff = tile_off(item), n_here = d - toff;
-    const Ctx ctx = begin2(item, total, table);
-    const float nu = ctx.nu, s_over_nu = ctx.s_over_nu;
-    const int mode = ctx.mode;
-    const float *mag = ctx.mag;
-    const Philox rng(seed, stream_id, p);
-    const uint64_t b = base(item);
-    uint32_t *nibs = reinterpret_cast<uint32_t *>(payload + (uint64_t)p * g.stride + kHeaderBytes);
-    const uint32_t n_words = (uint32_t)ru4(cdiv(d, 8));
-#pragma unroll 2
-    for (uint32_t w = (toff >> 3) + threadIdx.x; w < n_words; w += kCThreads) {
-      const uint32_t j0 = w * 8;
-      uint32_t rnd[8];
-      rng.block(j0 >> 2, rnd);
-      rng.block((j0 >> 2) + 1, rnd + 4);
-      uint32_t word = 0;
-      for (int c = 0; c < 8; ++c) {
-        const uint32_t j = j0 + c;
-        if (j < d) {
-          const float q = ragged_q(g.part_base(p) + j);
-          float r = q;
-          if (mode == 1) word |= quantise<false>(q, nu, s_over_nu, rnd[c], mag, &r) << (4 * c);
-          else if (mode == 2) word |= quantise<true>(q, nu, s_over_nu, rnd[c], mag, &r) << (4 * c);
-          if (EF) res[g.part_base(p) + j] = r;
-        }
-      }
-      nibs[w] = word;
-    }
-    (void)n_here;
-    (void)b;
-  }
 };
 
 template <class G, bool EF>

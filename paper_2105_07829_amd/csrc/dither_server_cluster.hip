@@ -52,7 +52,6 @@ struct DitherServerOp {
   __device__ bool needs_total() const { return override == nullptr; }
   __device__ uint32_t part_of(uint32_t item) const { return __builtin_amdgcn_readfirstlane(item / cg.tiles_per_part); }
   __device__ uint32_t tile_off(uint32_t item) const { return __builtin_amdgcn_readfirstlane((item % cg.tiles_per_part) * kCTile); }
-  __device__ bool full(uint32_t item) const { return g.part_size(part_of(item)) - tile_off(item) >= (uint32_t)kCTile; }
   __device__ uint64_t base(uint32_t item) const { return uniform_off(g.part_base(part_of(item)) + tile_off(item)); }
   __device__ void slots_of(uint32_t item, uint32_t *first, uint32_t *count) const {
     uint32_t p = part_of(item);
@@ -179,68 +178,6 @@ struct DitherServerOp {
     else row2_body<0>(item, u, h, ctx);
   }
 
-  // Ragged last tile of a partition (at most one per call): nothing kept in registers, phase 2
-  // recomputes Delta.  One word (8 elements) of every worker per thread and step.
-  __device__ void ragged_deltas(uint32_t p, uint32_t d, uint32_t w, const float *lut, float out[8]) const {
-    float acc[8];
-#pragma unroll
-    for (int c = 0; c < 8; ++c) acc[c] = 0.0f;
-    const int n = NW > 0 ? NW : msgs.n;
-    for (int i = 0; i < n; ++i) {
-      const uint32_t word = reinterpret_cast<const uint32_t *>(msgs.ptr[i] + (uint64_t)p * g.stride + kHeaderBytes)[w];
-#pragma unroll
-      for (int c = 0; c < 8; ++c) acc[c] = acc[c] + lut[i * 16 + ((word >> (4 * c)) & 15u)];
-    }
-#pragma unroll
-    for (int c = 0; c < 8; ++c) {
-      const uint32_t j = w * 8 + c;
-      const float mean = acc[c] * msgs.inv_n;
-      out[c] = j < d ? (EF ? mean + res[g.part_base(p) + j] : mean) : 0.0f;
-    }
-  }
-  __device__ double ragged_phase1(uint32_t item, float *table) const {
-    const uint32_t p = part_of(item), toff = tile_off(item);
-    const uint32_t d = g.part_size(p);
-    fill_luts(p, table);
-    const uint32_t n_words = (uint32_t)cdiv(d, 8);
-    double sum = 0.0;
-    float mx = 0.0f;
-    for (uint32_t w = (toff >> 3) + threadIdx.x; w < n_words; w += kCThreads) {
-      float v[8];
-      ragged_deltas(p, d, w, table, v);
-#pragma unroll
-      for (int c = 0; c < 8; ++c) {
-        if (LINF) mx = fmaxf(mx, fabsf(v[c]));
-        else sum = fma((double)v[c], (double)v[c], sum);
-      }
-    }
-    return LINF ? (double)mx : sum;
-  }
-  __device__ void ragged_phase2(uint32_t item, double total, float *table) const {
-    const uint32_t p = part_of(item), toff = tile_off(item);
-    const uint32_t d = g.part_size(p);
-    const Ctx ctx = begin2(item, total, table);
-    const Philox rng(seed, stream_id, p);
-    uint32_t *nibs = reinterpret_cast<uint32_t *>(payload + (uint64_t)p * g.stride + kHeaderBytes);
-    const uint32_t n_data = (uint32_t)cdiv(d, 8), n_words = (uint32_t)ru4(n_data);
-    for (uint32_t w = (toff >> 3) + threadIdx.x; w < n_words; w += kCThreads) {
-      uint32_t word = 0;
-      if (w < n_data) {
-        float v[8], r[8];
-        ragged_deltas(p, d, w, table, v);
-        if (ctx.mode == 1) word = dither_row<1>(v, ctx.nu, ctx.s_over_nu, levels, rng, w * 8, ctx.mag, r);
-        else if (ctx.mode == 2) word = dither_row<2>(v, ctx.nu, ctx.s_over_nu, levels, rng, w * 8, ctx.mag, r);
-        else word = dither_row<0>(v, ctx.nu, ctx.s_over_nu, levels, rng, w * 8, ctx.mag, r);
-        // elements past d are zero and quantise to nibble 0
-        if (EF) {
-#pragma unroll
-          for (int c = 0; c < 8; ++c)
-            if (w * 8 + c < d) res[g.part_base(p) + w * 8 + c] = r[c];
-        }
-      }
-      nibs[w] = word;
-    }
-  }
 };
 
 template <bool EF, bool LINF>

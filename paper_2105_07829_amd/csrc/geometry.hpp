@@ -41,6 +41,8 @@ struct Geo {
   uint32_t k_cap;        // kept elements of a full partition (TOPK/RANDK), else 0
   uint64_t stride;       // bytes between records
   double k_ratio;
+  uint32_t part0;        // partition number of partition 0 of this view (non-zero when a call
+                         // hands the tail of a gradient to a different set of kernels)
 
   BPC_HD uint64_t part_base(uint32_t p) const { return (uint64_t)p * part_elems; }
   BPC_HD uint32_t part_size(uint32_t p) const {
@@ -84,6 +86,7 @@ inline Geo make_geo(const bpc_params_t *p, uint64_t D) {
   g.k_cap = (p->kind == BPC_TOPK || p->kind == BPC_RANDK) ? (uint32_t)k_rule(p->k_ratio, p->part_elems) : 0;
   g.stride = stride_of(p);
   g.k_ratio = p->k_ratio;
+  g.part0 = 0;
   return g;
 }
 

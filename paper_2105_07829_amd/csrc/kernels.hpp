@@ -32,6 +32,18 @@ struct Workspace {
 
 hipError_t fill_zero(void *ptr, size_t bytes, hipStream_t stream);
 
+// The same call restricted to the ragged last partition: every pointer advanced past the
+// `full_parts` full partitions that another kernel has taken.
+inline void advance_to_tail(uint32_t full_parts, const Geo &g, Source *src, uint8_t **payload,
+                            bpc_params_t *prm) {
+  const uint64_t elems = (uint64_t)full_parts * g.part_elems;
+  if (src->grad) src->grad = (const uint8_t *)src->grad + elems * (src->dtype == BPC_F16 ? 2 : 4);
+  if (src->residual) src->residual += elems;
+  for (int i = 0; i < src->msgs.n; ++i) src->msgs.ptr[i] += (uint64_t)full_parts * g.stride;
+  *payload += (uint64_t)full_parts * g.stride;
+  if (prm->norm_override) prm->norm_override += full_parts;
+}
+
 // C(q) and the residual update for each kind; the same entry serves worker and server.
 hipError_t sign_encode(const Geo &g, const bpc_params_t &prm, const Source &src, uint8_t *payload,
                        const Workspace &ws, hipStream_t stream);

@@ -3,6 +3,7 @@
 //   reduce : v_j from the source, sign bits by wave ballot, per-tile partial of sum |v_j| in f64
 //   finish : sigma = (f32)(sum / d) per partition, written to the record header
 //   apply  : residual_j = v_j - (bit ? -sigma : sigma)
+#include "cluster.hpp"
 #include "sources.hpp"
 
 namespace bpc {
@@ -85,13 +86,24 @@ __global__ __launch_bounds__(kThreads) void sign_apply_kernel(Geo g, SRC src, co
   }
 }
 
-hipError_t sign_encode(const Geo &g, const bpc_params_t &prm, const Source &src, uint8_t *payload,
+hipError_t sign_encode(const Geo &g_in, const bpc_params_t &prm_in, const Source &src_in, uint8_t *payload,
                        const Workspace &ws, hipStream_t stream) {
-  {
+  // Full partitions that are a whole number of register tiles go to the single-pass kernel,
+  // a ragged last partition (or everything, if the shape does not fit) to the passes below.
+  const SplitGeo sp = split_geo(g_in);
+  Geo g = g_in;
+  Source src = src_in;
+  bpc_params_t prm = prm_in;
+  if (sp.single_pass && sp.head.P > 0) {
     bool used = false;
-    hipError_t e = src.grad ? sign_worker_single_pass(g, prm, src, payload, ws, stream, &used)
-                            : sign_server_single_pass(g, prm, src, payload, ws, stream, &used);
-    if (e != hipSuccess || used) return e;
+    hipError_t e = src.grad ? sign_worker_single_pass(sp.head, prm, src, payload, ws, stream, &used)
+                            : sign_server_single_pass(sp.head, prm, src, payload, ws, stream, &used);
+    if (e != hipSuccess) return e;
+    if (used) {
+      if (sp.tail.D == 0) return hipSuccess;
+      advance_to_tail(sp.head.P, g_in, &src, &payload, &prm);
+      g = sp.tail;
+    }
   }
   double *partials = ws.at<double>(ws.lay.partials);
   auto make_server = [&] { return SignMsgSource{src.msgs, src.residual, g.stride}; };

@@ -9,15 +9,20 @@ namespace bpc {
 
 constexpr int kRows = kCPerThread / 4;  // 8 rows of 4096 elements; a thread owns 4 consecutive per row
 
-__device__ inline void widen4(const float4 &g, float out[4]) { out[0] = g.x; out[1] = g.y; out[2] = g.z; out[3] = g.w; }
-__device__ inline void widen4(const uint2 &g, float out[4]) {
-  float2 a = __half22float2(*reinterpret_cast<const __half2 *>(&g.x));
-  float2 b = __half22float2(*reinterpret_cast<const __half2 *>(&g.y));
+__device__ inline void widen4(const u32x4 &g, float out[4]) {
+  out[0] = __uint_as_float(g.x); out[1] = __uint_as_float(g.y); out[2] = __uint_as_float(g.z); out[3] = __uint_as_float(g.w);
+}
+__device__ inline void widen4(const u32x2 &g, float out[4]) {
+  const uint32_t lo = g.x, hi = g.y;
+  float2 a = __half22float2(*reinterpret_cast<const __half2 *>(&lo));
+  float2 b = __half22float2(*reinterpret_cast<const __half2 *>(&hi));
   out[0] = a.x; out[1] = a.y; out[2] = b.x; out[3] = b.y;
 }
 template <class G> struct Vec4Of;
-template <> struct Vec4Of<float> { using type = float4; };
-template <> struct Vec4Of<__half> { using type = uint2; };
+template <> struct Vec4Of<float> { using type = u32x4; };
+template <> struct Vec4Of<__half> { using type = u32x2; };
+__device__ inline u32x4 tile_load4(const TileBuf &b, uint32_t lane_off, uint32_t row_off, const float *) { return b.load16(lane_off, row_off); }
+__device__ inline u32x2 tile_load4(const TileBuf &b, uint32_t lane_off, uint32_t row_off, const __half *) { return b.load8(lane_off, row_off); }
 
 // Sign bits of a row: every lane holds a nibble for its 4 elements; 8 neighbouring lanes are
 // merged into one 32-bit word which lane 8w of the wave ends up holding.
@@ -37,7 +42,7 @@ __device__ inline uint32_t merge8(uint32_t nib) {
 template <class G, bool EF>
 struct SignWorkerOp {
   using GV = typename Vec4Of<G>::type;
-  struct Raw { GV g[kRows]; float4 e[kRows]; };
+  struct Raw { GV g[kRows]; u32x4 e[kRows]; };
   struct Held { float q[kCPerThread]; };
   static constexpr bool kMax = false;
   static constexpr int kRowsPerTile = kRows;
@@ -57,7 +62,6 @@ struct SignWorkerOp {
   __device__ bool needs_total() const { return override == nullptr; }
   __device__ uint32_t part_of(uint32_t item) const { return __builtin_amdgcn_readfirstlane(item / cg.tiles_per_part); }
   __device__ uint32_t tile_off(uint32_t item) const { return __builtin_amdgcn_readfirstlane((item % cg.tiles_per_part) * kCTile); }
-  __device__ bool full(uint32_t item) const { return g.part_size(part_of(item)) - tile_off(item) >= (uint32_t)kCTile; }
   __device__ uint64_t base(uint32_t item) const { return uniform_off(g.part_base(part_of(item)) + tile_off(item)); }
   __device__ void slots_of(uint32_t item, uint32_t *first, uint32_t *count) const {
     uint32_t p = part_of(item);
@@ -69,9 +73,13 @@ struct SignWorkerOp {
   }
 
   __device__ void issue_row(uint32_t item, int u, Raw &raw) const {
-    const uint64_t b = uniform_off(base(item) + (uint32_t)u * (kCThreads * 4));
-    raw.g[u] = reinterpret_cast<const GV *>(grad + b)[threadIdx.x];
-    if (EF) raw.e[u] = reinterpret_cast<const float4 *>(res + b)[threadIdx.x];
+    const uint64_t b = base(item);
+    const TileBuf gb(grad + b, kCTile * sizeof(G));
+    raw.g[u] = tile_load4(gb, threadIdx.x * (4 * sizeof(G)), u * (kCThreads * 4 * sizeof(G)), grad);
+    if (EF) {
+      const TileBuf eb(res + b, kCTile * 4);
+      raw.e[u] = eb.load16(threadIdx.x * 16, u * (kCThreads * 16));
+    }
   }
 
   __device__ double phase1(uint32_t, Raw &raw, Held &h, float *) const {
@@ -80,7 +88,8 @@ struct SignWorkerOp {
     for (int u = 0; u < kRows; ++u) {
       float w[4];
       widen4(raw.g[u], w);
-      const float e[4] = {raw.e[u].x, raw.e[u].y, raw.e[u].z, raw.e[u].w};
+      float e[4];
+      widen4(raw.e[u], e);
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
         float q = EF ? w[c] + e[c] : w[c];
@@ -92,7 +101,7 @@ struct SignWorkerOp {
   }
 
   __device__ void early(uint32_t item, Held &h) const {
-    uint32_t *bits = bits_of(part_of(item));
+    const TileBuf bb(bits_of(part_of(item)) + (tile_off(item) >> 5), kCTile / 8);
     const uint32_t t = threadIdx.x;
 #pragma unroll
     for (int u = 0; u < kRows; ++u) {
@@ -100,8 +109,7 @@ struct SignWorkerOp {
 #pragma unroll
       for (int c = 0; c < 4; ++c) nib |= (h.q[4 * u + c] < 0.0f ? 1u : 0u) << c;
       uint32_t word = merge8(nib);
-      uint32_t *row_words = bits + uniform_off((tile_off(item) >> 5) + u * (kCThreads * 4 / 32));
-      if ((t & 7) == 0) row_words[t >> 3] = word;
+      if ((t & 7) == 0) bb.store4(word, (t >> 3) * 4, u * (kCThreads * 4 / 8));
     }
   }
 
@@ -124,54 +132,13 @@ struct SignWorkerOp {
   __device__ void row2(uint32_t item, int u, Held &h, const Ctx &ctx) const {
     if (!EF) return;
     const float sigma = ctx.sigma;
-    float4 *o4 = reinterpret_cast<float4 *>(res + uniform_off(base(item) + (uint32_t)u * (kCThreads * 4)));
-    float4 o;
-    o.x = h.q[4 * u] - (h.q[4 * u] < 0.0f ? -sigma : sigma);
-    o.y = h.q[4 * u + 1] - (h.q[4 * u + 1] < 0.0f ? -sigma : sigma);
-    o.z = h.q[4 * u + 2] - (h.q[4 * u + 2] < 0.0f ? -sigma : sigma);
-    o.w = h.q[4 * u + 3] - (h.q[4 * u + 3] < 0.0f ? -sigma : sigma);
-    o4[threadIdx.x] = o;
+    const TileBuf ob(res + base(item) + u * (kCThreads * 4), kCThreads * 16);
+    float o[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) o[c] = h.q[4 * u + c] - (h.q[4 * u + c] < 0.0f ? -sigma : sigma);
+    ob.store16(as_u32x4(o[0], o[1], o[2], o[3]), threadIdx.x * 16);
   }
 
-  // Ragged last tile of a partition: lane-strided and rolled, nothing kept in registers;
-  // phase 2 reads g and e again (at most one such tile per call).
-  __device__ double ragged_phase1(uint32_t item, float *) const {
-    const uint32_t p = part_of(item), toff = tile_off(item);
-    const uint32_t d = g.part_size(p), n_here = d - toff;
-    const uint64_t b = base(item);
-    uint32_t *bits = bits_of(p);
-    const uint32_t n_words = (uint32_t)ru4(cdiv(d, 32));
-    const uint32_t lane = threadIdx.x & 63;
-    double acc = 0.0;
-#pragma unroll 4
-    for (uint32_t c0 = (threadIdx.x >> 6) * 64; c0 < (uint32_t)kCTile; c0 += kCThreads) {
-      uint32_t j = c0 + lane;
-      uint32_t word = (toff + c0) >> 5;
-      if (word >= n_words) break;
-      float v = 0.0f;
-      if (j < n_here) {
-        v = load_grad(grad, b + j);
-        if (EF) v = v + res[b + j];
-      }
-      uint64_t mask = __ballot(v < 0.0f);
-      if (lane == 0) *reinterpret_cast<uint64_t *>(bits + word) = mask;
-      acc += (double)fabsf(v);
-    }
-    return acc;
-  }
-  __device__ void ragged_phase2(uint32_t item, double total, float *) const {
-    const uint32_t p = part_of(item);
-    const float sigma = sigma_of(p, total);
-    header(item, sigma);
-    if (!EF) return;
-    const uint32_t n_here = g.part_size(p) - tile_off(item);
-    const uint64_t b = base(item);
-#pragma unroll 4
-    for (uint32_t j = threadIdx.x; j < n_here; j += kCThreads) {
-      float v = load_grad(grad, b + j) + res[b + j];
-      res[b + j] = v - (v < 0.0f ? -sigma : sigma);
-    }
-  }
 };
 
 // Returns hipSuccess with *used = false when the single-pass kernel cannot run this shape

@@ -58,7 +58,6 @@ struct SignServerOp {
   __device__ bool needs_total() const { return override == nullptr; }
   __device__ uint32_t part_of(uint32_t item) const { return __builtin_amdgcn_readfirstlane(item / cg.tiles_per_part); }
   __device__ uint32_t tile_off(uint32_t item) const { return __builtin_amdgcn_readfirstlane((item % cg.tiles_per_part) * kCTile); }
-  __device__ bool full(uint32_t item) const { return g.part_size(part_of(item)) - tile_off(item) >= (uint32_t)kCTile; }
   __device__ uint64_t base(uint32_t item) const { return uniform_off(g.part_base(part_of(item)) + tile_off(item)); }
   __device__ void slots_of(uint32_t item, uint32_t *first, uint32_t *count) const {
     uint32_t p = part_of(item);
@@ -191,76 +190,6 @@ struct SignServerOp {
     o4[1] = make_float4(r[4], r[5], r[6], r[7]);
   }
 
-  // Ragged last tile of a partition (at most one per call): not kept in registers, phase 2
-  // recomputes Delta.  A thread takes kBatch elements per step so that kBatch * n independent
-  // loads are in flight; the functions are not inlined to keep them out of the register
-  // budget of the main path.
-  static constexpr int kBatch = 4;
-  __device__ void ragged_deltas(uint32_t p, uint32_t d, uint32_t j0, float out[kBatch]) const {
-    float acc[kBatch];
-    uint32_t jc[kBatch];
-#pragma unroll
-    for (int k = 0; k < kBatch; ++k) {
-      acc[k] = 0.0f;
-      const uint32_t j = j0 + k * kCThreads;
-      jc[k] = j < d ? j : d - 1;  // clamped: always a valid element
-    }
-    const int n = NW > 0 ? NW : msgs.n;
-#pragma unroll 4
-    for (int i = 0; i < n; ++i) {
-      const uint8_t *rec = msgs.ptr[i] + (uint64_t)p * g.stride;
-      const float s = *reinterpret_cast<const float *>(rec);
-      const uint32_t *words = reinterpret_cast<const uint32_t *>(rec + kHeaderBytes);
-#pragma unroll
-      for (int k = 0; k < kBatch; ++k) {
-        const uint32_t w = words[jc[k] >> 5];
-        acc[k] = acc[k] + (((w >> (jc[k] & 31)) & 1u) ? -s : s);
-      }
-    }
-#pragma unroll
-    for (int k = 0; k < kBatch; ++k) {
-      const float mean = acc[k] * msgs.inv_n;
-      const float v = EF ? mean + res[g.part_base(p) + jc[k]] : mean;
-      out[k] = j0 + k * kCThreads < d ? v : 0.0f;
-    }
-  }
-  __device__ double ragged_phase1(uint32_t item, float *) const {
-    const uint32_t p = part_of(item), toff = tile_off(item);
-    const uint32_t d = g.part_size(p);
-    uint32_t *bits = reinterpret_cast<uint32_t *>(payload + (uint64_t)p * g.stride + kHeaderBytes);
-    const uint32_t n_words = (uint32_t)ru4(cdiv(d, 32));
-    double acc = 0.0;
-    // element j0 + k*kCThreads: lane-strided, a wave's 64 elements are two consecutive words
-    for (uint32_t c0 = 0; c0 < (uint32_t)kCTile; c0 += kBatch * kCThreads) {
-      const uint32_t j0 = toff + c0 + threadIdx.x;
-      if (((toff + c0) >> 5) >= n_words) break;
-      float v[kBatch];
-      ragged_deltas(p, d, j0, v);
-#pragma unroll
-      for (int k = 0; k < kBatch; ++k) {
-        const uint32_t word = (toff + c0 + k * kCThreads + (threadIdx.x & ~63u)) >> 5;
-        const uint64_t mask = __ballot(v[k] < 0.0f);
-        if (lane() == 0 && word < n_words) *reinterpret_cast<uint64_t *>(bits + word) = mask;
-        acc += (double)fabsf(v[k]);
-      }
-    }
-    return acc;
-  }
-  __device__ void ragged_phase2(uint32_t item, double total, float *table) const {
-    const float sigma = begin2(item, total, table).sigma;
-    if (!EF) return;
-    const uint32_t p = part_of(item);
-    const uint32_t d = g.part_size(p);
-    for (uint32_t j0 = tile_off(item) + threadIdx.x; j0 < d; j0 += kBatch * kCThreads) {
-      float v[kBatch];
-      ragged_deltas(p, d, j0, v);
-#pragma unroll
-      for (int k = 0; k < kBatch; ++k) {
-        const uint32_t j = j0 + k * kCThreads;
-        if (j < d) res[g.part_base(p) + j] = v[k] - (v[k] < 0.0f ? -sigma : sigma);
-      }
-    }
-  }
 };
 
 template <bool EF>
