@@ -8,14 +8,17 @@ namespace bpc {
 __global__ void slots_reset_kernel(double *slots, uint32_t n, uint32_t *status) {
   uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) slots[i] = -1.0;
-  if (i == 0) *status = 0;
+  if (i == 0) {
+    status[0] = 0;  // no wait has given up
+    status[1] = 0;  // next ticket
+  }
 }
 
-int cluster_capacity(const void *kernel, size_t dyn_lds) {
+int cluster_capacity(const void *kernel, int threads, size_t dyn_lds) {
   int dev = 0, cus = 0, per_cu = 0;
   if (hipGetDevice(&dev) != hipSuccess) return 0;
   if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
-  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kCThreads, dyn_lds) != hipSuccess) return 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, threads, dyn_lds) != hipSuccess) return 0;
   return cus * per_cu;
 }
 

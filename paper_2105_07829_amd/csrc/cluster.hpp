@@ -2,17 +2,32 @@
 // inputs and writing their outputs keep each tile in registers and synchronise the
 // workgroups that share a partition through global memory:
 //
-//   - the grid is persistent and launched cooperatively, so every workgroup is resident;
-//   - work items (partition, tile) are numbered partition-major and workgroup w takes items
-//     w, w+G, w+2G, ...; a partition has at most G tiles, so the tiles a workgroup waits
-//     for always belong to workgroups that are ahead of nothing but earlier partitions
-//     (no circular wait);
-//   - every item owns one slot (an f64); it is preset to -1 and the workgroup publishes its
-//     non-negative partial with one agent-scope atomic store.  The value is its own flag:
-//     readers poll the slots of their partition with agent-scope atomic loads until none is
-//     negative, so no fence (and no L2 write-back) is involved;
+//   - every tile (partition, tile), numbered partition-major, owns one slot (an f64).  It is
+//     preset to -1 and the workgroup that has the tile publishes its non-negative partial
+//     with one agent-scope atomic store.  The value is its own flag: readers poll the slots
+//     of their partition with agent-scope atomic loads until none is negative, so no fence
+//     (and no L2 write-back) is involved;
 //   - the poll is bounded: after kSpinLimit rounds the workgroup records the failure in a
-//     status word and carries on with the values it has, so the kernel always terminates.
+//     status word and carries on with the values it has, so the kernel always terminates;
+//   - partial results are combined in slot order, so the total does not depend on timing.
+//
+// Two drivers share this exchange.  They differ in how tiles get to workgroups, and each
+// keeps the wait free of cycles provided a partition has no more tiles than the device
+// holds workgroups of the kernel at once (the launcher checks that):
+//
+//   PERSISTENT (cluster_run_persistent): the grid is no larger than what is resident at
+//     once; workgroup w takes tiles w, w+G, w+2G, ...  A workgroup only ever waits for
+//     tiles of its current partition; those belong to workgroups that are resident and that
+//     publish before they wait.  Used where a tile's loads can be requested one tile ahead
+//     (the worker side: two streams per tile), which keeps the memory pipeline of a compute
+//     unit busy across the exchange.
+//   TICKETED (cluster_run_ticketed): one workgroup per tile; a workgroup takes the next tile
+//     number from a counter when it starts running, so numbers are handed out in start
+//     order.  When workgroups wait, the device keeps `capacity` of them resident, all with
+//     numbers at or above the oldest unfinished one; with tiles_per_partition <= capacity
+//     the whole oldest unfinished partition is therefore running, its tiles publish before
+//     they wait, and it completes.  Used where a tile needs many streams and latency-bound
+//     loads (the server side): many small workgroups per compute unit overlap each other.
 #pragma once
 #include "device_utils.hpp"
 #include "geometry.hpp"
@@ -20,20 +35,17 @@
 
 namespace bpc {
 
-constexpr int kCThreads = 1024;               // workgroup size of the cluster kernels (one per CU)
-constexpr int kCPerThread = 32;               // elements a thread keeps in registers
-constexpr int kCTile = kCThreads * kCPerThread;  // 32768
 constexpr int kSpinLimit = 1 << 22;
 
 struct ClusterGeo {
-  uint32_t tiles_per_part;  // kCTile-sized tiles of a full partition
+  uint32_t tiles_per_part;  // tiles of a full partition
   uint32_t n_items;         // tiles over all partitions
 };
 
-// `g` must describe full partitions only, each a whole number of tiles.
-inline ClusterGeo make_cluster_geo(const Geo &g) {
+// `g` must describe full partitions only, each a whole number of tiles of `tile` elements.
+inline ClusterGeo make_cluster_geo(const Geo &g, uint32_t tile) {
   ClusterGeo c;
-  c.tiles_per_part = (uint32_t)(g.part_elems / kCTile);
+  c.tiles_per_part = (uint32_t)(g.part_elems / tile);
   c.n_items = g.P * c.tiles_per_part;
   return c;
 }
@@ -45,9 +57,9 @@ struct SplitGeo {
   Geo head;           // the full partitions (head.D may be 0)
   Geo tail;           // the last, shorter partition as a one-partition gradient (tail.D may be 0)
 };
-inline SplitGeo split_geo(const Geo &g) {
+inline SplitGeo split_geo(const Geo &g, uint32_t tile) {
   SplitGeo s;
-  s.single_pass = g.part_elems % kCTile == 0;
+  s.single_pass = g.part_elems % tile == 0;
   const uint32_t p_full = (uint32_t)(g.D / g.part_elems);
   s.head = g;
   s.head.D = (uint64_t)p_full * g.part_elems;
@@ -61,16 +73,16 @@ inline SplitGeo split_geo(const Geo &g) {
   return s;
 }
 
-// Host side: cluster kernels are launched as ordinary kernels whose grid never exceeds what
-// the device can hold at once.  Two of them running concurrently (different streams) could
-// each end up partly resident and wait for each other's slots, so launches are chained:
-// every launch records an event, and a launch on another stream first waits for it.
+// Host side: the arguments above count the resident workgroups of ONE kernel.  Two cluster
+// kernels running concurrently (different streams) would share the device, so launches are
+// chained: every launch records an event, and a launch on another stream first waits for it.
 hipError_t cluster_launch_begin(hipStream_t stream);
 hipError_t cluster_launch_end(hipStream_t stream);
-// Number of workgroups of `kernel` (kCThreads threads, `dyn_lds` bytes of dynamic LDS) resident at once.
-int cluster_capacity(const void *kernel, size_t dyn_lds = 0);
+// Number of workgroups of `kernel` (`threads` threads, `dyn_lds` bytes of dynamic LDS) resident at once.
+int cluster_capacity(const void *kernel, int threads, size_t dyn_lds = 0);
 
 #if defined(__HIPCC__)
+// Presets the slots to "not published", clears the status word and the ticket counter.
 __global__ void slots_reset_kernel(double *slots, uint32_t n, uint32_t *status);
 
 __device__ inline void slot_publish(double *slot, double value) {
@@ -110,8 +122,8 @@ __device__ inline double slots_collect(const double *slots, uint32_t count, uint
 }
 
 // Workgroup-wide sum / max of per-thread values (fixed order); result valid in wave 0.
-template <bool MAX>
-__device__ inline double cluster_block_reduce(double x, double *red /*kCThreads/64*/) {
+template <bool MAX, int THREADS>
+__device__ inline double cluster_block_reduce(double x, double *red /*THREADS/64*/) {
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) {
     double o = __shfl_xor(x, off, 64);
@@ -123,9 +135,9 @@ __device__ inline double cluster_block_reduce(double x, double *red /*kCThreads/
   __syncthreads();
   double t = 0.0;
   if (wave == 0) {
-    t = lane < kCThreads / 64 ? red[lane] : 0.0;
+    t = lane < THREADS / 64 ? red[lane] : 0.0;
 #pragma unroll
-    for (int off = kCThreads / 128; off > 0; off >>= 1) {
+    for (int off = THREADS / 128; off > 0; off >>= 1) {
       double o = __shfl_xor(t, off, 64);
       t = MAX ? fmax(t, o) : t + o;
     }
@@ -133,32 +145,37 @@ __device__ inline double cluster_block_reduce(double x, double *red /*kCThreads/
   return t;
 }
 
-// Persistent, software-pipelined driver over the tiles of the full partitions (a ragged last
-// partition is left to the multi-pass kernels).  `Op` supplies:
+// What both drivers ask of an operator `Op`:
 //   struct Raw, struct Held, struct Ctx;         raw loads of a tile / what is kept for phase 2
-//   uint32_t n_items() const;
-//   void   issue_row(item, row, Raw&) const;     start the loads of one row of a tile
+//   static constexpr int kThreads;               workgroup size; a tile is kThreads * kCPerThread elements
+//   uint32_t n_items() const;  bool needs_total() const;
 //   double phase1(item, Raw&, Held&, table) const;   consume the loads, return the tile's partial
 //   void   early(item, Held&) const;             stores that do not need the norm
 //   Ctx    begin2(item, total, table) / row2(item, row, Held&, Ctx) const;   outputs of one row
 //   void   slots_of(item, first, count)          the partition's slots
 //   static constexpr int kRowsPerTile; static constexpr bool kMax (maximum instead of sum)
-//   static constexpr Prefetch kPrefetch; static constexpr int kTableFloats (LDS scratch, `table`)
+//   static constexpr int kTableFloats (LDS scratch, `table`)
 // The operator is passed by value in the kernel arguments and never modified, so it stays in
 // the kernel-argument segment (a modified copy would live in scratch memory).
-// The loads of a workgroup's next tile overlap its work on the current one (see Prefetch).
-// When a tile's loads are issued relative to the work on the previous tile.
+
+// When the persistent driver requests a workgroup's next tile, relative to its work on the
+// current one.
 enum class Prefetch {
-  kEarly,        // all of them right after phase 1 of the previous tile (phase 2 is mostly stores)
-  kInterleaved,  // row by row between the rows of output of the previous tile (phase 2 is
-                 // arithmetic-heavy: loads, arithmetic and stores of the CU interleave)
-  kNone          // not ahead of time: phase 1 issues its own loads and hides them behind its
-                 // arithmetic
+  kEarly,        // issue_row() of every row right after phase 1: everything is in flight during
+                 // the exchange (phase 2 is mostly stores)
+  kSplit,        // issue_first() of every row right after phase 1, issue_second() once the
+                 // partition's total is known: the waves that poll have little of their own in
+                 // flight, and phase 2's arithmetic runs under the second part
+  kInterleaved   // issue_row(u) after row u of phase 2 (fewest registers)
 };
 
+// Persistent driver.  In addition `Op` supplies
+//   void issue_row(item, row, Raw&) const [, issue_first / issue_second for kSplit];
+//   static constexpr Prefetch kPrefetch.
 template <class Op>
-__device__ inline void cluster_run(const Op &op, float *table, double *slots, uint32_t *status) {
-  __shared__ double red[kCThreads / 64];
+__device__ inline void cluster_run_persistent(const Op &op, float *table, double *slots, uint32_t *status) {
+  constexpr int kT = Op::kThreads;
+  __shared__ double red[kT / 64];
   __shared__ double total_sh;
   const uint32_t n_items = op.n_items();
   // item numbers are the same for every lane: keeping them in scalar registers makes all
@@ -166,20 +183,28 @@ __device__ inline void cluster_run(const Op &op, float *table, double *slots, ui
   uint32_t item = __builtin_amdgcn_readfirstlane(blockIdx.x);
   if (item >= n_items) return;
   typename Op::Raw raw;
-  if (Op::kPrefetch != Prefetch::kNone) {
 #pragma unroll
-    for (int u = 0; u < Op::kRowsPerTile; ++u) op.issue_row(item, u, raw);
-  }
+  for (int u = 0; u < Op::kRowsPerTile; ++u) op.issue_row(item, u, raw);
+  // Wait for them here (vmcnt 0; the other counters untouched).  The loop below is then
+  // entered with nothing in flight on this path, so the waits the compiler places inside it
+  // are those of the steady state, where stores and the next tile's loads are younger than
+  // the data a row needs and may stay in flight (vector-memory waits count in issue order).
+  __builtin_amdgcn_s_waitcnt(0x0F70);
   for (;;) {
     typename Op::Held held;
     double part = op.phase1(item, raw, held, table);
     const uint32_t next = __builtin_amdgcn_readfirstlane(item + gridDim.x);
     const bool have_next = next < n_items;
-    if (Op::kPrefetch == Prefetch::kEarly && have_next) {
+    if (have_next) {
+      if constexpr (Op::kPrefetch == Prefetch::kEarly) {
 #pragma unroll
-      for (int u = 0; u < Op::kRowsPerTile; ++u) op.issue_row(next, u, raw);
+        for (int u = 0; u < Op::kRowsPerTile; ++u) op.issue_row(next, u, raw);
+      } else if constexpr (Op::kPrefetch == Prefetch::kSplit) {
+#pragma unroll
+        for (int u = 0; u < Op::kRowsPerTile; ++u) op.issue_first(next, u, raw);
+      }
     }
-    part = cluster_block_reduce<Op::kMax>(part, red);
+    part = cluster_block_reduce<Op::kMax, kT>(part, red);
     if (threadIdx.x < 64) {
       uint32_t first, count;
       op.slots_of(item, &first, &count);
@@ -192,6 +217,12 @@ __device__ inline void cluster_run(const Op &op, float *table, double *slots, ui
     op.early(item, held);
     __syncthreads();
     const double total = total_sh;
+    if constexpr (Op::kPrefetch == Prefetch::kSplit) {
+      if (have_next) {
+#pragma unroll
+        for (int u = 0; u < Op::kRowsPerTile; ++u) op.issue_second(next, u, raw);
+      }
+    }
     const typename Op::Ctx ctx = op.begin2(item, total, table);
 #pragma unroll
     for (int u = 0; u < Op::kRowsPerTile; ++u) {
@@ -202,6 +233,39 @@ __device__ inline void cluster_run(const Op &op, float *table, double *slots, ui
     item = next;
     __syncthreads();
   }
+}
+
+// Ticketed driver: phase 1 of `Op` issues its own loads.  `status[1]` is the ticket counter.
+template <class Op>
+__device__ inline void cluster_run_ticketed(const Op &op, float *table, double *slots, uint32_t *status) {
+  constexpr int kT = Op::kThreads;
+  __shared__ double red[kT / 64];
+  __shared__ double total_sh;
+  __shared__ uint32_t item_sh;
+  if (threadIdx.x == 0) item_sh = atomicAdd(status + 1, 1u);
+  __syncthreads();
+  // the same for every lane: keeping it in a scalar register makes all tile addresses scalar
+  const uint32_t item = __builtin_amdgcn_readfirstlane(item_sh);
+  if (item >= op.n_items()) return;
+  typename Op::Raw raw;
+  typename Op::Held held;
+  double part = op.phase1(item, raw, held, table);
+  part = cluster_block_reduce<Op::kMax, kT>(part, red);
+  if (threadIdx.x < 64) {
+    uint32_t first, count;
+    op.slots_of(item, &first, &count);
+    if (op.needs_total()) {
+      if (threadIdx.x == 0) slot_publish(slots + item, part);
+      double total = slots_collect<Op::kMax>(slots + first, count, status);
+      if (threadIdx.x == 0) total_sh = total;
+    }
+  }
+  op.early(item, held);
+  __syncthreads();
+  const double total = total_sh;
+  const typename Op::Ctx ctx = op.begin2(item, total, table);
+#pragma unroll
+  for (int u = 0; u < Op::kRowsPerTile; ++u) op.row2(item, u, held, ctx);
 }
 #endif
 

@@ -1,46 +1,53 @@
-// Kernel wrapper and launcher shared by the single-pass (cluster) kernels.
+// Kernel wrappers and launcher shared by the single-pass (cluster) kernels.
 #pragma once
 #include "cluster.hpp"
 #include "kernels.hpp"
 
 namespace bpc {
 
+// 4 waves per SIMD at least, i.e. at most 128 vector registers a lane.
 template <class Op>
-__global__ __launch_bounds__(kCThreads, 4) void cluster_kernel(const Op op, double *slots, uint32_t *status) {
+__global__ __launch_bounds__(Op::kThreads, 4) void cluster_kernel(const Op op, double *slots, uint32_t *status) {
   __shared__ float table[Op::kTableFloats];
-  cluster_run(op, table, slots, status);
+  if constexpr (Op::kPersistent) cluster_run_persistent(op, table, slots, status);
+  else cluster_run_ticketed(op, table, slots, status);
 }
 
 // Same, with the operator's LDS scratch allocated at launch (sizes above the static limit).
 template <class Op>
-__global__ __launch_bounds__(kCThreads, 4) void cluster_kernel_dyn(const Op op, double *slots, uint32_t *status) {
+__global__ __launch_bounds__(Op::kThreads, 4) void cluster_kernel_dyn(const Op op, double *slots, uint32_t *status) {
   extern __shared__ float dyn_table[];
-  cluster_run(op, dyn_table, slots, status);
+  if constexpr (Op::kPersistent) cluster_run_persistent(op, dyn_table, slots, status);
+  else cluster_run_ticketed(op, dyn_table, slots, status);
 }
 
+// Launches `op` over the tiles of `cg`.  *used = false (and nothing is enqueued) when the
+// shape cannot take the single-pass kernel: a partition has more tiles than the device holds
+// workgroups at once.
 template <class Op>
 static hipError_t launch_cluster(const Op &op, const ClusterGeo &cg, double *slots, uint32_t *status,
                                  hipStream_t stream, bool *used, size_t dyn_lds = 0) {
   const void *fn = dyn_lds ? reinterpret_cast<const void *>(&cluster_kernel_dyn<Op>)
                            : reinterpret_cast<const void *>(&cluster_kernel<Op>);
-  static int capacity = 0;  // per kernel instantiation; a property of the device and the code object
+  static int capacity = 0;  // resident workgroups; per kernel instantiation, a property of the device and the code object
   if (capacity == 0) {
     if (dyn_lds && hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)Op::kMaxDynLds) != hipSuccess) {
       *used = false;
       return hipSuccess;
     }
-    capacity = cluster_capacity(fn, dyn_lds ? Op::kMaxDynLds : 0);
+    capacity = cluster_capacity(fn, Op::kThreads, dyn_lds ? Op::kMaxDynLds : 0);
   }
   *used = false;
   if (capacity <= 0) return hipSuccess;
-  uint32_t grid = cg.n_items < (uint32_t)capacity ? cg.n_items : (uint32_t)capacity;
-  if (cg.tiles_per_part > grid) return hipSuccess;  // a partition must fit in the resident grid
+  if (cg.tiles_per_part > (uint32_t)capacity) return hipSuccess;
+  // persistent: every workgroup resident; ticketed: one workgroup per tile
+  const uint32_t grid = Op::kPersistent && cg.n_items > (uint32_t)capacity ? (uint32_t)capacity : cg.n_items;
   *used = true;
   hipError_t e = cluster_launch_begin(stream);
   if (e != hipSuccess) return e;
   slots_reset_kernel<<<(uint32_t)cdiv(cg.n_items, 256), 256, 0, stream>>>(slots, cg.n_items, status);
-  if (dyn_lds) cluster_kernel_dyn<Op><<<grid, kCThreads, dyn_lds, stream>>>(op, slots, status);
-  else cluster_kernel<Op><<<grid, kCThreads, 0, stream>>>(op, slots, status);
+  if (dyn_lds) cluster_kernel_dyn<Op><<<grid, Op::kThreads, dyn_lds, stream>>>(op, slots, status);
+  else cluster_kernel<Op><<<grid, Op::kThreads, 0, stream>>>(op, slots, status);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   return cluster_launch_end(stream);

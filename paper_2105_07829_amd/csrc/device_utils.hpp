@@ -79,6 +79,12 @@ struct TileBuf {
     __builtin_amdgcn_raw_buffer_store_b32(v, r, (int)lane_off, (int)row_off, 0);
   }
 };
+// A value every lane loads from the same address, moved to a scalar register inside the
+// branch that loads it: the wait for the load then stays in that branch instead of draining
+// every load in flight where the branches join (vector-memory waits are counted in order).
+__device__ inline float uniform_load(const float *p) {
+  return __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(*p)));
+}
 __device__ inline u32x4 as_u32x4(float a, float b, float c, float d) {
   u32x4 v;
   v.x = __float_as_uint(a); v.y = __float_as_uint(b); v.z = __float_as_uint(c); v.w = __float_as_uint(d);

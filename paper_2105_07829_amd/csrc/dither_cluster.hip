@@ -1,5 +1,5 @@
 // Linear-dithering worker, single pass (Algorithm 4 worker lines with the stochastic
-// multi-level quantiser): a workgroup reads a 32768-element tile of g and e once, keeps
+// multi-level quantiser): a workgroup reads a tile (32768 elements) of g and e once, keeps
 // q = g + e in registers, publishes its part of ||q||_2^2 (or max |q|), waits for the
 // partition's norm, then draws the levels, writes the packed nibbles and e' = q - decode.
 #include "cluster_launch.hpp"
@@ -28,10 +28,10 @@ __device__ inline void widen8(const u32x4 &g, float out[8]) {
 }
 // 8 consecutive gradient elements of thread t in row u of a tile window
 __device__ inline F32x8 tile_load8(const TileBuf &b, int u, const float *) {
-  return {b.load16(threadIdx.x * 32, u * (kCThreads * 32)), b.load16(threadIdx.x * 32 + 16, u * (kCThreads * 32))};
+  return {b.load16(threadIdx.x * 32, u * (kWThreads * 32)), b.load16(threadIdx.x * 32 + 16, u * (kWThreads * 32))};
 }
 __device__ inline u32x4 tile_load8(const TileBuf &b, int u, const __half *) {
-  return b.load16(threadIdx.x * 16, u * (kCThreads * 16));
+  return b.load16(threadIdx.x * 16, u * (kWThreads * 16));
 }
 
 template <class G, bool EF, bool LINF>
@@ -43,7 +43,10 @@ struct DitherWorkerOp {
   static constexpr int kRowsPerTile = kDRows;
   static constexpr int kTableFloats = 8;
   static constexpr size_t kMaxDynLds = 0;
-  static constexpr Prefetch kPrefetch = Prefetch::kInterleaved;
+  static constexpr int kThreads = kWThreads;
+  static constexpr bool kPersistent = true;
+  // f32 gradients: the raw loads of a whole tile plus q do not fit the register budget
+  static constexpr Prefetch kPrefetch = sizeof(G) == 2 ? Prefetch::kSplit : Prefetch::kInterleaved;
   struct Ctx { float nu, s_over_nu; int mode; const float *mag; };
 
   Geo g;
@@ -58,18 +61,23 @@ struct DitherWorkerOp {
   __device__ uint32_t n_items() const { return cg.n_items; }
   __device__ bool needs_total() const { return override == nullptr; }
   __device__ uint32_t part_of(uint32_t item) const { return __builtin_amdgcn_readfirstlane(item / cg.tiles_per_part); }
-  __device__ uint32_t tile_off(uint32_t item) const { return __builtin_amdgcn_readfirstlane((item % cg.tiles_per_part) * kCTile); }
+  __device__ uint32_t tile_off(uint32_t item) const { return __builtin_amdgcn_readfirstlane((item % cg.tiles_per_part) * kWTile); }
   __device__ uint64_t base(uint32_t item) const { return uniform_off(g.part_base(part_of(item)) + tile_off(item)); }
   __device__ void slots_of(uint32_t item, uint32_t *first, uint32_t *count) const {
     uint32_t p = part_of(item);
     *first = p * cg.tiles_per_part;
-    *count = (uint32_t)cdiv(g.part_size(p), kCTile);
+    *count = (uint32_t)cdiv(g.part_size(p), kWTile);
   }
 
+  __device__ void issue_first(uint32_t item, int u, Raw &raw) const {
+    raw.g[u] = tile_load8(TileBuf(grad + base(item), kWTile * sizeof(G)), u, grad);
+  }
+  __device__ void issue_second(uint32_t item, int u, Raw &raw) const {
+    if (EF) raw.e[u] = tile_load8(TileBuf(res + base(item), kWTile * 4), u, (const float *)nullptr);
+  }
   __device__ void issue_row(uint32_t item, int u, Raw &raw) const {
-    const uint64_t b = base(item);
-    raw.g[u] = tile_load8(TileBuf(grad + b, kCTile * sizeof(G)), u, grad);
-    if (EF) raw.e[u] = tile_load8(TileBuf(res + b, kCTile * 4), u, (const float *)nullptr);
+    issue_first(item, u, raw);
+    issue_second(item, u, raw);
   }
 
   __device__ double phase1(uint32_t, Raw &raw, Held &h, float *) const {
@@ -94,7 +102,7 @@ struct DitherWorkerOp {
   __device__ void early(uint32_t, Held &) const {}
 
   __device__ float nu_of(uint32_t p, double total) const {
-    if (override) return override[p];
+    if (override) return uniform_load(override + p);
     return LINF ? (float)total : (float)sqrt(total);
   }
   __device__ void header(uint32_t item, float nu) const {
@@ -156,7 +164,7 @@ struct DitherWorkerOp {
     const Philox rng(seed, stream_id, p);
     const uint64_t b = base(item);
     uint32_t *nibs = reinterpret_cast<uint32_t *>(payload + (uint64_t)p * g.stride + kHeaderBytes);
-    const uint32_t off = (u * kCThreads + threadIdx.x) * 8;  // within the tile
+    const uint32_t off = (u * kWThreads + threadIdx.x) * 8;  // within the tile
     const uint32_t j0 = tile_off(item) + off;                // within the partition
     uint32_t word = 0;
     float r[8];
@@ -171,9 +179,9 @@ struct DitherWorkerOp {
       for (int c = 0; c < 8; ++c)
         word |= quantise<MODE == 2>(h.q[8 * u + c], nu, s_over_nu, rnd[c], mag, &r[c]) << (4 * c);
     }
-    TileBuf(nibs + (tile_off(item) >> 3), kCTile / 2).store4(word, threadIdx.x * 4, u * (kCThreads * 4));
+    TileBuf(nibs + (tile_off(item) >> 3), kWTile / 2).store4(word, threadIdx.x * 4, u * (kWThreads * 4));
     if (EF) {
-      const TileBuf ob(res + b + u * (kCThreads * 8), kCThreads * 32);
+      const TileBuf ob(res + b + u * (kWThreads * 8), kWThreads * 32);
       ob.store16(as_u32x4(r[0], r[1], r[2], r[3]), threadIdx.x * 32);
       ob.store16(as_u32x4(r[4], r[5], r[6], r[7]), threadIdx.x * 32 + 16);
     }
@@ -196,7 +204,7 @@ static hipError_t launch_dither(const Geo &g, const ClusterGeo &cg, const bpc_pa
 
 hipError_t dither_worker_single_pass(const Geo &g, const bpc_params_t &prm, const Source &src, uint8_t *payload,
                                      const Workspace &ws, hipStream_t stream, bool *used) {
-  ClusterGeo cg = make_cluster_geo(g);
+  ClusterGeo cg = make_cluster_geo(g, kWTile);
   double *slots = ws.at<double>(ws.lay.slots);
   uint32_t *status = ws.at<uint32_t>(ws.lay.status);
   const bool f16 = src.dtype == BPC_F16;

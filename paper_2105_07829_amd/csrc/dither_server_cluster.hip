@@ -1,10 +1,10 @@
 // Linear-dithering server, single pass (Algorithm 4 server lines): Delta = mean of the n
 // decoded worker messages + e~, p = C(Delta) with fresh stochastic levels, e~' = Delta - p.
-// A workgroup reads a 32768-element tile of e~ and the matching nibbles of the n messages
+// A workgroup reads a tile (8192 elements) of e~ and the matching nibbles of the n messages
 // once, keeps Delta in registers, exchanges its part of ||Delta||_2^2 (or max |Delta|) and
 // then writes the packed levels and e~'.
 //
-// A thread owns 8 consecutive elements per row (4 rows of 8192 elements), i.e. one 32-bit word
+// A thread owns 8 consecutive elements per row (4 rows of 2048 elements), i.e. one 32-bit word
 // of every worker's nibbles per row.  A nibble indexes a 16-entry LDS table per worker that
 // holds the decoded values +-(nu_i * level) / s.
 #include "dither_common.hpp"
@@ -37,7 +37,8 @@ struct DitherServerOp {
   static constexpr int kRowsPerTile = kDSRows;
   static constexpr int kTableFloats = kMaxWorkers * 16 + 8;   // decode tables, then the 8 output magnitudes
   static constexpr size_t kMaxDynLds = 0;
-  static constexpr Prefetch kPrefetch = Prefetch::kNone;
+  static constexpr int kThreads = kSThreads;
+  static constexpr bool kPersistent = false;
 
   Geo g;
   ClusterGeo cg;
@@ -51,17 +52,17 @@ struct DitherServerOp {
   __device__ uint32_t n_items() const { return cg.n_items; }
   __device__ bool needs_total() const { return override == nullptr; }
   __device__ uint32_t part_of(uint32_t item) const { return __builtin_amdgcn_readfirstlane(item / cg.tiles_per_part); }
-  __device__ uint32_t tile_off(uint32_t item) const { return __builtin_amdgcn_readfirstlane((item % cg.tiles_per_part) * kCTile); }
+  __device__ uint32_t tile_off(uint32_t item) const { return __builtin_amdgcn_readfirstlane((item % cg.tiles_per_part) * kSTile); }
   __device__ uint64_t base(uint32_t item) const { return uniform_off(g.part_base(part_of(item)) + tile_off(item)); }
   __device__ void slots_of(uint32_t item, uint32_t *first, uint32_t *count) const {
     uint32_t p = part_of(item);
     *first = p * cg.tiles_per_part;
-    *count = (uint32_t)cdiv(g.part_size(p), kCTile);
+    *count = (uint32_t)cdiv(g.part_size(p), kSTile);
   }
 
   __device__ void issue_row(uint32_t item, int u, Raw &raw) const {
     if (!EF) return;
-    const uint64_t b = uniform_off(base(item) + (uint32_t)u * (kCThreads * 8));
+    const uint64_t b = uniform_off(base(item) + (uint32_t)u * (kSThreads * 8));
     const float4 *e4 = reinterpret_cast<const float4 *>(res + b) + threadIdx.x * 2;
     raw.e[2 * u] = e4[0];
     raw.e[2 * u + 1] = e4[1];
@@ -70,7 +71,7 @@ struct DitherServerOp {
   // Decode tables of all workers for partition p: lut[i*16 + nibble].
   __device__ void fill_luts(uint32_t p, float *lut) const {
     __syncthreads();
-    for (int e = threadIdx.x; e < msgs.n * 16; e += kCThreads) {
+    for (int e = threadIdx.x; e < msgs.n * 16; e += kSThreads) {
       const int i = e >> 4, nib = e & 15;
       const float nu = *reinterpret_cast<const float *>(msgs.ptr[i] + (uint64_t)p * g.stride);
       const float mag = (nu * (float)(nib & 7)) / (float)levels;
@@ -84,7 +85,7 @@ struct DitherServerOp {
     const uint32_t *nibs = reinterpret_cast<const uint32_t *>(
         msgs.ptr[i] + uniform_off((uint64_t)part_of(item) * g.stride + kHeaderBytes + (tile_off(item) >> 1)));
 #pragma unroll
-    for (int u = 0; u < kDSRows; ++u) out[u] = nibs[u * kCThreads + threadIdx.x];
+    for (int u = 0; u < kDSRows; ++u) out[u] = nibs[u * kSThreads + threadIdx.x];
   }
 
   __device__ static void add_worker(const uint32_t word[kDSRows], const float *lut_i, float acc[kCPerThread]) {
@@ -140,7 +141,7 @@ struct DitherServerOp {
   __device__ void early(uint32_t, Held &) const {}
 
   __device__ float nu_of(uint32_t p, double total) const {
-    if (override) return override[p];
+    if (override) return uniform_load(override + p);
     return LINF ? (float)total : (float)sqrt(total);
   }
   __device__ Ctx begin2(uint32_t item, double total, float *table) const {
@@ -161,13 +162,13 @@ struct DitherServerOp {
   __device__ void row2_body(uint32_t item, int u, Held &h, const Ctx &ctx) const {
     const uint32_t p = part_of(item);
     const Philox rng(seed, stream_id, p);
-    const uint32_t j0 = tile_off(item) + (u * kCThreads + threadIdx.x) * 8;
+    const uint32_t j0 = tile_off(item) + (u * kSThreads + threadIdx.x) * 8;
     float r[8];
     const uint32_t word = dither_row<MODE>(&h.delta[8 * u], ctx.nu, ctx.s_over_nu, levels, rng, j0, ctx.mag, r);
     uint32_t *nibs = reinterpret_cast<uint32_t *>(payload + (uint64_t)p * g.stride + kHeaderBytes);
-    (nibs + uniform_off((tile_off(item) + u * (kCThreads * 8)) >> 3))[threadIdx.x] = word;
+    (nibs + uniform_off((tile_off(item) + u * (kSThreads * 8)) >> 3))[threadIdx.x] = word;
     if (EF) {
-      float4 *o4 = reinterpret_cast<float4 *>(res + uniform_off(base(item) + (uint32_t)u * (kCThreads * 8))) + threadIdx.x * 2;
+      float4 *o4 = reinterpret_cast<float4 *>(res + uniform_off(base(item) + (uint32_t)u * (kSThreads * 8))) + threadIdx.x * 2;
       o4[0] = make_float4(r[0], r[1], r[2], r[3]);
       o4[1] = make_float4(r[4], r[5], r[6], r[7]);
     }
@@ -201,7 +202,7 @@ static hipError_t launch_dither_server(const Geo &g, const ClusterGeo &cg, const
 
 hipError_t dither_server_single_pass(const Geo &g, const bpc_params_t &prm, const Source &src, uint8_t *payload,
                                      const Workspace &ws, hipStream_t stream, bool *used) {
-  ClusterGeo cg = make_cluster_geo(g);
+  ClusterGeo cg = make_cluster_geo(g, kSTile);
   double *slots = ws.at<double>(ws.lay.slots);
   uint32_t *status = ws.at<uint32_t>(ws.lay.status);
   const bool linf = prm.norm == BPC_NORM_LINF;

@@ -17,6 +17,11 @@ namespace bpc {
 constexpr int kMaxWorkers = 64;      // most worker messages one aggregate call accepts
 constexpr int kTile = 4096;          // elements one workgroup handles in the streaming kernels
 constexpr int kThreads = 256;        // workgroup size of the streaming kernels
+constexpr int kCPerThread = 32;      // elements a thread of the single-pass (cluster) kernels keeps in registers
+constexpr int kWThreads = 1024;      // workgroup size of the worker-side cluster kernels (persistent, one per CU)
+constexpr int kSThreads = 256;       // workgroup size of the server-side cluster kernels (one small workgroup per tile)
+constexpr int kWTile = kWThreads * kCPerThread;  // 32768
+constexpr int kSTile = kSThreads * kCPerThread;  // 8192
 constexpr uint32_t kHeaderBytes = 16;
 
 BPC_HD inline uint64_t ru4(uint64_t x) { return (x + 3) / 4 * 4; }
@@ -98,8 +103,8 @@ struct WsLayout {
   size_t hist;       // u32[P*4096]: top-k radix histograms (2048 + 1024 + 1024 bins)
   size_t state;      // u32[P*8]: top-k selection state
   size_t tilecnt;    // u32[2*n_tiles]: per-tile (greater, equal) counts, then offsets
-  size_t slots;      // double[3 * tiles of 32768]: partition-wide reductions of the single-pass kernels
-  size_t status;     // u32[64]: word 0 is non-zero if a single-pass kernel gave up waiting
+  size_t slots;      // double[tiles of kSTile]: partition-wide reductions of the single-pass kernels
+  size_t status;     // u32[64]: word 0 is non-zero if a single-pass kernel gave up waiting, word 1 is its ticket counter
   size_t norms;      // double[3*P]: LANS block norms when blocks are the partitions
   size_t total;
 };
@@ -115,7 +120,7 @@ inline WsLayout ws_layout(const bpc_params_t *p, uint64_t D) {
   w.hist = take(p->kind == BPC_TOPK ? sizeof(uint32_t) * 4096 * (size_t)g.P : 0);
   w.state = take(p->kind == BPC_TOPK ? sizeof(uint32_t) * 8 * (size_t)g.P : 0);
   w.tilecnt = take(p->kind == BPC_TOPK ? sizeof(uint32_t) * 2 * (size_t)g.n_tiles : 0);
-  w.slots = take(sizeof(double) * 3 * ((size_t)g.P * cdiv(g.part_elems, 32768)));
+  w.slots = take(sizeof(double) * ((size_t)g.P * cdiv(g.part_elems, kSTile)));
   w.status = take(256);
   w.norms = take(sizeof(double) * 3 * (size_t)g.P);
   w.total = off;

@@ -90,7 +90,7 @@ hipError_t sign_encode(const Geo &g_in, const bpc_params_t &prm_in, const Source
                        const Workspace &ws, hipStream_t stream) {
   // Full partitions that are a whole number of register tiles go to the single-pass kernel,
   // a ragged last partition (or everything, if the shape does not fit) to the passes below.
-  const SplitGeo sp = split_geo(g_in);
+  const SplitGeo sp = split_geo(g_in, src_in.grad ? kWTile : kSTile);
   Geo g = g_in;
   Source src = src_in;
   bpc_params_t prm = prm_in;

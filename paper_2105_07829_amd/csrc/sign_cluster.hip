@@ -1,5 +1,5 @@
 // Scaled-sign worker, single pass (Algorithm 4 worker lines with C(v) = ||v||_1/d sign(v)):
-// each workgroup reads a 32768-element tile of g and e once, keeps q = g + e in registers,
+// each workgroup reads a tile (32768 elements) of g and e once, keeps q = g + e in registers,
 // writes the sign bits, publishes its part of ||q||_1, waits for the partition's sum and then
 // writes e' = q -+ sigma.  HBM traffic is the algorithmic minimum: g and e read once, e' and
 // the bits written once.
@@ -48,7 +48,10 @@ struct SignWorkerOp {
   static constexpr int kRowsPerTile = kRows;
   static constexpr int kTableFloats = 1;
   static constexpr size_t kMaxDynLds = 0;
-  static constexpr Prefetch kPrefetch = Prefetch::kEarly;
+  static constexpr int kThreads = kWThreads;
+  static constexpr bool kPersistent = true;
+  // f32 gradients: the raw loads of a whole tile plus q do not fit the register budget
+  static constexpr Prefetch kPrefetch = sizeof(G) == 2 ? Prefetch::kEarly : Prefetch::kSplit;
   struct Ctx { float sigma; };
 
   Geo g;
@@ -61,25 +64,30 @@ struct SignWorkerOp {
   __device__ uint32_t n_items() const { return cg.n_items; }
   __device__ bool needs_total() const { return override == nullptr; }
   __device__ uint32_t part_of(uint32_t item) const { return __builtin_amdgcn_readfirstlane(item / cg.tiles_per_part); }
-  __device__ uint32_t tile_off(uint32_t item) const { return __builtin_amdgcn_readfirstlane((item % cg.tiles_per_part) * kCTile); }
+  __device__ uint32_t tile_off(uint32_t item) const { return __builtin_amdgcn_readfirstlane((item % cg.tiles_per_part) * kWTile); }
   __device__ uint64_t base(uint32_t item) const { return uniform_off(g.part_base(part_of(item)) + tile_off(item)); }
   __device__ void slots_of(uint32_t item, uint32_t *first, uint32_t *count) const {
     uint32_t p = part_of(item);
     *first = p * cg.tiles_per_part;
-    *count = (uint32_t)cdiv(g.part_size(p), kCTile);
+    *count = (uint32_t)cdiv(g.part_size(p), kWTile);
   }
   __device__ uint32_t *bits_of(uint32_t p) const {
     return reinterpret_cast<uint32_t *>(payload + (uint64_t)p * g.stride + kHeaderBytes);
   }
 
-  __device__ void issue_row(uint32_t item, int u, Raw &raw) const {
-    const uint64_t b = base(item);
-    const TileBuf gb(grad + b, kCTile * sizeof(G));
-    raw.g[u] = tile_load4(gb, threadIdx.x * (4 * sizeof(G)), u * (kCThreads * 4 * sizeof(G)), grad);
+  __device__ void issue_first(uint32_t item, int u, Raw &raw) const {
+    const TileBuf gb(grad + base(item), kWTile * sizeof(G));
+    raw.g[u] = tile_load4(gb, threadIdx.x * (4 * sizeof(G)), u * (kWThreads * 4 * sizeof(G)), grad);
+  }
+  __device__ void issue_second(uint32_t item, int u, Raw &raw) const {
     if (EF) {
-      const TileBuf eb(res + b, kCTile * 4);
-      raw.e[u] = eb.load16(threadIdx.x * 16, u * (kCThreads * 16));
+      const TileBuf eb(res + base(item), kWTile * 4);
+      raw.e[u] = eb.load16(threadIdx.x * 16, u * (kWThreads * 16));
     }
+  }
+  __device__ void issue_row(uint32_t item, int u, Raw &raw) const {
+    issue_first(item, u, raw);
+    issue_second(item, u, raw);
   }
 
   __device__ double phase1(uint32_t, Raw &raw, Held &h, float *) const {
@@ -101,7 +109,7 @@ struct SignWorkerOp {
   }
 
   __device__ void early(uint32_t item, Held &h) const {
-    const TileBuf bb(bits_of(part_of(item)) + (tile_off(item) >> 5), kCTile / 8);
+    const TileBuf bb(bits_of(part_of(item)) + (tile_off(item) >> 5), kWTile / 8);
     const uint32_t t = threadIdx.x;
 #pragma unroll
     for (int u = 0; u < kRows; ++u) {
@@ -109,12 +117,13 @@ struct SignWorkerOp {
 #pragma unroll
       for (int c = 0; c < 4; ++c) nib |= (h.q[4 * u + c] < 0.0f ? 1u : 0u) << c;
       uint32_t word = merge8(nib);
-      if ((t & 7) == 0) bb.store4(word, (t >> 3) * 4, u * (kCThreads * 4 / 8));
+      if ((t & 7) == 0) bb.store4(word, (t >> 3) * 4, u * (kWThreads * 4 / 8));
     }
   }
 
   __device__ float sigma_of(uint32_t p, double total) const {
-    return override ? override[p] : (float)(total / (double)g.part_size(p));
+    if (override) return uniform_load(override + p);
+    return (float)(total / (double)g.part_size(p));
   }
   __device__ void header(uint32_t item, float sigma) const {
     if (tile_off(item) == 0 && threadIdx.x == 0) {
@@ -132,7 +141,7 @@ struct SignWorkerOp {
   __device__ void row2(uint32_t item, int u, Held &h, const Ctx &ctx) const {
     if (!EF) return;
     const float sigma = ctx.sigma;
-    const TileBuf ob(res + base(item) + u * (kCThreads * 4), kCThreads * 16);
+    const TileBuf ob(res + base(item) + u * (kWThreads * 4), kWThreads * 16);
     float o[4];
 #pragma unroll
     for (int c = 0; c < 4; ++c) o[c] = h.q[4 * u + c] - (h.q[4 * u + c] < 0.0f ? -sigma : sigma);
@@ -145,7 +154,7 @@ struct SignWorkerOp {
 // (the caller then takes the multi-pass path).
 hipError_t sign_worker_single_pass(const Geo &g, const bpc_params_t &prm, const Source &src, uint8_t *payload,
                                    const Workspace &ws, hipStream_t stream, bool *used) {
-  ClusterGeo cg = make_cluster_geo(g);
+  ClusterGeo cg = make_cluster_geo(g, kWTile);
   double *slots = ws.at<double>(ws.lay.slots);
   uint32_t *status = ws.at<uint32_t>(ws.lay.status);
   const bool f16 = src.dtype == BPC_F16;

@@ -1,9 +1,9 @@
 // Scaled-sign server, single pass (Algorithm 4 server lines): Delta = mean of the n decoded
-// worker messages + e~, p = C(Delta), e~' = Delta - p.  A workgroup reads a 32768-element
+// worker messages + e~, p = C(Delta), e~' = Delta - p.  A workgroup reads an 8192-element
 // tile of e~ and the matching bits of the n messages once, keeps Delta in registers, writes
 // the sign bits of Delta, exchanges its part of ||Delta||_1 and writes e~' = Delta -+ sigma.
 //
-// A thread owns 8 consecutive elements per row (4 rows of 8192 elements per tile), i.e. one
+// A thread owns 8 consecutive elements per row (4 rows of 2048 elements per tile), i.e. one
 // byte of every worker's sign bits per row; shifting a bit to the sign position and merging it
 // into |sigma_i| gives +-sigma_i in two instructions.
 #include "cluster_launch.hpp"
@@ -43,7 +43,8 @@ struct SignServerOp {
   static constexpr bool kMax = false;
   static constexpr int kRowsPerTile = kSRows;
   static constexpr int kTableFloats = kMaxWorkers;
-  static constexpr Prefetch kPrefetch = Prefetch::kNone;
+  static constexpr int kThreads = kSThreads;
+  static constexpr bool kPersistent = false;
   static constexpr size_t kMaxDynLds = 0;
   struct Ctx { float sigma; };
 
@@ -57,18 +58,18 @@ struct SignServerOp {
   __device__ uint32_t n_items() const { return cg.n_items; }
   __device__ bool needs_total() const { return override == nullptr; }
   __device__ uint32_t part_of(uint32_t item) const { return __builtin_amdgcn_readfirstlane(item / cg.tiles_per_part); }
-  __device__ uint32_t tile_off(uint32_t item) const { return __builtin_amdgcn_readfirstlane((item % cg.tiles_per_part) * kCTile); }
+  __device__ uint32_t tile_off(uint32_t item) const { return __builtin_amdgcn_readfirstlane((item % cg.tiles_per_part) * kSTile); }
   __device__ uint64_t base(uint32_t item) const { return uniform_off(g.part_base(part_of(item)) + tile_off(item)); }
   __device__ void slots_of(uint32_t item, uint32_t *first, uint32_t *count) const {
     uint32_t p = part_of(item);
     *first = p * cg.tiles_per_part;
-    *count = (uint32_t)cdiv(g.part_size(p), kCTile);
+    *count = (uint32_t)cdiv(g.part_size(p), kSTile);
   }
   __device__ static uint32_t lane() { return threadIdx.x & 63; }
 
   __device__ void issue_row(uint32_t item, int u, Raw &raw) const {
     if (!EF) return;
-    const uint64_t b = uniform_off(base(item) + (uint32_t)u * (kCThreads * 8));
+    const uint64_t b = uniform_off(base(item) + (uint32_t)u * (kSThreads * 8));
     const float4 *e4 = reinterpret_cast<const float4 *>(res + b) + threadIdx.x * 2;
     raw.e[2 * u] = e4[0];
     raw.e[2 * u + 1] = e4[1];
@@ -78,7 +79,7 @@ struct SignServerOp {
   __device__ void load_bytes(uint32_t item, int i, uint32_t out[kSRows]) const {
     const uint8_t *bits = msgs.ptr[i] + uniform_off((uint64_t)part_of(item) * g.stride + kHeaderBytes + (tile_off(item) >> 3));
 #pragma unroll
-    for (int u = 0; u < kSRows; ++u) out[u] = bits[u * kCThreads + threadIdx.x];
+    for (int u = 0; u < kSRows; ++u) out[u] = bits[u * kSThreads + threadIdx.x];
   }
 
   __device__ void add_worker(const uint32_t byte[kSRows], float sigma_i, float acc[kCPerThread]) const {
@@ -158,13 +159,14 @@ struct SignServerOp {
       // DPP row_shl:n reads lane i+n of the 16-lane row (0 past its end)
       byte |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)byte, 0x101, 0xf, 0xf, true) << 8;
       byte |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)byte, 0x102, 0xf, 0xf, true) << 16;
-      uint32_t *row_words = bits + uniform_off((tile_off(item) >> 5) + u * (kCThreads * 8 / 32));
+      uint32_t *row_words = bits + uniform_off((tile_off(item) >> 5) + u * (kSThreads * 8 / 32));
       if ((threadIdx.x & 3) == 0) row_words[threadIdx.x >> 2] = byte;
     }
   }
 
   __device__ float sigma_of(uint32_t p, double total) const {
-    return override ? override[p] : (float)(total / (double)g.part_size(p));
+    if (override) return uniform_load(override + p);
+    return (float)(total / (double)g.part_size(p));
   }
   __device__ void header(uint32_t item, float s) const {
     if (tile_off(item) == 0 && threadIdx.x == 0) {
@@ -181,7 +183,7 @@ struct SignServerOp {
   __device__ void row2(uint32_t item, int u, Held &h, const Ctx &ctx) const {
     if (!EF) return;
     const float sigma = ctx.sigma;
-    const uint64_t b = uniform_off(base(item) + (uint32_t)u * (kCThreads * 8));
+    const uint64_t b = uniform_off(base(item) + (uint32_t)u * (kSThreads * 8));
     float4 *o4 = reinterpret_cast<float4 *>(res + b) + threadIdx.x * 2;
     float r[8];
 #pragma unroll
@@ -208,7 +210,7 @@ static hipError_t launch_sign_server(const Geo &g, const ClusterGeo &cg, const b
 
 hipError_t sign_server_single_pass(const Geo &g, const bpc_params_t &prm, const Source &src, uint8_t *payload,
                                    const Workspace &ws, hipStream_t stream, bool *used) {
-  ClusterGeo cg = make_cluster_geo(g);
+  ClusterGeo cg = make_cluster_geo(g, kSTile);
   double *slots = ws.at<double>(ws.lay.slots);
   uint32_t *status = ws.at<uint32_t>(ws.lay.status);
   if (src.residual) return launch_sign_server<true>(g, cg, prm, src, payload, slots, status, stream, used);
