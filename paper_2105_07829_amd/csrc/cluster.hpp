@@ -42,24 +42,35 @@ struct ClusterGeo {
   uint32_t n_items;         // tiles over all partitions
 };
 
-// `g` must describe full partitions only, each a whole number of tiles of `tile` elements.
+// A full partition must be a whole number of tiles of `tile` elements; a shorter last
+// partition has the tiles it needs, the last of them possibly ragged.
 inline ClusterGeo make_cluster_geo(const Geo &g, uint32_t tile) {
   ClusterGeo c;
   c.tiles_per_part = (uint32_t)(g.part_elems / tile);
-  c.n_items = g.P * c.tiles_per_part;
+  const uint32_t p_full = (uint32_t)(g.D / g.part_elems);
+  c.n_items = p_full * c.tiles_per_part + (uint32_t)cdiv(g.D - (uint64_t)p_full * g.part_elems, tile);
   return c;
 }
 
-// Splits a gradient into the part the single-pass kernels take (whole partitions that are a
-// whole number of tiles) and the ragged last partition, if any.
+// Splits a gradient into the part the single-pass kernels take and the part left to the
+// multi-pass kernels.  `ragged_ok`: the single-pass kernel bounds its accesses to a shorter
+// last partition itself; otherwise it gets the full partitions only.
 struct SplitGeo {
   bool single_pass;   // false: the partition size is not a multiple of the tile
-  Geo head;           // the full partitions (head.D may be 0)
+  Geo head;           // what the single-pass kernel takes (head.D may be 0)
   Geo tail;           // the last, shorter partition as a one-partition gradient (tail.D may be 0)
 };
-inline SplitGeo split_geo(const Geo &g, uint32_t tile) {
+inline SplitGeo split_geo(const Geo &g, uint32_t tile, bool ragged_ok) {
   SplitGeo s;
   s.single_pass = g.part_elems % tile == 0;
+  if (ragged_ok) {
+    s.head = g;
+    s.tail = g;
+    s.tail.D = 0;
+    s.tail.P = 0;
+    s.tail.n_tiles = 0;
+    return s;
+  }
   const uint32_t p_full = (uint32_t)(g.D / g.part_elems);
   s.head = g;
   s.head.D = (uint64_t)p_full * g.part_elems;

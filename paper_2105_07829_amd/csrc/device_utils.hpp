@@ -85,6 +85,12 @@ struct TileBuf {
 __device__ inline float uniform_load(const float *p) {
   return __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(*p)));
 }
+// Descriptor of row elements [row0, row0 + row_elems) of an f32 tile of which only the first
+// `valid` elements exist: accesses to the rest read 0 / are dropped.
+__device__ inline TileBuf row_buf(const float *tile_base, uint32_t valid, uint32_t row0, uint32_t row_elems) {
+  const uint32_t in_row = valid > row0 ? valid - row0 : 0u;
+  return TileBuf(tile_base + row0, (in_row < row_elems ? in_row : row_elems) * 4);
+}
 __device__ inline u32x4 as_u32x4(float a, float b, float c, float d) {
   u32x4 v;
   v.x = __float_as_uint(a); v.y = __float_as_uint(b); v.z = __float_as_uint(c); v.w = __float_as_uint(d);

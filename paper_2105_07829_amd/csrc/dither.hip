@@ -127,7 +127,10 @@ hipError_t dither_encode(const Geo &g_in, const bpc_params_t &prm_in, const Sour
                          const Workspace &ws, hipStream_t stream) {
   // Full partitions that are a whole number of register tiles go to the single-pass kernel,
   // a ragged last partition (or everything, if the shape does not fit) to the passes below.
-  const SplitGeo sp = split_geo(g_in, src_in.grad ? kWTile : kSTile);
+  // The single-pass kernels bound a shorter last partition through their buffer descriptors
+  // (dword granularity, so an odd number of f16 gradient elements is left to the passes below).
+  const bool ragged_ok = !(src_in.grad && src_in.dtype == BPC_F16 && (g_in.D & 1));
+  const SplitGeo sp = split_geo(g_in, src_in.grad ? kWTile : kSTile, ragged_ok);
   Geo g = g_in;
   Source src = src_in;
   bpc_params_t prm = prm_in;

@@ -69,11 +69,18 @@ struct DitherWorkerOp {
     *count = (uint32_t)cdiv(g.part_size(p), kWTile);
   }
 
+  // Elements of the tile that lie inside its partition.  Every tile access goes through a
+  // buffer descriptor of exactly that many elements: loads past it return 0 (q = 0 there:
+  // nothing for the norm, level 0) and stores past it are dropped.
+  __device__ uint32_t valid_of(uint32_t item) const {
+    const uint32_t left = g.part_size(part_of(item)) - tile_off(item);
+    return __builtin_amdgcn_readfirstlane(left < (uint32_t)kWTile ? left : (uint32_t)kWTile);
+  }
   __device__ void issue_first(uint32_t item, int u, Raw &raw) const {
-    raw.g[u] = tile_load8(TileBuf(grad + base(item), kWTile * sizeof(G)), u, grad);
+    raw.g[u] = tile_load8(TileBuf(grad + base(item), valid_of(item) * sizeof(G)), u, grad);
   }
   __device__ void issue_second(uint32_t item, int u, Raw &raw) const {
-    if (EF) raw.e[u] = tile_load8(TileBuf(res + base(item), kWTile * 4), u, (const float *)nullptr);
+    if (EF) raw.e[u] = tile_load8(TileBuf(res + base(item), valid_of(item) * 4), u, (const float *)nullptr);
   }
   __device__ void issue_row(uint32_t item, int u, Raw &raw) const {
     issue_first(item, u, raw);
@@ -181,7 +188,7 @@ struct DitherWorkerOp {
     }
     TileBuf(nibs + (tile_off(item) >> 3), kWTile / 2).store4(word, threadIdx.x * 4, u * (kWThreads * 4));
     if (EF) {
-      const TileBuf ob(res + b + u * (kWThreads * 8), kWThreads * 32);
+      const TileBuf ob = row_buf(res + b, valid_of(item), u * (kWThreads * 8), kWThreads * 8);
       ob.store16(as_u32x4(r[0], r[1], r[2], r[3]), threadIdx.x * 32);
       ob.store16(as_u32x4(r[4], r[5], r[6], r[7]), threadIdx.x * 32 + 16);
     }

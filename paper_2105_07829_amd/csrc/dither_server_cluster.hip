@@ -30,7 +30,7 @@ inline DMsgPtrs dmsg_ptrs(const WorkerMsgs &m) {
 // NW > 0: number of workers known at compile time (unrolled); NW == 0: rolled loop.
 template <bool EF, bool LINF, int NW>
 struct DitherServerOp {
-  struct Raw { float4 e[2 * kDSRows]; };
+  struct Raw { u32x4 e[2 * kDSRows]; };
   struct Held { float delta[kCPerThread]; };
   struct Ctx { float nu, s_over_nu; int mode; const float *mag; };
   static constexpr bool kMax = LINF;
@@ -60,12 +60,20 @@ struct DitherServerOp {
     *count = (uint32_t)cdiv(g.part_size(p), kSTile);
   }
 
+  // Elements of the tile that lie inside its partition (fewer than a tile's only at the end of
+  // a shorter last partition).  e~ is read and written through descriptors of that many
+  // elements; the messages are read from their padded records and what they decode to past
+  // the partition's end is cleared, so those elements add nothing to the norm and encode as
+  // zero bits.
+  __device__ uint32_t valid_of(uint32_t item) const {
+    const uint32_t left = g.part_size(part_of(item)) - tile_off(item);
+    return __builtin_amdgcn_readfirstlane(left < (uint32_t)kSTile ? left : (uint32_t)kSTile);
+  }
   __device__ void issue_row(uint32_t item, int u, Raw &raw) const {
     if (!EF) return;
-    const uint64_t b = uniform_off(base(item) + (uint32_t)u * (kSThreads * 8));
-    const float4 *e4 = reinterpret_cast<const float4 *>(res + b) + threadIdx.x * 2;
-    raw.e[2 * u] = e4[0];
-    raw.e[2 * u + 1] = e4[1];
+    const TileBuf eb = row_buf(res + base(item), valid_of(item), u * (kSThreads * 8), kSThreads * 8);
+    raw.e[2 * u] = eb.load16(threadIdx.x * 32, 0);
+    raw.e[2 * u + 1] = eb.load16(threadIdx.x * 32 + 16, 0);
   }
 
   // Decode tables of all workers for partition p: lut[i*16 + nibble].
@@ -121,16 +129,22 @@ struct DitherServerOp {
         add_worker(word, table + i * 16, acc);
       }
     }
+    const uint32_t valid = valid_of(item);
     double sum = 0.0;
     float mx = 0.0f;
 #pragma unroll
     for (int u = 0; u < kDSRows; ++u) {
-      const float e[8] = {raw.e[2 * u].x, raw.e[2 * u].y, raw.e[2 * u].z, raw.e[2 * u].w,
-                          raw.e[2 * u + 1].x, raw.e[2 * u + 1].y, raw.e[2 * u + 1].z, raw.e[2 * u + 1].w};
+      const u32x4 ea = raw.e[2 * u], eb = raw.e[2 * u + 1];
+      const float e[8] = {__uint_as_float(ea.x), __uint_as_float(ea.y), __uint_as_float(ea.z), __uint_as_float(ea.w),
+                          __uint_as_float(eb.x), __uint_as_float(eb.y), __uint_as_float(eb.z), __uint_as_float(eb.w)};
+      // elements of this thread's row segment that exist
+      const uint32_t seg0 = (u * kSThreads + threadIdx.x) * 8;
+      const uint32_t have = valid > seg0 ? valid - seg0 : 0u;
 #pragma unroll
       for (int c = 0; c < 8; ++c) {
         float mean = acc[8 * u + c] * msgs.inv_n;
         float d = EF ? mean + e[c] : mean;
+        d = (uint32_t)c < have ? d : 0.0f;
         h.delta[8 * u + c] = d;
         if (LINF) mx = fmaxf(mx, fabsf(d));
         else sum = fma((double)d, (double)d, sum);
@@ -168,9 +182,9 @@ struct DitherServerOp {
     uint32_t *nibs = reinterpret_cast<uint32_t *>(payload + (uint64_t)p * g.stride + kHeaderBytes);
     (nibs + uniform_off((tile_off(item) + u * (kSThreads * 8)) >> 3))[threadIdx.x] = word;
     if (EF) {
-      float4 *o4 = reinterpret_cast<float4 *>(res + uniform_off(base(item) + (uint32_t)u * (kSThreads * 8))) + threadIdx.x * 2;
-      o4[0] = make_float4(r[0], r[1], r[2], r[3]);
-      o4[1] = make_float4(r[4], r[5], r[6], r[7]);
+      const TileBuf ob = row_buf(res + base(item), valid_of(item), u * (kSThreads * 8), kSThreads * 8);
+      ob.store16(as_u32x4(r[0], r[1], r[2], r[3]), threadIdx.x * 32);
+      ob.store16(as_u32x4(r[4], r[5], r[6], r[7]), threadIdx.x * 32 + 16);
     }
   }
   __device__ void row2(uint32_t item, int u, Held &h, const Ctx &ctx) const {

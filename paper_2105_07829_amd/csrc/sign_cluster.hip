@@ -71,17 +71,24 @@ struct SignWorkerOp {
     *first = p * cg.tiles_per_part;
     *count = (uint32_t)cdiv(g.part_size(p), kWTile);
   }
+  // Elements of the tile that lie inside its partition.  Every tile access goes through a
+  // buffer descriptor of exactly that many elements: loads past it return 0 (q = 0 there:
+  // nothing for the norm, a clear sign bit) and stores past it are dropped.
+  __device__ uint32_t valid_of(uint32_t item) const {
+    const uint32_t left = g.part_size(part_of(item)) - tile_off(item);
+    return __builtin_amdgcn_readfirstlane(left < (uint32_t)kWTile ? left : (uint32_t)kWTile);
+  }
   __device__ uint32_t *bits_of(uint32_t p) const {
     return reinterpret_cast<uint32_t *>(payload + (uint64_t)p * g.stride + kHeaderBytes);
   }
 
   __device__ void issue_first(uint32_t item, int u, Raw &raw) const {
-    const TileBuf gb(grad + base(item), kWTile * sizeof(G));
+    const TileBuf gb(grad + base(item), valid_of(item) * sizeof(G));
     raw.g[u] = tile_load4(gb, threadIdx.x * (4 * sizeof(G)), u * (kWThreads * 4 * sizeof(G)), grad);
   }
   __device__ void issue_second(uint32_t item, int u, Raw &raw) const {
     if (EF) {
-      const TileBuf eb(res + base(item), kWTile * 4);
+      const TileBuf eb(res + base(item), valid_of(item) * 4);
       raw.e[u] = eb.load16(threadIdx.x * 16, u * (kWThreads * 16));
     }
   }
@@ -141,7 +148,7 @@ struct SignWorkerOp {
   __device__ void row2(uint32_t item, int u, Held &h, const Ctx &ctx) const {
     if (!EF) return;
     const float sigma = ctx.sigma;
-    const TileBuf ob(res + base(item) + u * (kWThreads * 4), kWThreads * 16);
+    const TileBuf ob = row_buf(res + base(item), valid_of(item), u * (kWThreads * 4), kWThreads * 4);
     float o[4];
 #pragma unroll
     for (int c = 0; c < 4; ++c) o[c] = h.q[4 * u + c] - (h.q[4 * u + c] < 0.0f ? -sigma : sigma);

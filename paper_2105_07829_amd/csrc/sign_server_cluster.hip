@@ -38,7 +38,7 @@ __device__ inline float pick_sign(uint32_t byte, uint32_t mag) {
 // the byte loads can be scheduled ahead of their use; NW == 0: any number, rolled loop.
 template <bool EF, int NW>
 struct SignServerOp {
-  struct Raw { float4 e[2 * kSRows]; };
+  struct Raw { u32x4 e[2 * kSRows]; };
   struct Held { float delta[kCPerThread]; };
   static constexpr bool kMax = false;
   static constexpr int kRowsPerTile = kSRows;
@@ -67,12 +67,20 @@ struct SignServerOp {
   }
   __device__ static uint32_t lane() { return threadIdx.x & 63; }
 
+  // Elements of the tile that lie inside its partition (fewer than a tile's only at the end of
+  // a shorter last partition).  e~ is read and written through descriptors of that many
+  // elements; the messages are read from their padded records and what they decode to past
+  // the partition's end is cleared, so those elements add nothing to the norm and encode as
+  // zero bits.
+  __device__ uint32_t valid_of(uint32_t item) const {
+    const uint32_t left = g.part_size(part_of(item)) - tile_off(item);
+    return __builtin_amdgcn_readfirstlane(left < (uint32_t)kSTile ? left : (uint32_t)kSTile);
+  }
   __device__ void issue_row(uint32_t item, int u, Raw &raw) const {
     if (!EF) return;
-    const uint64_t b = uniform_off(base(item) + (uint32_t)u * (kSThreads * 8));
-    const float4 *e4 = reinterpret_cast<const float4 *>(res + b) + threadIdx.x * 2;
-    raw.e[2 * u] = e4[0];
-    raw.e[2 * u + 1] = e4[1];
+    const TileBuf eb = row_buf(res + base(item), valid_of(item), u * (kSThreads * 8), kSThreads * 8);
+    raw.e[2 * u] = eb.load16(threadIdx.x * 32, 0);
+    raw.e[2 * u + 1] = eb.load16(threadIdx.x * 32 + 16, 0);
   }
 
   // The byte of worker i's sign bits that covers this thread's 8 elements of each row.
@@ -132,15 +140,21 @@ struct SignServerOp {
         add_worker(byte, sig[i], acc);
       }
     }
+    const uint32_t valid = valid_of(item);
     double sum = 0.0;
 #pragma unroll
     for (int u = 0; u < kSRows; ++u) {
-      const float e[8] = {raw.e[2 * u].x, raw.e[2 * u].y, raw.e[2 * u].z, raw.e[2 * u].w,
-                          raw.e[2 * u + 1].x, raw.e[2 * u + 1].y, raw.e[2 * u + 1].z, raw.e[2 * u + 1].w};
+      const u32x4 ea = raw.e[2 * u], eb = raw.e[2 * u + 1];
+      const float e[8] = {__uint_as_float(ea.x), __uint_as_float(ea.y), __uint_as_float(ea.z), __uint_as_float(ea.w),
+                          __uint_as_float(eb.x), __uint_as_float(eb.y), __uint_as_float(eb.z), __uint_as_float(eb.w)};
+      // elements of this thread's row segment that exist
+      const uint32_t seg0 = (u * kSThreads + threadIdx.x) * 8;
+      const uint32_t have = valid > seg0 ? valid - seg0 : 0u;
 #pragma unroll
       for (int c = 0; c < 8; ++c) {
         float mean = acc[8 * u + c] * msgs.inv_n;
         float d = EF ? mean + e[c] : mean;
+        d = (uint32_t)c < have ? d : 0.0f;
         h.delta[8 * u + c] = d;
         sum += (double)fabsf(d);
       }
@@ -183,13 +197,12 @@ struct SignServerOp {
   __device__ void row2(uint32_t item, int u, Held &h, const Ctx &ctx) const {
     if (!EF) return;
     const float sigma = ctx.sigma;
-    const uint64_t b = uniform_off(base(item) + (uint32_t)u * (kSThreads * 8));
-    float4 *o4 = reinterpret_cast<float4 *>(res + b) + threadIdx.x * 2;
+    const TileBuf ob = row_buf(res + base(item), valid_of(item), u * (kSThreads * 8), kSThreads * 8);
     float r[8];
 #pragma unroll
     for (int c = 0; c < 8; ++c) r[c] = h.delta[8 * u + c] - (h.delta[8 * u + c] < 0.0f ? -sigma : sigma);
-    o4[0] = make_float4(r[0], r[1], r[2], r[3]);
-    o4[1] = make_float4(r[4], r[5], r[6], r[7]);
+    ob.store16(as_u32x4(r[0], r[1], r[2], r[3]), threadIdx.x * 32);
+    ob.store16(as_u32x4(r[4], r[5], r[6], r[7]), threadIdx.x * 32 + 16);
   }
 
 };

@@ -97,8 +97,8 @@ def test_worker_stage(gu, orc, name, dtype, ef):
                 assert gu.close(res_gpu, res_ref, REL), name
 
 
-BIG_PE = 131072                          # two 65536-element register tiles per partition
-BIG_D = 2 * BIG_PE + 70000               # tail partition: one full tile and a ragged one
+BIG_PE = 131072                          # several register-resident tiles per partition (4 worker-side, 16 server-side)
+BIG_D = 2 * BIG_PE + 70000               # tail partition: full tiles and a ragged one
 
 
 @pytest.mark.parametrize("name", sorted(KW))
@@ -172,6 +172,41 @@ def test_server_stage(gu, orc, name, ef, n):
                 assert np.array_equal(res_gpu.view(np.uint32), res_ref.view(np.uint32))
             else:
                 assert gu.close(res_gpu, res_ref, REL), name
+
+
+@pytest.mark.parametrize("name", [k for k in sorted(KW) if base_kind(k) in ("sign", "dither")])
+@pytest.mark.parametrize("ef", [True, False])
+@pytest.mark.parametrize("n", [3, 16])
+def test_server_stage_large_partitions(gu, orc, name, ef, n):
+    """Server stage on partitions that span several tiles of the single-pass kernel, with and
+    without a ragged last partition."""
+    for D in (BIG_D, 2 * BIG_PE, 65536 + 3):
+        kw = dict(KW[name])
+        ins = []
+        for i in range(n):
+            if "stream_id" in kw:
+                kw["stream_id"] = (1 << 32) | i
+            ins.append(gu.both_params(orc, base_kind(name), BIG_PE, **kw))
+        if "stream_id" in kw:
+            kw["stream_id"] = (1 << 32) | (1 << 16)
+        out_o, out_b = gu.both_params(orc, base_kind(name), BIG_PE, **kw)
+        payloads = [orc.compress(ins[i][0], grads(D, np.float32, 100 * i + D), None) for i in range(n)]
+        et = (rng(78 + D).standard_normal(D) * 2e-4).astype(np.float32) if ef else None
+        res_ref = None if et is None else et.copy()
+        pay_ref = orc.server_aggregate([p[0] for p in ins], payloads, out_o, res_ref, D)
+        pay_gpu, res_gpu = gu.gpu_server([p[1] for p in ins], payloads, out_b, et, D)
+
+        def redo(norms):
+            o2, _ = gu.both_params(orc, base_kind(name), BIG_PE, norm_override=norms, **kw)
+            r2 = None if et is None else et.copy()
+            out = orc.server_aggregate([p[0] for p in ins], payloads, o2, r2, D)
+            if r2 is not None:
+                res_ref[:] = r2
+            return out
+
+        compare_payload(gu, orc, name, out_o, pay_gpu, pay_ref, D, BIG_PE, redo)
+        if ef:
+            assert gu.close(res_gpu, res_ref, REL), name
 
 
 @pytest.mark.parametrize("name", sorted(KW))
