@@ -53,30 +53,38 @@ __device__ inline uint64_t uniform_off(uint64_t v) {
 // return 0 and writes past it are dropped by the hardware, which the callers never rely on).
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+// AUX is the cache policy of an access: 0 = default, kNonTemporal = data used once.
+constexpr int kNonTemporal = 2;
 struct TileBuf {
   __amdgpu_buffer_rsrc_t r;
   __device__ TileBuf(const void *base, uint32_t bytes)
       : r(__builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000)) {}
+  template <int AUX = 0>
   __device__ u32x4 load16(uint32_t lane_off, uint32_t row_off) const {
-    return __builtin_amdgcn_raw_buffer_load_b128(r, (int)lane_off, (int)row_off, 0);
+    return __builtin_amdgcn_raw_buffer_load_b128(r, (int)lane_off, (int)row_off, AUX);
   }
+  template <int AUX = 0>
   __device__ u32x2 load8(uint32_t lane_off, uint32_t row_off) const {
-    return __builtin_amdgcn_raw_buffer_load_b64(r, (int)lane_off, (int)row_off, 0);
+    return __builtin_amdgcn_raw_buffer_load_b64(r, (int)lane_off, (int)row_off, AUX);
   }
+  template <int AUX = 0>
   __device__ uint32_t load4(uint32_t lane_off, uint32_t row_off) const {
-    return __builtin_amdgcn_raw_buffer_load_b32(r, (int)lane_off, (int)row_off, 0);
+    return __builtin_amdgcn_raw_buffer_load_b32(r, (int)lane_off, (int)row_off, AUX);
   }
+  template <int AUX = 0>
   __device__ uint32_t load1(uint32_t lane_off, uint32_t row_off) const {
-    return (uint32_t)__builtin_amdgcn_raw_buffer_load_b8(r, (int)lane_off, (int)row_off, 0);
+    return (uint32_t)__builtin_amdgcn_raw_buffer_load_b8(r, (int)lane_off, (int)row_off, AUX);
   }
   // 16-byte stores take no scalar offset: with one, the hardware was seen to pick up a data
   // register that the next instruction overwrites (the compiler only spaces the two apart
   // when the offset field is a constant).  Callers put the row into the descriptor's base.
+  template <int AUX = 0>
   __device__ void store16(u32x4 v, uint32_t lane_off) const {
-    __builtin_amdgcn_raw_buffer_store_b128(v, r, (int)lane_off, 0, 0);
+    __builtin_amdgcn_raw_buffer_store_b128(v, r, (int)lane_off, 0, AUX);
   }
+  template <int AUX = 0>
   __device__ void store4(uint32_t v, uint32_t lane_off, uint32_t row_off) const {
-    __builtin_amdgcn_raw_buffer_store_b32(v, r, (int)lane_off, (int)row_off, 0);
+    __builtin_amdgcn_raw_buffer_store_b32(v, r, (int)lane_off, (int)row_off, AUX);
   }
 };
 // A value every lane loads from the same address, moved to a scalar register inside the

@@ -21,8 +21,8 @@ __device__ inline void widen4(const u32x2 &g, float out[4]) {
 template <class G> struct Vec4Of;
 template <> struct Vec4Of<float> { using type = u32x4; };
 template <> struct Vec4Of<__half> { using type = u32x2; };
-__device__ inline u32x4 tile_load4(const TileBuf &b, uint32_t lane_off, uint32_t row_off, const float *) { return b.load16(lane_off, row_off); }
-__device__ inline u32x2 tile_load4(const TileBuf &b, uint32_t lane_off, uint32_t row_off, const __half *) { return b.load8(lane_off, row_off); }
+__device__ inline u32x4 tile_load4(const TileBuf &b, uint32_t lane_off, uint32_t row_off, const float *) { return b.load16<kNonTemporal>(lane_off, row_off); }
+__device__ inline u32x2 tile_load4(const TileBuf &b, uint32_t lane_off, uint32_t row_off, const __half *) { return b.load8<kNonTemporal>(lane_off, row_off); }
 
 // Sign bits of a row: every lane holds a nibble for its 4 elements; 8 neighbouring lanes are
 // merged into one 32-bit word which lane 8w of the wave ends up holding.
@@ -89,7 +89,7 @@ struct SignWorkerOp {
   __device__ void issue_second(uint32_t item, int u, Raw &raw) const {
     if (EF) {
       const TileBuf eb(res + base(item), valid_of(item) * 4);
-      raw.e[u] = eb.load16(threadIdx.x * 16, u * (kWThreads * 16));
+      raw.e[u] = eb.load16<kNonTemporal>(threadIdx.x * 16, u * (kWThreads * 16));
     }
   }
   __device__ void issue_row(uint32_t item, int u, Raw &raw) const {
@@ -124,7 +124,7 @@ struct SignWorkerOp {
 #pragma unroll
       for (int c = 0; c < 4; ++c) nib |= (h.q[4 * u + c] < 0.0f ? 1u : 0u) << c;
       uint32_t word = merge8(nib);
-      if ((t & 7) == 0) bb.store4(word, (t >> 3) * 4, u * (kWThreads * 4 / 8));
+      if ((t & 7) == 0) bb.store4<kNonTemporal>(word, (t >> 3) * 4, u * (kWThreads * 4 / 8));
     }
   }
 
@@ -152,7 +152,7 @@ struct SignWorkerOp {
     float o[4];
 #pragma unroll
     for (int c = 0; c < 4; ++c) o[c] = h.q[4 * u + c] - (h.q[4 * u + c] < 0.0f ? -sigma : sigma);
-    ob.store16(as_u32x4(o[0], o[1], o[2], o[3]), threadIdx.x * 16);
+    ob.store16<kNonTemporal>(as_u32x4(o[0], o[1], o[2], o[3]), threadIdx.x * 16);
   }
 
 };

@@ -17,6 +17,14 @@ struct SignDec {
     uint32_t w = reinterpret_cast<const uint32_t *>(rec + kHeaderBytes)[j >> 5];
     return ((w >> (j & 31)) & 1u) ? -s : s;
   }
+  // 4 consecutive elements from j (a multiple of 4)
+  __device__ void at4(const Geo &, uint32_t p, uint32_t j, uint32_t, const float *, float out[4]) const {
+    const uint8_t *rec = payload + (uint64_t)p * stride;
+    const float s = *reinterpret_cast<const float *>(rec);
+    const uint32_t nib = rec[kHeaderBytes + (j >> 3)] >> (j & 4);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) out[c] = ((nib >> c) & 1u) ? -s : s;
+  }
 };
 struct DitherDec {
   const uint8_t *payload; uint64_t stride; uint32_t levels;
@@ -33,6 +41,12 @@ struct DitherDec {
     const uint32_t *nibs = reinterpret_cast<const uint32_t *>(payload + (uint64_t)p * stride + kHeaderBytes);
     return lds[(nibs[j >> 3] >> (4 * (j & 7))) & 15u];
   }
+  __device__ void at4(const Geo &, uint32_t p, uint32_t j, uint32_t, const float *lds, float out[4]) const {
+    const uint32_t *nibs = reinterpret_cast<const uint32_t *>(payload + (uint64_t)p * stride + kHeaderBytes);
+    const uint32_t w = nibs[j >> 3] >> (4 * (j & 4));
+#pragma unroll
+    for (int c = 0; c < 4; ++c) out[c] = lds[(w >> (4 * c)) & 15u];
+  }
 };
 struct IdentityDec {
   const uint8_t *payload; uint64_t stride;
@@ -41,12 +55,23 @@ struct IdentityDec {
   __device__ float at(const Geo &, uint32_t p, uint32_t j, const float *) const {
     return reinterpret_cast<const float *>(payload + (uint64_t)p * stride + kHeaderBytes)[j];
   }
+  // the record is padded to a full partition, so the 16 bytes are always inside it
+  __device__ void at4(const Geo &, uint32_t p, uint32_t j, uint32_t, const float *, float out[4]) const {
+    const float4 a = reinterpret_cast<const float4 *>(payload + (uint64_t)p * stride + kHeaderBytes)[j >> 2];
+    out[0] = a.x; out[1] = a.y; out[2] = a.z; out[3] = a.w;
+  }
 };
 struct DenseDec {
   const float *dense;
   static constexpr int kLdsFloats = 1;
   __device__ void begin(uint32_t, float *) const {}
   __device__ float at(const Geo &g, uint32_t p, uint32_t j, const float *) const { return dense[g.part_base(p) + j]; }
+  // `left` = elements of the partition from j on; reads past them return 0
+  __device__ void at4(const Geo &g, uint32_t p, uint32_t j, uint32_t left, const float *, float out[4]) const {
+    const TileBuf b(dense + g.part_base(p) + j, (left < 4u ? left : 4u) * 4);
+    const u32x4 lo = b.load16(0, 0);
+    out[0] = __uint_as_float(lo.x); out[1] = __uint_as_float(lo.y); out[2] = __uint_as_float(lo.z); out[3] = __uint_as_float(lo.w);
+  }
 };
 
 struct OptArgs {
@@ -133,6 +158,57 @@ __global__ __launch_bounds__(kThreads) void update_moments_kernel(Geo g, DEC dec
   }
 }
 
+// ADAM in one pass.  A thread owns 4 consecutive elements per row of 1024, so every 16-byte
+// access of a wave covers whole cache lines (which is what lets the stores be non-temporal);
+// all loads of a tile are requested before the first is used.  x, m and v go through buffer
+// descriptors that end with the partition: reads past it return 0 and stores past it are
+// dropped, so a ragged last tile needs no other care.
+constexpr int kURow = kThreads * 4;
+constexpr int kURows = kTile / kURow;
+template <class DEC>
+__global__ __launch_bounds__(kThreads) void adam_update_kernel(Geo g, DEC dec, float *x, float *m, float *v, OptArgs o) {
+  __shared__ float lds[DEC::kLdsFloats];
+  const uint32_t p = __builtin_amdgcn_readfirstlane(blockIdx.x / g.tiles_per_part);
+  const uint32_t tile = __builtin_amdgcn_readfirstlane(blockIdx.x % g.tiles_per_part);
+  const uint32_t d = g.part_size(p);
+  dec.begin(p, lds);
+  const uint64_t tile_base = g.part_base(p) + (uint64_t)tile * kTile;
+  const uint32_t valid = d - tile * kTile < (uint32_t)kTile ? d - tile * kTile : (uint32_t)kTile;
+  const float omb1 = 1.0f - o.beta1, omb2 = 1.0f - o.beta2;
+  u32x4 xr[kURows], mr[kURows], vr[kURows];
+  float gr[kURows][4];
+#pragma unroll
+  for (int u = 0; u < kURows; ++u) {
+    mr[u] = row_buf(m + tile_base, valid, u * kURow, kURow).load16<kNonTemporal>(threadIdx.x * 16, 0);
+    vr[u] = row_buf(v + tile_base, valid, u * kURow, kURow).load16<kNonTemporal>(threadIdx.x * 16, 0);
+    xr[u] = row_buf(x + tile_base, valid, u * kURow, kURow).load16<kNonTemporal>(threadIdx.x * 16, 0);
+    const uint32_t j = tile * kTile + u * kURow + threadIdx.x * 4;
+    dec.at4(g, p, j, d > j ? d - j : 0u, lds, gr[u]);
+  }
+#pragma unroll
+  for (int u = 0; u < kURows; ++u) {
+    const uint32_t mi[4] = {mr[u].x, mr[u].y, mr[u].z, mr[u].w};
+    const uint32_t vi[4] = {vr[u].x, vr[u].y, vr[u].z, vr[u].w};
+    const uint32_t xi[4] = {xr[u].x, xr[u].y, xr[u].z, xr[u].w};
+    float mo[4], vo[4], xo[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const float gj = gr[u][c];
+      const float mj = o.beta1 * __uint_as_float(mi[c]) + omb1 * gj;
+      const float vj = o.beta2 * __uint_as_float(vi[c]) + omb2 * (gj * gj);
+      const float xj = __uint_as_float(xi[c]);
+      float u_r, u_c;
+      ratios(o, gj, mj, vj, xj, &u_r, &u_c);
+      mo[c] = mj;
+      vo[c] = vj;
+      xo[c] = xj - o.lr * u_r;
+    }
+    row_buf(m + tile_base, valid, u * kURow, kURow).store16<kNonTemporal>(as_u32x4(mo[0], mo[1], mo[2], mo[3]), threadIdx.x * 16);
+    row_buf(v + tile_base, valid, u * kURow, kURow).store16<kNonTemporal>(as_u32x4(vo[0], vo[1], vo[2], vo[3]), threadIdx.x * 16);
+    row_buf(x + tile_base, valid, u * kURow, kURow).store16<kNonTemporal>(as_u32x4(xo[0], xo[1], xo[2], xo[3]), threadIdx.x * 16);
+  }
+}
+
 template <class DEC>
 __global__ __launch_bounds__(kThreads) void lans_apply_kernel(Geo g, DEC dec, float *x, const float *m,
                                                               const float *v, OptArgs o, const double *norms) {
@@ -171,7 +247,7 @@ static hipError_t run_update(const Geo &g, DEC dec, float *x, float *m, float *v
   OptArgs o{opt.lr, opt.beta1, opt.beta2, opt.eps, opt.weight_decay, opt.bias_corr1, opt.bias_corr2,
             opt.phi_lo, opt.phi_hi, opt.block_offsets, opt.n_blocks};
   if (opt.kind == BPC_OPT_ADAM) {
-    update_moments_kernel<DEC, false><<<g.n_tiles, kThreads, 0, stream>>>(g, dec, x, m, v, o, nullptr);
+    adam_update_kernel<DEC><<<g.n_tiles, kThreads, 0, stream>>>(g, dec, x, m, v, o);
     return hipGetLastError();
   }
   uint64_t nb = opt.block_offsets ? opt.n_blocks : g.P;
