@@ -9,6 +9,7 @@ namespace bpc {
 
 struct SignDec {
   const uint8_t *payload; uint64_t stride;
+  __device__ const float *dense_base() const { return nullptr; }
   static constexpr int kLdsFloats = 1;
   __device__ void begin(uint32_t, float *) const {}
   __device__ float at(const Geo &, uint32_t p, uint32_t j, const float *) const {
@@ -18,7 +19,7 @@ struct SignDec {
     return ((w >> (j & 31)) & 1u) ? -s : s;
   }
   // 4 consecutive elements from j (a multiple of 4)
-  __device__ void at4(const Geo &, uint32_t p, uint32_t j, uint32_t, const float *, float out[4]) const {
+  __device__ void at4(const Geo &, uint32_t p, uint32_t j, const TileBuf &, const float *, float out[4]) const {
     const uint8_t *rec = payload + (uint64_t)p * stride;
     const float s = *reinterpret_cast<const float *>(rec);
     const uint32_t nib = rec[kHeaderBytes + (j >> 3)] >> (j & 4);
@@ -28,6 +29,7 @@ struct SignDec {
 };
 struct DitherDec {
   const uint8_t *payload; uint64_t stride; uint32_t levels;
+  __device__ const float *dense_base() const { return nullptr; }
   static constexpr int kLdsFloats = 16;
   __device__ void begin(uint32_t p, float *lds) const {
     if (threadIdx.x < 16) {
@@ -41,7 +43,7 @@ struct DitherDec {
     const uint32_t *nibs = reinterpret_cast<const uint32_t *>(payload + (uint64_t)p * stride + kHeaderBytes);
     return lds[(nibs[j >> 3] >> (4 * (j & 7))) & 15u];
   }
-  __device__ void at4(const Geo &, uint32_t p, uint32_t j, uint32_t, const float *lds, float out[4]) const {
+  __device__ void at4(const Geo &, uint32_t p, uint32_t j, const TileBuf &, const float *lds, float out[4]) const {
     const uint32_t *nibs = reinterpret_cast<const uint32_t *>(payload + (uint64_t)p * stride + kHeaderBytes);
     const uint32_t w = nibs[j >> 3] >> (4 * (j & 4));
 #pragma unroll
@@ -50,26 +52,28 @@ struct DitherDec {
 };
 struct IdentityDec {
   const uint8_t *payload; uint64_t stride;
+  __device__ const float *dense_base() const { return nullptr; }
   static constexpr int kLdsFloats = 1;
   __device__ void begin(uint32_t, float *) const {}
   __device__ float at(const Geo &, uint32_t p, uint32_t j, const float *) const {
     return reinterpret_cast<const float *>(payload + (uint64_t)p * stride + kHeaderBytes)[j];
   }
   // the record is padded to a full partition, so the 16 bytes are always inside it
-  __device__ void at4(const Geo &, uint32_t p, uint32_t j, uint32_t, const float *, float out[4]) const {
+  __device__ void at4(const Geo &, uint32_t p, uint32_t j, const TileBuf &, const float *, float out[4]) const {
     const float4 a = reinterpret_cast<const float4 *>(payload + (uint64_t)p * stride + kHeaderBytes)[j >> 2];
     out[0] = a.x; out[1] = a.y; out[2] = a.z; out[3] = a.w;
   }
 };
 struct DenseDec {
   const float *dense;
+  __device__ const float *dense_base() const { return dense; }
   static constexpr int kLdsFloats = 1;
   __device__ void begin(uint32_t, float *) const {}
   __device__ float at(const Geo &g, uint32_t p, uint32_t j, const float *) const { return dense[g.part_base(p) + j]; }
-  // `left` = elements of the partition from j on; reads past them return 0
-  __device__ void at4(const Geo &g, uint32_t p, uint32_t j, uint32_t left, const float *, float out[4]) const {
-    const TileBuf b(dense + g.part_base(p) + j, (left < 4u ? left : 4u) * 4);
-    const u32x4 lo = b.load16(0, 0);
+  // `row` bounds the row this thread's 4 elements belong to (the same descriptor in every
+  // lane); reads past the partition's end return 0
+  __device__ void at4(const Geo &, uint32_t, uint32_t, const TileBuf &row, const float *, float out[4]) const {
+    const u32x4 lo = row.load16<kNonTemporal>(threadIdx.x * 16, 0);
     out[0] = __uint_as_float(lo.x); out[1] = __uint_as_float(lo.y); out[2] = __uint_as_float(lo.z); out[3] = __uint_as_float(lo.w);
   }
 };
@@ -183,7 +187,7 @@ __global__ __launch_bounds__(kThreads) void adam_update_kernel(Geo g, DEC dec, f
     vr[u] = row_buf(v + tile_base, valid, u * kURow, kURow).load16<kNonTemporal>(threadIdx.x * 16, 0);
     xr[u] = row_buf(x + tile_base, valid, u * kURow, kURow).load16<kNonTemporal>(threadIdx.x * 16, 0);
     const uint32_t j = tile * kTile + u * kURow + threadIdx.x * 4;
-    dec.at4(g, p, j, d > j ? d - j : 0u, lds, gr[u]);
+    dec.at4(g, p, j, row_buf(dec.dense_base() + tile_base, valid, u * kURow, kURow), lds, gr[u]);
   }
 #pragma unroll
   for (int u = 0; u < kURows; ++u) {
