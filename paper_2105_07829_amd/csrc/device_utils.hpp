@@ -108,6 +108,20 @@ __device__ inline u32x4 as_u32x4(float a, float b, float c, float d) {
 __device__ inline float load_grad(const float *g, uint64_t i) { return g[i]; }
 __device__ inline float load_grad(const __half *g, uint64_t i) { return __half2float(g[i]); }
 
+// Inclusive prefix sum over the 64 lanes of a wave with DPP moves: shifts by 1, 2, 4, 8 inside
+// the 16-lane rows (a lane whose source is outside its row adds 0), then lane 15 of rows 0 and
+// 2 broadcast to rows 1 and 3, then lane 31 to rows 2 and 3.
+__device__ inline uint32_t wave_inclusive_scan_u32(uint32_t x) {
+  int v = (int)x;
+  v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, true);   // row_shr:1
+  v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, true);   // row_shr:2
+  v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, true);   // row_shr:4
+  v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, true);   // row_shr:8
+  v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);  // row_bcast:15 into rows 1, 3
+  v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);  // row_bcast:31 into rows 2, 3
+  return (uint32_t)v;
+}
+
 // Sum over the 64 lanes in a fixed butterfly order (same bits on every run).
 __device__ inline double wave_sum(double x) {
 #pragma unroll
