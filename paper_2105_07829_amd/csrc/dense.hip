@@ -55,31 +55,51 @@ hipError_t identity_encode(const Geo &g, const bpc_params_t &, const Source &src
   });
 }
 
-// Element-wise decode of the bit-packed kinds and of the identity record.
-__global__ __launch_bounds__(kThreads) void decode_packed_kernel(Geo g, int kind, uint32_t levels,
-                                                                 const uint8_t *payload, float *out) {
-  const uint32_t p = blockIdx.x / g.tiles_per_part;
-  const uint32_t tile = blockIdx.x % g.tiles_per_part;
+// Decode of the bit-packed kinds and of the identity record.  A thread owns 4 consecutive
+// elements per row of 1024, so the 16-byte stores of a wave cover whole cache lines and can be
+// non-temporal; the output goes through a descriptor that ends with the partition (stores
+// past it are dropped).  The records are padded to a full partition, so reads stay inside.
+template <int KIND>
+__global__ __launch_bounds__(kThreads) void decode_packed_kernel(Geo g, uint32_t levels, const uint8_t *payload, float *out) {
+  constexpr int kRow = kThreads * 4, kRows = kTile / kRow;
+  const uint32_t p = __builtin_amdgcn_readfirstlane(blockIdx.x / g.tiles_per_part);
+  const uint32_t tile = __builtin_amdgcn_readfirstlane(blockIdx.x % g.tiles_per_part);
   const uint32_t d = g.part_size(p);
   const uint8_t *rec = payload + (uint64_t)p * g.stride;
   const float scale = *reinterpret_cast<const float *>(rec);
-  const uint32_t *words = reinterpret_cast<const uint32_t *>(rec + kHeaderBytes);
-  const uint64_t base = g.part_base(p);
+  const uint8_t *body = rec + kHeaderBytes;
+  const uint32_t valid = d - tile * kTile < (uint32_t)kTile ? d - tile * kTile : (uint32_t)kTile;
+  float *tile_out = out + g.part_base(p) + (uint64_t)tile * kTile;
+  float lut[8];   // dithering: the decoded magnitudes (scale * level) / s
+  if (KIND == BPC_DITHER) {
 #pragma unroll
-  for (int c = 0; c < kTile / kThreads; ++c) {
-    uint32_t j = tile * kTile + c * kThreads + threadIdx.x;
-    if (j >= d) continue;
-    float v;
-    if (kind == BPC_SIGN) {
-      v = ((words[j >> 5] >> (j & 31)) & 1u) ? -scale : scale;
-    } else if (kind == BPC_DITHER) {
-      uint32_t nib = (words[j >> 3] >> (4 * (j & 7))) & 15u;
-      float mag = (scale * (float)(nib & 7u)) / (float)levels;
-      v = (nib & 8u) ? -mag : mag;
+    for (int l = 0; l < 8; ++l) lut[l] = (scale * (float)l) / (float)levels;
+  }
+#pragma unroll
+  for (int u = 0; u < kRows; ++u) {
+    const uint32_t j = tile * kTile + u * kRow + threadIdx.x * 4;   // partition-local, a multiple of 4
+    float v[4];
+    if (KIND == BPC_SIGN) {
+      const uint32_t nib = body[j >> 3] >> (j & 4);
+#pragma unroll
+      for (int c = 0; c < 4; ++c) v[c] = ((nib >> c) & 1u) ? -scale : scale;
+    } else if (KIND == BPC_DITHER) {
+      const uint32_t half = reinterpret_cast<const uint16_t *>(body)[j >> 2];
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const uint32_t nib = (half >> (4 * c)) & 15u;
+        const uint32_t l = nib & 7u;
+        // select from the eight values held in registers (no indexed array)
+        float mag = lut[0];
+#pragma unroll
+        for (int q = 1; q < 8; ++q) mag = l == (uint32_t)q ? lut[q] : mag;
+        v[c] = (nib & 8u) ? -mag : mag;
+      }
     } else {
-      v = __uint_as_float(words[j]);
+      const float4 q = reinterpret_cast<const float4 *>(body)[j >> 2];
+      v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
     }
-    out[base + j] = v;
+    row_buf(tile_out, valid, u * kRow, kRow).store16<kNonTemporal>(as_u32x4(v[0], v[1], v[2], v[3]), threadIdx.x * 16);
   }
 }
 
@@ -136,7 +156,9 @@ hipError_t decode_dense(const Geo &g, const bpc_params_t &prm, const uint8_t *pa
     if (e != hipSuccess) return e;
     return scatter_add_sparse(g, prm, payload, out, stream);
   }
-  decode_packed_kernel<<<g.n_tiles, kThreads, 0, stream>>>(g, prm.kind, prm.levels, payload, out);
+  if (prm.kind == BPC_SIGN) decode_packed_kernel<BPC_SIGN><<<g.n_tiles, kThreads, 0, stream>>>(g, prm.levels, payload, out);
+  else if (prm.kind == BPC_DITHER) decode_packed_kernel<BPC_DITHER><<<g.n_tiles, kThreads, 0, stream>>>(g, prm.levels, payload, out);
+  else decode_packed_kernel<BPC_IDENTITY><<<g.n_tiles, kThreads, 0, stream>>>(g, prm.levels, payload, out);
   return hipGetLastError();
 }
 
