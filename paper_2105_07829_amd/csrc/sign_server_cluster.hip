@@ -42,7 +42,9 @@ struct SignServerOp {
   struct Held { float delta[kCPerThread]; };
   static constexpr bool kMax = false;
   static constexpr int kRowsPerTile = kSRows;
-  static constexpr int kTableFloats = kMaxWorkers;
+  // LDS: the n scales, then (NW > 0) the tile's sign bits of every worker, 1 KiB each
+  static constexpr int kBitsPerWorker = kSTile / 8;   // bytes
+  static constexpr int kTableFloats = kMaxWorkers + (NW > 0 ? NW * kBitsPerWorker / 4 : 0);
   static constexpr int kThreads = kSThreads;
   static constexpr bool kPersistent = false;
   static constexpr size_t kMaxDynLds = 0;
@@ -112,28 +114,46 @@ struct SignServerOp {
 
   __device__ double phase1(uint32_t item, Raw &raw, Held &h, float *sig) const {
     const uint32_t p = part_of(item);
-    // the tile's own e~ loads go out first and land while the worker sums are formed
+    // everything the tile needs is requested in one go: its own e~, the n scales and (NW > 0)
+    // the tile's sign bits of every worker
 #pragma unroll
     for (int u = 0; u < kSRows; ++u) issue_row(item, u, raw);
-    __syncthreads();
-    if ((int)threadIdx.x < msgs.n)
-      sig[threadIdx.x] = *reinterpret_cast<const float *>(msgs.ptr[threadIdx.x] + (uint64_t)p * g.stride);
-    __syncthreads();
     float acc[kCPerThread];
 #pragma unroll
     for (int k = 0; k < kCPerThread; ++k) acc[k] = 0.0f;
+    float my_sigma = 0.0f;
+    if ((int)threadIdx.x < msgs.n)
+      my_sigma = *reinterpret_cast<const float *>(msgs.ptr[threadIdx.x] + (uint64_t)p * g.stride);
     if (NW > 0) {
-      // groups of 8 workers: 32 byte loads in flight, consumed in order as they land
-      constexpr int kGroup = NW == 0 ? 1 : NW < 4 ? NW : 4;
+      // The bits come in with one 16-byte load per 128 elements and worker (wave w fetches
+      // workers w, w+4, ...: one round trip for everything instead of one per group of byte
+      // loads) and are handed out through LDS.
+      uint8_t *staged = reinterpret_cast<uint8_t *>(sig + kMaxWorkers);
+      const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+      const uint64_t rec_off = uniform_off((uint64_t)p * g.stride + kHeaderBytes + (tile_off(item) >> 3));
+      u32x4 fetched[NW > 0 ? (NW + 3) / 4 : 1];
 #pragma unroll
-      for (int i0 = 0; i0 < NW; i0 += kGroup) {
-        uint32_t byte[kGroup][kSRows];
+      for (int i = 0; i < NW; ++i)
+        if ((uint32_t)(i & 3) == wave)
+          fetched[i >> 2] = reinterpret_cast<const u32x4 *>(msgs.ptr[i] + rec_off)[lane];
+      __syncthreads();   // the LDS scratch may still be in use by the caller
+      if ((int)threadIdx.x < msgs.n) sig[threadIdx.x] = my_sigma;
 #pragma unroll
-        for (int k = 0; k < kGroup; ++k) load_bytes(item, i0 + k, byte[k]);
+      for (int i = 0; i < NW; ++i)
+        if ((uint32_t)(i & 3) == wave)
+          reinterpret_cast<u32x4 *>(staged + i * kBitsPerWorker)[lane] = fetched[i >> 2];
+      __syncthreads();
 #pragma unroll
-        for (int k = 0; k < kGroup; ++k) add_worker(byte[k], sig[i0 + k], acc);
+      for (int i = 0; i < NW; ++i) {
+        uint32_t byte[kSRows];
+#pragma unroll
+        for (int u = 0; u < kSRows; ++u) byte[u] = staged[i * kBitsPerWorker + u * kSThreads + threadIdx.x];
+        add_worker(byte, sig[i], acc);
       }
     } else {
+      __syncthreads();
+      if ((int)threadIdx.x < msgs.n) sig[threadIdx.x] = my_sigma;
+      __syncthreads();
       for (int i = 0; i < msgs.n; ++i) {
         uint32_t byte[kSRows];
         load_bytes(item, i, byte);

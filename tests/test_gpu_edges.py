@@ -1,0 +1,159 @@
+"""GPU parity on the degenerate inputs of the method: empty gradients, all-zero and constant
+vectors (zero scale / norm, top-k ties inside and across tiles), values so small that s/nu
+overflows, the largest number of workers the server accepts.  Same bars as test_gpu_parity:
+bits, indices and draws exact; floating-point values to 1e-6 relative."""
+import numpy as np
+import pytest
+
+import fmt
+
+pytestmark = pytest.mark.gpu
+
+REL = 1e-6
+PE = 8192          # one tile of the single-pass server kernels per partition
+BIG_PE = 131072    # several tiles per partition
+
+
+@pytest.fixture(scope="module")
+def gu():
+    import torch
+    assert torch.cuda.is_available()
+    import gpu_util
+    gpu_util.bpc.lib()
+    return gpu_util
+
+
+KW = {
+    "sign": {},
+    "topk": dict(k_ratio=0.01),
+    "randk": dict(k_ratio=0.02, value_scale=1.0, seed=11, stream_id=(2 << 32) | 5),
+    "dither": dict(levels=4, seed=0xFEED, stream_id=(7 << 32) | 1),
+    "identity": {},
+}
+
+
+def defined_equal(kind, pay_a, pay_b, po, orc, D, pe, kw):
+    strd = orc.partition_stride(po)
+    k_cap = fmt.k_of(kw.get("k_ratio", 0.01), pe) if kind in ("topk", "randk") else 0
+    for p, d in enumerate(fmt.part_sizes(D, pe)):
+        k = fmt.k_of(kw.get("k_ratio", 0.01), d) if k_cap else 0
+        ra, rb = fmt.record(pay_a, p, strd), fmt.record(pay_b, p, strd)
+        for lo, hi in fmt.defined_bytes(kind, d, k, k_cap):
+            if not np.array_equal(ra[lo:hi], rb[lo:hi]):
+                return False
+    return True
+
+
+@pytest.mark.parametrize("kind", sorted(KW))
+def test_empty_gradient_is_a_no_op(gu, orc, kind):
+    import torch
+    bpc = gu.bpc
+    _, pb = gu.both_params(orc, kind, PE, **KW[kind])
+    g = torch.empty(0, dtype=torch.float32, device=gu.DEV)
+    guard = torch.full((64,), 0x5A, dtype=torch.uint8, device=gu.DEV)
+    ws = torch.zeros(256, dtype=torch.uint8, device=gu.DEV)
+    bpc.bpc_compress(pb, g, None, guard, ws)
+    bpc.bpc_decompress(pb, guard, g)
+    bpc.bpc_server_aggregate([pb], [guard], pb, None, 0, guard, ws)
+    bpc.bpc_adaptive_update(pb, guard, g, g, g, bpc.make_opt(bpc.OPT_ADAM, 1e-3, 0.9, 0.999, 1e-8, 0.0, 1), ws)
+    torch.cuda.synchronize()
+    assert bool((guard == 0x5A).all())
+
+
+@pytest.mark.parametrize("kind", sorted(KW))
+@pytest.mark.parametrize("pe", [PE, BIG_PE])
+def test_all_zero_vectors(gu, orc, kind, pe):
+    """sigma = 0 / nu = 0 / every key ties at 0: zero scale, level 0 everywhere, the k lowest
+    indices for top-k; residuals stay zero."""
+    D = 2 * pe + 4099
+    po, pb = gu.both_params(orc, kind, pe, **KW[kind])
+    g = np.zeros(D, np.float32)
+    g[5] = -0.0                       # a negative zero is not "less than zero"
+    res_ref = np.zeros(D, np.float32)
+    pay_ref = orc.compress(po, g, res_ref)
+    pay_gpu, res_gpu = gu.gpu_compress(pb, g, np.zeros(D, np.float32))
+    assert defined_equal(kind, pay_gpu, pay_ref, po, orc, D, pe, KW[kind])
+    assert np.array_equal(res_gpu.view(np.uint32) & 0x7fffffff, res_ref.view(np.uint32) & 0x7fffffff)
+    out = gu.gpu_decompress(pb, pay_gpu, D)
+    assert np.array_equal(out, orc.decompress(po, pay_ref, D))
+
+
+@pytest.mark.parametrize("pe", [PE, BIG_PE])
+@pytest.mark.parametrize("dtype", [np.float32, np.float16])
+def test_topk_ties_take_the_lowest_indices(gu, orc, pe, dtype):
+    """Every magnitude equal (signs mixed): the kept set is decided by index alone, inside a
+    tile, across the tiles of a partition and in a ragged last partition."""
+    D = 2 * pe + 4099
+    po, pb = gu.both_params(orc, "topk", pe, k_ratio=0.013)
+    rs = np.random.default_rng(5)
+    g = (np.where(rs.random(D) < 0.5, -1.0, 1.0) * 0.25).astype(dtype)
+    # a handful of larger entries late in each partition, so the ties fill the rest of k
+    g[pe - 7] = 3.0
+    g[2 * pe - 1] = -2.0
+    g[D - 1] = 5.0
+    e = np.zeros(D, np.float32)
+    res_ref = e.copy()
+    pay_ref = orc.compress(po, g, res_ref)
+    pay_gpu, res_gpu = gu.gpu_compress(pb, g, e.copy())
+    assert defined_equal("topk", pay_gpu, pay_ref, po, orc, D, pe, dict(k_ratio=0.013))
+    assert np.array_equal(res_gpu.view(np.uint32), res_ref.view(np.uint32))
+
+
+@pytest.mark.parametrize("norm", [0, 1])
+def test_dither_tiny_values_divide_per_element(gu, orc, norm):
+    """nu so small that s/nu is not finite: the quantiser divides per element instead."""
+    D = BIG_PE + 777
+    kw = dict(levels=7, norm=norm, seed=3, stream_id=4)
+    po, pb = gu.both_params(orc, "dither", BIG_PE, **kw)
+    rs = np.random.default_rng(8)
+    g = (rs.standard_normal(D) * 1e-42).astype(np.float32)      # subnormal magnitudes
+    e = (rs.standard_normal(D) * 1e-43).astype(np.float32)
+    res_ref = e.copy()
+    pay_ref = orc.compress(po, g, res_ref)
+    pay_gpu, res_gpu = gu.gpu_compress(pb, g, e.copy())
+    strd = orc.partition_stride(po)
+    for p in range(len(fmt.part_sizes(D, BIG_PE))):
+        assert fmt.header_f32(fmt.record(pay_gpu, p, strd)) == fmt.header_f32(fmt.record(pay_ref, p, strd))
+    assert defined_equal("dither", pay_gpu, pay_ref, po, orc, D, BIG_PE, kw)
+    assert np.array_equal(res_gpu.view(np.uint32), res_ref.view(np.uint32))
+
+
+@pytest.mark.parametrize("kind", ["sign", "dither", "topk", "randk", "identity"])
+def test_server_with_the_most_workers(gu, orc, kind):
+    n = gu.bpc.MAX_WORKERS
+    D = PE + 1234
+    kw = dict(KW[kind])
+    ins = []
+    for i in range(n):
+        if "stream_id" in kw:
+            kw["stream_id"] = (1 << 32) | i
+        ins.append(gu.both_params(orc, kind, PE, **kw))
+    if "stream_id" in kw:
+        kw["stream_id"] = (1 << 32) | (1 << 16)
+    out_o, out_b = gu.both_params(orc, kind, PE, **kw)
+    rs = np.random.default_rng(21)
+    payloads = [orc.compress(ins[i][0], (rs.standard_normal(D) * 1e-3).astype(np.float32), None) for i in range(n)]
+    et = (rs.standard_normal(D) * 2e-4).astype(np.float32)
+    res_ref = et.copy()
+    pay_ref = orc.server_aggregate([p[0] for p in ins], payloads, out_o, res_ref, D)
+    pay_gpu, res_gpu = gu.gpu_server([p[1] for p in ins], payloads, out_b, et.copy(), D)
+    strd = orc.partition_stride(out_o)
+    if kind in ("sign", "dither"):
+        # scale within tolerance; bits on equal terms when it matches exactly
+        for p in range(len(fmt.part_sizes(D, PE))):
+            hg, ho = fmt.header_f32(fmt.record(pay_gpu, p, strd)), fmt.header_f32(fmt.record(pay_ref, p, strd))
+            assert abs(float(hg) - float(ho)) <= REL * abs(float(ho))
+        if all(fmt.header_f32(fmt.record(pay_gpu, p, strd)) == fmt.header_f32(fmt.record(pay_ref, p, strd))
+               for p in range(len(fmt.part_sizes(D, PE)))):
+            assert defined_equal(kind, pay_gpu, pay_ref, out_o, orc, D, PE, kw)
+    elif kind == "randk":
+        for p in range(len(fmt.part_sizes(D, PE))):
+            kg, vg = fmt.randk_values(fmt.record(pay_gpu, p, strd))
+            kr, vr = fmt.randk_values(fmt.record(pay_ref, p, strd))
+            assert kg == kr and gu.close(vg, vr, REL)
+    else:
+        assert defined_equal(kind, pay_gpu, pay_ref, out_o, orc, D, PE, kw)
+    if kind in ("identity", "topk"):
+        assert np.array_equal(res_gpu.view(np.uint32), res_ref.view(np.uint32))
+    else:
+        assert gu.close(res_gpu, res_ref, REL)
