@@ -75,7 +75,7 @@ static int params_ok(const orc_params *p) {
   switch (p->kind) {
     case ORC_IDENTITY: case ORC_SIGN: return 1;
     case ORC_TOPK: case ORC_RANDK: return p->k_ratio > 0.0 && p->k_ratio <= 1.0;
-    case ORC_DITHER:
+    case ORC_DITHER: case ORC_NATDITHER:
       return p->levels >= 1 && p->levels <= 7 && (p->norm == ORC_NORM_L2 || p->norm == ORC_NORM_LINF);
     default: return 0;
   }
@@ -97,7 +97,7 @@ size_t orc_partition_stride(const orc_params *p) {
   switch (p->kind) {
     case ORC_IDENTITY: words = ru4(d); break;
     case ORC_SIGN:     words = ru4((d + 31) / 32); break;
-    case ORC_DITHER:   words = ru4((d + 7) / 8); break;
+    case ORC_DITHER: case ORC_NATDITHER: words = ru4((d + 7) / 8); break;
     case ORC_TOPK:     words = 2 * ru4(orc_partition_k(p, d)); break;
     case ORC_RANDK:    words = ru4(orc_partition_k(p, d)); break;
   }
@@ -275,6 +275,71 @@ static void decode_dither(const orc_params *p, const unsigned char *rec, uint64_
   }
 }
 
+/* Natural dithering, the power-of-two sibling of the quantiser above that the paper lists
+ * among its compressors (Section 5, "natural dithering"): the levels l = 1..s stand for the
+ * magnitudes nu * 2^(l-s), level 0 for zero, and |q_j| is rounded to one of its two
+ * neighbouring levels at random so that the expectation is |q_j|.
+ * With y = |q_j| * 2^(s-1) / nu (levels sit at y = 0, 1, 2, 4, ..., 2^(s-1)):
+ *   y < 1        : lower level 0, upper level 1, P(up) = y
+ *   2^e <= y     : lower level e+1, P(up) = y / 2^e - 1 (the fraction bits of y, exact)
+ * Same record as linear dithering: norm, then one nibble (sign, level) per element. */
+static void encode_natdither(const orc_params *p, uint64_t part_no, const float *q, uint64_t d,
+                             const float *nu_given, unsigned char *rec) {
+  float nu;
+  if (nu_given) {
+    nu = *nu_given;
+  } else if (p->norm == ORC_NORM_L2) {
+    double ss = 0.0;
+    for (uint64_t j = 0; j < d; ++j) ss += (double)q[j] * (double)q[j];
+    nu = (float)sqrt(ss);
+  } else {
+    nu = 0.0f;
+    for (uint64_t j = 0; j < d; ++j) if (fabsf(q[j]) > nu) nu = fabsf(q[j]);
+  }
+  uint64_t words = ru4((d + 7) / 8);
+  put_f32(rec, 0, nu);
+  put_u32(rec, 1, 0); put_u32(rec, 2, 0); put_u32(rec, 3, 0);
+  for (uint64_t w = 0; w < words; ++w) put_u32(rec, 4 + w, 0);
+  if (!(nu > 0.0f)) return;
+  unsigned s = p->levels;
+  float top = (float)(1u << (s - 1));        /* y of the highest level */
+  /* the quotient is formed once per partition; per element only if it overflows */
+  float top_over_nu = top / nu;
+  for (uint64_t j = 0; j < d; ++j) {
+    float y = isfinite(top_over_nu) ? fabsf(q[j]) * top_over_nu : (fabsf(q[j]) * top) / nu;
+    unsigned lower;
+    float up;
+    if (y < 1.0f) {
+      lower = 0;
+      up = y;
+    } else {
+      uint32_t bits = float_bits(y);
+      lower = (unsigned)(bits >> 23) - 127u + 1u;          /* floor(log2 y) + 1 */
+      uint32_t frac = (bits & 0x007fffffu) | 0x3f800000u;  /* y / 2^floor(log2 y), in [1, 2) */
+      float m; memcpy(&m, &frac, 4);
+      up = m - 1.0f;
+    }
+    float u = (float)(draw_word(p, part_no, j) >> 8) * 0x1p-24f;
+    unsigned level = lower + (u < up ? 1u : 0u);
+    if (level > s) level = s;
+    uint32_t nibble = (q[j] < 0.0f ? 8u : 0u) | level;
+    uint32_t w = get_u32(rec, 4 + j / 8);
+    w |= nibble << (4 * (j % 8));
+    put_u32(rec, 4 + j / 8, w);
+  }
+}
+
+static void decode_natdither(const orc_params *p, const unsigned char *rec, uint64_t d, float *out) {
+  float nu = get_f32(rec, 0);
+  float top = (float)(1u << (p->levels - 1));
+  for (uint64_t j = 0; j < d; ++j) {
+    uint32_t nibble = (get_u32(rec, 4 + j / 8) >> (4 * (j % 8))) & 0xfu;
+    unsigned level = nibble & 7u;
+    float mag = level == 0 ? 0.0f : (nu * (float)(1u << (level - 1))) / top;
+    out[j] = (nibble & 8u) ? -mag : mag;
+  }
+}
+
 static void encode_identity(const float *q, uint64_t d, unsigned char *rec) {
   put_u32(rec, 0, 0); put_u32(rec, 1, 0); put_u32(rec, 2, 0); put_u32(rec, 3, 0);
   for (uint64_t j = 0; j < d; ++j) put_f32(rec, 4 + j, q[j]);
@@ -291,6 +356,7 @@ void orc_encode_partition(const orc_params *p, uint64_t part_no, const float *no
     case ORC_TOPK:     encode_topk(p, q, d, rec); break;
     case ORC_RANDK:    encode_randk(p, part_no, q, d, rec); break;
     case ORC_DITHER:   encode_dither(p, part_no, q, d, norm_override1, rec); break;
+    case ORC_NATDITHER: encode_natdither(p, part_no, q, d, norm_override1, rec); break;
   }
 }
 
@@ -302,6 +368,7 @@ void orc_decode_partition(const orc_params *p, uint64_t part_no, const unsigned 
     case ORC_TOPK:     decode_topk(p, rec, d, out); break;
     case ORC_RANDK:    decode_randk(p, part_no, rec, d, out); break;
     case ORC_DITHER:   decode_dither(p, rec, d, out); break;
+    case ORC_NATDITHER: decode_natdither(p, rec, d, out); break;
   }
 }
 

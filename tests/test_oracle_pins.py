@@ -289,6 +289,84 @@ def test_dither_uses_one_draw_per_element_in_index_order(orc):
         assert lvl[j] == exp
 
 
+# ---------------------------------------------------------------- natural dithering
+@pytest.mark.parametrize("norm", ["l2", "linf"])
+def test_natural_dither_unbiased_on_power_of_two_levels(orc, norm):
+    """Decoded magnitudes are 0 or nu * 2^(l-s); each element lands on one of the two levels
+    that bracket it; the mean over many seeds is the input (Definition 1: E[C(x)] = x)."""
+    d, s, trials = 48, 4, 12000
+    x = rng(15).standard_normal(d).astype(np.float32)
+    x[7] *= np.float32(0.01)                  # one element below the smallest level
+    nm = orc.NORM_L2 if norm == "l2" else orc.NORM_LINF
+    nu_ref = np.float32(np.sqrt((x.astype(np.float64) ** 2).sum())) if norm == "l2" else np.abs(x).max()
+    grid = np.array([0.0] + [float(nu_ref) * 2.0 ** (l - s) for l in range(1, s + 1)])
+    acc = np.zeros(d)
+    acc2 = np.zeros(d)
+    ax = np.abs(x.astype(np.float64))
+    lo_ref = np.array([grid[grid <= a * (1 + 1e-7)].max() for a in ax])
+    hi_ref = np.array([grid[grid >= a * (1 - 1e-7)].min() for a in ax])
+    for t in range(trials):
+        p = orc.make_params(orc.NATDITHER, PE, levels=s, norm=nm, seed=t, stream_id=77)
+        rec = orc.encode_partition(p, 0, x)
+        nu, sgn, lvl, _ = fmt.dither_nibbles(rec, d)
+        assert nu == nu_ref and lvl.max() <= s
+        assert np.array_equal(sgn, x < 0)
+        dec = orc.decode_partition(p, 0, rec, d).astype(np.float64)
+        mags = np.abs(dec)
+        assert np.all(np.isin(mags, grid))                     # exact: scaling by powers of two
+        assert np.all((mags == lo_ref) | (mags == hi_ref))
+        acc += dec
+        acc2 += dec * dec
+    mean = acc / trials
+    se = np.sqrt(np.maximum(acc2 / trials - mean ** 2, 1e-30) / trials)
+    assert np.all(np.abs(mean - x) <= 4.5 * se + 1e-6)
+    # both neighbours of an interior element do occur
+    assert np.all((acc2 / trials - mean ** 2 > 0) | np.isin(ax, grid))
+
+
+def test_natural_dither_exact_on_levels_and_equals_linear_for_one_level(orc):
+    """Inputs that sit on a level are sent as they are; with s = 1 the levels are {0, nu} for
+    both quantisers, so the two must produce the same bytes from the same draws."""
+    s = 5
+    lv = np.array([0, 1, 2, 3, 4, 5, 5, 3, 1, 0, 2], dtype=np.int64)
+    sg = np.array([1, -1, 1, -1, 1, -1, 1, 1, -1, 1, -1], dtype=np.float32)
+    mag = np.where(lv == 0, 0.0, 2.0 ** (lv - s)).astype(np.float32)       # nu = 1 (max norm)
+    x = sg * mag
+    for seed in range(20):
+        p = orc.make_params(orc.NATDITHER, PE, levels=s, norm=orc.NORM_LINF, seed=seed)
+        rec = orc.encode_partition(p, 0, x)
+        nu, sgn, lvl, _ = fmt.dither_nibbles(rec, x.size)
+        assert nu == 1.0 and np.array_equal(lvl, lv.astype(np.uint8))
+        assert np.array_equal(orc.decode_partition(p, 0, rec, x.size), x)
+    y = rng(19).standard_normal(500).astype(np.float32)
+    for norm in (orc.NORM_L2, orc.NORM_LINF):
+        pn = orc.make_params(orc.NATDITHER, PE, levels=1, norm=norm, seed=6, stream_id=3)
+        pl = orc.make_params(orc.DITHER, PE, levels=1, norm=norm, seed=6, stream_id=3)
+        rn, rl = orc.encode_partition(pn, 2, y), orc.encode_partition(pl, 2, y)
+        assert np.array_equal(rn[:16 + 4 * ((y.size + 7) // 8)], rl[:16 + 4 * ((y.size + 7) // 8)])
+        assert np.array_equal(orc.decode_partition(pn, 2, rn, y.size), orc.decode_partition(pl, 2, rl, y.size))
+
+
+def test_natural_dither_probability_is_the_distance_to_the_lower_level(orc):
+    """For y = |q| 2^(s-1)/nu between 2^e and 2^(e+1) the upper level is taken with probability
+    (y - 2^e)/2^e; below the first level with probability y.  Checked as frequencies."""
+    s = 3                                     # levels at y = 0, 1, 2, 4 with nu = 1
+    ys = np.array([0.25, 0.8, 1.0, 1.5, 2.0, 3.0, 3.9], dtype=np.float64)
+    p_up = np.array([0.25, 0.8, 0.0, 0.5, 0.0, 0.5, 0.95])
+    lower = np.array([0, 0, 1, 1, 2, 2, 2])
+    x = (ys / 4.0).astype(np.float32)
+    x = np.concatenate([x, [np.float32(1.0)]])            # fixes the max norm at 1
+    trials = 20000
+    ups = np.zeros(ys.size)
+    for t in range(trials):
+        p = orc.make_params(orc.NATDITHER, PE, levels=s, norm=orc.NORM_LINF, seed=1000 + t, stream_id=5)
+        _, _, lvl, _ = fmt.dither_nibbles(orc.encode_partition(p, 0, x), x.size)
+        assert np.all((lvl[:-1] == lower) | (lvl[:-1] == lower + 1)) and lvl[-1] == s
+        ups += lvl[:-1] == lower + 1
+    freq = ups / trials
+    assert np.all(np.abs(freq - p_up) <= 4.5 * np.sqrt(np.maximum(p_up * (1 - p_up), 1e-12) / trials) + 1e-12)
+
+
 def test_zero_vector_encodes_to_zero(orc):
     z = np.zeros(100, dtype=np.float32)
     for kind in (orc.SIGN, orc.DITHER, orc.TOPK, orc.RANDK, orc.IDENTITY):
