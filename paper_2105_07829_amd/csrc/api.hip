@@ -105,7 +105,7 @@ bpc_status_t bpc_server_aggregate(const bpc_params_t *in, const void *const *pay
     if (in[i].kind != out->kind || in[i].part_elems != out->part_elems) return BPC_ERR_INVALID_ARG;
     if ((out->kind == BPC_TOPK || out->kind == BPC_RANDK) && in[i].k_ratio != out->k_ratio)
       return BPC_ERR_INVALID_ARG;
-    if (out->kind == BPC_DITHER && in[i].levels != out->levels) return BPC_ERR_INVALID_ARG;
+    if ((out->kind == BPC_DITHER || out->kind == BPC_NATDITHER) && in[i].levels != out->levels) return BPC_ERR_INVALID_ARG;
   }
   if (D == 0) return BPC_OK;
   if (!payloads || !out_payload) return BPC_ERR_INVALID_ARG;

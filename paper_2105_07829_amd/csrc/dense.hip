@@ -60,7 +60,7 @@ hipError_t identity_encode(const Geo &g, const bpc_params_t &, const Source &src
 // non-temporal; the output goes through a descriptor that ends with the partition (stores
 // past it are dropped).  The records are padded to a full partition, so reads stay inside.
 template <int KIND>
-__global__ __launch_bounds__(kThreads) void decode_packed_kernel(Geo g, uint32_t levels, const uint8_t *payload, float *out) {
+__global__ __launch_bounds__(kThreads) void decode_packed_kernel(Geo g, uint32_t levels, bool natural, const uint8_t *payload, float *out) {
   constexpr int kRow = kThreads * 4, kRows = kTile / kRow;
   const uint32_t p = __builtin_amdgcn_readfirstlane(blockIdx.x / g.tiles_per_part);
   const uint32_t tile = __builtin_amdgcn_readfirstlane(blockIdx.x % g.tiles_per_part);
@@ -70,10 +70,10 @@ __global__ __launch_bounds__(kThreads) void decode_packed_kernel(Geo g, uint32_t
   const uint8_t *body = rec + kHeaderBytes;
   const uint32_t valid = d - tile * kTile < (uint32_t)kTile ? d - tile * kTile : (uint32_t)kTile;
   float *tile_out = out + g.part_base(p) + (uint64_t)tile * kTile;
-  float lut[8];   // dithering: the decoded magnitudes (scale * level) / s
+  float lut[8];   // dithering: the decoded magnitudes of the levels
   if (KIND == BPC_DITHER) {
 #pragma unroll
-    for (int l = 0; l < 8; ++l) lut[l] = (scale * (float)l) / (float)levels;
+    for (int l = 0; l < 8; ++l) lut[l] = (uint32_t)l <= levels ? dither_mag(scale, l, levels, natural) : 0.0f;
   }
 #pragma unroll
   for (int u = 0; u < kRows; ++u) {
@@ -156,9 +156,11 @@ hipError_t decode_dense(const Geo &g, const bpc_params_t &prm, const uint8_t *pa
     if (e != hipSuccess) return e;
     return scatter_add_sparse(g, prm, payload, out, stream);
   }
-  if (prm.kind == BPC_SIGN) decode_packed_kernel<BPC_SIGN><<<g.n_tiles, kThreads, 0, stream>>>(g, prm.levels, payload, out);
-  else if (prm.kind == BPC_DITHER) decode_packed_kernel<BPC_DITHER><<<g.n_tiles, kThreads, 0, stream>>>(g, prm.levels, payload, out);
-  else decode_packed_kernel<BPC_IDENTITY><<<g.n_tiles, kThreads, 0, stream>>>(g, prm.levels, payload, out);
+  const bool natural = prm.kind == BPC_NATDITHER;
+  if (prm.kind == BPC_SIGN) decode_packed_kernel<BPC_SIGN><<<g.n_tiles, kThreads, 0, stream>>>(g, prm.levels, false, payload, out);
+  else if (prm.kind == BPC_DITHER || natural)
+    decode_packed_kernel<BPC_DITHER><<<g.n_tiles, kThreads, 0, stream>>>(g, prm.levels, natural, payload, out);
+  else decode_packed_kernel<BPC_IDENTITY><<<g.n_tiles, kThreads, 0, stream>>>(g, prm.levels, false, payload, out);
   return hipGetLastError();
 }
 

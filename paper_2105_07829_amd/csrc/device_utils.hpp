@@ -108,6 +108,15 @@ __device__ inline u32x4 as_u32x4(float a, float b, float c, float d) {
 __device__ inline float load_grad(const float *g, uint64_t i) { return g[i]; }
 __device__ inline float load_grad(const __half *g, uint64_t i) { return __half2float(g[i]); }
 
+// The two dithering level maps.  Linear: level l stands for (nu * l) / s.  Natural: level 0
+// for 0, level l >= 1 for (nu * 2^(l-1)) / 2^(s-1).  `dither_top` is the value of
+// a = |q| * top / nu at the highest level.
+__device__ inline float dither_top(uint32_t s, bool natural) { return natural ? (float)(1u << (s - 1)) : (float)s; }
+__device__ inline float dither_mag(float nu, uint32_t level, uint32_t s, bool natural) {
+  if (!natural) return (nu * (float)level) / (float)s;
+  return level == 0 ? 0.0f : (nu * (float)(1u << (level - 1))) / (float)(1u << (s - 1));
+}
+
 // Inclusive prefix sum over the 64 lanes of a wave with DPP moves: shifts by 1, 2, 4, 8 inside
 // the 16-lane rows (a lane whose source is outside its row adds 0), then lane 15 of rows 0 and
 // 2 broadcast to rows 1 and 3, then lane 31 to rows 2 and 3.

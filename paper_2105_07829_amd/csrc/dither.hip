@@ -1,5 +1,5 @@
-// Linear dithering (the stochastic multi-level quantiser the paper cites for its "dithering"
-// compressors, Section 3.2): with a = s|v_j|/nu the level is floor(a)+1 with probability
+// Dithering, multi-pass form (linear levels: the stochastic multi-level quantiser the paper
+// cites for its "dithering" compressors, Section 3.2; natural levels: powers of two): with a = s|v_j|/nu the level is floor(a)+1 with probability
 // a-floor(a), else floor(a).  Message: nu once, then one nibble (sign, level) per element.
 // Residual update as in Algorithm 4.  Three launches per call:
 //   reduce : per-tile partial of sum v_j^2 (f64) or max |v_j|
@@ -68,26 +68,37 @@ __global__ __launch_bounds__(64) void dither_finish_kernel(Geo g, const double *
 }
 
 // Level and residual of one element; `r` is the element's random word.
-__device__ inline uint32_t dither_one(float v, float nu, uint32_t s, uint32_t r, float *resid) {
+__device__ inline uint32_t dither_one(float v, float nu, uint32_t s, bool natural, uint32_t r, float *resid) {
   if (!(nu > 0.0f)) {
     *resid = v;
     return 0u;
   }
-  const float s_over_nu = (float)s / nu;   // once per partition in effect: nu and s are uniform
-  float a = s_over_nu <= 3.402823466e38f ? fabsf(v) * s_over_nu : (fabsf(v) * (float)s) / nu;
-  float l = floorf(a);
-  float f = a - l;
-  float u = (float)(r >> 8) * 0x1p-24f;
-  uint32_t level = (uint32_t)l + (u < f ? 1u : 0u);
+  const float top = dither_top(s, natural);
+  const float top_over_nu = top / nu;   // once per partition in effect: nu and s are uniform
+  const float a = top_over_nu <= 3.402823466e38f ? fabsf(v) * top_over_nu : (fabsf(v) * top) / nu;
+  uint32_t lower;
+  float f;
+  if (!natural) {
+    const float l = floorf(a);
+    f = a - l;
+    lower = (uint32_t)l;
+  } else {   // levels at a = 0, 1, 2, 4, ...: exponent field and fraction bits of a
+    const uint32_t bits = __float_as_uint(a);
+    const bool below = a < 1.0f;
+    lower = below ? 0u : (bits >> 23) - 126u;
+    f = below ? a : __uint_as_float((bits & 0x007fffffu) | 0x3f800000u) - 1.0f;
+  }
+  const float u = (float)(r >> 8) * 0x1p-24f;
+  uint32_t level = lower + (u < f ? 1u : 0u);
   level = level > s ? s : level;
-  float mag = (nu * (float)level) / (float)s;
+  const float mag = dither_mag(nu, level, s, natural);
   *resid = v - (v < 0.0f ? -mag : mag);
   return (v < 0.0f ? 8u : 0u) | level;
 }
 
 template <class SRC>
 __global__ __launch_bounds__(kThreads) void dither_apply_kernel(Geo g, SRC src, uint8_t *payload, float *residual,
-                                                                uint32_t levels, uint64_t seed,
+                                                                uint32_t levels, bool natural, uint64_t seed,
                                                                 uint64_t stream_id) {
   __shared__ float lds[SRC::kLdsFloats];
   const uint32_t p = blockIdx.x / g.tiles_per_part;
@@ -114,7 +125,7 @@ __global__ __launch_bounds__(kThreads) void dither_apply_kernel(Geo g, SRC src, 
       if (j < d) {
         float r;
         float v = src.at(g, p, j, lds);
-        uint32_t nib = dither_one(v, nu, levels, rnd[e], &r);
+        uint32_t nib = dither_one(v, nu, levels, natural, rnd[e], &r);
         word |= nib << (4 * e);
         if (residual) residual[base + j] = r;
       }
@@ -147,12 +158,13 @@ hipError_t dither_encode(const Geo &g_in, const bpc_params_t &prm_in, const Sour
   }
   double *partials = ws.at<double>(ws.lay.partials);
   const int linf = prm.norm == BPC_NORM_LINF;
-  auto make_server = [&] { return DitherMsgSource{src.msgs, src.residual, g.stride, prm.levels}; };
+  const bool natural = prm.kind == BPC_NATDITHER;
+  auto make_server = [&] { return DitherMsgSource{src.msgs, src.residual, g.stride, prm.levels, natural}; };
   return with_source(src, make_server, [&](auto s) -> hipError_t {
     using S = decltype(s);
     if (!prm.norm_override) dither_reduce_kernel<S><<<g.n_tiles, kThreads, 0, stream>>>(g, s, partials, linf);
     dither_finish_kernel<<<g.P, 64, 0, stream>>>(g, partials, prm.norm_override, linf, payload);
-    dither_apply_kernel<S><<<g.n_tiles, kThreads, 0, stream>>>(g, s, payload, src.residual, prm.levels, prm.seed,
+    dither_apply_kernel<S><<<g.n_tiles, kThreads, 0, stream>>>(g, s, payload, src.residual, prm.levels, natural, prm.seed,
                                                                prm.stream_id);
     return hipGetLastError();
   });

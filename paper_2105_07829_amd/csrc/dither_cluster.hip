@@ -2,7 +2,7 @@
 // multi-level quantiser): a workgroup reads a tile (32768 elements) of g and e once, keeps
 // q = g + e in registers, publishes its part of ||q||_2^2 (or max |q|), waits for the
 // partition's norm, then draws the levels, writes the packed nibbles and e' = q - decode.
-#include "cluster_launch.hpp"
+#include "dither_common.hpp"
 
 namespace bpc {
 
@@ -34,7 +34,7 @@ __device__ inline u32x4 tile_load8(const TileBuf &b, int u, const __half *) {
   return b.load16(threadIdx.x * 16, u * (kWThreads * 16));
 }
 
-template <class G, bool EF, bool LINF>
+template <class G, bool EF, bool LINF, bool NAT>
 struct DitherWorkerOp {
   using GV = typename Vec8Of<G>::type;
   struct Raw { GV g[kDRows]; F32x8 e[kDRows]; };
@@ -47,7 +47,7 @@ struct DitherWorkerOp {
   static constexpr bool kPersistent = true;
   // f32 gradients: the raw loads of a whole tile plus q do not fit the register budget
   static constexpr Prefetch kPrefetch = sizeof(G) == 2 ? Prefetch::kSplit : Prefetch::kInterleaved;
-  struct Ctx { float nu, s_over_nu; int mode; const float *mag; };
+  struct Ctx { float nu, top_over_nu; int mode; const float *mag; };
 
   Geo g;
   ClusterGeo cg;
@@ -120,42 +120,13 @@ struct DitherWorkerOp {
     }
   }
 
-  // Level, nibble and residual of one element.  The decoded magnitude (nu * level) / s comes
-  // from a table of the s + 1 possible values.
-  // a = s|q|/nu is |q| * (s/nu); SLOW (s/nu not finite) divides per element instead.
-  template <bool SLOW>
-  __device__ uint32_t quantise(float q, float nu, float s_over_nu, uint32_t r, const float *mag,
-                               float *resid) const {
-    const uint32_t s = levels;
-    float a = SLOW ? (fabsf(q) * (float)s) / nu : fabsf(q) * s_over_nu;
-    float l = floorf(a);
-    float f = a - l;
-    float u = (float)(r >> 8) * 0x1p-24f;
-    uint32_t level = (uint32_t)l + (u < f ? 1u : 0u);
-    level = level > s ? s : level;
-    const float m = mag[level];
-    *resid = q - (q < 0.0f ? -m : m);
-    return (q < 0.0f ? 8u : 0u) | level;
-  }
-
-  __device__ void fill_table(float nu, float *mag) const {
-    __syncthreads();
-    if (threadIdx.x < 8) mag[threadIdx.x] = (nu * (float)threadIdx.x) / (float)levels;
-    __syncthreads();
-  }
-
-  // 0: nu is not positive, everything encodes to level 0; 1: fast path; 2: per-element division
-  __device__ static int mode_of(float nu, float s_over_nu) {
-    return !(nu > 0.0f) ? 0 : s_over_nu <= 3.402823466e38f ? 1 : 2;
-  }
-
   __device__ Ctx begin2(uint32_t item, double total, float *mag) const {
     const uint32_t p = part_of(item);
     const float nu = nu_of(p, total);
     header(item, nu);
-    fill_table(nu, mag);
-    const float s_over_nu = (float)levels / nu;
-    return Ctx{nu, s_over_nu, mode_of(nu, s_over_nu), mag};
+    dither_fill_table(nu, levels, NAT, mag);
+    const float top_over_nu = dither_top(levels, NAT) / nu;
+    return Ctx{nu, top_over_nu, dither_mode(nu, top_over_nu), mag};
   }
   __device__ void row2(uint32_t item, int u, Held &h, const Ctx &ctx) const {
     if (ctx.mode == 1) row2_body<1>(item, u, h, ctx);
@@ -165,7 +136,7 @@ struct DitherWorkerOp {
 
   template <int MODE>
   __device__ void row2_body(uint32_t item, int u, Held &h, const Ctx &ctx) const {
-    const float nu = ctx.nu, s_over_nu = ctx.s_over_nu;
+    const float nu = ctx.nu, top_over_nu = ctx.top_over_nu, top = dither_top(levels, NAT);
     const float *mag = ctx.mag;
     const uint32_t p = part_of(item);
     const Philox rng(seed, stream_id, p);
@@ -184,7 +155,7 @@ struct DitherWorkerOp {
       rng.block((j0 >> 2) + 1, rnd + 4);
 #pragma unroll
       for (int c = 0; c < 8; ++c)
-        word |= quantise<MODE == 2>(h.q[8 * u + c], nu, s_over_nu, rnd[c], mag, &r[c]) << (4 * c);
+        word |= dither_quantise<MODE == 2, NAT>(h.q[8 * u + c], nu, top_over_nu, top, levels, rnd[c], mag, &r[c]) << (4 * c);
     }
     TileBuf(nibs + (tile_off(item) >> 3), kWTile / 2).store4(word, threadIdx.x * 4, u * (kWThreads * 4));
     if (EF) {
@@ -200,13 +171,18 @@ template <class G, bool EF>
 static hipError_t launch_dither(const Geo &g, const ClusterGeo &cg, const bpc_params_t &prm, const Source &src,
                                 uint8_t *payload, double *slots, uint32_t *status, hipStream_t stream,
                                 bool *used) {
-  if (prm.norm == BPC_NORM_LINF)
-    return launch_cluster(DitherWorkerOp<G, EF, true>{g, cg, (const G *)src.grad, src.residual, payload,
-                                                      prm.norm_override, prm.levels, prm.seed, prm.stream_id},
-                          cg, slots, status, stream, used);
-  return launch_cluster(DitherWorkerOp<G, EF, false>{g, cg, (const G *)src.grad, src.residual, payload,
-                                                     prm.norm_override, prm.levels, prm.seed, prm.stream_id},
-                        cg, slots, status, stream, used);
+#define BPC_DW(LINF, NAT)                                                                                  \
+  return launch_cluster(DitherWorkerOp<G, EF, LINF, NAT>{g, cg, (const G *)src.grad, src.residual, payload, \
+                                                         prm.norm_override, prm.levels, prm.seed, prm.stream_id}, \
+                        cg, slots, status, stream, used)
+  const bool nat = prm.kind == BPC_NATDITHER;
+  if (prm.norm == BPC_NORM_LINF) {
+    if (nat) BPC_DW(true, true);
+    BPC_DW(true, false);
+  }
+  if (nat) BPC_DW(false, true);
+  BPC_DW(false, false);
+#undef BPC_DW
 }
 
 hipError_t dither_worker_single_pass(const Geo &g, const bpc_params_t &prm, const Source &src, uint8_t *payload,

@@ -28,11 +28,11 @@ inline DMsgPtrs dmsg_ptrs(const WorkerMsgs &m) {
 }
 
 // NW > 0: number of workers known at compile time (unrolled); NW == 0: rolled loop.
-template <bool EF, bool LINF, int NW>
+template <bool EF, bool LINF, int NW, bool NAT>
 struct DitherServerOp {
   struct Raw { u32x4 e[2 * kDSRows]; };
   struct Held { float delta[kCPerThread]; };
-  struct Ctx { float nu, s_over_nu; int mode; const float *mag; };
+  struct Ctx { float nu, top_over_nu; int mode; const float *mag; };
   static constexpr bool kMax = LINF;
   static constexpr int kRowsPerTile = kDSRows;
   static constexpr int kTableFloats = kMaxWorkers * 16 + 8;   // decode tables, then the 8 output magnitudes
@@ -82,7 +82,7 @@ struct DitherServerOp {
     for (int e = threadIdx.x; e < msgs.n * 16; e += kSThreads) {
       const int i = e >> 4, nib = e & 15;
       const float nu = *reinterpret_cast<const float *>(msgs.ptr[i] + (uint64_t)p * g.stride);
-      const float mag = (nu * (float)(nib & 7)) / (float)levels;
+      const float mag = dither_mag(nu, nib & 7, levels, NAT);
       lut[e] = (nib & 8) ? -mag : mag;
     }
     __syncthreads();
@@ -167,9 +167,9 @@ struct DitherServerOp {
       hdr[1] = 0; hdr[2] = 0; hdr[3] = 0;
     }
     float *mag = table + kMaxWorkers * 16;
-    dither_fill_table(nu, levels, mag);
-    const float s_over_nu = (float)levels / nu;
-    return Ctx{nu, s_over_nu, dither_mode(nu, s_over_nu), mag};
+    dither_fill_table(nu, levels, NAT, mag);
+    const float top_over_nu = dither_top(levels, NAT) / nu;
+    return Ctx{nu, top_over_nu, dither_mode(nu, top_over_nu), mag};
   }
 
   template <int MODE>
@@ -178,7 +178,7 @@ struct DitherServerOp {
     const Philox rng(seed, stream_id, p);
     const uint32_t j0 = tile_off(item) + (u * kSThreads + threadIdx.x) * 8;
     float r[8];
-    const uint32_t word = dither_row<MODE>(&h.delta[8 * u], ctx.nu, ctx.s_over_nu, levels, rng, j0, ctx.mag, r);
+    const uint32_t word = dither_row<MODE, NAT>(&h.delta[8 * u], ctx.nu, ctx.top_over_nu, dither_top(levels, NAT), levels, rng, j0, ctx.mag, r);
     uint32_t *nibs = reinterpret_cast<uint32_t *>(payload + (uint64_t)p * g.stride + kHeaderBytes);
     (nibs + uniform_off((tile_off(item) + u * (kSThreads * 8)) >> 3))[threadIdx.x] = word;
     if (EF) {
@@ -195,14 +195,14 @@ struct DitherServerOp {
 
 };
 
-template <bool EF, bool LINF>
+template <bool EF, bool LINF, bool NAT>
 static hipError_t launch_dither_server(const Geo &g, const ClusterGeo &cg, const bpc_params_t &prm,
                                        const Source &src, uint8_t *payload, double *slots, uint32_t *status,
                                        hipStream_t stream, bool *used) {
   const DMsgPtrs mp = dmsg_ptrs(src.msgs);
   float *res = src.residual;
 #define BPC_DS(NW)                                                                                          \
-  return launch_cluster(DitherServerOp<EF, LINF, NW>{g, cg, mp, res, payload, prm.norm_override, prm.levels, \
+  return launch_cluster(DitherServerOp<EF, LINF, NW, NAT>{g, cg, mp, res, payload, prm.norm_override, prm.levels, \
                                                      prm.seed, prm.stream_id},                              \
                         cg, slots, status, stream, used)
   switch (mp.n) {
@@ -219,12 +219,17 @@ hipError_t dither_server_single_pass(const Geo &g, const bpc_params_t &prm, cons
   ClusterGeo cg = make_cluster_geo(g, kSTile);
   double *slots = ws.at<double>(ws.lay.slots);
   uint32_t *status = ws.at<uint32_t>(ws.lay.status);
-  const bool linf = prm.norm == BPC_NORM_LINF;
-  if (src.residual)
-    return linf ? launch_dither_server<true, true>(g, cg, prm, src, payload, slots, status, stream, used)
-                : launch_dither_server<true, false>(g, cg, prm, src, payload, slots, status, stream, used);
-  return linf ? launch_dither_server<false, true>(g, cg, prm, src, payload, slots, status, stream, used)
-              : launch_dither_server<false, false>(g, cg, prm, src, payload, slots, status, stream, used);
+  const bool linf = prm.norm == BPC_NORM_LINF, nat = prm.kind == BPC_NATDITHER;
+#define BPC_DSL(EF)                                                                                              \
+  do {                                                                                                           \
+    if (linf && nat) return launch_dither_server<EF, true, true>(g, cg, prm, src, payload, slots, status, stream, used);   \
+    if (linf) return launch_dither_server<EF, true, false>(g, cg, prm, src, payload, slots, status, stream, used);         \
+    if (nat) return launch_dither_server<EF, false, true>(g, cg, prm, src, payload, slots, status, stream, used);          \
+    return launch_dither_server<EF, false, false>(g, cg, prm, src, payload, slots, status, stream, used);                  \
+  } while (0)
+  if (src.residual) BPC_DSL(true);
+  BPC_DSL(false);
+#undef BPC_DSL
 }
 
 }  // namespace bpc

@@ -62,7 +62,7 @@ inline bool params_valid(const bpc_params_t *p) {
   switch (p->kind) {
     case BPC_IDENTITY: case BPC_SIGN: return true;
     case BPC_TOPK: case BPC_RANDK: return p->k_ratio > 0.0 && p->k_ratio <= 1.0;
-    case BPC_DITHER:
+    case BPC_DITHER: case BPC_NATDITHER:
       return p->levels >= 1 && p->levels <= 7 && (p->norm == BPC_NORM_L2 || p->norm == BPC_NORM_LINF);
     default: return false;
   }
@@ -73,7 +73,7 @@ inline size_t stride_of(const bpc_params_t *p) {
   switch (p->kind) {
     case BPC_IDENTITY: words = ru4(d); break;
     case BPC_SIGN:     words = ru4(cdiv(d, 32)); break;
-    case BPC_DITHER:   words = ru4(cdiv(d, 8)); break;
+    case BPC_DITHER: case BPC_NATDITHER: words = ru4(cdiv(d, 8)); break;
     case BPC_TOPK:     words = 2 * ru4(k_rule(p->k_ratio, d)); break;
     case BPC_RANDK:    words = ru4(k_rule(p->k_ratio, d)); break;
   }

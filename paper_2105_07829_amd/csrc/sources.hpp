@@ -54,12 +54,13 @@ struct DitherMsgSource {
   const float *res;
   uint64_t stride;
   uint32_t levels;
+  bool natural;
   static constexpr int kLdsFloats = kMaxWorkers * 16;
   __device__ void begin(const Geo &, uint32_t p, float *lds) const {
     for (int e = threadIdx.x; e < msgs.n * 16; e += blockDim.x) {
       int i = e >> 4, nib = e & 15;
       float nu = *reinterpret_cast<const float *>(msgs.ptr[i] + (uint64_t)p * stride);
-      float mag = (nu * (float)(nib & 7)) / (float)levels;
+      float mag = dither_mag(nu, nib & 7, levels, natural);
       lds[e] = (nib & 8) ? -mag : mag;
     }
     __syncthreads();

@@ -28,13 +28,13 @@ struct SignDec {
   }
 };
 struct DitherDec {
-  const uint8_t *payload; uint64_t stride; uint32_t levels;
+  const uint8_t *payload; uint64_t stride; uint32_t levels; bool natural;
   __device__ const float *dense_base() const { return nullptr; }
   static constexpr int kLdsFloats = 16;
   __device__ void begin(uint32_t p, float *lds) const {
     if (threadIdx.x < 16) {
       float nu = *reinterpret_cast<const float *>(payload + (uint64_t)p * stride);
-      float mag = (nu * (float)(threadIdx.x & 7)) / (float)levels;
+      float mag = dither_mag(nu, threadIdx.x & 7, levels, natural);
       lds[threadIdx.x] = (threadIdx.x & 8) ? -mag : mag;
     }
     __syncthreads();
@@ -267,7 +267,8 @@ hipError_t adaptive_update(const Geo &g, const bpc_params_t &prm, const uint8_t 
   double *norms = ws.at<double>(ws.lay.norms);
   switch (prm.kind) {
     case BPC_SIGN: return run_update(g, SignDec{payload, g.stride}, x, m, v, opt, norms, stream);
-    case BPC_DITHER: return run_update(g, DitherDec{payload, g.stride, prm.levels}, x, m, v, opt, norms, stream);
+    case BPC_DITHER: case BPC_NATDITHER:
+      return run_update(g, DitherDec{payload, g.stride, prm.levels, prm.kind == BPC_NATDITHER}, x, m, v, opt, norms, stream);
     case BPC_IDENTITY: return run_update(g, IdentityDec{payload, g.stride}, x, m, v, opt, norms, stream);
     default: {
       float *dense = ws.at<float>(ws.lay.dense);

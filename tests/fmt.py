@@ -19,7 +19,7 @@ def stride(kind, part_elems, k_ratio=0.0):
         words = ru4(part_elems)
     elif kind == "sign":
         words = ru4((part_elems + 31) // 32)
-    elif kind == "dither":
+    elif kind in ("dither", "natdither"):
         words = ru4((part_elems + 7) // 8)
     elif kind == "topk":
         words = 2 * ru4(k_of(k_ratio, part_elems))
@@ -85,7 +85,7 @@ def defined_bytes(kind, d, k=0, k_cap=0):
         return [(0, 16 + 4 * d)]
     if kind == "sign":
         return [(0, 16 + 4 * ru4((d + 31) // 32))]
-    if kind == "dither":
+    if kind in ("dither", "natdither"):
         return [(0, 16 + 4 * ru4((d + 7) // 8))]
     if kind == "topk":
         off = 16 + 4 * ru4(k_cap)

@@ -28,6 +28,7 @@ KW = {
     "topk": dict(k_ratio=0.01),
     "randk": dict(k_ratio=0.02, value_scale=1.0, seed=11, stream_id=(2 << 32) | 5),
     "dither": dict(levels=4, seed=0xFEED, stream_id=(7 << 32) | 1),
+    "natdither": dict(levels=6, seed=0xBEEF, stream_id=(7 << 32) | 2),
     "identity": {},
 }
 
@@ -99,12 +100,13 @@ def test_topk_ties_take_the_lowest_indices(gu, orc, pe, dtype):
     assert np.array_equal(res_gpu.view(np.uint32), res_ref.view(np.uint32))
 
 
+@pytest.mark.parametrize("kind", ["dither", "natdither"])
 @pytest.mark.parametrize("norm", [0, 1])
-def test_dither_tiny_values_divide_per_element(gu, orc, norm):
+def test_dither_tiny_values_divide_per_element(gu, orc, norm, kind):
     """nu so small that s/nu is not finite: the quantiser divides per element instead."""
     D = BIG_PE + 777
     kw = dict(levels=7, norm=norm, seed=3, stream_id=4)
-    po, pb = gu.both_params(orc, "dither", BIG_PE, **kw)
+    po, pb = gu.both_params(orc, kind, BIG_PE, **kw)
     rs = np.random.default_rng(8)
     g = (rs.standard_normal(D) * 1e-42).astype(np.float32)      # subnormal magnitudes
     e = (rs.standard_normal(D) * 1e-43).astype(np.float32)
@@ -114,11 +116,11 @@ def test_dither_tiny_values_divide_per_element(gu, orc, norm):
     strd = orc.partition_stride(po)
     for p in range(len(fmt.part_sizes(D, BIG_PE))):
         assert fmt.header_f32(fmt.record(pay_gpu, p, strd)) == fmt.header_f32(fmt.record(pay_ref, p, strd))
-    assert defined_equal("dither", pay_gpu, pay_ref, po, orc, D, BIG_PE, kw)
+    assert defined_equal(kind, pay_gpu, pay_ref, po, orc, D, BIG_PE, kw)
     assert np.array_equal(res_gpu.view(np.uint32), res_ref.view(np.uint32))
 
 
-@pytest.mark.parametrize("kind", ["sign", "dither", "topk", "randk", "identity"])
+@pytest.mark.parametrize("kind", ["sign", "dither", "natdither", "topk", "randk", "identity"])
 def test_server_with_the_most_workers(gu, orc, kind):
     n = gu.bpc.MAX_WORKERS
     D = PE + 1234
@@ -138,7 +140,7 @@ def test_server_with_the_most_workers(gu, orc, kind):
     pay_ref = orc.server_aggregate([p[0] for p in ins], payloads, out_o, res_ref, D)
     pay_gpu, res_gpu = gu.gpu_server([p[1] for p in ins], payloads, out_b, et.copy(), D)
     strd = orc.partition_stride(out_o)
-    if kind in ("sign", "dither"):
+    if kind in ("sign", "dither", "natdither"):
         # scale within tolerance; bits on equal terms when it matches exactly
         for p in range(len(fmt.part_sizes(D, PE))):
             hg, ho = fmt.header_f32(fmt.record(pay_gpu, p, strd)), fmt.header_f32(fmt.record(pay_ref, p, strd))

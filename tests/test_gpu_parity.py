@@ -40,6 +40,8 @@ KW = {
     "randk_scaled": dict(k_ratio=0.02, value_scale=-1.0, seed=99, stream_id=3),
     "dither": dict(levels=4, seed=0xFEEDFACECAFEBEEF, stream_id=(7 << 32) | 1),
     "dither_linf": dict(levels=7, norm=1, seed=5, stream_id=9),
+    "natdither": dict(levels=5, seed=0xABCDEF, stream_id=(3 << 32) | 2),
+    "natdither_linf": dict(levels=3, norm=1, seed=6, stream_id=10),
 }
 
 
@@ -53,7 +55,7 @@ def compare_payload(gu, orc, name, po, pay_gpu, pay_ref, D, pe, ref_fn):
     strd = orc.partition_stride(po)
     sizes = fmt.part_sizes(D, pe)
     assert pay_gpu.size == pay_ref.size == strd * len(sizes)
-    if kind in ("sign", "dither"):
+    if kind in ("sign", "dither", "natdither"):
         # scale / norm within tolerance, then every packed bit on equal terms
         hg = np.array([fmt.header_f32(fmt.record(pay_gpu, p, strd)) for p in range(len(sizes))], dtype=np.float32)
         hr = np.array([fmt.header_f32(fmt.record(pay_ref, p, strd)) for p in range(len(sizes))], dtype=np.float32)
@@ -174,7 +176,7 @@ def test_server_stage(gu, orc, name, ef, n):
                 assert gu.close(res_gpu, res_ref, REL), name
 
 
-@pytest.mark.parametrize("name", [k for k in sorted(KW) if base_kind(k) in ("sign", "dither")])
+@pytest.mark.parametrize("name", [k for k in sorted(KW) if base_kind(k) in ("sign", "dither", "natdither")])
 @pytest.mark.parametrize("ef", [True, False])
 @pytest.mark.parametrize("n", [3, 16])
 def test_server_stage_large_partitions(gu, orc, name, ef, n):
@@ -252,7 +254,7 @@ def test_update_stage(gu, orc, name, opt_kind):
 def test_deterministic_bytes(gu, orc):
     """Same call twice gives identical bytes for the kinds whose arithmetic has a fixed order."""
     D = 2 * PE + 4137
-    for name in ("sign", "topk", "dither", "identity"):
+    for name in ("sign", "topk", "dither", "natdither", "identity"):
         po, pb = gu.both_params(orc, base_kind(name), PE, **KW[name])
         g = grads(D, np.float16, 8)
         e = (rng(9).standard_normal(D) * 3e-4).astype(np.float32)
@@ -266,7 +268,7 @@ def test_deterministic_bytes(gu, orc):
                 assert np.array_equal(fmt.record(a[0], p, strd)[lo:hi], fmt.record(b[0], p, strd)[lo:hi])
 
 
-@pytest.mark.parametrize("name", ["sign", "topk", "dither", "randk", "identity"])
+@pytest.mark.parametrize("name", ["sign", "topk", "dither", "natdither", "randk", "identity"])
 def test_chained_pipeline_three_steps(gu, orc, name):
     """Algorithm 4 + the Adam-style update chained on the GPU only (each stage consumes the GPU's
     own previous outputs) against the chained oracle."""
@@ -297,7 +299,7 @@ def test_chained_pipeline_three_steps(gu, orc, name):
         out_o, out_b = gu.both_params(orc, name, PE, **kw)
         p_o = orc.server_aggregate([p[0] for p in ins], pay_o, out_o, et_o, D)
         p_g, et_g = gu.gpu_server([p[1] for p in ins], pay_g, out_b, et_g, D)
-        if name in ("sign", "dither"):
+        if name in ("sign", "dither", "natdither"):
             strd = orc.partition_stride(out_o)
             for p, d in enumerate(fmt.part_sizes(D, PE)):
                 for lo, hi in fmt.defined_bytes(name, d):
@@ -313,5 +315,5 @@ def test_chained_pipeline_three_steps(gu, orc, name):
         assert gu.close(a, b, 1e-5 if name == "randk" else REL)
     for i in range(n):
         assert gu.close(e_g[i], e_o[i], 1e-5 if name == "randk" else REL)
-    if name in ("sign", "dither"):
+    if name in ("sign", "dither", "natdither"):
         assert diff_bytes == 0

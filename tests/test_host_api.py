@@ -35,6 +35,7 @@ def test_sizes_follow_the_record_format(bpc):
     pe = 1 << 20
     assert bpc.partition_stride(bpc.make_params(bpc.SIGN, pe)) == fmt.stride("sign", pe)
     assert bpc.partition_stride(bpc.make_params(bpc.DITHER, pe)) == fmt.stride("dither", pe)
+    assert bpc.partition_stride(bpc.make_params(bpc.NATDITHER, pe)) == fmt.stride("natdither", pe)
     assert bpc.partition_stride(bpc.make_params(bpc.IDENTITY, pe)) == fmt.stride("identity", pe)
     assert bpc.partition_stride(bpc.make_params(bpc.TOPK, pe, k_ratio=0.01)) == fmt.stride("topk", pe, 0.01)
     assert bpc.partition_stride(bpc.make_params(bpc.RANDK, pe, k_ratio=0.01)) == fmt.stride("randk", pe, 0.01)

@@ -369,14 +369,14 @@ def test_natural_dither_probability_is_the_distance_to_the_lower_level(orc):
 
 def test_zero_vector_encodes_to_zero(orc):
     z = np.zeros(100, dtype=np.float32)
-    for kind in (orc.SIGN, orc.DITHER, orc.TOPK, orc.RANDK, orc.IDENTITY):
+    for kind in (orc.SIGN, orc.DITHER, orc.NATDITHER, orc.TOPK, orc.RANDK, orc.IDENTITY):
         p = orc.make_params(kind, PE, k_ratio=0.1, levels=4)
         dec = orc.decode_partition(p, 0, orc.encode_partition(p, 0, z), 100)
         assert not dec.any()
 
 
 # ---------------------------------------------------------------- Algorithm 4 identities
-KINDS = ["identity", "sign", "topk", "randk", "randk_scaled", "dither"]
+KINDS = ["identity", "sign", "topk", "randk", "randk_scaled", "dither", "natdither"]
 
 
 def params_for(orc, name, pe=PE, seed=1, stream=0):
@@ -392,6 +392,8 @@ def params_for(orc, name, pe=PE, seed=1, stream=0):
         return orc.make_params(orc.RANDK, pe, k_ratio=0.05, value_scale=-1.0, seed=seed, stream_id=stream)
     if name == "dither":
         return orc.make_params(orc.DITHER, pe, levels=4, seed=seed, stream_id=stream)
+    if name == "natdither":
+        return orc.make_params(orc.NATDITHER, pe, levels=4, seed=seed, stream_id=stream)
     raise ValueError(name)
 
 
