@@ -42,7 +42,7 @@ def payload_bytes_per_elem(w):
     k = w["kind"]
     if k == "sign":
         return 1.0 / 8
-    if k == "dither":
+    if k in ("dither", "natdither"):
         return 0.5
     if k == "topk":
         return 8 * w["k_ratio"]
@@ -68,7 +68,8 @@ class Pipeline:
         dev = "cuda"
         self.D, self.n = w["D"], w["n_workers"]
         self.pe = synth.part_elems(w["dtype"])
-        kind = {"sign": bpc.SIGN, "topk": bpc.TOPK, "randk": bpc.RANDK, "dither": bpc.DITHER}[w["kind"]]
+        kind = {"sign": bpc.SIGN, "topk": bpc.TOPK, "randk": bpc.RANDK, "dither": bpc.DITHER,
+                "natdither": bpc.NATDITHER}[w["kind"]]
         self.kw = dict(k_ratio=w.get("k_ratio", 0.01), levels=w.get("levels", 4),
                        value_scale=w.get("value_scale", 1.0), seed=synth.BASE_SEED)
         self.kind = kind
@@ -166,7 +167,8 @@ def cpu_baseline(name, w, n_parts, n_steps, synth):
     n = w["n_workers"]
     D = pe * n_parts
     cores = min(os.cpu_count() or 1, 16)
-    kind = {"sign": oracle.SIGN, "topk": oracle.TOPK, "randk": oracle.RANDK, "dither": oracle.DITHER}[w["kind"]]
+    kind = {"sign": oracle.SIGN, "topk": oracle.TOPK, "randk": oracle.RANDK, "dither": oracle.DITHER,
+            "natdither": oracle.NATDITHER}[w["kind"]]
     kw = dict(k_ratio=w.get("k_ratio", 0.01), levels=w.get("levels", 4), value_scale=w.get("value_scale", 1.0),
               seed=synth.BASE_SEED)
     grads = [synth.host_gradient(w["dist"], D, w["dtype"], worker=i) for i in range(n)]

@@ -41,6 +41,9 @@ WORKLOADS = {
                       ef=True, opt="adam"),
     "bert_large": dict(D=336_000_000, dtype="f16", dist="student_t3", kind="dither", levels=4,
                        n_workers=16, ef=True, opt="adam"),
+    # not a BASELINE configuration: the bert_large shape with the natural (power-of-two) level map
+    "bert_large_natural": dict(D=336_000_000, dtype="f16", dist="student_t3", kind="natdither", levels=4,
+                               n_workers=16, ef=True, opt="adam"),
 }
 
 

@@ -38,7 +38,7 @@ def record_equal(kind, rec_g, rec_o, d, k, k_cap):
     return True
 
 
-@pytest.mark.parametrize("name", ["sign_1m", "resnet50", "vgg16", "bert_base", "bert_large"])
+@pytest.mark.parametrize("name", ["sign_1m", "resnet50", "vgg16", "bert_base", "bert_large", "bert_large_natural"])
 def test_full_size_pipeline(env, orc, name):
     gu, synth, torch = env
     bpc = gu.bpc
@@ -48,7 +48,8 @@ def test_full_size_pipeline(env, orc, name):
     P = (D + pe - 1) // pe
     kw = dict(k_ratio=w.get("k_ratio", 0.01), levels=w.get("levels", 4), value_scale=w.get("value_scale", 1.0),
               seed=synth.BASE_SEED)
-    kind_o = {"sign": orc.SIGN, "topk": orc.TOPK, "randk": orc.RANDK, "dither": orc.DITHER}[kind]
+    kind_o = {"sign": orc.SIGN, "topk": orc.TOPK, "randk": orc.RANDK, "dither": orc.DITHER,
+              "natdither": orc.NATDITHER}[kind]
     kind_b = gu.KIND_B[kind]
     k_cap = fmt.k_of(kw["k_ratio"], pe) if kind in ("topk", "randk") else 0
     dev = gu.DEV
@@ -90,7 +91,7 @@ def test_full_size_pipeline(env, orc, name):
         rec_g = pays[0][p * strd:(p + 1) * strd].cpu().numpy()
         res_o = e_host[p].copy()
         rec_o = orc.compress(prm_o((1 << 32) | 0, p), g_host[p], res_o)
-        if kind in ("sign", "dither"):
+        if kind in ("sign", "dither", "natdither"):
             hg, ho = fmt.header_f32(rec_g), fmt.header_f32(rec_o)
             assert abs(float(hg) - float(ho)) <= REL * abs(float(ho))
             if hg != ho:       # packed bits on equal terms: oracle with the GPU's scale
@@ -119,7 +120,7 @@ def test_full_size_pipeline(env, orc, name):
         rec_g = out_pay[p * strd:(p + 1) * strd].cpu().numpy()
         res_o = s_host[p].copy()
         rec_o = orc.server_aggregate(ins_o, recs, prm_o(out_stream, p), res_o, d)
-        if kind in ("sign", "dither"):
+        if kind in ("sign", "dither", "natdither"):
             hg, ho = fmt.header_f32(rec_g), fmt.header_f32(rec_o)
             assert abs(float(hg) - float(ho)) <= REL * abs(float(ho))
             if hg != ho:
