@@ -21,13 +21,14 @@
 //     publish before they wait.  Used where a tile's loads can be requested one tile ahead
 //     (the worker side: two streams per tile), which keeps the memory pipeline of a compute
 //     unit busy across the exchange.
-//   TICKETED (cluster_run_ticketed): one workgroup per tile; a workgroup takes the next tile
-//     number from a counter when it starts running, so numbers are handed out in start
-//     order.  When workgroups wait, the device keeps `capacity` of them resident, all with
-//     numbers at or above the oldest unfinished one; with tiles_per_partition <= capacity
-//     the whole oldest unfinished partition is therefore running, its tiles publish before
-//     they wait, and it completes.  Used where a tile needs many streams and latency-bound
-//     loads (the server side): many small workgroups per compute unit overlap each other.
+//   TICKETED (cluster_run_ticketed): the grid is resident as a whole too, but a workgroup
+//     takes the number of its next tile from a counter, so tiles are handed out in the order
+//     in which workgroups become free.  Every workgroup holds at most one unfinished tile;
+//     if all G of them wait, the unfinished tiles are G distinct numbers at or above the
+//     oldest one, so with tiles_per_partition <= G the whole oldest unfinished partition has
+//     been handed out, its tiles publish before they wait, and it completes.  Used where a
+//     tile needs many streams and latency-bound loads (the server side): many small
+//     workgroups per compute unit overlap each other, without a prefetch to keep in registers.
 #pragma once
 #include "device_utils.hpp"
 #include "geometry.hpp"
@@ -96,6 +97,11 @@ int cluster_capacity(const void *kernel, int threads, size_t dyn_lds = 0);
 // Presets the slots to "not published", clears the status word and the ticket counter.
 __global__ void slots_reset_kernel(double *slots, uint32_t n, uint32_t *status);
 
+// A slot is unpublished while it holds exactly the preset -1.0.  Partials are sums of
+// magnitudes or squares, so no published value has that bit pattern, whatever the inputs
+// (a NaN partial from non-finite inputs still counts as published: no wait depends on the data).
+constexpr long long kSlotUnpublished = (long long)0xBFF0000000000000ull;
+__device__ inline bool slot_published(double x) { return __double_as_longlong(x) != kSlotUnpublished; }
 __device__ inline void slot_publish(double *slot, double value) {
   __hip_atomic_store(slot, value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
@@ -113,8 +119,9 @@ __device__ inline double slots_collect(const double *slots, uint32_t count, uint
     v = 0.0;
     for (uint32_t s = lane; s < count; s += 64) {
       double x = __hip_atomic_load(slots + s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      ok = ok && x >= 0.0;
-      x = x >= 0.0 ? x : 0.0;
+      const bool pub = slot_published(x);
+      ok = ok && pub;
+      x = pub ? x : 0.0;
       v = MAX ? fmax(v, x) : v + x;
     }
     if (__all(ok)) break;
@@ -247,36 +254,46 @@ __device__ inline void cluster_run_persistent(const Op &op, float *table, double
 }
 
 // Ticketed driver: phase 1 of `Op` issues its own loads.  `status[1]` is the ticket counter.
+// The grid is resident as a whole (the launcher sizes it) and every workgroup keeps taking
+// tickets until none is left.  (Launching one workgroup per tile instead would tie each
+// workgroup to the XCD its index maps to; near the end of the grid the tiles still to come
+// would then all belong to the one or two XCDs that are behind, too few workgroups to hold a
+// whole partition, and the waits would only end at their bound.)
 template <class Op>
 __device__ inline void cluster_run_ticketed(const Op &op, float *table, double *slots, uint32_t *status) {
   constexpr int kT = Op::kThreads;
   __shared__ double red[kT / 64];
   __shared__ double total_sh;
   __shared__ uint32_t item_sh;
-  if (threadIdx.x == 0) item_sh = atomicAdd(status + 1, 1u);
-  __syncthreads();
-  // the same for every lane: keeping it in a scalar register makes all tile addresses scalar
-  const uint32_t item = __builtin_amdgcn_readfirstlane(item_sh);
-  if (item >= op.n_items()) return;
-  typename Op::Raw raw;
-  typename Op::Held held;
-  double part = op.phase1(item, raw, held, table);
-  part = cluster_block_reduce<Op::kMax, kT>(part, red);
-  if (threadIdx.x < 64) {
-    uint32_t first, count;
-    op.slots_of(item, &first, &count);
-    if (op.needs_total()) {
-      if (threadIdx.x == 0) slot_publish(slots + item, part);
-      double total = slots_collect<Op::kMax>(slots + first, count, status);
-      if (threadIdx.x == 0) total_sh = total;
+  for (;;) {
+    if (threadIdx.x == 0) item_sh = atomicAdd(status + 1, 1u);
+    __syncthreads();
+    // the same for every lane: keeping it in a scalar register makes all tile addresses scalar
+    const uint32_t item = __builtin_amdgcn_readfirstlane(item_sh);
+    if (item >= op.n_items()) break;
+    typename Op::Raw raw;
+    typename Op::Held held;
+    double part = op.phase1(item, raw, held, table);
+    part = cluster_block_reduce<Op::kMax, kT>(part, red);
+    if (threadIdx.x < 64) {
+      uint32_t first, count;
+      op.slots_of(item, &first, &count);
+      if (op.needs_total()) {
+        if (threadIdx.x == 0) slot_publish(slots + item, part);
+        double total = slots_collect<Op::kMax>(slots + first, count, status);
+        if (threadIdx.x == 0) total_sh = total;
+      }
     }
-  }
-  op.early(item, held);
-  __syncthreads();
-  const double total = total_sh;
-  const typename Op::Ctx ctx = op.begin2(item, total, table);
+    op.early(item, held);
+    __syncthreads();
+    const double total = total_sh;
+    const typename Op::Ctx ctx = op.begin2(item, total, table);
 #pragma unroll
-  for (int u = 0; u < Op::kRowsPerTile; ++u) op.row2(item, u, held, ctx);
+    for (int u = 0; u < Op::kRowsPerTile; ++u) op.row2(item, u, held, ctx);
+    // (drawing the next ticket earlier, under these stores, was slower: a tile drawn early
+    // starts late, and its whole partition waits for it)
+    __syncthreads();   // the LDS words above are rewritten by the next round
+  }
 }
 #endif
 

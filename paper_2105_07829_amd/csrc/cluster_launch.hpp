@@ -40,8 +40,8 @@ static hipError_t launch_cluster(const Op &op, const ClusterGeo &cg, double *slo
   *used = false;
   if (capacity <= 0) return hipSuccess;
   if (cg.tiles_per_part > (uint32_t)capacity) return hipSuccess;
-  // persistent: every workgroup resident; ticketed: one workgroup per tile
-  const uint32_t grid = Op::kPersistent && cg.n_items > (uint32_t)capacity ? (uint32_t)capacity : cg.n_items;
+  // the whole grid is resident at once
+  const uint32_t grid = cg.n_items > (uint32_t)capacity ? (uint32_t)capacity : cg.n_items;
   *used = true;
   hipError_t e = cluster_launch_begin(stream);
   if (e != hipSuccess) return e;

@@ -100,11 +100,11 @@ inline Geo make_geo(const bpc_params_t *p, uint64_t D) {
 struct WsLayout {
   size_t partials;   // double[n_tiles]: per-tile partial norms
   size_t dense;      // float[D]: q / Delta / decoded message when no caller buffer can hold it
-  size_t hist;       // u32[P*8*4096]: top-k radix histograms (2048 + 1024 + 1024 bins), 8 copies a partition
-                     // for the single-pass kernel (the multi-pass kernels use the first P*4096 words)
+  size_t hist;       // u32[P*4096]: top-k radix histograms (2048 + 1024 + 1024 bins)
   size_t state;      // u32[P*8]: top-k selection state
   size_t tilecnt;    // u32[2*n_tiles]: per-tile (greater, equal) counts, then offsets
-  size_t slots;      // double[tiles of kSTile]: partition-wide reductions of the single-pass kernels
+  size_t slots;      // double[3 * tiles of kSTile]: partition-wide reductions of the single-pass kernels
+                     // (one per tile; three for the LANS block norms)
   size_t status;     // u32[64]: word 0 is non-zero if a single-pass kernel gave up waiting, word 1 is its ticket counter
   size_t norms;      // double[3*P]: LANS block norms when blocks are the partitions
   size_t total;
@@ -118,10 +118,10 @@ inline WsLayout ws_layout(const bpc_params_t *p, uint64_t D) {
   bool sparse = p->kind == BPC_TOPK || p->kind == BPC_RANDK;
   w.partials = take(sizeof(double) * (size_t)g.n_tiles);
   w.dense = take(sparse ? sizeof(float) * (size_t)D : 0);
-  w.hist = take(p->kind == BPC_TOPK ? sizeof(uint32_t) * 8 * 4096 * (size_t)g.P : 0);
+  w.hist = take(p->kind == BPC_TOPK ? sizeof(uint32_t) * 4096 * (size_t)g.P : 0);
   w.state = take(p->kind == BPC_TOPK ? sizeof(uint32_t) * 8 * (size_t)g.P : 0);
   w.tilecnt = take(p->kind == BPC_TOPK ? sizeof(uint32_t) * 2 * (size_t)g.n_tiles : 0);
-  w.slots = take(sizeof(double) * ((size_t)g.P * cdiv(g.part_elems, kSTile)));
+  w.slots = take(sizeof(double) * 3 * ((size_t)g.P * cdiv(g.part_elems, kSTile)));
   w.status = take(256);
   w.norms = take(sizeof(double) * 3 * (size_t)g.P);
   w.total = off;

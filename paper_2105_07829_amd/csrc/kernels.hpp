@@ -56,11 +56,6 @@ hipError_t topk_encode(const Geo &g, const bpc_params_t &prm, const bpc_params_t
 hipError_t randk_encode(const Geo &g, const bpc_params_t &prm, const bpc_params_t *in_prm, const Source &src,
                         uint8_t *payload, const Workspace &ws, hipStream_t stream);
 
-// Top-k in one pass over the data (topk_cluster.hip); `dense_sum` is the server's sum of the
-// decoded worker messages (NULL on the worker side).  *used = false: shape not supported.
-hipError_t topk_single_pass(const Geo &g, const Source &src, const float *dense_sum, uint8_t *payload,
-                            const Workspace &ws, hipStream_t stream, bool *used);
-
 // out[idx] += decoded sparse entries (TOPK: plain store).  `out` holds the running sum.
 hipError_t scatter_add_sparse(const Geo &g, const bpc_params_t &prm, const uint8_t *payload, float *out,
                               hipStream_t stream);

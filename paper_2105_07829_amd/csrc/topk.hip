@@ -264,21 +264,14 @@ hipError_t topk_encode(const Geo &g, const bpc_params_t &, const bpc_params_t *,
   // the vector being compressed ends up in the residual buffer (error feedback) or the workspace
   float *buf = src.residual ? src.residual : dense;
   hipError_t e;
-  bool used = false;
-  if (src.grad) {
-    e = topk_single_pass(g, src, nullptr, payload, ws, stream, &used);
-    if (e != hipSuccess || used) return e;
-  } else {
+  if (!src.grad) {
     // server: sum the n decoded messages into the workspace in worker order
     e = fill_zero(dense, sizeof(float) * g.D, stream);
     if (e != hipSuccess) return e;
     dim3 grid((uint32_t)cdiv(g.k_cap, kThreads), g.P);
     for (int i = 0; i < src.msgs.n; ++i)
       topk_accumulate_kernel<<<grid, kThreads, 0, stream>>>(g, src.msgs.ptr[i], dense);
-    e = topk_single_pass(g, src, dense, payload, ws, stream, &used);
-    if (e != hipSuccess || used) return e;
   }
-  // multi-pass selection (shapes the single-pass kernel does not take)
   e = fill_zero(hist, sizeof(uint32_t) * kHistPerPart * (size_t)g.P, stream);
   if (e != hipSuccess) return e;
   if (src.grad) {

@@ -3,6 +3,7 @@
 //   ADAM : one launch, x -= lr * (r + wd*x)
 //   LANS : moments + block norms (||x_b||, ||r + wd x||_b, ||c + wd x||_b, f64 sums), then
 //          x -= lr * phi(||x_b||) * (beta1 (r+wd x)/||.|| + (1-beta1) (c+wd x)/||.||)
+#include "cluster_launch.hpp"
 #include "sources.hpp"
 
 namespace bpc {
@@ -213,6 +214,137 @@ __global__ __launch_bounds__(kThreads) void adam_update_kernel(Geo g, DEC dec, f
   }
 }
 
+// LANS in one pass when the blocks are the partitions: a workgroup (512 threads, 16 elements a
+// thread, an 8192-element tile) updates and stores the moments, keeps x, r + wd x and c + wd x
+// in registers, exchanges its three partial square sums with the other tiles of the partition
+// (one f64 slot each, published and polled as in cluster.hpp; resident grid, tiles handed out
+// by ticket) and then writes x.  Sums are combined in slot order, so the result does not
+// depend on timing.  Same traffic as ADAM: payload, m, v, x read once, m, v, x written once.
+constexpr int kLThreads = 512;
+constexpr int kLPer = kSTile / kLThreads;   // 16
+constexpr int kLRows = kLPer / 4;           // 4 rows of 2048 elements, 4 consecutive a thread
+constexpr int kLRow = kLThreads * 4;
+template <class DEC>
+__global__ __launch_bounds__(kLThreads, 4) void lans_single_kernel(Geo g, ClusterGeo cg, DEC dec, float *x, float *m, float *v,
+                                                                  OptArgs o, double *slots, uint32_t *status) {
+  __shared__ float lds[DEC::kLdsFloats];
+  __shared__ double red[kLThreads / 64];
+  __shared__ double total_sh[3];
+  __shared__ uint32_t item_sh;
+  // the grid is resident as a whole; workgroups take tiles by ticket until none is left
+  for (;;) {
+  if (threadIdx.x == 0) item_sh = atomicAdd(status + 1, 1u);
+  __syncthreads();
+  const uint32_t item = __builtin_amdgcn_readfirstlane(item_sh);
+  if (item >= cg.n_items) break;
+  const uint32_t p = __builtin_amdgcn_readfirstlane(item / cg.tiles_per_part);
+  const uint32_t tile = __builtin_amdgcn_readfirstlane(item % cg.tiles_per_part);
+  const uint32_t d = g.part_size(p);
+  const uint32_t tiles_in_part = (uint32_t)cdiv(d, kSTile);
+  dec.begin(p, lds);
+  const uint64_t tile_base = g.part_base(p) + (uint64_t)tile * kSTile;
+  const uint32_t valid = d - tile * kSTile < (uint32_t)kSTile ? d - tile * kSTile : (uint32_t)kSTile;
+  const float omb1 = 1.0f - o.beta1, omb2 = 1.0f - o.beta2;
+  u32x4 xr[kLRows], mr[kLRows], vr[kLRows];
+  float gr[kLRows][4];
+#pragma unroll
+  for (int u = 0; u < kLRows; ++u) {
+    mr[u] = row_buf(m + tile_base, valid, u * kLRow, kLRow).load16<kNonTemporal>(threadIdx.x * 16, 0);
+    vr[u] = row_buf(v + tile_base, valid, u * kLRow, kLRow).load16<kNonTemporal>(threadIdx.x * 16, 0);
+    xr[u] = row_buf(x + tile_base, valid, u * kLRow, kLRow).load16<kNonTemporal>(threadIdx.x * 16, 0);
+    const uint32_t j = tile * kSTile + u * kLRow + threadIdx.x * 4;
+    dec.at4(g, p, j, row_buf(dec.dense_base() + tile_base, valid, u * kLRow, kLRow), lds, gr[u]);
+  }
+  float xs[kLPer], ur[kLPer], uc[kLPer];
+  double s_x = 0.0, s_r = 0.0, s_c = 0.0;
+#pragma unroll
+  for (int u = 0; u < kLRows; ++u) {
+    const uint32_t mi[4] = {mr[u].x, mr[u].y, mr[u].z, mr[u].w};
+    const uint32_t vi[4] = {vr[u].x, vr[u].y, vr[u].z, vr[u].w};
+    const uint32_t xi[4] = {xr[u].x, xr[u].y, xr[u].z, xr[u].w};
+    float mo[4], vo[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const float gj = gr[u][c];
+      const float mj = o.beta1 * __uint_as_float(mi[c]) + omb1 * gj;
+      const float vj = o.beta2 * __uint_as_float(vi[c]) + omb2 * (gj * gj);
+      const float xj = __uint_as_float(xi[c]);
+      float u_r, u_c;
+      ratios(o, gj, mj, vj, xj, &u_r, &u_c);
+      mo[c] = mj;
+      vo[c] = vj;
+      // what the padded record decodes to past the partition's end takes no part in the norms
+      const bool in = (uint32_t)(u * kLRow) + threadIdx.x * 4 + c < valid;
+      xs[4 * u + c] = xj;
+      ur[4 * u + c] = u_r;
+      uc[4 * u + c] = u_c;
+      s_x = in ? fma((double)xj, (double)xj, s_x) : s_x;
+      s_r = in ? fma((double)u_r, (double)u_r, s_r) : s_r;
+      s_c = in ? fma((double)u_c, (double)u_c, s_c) : s_c;
+    }
+    row_buf(m + tile_base, valid, u * kLRow, kLRow).store16<kNonTemporal>(as_u32x4(mo[0], mo[1], mo[2], mo[3]), threadIdx.x * 16);
+    row_buf(v + tile_base, valid, u * kLRow, kLRow).store16<kNonTemporal>(as_u32x4(vo[0], vo[1], vo[2], vo[3]), threadIdx.x * 16);
+  }
+  const double t_x = cluster_block_reduce<false, kLThreads>(s_x, red);
+  const double t_r = cluster_block_reduce<false, kLThreads>(s_r, red);
+  const double t_c = cluster_block_reduce<false, kLThreads>(s_c, red);
+  if (threadIdx.x < 64) {
+    // slot 3*tile + k of the partition holds this tile's k-th partial
+    double *ps = slots + 3ull * p * cg.tiles_per_part;
+    if (threadIdx.x == 0) {
+      slot_publish(ps + 3 * tile + 0, t_x);
+      slot_publish(ps + 3 * tile + 1, t_r);
+      slot_publish(ps + 3 * tile + 2, t_c);
+    }
+    const uint32_t lane = threadIdx.x;
+    double a0, a1, a2;
+    int spins = 0;
+    for (;;) {
+      bool ok = true;
+      a0 = 0.0; a1 = 0.0; a2 = 0.0;
+      for (uint32_t s = lane; s < tiles_in_part; s += 64) {
+        const double q0 = __hip_atomic_load(ps + 3 * s + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const double q1 = __hip_atomic_load(ps + 3 * s + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const double q2 = __hip_atomic_load(ps + 3 * s + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        ok = ok && slot_published(q0) && slot_published(q1) && slot_published(q2);
+        a0 += slot_published(q0) ? q0 : 0.0;
+        a1 += slot_published(q1) ? q1 : 0.0;
+        a2 += slot_published(q2) ? q2 : 0.0;
+      }
+      if (__all(ok)) break;
+      if (++spins > kSpinLimit) {
+        if (lane == 0) atomicOr(status, 1u);
+        break;
+      }
+      __builtin_amdgcn_s_sleep(16);
+    }
+    a0 = wave_sum(a0);
+    a1 = wave_sum(a1);
+    a2 = wave_sum(a2);
+    if (lane == 0) { total_sh[0] = a0; total_sh[1] = a1; total_sh[2] = a2; }
+  }
+  __syncthreads();
+  const float norm_x = (float)sqrt(total_sh[0]);
+  const float norm_r = (float)sqrt(total_sh[1]);
+  const float norm_c = (float)sqrt(total_sh[2]);
+  float phi = norm_x < o.phi_lo ? o.phi_lo : norm_x;
+  phi = phi > o.phi_hi ? o.phi_hi : phi;
+  const float w_r = norm_r > 0.0f ? o.beta1 / norm_r : 0.0f;
+  const float w_c = norm_c > 0.0f ? omb1 / norm_c : 0.0f;
+#pragma unroll
+  for (int u = 0; u < kLRows; ++u) {
+    float xo[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const float dir = phi * (w_r * ur[4 * u + c] + w_c * uc[4 * u + c]);
+      xo[c] = xs[4 * u + c] - o.lr * dir;
+    }
+    row_buf(x + tile_base, valid, u * kLRow, kLRow).store16<kNonTemporal>(as_u32x4(xo[0], xo[1], xo[2], xo[3]), threadIdx.x * 16);
+  }
+  __syncthreads();   // the LDS words are rewritten by the next round
+  }
+}
+
 template <class DEC>
 __global__ __launch_bounds__(kThreads) void lans_apply_kernel(Geo g, DEC dec, float *x, const float *m,
                                                               const float *v, OptArgs o, const double *norms) {
@@ -245,14 +377,43 @@ __global__ __launch_bounds__(kThreads) void lans_apply_kernel(Geo g, DEC dec, fl
   }
 }
 
+// LANS with the partitions as blocks, one pass.  *used = false: shape not supported.
+template <class DEC>
+static hipError_t run_lans_single(const Geo &g, DEC dec, float *x, float *m, float *v, const OptArgs &o,
+                                  const Workspace &ws, hipStream_t stream, bool *used) {
+  *used = false;
+  if (g.part_elems % kSTile != 0) return hipSuccess;
+  const ClusterGeo cg = make_cluster_geo(g, kSTile);
+  static int capacity = 0;
+  if (capacity == 0) capacity = cluster_capacity(reinterpret_cast<const void *>(&lans_single_kernel<DEC>), kLThreads, 0);
+  if (capacity <= 0 || cg.tiles_per_part > (uint32_t)capacity) return hipSuccess;
+  *used = true;
+  double *slots = ws.at<double>(ws.lay.slots);
+  uint32_t *status = ws.at<uint32_t>(ws.lay.status);
+  hipError_t e = cluster_launch_begin(stream);
+  if (e != hipSuccess) return e;
+  const uint32_t n_slots = 3 * g.P * cg.tiles_per_part;
+  slots_reset_kernel<<<(uint32_t)cdiv(n_slots, 256), 256, 0, stream>>>(slots, n_slots, status);
+  const uint32_t grid = cg.n_items > (uint32_t)capacity ? (uint32_t)capacity : cg.n_items;
+  lans_single_kernel<DEC><<<grid, kLThreads, 0, stream>>>(g, cg, dec, x, m, v, o, slots, status);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  return cluster_launch_end(stream);
+}
+
 template <class DEC>
 static hipError_t run_update(const Geo &g, DEC dec, float *x, float *m, float *v, const bpc_opt_t &opt,
-                             double *norms, hipStream_t stream) {
+                             double *norms, const Workspace &ws, hipStream_t stream) {
   OptArgs o{opt.lr, opt.beta1, opt.beta2, opt.eps, opt.weight_decay, opt.bias_corr1, opt.bias_corr2,
             opt.phi_lo, opt.phi_hi, opt.block_offsets, opt.n_blocks};
   if (opt.kind == BPC_OPT_ADAM) {
     adam_update_kernel<DEC><<<g.n_tiles, kThreads, 0, stream>>>(g, dec, x, m, v, o);
     return hipGetLastError();
+  }
+  if (!opt.block_offsets) {
+    bool used = false;
+    hipError_t e1 = run_lans_single(g, dec, x, m, v, o, ws, stream, &used);
+    if (e1 != hipSuccess || used) return e1;
   }
   uint64_t nb = opt.block_offsets ? opt.n_blocks : g.P;
   hipError_t e = fill_zero(norms, sizeof(double) * 3 * nb, stream);
@@ -266,15 +427,15 @@ hipError_t adaptive_update(const Geo &g, const bpc_params_t &prm, const uint8_t 
                            float *v, const bpc_opt_t &opt, const Workspace &ws, hipStream_t stream) {
   double *norms = ws.at<double>(ws.lay.norms);
   switch (prm.kind) {
-    case BPC_SIGN: return run_update(g, SignDec{payload, g.stride}, x, m, v, opt, norms, stream);
+    case BPC_SIGN: return run_update(g, SignDec{payload, g.stride}, x, m, v, opt, norms, ws, stream);
     case BPC_DITHER: case BPC_NATDITHER:
-      return run_update(g, DitherDec{payload, g.stride, prm.levels, prm.kind == BPC_NATDITHER}, x, m, v, opt, norms, stream);
-    case BPC_IDENTITY: return run_update(g, IdentityDec{payload, g.stride}, x, m, v, opt, norms, stream);
+      return run_update(g, DitherDec{payload, g.stride, prm.levels, prm.kind == BPC_NATDITHER}, x, m, v, opt, norms, ws, stream);
+    case BPC_IDENTITY: return run_update(g, IdentityDec{payload, g.stride}, x, m, v, opt, norms, ws, stream);
     default: {
       float *dense = ws.at<float>(ws.lay.dense);
       hipError_t e = decode_dense(g, prm, payload, dense, stream);
       if (e != hipSuccess) return e;
-      return run_update(g, DenseDec{dense}, x, m, v, opt, norms, stream);
+      return run_update(g, DenseDec{dense}, x, m, v, opt, norms, ws, stream);
     }
   }
 }
