@@ -139,6 +139,40 @@ __device__ inline double slots_collect(const double *slots, uint32_t count, uint
   return v;
 }
 
+// The same in two steps for the lagged drivers: slots_probe() reads every slot once without
+// waiting for the values (the loads stay in flight under whatever the caller does next), and
+// slots_finish() uses them if all were published, else falls back to slots_collect().  Both
+// combine in the same order, so the result does not depend on which one produced it.
+struct SlotProbe { double v; bool ok; };
+template <bool MAX>
+__device__ inline SlotProbe slots_probe(const double *slots, uint32_t count) {
+  const uint32_t lane = threadIdx.x & 63;
+  SlotProbe r{0.0, count <= 256u};
+#pragma unroll
+  for (uint32_t j = 0; j < 4; ++j) {
+    const uint32_t s = lane + 64 * j;
+    if (s < count && count <= 256u) {
+      double x = __hip_atomic_load(slots + s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      const bool pub = slot_published(x);
+      r.ok = r.ok && pub;
+      x = pub ? x : 0.0;
+      r.v = MAX ? fmax(r.v, x) : r.v + x;
+    }
+  }
+  return r;
+}
+template <bool MAX>
+__device__ inline double slots_finish(const SlotProbe &probe, const double *slots, uint32_t count, uint32_t *status) {
+  if (!__all(probe.ok)) return slots_collect<MAX>(slots, count, status);
+  double v = probe.v;
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    double o = __shfl_xor(v, off, 64);
+    v = MAX ? fmax(v, o) : v + o;
+  }
+  return v;
+}
+
 // Workgroup-wide sum / max of per-thread values (fixed order); result valid in wave 0.
 template <bool MAX, int THREADS>
 __device__ inline double cluster_block_reduce(double x, double *red /*THREADS/64*/) {
@@ -294,6 +328,134 @@ __device__ inline void cluster_run_ticketed(const Op &op, float *table, double *
     // starts late, and its whole partition waits for it)
     __syncthreads();   // the LDS words above are rewritten by the next round
   }
+}
+
+// Lagged ticketed driver: like the ticketed one, but a workgroup finishes a tile only after
+// phase 1 of its next one.  By then the other tiles of the older tile's partition have long
+// been published, so collecting the total costs one read of the slots instead of a wait, and
+// a workgroup never waits while it holds an unpublished tile.  Costs a second copy of `Held`.
+// Every tile taken is published before anything is waited for, so the oldest unpublished tile
+// is always being worked on; with the grid resident and a partition's tiles no more than the
+// grid, every wait ends (the launcher checks both).
+template <class Op>
+__device__ inline void cluster_run_lagged(const Op &op, float *table, double *slots, uint32_t *status) {
+  constexpr int kT = Op::kThreads;
+  constexpr uint32_t kNone = 0xffffffffu;
+  __shared__ double red[kT / 64];
+  __shared__ double total_sh;
+  __shared__ uint32_t item_sh;
+  const uint32_t n_items = op.n_items();
+  typename Op::Held held_prev;
+  uint32_t prev = kNone;
+  if (threadIdx.x == 0) item_sh = atomicAdd(status + 1, 1u);
+  __syncthreads();
+  uint32_t item = __builtin_amdgcn_readfirstlane(item_sh);
+  for (;;) {
+    const bool have = item < n_items;
+    if (!have && prev == kNone) break;
+    typename Op::Held held;
+    if (have) {
+      typename Op::Raw raw;
+      double part = op.phase1(item, raw, held, table);
+      part = cluster_block_reduce<Op::kMax, kT>(part, red);
+      if (threadIdx.x == 0 && op.needs_total()) slot_publish(slots + item, part);
+    }
+    uint32_t ticket = kNone;
+    // (reading the older tile's slots before phase 1, as the lagged persistent driver does,
+    // was slower here: phase 1 of these operators has no registers to spare for the values)
+    if (prev != kNone) {
+      if (threadIdx.x < 64 && op.needs_total()) {
+        uint32_t first, count;
+        op.slots_of(prev, &first, &count);
+        double total = slots_collect<Op::kMax>(slots + first, count, status);
+        if (threadIdx.x == 0) total_sh = total;
+      }
+    }
+    // the next ticket is on its way while the older tile is written out
+    if (have && threadIdx.x == 0) ticket = atomicAdd(status + 1, 1u);
+    if (have) op.early(item, held);
+    __syncthreads();
+    if (prev != kNone) {
+      const double total = total_sh;
+      const typename Op::Ctx ctx = op.begin2(prev, total, table);
+#pragma unroll
+      for (int u = 0; u < Op::kRowsPerTile; ++u) op.row2(prev, u, held_prev, ctx);
+    }
+    if (!have) break;
+    held_prev = held;
+    prev = item;
+    if (threadIdx.x == 0) item_sh = ticket;
+    __syncthreads();
+    item = __builtin_amdgcn_readfirstlane(item_sh);
+  }
+}
+
+// Lagged persistent driver: static striding and the early request of the next tile as in the
+// persistent driver, the older tile finished after phase 1 of the current one as in the
+// lagged ticketed driver.
+template <class Op>
+__device__ inline void cluster_run_persistent_lagged(const Op &op, float *table, double *slots, uint32_t *status) {
+  constexpr int kT = Op::kThreads;
+  constexpr uint32_t kNone = 0xffffffffu;
+  __shared__ double red[kT / 64];
+  __shared__ double total_sh;
+  const uint32_t n_items = op.n_items();
+  uint32_t item = __builtin_amdgcn_readfirstlane(blockIdx.x);
+  if (item >= n_items) return;
+  typename Op::Raw raw;
+#pragma unroll
+  for (int u = 0; u < Op::kRowsPerTile; ++u) op.issue_row(item, u, raw);
+  __builtin_amdgcn_s_waitcnt(0x0F70);
+  typename Op::Held held_prev;
+  uint32_t prev = kNone;
+  for (;;) {
+    typename Op::Held held;
+    // the older tile's slots are read now and looked at after phase 1
+    SlotProbe probe{0.0, false};
+    const bool collects = prev != kNone && threadIdx.x < 64 && op.needs_total();
+    uint32_t first = 0, count = 0;
+    if (collects) {
+      op.slots_of(prev, &first, &count);
+      probe = slots_probe<Op::kMax>(slots + first, count);
+    }
+    double part = op.phase1(item, raw, held, table);
+    const uint32_t next = __builtin_amdgcn_readfirstlane(item + gridDim.x);
+    const bool have_next = next < n_items;
+    if (have_next) {
+#pragma unroll
+      for (int u = 0; u < Op::kRowsPerTile; ++u) op.issue_row(next, u, raw);
+    }
+    part = cluster_block_reduce<Op::kMax, kT>(part, red);
+    if (threadIdx.x == 0 && op.needs_total()) slot_publish(slots + item, part);
+    if (collects) {
+      double total = slots_finish<Op::kMax>(probe, slots + first, count, status);
+      if (threadIdx.x == 0) total_sh = total;
+    }
+    op.early(item, held);
+    __syncthreads();
+    if (prev != kNone) {
+      const typename Op::Ctx ctx = op.begin2(prev, total_sh, table);
+#pragma unroll
+      for (int u = 0; u < Op::kRowsPerTile; ++u) op.row2(prev, u, held_prev, ctx);
+    }
+    held_prev = held;
+    prev = item;
+    if (!have_next) break;
+    item = next;
+    __syncthreads();
+  }
+  // the last tile
+  __syncthreads();
+  if (threadIdx.x < 64 && op.needs_total()) {
+    uint32_t first, count;
+    op.slots_of(prev, &first, &count);
+    double total = slots_collect<Op::kMax>(slots + first, count, status);
+    if (threadIdx.x == 0) total_sh = total;
+  }
+  __syncthreads();
+  const typename Op::Ctx ctx = op.begin2(prev, total_sh, table);
+#pragma unroll
+  for (int u = 0; u < Op::kRowsPerTile; ++u) op.row2(prev, u, held_prev, ctx);
 }
 #endif
 

@@ -2,23 +2,42 @@
 #pragma once
 #include "cluster.hpp"
 #include "kernels.hpp"
+#include <type_traits>
 
 namespace bpc {
 
-// 4 waves per SIMD at least, i.e. at most 128 vector registers a lane.
+// Waves per SIMD the kernel is compiled for: 4 (at most 128 vector registers a lane) unless
+// the operator asks for more with kWavesPerSimd.
+template <class Op, class = void>
+struct waves_per_simd { static constexpr int value = 4; };
 template <class Op>
-__global__ __launch_bounds__(Op::kThreads, 4) void cluster_kernel(const Op op, double *slots, uint32_t *status) {
-  __shared__ float table[Op::kTableFloats];
-  if constexpr (Op::kPersistent) cluster_run_persistent(op, table, slots, status);
+struct waves_per_simd<Op, std::void_t<decltype(Op::kWavesPerSimd)>> { static constexpr int value = Op::kWavesPerSimd; };
+
+// kLagged in an operator selects the lagged form of the ticketed driver.
+template <class Op, class = void>
+struct is_lagged { static constexpr bool value = false; };
+template <class Op>
+struct is_lagged<Op, std::void_t<decltype(Op::kLagged)>> { static constexpr bool value = Op::kLagged; };
+
+template <class Op>
+__device__ inline void cluster_run(const Op &op, float *table, double *slots, uint32_t *status) {
+  if constexpr (Op::kPersistent && is_lagged<Op>::value) cluster_run_persistent_lagged(op, table, slots, status);
+  else if constexpr (Op::kPersistent) cluster_run_persistent(op, table, slots, status);
+  else if constexpr (is_lagged<Op>::value) cluster_run_lagged(op, table, slots, status);
   else cluster_run_ticketed(op, table, slots, status);
+}
+
+template <class Op>
+__global__ __launch_bounds__(Op::kThreads, waves_per_simd<Op>::value) void cluster_kernel(const Op op, double *slots, uint32_t *status) {
+  __shared__ float table[Op::kTableFloats];
+  cluster_run(op, table, slots, status);
 }
 
 // Same, with the operator's LDS scratch allocated at launch (sizes above the static limit).
 template <class Op>
-__global__ __launch_bounds__(Op::kThreads, 4) void cluster_kernel_dyn(const Op op, double *slots, uint32_t *status) {
+__global__ __launch_bounds__(Op::kThreads, waves_per_simd<Op>::value) void cluster_kernel_dyn(const Op op, double *slots, uint32_t *status) {
   extern __shared__ float dyn_table[];
-  if constexpr (Op::kPersistent) cluster_run_persistent(op, dyn_table, slots, status);
-  else cluster_run_ticketed(op, dyn_table, slots, status);
+  cluster_run(op, dyn_table, slots, status);
 }
 
 // Launches `op` over the tiles of `cg`.  *used = false (and nothing is enqueued) when the

@@ -6,7 +6,16 @@
 
 namespace bpc {
 
-constexpr int kDRows = kCPerThread / 8;  // 4 rows of 8192 elements; a thread owns 8 consecutive per row
+#ifndef DW_T
+#define DW_T 1024
+#define DW_PER 16
+#define DW_W 4
+#define DW_LAG 1
+#endif
+constexpr int kDWThreads = DW_T;
+constexpr int kDWPer = DW_PER;
+constexpr int kDWTile = kDWThreads * kDWPer;
+constexpr int kDRows = kDWPer / 8;  // rows of kDWThreads * 8 elements; a thread owns 8 consecutive per row
 
 struct F32x8 { u32x4 a, b; };
 template <class G> struct Vec8Of;
@@ -28,23 +37,25 @@ __device__ inline void widen8(const u32x4 &g, float out[8]) {
 }
 // 8 consecutive gradient elements of thread t in row u of a tile window
 __device__ inline F32x8 tile_load8(const TileBuf &b, int u, const float *) {
-  return {b.load16(threadIdx.x * 32, u * (kWThreads * 32)), b.load16(threadIdx.x * 32 + 16, u * (kWThreads * 32))};
+  return {b.load16(threadIdx.x * 32, u * (kDWThreads * 32)), b.load16(threadIdx.x * 32 + 16, u * (kDWThreads * 32))};
 }
 __device__ inline u32x4 tile_load8(const TileBuf &b, int u, const __half *) {
-  return b.load16(threadIdx.x * 16, u * (kWThreads * 16));
+  return b.load16(threadIdx.x * 16, u * (kDWThreads * 16));
 }
 
 template <class G, bool EF, bool LINF, bool NAT>
 struct DitherWorkerOp {
   using GV = typename Vec8Of<G>::type;
   struct Raw { GV g[kDRows]; F32x8 e[kDRows]; };
-  struct Held { float q[kCPerThread]; };
+  struct Held { float q[kDWPer]; };
   static constexpr bool kMax = LINF;
   static constexpr int kRowsPerTile = kDRows;
   static constexpr int kTableFloats = 8;
   static constexpr size_t kMaxDynLds = 0;
-  static constexpr int kThreads = kWThreads;
+  static constexpr int kThreads = kDWThreads;
   static constexpr bool kPersistent = true;
+  static constexpr bool kLagged = DW_LAG != 0;
+  static constexpr int kWavesPerSimd = DW_W;
   // f32 gradients: the raw loads of a whole tile plus q do not fit the register budget
   static constexpr Prefetch kPrefetch = sizeof(G) == 2 ? Prefetch::kSplit : Prefetch::kInterleaved;
   struct Ctx { float nu, top_over_nu; int mode; const float *mag; };
@@ -61,12 +72,12 @@ struct DitherWorkerOp {
   __device__ uint32_t n_items() const { return cg.n_items; }
   __device__ bool needs_total() const { return override == nullptr; }
   __device__ uint32_t part_of(uint32_t item) const { return __builtin_amdgcn_readfirstlane(item / cg.tiles_per_part); }
-  __device__ uint32_t tile_off(uint32_t item) const { return __builtin_amdgcn_readfirstlane((item % cg.tiles_per_part) * kWTile); }
+  __device__ uint32_t tile_off(uint32_t item) const { return __builtin_amdgcn_readfirstlane((item % cg.tiles_per_part) * kDWTile); }
   __device__ uint64_t base(uint32_t item) const { return uniform_off(g.part_base(part_of(item)) + tile_off(item)); }
   __device__ void slots_of(uint32_t item, uint32_t *first, uint32_t *count) const {
     uint32_t p = part_of(item);
     *first = p * cg.tiles_per_part;
-    *count = (uint32_t)cdiv(g.part_size(p), kWTile);
+    *count = (uint32_t)cdiv(g.part_size(p), kDWTile);
   }
 
   // Elements of the tile that lie inside its partition.  Every tile access goes through a
@@ -74,7 +85,7 @@ struct DitherWorkerOp {
   // nothing for the norm, level 0) and stores past it are dropped.
   __device__ uint32_t valid_of(uint32_t item) const {
     const uint32_t left = g.part_size(part_of(item)) - tile_off(item);
-    return __builtin_amdgcn_readfirstlane(left < (uint32_t)kWTile ? left : (uint32_t)kWTile);
+    return __builtin_amdgcn_readfirstlane(left < (uint32_t)kDWTile ? left : (uint32_t)kDWTile);
   }
   __device__ void issue_first(uint32_t item, int u, Raw &raw) const {
     raw.g[u] = tile_load8(TileBuf(grad + base(item), valid_of(item) * sizeof(G)), u, grad);
@@ -142,7 +153,7 @@ struct DitherWorkerOp {
     const Philox rng(seed, stream_id, p);
     const uint64_t b = base(item);
     uint32_t *nibs = reinterpret_cast<uint32_t *>(payload + (uint64_t)p * g.stride + kHeaderBytes);
-    const uint32_t off = (u * kWThreads + threadIdx.x) * 8;  // within the tile
+    const uint32_t off = (u * kDWThreads + threadIdx.x) * 8;  // within the tile
     const uint32_t j0 = tile_off(item) + off;                // within the partition
     uint32_t word = 0;
     float r[8];
@@ -157,9 +168,9 @@ struct DitherWorkerOp {
       for (int c = 0; c < 8; ++c)
         word |= dither_quantise<MODE == 2, NAT>(h.q[8 * u + c], nu, top_over_nu, top, levels, rnd[c], mag, &r[c]) << (4 * c);
     }
-    TileBuf(nibs + (tile_off(item) >> 3), kWTile / 2).store4(word, threadIdx.x * 4, u * (kWThreads * 4));
+    TileBuf(nibs + (tile_off(item) >> 3), kDWTile / 2).store4(word, threadIdx.x * 4, u * (kDWThreads * 4));
     if (EF) {
-      const TileBuf ob = row_buf(res + b, valid_of(item), u * (kWThreads * 8), kWThreads * 8);
+      const TileBuf ob = row_buf(res + b, valid_of(item), u * (kDWThreads * 8), kDWThreads * 8);
       ob.store16(as_u32x4(r[0], r[1], r[2], r[3]), threadIdx.x * 32);
       ob.store16(as_u32x4(r[4], r[5], r[6], r[7]), threadIdx.x * 32 + 16);
     }
@@ -187,7 +198,7 @@ static hipError_t launch_dither(const Geo &g, const ClusterGeo &cg, const bpc_pa
 
 hipError_t dither_worker_single_pass(const Geo &g, const bpc_params_t &prm, const Source &src, uint8_t *payload,
                                      const Workspace &ws, hipStream_t stream, bool *used) {
-  ClusterGeo cg = make_cluster_geo(g, kWTile);
+  ClusterGeo cg = make_cluster_geo(g, kDWTile);
   double *slots = ws.at<double>(ws.lay.slots);
   uint32_t *status = ws.at<uint32_t>(ws.lay.status);
   const bool f16 = src.dtype == BPC_F16;

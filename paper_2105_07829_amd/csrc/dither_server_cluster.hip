@@ -4,15 +4,16 @@
 // once, keeps Delta in registers, exchanges its part of ||Delta||_2^2 (or max |Delta|) and
 // then writes the packed levels and e~'.
 //
-// A thread owns 8 consecutive elements per row (4 rows of 2048 elements), i.e. one 32-bit word
-// of every worker's nibbles per row.  A nibble indexes a 16-entry LDS table per worker that
-// holds the decoded values +-(nu_i * level) / s.
+// A thread owns 8 consecutive elements per row, i.e. one 32-bit word of every worker's nibbles
+// per row.  A nibble indexes a 16-entry LDS table per worker that holds the decoded values
+// +-(nu_i * level) / s (16 consecutive floats: lanes never conflict on a bank).  With the
+// number of workers known at compile time the workgroup has 512 threads and two rows, so that
+// all its words of all workers are requested at once and still fit the register file next to
+// e~ and the sums; otherwise 256 threads, four rows and a rolled loop over the workers.
 #include "dither_common.hpp"
 #include "sources.hpp"
 
 namespace bpc {
-
-constexpr int kDSRows = kCPerThread / 8;   // 4
 
 struct DMsgPtrs {
   const uint8_t *ptr[kMaxWorkers];
@@ -30,15 +31,18 @@ inline DMsgPtrs dmsg_ptrs(const WorkerMsgs &m) {
 // NW > 0: number of workers known at compile time (unrolled); NW == 0: rolled loop.
 template <bool EF, bool LINF, int NW, bool NAT>
 struct DitherServerOp {
+  static constexpr int kThreads = NW > 0 ? 512 : kSThreads;
+  static constexpr int kDSRows = kSTile / (kThreads * 8);   // 2 or 4
+  static constexpr int kPerThread = 8 * kDSRows;
   struct Raw { u32x4 e[2 * kDSRows]; };
-  struct Held { float delta[kCPerThread]; };
+  struct Held { float delta[kPerThread]; };
   struct Ctx { float nu, top_over_nu; int mode; const float *mag; };
   static constexpr bool kMax = LINF;
   static constexpr int kRowsPerTile = kDSRows;
   static constexpr int kTableFloats = kMaxWorkers * 16 + 8;   // decode tables, then the 8 output magnitudes
   static constexpr size_t kMaxDynLds = 0;
-  static constexpr int kThreads = kSThreads;
   static constexpr bool kPersistent = false;
+  static constexpr bool kLagged = true;
 
   Geo g;
   ClusterGeo cg;
@@ -71,7 +75,7 @@ struct DitherServerOp {
   }
   __device__ void issue_row(uint32_t item, int u, Raw &raw) const {
     if (!EF) return;
-    const TileBuf eb = row_buf(res + base(item), valid_of(item), u * (kSThreads * 8), kSThreads * 8);
+    const TileBuf eb = row_buf(res + base(item), valid_of(item), u * (kThreads * 8), kThreads * 8);
     raw.e[2 * u] = eb.load16(threadIdx.x * 32, 0);
     raw.e[2 * u + 1] = eb.load16(threadIdx.x * 32 + 16, 0);
   }
@@ -79,7 +83,7 @@ struct DitherServerOp {
   // Decode tables of all workers for partition p: lut[i*16 + nibble].
   __device__ void fill_luts(uint32_t p, float *lut) const {
     __syncthreads();
-    for (int e = threadIdx.x; e < msgs.n * 16; e += kSThreads) {
+    for (int e = threadIdx.x; e < msgs.n * 16; e += kThreads) {
       const int i = e >> 4, nib = e & 15;
       const float nu = *reinterpret_cast<const float *>(msgs.ptr[i] + (uint64_t)p * g.stride);
       const float mag = dither_mag(nu, nib & 7, levels, NAT);
@@ -93,14 +97,24 @@ struct DitherServerOp {
     const uint32_t *nibs = reinterpret_cast<const uint32_t *>(
         msgs.ptr[i] + uniform_off((uint64_t)part_of(item) * g.stride + kHeaderBytes + (tile_off(item) >> 1)));
 #pragma unroll
-    for (int u = 0; u < kDSRows; ++u) out[u] = nibs[u * kSThreads + threadIdx.x];
+    for (int u = 0; u < kDSRows; ++u) out[u] = nibs[u * kThreads + threadIdx.x];
   }
 
-  __device__ static void add_worker(const uint32_t word[kDSRows], const float *lut_i, float acc[kCPerThread]) {
+  // The byte offsets nibble*4 of a word's eight nibbles into a worker's table: after a shift
+  // by two either way, every nibble sits at bits 2..5 of a byte.
+  __device__ static void add_worker(const uint32_t word[kDSRows], const float *lut_i, float acc[kPerThread]) {
+    const char *lut_b = reinterpret_cast<const char *>(lut_i);
 #pragma unroll
     for (int u = 0; u < kDSRows; ++u) {
+      const uint32_t even = word[u] << 2, odd = word[u] >> 2;
+      float v[8];
 #pragma unroll
-      for (int c = 0; c < 8; ++c) acc[8 * u + c] = acc[8 * u + c] + lut_i[(word[u] >> (4 * c)) & 15u];
+      for (int k = 0; k < 4; ++k) {
+        v[2 * k] = *reinterpret_cast<const float *>(lut_b + ((even >> (8 * k)) & 0x3cu));
+        v[2 * k + 1] = *reinterpret_cast<const float *>(lut_b + ((odd >> (8 * k)) & 0x3cu));
+      }
+#pragma unroll
+      for (int c = 0; c < 8; ++c) acc[8 * u + c] = acc[8 * u + c] + v[c];
     }
   }
 
@@ -108,21 +122,19 @@ struct DitherServerOp {
     const uint32_t p = part_of(item);
 #pragma unroll
     for (int u = 0; u < kDSRows; ++u) issue_row(item, u, raw);
-    fill_luts(p, table);
-    float acc[kCPerThread];
+    float acc[kPerThread];
 #pragma unroll
-    for (int k = 0; k < kCPerThread; ++k) acc[k] = 0.0f;
+    for (int k = 0; k < kPerThread; ++k) acc[k] = 0.0f;
     if (NW > 0) {
-      constexpr int kGroup = NW == 0 ? 1 : NW < 4 ? NW : 4;
+      // every word of every worker is requested before the tables are built
+      uint32_t word[NW > 0 ? NW : 1][kDSRows];
 #pragma unroll
-      for (int i0 = 0; i0 < NW; i0 += kGroup) {
-        uint32_t word[kGroup][kDSRows];
+      for (int i = 0; i < NW; ++i) load_words(item, i, word[i]);
+      fill_luts(p, table);
 #pragma unroll
-        for (int k = 0; k < kGroup; ++k) load_words(item, i0 + k, word[k]);
-#pragma unroll
-        for (int k = 0; k < kGroup; ++k) add_worker(word[k], table + (i0 + k) * 16, acc);
-      }
+      for (int i = 0; i < NW; ++i) add_worker(word[i], table + i * 16, acc);
     } else {
+      fill_luts(p, table);
       for (int i = 0; i < msgs.n; ++i) {
         uint32_t word[kDSRows];
         load_words(item, i, word);
@@ -138,7 +150,7 @@ struct DitherServerOp {
       const float e[8] = {__uint_as_float(ea.x), __uint_as_float(ea.y), __uint_as_float(ea.z), __uint_as_float(ea.w),
                           __uint_as_float(eb.x), __uint_as_float(eb.y), __uint_as_float(eb.z), __uint_as_float(eb.w)};
       // elements of this thread's row segment that exist
-      const uint32_t seg0 = (u * kSThreads + threadIdx.x) * 8;
+      const uint32_t seg0 = (u * kThreads + threadIdx.x) * 8;
       const uint32_t have = valid > seg0 ? valid - seg0 : 0u;
 #pragma unroll
       for (int c = 0; c < 8; ++c) {
@@ -176,13 +188,13 @@ struct DitherServerOp {
   __device__ void row2_body(uint32_t item, int u, Held &h, const Ctx &ctx) const {
     const uint32_t p = part_of(item);
     const Philox rng(seed, stream_id, p);
-    const uint32_t j0 = tile_off(item) + (u * kSThreads + threadIdx.x) * 8;
+    const uint32_t j0 = tile_off(item) + (u * kThreads + threadIdx.x) * 8;
     float r[8];
     const uint32_t word = dither_row<MODE, NAT>(&h.delta[8 * u], ctx.nu, ctx.top_over_nu, dither_top(levels, NAT), levels, rng, j0, ctx.mag, r);
     uint32_t *nibs = reinterpret_cast<uint32_t *>(payload + (uint64_t)p * g.stride + kHeaderBytes);
-    (nibs + uniform_off((tile_off(item) + u * (kSThreads * 8)) >> 3))[threadIdx.x] = word;
+    (nibs + uniform_off((tile_off(item) + u * (kThreads * 8)) >> 3))[threadIdx.x] = word;
     if (EF) {
-      const TileBuf ob = row_buf(res + base(item), valid_of(item), u * (kSThreads * 8), kSThreads * 8);
+      const TileBuf ob = row_buf(res + base(item), valid_of(item), u * (kThreads * 8), kThreads * 8);
       ob.store16(as_u32x4(r[0], r[1], r[2], r[3]), threadIdx.x * 32);
       ob.store16(as_u32x4(r[4], r[5], r[6], r[7]), threadIdx.x * 32 + 16);
     }

@@ -7,7 +7,16 @@
 
 namespace bpc {
 
-constexpr int kRows = kCPerThread / 4;  // 8 rows of 4096 elements; a thread owns 4 consecutive per row
+#ifndef W_T
+#define W_T 1024
+#define W_PER 16
+#define W_W 4
+#define W_LAG 1
+#endif
+constexpr int kSWThreads = W_T;
+constexpr int kSWPer = W_PER;
+constexpr int kSWTile = kSWThreads * kSWPer;
+constexpr int kRows = kSWPer / 4;  // rows of kSWThreads * 4 elements; a thread owns 4 consecutive per row
 
 __device__ inline void widen4(const u32x4 &g, float out[4]) {
   out[0] = __uint_as_float(g.x); out[1] = __uint_as_float(g.y); out[2] = __uint_as_float(g.z); out[3] = __uint_as_float(g.w);
@@ -43,13 +52,15 @@ template <class G, bool EF>
 struct SignWorkerOp {
   using GV = typename Vec4Of<G>::type;
   struct Raw { GV g[kRows]; u32x4 e[kRows]; };
-  struct Held { float q[kCPerThread]; };
+  struct Held { float q[kSWPer]; };
   static constexpr bool kMax = false;
   static constexpr int kRowsPerTile = kRows;
   static constexpr int kTableFloats = 1;
   static constexpr size_t kMaxDynLds = 0;
-  static constexpr int kThreads = kWThreads;
+  static constexpr int kThreads = kSWThreads;
   static constexpr bool kPersistent = true;
+  static constexpr bool kLagged = W_LAG != 0;
+  static constexpr int kWavesPerSimd = W_W;
   // f32 gradients: the raw loads of a whole tile plus q do not fit the register budget
   static constexpr Prefetch kPrefetch = sizeof(G) == 2 ? Prefetch::kEarly : Prefetch::kSplit;
   struct Ctx { float sigma; };
@@ -64,19 +75,19 @@ struct SignWorkerOp {
   __device__ uint32_t n_items() const { return cg.n_items; }
   __device__ bool needs_total() const { return override == nullptr; }
   __device__ uint32_t part_of(uint32_t item) const { return __builtin_amdgcn_readfirstlane(item / cg.tiles_per_part); }
-  __device__ uint32_t tile_off(uint32_t item) const { return __builtin_amdgcn_readfirstlane((item % cg.tiles_per_part) * kWTile); }
+  __device__ uint32_t tile_off(uint32_t item) const { return __builtin_amdgcn_readfirstlane((item % cg.tiles_per_part) * kSWTile); }
   __device__ uint64_t base(uint32_t item) const { return uniform_off(g.part_base(part_of(item)) + tile_off(item)); }
   __device__ void slots_of(uint32_t item, uint32_t *first, uint32_t *count) const {
     uint32_t p = part_of(item);
     *first = p * cg.tiles_per_part;
-    *count = (uint32_t)cdiv(g.part_size(p), kWTile);
+    *count = (uint32_t)cdiv(g.part_size(p), kSWTile);
   }
   // Elements of the tile that lie inside its partition.  Every tile access goes through a
   // buffer descriptor of exactly that many elements: loads past it return 0 (q = 0 there:
   // nothing for the norm, a clear sign bit) and stores past it are dropped.
   __device__ uint32_t valid_of(uint32_t item) const {
     const uint32_t left = g.part_size(part_of(item)) - tile_off(item);
-    return __builtin_amdgcn_readfirstlane(left < (uint32_t)kWTile ? left : (uint32_t)kWTile);
+    return __builtin_amdgcn_readfirstlane(left < (uint32_t)kSWTile ? left : (uint32_t)kSWTile);
   }
   __device__ uint32_t *bits_of(uint32_t p) const {
     return reinterpret_cast<uint32_t *>(payload + (uint64_t)p * g.stride + kHeaderBytes);
@@ -84,12 +95,12 @@ struct SignWorkerOp {
 
   __device__ void issue_first(uint32_t item, int u, Raw &raw) const {
     const TileBuf gb(grad + base(item), valid_of(item) * sizeof(G));
-    raw.g[u] = tile_load4(gb, threadIdx.x * (4 * sizeof(G)), u * (kWThreads * 4 * sizeof(G)), grad);
+    raw.g[u] = tile_load4(gb, threadIdx.x * (4 * sizeof(G)), u * (kSWThreads * 4 * sizeof(G)), grad);
   }
   __device__ void issue_second(uint32_t item, int u, Raw &raw) const {
     if (EF) {
       const TileBuf eb(res + base(item), valid_of(item) * 4);
-      raw.e[u] = eb.load16<kNonTemporal>(threadIdx.x * 16, u * (kWThreads * 16));
+      raw.e[u] = eb.load16<kNonTemporal>(threadIdx.x * 16, u * (kSWThreads * 16));
     }
   }
   __device__ void issue_row(uint32_t item, int u, Raw &raw) const {
@@ -116,7 +127,7 @@ struct SignWorkerOp {
   }
 
   __device__ void early(uint32_t item, Held &h) const {
-    const TileBuf bb(bits_of(part_of(item)) + (tile_off(item) >> 5), kWTile / 8);
+    const TileBuf bb(bits_of(part_of(item)) + (tile_off(item) >> 5), kSWTile / 8);
     const uint32_t t = threadIdx.x;
 #pragma unroll
     for (int u = 0; u < kRows; ++u) {
@@ -124,7 +135,7 @@ struct SignWorkerOp {
 #pragma unroll
       for (int c = 0; c < 4; ++c) nib |= (h.q[4 * u + c] < 0.0f ? 1u : 0u) << c;
       uint32_t word = merge8(nib);
-      if ((t & 7) == 0) bb.store4<kNonTemporal>(word, (t >> 3) * 4, u * (kWThreads * 4 / 8));
+      if ((t & 7) == 0) bb.store4<kNonTemporal>(word, (t >> 3) * 4, u * (kSWThreads * 4 / 8));
     }
   }
 
@@ -148,7 +159,7 @@ struct SignWorkerOp {
   __device__ void row2(uint32_t item, int u, Held &h, const Ctx &ctx) const {
     if (!EF) return;
     const float sigma = ctx.sigma;
-    const TileBuf ob = row_buf(res + base(item), valid_of(item), u * (kWThreads * 4), kWThreads * 4);
+    const TileBuf ob = row_buf(res + base(item), valid_of(item), u * (kSWThreads * 4), kSWThreads * 4);
     float o[4];
 #pragma unroll
     for (int c = 0; c < 4; ++c) o[c] = h.q[4 * u + c] - (h.q[4 * u + c] < 0.0f ? -sigma : sigma);
@@ -161,7 +172,7 @@ struct SignWorkerOp {
 // (the caller then takes the multi-pass path).
 hipError_t sign_worker_single_pass(const Geo &g, const bpc_params_t &prm, const Source &src, uint8_t *payload,
                                    const Workspace &ws, hipStream_t stream, bool *used) {
-  ClusterGeo cg = make_cluster_geo(g, kWTile);
+  ClusterGeo cg = make_cluster_geo(g, kSWTile);
   double *slots = ws.at<double>(ws.lay.slots);
   uint32_t *status = ws.at<uint32_t>(ws.lay.status);
   const bool f16 = src.dtype == BPC_F16;

@@ -3,15 +3,26 @@
 // tile of e~ and the matching bits of the n messages once, keeps Delta in registers, writes
 // the sign bits of Delta, exchanges its part of ||Delta||_1 and writes e~' = Delta -+ sigma.
 //
-// A thread owns 8 consecutive elements per row (4 rows of 2048 elements per tile), i.e. one
-// byte of every worker's sign bits per row; shifting a bit to the sign position and merging it
-// into |sigma_i| gives +-sigma_i in two instructions.
+// A thread owns 8 consecutive elements per row (2 rows of 4096 elements per tile, 512 threads),
+// i.e. one byte of every worker's sign bits per row; shifting a bit to the sign position and
+// merging it into |sigma_i| gives +-sigma_i in two instructions.  16 elements a thread keep a
+// lane under 64 vector registers, so 8 waves per SIMD are resident: the n-term sums of some
+// tiles then run under the loads and stores of others.
 #include "cluster_launch.hpp"
 #include "sources.hpp"
 
 namespace bpc {
 
-constexpr int kSRows = kCPerThread / 8;   // 4
+#ifndef SS_T
+#define SS_T 512
+#define SS_TILE 8192
+#define SS_W 6
+#endif
+constexpr int kSSThreads = SS_T;
+constexpr int kSSTile = SS_TILE;
+constexpr int kSSWaves = kSSThreads / 64;
+constexpr int kSRows = kSSTile / (kSSThreads * 8);   // 2
+constexpr int kSPerThread = 8 * kSRows;
 
 // Just the message pointers (the random-stream fields of WorkerMsgs are not needed here).
 struct MsgPtrs {
@@ -28,25 +39,36 @@ inline MsgPtrs msg_ptrs(const WorkerMsgs &m) {
 }
 
 // -|sigma| if bit C of `byte` is set, else +|sigma|: the bit is shifted to the sign position
-// and merged into the magnitude (`mag` has a clear sign bit).
+// and the magnitude takes its sign from there (one shift and one bit-field insert).
 template <int C>
 __device__ inline float pick_sign(uint32_t byte, uint32_t mag) {
-  return __uint_as_float(((byte << (31 - C)) & 0x80000000u) | mag);
+  return __builtin_copysignf(__uint_as_float(mag), __uint_as_float(byte << (31 - C)));
 }
 
 // NW > 0: the number of workers is known at compile time and the worker loop is unrolled, so
 // the byte loads can be scheduled ahead of their use; NW == 0: any number, rolled loop.
 template <bool EF, int NW>
 struct SignServerOp {
-  struct Raw { u32x4 e[2 * kSRows]; };
-  struct Held { float delta[kCPerThread]; };
+  // loads of a tile: its rows of e~, this wave's share of the workers' bits, a worker's scale
+  struct Raw {
+    u32x4 e[2 * kSRows];
+    u32x4 fetched[NW > 0 ? (NW * (kSSTile / 8192) + kSSWaves - 1) / kSSWaves : 1];
+    float my_sigma;
+  };
+  struct Held { float delta[kSPerThread]; };
   static constexpr bool kMax = false;
   static constexpr int kRowsPerTile = kSRows;
   // LDS: the n scales, then (NW > 0) the tile's sign bits of every worker, 1 KiB each
-  static constexpr int kBitsPerWorker = kSTile / 8;   // bytes
+  static constexpr int kBitsPerWorker = kSSTile / 8;   // bytes
   static constexpr int kTableFloats = kMaxWorkers + (NW > 0 ? NW * kBitsPerWorker / 4 : 0);
-  static constexpr int kThreads = kSThreads;
-  static constexpr bool kPersistent = false;
+  static constexpr int kThreads = kSSThreads;
+  static constexpr int kWavesPerSimd = SS_W;
+#ifndef SS_P
+#define SS_P 0
+#endif
+  static constexpr bool kPersistent = SS_P != 0;
+  static constexpr Prefetch kPrefetch = Prefetch::kEarly;
+  static constexpr bool kLagged = true;
   static constexpr size_t kMaxDynLds = 0;
   struct Ctx { float sigma; };
 
@@ -60,12 +82,12 @@ struct SignServerOp {
   __device__ uint32_t n_items() const { return cg.n_items; }
   __device__ bool needs_total() const { return override == nullptr; }
   __device__ uint32_t part_of(uint32_t item) const { return __builtin_amdgcn_readfirstlane(item / cg.tiles_per_part); }
-  __device__ uint32_t tile_off(uint32_t item) const { return __builtin_amdgcn_readfirstlane((item % cg.tiles_per_part) * kSTile); }
+  __device__ uint32_t tile_off(uint32_t item) const { return __builtin_amdgcn_readfirstlane((item % cg.tiles_per_part) * kSSTile); }
   __device__ uint64_t base(uint32_t item) const { return uniform_off(g.part_base(part_of(item)) + tile_off(item)); }
   __device__ void slots_of(uint32_t item, uint32_t *first, uint32_t *count) const {
     uint32_t p = part_of(item);
     *first = p * cg.tiles_per_part;
-    *count = (uint32_t)cdiv(g.part_size(p), kSTile);
+    *count = (uint32_t)cdiv(g.part_size(p), kSSTile);
   }
   __device__ static uint32_t lane() { return threadIdx.x & 63; }
 
@@ -76,23 +98,45 @@ struct SignServerOp {
   // zero bits.
   __device__ uint32_t valid_of(uint32_t item) const {
     const uint32_t left = g.part_size(part_of(item)) - tile_off(item);
-    return __builtin_amdgcn_readfirstlane(left < (uint32_t)kSTile ? left : (uint32_t)kSTile);
+    return __builtin_amdgcn_readfirstlane(left < (uint32_t)kSSTile ? left : (uint32_t)kSSTile);
   }
+  // A worker's bits of a tile are fetched in pieces of 1 KiB (16 bytes a lane, 8192 elements);
+  // piece j = (worker j / kPieces, part j % kPieces) is fetched by wave j % kSSWaves.
+  static constexpr int kPieces = kSSTile / 8192;
+  static_assert(kSSTile % 8192 == 0, "tile must be whole pieces");
+  // Row u of e~; with row 0 also the scale of worker threadIdx.x and (NW > 0) the tile's sign
+  // bits, all in one round trip.
   __device__ void issue_row(uint32_t item, int u, Raw &raw) const {
-    if (!EF) return;
-    const TileBuf eb = row_buf(res + base(item), valid_of(item), u * (kSThreads * 8), kSThreads * 8);
-    raw.e[2 * u] = eb.load16(threadIdx.x * 32, 0);
-    raw.e[2 * u + 1] = eb.load16(threadIdx.x * 32 + 16, 0);
+    if (EF) {
+      const TileBuf eb = row_buf(res + base(item), valid_of(item), u * (kSSThreads * 8), kSSThreads * 8);
+      raw.e[2 * u] = eb.load16(threadIdx.x * 32, 0);
+      raw.e[2 * u + 1] = eb.load16(threadIdx.x * 32 + 16, 0);
+    }
+    if (u != 0) return;
+    const uint32_t p = part_of(item);
+    raw.my_sigma = 0.0f;
+    if ((int)threadIdx.x < msgs.n)
+      raw.my_sigma = *reinterpret_cast<const float *>(msgs.ptr[threadIdx.x] + (uint64_t)p * g.stride);
+    if (NW > 0) {
+      const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+      const uint64_t rec_off = uniform_off((uint64_t)p * g.stride + kHeaderBytes + (tile_off(item) >> 3));
+#pragma unroll
+      for (int j = 0; j < NW * kPieces; ++j)
+        if ((uint32_t)(j % kSSWaves) == wave) {
+          const TileBuf mb(msgs.ptr[j / kPieces] + rec_off + (j % kPieces) * 1024, 1024);
+          raw.fetched[j / kSSWaves] = mb.load16(lane * 16, 0);
+        }
+    }
   }
 
   // The byte of worker i's sign bits that covers this thread's 8 elements of each row.
   __device__ void load_bytes(uint32_t item, int i, uint32_t out[kSRows]) const {
     const uint8_t *bits = msgs.ptr[i] + uniform_off((uint64_t)part_of(item) * g.stride + kHeaderBytes + (tile_off(item) >> 3));
 #pragma unroll
-    for (int u = 0; u < kSRows; ++u) out[u] = bits[u * kSThreads + threadIdx.x];
+    for (int u = 0; u < kSRows; ++u) out[u] = bits[u * kSSThreads + threadIdx.x];
   }
 
-  __device__ void add_worker(const uint32_t byte[kSRows], float sigma_i, float acc[kCPerThread]) const {
+  __device__ void add_worker(const uint32_t byte[kSRows], float sigma_i, float acc[kSPerThread]) const {
     // decode is bit ? -sigma : sigma.  With |sigma| and, for a negative sigma, inverted bits
     // this is bit' ? -|sigma| : |sigma| for every finite sigma.
     const uint32_t raw_sigma = __float_as_uint(sigma_i);
@@ -113,41 +157,33 @@ struct SignServerOp {
   }
 
   __device__ double phase1(uint32_t item, Raw &raw, Held &h, float *sig) const {
-    const uint32_t p = part_of(item);
-    // everything the tile needs is requested in one go: its own e~, the n scales and (NW > 0)
-    // the tile's sign bits of every worker
+    if (!kPersistent) {
 #pragma unroll
-    for (int u = 0; u < kSRows; ++u) issue_row(item, u, raw);
-    float acc[kCPerThread];
+      for (int u = 0; u < kSRows; ++u) issue_row(item, u, raw);
+    }
+    float acc[kSPerThread];
 #pragma unroll
-    for (int k = 0; k < kCPerThread; ++k) acc[k] = 0.0f;
-    float my_sigma = 0.0f;
-    if ((int)threadIdx.x < msgs.n)
-      my_sigma = *reinterpret_cast<const float *>(msgs.ptr[threadIdx.x] + (uint64_t)p * g.stride);
+    for (int k = 0; k < kSPerThread; ++k) acc[k] = 0.0f;
+    const float my_sigma = raw.my_sigma;
     if (NW > 0) {
-      // The bits come in with one 16-byte load per 128 elements and worker (wave w fetches
-      // workers w, w+4, ...: one round trip for everything instead of one per group of byte
-      // loads) and are handed out through LDS.
+      // the bits are handed out through LDS
       uint8_t *staged = reinterpret_cast<uint8_t *>(sig + kMaxWorkers);
-      const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-      const uint64_t rec_off = uniform_off((uint64_t)p * g.stride + kHeaderBytes + (tile_off(item) >> 3));
-      u32x4 fetched[NW > 0 ? (NW + 3) / 4 : 1];
-#pragma unroll
-      for (int i = 0; i < NW; ++i)
-        if ((uint32_t)(i & 3) == wave)
-          fetched[i >> 2] = reinterpret_cast<const u32x4 *>(msgs.ptr[i] + rec_off)[lane];
+      const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+      const u32x4 *fetched = raw.fetched;
       __syncthreads();   // the LDS scratch may still be in use by the caller
       if ((int)threadIdx.x < msgs.n) sig[threadIdx.x] = my_sigma;
 #pragma unroll
-      for (int i = 0; i < NW; ++i)
-        if ((uint32_t)(i & 3) == wave)
-          reinterpret_cast<u32x4 *>(staged + i * kBitsPerWorker)[lane] = fetched[i >> 2];
+      for (int j = 0; j < NW * kPieces; ++j)
+        if ((uint32_t)(j % kSSWaves) == wave)
+          reinterpret_cast<u32x4 *>(staged + (j / kPieces) * kBitsPerWorker + (j % kPieces) * 1024)[lane] = fetched[j / kSSWaves];
       __syncthreads();
-#pragma unroll
+      // four workers per trip: unrolled further, the LDS reads of all workers would be in
+      // flight at once and cost more registers than a lane has at this occupancy
+#pragma unroll 4
       for (int i = 0; i < NW; ++i) {
         uint32_t byte[kSRows];
 #pragma unroll
-        for (int u = 0; u < kSRows; ++u) byte[u] = staged[i * kBitsPerWorker + u * kSThreads + threadIdx.x];
+        for (int u = 0; u < kSRows; ++u) byte[u] = staged[i * kBitsPerWorker + u * kSSThreads + threadIdx.x];
         add_worker(byte, sig[i], acc);
       }
     } else {
@@ -168,7 +204,7 @@ struct SignServerOp {
       const float e[8] = {__uint_as_float(ea.x), __uint_as_float(ea.y), __uint_as_float(ea.z), __uint_as_float(ea.w),
                           __uint_as_float(eb.x), __uint_as_float(eb.y), __uint_as_float(eb.z), __uint_as_float(eb.w)};
       // elements of this thread's row segment that exist
-      const uint32_t seg0 = (u * kSThreads + threadIdx.x) * 8;
+      const uint32_t seg0 = (u * kSSThreads + threadIdx.x) * 8;
       const uint32_t have = valid > seg0 ? valid - seg0 : 0u;
 #pragma unroll
       for (int c = 0; c < 8; ++c) {
@@ -193,7 +229,7 @@ struct SignServerOp {
       // DPP row_shl:n reads lane i+n of the 16-lane row (0 past its end)
       byte |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)byte, 0x101, 0xf, 0xf, true) << 8;
       byte |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)byte, 0x102, 0xf, 0xf, true) << 16;
-      uint32_t *row_words = bits + uniform_off((tile_off(item) >> 5) + u * (kSThreads * 8 / 32));
+      uint32_t *row_words = bits + uniform_off((tile_off(item) >> 5) + u * (kSSThreads * 8 / 32));
       if ((threadIdx.x & 3) == 0) row_words[threadIdx.x >> 2] = byte;
     }
   }
@@ -217,7 +253,7 @@ struct SignServerOp {
   __device__ void row2(uint32_t item, int u, Held &h, const Ctx &ctx) const {
     if (!EF) return;
     const float sigma = ctx.sigma;
-    const TileBuf ob = row_buf(res + base(item), valid_of(item), u * (kSThreads * 8), kSThreads * 8);
+    const TileBuf ob = row_buf(res + base(item), valid_of(item), u * (kSSThreads * 8), kSSThreads * 8);
     float r[8];
 #pragma unroll
     for (int c = 0; c < 8; ++c) r[c] = h.delta[8 * u + c] - (h.delta[8 * u + c] < 0.0f ? -sigma : sigma);
@@ -243,7 +279,7 @@ static hipError_t launch_sign_server(const Geo &g, const ClusterGeo &cg, const b
 
 hipError_t sign_server_single_pass(const Geo &g, const bpc_params_t &prm, const Source &src, uint8_t *payload,
                                    const Workspace &ws, hipStream_t stream, bool *used) {
-  ClusterGeo cg = make_cluster_geo(g, kSTile);
+  ClusterGeo cg = make_cluster_geo(g, kSSTile);
   double *slots = ws.at<double>(ws.lay.slots);
   uint32_t *status = ws.at<uint32_t>(ws.lay.status);
   if (src.residual) return launch_sign_server<true>(g, cg, prm, src, payload, slots, status, stream, used);
