@@ -27,6 +27,19 @@ struct SignDec {
 #pragma unroll
     for (int c = 0; c < 4; ++c) out[c] = ((nib >> c) & 1u) ? -s : s;
   }
+  // The same in two steps, for callers that request a tile ahead of its use: the record's
+  // header value and the raw bits first, the values later.
+  using R4 = uint32_t;
+  __device__ float header(uint32_t p) const { return *reinterpret_cast<const float *>(payload + (uint64_t)p * stride); }
+  __device__ void table(float, float *) const {}
+  __device__ R4 load4(const Geo &, uint32_t p, uint32_t j, const TileBuf &) const {
+    return (payload + (uint64_t)p * stride)[kHeaderBytes + (j >> 3)];
+  }
+  __device__ void decode4(R4 r, uint32_t j, float hdr, const float *, float out[4]) const {
+    const uint32_t nib = r >> (j & 4);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) out[c] = ((nib >> c) & 1u) ? -hdr : hdr;
+  }
 };
 struct DitherDec {
   const uint8_t *payload; uint64_t stride; uint32_t levels; bool natural;
@@ -50,6 +63,23 @@ struct DitherDec {
 #pragma unroll
     for (int c = 0; c < 4; ++c) out[c] = lds[(w >> (4 * c)) & 15u];
   }
+  using R4 = uint32_t;
+  __device__ float header(uint32_t p) const { return *reinterpret_cast<const float *>(payload + (uint64_t)p * stride); }
+  // all threads; the caller synchronises before and after
+  __device__ void table(float nu, float *lds) const {
+    if (threadIdx.x < 16) {
+      float mag = dither_mag(nu, threadIdx.x & 7, levels, natural);
+      lds[threadIdx.x] = (threadIdx.x & 8) ? -mag : mag;
+    }
+  }
+  __device__ R4 load4(const Geo &, uint32_t p, uint32_t j, const TileBuf &) const {
+    return reinterpret_cast<const uint32_t *>(payload + (uint64_t)p * stride + kHeaderBytes)[j >> 3];
+  }
+  __device__ void decode4(R4 r, uint32_t j, float, const float *lds, float out[4]) const {
+    const uint32_t w = r >> (4 * (j & 4));
+#pragma unroll
+    for (int c = 0; c < 4; ++c) out[c] = lds[(w >> (4 * c)) & 15u];
+  }
 };
 struct IdentityDec {
   const uint8_t *payload; uint64_t stride;
@@ -64,6 +94,15 @@ struct IdentityDec {
     const float4 a = reinterpret_cast<const float4 *>(payload + (uint64_t)p * stride + kHeaderBytes)[j >> 2];
     out[0] = a.x; out[1] = a.y; out[2] = a.z; out[3] = a.w;
   }
+  using R4 = u32x4;
+  __device__ float header(uint32_t) const { return 0.0f; }
+  __device__ void table(float, float *) const {}
+  __device__ R4 load4(const Geo &, uint32_t p, uint32_t j, const TileBuf &) const {
+    return reinterpret_cast<const u32x4 *>(payload + (uint64_t)p * stride + kHeaderBytes)[j >> 2];
+  }
+  __device__ void decode4(R4 r, uint32_t, float, const float *, float out[4]) const {
+    out[0] = __uint_as_float(r.x); out[1] = __uint_as_float(r.y); out[2] = __uint_as_float(r.z); out[3] = __uint_as_float(r.w);
+  }
 };
 struct DenseDec {
   const float *dense;
@@ -76,6 +115,13 @@ struct DenseDec {
   __device__ void at4(const Geo &, uint32_t, uint32_t, const TileBuf &row, const float *, float out[4]) const {
     const u32x4 lo = row.load16<kNonTemporal>(threadIdx.x * 16, 0);
     out[0] = __uint_as_float(lo.x); out[1] = __uint_as_float(lo.y); out[2] = __uint_as_float(lo.z); out[3] = __uint_as_float(lo.w);
+  }
+  using R4 = u32x4;
+  __device__ float header(uint32_t) const { return 0.0f; }
+  __device__ void table(float, float *) const {}
+  __device__ R4 load4(const Geo &, uint32_t, uint32_t, const TileBuf &row) const { return row.load16<kNonTemporal>(threadIdx.x * 16, 0); }
+  __device__ void decode4(R4 r, uint32_t, float, const float *, float out[4]) const {
+    out[0] = __uint_as_float(r.x); out[1] = __uint_as_float(r.y); out[2] = __uint_as_float(r.z); out[3] = __uint_as_float(r.w);
   }
 };
 
@@ -93,6 +139,20 @@ __device__ inline void ratios(const OptArgs &o, float g, float m, float v, float
   float decay = o.wd * x;
   *u_r = m_hat / denom + decay;
   *u_c = g / denom + decay;
+}
+
+// The same for the single-pass LANS kernel, which is bound by its arithmetic: the bias
+// corrections as factors, and the hardware's reciprocal and square root (1 ulp each) in place
+// of the correctly rounded sequences.  r and c differ from the divisions above by a few ulp;
+// in x that is far inside the 1e-6 the update is held to.
+__device__ inline void ratios_fast(const OptArgs &o, float inv_bc1, float inv_bc2, float g, float m, float v, float x,
+                                   float *u_r, float *u_c) {
+  float m_hat = m * inv_bc1;
+  float v_hat = v * inv_bc2;
+  float inv = __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(v_hat) + o.eps);
+  float decay = o.wd * x;
+  *u_r = m_hat * inv + decay;
+  *u_c = g * inv + decay;
 }
 
 __device__ inline uint32_t find_block(const uint64_t *offs, uint64_t n_blocks, uint64_t i) {
@@ -214,135 +274,196 @@ __global__ __launch_bounds__(kThreads) void adam_update_kernel(Geo g, DEC dec, f
   }
 }
 
-// LANS in one pass when the blocks are the partitions: a workgroup (512 threads, 16 elements a
-// thread, an 8192-element tile) updates and stores the moments, keeps x, r + wd x and c + wd x
-// in registers, exchanges its three partial square sums with the other tiles of the partition
-// (one f64 slot each, published and polled as in cluster.hpp; resident grid, tiles handed out
-// by ticket) and then writes x.  Sums are combined in slot order, so the result does not
-// depend on timing.  Same traffic as ADAM: payload, m, v, x read once, m, v, x written once.
-constexpr int kLThreads = 512;
-constexpr int kLPer = kSTile / kLThreads;   // 16
-constexpr int kLRows = kLPer / 4;           // 4 rows of 2048 elements, 4 consecutive a thread
+// LANS in one pass when the blocks are the partitions.  A workgroup (1024 threads, 8 elements
+// a thread, an 8192-element tile; tiles at a fixed stride, the grid resident as a whole)
+// updates and stores the moments, keeps x, r + wd x and c + wd x in registers and publishes its
+// three partial square sums (one f64 slot each, as in cluster.hpp).  It writes a tile's x
+// only after phase 1 of its next tile: by then the other tiles of the older tile's partition
+// have been published, so collecting the three totals is one read of the slots, and the loads
+// of the next tile are already under way.  Sums are combined in slot order, so the result
+// does not depend on timing.  Same traffic as ADAM: payload, m, v, x read once, m, v, x
+// written once.
+constexpr int kLThreads = 1024;
+constexpr int kLPer = kSTile / kLThreads;   // 8
+constexpr int kLRows = kLPer / 4;           // 2 rows of 4096 elements, 4 consecutive a thread
 constexpr int kLRow = kLThreads * 4;
+
+struct LansTile {
+  uint32_t p, tile, valid, tiles_in_part;
+  uint64_t base;
+};
+__device__ inline LansTile lans_tile(const Geo &g, const ClusterGeo &cg, uint32_t item) {
+  LansTile t;
+  t.p = __builtin_amdgcn_readfirstlane(item / cg.tiles_per_part);
+  t.tile = __builtin_amdgcn_readfirstlane(item % cg.tiles_per_part);
+  const uint32_t d = g.part_size(t.p);
+  t.tiles_in_part = (uint32_t)cdiv(d, kSTile);
+  t.base = uniform_off(g.part_base(t.p) + (uint64_t)t.tile * kSTile);
+  const uint32_t left = d - t.tile * kSTile;
+  t.valid = __builtin_amdgcn_readfirstlane(left < (uint32_t)kSTile ? left : (uint32_t)kSTile);
+  return t;
+}
 template <class DEC>
-__global__ __launch_bounds__(kLThreads, 4) void lans_single_kernel(Geo g, ClusterGeo cg, DEC dec, float *x, float *m, float *v,
-                                                                  OptArgs o, double *slots, uint32_t *status) {
-  __shared__ float lds[DEC::kLdsFloats];
-  __shared__ double red[kLThreads / 64];
-  __shared__ double total_sh[3];
-  __shared__ uint32_t item_sh;
-  // the grid is resident as a whole; workgroups take tiles by ticket until none is left
+struct LansRaw {
+  u32x4 m[kLRows], v[kLRows], x[kLRows];
+  typename DEC::R4 g[kLRows];
+  float hdr;
+};
+struct LansHeld { float xs[kLPer], ur[kLPer], uc[kLPer]; };
+
+template <class DEC>
+__device__ inline void lans_issue(const Geo &g, const ClusterGeo &cg, const DEC &dec, const float *x, const float *m,
+                                  const float *v, uint32_t item, LansRaw<DEC> &raw) {
+  const LansTile t = lans_tile(g, cg, item);
+  raw.hdr = dec.header(t.p);
+#pragma unroll
+  for (int u = 0; u < kLRows; ++u) {
+    raw.m[u] = row_buf(m + t.base, t.valid, u * kLRow, kLRow).load16<kNonTemporal>(threadIdx.x * 16, 0);
+    raw.v[u] = row_buf(v + t.base, t.valid, u * kLRow, kLRow).load16<kNonTemporal>(threadIdx.x * 16, 0);
+    raw.x[u] = row_buf(x + t.base, t.valid, u * kLRow, kLRow).load16<kNonTemporal>(threadIdx.x * 16, 0);
+    const uint32_t j = t.tile * kSTile + u * kLRow + threadIdx.x * 4;
+    raw.g[u] = dec.load4(g, t.p, j, row_buf(dec.dense_base() + t.base, t.valid, u * kLRow, kLRow));
+  }
+}
+
+// First wave: the three totals of a partition once all its tiles have published theirs.
+__device__ inline void lans_collect(const double *ps, uint32_t tiles_in_part, uint32_t *status, double *total_sh) {
+  const uint32_t lane = threadIdx.x;
+  double a0, a1, a2;
+  int spins = 0;
   for (;;) {
-  if (threadIdx.x == 0) item_sh = atomicAdd(status + 1, 1u);
-  __syncthreads();
-  const uint32_t item = __builtin_amdgcn_readfirstlane(item_sh);
-  if (item >= cg.n_items) break;
-  const uint32_t p = __builtin_amdgcn_readfirstlane(item / cg.tiles_per_part);
-  const uint32_t tile = __builtin_amdgcn_readfirstlane(item % cg.tiles_per_part);
-  const uint32_t d = g.part_size(p);
-  const uint32_t tiles_in_part = (uint32_t)cdiv(d, kSTile);
-  dec.begin(p, lds);
-  const uint64_t tile_base = g.part_base(p) + (uint64_t)tile * kSTile;
-  const uint32_t valid = d - tile * kSTile < (uint32_t)kSTile ? d - tile * kSTile : (uint32_t)kSTile;
-  const float omb1 = 1.0f - o.beta1, omb2 = 1.0f - o.beta2;
-  u32x4 xr[kLRows], mr[kLRows], vr[kLRows];
-  float gr[kLRows][4];
-#pragma unroll
-  for (int u = 0; u < kLRows; ++u) {
-    mr[u] = row_buf(m + tile_base, valid, u * kLRow, kLRow).load16<kNonTemporal>(threadIdx.x * 16, 0);
-    vr[u] = row_buf(v + tile_base, valid, u * kLRow, kLRow).load16<kNonTemporal>(threadIdx.x * 16, 0);
-    xr[u] = row_buf(x + tile_base, valid, u * kLRow, kLRow).load16<kNonTemporal>(threadIdx.x * 16, 0);
-    const uint32_t j = tile * kSTile + u * kLRow + threadIdx.x * 4;
-    dec.at4(g, p, j, row_buf(dec.dense_base() + tile_base, valid, u * kLRow, kLRow), lds, gr[u]);
-  }
-  float xs[kLPer], ur[kLPer], uc[kLPer];
-  double s_x = 0.0, s_r = 0.0, s_c = 0.0;
-#pragma unroll
-  for (int u = 0; u < kLRows; ++u) {
-    const uint32_t mi[4] = {mr[u].x, mr[u].y, mr[u].z, mr[u].w};
-    const uint32_t vi[4] = {vr[u].x, vr[u].y, vr[u].z, vr[u].w};
-    const uint32_t xi[4] = {xr[u].x, xr[u].y, xr[u].z, xr[u].w};
-    float mo[4], vo[4];
-#pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      const float gj = gr[u][c];
-      const float mj = o.beta1 * __uint_as_float(mi[c]) + omb1 * gj;
-      const float vj = o.beta2 * __uint_as_float(vi[c]) + omb2 * (gj * gj);
-      const float xj = __uint_as_float(xi[c]);
-      float u_r, u_c;
-      ratios(o, gj, mj, vj, xj, &u_r, &u_c);
-      mo[c] = mj;
-      vo[c] = vj;
-      // what the padded record decodes to past the partition's end takes no part in the norms
-      const bool in = (uint32_t)(u * kLRow) + threadIdx.x * 4 + c < valid;
-      xs[4 * u + c] = xj;
-      ur[4 * u + c] = u_r;
-      uc[4 * u + c] = u_c;
-      s_x = in ? fma((double)xj, (double)xj, s_x) : s_x;
-      s_r = in ? fma((double)u_r, (double)u_r, s_r) : s_r;
-      s_c = in ? fma((double)u_c, (double)u_c, s_c) : s_c;
+    bool ok = true;
+    a0 = 0.0; a1 = 0.0; a2 = 0.0;
+    for (uint32_t s = lane; s < tiles_in_part; s += 64) {
+      const double q0 = __hip_atomic_load(ps + 3 * s + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      const double q1 = __hip_atomic_load(ps + 3 * s + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      const double q2 = __hip_atomic_load(ps + 3 * s + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      ok = ok && slot_published(q0) && slot_published(q1) && slot_published(q2);
+      a0 += slot_published(q0) ? q0 : 0.0;
+      a1 += slot_published(q1) ? q1 : 0.0;
+      a2 += slot_published(q2) ? q2 : 0.0;
     }
-    row_buf(m + tile_base, valid, u * kLRow, kLRow).store16<kNonTemporal>(as_u32x4(mo[0], mo[1], mo[2], mo[3]), threadIdx.x * 16);
-    row_buf(v + tile_base, valid, u * kLRow, kLRow).store16<kNonTemporal>(as_u32x4(vo[0], vo[1], vo[2], vo[3]), threadIdx.x * 16);
-  }
-  const double t_x = cluster_block_reduce<false, kLThreads>(s_x, red);
-  const double t_r = cluster_block_reduce<false, kLThreads>(s_r, red);
-  const double t_c = cluster_block_reduce<false, kLThreads>(s_c, red);
-  if (threadIdx.x < 64) {
-    // slot 3*tile + k of the partition holds this tile's k-th partial
-    double *ps = slots + 3ull * p * cg.tiles_per_part;
-    if (threadIdx.x == 0) {
-      slot_publish(ps + 3 * tile + 0, t_x);
-      slot_publish(ps + 3 * tile + 1, t_r);
-      slot_publish(ps + 3 * tile + 2, t_c);
+    if (__all(ok)) break;
+    if (++spins > kSpinLimit) {
+      if (lane == 0) atomicOr(status, 1u);
+      break;
     }
-    const uint32_t lane = threadIdx.x;
-    double a0, a1, a2;
-    int spins = 0;
-    for (;;) {
-      bool ok = true;
-      a0 = 0.0; a1 = 0.0; a2 = 0.0;
-      for (uint32_t s = lane; s < tiles_in_part; s += 64) {
-        const double q0 = __hip_atomic_load(ps + 3 * s + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const double q1 = __hip_atomic_load(ps + 3 * s + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const double q2 = __hip_atomic_load(ps + 3 * s + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        ok = ok && slot_published(q0) && slot_published(q1) && slot_published(q2);
-        a0 += slot_published(q0) ? q0 : 0.0;
-        a1 += slot_published(q1) ? q1 : 0.0;
-        a2 += slot_published(q2) ? q2 : 0.0;
-      }
-      if (__all(ok)) break;
-      if (++spins > kSpinLimit) {
-        if (lane == 0) atomicOr(status, 1u);
-        break;
-      }
-      __builtin_amdgcn_s_sleep(16);
-    }
-    a0 = wave_sum(a0);
-    a1 = wave_sum(a1);
-    a2 = wave_sum(a2);
-    if (lane == 0) { total_sh[0] = a0; total_sh[1] = a1; total_sh[2] = a2; }
+    __builtin_amdgcn_s_sleep(16);
   }
-  __syncthreads();
+  a0 = wave_sum(a0);
+  a1 = wave_sum(a1);
+  a2 = wave_sum(a2);
+  if (lane == 0) { total_sh[0] = a0; total_sh[1] = a1; total_sh[2] = a2; }
+}
+
+// x of a tile whose partition's totals are in total_sh.
+__device__ inline void lans_write_x(const Geo &g, const ClusterGeo &cg, const OptArgs &o, float *x, uint32_t item,
+                                    const LansHeld &h, const double *total_sh) {
+  const LansTile t = lans_tile(g, cg, item);
   const float norm_x = (float)sqrt(total_sh[0]);
   const float norm_r = (float)sqrt(total_sh[1]);
   const float norm_c = (float)sqrt(total_sh[2]);
   float phi = norm_x < o.phi_lo ? o.phi_lo : norm_x;
   phi = phi > o.phi_hi ? o.phi_hi : phi;
   const float w_r = norm_r > 0.0f ? o.beta1 / norm_r : 0.0f;
-  const float w_c = norm_c > 0.0f ? omb1 / norm_c : 0.0f;
+  const float w_c = norm_c > 0.0f ? (1.0f - o.beta1) / norm_c : 0.0f;
 #pragma unroll
   for (int u = 0; u < kLRows; ++u) {
     float xo[4];
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
-      const float dir = phi * (w_r * ur[4 * u + c] + w_c * uc[4 * u + c]);
-      xo[c] = xs[4 * u + c] - o.lr * dir;
+      const float dir = phi * (w_r * h.ur[4 * u + c] + w_c * h.uc[4 * u + c]);
+      xo[c] = h.xs[4 * u + c] - o.lr * dir;
     }
-    row_buf(x + tile_base, valid, u * kLRow, kLRow).store16<kNonTemporal>(as_u32x4(xo[0], xo[1], xo[2], xo[3]), threadIdx.x * 16);
+    row_buf(x + t.base, t.valid, u * kLRow, kLRow).store16<kNonTemporal>(as_u32x4(xo[0], xo[1], xo[2], xo[3]), threadIdx.x * 16);
   }
-  __syncthreads();   // the LDS words are rewritten by the next round
+}
+
+template <class DEC>
+__global__ __launch_bounds__(kLThreads) void lans_single_kernel(Geo g, ClusterGeo cg, DEC dec, float *x, float *m, float *v,
+                                                               OptArgs o, double *slots, uint32_t *status) {
+  __shared__ float lds[DEC::kLdsFloats];
+  __shared__ double red[kLThreads / 64];
+  __shared__ double total_sh[3];
+  constexpr uint32_t kNone = 0xffffffffu;
+  uint32_t item = __builtin_amdgcn_readfirstlane(blockIdx.x);
+  if (item >= cg.n_items) return;
+  LansRaw<DEC> raw;
+  lans_issue(g, cg, dec, x, m, v, item, raw);
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the loop is entered with nothing in flight
+  LansHeld prev_h;
+  uint32_t prev = kNone;
+  const float omb1 = 1.0f - o.beta1, omb2 = 1.0f - o.beta2;
+  const float inv_bc1 = 1.0f / o.bc1, inv_bc2 = 1.0f / o.bc2;
+  for (;;) {
+    const LansTile t = lans_tile(g, cg, item);
+    __syncthreads();   // the table of the tile before
+    dec.table(raw.hdr, lds);
+    __syncthreads();
+    LansHeld h;
+    double s_x = 0.0, s_r = 0.0, s_c = 0.0;
+#pragma unroll
+    for (int u = 0; u < kLRows; ++u) {
+      const uint32_t mi[4] = {raw.m[u].x, raw.m[u].y, raw.m[u].z, raw.m[u].w};
+      const uint32_t vi[4] = {raw.v[u].x, raw.v[u].y, raw.v[u].z, raw.v[u].w};
+      const uint32_t xi[4] = {raw.x[u].x, raw.x[u].y, raw.x[u].z, raw.x[u].w};
+      float gr[4];
+      dec.decode4(raw.g[u], t.tile * kSTile + u * kLRow + threadIdx.x * 4, raw.hdr, lds, gr);
+      float mo[4], vo[4];
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const float gj = gr[c];
+        const float mj = o.beta1 * __uint_as_float(mi[c]) + omb1 * gj;
+        const float vj = o.beta2 * __uint_as_float(vi[c]) + omb2 * (gj * gj);
+        const float xj = __uint_as_float(xi[c]);
+        float u_r, u_c;
+        ratios_fast(o, inv_bc1, inv_bc2, gj, mj, vj, xj, &u_r, &u_c);
+        mo[c] = mj;
+        vo[c] = vj;
+        // what the padded record decodes to past the partition's end takes no part in the norms
+        const bool in = (uint32_t)(u * kLRow) + threadIdx.x * 4 + c < t.valid;
+        h.xs[4 * u + c] = xj;
+        h.ur[4 * u + c] = u_r;
+        h.uc[4 * u + c] = u_c;
+        s_x = in ? fma((double)xj, (double)xj, s_x) : s_x;
+        s_r = in ? fma((double)u_r, (double)u_r, s_r) : s_r;
+        s_c = in ? fma((double)u_c, (double)u_c, s_c) : s_c;
+      }
+      row_buf(m + t.base, t.valid, u * kLRow, kLRow).store16<kNonTemporal>(as_u32x4(mo[0], mo[1], mo[2], mo[3]), threadIdx.x * 16);
+      row_buf(v + t.base, t.valid, u * kLRow, kLRow).store16<kNonTemporal>(as_u32x4(vo[0], vo[1], vo[2], vo[3]), threadIdx.x * 16);
+    }
+    const uint32_t next = __builtin_amdgcn_readfirstlane(item + gridDim.x);
+    const bool have_next = next < cg.n_items;
+    if (have_next) lans_issue(g, cg, dec, x, m, v, next, raw);
+    const double t_x = cluster_block_reduce<false, kLThreads>(s_x, red);
+    const double t_r = cluster_block_reduce<false, kLThreads>(s_r, red);
+    const double t_c = cluster_block_reduce<false, kLThreads>(s_c, red);
+    if (threadIdx.x == 0) {
+      // slot 3*tile + k of the partition holds this tile's k-th partial
+      double *ps = slots + 3ull * t.p * cg.tiles_per_part;
+      slot_publish(ps + 3 * t.tile + 0, t_x);
+      slot_publish(ps + 3 * t.tile + 1, t_r);
+      slot_publish(ps + 3 * t.tile + 2, t_c);
+    }
+    if (prev != kNone && threadIdx.x < 64) {
+      const LansTile tp = lans_tile(g, cg, prev);
+      lans_collect(slots + 3ull * tp.p * cg.tiles_per_part, tp.tiles_in_part, status, total_sh);
+    }
+    __syncthreads();
+    if (prev != kNone) lans_write_x(g, cg, o, x, prev, prev_h, total_sh);
+    prev_h = h;
+    prev = item;
+    if (!have_next) break;
+    item = next;
   }
+  // the last tile
+  __syncthreads();
+  if (threadIdx.x < 64) {
+    const LansTile tp = lans_tile(g, cg, prev);
+    lans_collect(slots + 3ull * tp.p * cg.tiles_per_part, tp.tiles_in_part, status, total_sh);
+  }
+  __syncthreads();
+  lans_write_x(g, cg, o, x, prev, prev_h, total_sh);
 }
 
 template <class DEC>
