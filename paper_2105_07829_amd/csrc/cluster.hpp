@@ -11,24 +11,28 @@
 //     status word and carries on with the values it has, so the kernel always terminates;
 //   - partial results are combined in slot order, so the total does not depend on timing.
 //
-// Two drivers share this exchange.  They differ in how tiles get to workgroups, and each
-// keeps the wait free of cycles provided a partition has no more tiles than the device
-// holds workgroups of the kernel at once (the launcher checks that):
+// Two drivers share this exchange.  Both are LAGGED: a workgroup publishes the partial of
+// tile k, then finishes tile k-1 (collects its partition's total and writes its outputs), then
+// goes on to tile k+1.  Tile k-1 was published a whole phase 1 earlier, so the other tiles of
+// its partition have had that long to publish too, and collecting the total is as a rule one
+// read of the slots instead of a wait; the price is a second copy of what a tile keeps for
+// its phase 2.  A workgroup never waits while it holds a tile it has not published, so the
+// oldest unpublished tile is always being worked on, and every wait ends provided the grid is
+// resident as a whole and a partition has no more tiles than the grid (the launcher checks
+// both).  They differ in how tiles get to workgroups:
 //
-//   PERSISTENT (cluster_run_persistent): the grid is no larger than what is resident at
-//     once; workgroup w takes tiles w, w+G, w+2G, ...  A workgroup only ever waits for
-//     tiles of its current partition; those belong to workgroups that are resident and that
-//     publish before they wait.  Used where a tile's loads can be requested one tile ahead
-//     (the worker side: two streams per tile), which keeps the memory pipeline of a compute
-//     unit busy across the exchange.
-//   TICKETED (cluster_run_ticketed): the grid is resident as a whole too, but a workgroup
-//     takes the number of its next tile from a counter, so tiles are handed out in the order
-//     in which workgroups become free.  Every workgroup holds at most one unfinished tile;
-//     if all G of them wait, the unfinished tiles are G distinct numbers at or above the
-//     oldest one, so with tiles_per_partition <= G the whole oldest unfinished partition has
-//     been handed out, its tiles publish before they wait, and it completes.  Used where a
-//     tile needs many streams and latency-bound loads (the server side): many small
-//     workgroups per compute unit overlap each other, without a prefetch to keep in registers.
+//   PERSISTENT (cluster_run_persistent): workgroup w takes tiles w, w+G, w+2G, ... and
+//     requests the loads of its next tile right after phase 1 of the current one, so the
+//     memory pipeline of a compute unit stays busy across the exchange.  Used on the worker
+//     side (two input streams per tile, one large workgroup per compute unit).
+//   TICKETED (cluster_run_ticketed): a workgroup takes the number of its next tile from a
+//     counter, so tiles are handed out in the order in which workgroups become free, and phase
+//     1 issues its own loads.  Used on the server side (n + 1 input streams and n-term sums
+//     per tile): several workgroups per compute unit overlap each other's loads and
+//     arithmetic, with no prefetch to keep in registers.
+//   (Launching one workgroup per tile instead of a resident grid would tie each workgroup to
+//   the XCD its index maps to; near the end of the grid the tiles still to come would all
+//   belong to the one or two XCDs that are behind, too few workgroups to hold a partition.)
 #pragma once
 #include "device_utils.hpp"
 #include "geometry.hpp"
@@ -139,7 +143,7 @@ __device__ inline double slots_collect(const double *slots, uint32_t count, uint
   return v;
 }
 
-// The same in two steps for the lagged drivers: slots_probe() reads every slot once without
+// The same in two steps for the persistent driver: slots_probe() reads every slot once without
 // waiting for the values (the loads stay in flight under whatever the caller does next), and
 // slots_finish() uses them if all were published, else falls back to slots_collect().  Both
 // combine in the same order, so the result does not depend on which one produced it.
@@ -197,11 +201,14 @@ __device__ inline double cluster_block_reduce(double x, double *red /*THREADS/64
   return t;
 }
 
-// What both drivers ask of an operator `Op`:
+// What the drivers ask of an operator `Op`:
 //   struct Raw, struct Held, struct Ctx;         raw loads of a tile / what is kept for phase 2
-//   static constexpr int kThreads;               workgroup size; a tile is kThreads * kCPerThread elements
+//   static constexpr int kThreads;               workgroup size
+//   static constexpr bool kPersistent;           which driver
 //   uint32_t n_items() const;  bool needs_total() const;
-//   double phase1(item, Raw&, Held&, table) const;   consume the loads, return the tile's partial
+//   void   issue_row(item, row, Raw&) const;     (persistent) request a row of the tile's inputs
+//   double phase1(item, Raw&, Held&, table) const;   consume the loads (ticketed: request them
+//                                                first), return the tile's partial
 //   void   early(item, Held&) const;             stores that do not need the norm
 //   Ctx    begin2(item, total, table) / row2(item, row, Held&, Ctx) const;   outputs of one row
 //   void   slots_of(item, first, count)          the partition's slots
@@ -210,135 +217,9 @@ __device__ inline double cluster_block_reduce(double x, double *red /*THREADS/64
 // The operator is passed by value in the kernel arguments and never modified, so it stays in
 // the kernel-argument segment (a modified copy would live in scratch memory).
 
-// When the persistent driver requests a workgroup's next tile, relative to its work on the
-// current one.
-enum class Prefetch {
-  kEarly,        // issue_row() of every row right after phase 1: everything is in flight during
-                 // the exchange (phase 2 is mostly stores)
-  kSplit,        // issue_first() of every row right after phase 1, issue_second() once the
-                 // partition's total is known: the waves that poll have little of their own in
-                 // flight, and phase 2's arithmetic runs under the second part
-  kInterleaved   // issue_row(u) after row u of phase 2 (fewest registers)
-};
-
-// Persistent driver.  In addition `Op` supplies
-//   void issue_row(item, row, Raw&) const [, issue_first / issue_second for kSplit];
-//   static constexpr Prefetch kPrefetch.
-template <class Op>
-__device__ inline void cluster_run_persistent(const Op &op, float *table, double *slots, uint32_t *status) {
-  constexpr int kT = Op::kThreads;
-  __shared__ double red[kT / 64];
-  __shared__ double total_sh;
-  const uint32_t n_items = op.n_items();
-  // item numbers are the same for every lane: keeping them in scalar registers makes all
-  // tile addresses scalar
-  uint32_t item = __builtin_amdgcn_readfirstlane(blockIdx.x);
-  if (item >= n_items) return;
-  typename Op::Raw raw;
-#pragma unroll
-  for (int u = 0; u < Op::kRowsPerTile; ++u) op.issue_row(item, u, raw);
-  // Wait for them here (vmcnt 0; the other counters untouched).  The loop below is then
-  // entered with nothing in flight on this path, so the waits the compiler places inside it
-  // are those of the steady state, where stores and the next tile's loads are younger than
-  // the data a row needs and may stay in flight (vector-memory waits count in issue order).
-  __builtin_amdgcn_s_waitcnt(0x0F70);
-  for (;;) {
-    typename Op::Held held;
-    double part = op.phase1(item, raw, held, table);
-    const uint32_t next = __builtin_amdgcn_readfirstlane(item + gridDim.x);
-    const bool have_next = next < n_items;
-    if (have_next) {
-      if constexpr (Op::kPrefetch == Prefetch::kEarly) {
-#pragma unroll
-        for (int u = 0; u < Op::kRowsPerTile; ++u) op.issue_row(next, u, raw);
-      } else if constexpr (Op::kPrefetch == Prefetch::kSplit) {
-#pragma unroll
-        for (int u = 0; u < Op::kRowsPerTile; ++u) op.issue_first(next, u, raw);
-      }
-    }
-    part = cluster_block_reduce<Op::kMax, kT>(part, red);
-    if (threadIdx.x < 64) {
-      uint32_t first, count;
-      op.slots_of(item, &first, &count);
-      if (op.needs_total()) {
-        if (threadIdx.x == 0) slot_publish(slots + item, part);
-        double total = slots_collect<Op::kMax>(slots + first, count, status);
-        if (threadIdx.x == 0) total_sh = total;
-      }
-    }
-    op.early(item, held);
-    __syncthreads();
-    const double total = total_sh;
-    if constexpr (Op::kPrefetch == Prefetch::kSplit) {
-      if (have_next) {
-#pragma unroll
-        for (int u = 0; u < Op::kRowsPerTile; ++u) op.issue_second(next, u, raw);
-      }
-    }
-    const typename Op::Ctx ctx = op.begin2(item, total, table);
-#pragma unroll
-    for (int u = 0; u < Op::kRowsPerTile; ++u) {
-      op.row2(item, u, held, ctx);
-      if (Op::kPrefetch == Prefetch::kInterleaved && have_next) op.issue_row(next, u, raw);
-    }
-    if (!have_next) break;
-    item = next;
-    __syncthreads();
-  }
-}
-
-// Ticketed driver: phase 1 of `Op` issues its own loads.  `status[1]` is the ticket counter.
-// The grid is resident as a whole (the launcher sizes it) and every workgroup keeps taking
-// tickets until none is left.  (Launching one workgroup per tile instead would tie each
-// workgroup to the XCD its index maps to; near the end of the grid the tiles still to come
-// would then all belong to the one or two XCDs that are behind, too few workgroups to hold a
-// whole partition, and the waits would only end at their bound.)
+// Ticketed driver.  `status[1]` is the ticket counter.
 template <class Op>
 __device__ inline void cluster_run_ticketed(const Op &op, float *table, double *slots, uint32_t *status) {
-  constexpr int kT = Op::kThreads;
-  __shared__ double red[kT / 64];
-  __shared__ double total_sh;
-  __shared__ uint32_t item_sh;
-  for (;;) {
-    if (threadIdx.x == 0) item_sh = atomicAdd(status + 1, 1u);
-    __syncthreads();
-    // the same for every lane: keeping it in a scalar register makes all tile addresses scalar
-    const uint32_t item = __builtin_amdgcn_readfirstlane(item_sh);
-    if (item >= op.n_items()) break;
-    typename Op::Raw raw;
-    typename Op::Held held;
-    double part = op.phase1(item, raw, held, table);
-    part = cluster_block_reduce<Op::kMax, kT>(part, red);
-    if (threadIdx.x < 64) {
-      uint32_t first, count;
-      op.slots_of(item, &first, &count);
-      if (op.needs_total()) {
-        if (threadIdx.x == 0) slot_publish(slots + item, part);
-        double total = slots_collect<Op::kMax>(slots + first, count, status);
-        if (threadIdx.x == 0) total_sh = total;
-      }
-    }
-    op.early(item, held);
-    __syncthreads();
-    const double total = total_sh;
-    const typename Op::Ctx ctx = op.begin2(item, total, table);
-#pragma unroll
-    for (int u = 0; u < Op::kRowsPerTile; ++u) op.row2(item, u, held, ctx);
-    // (drawing the next ticket earlier, under these stores, was slower: a tile drawn early
-    // starts late, and its whole partition waits for it)
-    __syncthreads();   // the LDS words above are rewritten by the next round
-  }
-}
-
-// Lagged ticketed driver: like the ticketed one, but a workgroup finishes a tile only after
-// phase 1 of its next one.  By then the other tiles of the older tile's partition have long
-// been published, so collecting the total costs one read of the slots instead of a wait, and
-// a workgroup never waits while it holds an unpublished tile.  Costs a second copy of `Held`.
-// Every tile taken is published before anything is waited for, so the oldest unpublished tile
-// is always being worked on; with the grid resident and a partition's tiles no more than the
-// grid, every wait ends (the launcher checks both).
-template <class Op>
-__device__ inline void cluster_run_lagged(const Op &op, float *table, double *slots, uint32_t *status) {
   constexpr int kT = Op::kThreads;
   constexpr uint32_t kNone = 0xffffffffu;
   __shared__ double red[kT / 64];
@@ -361,7 +242,7 @@ __device__ inline void cluster_run_lagged(const Op &op, float *table, double *sl
       if (threadIdx.x == 0 && op.needs_total()) slot_publish(slots + item, part);
     }
     uint32_t ticket = kNone;
-    // (reading the older tile's slots before phase 1, as the lagged persistent driver does,
+    // (reading the older tile's slots before phase 1, as the persistent driver does,
     // was slower here: phase 1 of these operators has no registers to spare for the values)
     if (prev != kNone) {
       if (threadIdx.x < 64 && op.needs_total()) {
@@ -390,11 +271,10 @@ __device__ inline void cluster_run_lagged(const Op &op, float *table, double *sl
   }
 }
 
-// Lagged persistent driver: static striding and the early request of the next tile as in the
-// persistent driver, the older tile finished after phase 1 of the current one as in the
-// lagged ticketed driver.
+// Persistent driver.  The older tile's slots are read before phase 1 of the current tile and
+// looked at after it, so that read is off the critical path as well.
 template <class Op>
-__device__ inline void cluster_run_persistent_lagged(const Op &op, float *table, double *slots, uint32_t *status) {
+__device__ inline void cluster_run_persistent(const Op &op, float *table, double *slots, uint32_t *status) {
   constexpr int kT = Op::kThreads;
   constexpr uint32_t kNone = 0xffffffffu;
   __shared__ double red[kT / 64];

@@ -13,17 +13,9 @@ struct waves_per_simd { static constexpr int value = 4; };
 template <class Op>
 struct waves_per_simd<Op, std::void_t<decltype(Op::kWavesPerSimd)>> { static constexpr int value = Op::kWavesPerSimd; };
 
-// kLagged in an operator selects the lagged form of the ticketed driver.
-template <class Op, class = void>
-struct is_lagged { static constexpr bool value = false; };
-template <class Op>
-struct is_lagged<Op, std::void_t<decltype(Op::kLagged)>> { static constexpr bool value = Op::kLagged; };
-
 template <class Op>
 __device__ inline void cluster_run(const Op &op, float *table, double *slots, uint32_t *status) {
-  if constexpr (Op::kPersistent && is_lagged<Op>::value) cluster_run_persistent_lagged(op, table, slots, status);
-  else if constexpr (Op::kPersistent) cluster_run_persistent(op, table, slots, status);
-  else if constexpr (is_lagged<Op>::value) cluster_run_lagged(op, table, slots, status);
+  if constexpr (Op::kPersistent) cluster_run_persistent(op, table, slots, status);
   else cluster_run_ticketed(op, table, slots, status);
 }
 

@@ -19,8 +19,9 @@ struct Philox {
     for (int r = 0; r < 10; ++r) {
       uint64_t p0 = (uint64_t)0xD2511F53u * a;
       uint64_t p1 = (uint64_t)0xCD9E8D57u * c;
-      uint32_t na = (uint32_t)(p1 >> 32) ^ (b ^ ka);
-      uint32_t nc = (uint32_t)(p0 >> 32) ^ (d ^ kb);
+      // three-way exclusive or in one instruction (truth table 0x96)
+      uint32_t na = __builtin_amdgcn_bitop3_b32((uint32_t)(p1 >> 32), b, ka, 0x96);
+      uint32_t nc = __builtin_amdgcn_bitop3_b32((uint32_t)(p0 >> 32), d, kb, 0x96);
       b = (uint32_t)p1;
       d = (uint32_t)p0;
       a = na;

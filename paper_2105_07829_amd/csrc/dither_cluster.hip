@@ -1,19 +1,14 @@
 // Linear-dithering worker, single pass (Algorithm 4 worker lines with the stochastic
-// multi-level quantiser): a workgroup reads a tile (32768 elements) of g and e once, keeps
+// multi-level quantiser): a workgroup reads a tile (16384 elements) of g and e once, keeps
 // q = g + e in registers, publishes its part of ||q||_2^2 (or max |q|), waits for the
 // partition's norm, then draws the levels, writes the packed nibbles and e' = q - decode.
 #include "dither_common.hpp"
 
 namespace bpc {
 
-#ifndef DW_T
-#define DW_T 1024
-#define DW_PER 16
-#define DW_W 4
-#define DW_LAG 1
-#endif
-constexpr int kDWThreads = DW_T;
-constexpr int kDWPer = DW_PER;
+// 1024 threads (one workgroup a CU) and 16 elements a thread, as in the scaled-sign worker.
+constexpr int kDWThreads = 1024;
+constexpr int kDWPer = 16;
 constexpr int kDWTile = kDWThreads * kDWPer;
 constexpr int kDRows = kDWPer / 8;  // rows of kDWThreads * 8 elements; a thread owns 8 consecutive per row
 
@@ -54,10 +49,6 @@ struct DitherWorkerOp {
   static constexpr size_t kMaxDynLds = 0;
   static constexpr int kThreads = kDWThreads;
   static constexpr bool kPersistent = true;
-  static constexpr bool kLagged = DW_LAG != 0;
-  static constexpr int kWavesPerSimd = DW_W;
-  // f32 gradients: the raw loads of a whole tile plus q do not fit the register budget
-  static constexpr Prefetch kPrefetch = sizeof(G) == 2 ? Prefetch::kSplit : Prefetch::kInterleaved;
   struct Ctx { float nu, top_over_nu; int mode; const float *mag; };
 
   Geo g;
@@ -87,15 +78,9 @@ struct DitherWorkerOp {
     const uint32_t left = g.part_size(part_of(item)) - tile_off(item);
     return __builtin_amdgcn_readfirstlane(left < (uint32_t)kDWTile ? left : (uint32_t)kDWTile);
   }
-  __device__ void issue_first(uint32_t item, int u, Raw &raw) const {
-    raw.g[u] = tile_load8(TileBuf(grad + base(item), valid_of(item) * sizeof(G)), u, grad);
-  }
-  __device__ void issue_second(uint32_t item, int u, Raw &raw) const {
-    if (EF) raw.e[u] = tile_load8(TileBuf(res + base(item), valid_of(item) * 4), u, (const float *)nullptr);
-  }
   __device__ void issue_row(uint32_t item, int u, Raw &raw) const {
-    issue_first(item, u, raw);
-    issue_second(item, u, raw);
+    raw.g[u] = tile_load8(TileBuf(grad + base(item), valid_of(item) * sizeof(G)), u, grad);
+    if (EF) raw.e[u] = tile_load8(TileBuf(res + base(item), valid_of(item) * 4), u, (const float *)nullptr);
   }
 
   __device__ double phase1(uint32_t, Raw &raw, Held &h, float *) const {

@@ -28,6 +28,18 @@ inline DMsgPtrs dmsg_ptrs(const WorkerMsgs &m) {
   return r;
 }
 
+// Byte B of `x`, and-ed with `mask`, in one instruction (the byte is picked by the operand's
+// sub-dword select instead of a shift).
+template <int B>
+__device__ inline uint32_t byte_and(uint32_t x, uint32_t mask) {
+  uint32_t r;
+  if (B == 0) asm("v_and_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_0" : "=v"(r) : "v"(mask), "v"(x));
+  else if (B == 1) asm("v_and_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_1" : "=v"(r) : "v"(mask), "v"(x));
+  else if (B == 2) asm("v_and_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_2" : "=v"(r) : "v"(mask), "v"(x));
+  else asm("v_and_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_3" : "=v"(r) : "v"(mask), "v"(x));
+  return r;
+}
+
 // NW > 0: number of workers known at compile time (unrolled); NW == 0: rolled loop.
 template <bool EF, bool LINF, int NW, bool NAT>
 struct DitherServerOp {
@@ -42,7 +54,6 @@ struct DitherServerOp {
   static constexpr int kTableFloats = kMaxWorkers * 16 + 8;   // decode tables, then the 8 output magnitudes
   static constexpr size_t kMaxDynLds = 0;
   static constexpr bool kPersistent = false;
-  static constexpr bool kLagged = true;
 
   Geo g;
   ClusterGeo cg;
@@ -108,11 +119,14 @@ struct DitherServerOp {
     for (int u = 0; u < kDSRows; ++u) {
       const uint32_t even = word[u] << 2, odd = word[u] >> 2;
       float v[8];
-#pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        v[2 * k] = *reinterpret_cast<const float *>(lut_b + ((even >> (8 * k)) & 0x3cu));
-        v[2 * k + 1] = *reinterpret_cast<const float *>(lut_b + ((odd >> (8 * k)) & 0x3cu));
-      }
+      v[0] = *reinterpret_cast<const float *>(lut_b + byte_and<0>(even, 0x3cu));
+      v[1] = *reinterpret_cast<const float *>(lut_b + byte_and<0>(odd, 0x3cu));
+      v[2] = *reinterpret_cast<const float *>(lut_b + byte_and<1>(even, 0x3cu));
+      v[3] = *reinterpret_cast<const float *>(lut_b + byte_and<1>(odd, 0x3cu));
+      v[4] = *reinterpret_cast<const float *>(lut_b + byte_and<2>(even, 0x3cu));
+      v[5] = *reinterpret_cast<const float *>(lut_b + byte_and<2>(odd, 0x3cu));
+      v[6] = *reinterpret_cast<const float *>(lut_b + byte_and<3>(even, 0x3cu));
+      v[7] = *reinterpret_cast<const float *>(lut_b + byte_and<3>(odd, 0x3cu));
 #pragma unroll
       for (int c = 0; c < 8; ++c) acc[8 * u + c] = acc[8 * u + c] + v[c];
     }

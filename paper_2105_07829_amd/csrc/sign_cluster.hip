@@ -1,5 +1,5 @@
 // Scaled-sign worker, single pass (Algorithm 4 worker lines with C(v) = ||v||_1/d sign(v)):
-// each workgroup reads a tile (32768 elements) of g and e once, keeps q = g + e in registers,
+// each workgroup reads a tile (16384 elements) of g and e once, keeps q = g + e in registers,
 // writes the sign bits, publishes its part of ||q||_1, waits for the partition's sum and then
 // writes e' = q -+ sigma.  HBM traffic is the algorithmic minimum: g and e read once, e' and
 // the bits written once.
@@ -7,14 +7,10 @@
 
 namespace bpc {
 
-#ifndef W_T
-#define W_T 1024
-#define W_PER 16
-#define W_W 4
-#define W_LAG 1
-#endif
-constexpr int kSWThreads = W_T;
-constexpr int kSWPer = W_PER;
+// 1024 threads (one workgroup a CU) and 16 elements a thread: q of two tiles (the current one
+// and the one awaiting its total) and the loads of a third fit the registers.
+constexpr int kSWThreads = 1024;
+constexpr int kSWPer = 16;
 constexpr int kSWTile = kSWThreads * kSWPer;
 constexpr int kRows = kSWPer / 4;  // rows of kSWThreads * 4 elements; a thread owns 4 consecutive per row
 
@@ -59,10 +55,6 @@ struct SignWorkerOp {
   static constexpr size_t kMaxDynLds = 0;
   static constexpr int kThreads = kSWThreads;
   static constexpr bool kPersistent = true;
-  static constexpr bool kLagged = W_LAG != 0;
-  static constexpr int kWavesPerSimd = W_W;
-  // f32 gradients: the raw loads of a whole tile plus q do not fit the register budget
-  static constexpr Prefetch kPrefetch = sizeof(G) == 2 ? Prefetch::kEarly : Prefetch::kSplit;
   struct Ctx { float sigma; };
 
   Geo g;
@@ -93,19 +85,13 @@ struct SignWorkerOp {
     return reinterpret_cast<uint32_t *>(payload + (uint64_t)p * g.stride + kHeaderBytes);
   }
 
-  __device__ void issue_first(uint32_t item, int u, Raw &raw) const {
+  __device__ void issue_row(uint32_t item, int u, Raw &raw) const {
     const TileBuf gb(grad + base(item), valid_of(item) * sizeof(G));
     raw.g[u] = tile_load4(gb, threadIdx.x * (4 * sizeof(G)), u * (kSWThreads * 4 * sizeof(G)), grad);
-  }
-  __device__ void issue_second(uint32_t item, int u, Raw &raw) const {
     if (EF) {
       const TileBuf eb(res + base(item), valid_of(item) * 4);
       raw.e[u] = eb.load16<kNonTemporal>(threadIdx.x * 16, u * (kSWThreads * 16));
     }
-  }
-  __device__ void issue_row(uint32_t item, int u, Raw &raw) const {
-    issue_first(item, u, raw);
-    issue_second(item, u, raw);
   }
 
   __device__ double phase1(uint32_t, Raw &raw, Held &h, float *) const {

@@ -13,13 +13,8 @@
 
 namespace bpc {
 
-#ifndef SS_T
-#define SS_T 512
-#define SS_TILE 8192
-#define SS_W 6
-#endif
-constexpr int kSSThreads = SS_T;
-constexpr int kSSTile = SS_TILE;
+constexpr int kSSThreads = 512;
+constexpr int kSSTile = 8192;
 constexpr int kSSWaves = kSSThreads / 64;
 constexpr int kSRows = kSSTile / (kSSThreads * 8);   // 2
 constexpr int kSPerThread = 8 * kSRows;
@@ -62,13 +57,8 @@ struct SignServerOp {
   static constexpr int kBitsPerWorker = kSSTile / 8;   // bytes
   static constexpr int kTableFloats = kMaxWorkers + (NW > 0 ? NW * kBitsPerWorker / 4 : 0);
   static constexpr int kThreads = kSSThreads;
-  static constexpr int kWavesPerSimd = SS_W;
-#ifndef SS_P
-#define SS_P 0
-#endif
-  static constexpr bool kPersistent = SS_P != 0;
-  static constexpr Prefetch kPrefetch = Prefetch::kEarly;
-  static constexpr bool kLagged = true;
+  static constexpr int kWavesPerSimd = 6;   // 80 registers a lane, three workgroups a CU
+  static constexpr bool kPersistent = false;
   static constexpr size_t kMaxDynLds = 0;
   struct Ctx { float sigma; };
 
@@ -157,10 +147,8 @@ struct SignServerOp {
   }
 
   __device__ double phase1(uint32_t item, Raw &raw, Held &h, float *sig) const {
-    if (!kPersistent) {
 #pragma unroll
-      for (int u = 0; u < kSRows; ++u) issue_row(item, u, raw);
-    }
+    for (int u = 0; u < kSRows; ++u) issue_row(item, u, raw);
     float acc[kSPerThread];
 #pragma unroll
     for (int k = 0; k < kSPerThread; ++k) acc[k] = 0.0f;
