@@ -43,7 +43,11 @@ def payload_bytes_per_elem(w):
     if k == "sign":
         return 1.0 / 8
     if k in ("dither", "natdither"):
-        return 0.5
+        # a nibble, plus one bit for each level bit above the third (linear levels beyond 7)
+        levels, planes = w.get("levels", 4), 0
+        while k == "dither" and (levels >> (3 + planes)):
+            planes += 1
+        return 0.5 + planes / 8
     if k == "topk":
         return 8 * w["k_ratio"]
     if k == "randk":

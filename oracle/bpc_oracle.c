@@ -75,10 +75,22 @@ static int params_ok(const orc_params *p) {
   switch (p->kind) {
     case ORC_IDENTITY: case ORC_SIGN: return 1;
     case ORC_TOPK: case ORC_RANDK: return p->k_ratio > 0.0 && p->k_ratio <= 1.0;
-    case ORC_DITHER: case ORC_NATDITHER:
+    case ORC_DITHER:
+      return p->levels >= 1 && p->levels <= 63 && (p->norm == ORC_NORM_L2 || p->norm == ORC_NORM_LINF);
+    case ORC_NATDITHER:
       return p->levels >= 1 && p->levels <= 7 && (p->norm == ORC_NORM_L2 || p->norm == ORC_NORM_LINF);
     default: return 0;
   }
+}
+
+/* Linear dithering with more than 7 levels (the 5- and 7-bit forms of Section 5's list): the
+ * level bits above the third go into bit planes after the nibbles, one bit per element and
+ * plane, so a message costs 4 + planes bits per element.  s <= 7: 0, <= 15: 1, <= 31: 2,
+ * <= 63: 3 planes. */
+static unsigned dither_planes(unsigned levels) {
+  unsigned planes = 0;
+  while ((levels >> (3 + planes)) != 0) ++planes;
+  return planes;
 }
 
 /* k = max(1, floor(ratio*d)), never above d. */
@@ -97,7 +109,8 @@ size_t orc_partition_stride(const orc_params *p) {
   switch (p->kind) {
     case ORC_IDENTITY: words = ru4(d); break;
     case ORC_SIGN:     words = ru4((d + 31) / 32); break;
-    case ORC_DITHER: case ORC_NATDITHER: words = ru4((d + 7) / 8); break;
+    case ORC_DITHER:   words = ru4((d + 7) / 8) + dither_planes(p->levels) * ru4((d + 31) / 32); break;
+    case ORC_NATDITHER: words = ru4((d + 7) / 8); break;
     case ORC_TOPK:     words = 2 * ru4(orc_partition_k(p, d)); break;
     case ORC_RANDK:    words = ru4(orc_partition_k(p, d)); break;
   }
@@ -243,9 +256,14 @@ static void encode_dither(const orc_params *p, uint64_t part_no, const float *q,
     for (uint64_t j = 0; j < d; ++j) if (fabsf(q[j]) > nu) nu = fabsf(q[j]);
   }
   uint64_t words = ru4((d + 7) / 8);
+  /* plane t starts after the nibbles of a full partition, whatever d is */
+  unsigned planes = dither_planes(p->levels);
+  uint64_t plane0 = 4 + ru4((p->part_elems + 7) / 8), plane_words = ru4((p->part_elems + 31) / 32);
   put_f32(rec, 0, nu);
   put_u32(rec, 1, 0); put_u32(rec, 2, 0); put_u32(rec, 3, 0);
   for (uint64_t w = 0; w < words; ++w) put_u32(rec, 4 + w, 0);
+  for (unsigned t = 0; t < planes; ++t)
+    for (uint64_t w = 0; w < ru4((d + 31) / 32); ++w) put_u32(rec, plane0 + t * plane_words + w, 0);
   if (!(nu > 0.0f)) return;
   unsigned s = p->levels;
   /* a = s|q_j|/nu is evaluated as |q_j| * (s/nu), the quotient formed once per partition;
@@ -258,19 +276,28 @@ static void encode_dither(const orc_params *p, uint64_t part_no, const float *q,
     float u = (float)(draw_word(p, part_no, j) >> 8) * 0x1p-24f;
     unsigned level = (unsigned)l + (u < f ? 1u : 0u);
     if (level > s) level = s;
-    uint32_t nibble = (q[j] < 0.0f ? 8u : 0u) | level;
+    uint32_t nibble = (q[j] < 0.0f ? 8u : 0u) | (level & 7u);
     uint32_t w = get_u32(rec, 4 + j / 8);
     w |= nibble << (4 * (j % 8));
     put_u32(rec, 4 + j / 8, w);
+    for (unsigned t = 0; t < planes; ++t) {
+      uint64_t at = plane0 + t * plane_words + j / 32;
+      put_u32(rec, at, get_u32(rec, at) | (((level >> (3 + t)) & 1u) << (j % 32)));
+    }
   }
 }
 
 static void decode_dither(const orc_params *p, const unsigned char *rec, uint64_t d, float *out) {
   float nu = get_f32(rec, 0);
   float s = (float)p->levels;
+  unsigned planes = dither_planes(p->levels);
+  uint64_t plane0 = 4 + ru4((p->part_elems + 7) / 8), plane_words = ru4((p->part_elems + 31) / 32);
   for (uint64_t j = 0; j < d; ++j) {
     uint32_t nibble = (get_u32(rec, 4 + j / 8) >> (4 * (j % 8))) & 0xfu;
-    float mag = (nu * (float)(nibble & 7u)) / s;
+    uint32_t level = nibble & 7u;
+    for (unsigned t = 0; t < planes; ++t)
+      level |= ((get_u32(rec, plane0 + t * plane_words + j / 32) >> (j % 32)) & 1u) << (3 + t);
+    float mag = (nu * (float)level) / s;
     out[j] = (nibble & 8u) ? -mag : mag;
   }
 }

@@ -103,6 +103,43 @@ __global__ __launch_bounds__(kThreads) void decode_packed_kernel(Geo g, uint32_t
   }
 }
 
+// Linear dithering with bit planes (more than 7 levels): 4 consecutive elements a thread as
+// above; the level is the nibble's low three bits plus one bit from each plane, the value
+// (nu * level) / s as the format defines it.
+__global__ __launch_bounds__(kThreads) void decode_dither_wide_kernel(Geo g, uint32_t levels, const uint8_t *payload, float *out) {
+  constexpr int kRow = kThreads * 4, kRows = kTile / kRow;
+  const uint32_t p = __builtin_amdgcn_readfirstlane(blockIdx.x / g.tiles_per_part);
+  const uint32_t tile = __builtin_amdgcn_readfirstlane(blockIdx.x % g.tiles_per_part);
+  const uint32_t d = g.part_size(p);
+  const uint8_t *rec = payload + (uint64_t)p * g.stride;
+  const float nu = *reinterpret_cast<const float *>(rec);
+  const uint8_t *body = rec + kHeaderBytes;
+  const uint32_t planes = dither_planes(levels);
+  const uint8_t *plane0 = rec + dither_plane0(g.part_elems);
+  const uint64_t plane_bytes = dither_plane_bytes(g.part_elems);
+  const uint32_t valid = d - tile * kTile < (uint32_t)kTile ? d - tile * kTile : (uint32_t)kTile;
+  float *tile_out = out + g.part_base(p) + (uint64_t)tile * kTile;
+#pragma unroll
+  for (int u = 0; u < kRows; ++u) {
+    const uint32_t j = tile * kTile + u * kRow + threadIdx.x * 4;   // partition-local, a multiple of 4
+    const uint32_t half = reinterpret_cast<const uint16_t *>(body)[j >> 2];
+    uint32_t hi[4] = {0, 0, 0, 0};
+    for (uint32_t t = 0; t < planes; ++t) {
+      const uint32_t bits = plane0[t * plane_bytes + (j >> 3)] >> (j & 4);
+#pragma unroll
+      for (int c = 0; c < 4; ++c) hi[c] |= ((bits >> c) & 1u) << (3 + t);
+    }
+    float v[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const uint32_t nib = (half >> (4 * c)) & 15u;
+      const float mag = dither_mag(nu, (nib & 7u) | hi[c], levels, false);
+      v[c] = (nib & 8u) ? -mag : mag;
+    }
+    row_buf(tile_out, valid, u * kRow, kRow).store16<kNonTemporal>(as_u32x4(v[0], v[1], v[2], v[3]), threadIdx.x * 16);
+  }
+}
+
 // Top-k: out[idx_t] = val_t.  `out` was zero-filled before.
 __global__ __launch_bounds__(kThreads) void decode_topk_kernel(Geo g, const uint8_t *payload, float *out) {
   const uint32_t p = blockIdx.y;
@@ -158,6 +195,8 @@ hipError_t decode_dense(const Geo &g, const bpc_params_t &prm, const uint8_t *pa
   }
   const bool natural = prm.kind == BPC_NATDITHER;
   if (prm.kind == BPC_SIGN) decode_packed_kernel<BPC_SIGN><<<g.n_tiles, kThreads, 0, stream>>>(g, prm.levels, false, payload, out);
+  else if (prm.kind == BPC_DITHER && dither_planes(prm.levels) > 0)
+    decode_dither_wide_kernel<<<g.n_tiles, kThreads, 0, stream>>>(g, prm.levels, payload, out);
   else if (prm.kind == BPC_DITHER || natural)
     decode_packed_kernel<BPC_DITHER><<<g.n_tiles, kThreads, 0, stream>>>(g, prm.levels, natural, payload, out);
   else decode_packed_kernel<BPC_IDENTITY><<<g.n_tiles, kThreads, 0, stream>>>(g, prm.levels, false, payload, out);

@@ -25,12 +25,28 @@ __global__ __launch_bounds__(kThreads) void dither_reduce_kernel(Geo g, SRC src,
   src.begin(g, p, lds);
   double acc = 0.0;
   float mx = 0.0f;
+  if constexpr (has_at8<SRC>::value) {
+    // sources that decode a message word at a time: 8 consecutive elements a thread
 #pragma unroll
-  for (int c = 0; c < kTile / kThreads; ++c) {
-    uint32_t j = tile * kTile + c * kThreads + threadIdx.x;
-    float v = j < d ? src.at(g, p, j, lds) : 0.0f;
-    acc = fma((double)v, (double)v, acc);  // the product of two f32 is exact in f64
-    mx = fmaxf(mx, fabsf(v));
+    for (int row = 0; row < kRows; ++row) {
+      const uint32_t j0 = tile * kTile + row * kRowElems + threadIdx.x * kPerThread;
+      if (j0 >= d) continue;
+      float v8[8];
+      source_at8(src, g, p, j0, d, lds, v8);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        acc = fma((double)v8[e], (double)v8[e], acc);
+        mx = fmaxf(mx, fabsf(v8[e]));
+      }
+    }
+  } else {
+#pragma unroll
+    for (int c = 0; c < kTile / kThreads; ++c) {
+      uint32_t j = tile * kTile + c * kThreads + threadIdx.x;
+      float v = j < d ? src.at(g, p, j, lds) : 0.0f;
+      acc = fma((double)v, (double)v, acc);  // the product of two f32 is exact in f64
+      mx = fmaxf(mx, fabsf(v));
+    }
   }
   if (linf) {
     float m = block_max<kThreads>(mx, redf);
@@ -68,7 +84,8 @@ __global__ __launch_bounds__(64) void dither_finish_kernel(Geo g, const double *
 }
 
 // Level and residual of one element; `r` is the element's random word.
-__device__ inline uint32_t dither_one(float v, float nu, uint32_t s, bool natural, uint32_t r, float *resid) {
+__device__ inline uint32_t dither_one(float v, float nu, uint32_t s, bool natural, uint32_t r, const float *mags,
+                                      float *resid) {
   if (!(nu > 0.0f)) {
     *resid = v;
     return 0u;
@@ -91,9 +108,9 @@ __device__ inline uint32_t dither_one(float v, float nu, uint32_t s, bool natura
   const float u = (float)(r >> 8) * 0x1p-24f;
   uint32_t level = lower + (u < f ? 1u : 0u);
   level = level > s ? s : level;
-  const float mag = dither_mag(nu, level, s, natural);
+  const float mag = mags[level];
   *resid = v - (v < 0.0f ? -mag : mag);
-  return (v < 0.0f ? 8u : 0u) | level;
+  return (v < 0.0f ? 64u : 0u) | level;   // bit 6: sign, bits 0..5: level
 }
 
 template <class SRC>
@@ -104,33 +121,49 @@ __global__ __launch_bounds__(kThreads) void dither_apply_kernel(Geo g, SRC src, 
   const uint32_t p = blockIdx.x / g.tiles_per_part;
   const uint32_t tile = blockIdx.x % g.tiles_per_part;
   const uint32_t d = g.part_size(p);
-  src.begin(g, p, lds);
+  __shared__ float mags[64];   // decoded magnitudes of the levels 0..s
   uint8_t *rec = payload + (uint64_t)p * g.stride;
   const float nu = *reinterpret_cast<const float *>(rec);
+  if (threadIdx.x <= levels) mags[threadIdx.x] = dither_mag(nu, threadIdx.x, levels, natural);
+  src.begin(g, p, lds);   // ends with a barrier when it fills its tables
+  __syncthreads();
   uint32_t *nibs = reinterpret_cast<uint32_t *>(rec + kHeaderBytes);
   const uint32_t n_words = (uint32_t)ru4(cdiv(d, 8));
+  // bit planes of the levels above 7 (none for up to 7 levels): a byte per thread and plane
+  const uint32_t planes = natural ? 0u : dither_planes(levels);
+  uint8_t *plane0 = rec + dither_plane0(g.part_elems);
+  const uint64_t plane_stride = dither_plane_bytes(g.part_elems);
+  const uint32_t plane_bytes = planes ? (uint32_t)(4 * ru4(cdiv(d, 32))) : 0u;
   const uint64_t base = g.part_base(p);
   const Philox rng(seed, stream_id, p + g.part0);
 #pragma unroll
   for (int row = 0; row < kRows; ++row) {
     const uint32_t j0 = tile * kTile + row * kRowElems + threadIdx.x * kPerThread;
-    if ((j0 >> 3) >= n_words) continue;
+    const uint32_t w = j0 >> 3;
+    if (w >= n_words && w >= plane_bytes) continue;
     uint32_t rnd[8];
     rng.block(j0 >> 2, rnd);
     rng.block((j0 >> 2) + 1, rnd + 4);
-    uint32_t word = 0;
+    uint32_t word = 0, hi[3] = {0, 0, 0};
+    float v8[8];
+    source_at8(src, g, p, j0, d, lds, v8);
 #pragma unroll
     for (int e = 0; e < kPerThread; ++e) {
       uint32_t j = j0 + e;
       if (j < d) {
         float r;
-        float v = src.at(g, p, j, lds);
-        uint32_t nib = dither_one(v, nu, levels, natural, rnd[e], &r);
-        word |= nib << (4 * e);
+        float v = v8[e];
+        const uint32_t code = dither_one(v, nu, levels, natural, rnd[e], mags, &r);
+        word |= (((code >> 6) << 3) | (code & 7u)) << (4 * e);
+#pragma unroll
+        for (int t = 0; t < 3; ++t) hi[t] |= ((code >> (3 + t)) & 1u) << e;
         if (residual) residual[base + j] = r;
       }
     }
-    nibs[j0 >> 3] = word;
+    if (w < n_words) nibs[w] = word;
+    if (w < plane_bytes) {
+      for (uint32_t t = 0; t < planes; ++t) plane0[t * plane_stride + w] = (uint8_t)hi[t];
+    }
   }
 }
 
@@ -145,7 +178,10 @@ hipError_t dither_encode(const Geo &g_in, const bpc_params_t &prm_in, const Sour
   Geo g = g_in;
   Source src = src_in;
   bpc_params_t prm = prm_in;
-  if (sp.single_pass && sp.head.P > 0) {
+  // (the single-pass server reads and writes nibbles only: with more than 7 levels the server
+  // side takes the passes below)
+  const bool wide = prm_in.kind == BPC_DITHER && dither_planes(prm_in.levels) > 0;
+  if ((!wide || src.grad) && sp.single_pass && sp.head.P > 0) {
     bool used = false;
     hipError_t e = src.grad ? dither_worker_single_pass(sp.head, prm, src, payload, ws, stream, &used)
                             : dither_server_single_pass(sp.head, prm, src, payload, ws, stream, &used);
@@ -159,15 +195,17 @@ hipError_t dither_encode(const Geo &g_in, const bpc_params_t &prm_in, const Sour
   double *partials = ws.at<double>(ws.lay.partials);
   const int linf = prm.norm == BPC_NORM_LINF;
   const bool natural = prm.kind == BPC_NATDITHER;
-  auto make_server = [&] { return DitherMsgSource{src.msgs, src.residual, g.stride, prm.levels, natural}; };
-  return with_source(src, make_server, [&](auto s) -> hipError_t {
+  auto run = [&](auto s) -> hipError_t {
     using S = decltype(s);
     if (!prm.norm_override) dither_reduce_kernel<S><<<g.n_tiles, kThreads, 0, stream>>>(g, s, partials, linf);
     dither_finish_kernel<<<g.P, 64, 0, stream>>>(g, partials, prm.norm_override, linf, payload);
     dither_apply_kernel<S><<<g.n_tiles, kThreads, 0, stream>>>(g, s, payload, src.residual, prm.levels, natural, prm.seed,
                                                                prm.stream_id);
     return hipGetLastError();
-  });
+  };
+  if (wide && !src.grad) return run(DitherWideMsgSource{src.msgs, src.residual, g.stride, prm.levels});
+  auto make_server = [&] { return DitherMsgSource{src.msgs, src.residual, g.stride, prm.levels, natural}; };
+  return with_source(src, make_server, run);
 }
 
 }  // namespace bpc

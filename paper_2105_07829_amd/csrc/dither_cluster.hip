@@ -38,14 +38,15 @@ __device__ inline u32x4 tile_load8(const TileBuf &b, int u, const __half *) {
   return b.load16(threadIdx.x * 16, u * (kDWThreads * 16));
 }
 
-template <class G, bool EF, bool LINF, bool NAT>
+// WIDE: linear levels beyond 7, whose upper level bits go to the record's bit planes.
+template <class G, bool EF, bool LINF, bool NAT, bool WIDE = false>
 struct DitherWorkerOp {
   using GV = typename Vec8Of<G>::type;
   struct Raw { GV g[kDRows]; F32x8 e[kDRows]; };
   struct Held { float q[kDWPer]; };
   static constexpr bool kMax = LINF;
   static constexpr int kRowsPerTile = kDRows;
-  static constexpr int kTableFloats = 8;
+  static constexpr int kTableFloats = 64;   // decoded magnitudes of the levels 0..s
   static constexpr size_t kMaxDynLds = 0;
   static constexpr int kThreads = kDWThreads;
   static constexpr bool kPersistent = true;
@@ -140,7 +141,7 @@ struct DitherWorkerOp {
     uint32_t *nibs = reinterpret_cast<uint32_t *>(payload + (uint64_t)p * g.stride + kHeaderBytes);
     const uint32_t off = (u * kDWThreads + threadIdx.x) * 8;  // within the tile
     const uint32_t j0 = tile_off(item) + off;                // within the partition
-    uint32_t word = 0;
+    uint32_t word = 0, hi[3] = {0, 0, 0};
     float r[8];
     if (MODE == 0) {
 #pragma unroll
@@ -150,10 +151,26 @@ struct DitherWorkerOp {
       rng.block(j0 >> 2, rnd);
       rng.block((j0 >> 2) + 1, rnd + 4);
 #pragma unroll
-      for (int c = 0; c < 8; ++c)
-        word |= dither_quantise<MODE == 2, NAT>(h.q[8 * u + c], nu, top_over_nu, top, levels, rnd[c], mag, &r[c]) << (4 * c);
+      for (int c = 0; c < 8; ++c) {
+        const uint32_t code = dither_quantise<MODE == 2, NAT, WIDE>(h.q[8 * u + c], nu, top_over_nu, top, levels, rnd[c], mag, &r[c]);
+        if (WIDE) {
+          word |= (((code >> 6) << 3) | (code & 7u)) << (4 * c);
+#pragma unroll
+          for (int t = 0; t < 3; ++t) hi[t] |= ((code >> (3 + t)) & 1u) << c;
+        } else {
+          word |= code << (4 * c);
+        }
+      }
     }
     TileBuf(nibs + (tile_off(item) >> 3), kDWTile / 2).store4(word, threadIdx.x * 4, u * (kDWThreads * 4));
+    if (WIDE) {
+      // one byte per thread and plane: bit c = bit 3 + t of the level of the thread's element c
+      const uint8_t *rec = payload + (uint64_t)p * g.stride;
+      const uint32_t planes = dither_planes(levels);
+      for (uint32_t t = 0; t < planes; ++t)
+        TileBuf(rec + dither_plane0(g.part_elems) + t * dither_plane_bytes(g.part_elems) + (tile_off(item) >> 3), kDWTile / 8)
+            .store1(hi[t], threadIdx.x, u * kDWThreads);
+    }
     if (EF) {
       const TileBuf ob = row_buf(res + b, valid_of(item), u * (kDWThreads * 8), kDWThreads * 8);
       ob.store16(as_u32x4(r[0], r[1], r[2], r[3]), threadIdx.x * 32);
@@ -172,6 +189,15 @@ static hipError_t launch_dither(const Geo &g, const ClusterGeo &cg, const bpc_pa
                                                          prm.norm_override, prm.levels, prm.seed, prm.stream_id}, \
                         cg, slots, status, stream, used)
   const bool nat = prm.kind == BPC_NATDITHER;
+  if (!nat && dither_planes(prm.levels) > 0) {
+#define BPC_DWW(LINF)                                                                                             \
+  return launch_cluster(DitherWorkerOp<G, EF, LINF, false, true>{g, cg, (const G *)src.grad, src.residual, payload, \
+                                                                 prm.norm_override, prm.levels, prm.seed, prm.stream_id}, \
+                        cg, slots, status, stream, used)
+    if (prm.norm == BPC_NORM_LINF) BPC_DWW(true);
+    BPC_DWW(false);
+#undef BPC_DWW
+  }
   if (prm.norm == BPC_NORM_LINF) {
     if (nat) BPC_DW(true, true);
     BPC_DW(true, false);

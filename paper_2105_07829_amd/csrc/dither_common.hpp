@@ -17,7 +17,8 @@ __device__ inline int dither_mode(float nu, float s_over_nu) {
 // at a = 0, 1, 2, 4, ...: below 1 the lower level is 0 and a itself the probability; from 1
 // on the lower level is floor(log2 a) + 1 (the exponent field) and the probability is
 // a / 2^floor(log2 a) - 1 (the fraction bits), both exact.
-template <bool SLOW, bool NAT>
+// WIDE (linear levels beyond 7): the result is (sign << 6) | level instead of the nibble.
+template <bool SLOW, bool NAT, bool WIDE = false>
 __device__ inline uint32_t dither_quantise(float q, float nu, float top_over_nu, float top, uint32_t s, uint32_t r,
                                            const float *mag, float *resid) {
   const float a = SLOW ? (fabsf(q) * top) / nu : fabsf(q) * top_over_nu;
@@ -38,7 +39,7 @@ __device__ inline uint32_t dither_quantise(float q, float nu, float top_over_nu,
   level = level > s ? s : level;
   const float m = mag[level];
   *resid = q - (q < 0.0f ? -m : m);
-  return (q < 0.0f ? 8u : 0u) | level;
+  return (q < 0.0f ? (WIDE ? 64u : 8u) : 0u) | level;
 }
 
 // All threads of the workgroup: mag[l] = decoded magnitude of level l for l = 0..s.

@@ -17,11 +17,9 @@ namespace bpc {
 constexpr int kMaxWorkers = 64;      // most worker messages one aggregate call accepts
 constexpr int kTile = 4096;          // elements one workgroup handles in the streaming kernels
 constexpr int kThreads = 256;        // workgroup size of the streaming kernels
-constexpr int kCPerThread = 32;      // elements a thread of the single-pass (cluster) kernels keeps in registers
-constexpr int kWThreads = 1024;      // workgroup size of the worker-side cluster kernels (persistent, one per CU)
-constexpr int kSThreads = 256;       // workgroup size of the server-side cluster kernels (one small workgroup per tile)
-constexpr int kWTile = kWThreads * kCPerThread;  // 32768
-constexpr int kSTile = kSThreads * kCPerThread;  // 8192
+constexpr int kSThreads = 256;       // workgroup size of the server-side kernels when the number of workers is not one they are compiled for
+constexpr int kWTile = 16384;        // tile of the worker-side single-pass kernels (1024 threads x 16 elements)
+constexpr int kSTile = 8192;         // tile of the server-side single-pass kernels and of single-pass LANS
 constexpr uint32_t kHeaderBytes = 16;
 
 BPC_HD inline uint64_t ru4(uint64_t x) { return (x + 3) / 4 * 4; }
@@ -62,18 +60,31 @@ inline bool params_valid(const bpc_params_t *p) {
   switch (p->kind) {
     case BPC_IDENTITY: case BPC_SIGN: return true;
     case BPC_TOPK: case BPC_RANDK: return p->k_ratio > 0.0 && p->k_ratio <= 1.0;
-    case BPC_DITHER: case BPC_NATDITHER:
+    case BPC_DITHER:
+      return p->levels >= 1 && p->levels <= 63 && (p->norm == BPC_NORM_L2 || p->norm == BPC_NORM_LINF);
+    case BPC_NATDITHER:
       return p->levels >= 1 && p->levels <= 7 && (p->norm == BPC_NORM_L2 || p->norm == BPC_NORM_LINF);
     default: return false;
   }
 }
+
+// Bit planes that follow the nibbles of a linear-dithering record: level bits 3, 4, 5.
+BPC_HD inline uint32_t dither_planes(uint32_t levels) {
+  uint32_t planes = 0;
+  while ((levels >> (3 + planes)) != 0) ++planes;
+  return planes;
+}
+// Byte offset of plane 0 in a record, and bytes from one plane to the next.
+BPC_HD inline uint64_t dither_plane0(uint64_t part_elems) { return kHeaderBytes + 4 * ru4(cdiv(part_elems, 8)); }
+BPC_HD inline uint64_t dither_plane_bytes(uint64_t part_elems) { return 4 * ru4(cdiv(part_elems, 32)); }
 
 inline size_t stride_of(const bpc_params_t *p) {
   uint64_t d = p->part_elems, words = 0;
   switch (p->kind) {
     case BPC_IDENTITY: words = ru4(d); break;
     case BPC_SIGN:     words = ru4(cdiv(d, 32)); break;
-    case BPC_DITHER: case BPC_NATDITHER: words = ru4(cdiv(d, 8)); break;
+    case BPC_DITHER:   words = ru4(cdiv(d, 8)) + dither_planes(p->levels) * ru4(cdiv(d, 32)); break;
+    case BPC_NATDITHER: words = ru4(cdiv(d, 8)); break;
     case BPC_TOPK:     words = 2 * ru4(k_rule(p->k_ratio, d)); break;
     case BPC_RANDK:    words = ru4(k_rule(p->k_ratio, d)); break;
   }
@@ -115,7 +126,8 @@ inline WsLayout ws_layout(const bpc_params_t *p, uint64_t D) {
   WsLayout w;
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off += (bytes + 255) / 256 * 256; return o; };
-  bool sparse = p->kind == BPC_TOPK || p->kind == BPC_RANDK;
+  // kinds whose update reads a dense decode of the message from the workspace
+  bool sparse = p->kind == BPC_TOPK || p->kind == BPC_RANDK || (p->kind == BPC_DITHER && dither_planes(p->levels) > 0);
   w.partials = take(sizeof(double) * (size_t)g.n_tiles);
   w.dense = take(sparse ? sizeof(float) * (size_t)D : 0);
   w.hist = take(p->kind == BPC_TOPK ? sizeof(uint32_t) * 4096 * (size_t)g.P : 0);

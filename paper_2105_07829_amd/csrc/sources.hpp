@@ -6,6 +6,7 @@
 #pragma once
 #include "device_utils.hpp"
 #include "kernels.hpp"
+#include <type_traits>
 
 namespace bpc {
 
@@ -76,6 +77,86 @@ struct DitherMsgSource {
     return res ? mean + res[g.part_base(p) + j] : mean;
   }
 };
+
+// The same for linear dithering with bit planes (more than 7 levels): a table per worker of
+// the decoded magnitudes (nu_i * level) / s of its levels 0..s (at most 64).
+struct DitherWideMsgSource {
+  WorkerMsgs msgs;
+  const float *res;
+  uint64_t stride;
+  uint32_t levels;
+  static constexpr int kLdsFloats = kMaxWorkers * 64;
+  __device__ void begin(const Geo &, uint32_t p, float *lds) const {
+    for (int e = threadIdx.x; e < msgs.n * 64; e += blockDim.x) {
+      const int i = e >> 6;
+      const uint32_t level = e & 63;
+      const float nu = *reinterpret_cast<const float *>(msgs.ptr[i] + (uint64_t)p * stride);
+      lds[e] = level <= levels ? dither_mag(nu, level, levels, false) : 0.0f;
+    }
+    __syncthreads();
+  }
+  __device__ float at(const Geo &g, uint32_t p, uint32_t j, const float *lds) const {
+    const uint32_t planes = dither_planes(levels);
+    const uint64_t plane0 = dither_plane0(g.part_elems), plane_bytes = dither_plane_bytes(g.part_elems);
+    float acc = 0.0f;
+    for (int i = 0; i < msgs.n; ++i) {
+      const uint8_t *rec = msgs.ptr[i] + (uint64_t)p * stride;
+      const uint32_t nib = (reinterpret_cast<const uint32_t *>(rec + kHeaderBytes)[j >> 3] >> (4 * (j & 7))) & 15u;
+      uint32_t level = nib & 7u;
+      for (uint32_t t = 0; t < planes; ++t)
+        level |= ((reinterpret_cast<const uint32_t *>(rec + plane0 + t * plane_bytes)[j >> 5] >> (j & 31)) & 1u) << (3 + t);
+      const float mag = lds[i * 64 + level];
+      acc = acc + ((nib & 8u) ? -mag : mag);
+    }
+    float mean = acc * msgs.inv_n;
+    return res ? mean + res[g.part_base(p) + j] : mean;
+  }
+  // Elements j0 .. j0+7 (j0 a multiple of 8) at once: one nibble word and one byte per plane
+  // and worker instead of eight of each.  Same sums in the same order as at().
+  __device__ void at8(const Geo &g, uint32_t p, uint32_t j0, uint32_t d, const float *lds, float out[8]) const {
+    const uint32_t planes = dither_planes(levels);
+    const uint64_t plane0 = dither_plane0(g.part_elems), plane_bytes = dither_plane_bytes(g.part_elems);
+    float acc[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = 0.0f;
+    for (int i = 0; i < msgs.n; ++i) {
+      const uint8_t *rec = msgs.ptr[i] + (uint64_t)p * stride;
+      const uint32_t word = reinterpret_cast<const uint32_t *>(rec + kHeaderBytes)[j0 >> 3];
+      uint32_t hi[3] = {0, 0, 0};
+      for (uint32_t t = 0; t < planes; ++t) hi[t] = rec[plane0 + t * plane_bytes + (j0 >> 3)];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const uint32_t nib = (word >> (4 * e)) & 15u;
+        const uint32_t level = (nib & 7u) | (((hi[0] >> e) & 1u) << 3) | (((hi[1] >> e) & 1u) << 4) | (((hi[2] >> e) & 1u) << 5);
+        const float mag = lds[i * 64 + level];
+        acc[e] = acc[e] + ((nib & 8u) ? -mag : mag);
+      }
+    }
+    const uint64_t base = g.part_base(p);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float mean = acc[e] * msgs.inv_n;
+      out[e] = j0 + e < d ? (res ? mean + res[base + j0 + e] : mean) : 0.0f;
+    }
+  }
+};
+
+// Eight consecutive elements of a source: its own at8() if it has one, else eight at() calls;
+// elements at or past d are 0.
+template <class SRC, class = void>
+struct has_at8 : std::false_type {};
+template <class SRC>
+struct has_at8<SRC, std::void_t<decltype(&SRC::at8)>> : std::true_type {};
+template <class SRC>
+__device__ inline void source_at8(const SRC &src, const Geo &g, uint32_t p, uint32_t j0, uint32_t d, const float *lds,
+                                  float out[8]) {
+  if constexpr (has_at8<SRC>::value) {
+    src.at8(g, p, j0, d, lds, out);
+  } else {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) out[e] = j0 + e < d ? src.at(g, p, j0 + e, lds) : 0.0f;
+  }
+}
 
 // Delta from n identity messages (plain averaging, Algorithm 1).
 struct IdentityMsgSource {

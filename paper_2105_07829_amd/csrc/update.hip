@@ -550,15 +550,15 @@ hipError_t adaptive_update(const Geo &g, const bpc_params_t &prm, const uint8_t 
   switch (prm.kind) {
     case BPC_SIGN: return run_update(g, SignDec{payload, g.stride}, x, m, v, opt, norms, ws, stream);
     case BPC_DITHER: case BPC_NATDITHER:
+      if (prm.kind == BPC_DITHER && dither_planes(prm.levels) > 0) break;   // bit planes: through the dense decode below
       return run_update(g, DitherDec{payload, g.stride, prm.levels, prm.kind == BPC_NATDITHER}, x, m, v, opt, norms, ws, stream);
     case BPC_IDENTITY: return run_update(g, IdentityDec{payload, g.stride}, x, m, v, opt, norms, ws, stream);
-    default: {
-      float *dense = ws.at<float>(ws.lay.dense);
-      hipError_t e = decode_dense(g, prm, payload, dense, stream);
-      if (e != hipSuccess) return e;
-      return run_update(g, DenseDec{dense}, x, m, v, opt, norms, ws, stream);
-    }
+    default: break;
   }
+  float *dense = ws.at<float>(ws.lay.dense);
+  hipError_t e = decode_dense(g, prm, payload, dense, stream);
+  if (e != hipSuccess) return e;
+  return run_update(g, DenseDec{dense}, x, m, v, opt, norms, ws, stream);
 }
 
 }  // namespace bpc

@@ -44,6 +44,9 @@ WORKLOADS = {
     # not a BASELINE configuration: the bert_large shape with the natural (power-of-two) level map
     "bert_large_natural": dict(D=336_000_000, dtype="f16", dist="student_t3", kind="natdither", levels=4,
                                n_workers=16, ef=True, opt="adam"),
+    # nor is this: the 5-bit form of linear dithering (15 levels: nibbles and one bit plane)
+    "bert_large_5bit": dict(D=336_000_000, dtype="f16", dist="student_t3", kind="dither", levels=15,
+                            n_workers=16, ef=True, opt="adam"),
 }
 
 

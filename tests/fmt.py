@@ -14,12 +14,22 @@ def k_of(k_ratio, d):
     return min(d, max(1, int(np.floor(k_ratio * d))))
 
 
-def stride(kind, part_elems, k_ratio=0.0):
+def dither_planes(levels):
+    """Bit planes after the nibbles of a linear-dithering record: level bits 3, 4, 5."""
+    planes = 0
+    while (levels >> (3 + planes)) != 0:
+        planes += 1
+    return planes
+
+
+def stride(kind, part_elems, k_ratio=0.0, levels=4):
     if kind == "identity":
         words = ru4(part_elems)
     elif kind == "sign":
         words = ru4((part_elems + 31) // 32)
-    elif kind in ("dither", "natdither"):
+    elif kind == "dither":
+        words = ru4((part_elems + 7) // 8) + dither_planes(levels) * ru4((part_elems + 31) // 32)
+    elif kind == "natdither":
         words = ru4((part_elems + 7) // 8)
     elif kind == "topk":
         words = 2 * ru4(k_of(k_ratio, part_elems))
@@ -66,6 +76,19 @@ def dither_nibbles(rec, d):
     return header_f32(rec), (nib & 8) != 0, nib & 7, words
 
 
+def dither_levels(rec, d, part_elems, levels):
+    """-> (nu, sign bool[d], level uint8[d]) of a linear-dithering record with its bit planes."""
+    nu, sgn, lvl, _ = dither_nibbles(rec, d)
+    lvl = lvl.astype(np.uint8)
+    off0 = 16 + 4 * ru4((part_elems + 7) // 8)
+    pw = 4 * ru4((part_elems + 31) // 32)
+    for t in range(dither_planes(levels)):
+        words = rec[off0 + t * pw:off0 + t * pw + 4 * ((d + 31) // 32)].view(np.uint32)
+        bits = np.unpackbits(words.view(np.uint8), bitorder="little")[:d]
+        lvl |= (bits << (3 + t)).astype(np.uint8)
+    return nu, sgn, lvl
+
+
 def topk_entries(rec, k_cap):
     k = header_u32(rec)
     idx = rec[16:16 + 4 * k].view(np.int32)
@@ -79,8 +102,13 @@ def randk_values(rec):
     return k, rec[16:16 + 4 * k].view(np.float32)
 
 
-def defined_bytes(kind, d, k=0, k_cap=0):
+def defined_bytes(kind, d, k=0, k_cap=0, part_elems=0, levels=4):
     """Byte ranges of a record that the format defines for a partition of d elements."""
+    if kind == "dither" and dither_planes(levels) > 0:
+        off0 = 16 + 4 * ru4((part_elems + 7) // 8)
+        pw = 4 * ru4((part_elems + 31) // 32)
+        return [(0, 16 + 4 * ru4((d + 7) // 8))] + [(off0 + t * pw, off0 + t * pw + 4 * ru4((d + 31) // 32))
+                                                    for t in range(dither_planes(levels))]
     if kind == "identity":
         return [(0, 16 + 4 * d)]
     if kind == "sign":

@@ -31,14 +31,15 @@ def sample_partitions(P):
     return sorted({0, P // 2, P - 1})
 
 
-def record_equal(kind, rec_g, rec_o, d, k, k_cap):
-    for lo, hi in fmt.defined_bytes(kind, d, k, k_cap):
+def record_equal(kind, rec_g, rec_o, d, k, k_cap, pe=0, levels=4):
+    for lo, hi in fmt.defined_bytes(kind, d, k, k_cap, part_elems=pe, levels=levels):
         if not np.array_equal(rec_g[lo:hi], rec_o[lo:hi]):
             return False
     return True
 
 
-@pytest.mark.parametrize("name", ["sign_1m", "resnet50", "vgg16", "bert_base", "bert_large", "bert_large_natural"])
+@pytest.mark.parametrize("name", ["sign_1m", "resnet50", "vgg16", "bert_base", "bert_large", "bert_large_natural",
+                                  "bert_large_5bit"])
 def test_full_size_pipeline(env, orc, name):
     gu, synth, torch = env
     bpc = gu.bpc
@@ -97,7 +98,7 @@ def test_full_size_pipeline(env, orc, name):
             if hg != ho:       # packed bits on equal terms: oracle with the GPU's scale
                 res_o = e_host[p].copy()
                 rec_o = orc.compress(prm_o((1 << 32) | 0, p, norm=hg), g_host[p], res_o)
-        assert record_equal(kind, rec_g, rec_o, d, k, k_cap), (name, "worker", p)
+        assert record_equal(kind, rec_g, rec_o, d, k, k_cap, pe, kw["levels"]), (name, "worker", p)
         if kind == "topk":
             assert np.array_equal(e_after[p].view(np.uint32), res_o.view(np.uint32))
         else:
@@ -131,7 +132,7 @@ def test_full_size_pipeline(env, orc, name):
             ko, vo = fmt.randk_values(rec_o)
             assert kg == ko and gu.close(vg, vo, REL)
         else:
-            assert record_equal(kind, rec_g, rec_o, d, k, k_cap), (name, "server", p)
+            assert record_equal(kind, rec_g, rec_o, d, k, k_cap, pe, kw["levels"]), (name, "server", p)
         got = sres[sl(p)].cpu().numpy()
         if kind == "topk":
             assert np.array_equal(got.view(np.uint32), res_o.view(np.uint32))

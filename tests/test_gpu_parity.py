@@ -40,6 +40,8 @@ KW = {
     "randk_scaled": dict(k_ratio=0.02, value_scale=-1.0, seed=99, stream_id=3),
     "dither": dict(levels=4, seed=0xFEEDFACECAFEBEEF, stream_id=(7 << 32) | 1),
     "dither_linf": dict(levels=7, norm=1, seed=5, stream_id=9),
+    "dither_5bit": dict(levels=15, seed=0xC0FFEE, stream_id=(5 << 32) | 3),
+    "dither_7bit": dict(levels=63, norm=1, seed=77, stream_id=(6 << 32) | 4),
     "natdither": dict(levels=5, seed=0xABCDEF, stream_id=(3 << 32) | 2),
     "natdither_linf": dict(levels=3, norm=1, seed=6, stream_id=10),
 }
@@ -66,7 +68,7 @@ def compare_payload(gu, orc, name, po, pay_gpu, pay_ref, D, pe, ref_fn):
     for p, d in enumerate(sizes):
         rg, rr = fmt.record(pay_gpu, p, strd), fmt.record(pay_ref, p, strd)
         k = fmt.k_of(KW[name]["k_ratio"], d) if k_cap else 0
-        for lo, hi in fmt.defined_bytes(kind, d, k, k_cap):
+        for lo, hi in fmt.defined_bytes(kind, d, k, k_cap, part_elems=pe, levels=KW[name].get("levels", 4)):
             assert np.array_equal(rg[lo:hi], rr[lo:hi]), (name, "partition", p, "bytes", lo, hi)
     return pay_ref
 
@@ -254,7 +256,7 @@ def test_update_stage(gu, orc, name, opt_kind):
 def test_deterministic_bytes(gu, orc):
     """Same call twice gives identical bytes for the kinds whose arithmetic has a fixed order."""
     D = 2 * PE + 4137
-    for name in ("sign", "topk", "dither", "natdither", "identity"):
+    for name in ("sign", "topk", "dither", "dither_7bit", "natdither", "identity"):
         po, pb = gu.both_params(orc, base_kind(name), PE, **KW[name])
         g = grads(D, np.float16, 8)
         e = (rng(9).standard_normal(D) * 3e-4).astype(np.float32)
@@ -264,11 +266,12 @@ def test_deterministic_bytes(gu, orc):
         strd = orc.partition_stride(po)
         for p, d in enumerate(fmt.part_sizes(D, PE)):
             k = fmt.k_of(KW[name].get("k_ratio", 1.0), d)
-            for lo, hi in fmt.defined_bytes(name, d, k, fmt.k_of(KW[name].get("k_ratio", 1.0), PE)):
+            for lo, hi in fmt.defined_bytes(base_kind(name), d, k, fmt.k_of(KW[name].get("k_ratio", 1.0), PE),
+                                            part_elems=PE, levels=KW[name].get("levels", 4)):
                 assert np.array_equal(fmt.record(a[0], p, strd)[lo:hi], fmt.record(b[0], p, strd)[lo:hi])
 
 
-@pytest.mark.parametrize("name", ["sign", "topk", "dither", "natdither", "randk", "identity"])
+@pytest.mark.parametrize("name", ["sign", "topk", "dither", "dither_5bit", "natdither", "randk", "identity"])
 def test_chained_pipeline_three_steps(gu, orc, name):
     """Algorithm 4 + the Adam-style update chained on the GPU only (each stage consumes the GPU's
     own previous outputs) against the chained oracle."""
@@ -287,7 +290,7 @@ def test_chained_pipeline_three_steps(gu, orc, name):
             kw = dict(KW[name])
             if "stream_id" in kw:
                 kw["stream_id"] = (t << 32) | i
-            po, pb = gu.both_params(orc, name, PE, **kw)
+            po, pb = gu.both_params(orc, base_kind(name), PE, **kw)
             ins.append((po, pb))
             g = grads(D, np.float16, 1000 * t + i)
             pay_o.append(orc.compress(po, g, e_o[i]))
@@ -296,13 +299,13 @@ def test_chained_pipeline_three_steps(gu, orc, name):
         kw = dict(KW[name])
         if "stream_id" in kw:
             kw["stream_id"] = (t << 32) | (1 << 16)
-        out_o, out_b = gu.both_params(orc, name, PE, **kw)
+        out_o, out_b = gu.both_params(orc, base_kind(name), PE, **kw)
         p_o = orc.server_aggregate([p[0] for p in ins], pay_o, out_o, et_o, D)
         p_g, et_g = gu.gpu_server([p[1] for p in ins], pay_g, out_b, et_g, D)
-        if name in ("sign", "dither", "natdither"):
+        if base_kind(name) in ("sign", "dither", "natdither"):
             strd = orc.partition_stride(out_o)
             for p, d in enumerate(fmt.part_sizes(D, PE)):
-                for lo, hi in fmt.defined_bytes(name, d):
+                for lo, hi in fmt.defined_bytes(base_kind(name), d, part_elems=PE, levels=KW[name].get("levels", 4)):
                     diff_bytes += int((fmt.record(p_o, p, strd)[lo:hi] != fmt.record(p_g, p, strd)[lo:hi]).sum())
         oo = orc.make_opt(orc.OPT_ADAM, 1e-3, 0.9, 0.999, 1e-8, 0.01, t)
         ob = bpc.make_opt(bpc.OPT_ADAM, 1e-3, 0.9, 0.999, 1e-8, 0.01, t)
@@ -315,5 +318,5 @@ def test_chained_pipeline_three_steps(gu, orc, name):
         assert gu.close(a, b, 1e-5 if name == "randk" else REL)
     for i in range(n):
         assert gu.close(e_g[i], e_o[i], 1e-5 if name == "randk" else REL)
-    if name in ("sign", "dither", "natdither"):
+    if base_kind(name) in ("sign", "dither", "natdither"):
         assert diff_bytes == 0

@@ -36,6 +36,8 @@ def test_sizes_follow_the_record_format(bpc):
     assert bpc.partition_stride(bpc.make_params(bpc.SIGN, pe)) == fmt.stride("sign", pe)
     assert bpc.partition_stride(bpc.make_params(bpc.DITHER, pe)) == fmt.stride("dither", pe)
     assert bpc.partition_stride(bpc.make_params(bpc.NATDITHER, pe)) == fmt.stride("natdither", pe)
+    for s in (7, 8, 15, 16, 31, 32, 63):     # 4, 5, 6 and 7 bits per element
+        assert bpc.partition_stride(bpc.make_params(bpc.DITHER, pe, levels=s)) == fmt.stride("dither", pe, levels=s)
     assert bpc.partition_stride(bpc.make_params(bpc.IDENTITY, pe)) == fmt.stride("identity", pe)
     assert bpc.partition_stride(bpc.make_params(bpc.TOPK, pe, k_ratio=0.01)) == fmt.stride("topk", pe, 0.01)
     assert bpc.partition_stride(bpc.make_params(bpc.RANDK, pe, k_ratio=0.01)) == fmt.stride("randk", pe, 0.01)
@@ -63,7 +65,8 @@ def test_invalid_params_are_rejected(bpc):
     bad = [bpc.make_params(bpc.SIGN, 0), bpc.make_params(bpc.SIGN, 1000), bpc.make_params(9, 1024),
            bpc.make_params(bpc.TOPK, 1024, k_ratio=0.0), bpc.make_params(bpc.TOPK, 1024, k_ratio=1.5),
            bpc.make_params(bpc.RANDK, 1024, k_ratio=-1.0), bpc.make_params(bpc.DITHER, 1024, levels=0),
-           bpc.make_params(bpc.DITHER, 1024, levels=8), bpc.make_params(bpc.DITHER, 1024, norm=5)]
+           bpc.make_params(bpc.DITHER, 1024, levels=64), bpc.make_params(bpc.NATDITHER, 1024, levels=8),
+           bpc.make_params(bpc.DITHER, 1024, norm=5)]
     for p in bad:
         assert bpc.partition_stride(p) == 0
         assert bpc.payload_bytes(p, 4096) == 0

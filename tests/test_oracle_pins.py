@@ -289,6 +289,67 @@ def test_dither_uses_one_draw_per_element_in_index_order(orc):
         assert lvl[j] == exp
 
 
+@pytest.mark.parametrize("s", [15, 63, 20])
+def test_dither_with_bit_planes_unbiased_bounded_and_sized(orc, s):
+    """The 5- and 7-bit forms (and one in between): 4 + planes bits per element, levels up to s
+    split over the nibble and the planes, the same two-neighbour rounding, unbiased."""
+    d, trials = 40, 6000
+    planes = {15: 1, 63: 3, 20: 2}[s]
+    p0 = orc.make_params(orc.DITHER, PE, levels=s, norm=orc.NORM_LINF)
+    assert orc.partition_stride(p0) == 16 + 4 * (fmt.ru4(PE // 8) + planes * fmt.ru4(PE // 32))
+    assert orc.partition_stride(p0) == fmt.stride("dither", PE, levels=s)
+    x = rng(50 + s).standard_normal(d).astype(np.float32)
+    x[3] = np.abs(x).max() * np.float32(-1.5)      # the largest magnitude is negative: top level with the sign bit
+    nu_ref = np.abs(x).max()
+    acc = np.zeros(d)
+    acc2 = np.zeros(d)
+    seen_top = False
+    for t in range(trials):
+        p = orc.make_params(orc.DITHER, PE, levels=s, norm=orc.NORM_LINF, seed=t, stream_id=5)
+        rec = orc.encode_partition(p, 0, x)
+        nu, sgn, lvl = fmt.dither_levels(rec, d, PE, s)
+        assert nu == nu_ref and lvl.max() <= s and np.array_equal(sgn, x < 0)
+        assert lvl[3] == s
+        a = np.abs(x.astype(np.float64)) * s / float(nu)
+        assert np.all((lvl >= np.floor(a) - 1e-6) & (lvl <= np.floor(a) + 1 + 1e-6))
+        dec = orc.decode_partition(p, 0, rec, d)
+        # decode is (nu * level) / s, element by element
+        exp = (np.float32(nu) * lvl.astype(np.float32)) / np.float32(s)
+        assert np.array_equal(np.abs(dec), exp)
+        acc += dec
+        acc2 += dec.astype(np.float64) ** 2
+    mean = acc / trials
+    se = np.sqrt(np.maximum(acc2 / trials - mean ** 2, 1e-30) / trials)
+    assert np.all(np.abs(mean - x) <= 4.5 * se + 1e-6)
+
+
+def test_dither_bit_planes_take_the_high_level_bits_in_element_order(orc):
+    """Grid points need no rounding, so the record is known bit for bit: nibble = sign and the
+    low three level bits, plane t = bit 3 + t of each level, LSB first, planes at offsets fixed
+    by the partition size."""
+    s = 63
+    lv = np.array([63, 0, 8, 7, 16, 32, 40, 21, 1, 62] * 4, dtype=np.uint32)      # 40 elements: two plane words
+    sg = np.where(np.arange(lv.size) % 3 == 0, -1.0, 1.0).astype(np.float32)
+    x = sg * lv.astype(np.float32) * np.float32(2.0 ** -6)
+    x[0] = np.float32(-63 * 2.0 ** -6)
+    p = orc.make_params(orc.DITHER, PE, levels=s, norm=orc.NORM_LINF, seed=1)
+    rec = orc.encode_partition(p, 0, x)
+    assert fmt.header_f32(rec) == np.float32(63 * 2.0 ** -6)
+    nib_words = rec[16:16 + 4 * fmt.ru4((x.size + 7) // 8)].view(np.uint32)
+    for j in range(x.size):
+        nib = (int(nib_words[j // 8]) >> (4 * (j % 8))) & 15
+        assert nib == (8 if x[j] < 0 else 0) | (int(lv[j]) & 7)
+    off0 = 16 + 4 * fmt.ru4(PE // 8)
+    for t in range(3):
+        words = rec[off0 + t * 4 * fmt.ru4(PE // 32):][:8].view(np.uint32)
+        for j in range(x.size):
+            assert (int(words[j // 32]) >> (j % 32)) & 1 == (int(lv[j]) >> (3 + t)) & 1
+    assert np.array_equal(orc.decode_partition(p, 0, rec, x.size), x)
+    # with up to 7 levels there are no planes and the record is the nibble record as before
+    p7 = orc.make_params(orc.DITHER, PE, levels=7)
+    assert orc.partition_stride(p7) == 16 + 4 * fmt.ru4(PE // 8)
+
+
 # ---------------------------------------------------------------- natural dithering
 @pytest.mark.parametrize("norm", ["l2", "linf"])
 def test_natural_dither_unbiased_on_power_of_two_levels(orc, norm):
