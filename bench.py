@@ -48,6 +48,8 @@ def payload_bytes_per_elem(w):
         while k == "dither" and (levels >> (3 + planes)):
             planes += 1
         return 0.5 + planes / 8
+    if k == "fp16":
+        return 2.0
     if k == "topk":
         return 8 * w["k_ratio"]
     if k == "randk":
@@ -73,7 +75,7 @@ class Pipeline:
         self.D, self.n = w["D"], w["n_workers"]
         self.pe = synth.part_elems(w["dtype"])
         kind = {"sign": bpc.SIGN, "topk": bpc.TOPK, "randk": bpc.RANDK, "dither": bpc.DITHER,
-                "natdither": bpc.NATDITHER}[w["kind"]]
+                "natdither": bpc.NATDITHER, "fp16": bpc.FP16}[w["kind"]]
         self.kw = dict(k_ratio=w.get("k_ratio", 0.01), levels=w.get("levels", 4),
                        value_scale=w.get("value_scale", 1.0), seed=synth.BASE_SEED)
         self.kind = kind
@@ -172,7 +174,7 @@ def cpu_baseline(name, w, n_parts, n_steps, synth):
     D = pe * n_parts
     cores = min(os.cpu_count() or 1, 16)
     kind = {"sign": oracle.SIGN, "topk": oracle.TOPK, "randk": oracle.RANDK, "dither": oracle.DITHER,
-            "natdither": oracle.NATDITHER}[w["kind"]]
+            "natdither": oracle.NATDITHER, "fp16": oracle.FP16}[w["kind"]]
     kw = dict(k_ratio=w.get("k_ratio", 0.01), levels=w.get("levels", 4), value_scale=w.get("value_scale", 1.0),
               seed=synth.BASE_SEED)
     grads = [synth.host_gradient(w["dist"], D, w["dtype"], worker=i) for i in range(n)]

@@ -15,7 +15,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SO = os.path.join(_HERE, "libbpc_oracle.so")
 
-IDENTITY, SIGN, TOPK, RANDK, DITHER, NATDITHER = 0, 1, 2, 3, 4, 5
+IDENTITY, SIGN, TOPK, RANDK, DITHER, NATDITHER, FP16 = 0, 1, 2, 3, 4, 5, 6
 F32, F16 = 0, 1
 NORM_L2, NORM_LINF = 0, 1
 OPT_LANS, OPT_ADAM = 0, 1
@@ -60,6 +60,8 @@ def lib():
         L.orc_philox4x32_10.restype = None
         L.orc_half_to_float.argtypes = [C.c_uint16]
         L.orc_half_to_float.restype = C.c_float
+        L.orc_float_to_half.argtypes = [C.c_float]
+        L.orc_float_to_half.restype = C.c_uint16
         L.orc_partition_k.argtypes = [C.POINTER(Params), C.c_uint64]
         L.orc_partition_k.restype = C.c_uint64
         L.orc_partition_stride.argtypes = [C.POINTER(Params)]
@@ -137,6 +139,10 @@ def philox4x32_10(ctr, key) -> np.ndarray:
 
 def half_to_float(h: int) -> float:
     return float(lib().orc_half_to_float(int(h)))
+
+
+def float_to_half(x: float) -> int:
+    return int(lib().orc_float_to_half(float(x)))
 
 
 def partition_k(p: Params, d: int) -> int:

@@ -64,6 +64,37 @@ float orc_half_to_float(uint16_t h) {
 
 static uint32_t float_bits(float x) { uint32_t u; memcpy(&u, &x, 4); return u; }
 
+/* IEEE binary32 -> binary16, round to nearest, ties to even; magnitudes that round past the
+ * largest half (65504) become infinity, NaN stays NaN.  Done on the exact value: the float is
+ * m * 2^e with an integer m < 2^24, a half is an integer multiple of 2^max(e_h - 10, -24). */
+uint16_t orc_float_to_half(float x) {
+  uint32_t u = float_bits(x);
+  uint16_t sign = (uint16_t)((u >> 16) & 0x8000u);
+  uint32_t expo = (u >> 23) & 0xffu, frac = u & 0x7fffffu;
+  if (expo == 255) return (uint16_t)(sign | 0x7c00u | (frac ? 0x200u : 0u));
+  if (expo == 0) return sign;                       /* float zero/subnormal: below half the smallest half */
+  int e = (int)expo - 127;                          /* |x| = (1.frac) * 2^e */
+  uint64_t m = (uint64_t)(frac | 0x800000u);        /* |x| = m * 2^(e-23) */
+  /* spacing of the halves around |x|: 2^(e-10) for normal halves (e >= -14), else 2^-24 */
+  int unit = e >= -14 ? e - 10 : -24;
+  int shift = unit - (e - 23);                      /* |x| / 2^unit = m / 2^shift, shift >= 13 */
+  uint64_t q, rem, half_way;
+  if (shift >= 40) { q = 0; rem = 1; half_way = 2; }   /* far below half a unit */
+  else {
+    q = m >> shift;
+    rem = m & (((uint64_t)1 << shift) - 1);
+    half_way = (uint64_t)1 << (shift - 1);
+  }
+  if (rem > half_way || (rem == half_way && (q & 1u))) ++q;
+  /* q units of 2^unit: q < 2048 at entry; a carry to 2048 moves to the next exponent by itself
+   * because the half encoding is monotone in (exponent, fraction) */
+  uint32_t bits;
+  if (e >= -14) bits = ((uint32_t)(e + 15) << 10) + (uint32_t)(q - 1024);   /* q in [1024, 2048] */
+  else bits = (uint32_t)q;                                                    /* subnormal, or 1024 = smallest normal */
+  if (bits >= 0x7c00u) bits = 0x7c00u;              /* past 65504: infinity */
+  return (uint16_t)(sign | bits);
+}
+
 /* ------------------------------------------------------------------ */
 /* Sizes                                                               */
 /* ------------------------------------------------------------------ */
@@ -73,7 +104,7 @@ static int params_ok(const orc_params *p) {
   if (!p) return 0;
   if (p->part_elems == 0 || p->part_elems % 1024 != 0) return 0;
   switch (p->kind) {
-    case ORC_IDENTITY: case ORC_SIGN: return 1;
+    case ORC_IDENTITY: case ORC_SIGN: case ORC_FP16: return 1;
     case ORC_TOPK: case ORC_RANDK: return p->k_ratio > 0.0 && p->k_ratio <= 1.0;
     case ORC_DITHER:
       return p->levels >= 1 && p->levels <= 63 && (p->norm == ORC_NORM_L2 || p->norm == ORC_NORM_LINF);
@@ -113,6 +144,7 @@ size_t orc_partition_stride(const orc_params *p) {
     case ORC_NATDITHER: words = ru4((d + 7) / 8); break;
     case ORC_TOPK:     words = 2 * ru4(orc_partition_k(p, d)); break;
     case ORC_RANDK:    words = ru4(orc_partition_k(p, d)); break;
+    case ORC_FP16:     words = ru4((d + 1) / 2); break;
   }
   return (size_t)(16 + 4 * words);
 }
@@ -375,6 +407,24 @@ static void decode_identity(const unsigned char *rec, uint64_t d, float *out) {
   for (uint64_t j = 0; j < d; ++j) out[j] = get_f32(rec, 4 + j);
 }
 
+/* The data type conversion the paper uses where anything heavier would not pay (Section 4.1:
+ * FP32 to FP16 inside a node; Section 5.1 lists the half-precision baseline): every element is
+ * rounded to the nearest half, ties to even. */
+static void encode_fp16(const float *q, uint64_t d, unsigned char *rec) {
+  put_u32(rec, 0, 0); put_u32(rec, 1, 0); put_u32(rec, 2, 0); put_u32(rec, 3, 0);
+  uint64_t words = ru4((d + 1) / 2);
+  for (uint64_t w = 0; w < words; ++w) put_u32(rec, 4 + w, 0);
+  for (uint64_t j = 0; j < d; ++j) {
+    uint32_t w = get_u32(rec, 4 + j / 2);
+    w |= (uint32_t)orc_float_to_half(q[j]) << (16 * (j % 2));
+    put_u32(rec, 4 + j / 2, w);
+  }
+}
+static void decode_fp16(const unsigned char *rec, uint64_t d, float *out) {
+  for (uint64_t j = 0; j < d; ++j)
+    out[j] = orc_half_to_float((uint16_t)(get_u32(rec, 4 + j / 2) >> (16 * (j % 2))));
+}
+
 void orc_encode_partition(const orc_params *p, uint64_t part_no, const float *norm_override1,
                           const float *q, uint64_t d, unsigned char *rec) {
   switch (p->kind) {
@@ -384,6 +434,7 @@ void orc_encode_partition(const orc_params *p, uint64_t part_no, const float *no
     case ORC_RANDK:    encode_randk(p, part_no, q, d, rec); break;
     case ORC_DITHER:   encode_dither(p, part_no, q, d, norm_override1, rec); break;
     case ORC_NATDITHER: encode_natdither(p, part_no, q, d, norm_override1, rec); break;
+    case ORC_FP16:     encode_fp16(q, d, rec); break;
   }
 }
 
@@ -396,6 +447,7 @@ void orc_decode_partition(const orc_params *p, uint64_t part_no, const unsigned 
     case ORC_RANDK:    decode_randk(p, part_no, rec, d, out); break;
     case ORC_DITHER:   decode_dither(p, rec, d, out); break;
     case ORC_NATDITHER: decode_natdither(p, rec, d, out); break;
+    case ORC_FP16:     decode_fp16(rec, d, out); break;
   }
 }
 

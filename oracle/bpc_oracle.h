@@ -25,7 +25,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
-enum { ORC_IDENTITY = 0, ORC_SIGN = 1, ORC_TOPK = 2, ORC_RANDK = 3, ORC_DITHER = 4, ORC_NATDITHER = 5 };
+enum { ORC_IDENTITY = 0, ORC_SIGN = 1, ORC_TOPK = 2, ORC_RANDK = 3, ORC_DITHER = 4, ORC_NATDITHER = 5,
+       ORC_FP16 = 6 };
 enum { ORC_F32 = 0, ORC_F16 = 1 };
 enum { ORC_NORM_L2 = 0, ORC_NORM_LINF = 1 };
 enum { ORC_OPT_LANS = 0, ORC_OPT_ADAM = 1 };
@@ -52,6 +53,7 @@ typedef struct {
 
 void orc_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]);
 float orc_half_to_float(uint16_t h);
+uint16_t orc_float_to_half(float x);
 
 uint64_t orc_partition_k(const orc_params *p, uint64_t d);
 size_t orc_partition_stride(const orc_params *p);

@@ -56,6 +56,7 @@ static hipError_t encode(const Geo &g, const bpc_params_t &prm, const bpc_params
                          uint8_t *payload, const Workspace &ws, hipStream_t stream) {
   switch (prm.kind) {
     case BPC_IDENTITY: return identity_encode(g, prm, src, payload, ws, stream);
+    case BPC_FP16: return fp16_encode(g, prm, src, payload, ws, stream);
     case BPC_SIGN: return sign_encode(g, prm, src, payload, ws, stream);
     case BPC_TOPK: return topk_encode(g, prm, in_prm, src, payload, ws, stream);
     case BPC_RANDK: return randk_encode(g, prm, in_prm, src, payload, ws, stream);

@@ -95,6 +95,11 @@ __global__ __launch_bounds__(kThreads) void decode_packed_kernel(Geo g, uint32_t
         for (int q = 1; q < 8; ++q) mag = l == (uint32_t)q ? lut[q] : mag;
         v[c] = (nib & 8u) ? -mag : mag;
       }
+    } else if (KIND == BPC_FP16) {
+      const uint2 h = reinterpret_cast<const uint2 *>(body)[j >> 2];
+      const float2 a = __half22float2(*reinterpret_cast<const __half2 *>(&h.x));
+      const float2 b = __half22float2(*reinterpret_cast<const __half2 *>(&h.y));
+      v[0] = a.x; v[1] = a.y; v[2] = b.x; v[3] = b.y;
     } else {
       const float4 q = reinterpret_cast<const float4 *>(body)[j >> 2];
       v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
@@ -199,6 +204,7 @@ hipError_t decode_dense(const Geo &g, const bpc_params_t &prm, const uint8_t *pa
     decode_dither_wide_kernel<<<g.n_tiles, kThreads, 0, stream>>>(g, prm.levels, payload, out);
   else if (prm.kind == BPC_DITHER || natural)
     decode_packed_kernel<BPC_DITHER><<<g.n_tiles, kThreads, 0, stream>>>(g, prm.levels, natural, payload, out);
+  else if (prm.kind == BPC_FP16) decode_packed_kernel<BPC_FP16><<<g.n_tiles, kThreads, 0, stream>>>(g, prm.levels, false, payload, out);
   else decode_packed_kernel<BPC_IDENTITY><<<g.n_tiles, kThreads, 0, stream>>>(g, prm.levels, false, payload, out);
   return hipGetLastError();
 }

@@ -58,7 +58,7 @@ inline bool params_valid(const bpc_params_t *p) {
   if (!p) return false;
   if (p->part_elems == 0 || p->part_elems % 1024 != 0 || p->part_elems > (1ull << 31)) return false;
   switch (p->kind) {
-    case BPC_IDENTITY: case BPC_SIGN: return true;
+    case BPC_IDENTITY: case BPC_SIGN: case BPC_FP16: return true;
     case BPC_TOPK: case BPC_RANDK: return p->k_ratio > 0.0 && p->k_ratio <= 1.0;
     case BPC_DITHER:
       return p->levels >= 1 && p->levels <= 63 && (p->norm == BPC_NORM_L2 || p->norm == BPC_NORM_LINF);
@@ -87,6 +87,7 @@ inline size_t stride_of(const bpc_params_t *p) {
     case BPC_NATDITHER: words = ru4(cdiv(d, 8)); break;
     case BPC_TOPK:     words = 2 * ru4(k_rule(p->k_ratio, d)); break;
     case BPC_RANDK:    words = ru4(k_rule(p->k_ratio, d)); break;
+    case BPC_FP16:     words = ru4(cdiv(d, 2)); break;
   }
   return (size_t)(kHeaderBytes + 4 * words);
 }

@@ -49,6 +49,8 @@ hipError_t sign_encode(const Geo &g, const bpc_params_t &prm, const Source &src,
                        const Workspace &ws, hipStream_t stream);
 hipError_t dither_encode(const Geo &g, const bpc_params_t &prm, const Source &src, uint8_t *payload,
                          const Workspace &ws, hipStream_t stream);
+hipError_t fp16_encode(const Geo &g, const bpc_params_t &prm, const Source &src, uint8_t *payload,
+                       const Workspace &ws, hipStream_t stream);
 hipError_t identity_encode(const Geo &g, const bpc_params_t &prm, const Source &src, uint8_t *payload,
                            const Workspace &ws, hipStream_t stream);
 hipError_t topk_encode(const Geo &g, const bpc_params_t &prm, const bpc_params_t *in_prm, const Source &src,

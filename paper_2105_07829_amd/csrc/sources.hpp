@@ -10,6 +10,22 @@
 
 namespace bpc {
 
+// Eight consecutive f32 / f16 values from a 16-byte aligned position.
+__device__ inline void load8_aligned(const float *p, float out[8]) {
+  const float4 a = reinterpret_cast<const float4 *>(p)[0], b = reinterpret_cast<const float4 *>(p)[1];
+  out[0] = a.x; out[1] = a.y; out[2] = a.z; out[3] = a.w; out[4] = b.x; out[5] = b.y; out[6] = b.z; out[7] = b.w;
+}
+__device__ inline void load8_aligned(const __half *p, float out[8]) {
+  const uint4 w = *reinterpret_cast<const uint4 *>(p);
+  const uint32_t u[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const float2 f = __half22float2(*reinterpret_cast<const __half2 *>(&u[i]));
+    out[2 * i] = f.x;
+    out[2 * i + 1] = f.y;
+  }
+}
+
 // q = g + e, or g alone without error feedback (Algorithm 3).
 template <class T>
 struct GradSource {
@@ -21,6 +37,27 @@ struct GradSource {
     uint64_t i = g.part_base(p) + j;
     float x = load_grad(grad, i);
     return res ? x + res[i] : x;
+  }
+  // j0 a multiple of 8: a whole chunk inside the partition comes in with 16-byte loads (the
+  // buffers are 16-byte aligned and partitions start at multiples of 1024 elements)
+  __device__ void at8(const Geo &g, uint32_t p, uint32_t j0, uint32_t d, const float *, float out[8]) const {
+    const uint64_t i0 = g.part_base(p) + j0;
+    if (j0 + 8 <= d) {
+      float x[8];
+      load8_aligned(grad + i0, x);
+      if (res) {
+        float r[8];
+        load8_aligned(res + i0, r);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) out[e] = x[e] + r[e];
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) out[e] = x[e];
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) out[e] = j0 + e < d ? at(g, p, j0 + e, nullptr) : 0.0f;
+    }
   }
 };
 
@@ -157,6 +194,47 @@ __device__ inline void source_at8(const SRC &src, const Geo &g, uint32_t p, uint
     for (int e = 0; e < 8; ++e) out[e] = j0 + e < d ? src.at(g, p, j0 + e, lds) : 0.0f;
   }
 }
+
+// Delta from n FP16 messages.
+struct Fp16MsgSource {
+  WorkerMsgs msgs;
+  const float *res;
+  uint64_t stride;
+  static constexpr int kLdsFloats = 1;
+  __device__ void begin(const Geo &, uint32_t, float *) const {}
+  __device__ float at(const Geo &g, uint32_t p, uint32_t j, const float *) const {
+    float acc = 0.0f;
+    for (int i = 0; i < msgs.n; ++i) {
+      const __half *vals = reinterpret_cast<const __half *>(msgs.ptr[i] + (uint64_t)p * stride + kHeaderBytes);
+      acc = acc + __half2float(vals[j]);
+    }
+    float mean = acc * msgs.inv_n;
+    return res ? mean + res[g.part_base(p) + j] : mean;
+  }
+  // j0 a multiple of 8: one 16-byte load per worker (the record is padded to whole words and
+  // its tail is zero, so reading the 8 halves of the last chunk stays inside it)
+  __device__ void at8(const Geo &g, uint32_t p, uint32_t j0, uint32_t d, const float *, float out[8]) const {
+    float acc[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = 0.0f;
+    for (int i = 0; i < msgs.n; ++i) {
+      float v[8];
+      load8_aligned(reinterpret_cast<const __half *>(msgs.ptr[i] + (uint64_t)p * stride + kHeaderBytes) + j0, v);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[e] = acc[e] + v[e];
+    }
+    const uint64_t base = g.part_base(p);
+    float r[8];
+    if (res && j0 + 8 <= d) load8_aligned(res + base + j0, r);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float mean = acc[e] * msgs.inv_n;
+      if (j0 + e >= d) out[e] = 0.0f;
+      else if (!res) out[e] = mean;
+      else out[e] = mean + (j0 + 8 <= d ? r[e] : res[base + j0 + e]);
+    }
+  }
+};
 
 // Delta from n identity messages (plain averaging, Algorithm 1).
 struct IdentityMsgSource {

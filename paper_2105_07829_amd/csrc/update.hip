@@ -104,6 +104,31 @@ struct IdentityDec {
     out[0] = __uint_as_float(r.x); out[1] = __uint_as_float(r.y); out[2] = __uint_as_float(r.z); out[3] = __uint_as_float(r.w);
   }
 };
+struct Fp16Dec {
+  const uint8_t *payload; uint64_t stride;
+  __device__ const float *dense_base() const { return nullptr; }
+  static constexpr int kLdsFloats = 1;
+  __device__ void begin(uint32_t, float *) const {}
+  __device__ float at(const Geo &, uint32_t p, uint32_t j, const float *) const {
+    return __half2float(reinterpret_cast<const __half *>(payload + (uint64_t)p * stride + kHeaderBytes)[j]);
+  }
+  using R4 = u32x2;
+  __device__ float header(uint32_t) const { return 0.0f; }
+  __device__ void table(float, float *) const {}
+  // the record is padded to a full partition, so the 8 bytes are always inside it
+  __device__ R4 load4(const Geo &, uint32_t p, uint32_t j, const TileBuf &) const {
+    return reinterpret_cast<const u32x2 *>(payload + (uint64_t)p * stride + kHeaderBytes)[j >> 2];
+  }
+  __device__ void decode4(R4 r, uint32_t, float, const float *, float out[4]) const {
+    const uint32_t lo = r.x, hi = r.y;
+    const float2 a = __half22float2(*reinterpret_cast<const __half2 *>(&lo));
+    const float2 b = __half22float2(*reinterpret_cast<const __half2 *>(&hi));
+    out[0] = a.x; out[1] = a.y; out[2] = b.x; out[3] = b.y;
+  }
+  __device__ void at4(const Geo &g, uint32_t p, uint32_t j, const TileBuf &row, const float *lds, float out[4]) const {
+    decode4(load4(g, p, j, row), j, 0.0f, lds, out);
+  }
+};
 struct DenseDec {
   const float *dense;
   __device__ const float *dense_base() const { return dense; }
@@ -553,6 +578,7 @@ hipError_t adaptive_update(const Geo &g, const bpc_params_t &prm, const uint8_t 
       if (prm.kind == BPC_DITHER && dither_planes(prm.levels) > 0) break;   // bit planes: through the dense decode below
       return run_update(g, DitherDec{payload, g.stride, prm.levels, prm.kind == BPC_NATDITHER}, x, m, v, opt, norms, ws, stream);
     case BPC_IDENTITY: return run_update(g, IdentityDec{payload, g.stride}, x, m, v, opt, norms, ws, stream);
+    case BPC_FP16: return run_update(g, Fp16Dec{payload, g.stride}, x, m, v, opt, norms, ws, stream);
     default: break;
   }
   float *dense = ws.at<float>(ws.lay.dense);

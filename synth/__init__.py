@@ -45,6 +45,9 @@ WORKLOADS = {
     "bert_large_natural": dict(D=336_000_000, dtype="f16", dist="student_t3", kind="natdither", levels=4,
                                n_workers=16, ef=True, opt="adam"),
     # nor is this: the 5-bit form of linear dithering (15 levels: nibbles and one bit plane)
+    # nor this: the FP32 -> FP16 conversion as the compressor
+    "bert_large_fp16": dict(D=336_000_000, dtype="f16", dist="student_t3", kind="fp16",
+                            n_workers=16, ef=True, opt="adam"),
     "bert_large_5bit": dict(D=336_000_000, dtype="f16", dist="student_t3", kind="dither", levels=15,
                             n_workers=16, ef=True, opt="adam"),
 }

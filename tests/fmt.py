@@ -31,6 +31,8 @@ def stride(kind, part_elems, k_ratio=0.0, levels=4):
         words = ru4((part_elems + 7) // 8) + dither_planes(levels) * ru4((part_elems + 31) // 32)
     elif kind == "natdither":
         words = ru4((part_elems + 7) // 8)
+    elif kind == "fp16":
+        words = ru4((part_elems + 1) // 2)
     elif kind == "topk":
         words = 2 * ru4(k_of(k_ratio, part_elems))
     elif kind == "randk":
@@ -89,6 +91,11 @@ def dither_levels(rec, d, part_elems, levels):
     return nu, sgn, lvl
 
 
+def fp16_values(rec, d):
+    """-> float16[d] of an FP16 record."""
+    return rec[16:16 + 2 * d].view(np.float16)
+
+
 def topk_entries(rec, k_cap):
     k = header_u32(rec)
     idx = rec[16:16 + 4 * k].view(np.int32)
@@ -113,6 +120,8 @@ def defined_bytes(kind, d, k=0, k_cap=0, part_elems=0, levels=4):
         return [(0, 16 + 4 * d)]
     if kind == "sign":
         return [(0, 16 + 4 * ru4((d + 31) // 32))]
+    if kind == "fp16":
+        return [(0, 16 + 4 * ru4((d + 1) // 2))]
     if kind in ("dither", "natdither"):
         return [(0, 16 + 4 * ru4((d + 7) // 8))]
     if kind == "topk":

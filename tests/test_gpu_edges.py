@@ -30,6 +30,7 @@ KW = {
     "dither": dict(levels=4, seed=0xFEED, stream_id=(7 << 32) | 1),
     "natdither": dict(levels=6, seed=0xBEEF, stream_id=(7 << 32) | 2),
     "identity": {},
+    "fp16": {},
 }
 
 
@@ -120,7 +121,7 @@ def test_dither_tiny_values_divide_per_element(gu, orc, norm, kind):
     assert np.array_equal(res_gpu.view(np.uint32), res_ref.view(np.uint32))
 
 
-@pytest.mark.parametrize("kind", ["sign", "dither", "natdither", "topk", "randk", "identity"])
+@pytest.mark.parametrize("kind", ["sign", "dither", "natdither", "topk", "randk", "identity", "fp16"])
 def test_server_with_the_most_workers(gu, orc, kind):
     n = gu.bpc.MAX_WORKERS
     D = PE + 1234
@@ -155,7 +156,7 @@ def test_server_with_the_most_workers(gu, orc, kind):
             assert kg == kr and gu.close(vg, vr, REL)
     else:
         assert defined_equal(kind, pay_gpu, pay_ref, out_o, orc, D, PE, kw)
-    if kind in ("identity", "topk"):
+    if kind in ("identity", "topk", "fp16"):
         assert np.array_equal(res_gpu.view(np.uint32), res_ref.view(np.uint32))
     else:
         assert gu.close(res_gpu, res_ref, REL)

@@ -34,6 +34,7 @@ def grads(D, dtype, seed, scale=1e-3):
 
 KW = {
     "identity": {},
+    "fp16": {},
     "sign": {},
     "topk": dict(k_ratio=0.01),
     "randk": dict(k_ratio=0.02, value_scale=1.0, seed=0x1234567890ABCDEF, stream_id=(2 << 32) | 5),
@@ -95,7 +96,7 @@ def test_worker_stage(gu, orc, name, dtype, ef):
 
         compare_payload(gu, orc, name, po, pay_gpu, pay_ref, D, PE, redo)
         if ef:
-            if base_kind(name) in ("identity", "topk"):
+            if base_kind(name) in ("identity", "topk", "fp16"):
                 assert np.array_equal(res_gpu.view(np.uint32), res_ref.view(np.uint32))
             else:
                 assert gu.close(res_gpu, res_ref, REL), name
@@ -128,7 +129,7 @@ def test_worker_stage_large_partitions(gu, orc, name, dtype, ef):
 
         compare_payload(gu, orc, name, po, pay_gpu, pay_ref, D, BIG_PE, redo)
         if ef:
-            if base_kind(name) in ("identity", "topk"):
+            if base_kind(name) in ("identity", "topk", "fp16"):
                 assert np.array_equal(res_gpu.view(np.uint32), res_ref.view(np.uint32))
             else:
                 assert gu.close(res_gpu, res_ref, REL), name
@@ -172,7 +173,7 @@ def test_server_stage(gu, orc, name, ef, n):
         else:
             compare_payload(gu, orc, name, out_o, pay_gpu, pay_ref, D, PE, redo)
         if ef:
-            if base_kind(name) in ("identity", "topk"):
+            if base_kind(name) in ("identity", "topk", "fp16"):
                 assert np.array_equal(res_gpu.view(np.uint32), res_ref.view(np.uint32))
             else:
                 assert gu.close(res_gpu, res_ref, REL), name
@@ -256,7 +257,7 @@ def test_update_stage(gu, orc, name, opt_kind):
 def test_deterministic_bytes(gu, orc):
     """Same call twice gives identical bytes for the kinds whose arithmetic has a fixed order."""
     D = 2 * PE + 4137
-    for name in ("sign", "topk", "dither", "dither_7bit", "natdither", "identity"):
+    for name in ("sign", "topk", "dither", "dither_7bit", "natdither", "identity", "fp16"):
         po, pb = gu.both_params(orc, base_kind(name), PE, **KW[name])
         g = grads(D, np.float16, 8)
         e = (rng(9).standard_normal(D) * 3e-4).astype(np.float32)
@@ -271,7 +272,7 @@ def test_deterministic_bytes(gu, orc):
                 assert np.array_equal(fmt.record(a[0], p, strd)[lo:hi], fmt.record(b[0], p, strd)[lo:hi])
 
 
-@pytest.mark.parametrize("name", ["sign", "topk", "dither", "dither_5bit", "natdither", "randk", "identity"])
+@pytest.mark.parametrize("name", ["sign", "topk", "dither", "dither_5bit", "natdither", "randk", "identity", "fp16"])
 def test_chained_pipeline_three_steps(gu, orc, name):
     """Algorithm 4 + the Adam-style update chained on the GPU only (each stage consumes the GPU's
     own previous outputs) against the chained oracle."""

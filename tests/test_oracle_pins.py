@@ -350,6 +350,59 @@ def test_dither_bit_planes_take_the_high_level_bits_in_element_order(orc):
     assert orc.partition_stride(p7) == 16 + 4 * fmt.ru4(PE // 8)
 
 
+# ---------------------------------------------------------------- FP16 conversion
+def test_float_to_half_matches_an_independent_conversion(orc):
+    """Round to nearest even, overflow to infinity, subnormal halves, signed zeros: against
+    numpy's float32 -> float16 cast on random bit patterns and on the boundary cases."""
+    r = rng(123)
+    bits = r.integers(0, 2 ** 32, size=200000, dtype=np.uint64).astype(np.uint32)
+    xs = bits.view(np.float32)
+    xs = xs[np.isfinite(xs)]
+    special = np.array([0.0, -0.0, 65504.0, 65519.99, 65520.0, -65520.0, 65536.0, 1e30, -1e30, np.inf, -np.inf,
+                        2.0 ** -24, 2.0 ** -25, np.nextafter(np.float32(2.0 ** -25), np.float32(1)), 2.0 ** -26,
+                        2.0 ** -14, np.nextafter(np.float32(2.0 ** -14), np.float32(0)), 1.0 + 2.0 ** -11,
+                        1.0 + 2.0 ** -11 + 2.0 ** -20, 1.0 + 3 * 2.0 ** -11, 1e-45, -1e-45, 0.1, 1 / 3],
+                       dtype=np.float32)
+    # halves around the binade boundaries and exact ties between neighbouring halves
+    h = r.integers(0, 0x7bff, size=4000).astype(np.uint16)
+    lo = h.view(np.float16).astype(np.float32)
+    hi = (h + 1).astype(np.uint16).view(np.float16).astype(np.float32)
+    ties = ((lo.astype(np.float64) + hi.astype(np.float64)) / 2).astype(np.float32)   # exact in float32
+    allx = np.concatenate([xs[:60000], special, ties, -ties, np.nextafter(ties, np.float32(0)), np.nextafter(ties, np.float32(1e9))])
+    with np.errstate(over="ignore"):
+        want = allx.astype(np.float16).view(np.uint16)
+    got = np.array([orc.float_to_half(float(v)) for v in allx], dtype=np.uint16)
+    assert np.array_equal(got, want)
+    assert orc.float_to_half(float("nan")) & 0x7c00 == 0x7c00 and orc.float_to_half(float("nan")) & 0x3ff != 0
+
+
+def test_fp16_compressor_is_the_cast_and_its_residual_is_the_rounding_error(orc):
+    d = 1001                                         # odd: the last half-word is padded
+    x = (rng(4).standard_normal(d) * np.float32(3e-3)).astype(np.float32)
+    x[:4] = [0.0, -0.0, 70000.0, -1e-8]
+    p = orc.make_params(orc.FP16, PE)
+    assert orc.partition_stride(p) == 16 + 2 * PE == fmt.stride("fp16", PE)
+    rec = orc.encode_partition(p, 0, x)
+    assert not rec[:16].any()
+    with np.errstate(over="ignore"):
+        want = x.astype(np.float16)
+    assert np.array_equal(fmt.fp16_values(rec, d).view(np.uint16), want.view(np.uint16))
+    assert not rec[16 + 2 * d:16 + 4 * fmt.ru4((d + 1) // 2)].any()
+    dec = orc.decode_partition(p, 0, rec, d)
+    assert np.array_equal(dec.view(np.uint32), want.astype(np.float32).view(np.uint32))
+    # Definition 2 with a tiny 1 - delta: relative rounding error at most 2^-11 per normal element
+    fin = np.isfinite(dec) & (np.abs(x) >= 2.0 ** -14)
+    assert np.all(np.abs(dec[fin] - x[fin]) <= 2.0 ** -11 * np.abs(x[fin]))
+    # error feedback: residual + decode = q where both are finite
+    e = (rng(5).standard_normal(d) * np.float32(1e-4)).astype(np.float32)
+    g = x.copy()
+    g[2] = 1.0
+    res = e.copy()
+    pay = orc.compress(p, g, res)
+    q = g + e
+    assert np.array_equal(res, q - orc.decompress(p, pay, d))
+
+
 # ---------------------------------------------------------------- natural dithering
 @pytest.mark.parametrize("norm", ["l2", "linf"])
 def test_natural_dither_unbiased_on_power_of_two_levels(orc, norm):
@@ -437,7 +490,7 @@ def test_zero_vector_encodes_to_zero(orc):
 
 
 # ---------------------------------------------------------------- Algorithm 4 identities
-KINDS = ["identity", "sign", "topk", "randk", "randk_scaled", "dither", "natdither"]
+KINDS = ["identity", "sign", "topk", "randk", "randk_scaled", "dither", "natdither", "fp16"]
 
 
 def params_for(orc, name, pe=PE, seed=1, stream=0):
@@ -455,6 +508,8 @@ def params_for(orc, name, pe=PE, seed=1, stream=0):
         return orc.make_params(orc.DITHER, pe, levels=4, seed=seed, stream_id=stream)
     if name == "natdither":
         return orc.make_params(orc.NATDITHER, pe, levels=4, seed=seed, stream_id=stream)
+    if name == "fp16":
+        return orc.make_params(orc.FP16, pe)
     raise ValueError(name)
 
 
