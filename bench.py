@@ -52,6 +52,8 @@ def payload_bytes_per_elem(w):
         return 2.0
     if k == "topk":
         return 8 * w["k_ratio"]
+    if k == "topk16":
+        return 6 * w["k_ratio"]
     if k == "randk":
         return 4 * w["k_ratio"]
     return 4.0
@@ -75,7 +77,7 @@ class Pipeline:
         self.D, self.n = w["D"], w["n_workers"]
         self.pe = synth.part_elems(w["dtype"])
         kind = {"sign": bpc.SIGN, "topk": bpc.TOPK, "randk": bpc.RANDK, "dither": bpc.DITHER,
-                "natdither": bpc.NATDITHER, "fp16": bpc.FP16}[w["kind"]]
+                "natdither": bpc.NATDITHER, "fp16": bpc.FP16, "topk16": bpc.TOPK16}[w["kind"]]
         self.kw = dict(k_ratio=w.get("k_ratio", 0.01), levels=w.get("levels", 4),
                        value_scale=w.get("value_scale", 1.0), seed=synth.BASE_SEED)
         self.kind = kind
@@ -174,7 +176,7 @@ def cpu_baseline(name, w, n_parts, n_steps, synth):
     D = pe * n_parts
     cores = min(os.cpu_count() or 1, 16)
     kind = {"sign": oracle.SIGN, "topk": oracle.TOPK, "randk": oracle.RANDK, "dither": oracle.DITHER,
-            "natdither": oracle.NATDITHER, "fp16": oracle.FP16}[w["kind"]]
+            "natdither": oracle.NATDITHER, "fp16": oracle.FP16, "topk16": oracle.TOPK16}[w["kind"]]
     kw = dict(k_ratio=w.get("k_ratio", 0.01), levels=w.get("levels", 4), value_scale=w.get("value_scale", 1.0),
               seed=synth.BASE_SEED)
     grads = [synth.host_gradient(w["dist"], D, w["dtype"], worker=i) for i in range(n)]

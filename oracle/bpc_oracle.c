@@ -105,7 +105,7 @@ static int params_ok(const orc_params *p) {
   if (p->part_elems == 0 || p->part_elems % 1024 != 0) return 0;
   switch (p->kind) {
     case ORC_IDENTITY: case ORC_SIGN: case ORC_FP16: return 1;
-    case ORC_TOPK: case ORC_RANDK: return p->k_ratio > 0.0 && p->k_ratio <= 1.0;
+    case ORC_TOPK: case ORC_TOPK16: case ORC_RANDK: return p->k_ratio > 0.0 && p->k_ratio <= 1.0;
     case ORC_DITHER:
       return p->levels >= 1 && p->levels <= 63 && (p->norm == ORC_NORM_L2 || p->norm == ORC_NORM_LINF);
     case ORC_NATDITHER:
@@ -127,7 +127,7 @@ static unsigned dither_planes(unsigned levels) {
 /* k = max(1, floor(ratio*d)), never above d. */
 uint64_t orc_partition_k(const orc_params *p, uint64_t d) {
   if (!params_ok(p) || d == 0) return 0;
-  if (p->kind != ORC_TOPK && p->kind != ORC_RANDK) return 0;
+  if (p->kind != ORC_TOPK && p->kind != ORC_TOPK16 && p->kind != ORC_RANDK) return 0;
   uint64_t k = (uint64_t)floor(p->k_ratio * (double)d);
   if (k < 1) k = 1;
   if (k > d) k = d;
@@ -143,6 +143,7 @@ size_t orc_partition_stride(const orc_params *p) {
     case ORC_DITHER:   words = ru4((d + 7) / 8) + dither_planes(p->levels) * ru4((d + 31) / 32); break;
     case ORC_NATDITHER: words = ru4((d + 7) / 8); break;
     case ORC_TOPK:     words = 2 * ru4(orc_partition_k(p, d)); break;
+    case ORC_TOPK16:   words = ru4(orc_partition_k(p, d)) + ru4((orc_partition_k(p, d) + 1) / 2); break;
     case ORC_RANDK:    words = ru4(orc_partition_k(p, d)); break;
     case ORC_FP16:     words = ru4((d + 1) / 2); break;
   }
@@ -224,6 +225,19 @@ static void encode_topk(const orc_params *p, const float *q, uint64_t d, unsigne
   qsort(all, (size_t)k, sizeof(key_idx), by_idx_asc);
   put_u32(rec, 0, (uint32_t)k);
   put_u32(rec, 1, 0); put_u32(rec, 2, 0); put_u32(rec, 3, 0);
+  if (p->kind == ORC_TOPK16) {
+    /* the message format behind the compression rate quoted in Section 5.2: a 32-bit index
+     * and a half-precision value per kept element */
+    for (uint64_t w = 0; w < ru4((k + 1) / 2); ++w) put_u32(rec, 4 + kcap4 + w, 0);
+    for (uint64_t t = 0; t < k; ++t) {
+      put_u32(rec, 4 + t, all[t].idx);
+      uint32_t w = get_u32(rec, 4 + kcap4 + t / 2);
+      w |= (uint32_t)orc_float_to_half(q[all[t].idx]) << (16 * (t % 2));
+      put_u32(rec, 4 + kcap4 + t / 2, w);
+    }
+    free(all);
+    return;
+  }
   for (uint64_t t = 0; t < k; ++t) {
     put_u32(rec, 4 + t, all[t].idx);
     put_f32(rec, 4 + kcap4 + t, q[all[t].idx]);
@@ -237,7 +251,11 @@ static void decode_topk(const orc_params *p, const unsigned char *rec, uint64_t 
   for (uint64_t j = 0; j < d; ++j) out[j] = 0.0f;
   for (uint64_t t = 0; t < k; ++t) {
     uint32_t idx = get_u32(rec, 4 + t);
-    if (idx < d) out[idx] = get_f32(rec, 4 + kcap4 + t);
+    if (idx >= d) continue;
+    if (p->kind == ORC_TOPK16)
+      out[idx] = orc_half_to_float((uint16_t)(get_u32(rec, 4 + kcap4 + t / 2) >> (16 * (t % 2))));
+    else
+      out[idx] = get_f32(rec, 4 + kcap4 + t);
   }
 }
 
@@ -430,7 +448,7 @@ void orc_encode_partition(const orc_params *p, uint64_t part_no, const float *no
   switch (p->kind) {
     case ORC_IDENTITY: encode_identity(q, d, rec); break;
     case ORC_SIGN:     encode_sign(q, d, norm_override1, rec); break;
-    case ORC_TOPK:     encode_topk(p, q, d, rec); break;
+    case ORC_TOPK: case ORC_TOPK16: encode_topk(p, q, d, rec); break;
     case ORC_RANDK:    encode_randk(p, part_no, q, d, rec); break;
     case ORC_DITHER:   encode_dither(p, part_no, q, d, norm_override1, rec); break;
     case ORC_NATDITHER: encode_natdither(p, part_no, q, d, norm_override1, rec); break;
@@ -443,7 +461,7 @@ void orc_decode_partition(const orc_params *p, uint64_t part_no, const unsigned 
   switch (p->kind) {
     case ORC_IDENTITY: decode_identity(rec, d, out); break;
     case ORC_SIGN:     decode_sign(rec, d, out); break;
-    case ORC_TOPK:     decode_topk(p, rec, d, out); break;
+    case ORC_TOPK: case ORC_TOPK16: decode_topk(p, rec, d, out); break;
     case ORC_RANDK:    decode_randk(p, part_no, rec, d, out); break;
     case ORC_DITHER:   decode_dither(p, rec, d, out); break;
     case ORC_NATDITHER: decode_natdither(p, rec, d, out); break;

@@ -26,7 +26,7 @@
 #include <stdint.h>
 
 enum { ORC_IDENTITY = 0, ORC_SIGN = 1, ORC_TOPK = 2, ORC_RANDK = 3, ORC_DITHER = 4, ORC_NATDITHER = 5,
-       ORC_FP16 = 6 };
+       ORC_FP16 = 6, ORC_TOPK16 = 7 };
 enum { ORC_F32 = 0, ORC_F16 = 1 };
 enum { ORC_NORM_L2 = 0, ORC_NORM_LINF = 1 };
 enum { ORC_OPT_LANS = 0, ORC_OPT_ADAM = 1 };

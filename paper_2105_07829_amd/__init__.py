@@ -17,7 +17,7 @@ _CSRC = os.path.join(_HERE, "csrc")
 LIB_PATH = os.path.join(_HERE, "libbpc.so")
 
 # enums of include/bpc.h
-IDENTITY, SIGN, TOPK, RANDK, DITHER, NATDITHER, FP16 = 0, 1, 2, 3, 4, 5, 6
+IDENTITY, SIGN, TOPK, RANDK, DITHER, NATDITHER, FP16, TOPK16 = 0, 1, 2, 3, 4, 5, 6, 7
 F32, F16 = 0, 1
 NORM_L2, NORM_LINF = 0, 1
 OPT_LANS, OPT_ADAM = 0, 1

@@ -21,7 +21,7 @@ extern "C" {
 
 uint64_t bpc_partition_k(const bpc_params_t *params, uint64_t d) {
   if (!params_valid(params) || d == 0) return 0;
-  if (params->kind != BPC_TOPK && params->kind != BPC_RANDK) return 0;
+  if (params->kind != BPC_TOPK && params->kind != BPC_TOPK16 && params->kind != BPC_RANDK) return 0;
   return k_rule(params->k_ratio, d);
 }
 
@@ -58,7 +58,7 @@ static hipError_t encode(const Geo &g, const bpc_params_t &prm, const bpc_params
     case BPC_IDENTITY: return identity_encode(g, prm, src, payload, ws, stream);
     case BPC_FP16: return fp16_encode(g, prm, src, payload, ws, stream);
     case BPC_SIGN: return sign_encode(g, prm, src, payload, ws, stream);
-    case BPC_TOPK: return topk_encode(g, prm, in_prm, src, payload, ws, stream);
+    case BPC_TOPK: case BPC_TOPK16: return topk_encode(g, prm, in_prm, src, payload, ws, stream);
     case BPC_RANDK: return randk_encode(g, prm, in_prm, src, payload, ws, stream);
     default: return dither_encode(g, prm, src, payload, ws, stream);
   }
@@ -104,7 +104,7 @@ bpc_status_t bpc_server_aggregate(const bpc_params_t *in, const void *const *pay
   for (int i = 0; i < n; ++i) {
     if (!params_valid(&in[i])) return BPC_ERR_INVALID_ARG;
     if (in[i].kind != out->kind || in[i].part_elems != out->part_elems) return BPC_ERR_INVALID_ARG;
-    if ((out->kind == BPC_TOPK || out->kind == BPC_RANDK) && in[i].k_ratio != out->k_ratio)
+    if ((out->kind == BPC_TOPK || out->kind == BPC_TOPK16 || out->kind == BPC_RANDK) && in[i].k_ratio != out->k_ratio)
       return BPC_ERR_INVALID_ARG;
     if ((out->kind == BPC_DITHER || out->kind == BPC_NATDITHER) && in[i].levels != out->levels) return BPC_ERR_INVALID_ARG;
   }

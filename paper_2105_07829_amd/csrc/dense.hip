@@ -145,7 +145,8 @@ __global__ __launch_bounds__(kThreads) void decode_dither_wide_kernel(Geo g, uin
   }
 }
 
-// Top-k: out[idx_t] = val_t.  `out` was zero-filled before.
+// Top-k: out[idx_t] = val_t.  `out` was zero-filled before.  HALF: the values are halves.
+template <bool HALF>
 __global__ __launch_bounds__(kThreads) void decode_topk_kernel(Geo g, const uint8_t *payload, float *out) {
   const uint32_t p = blockIdx.y;
   const uint32_t d = g.part_size(p);
@@ -157,7 +158,7 @@ __global__ __launch_bounds__(kThreads) void decode_topk_kernel(Geo g, const uint
   const uint64_t base = g.part_base(p);
   for (uint32_t t = blockIdx.x * kThreads + threadIdx.x; t < k; t += gridDim.x * kThreads) {
     uint32_t j = idx[t];
-    if (j < d) out[base + j] = val[t];
+    if (j < d) out[base + j] = HALF ? __half2float(reinterpret_cast<const __half *>(val)[t]) : val[t];
   }
 }
 
@@ -185,7 +186,9 @@ hipError_t scatter_add_sparse(const Geo &g, const bpc_params_t &prm, const uint8
                               hipStream_t stream) {
   dim3 grid((uint32_t)cdiv(g.k_cap, kThreads), g.P);
   if (prm.kind == BPC_TOPK)
-    decode_topk_kernel<<<grid, kThreads, 0, stream>>>(g, payload, out);
+    decode_topk_kernel<false><<<grid, kThreads, 0, stream>>>(g, payload, out);
+  else if (prm.kind == BPC_TOPK16)
+    decode_topk_kernel<true><<<grid, kThreads, 0, stream>>>(g, payload, out);
   else
     decode_randk_kernel<<<grid, kThreads, 0, stream>>>(g, payload, out, prm.value_scale, prm.seed, prm.stream_id);
   return hipGetLastError();
@@ -193,7 +196,7 @@ hipError_t scatter_add_sparse(const Geo &g, const bpc_params_t &prm, const uint8
 
 hipError_t decode_dense(const Geo &g, const bpc_params_t &prm, const uint8_t *payload, float *out,
                         hipStream_t stream) {
-  if (prm.kind == BPC_TOPK || prm.kind == BPC_RANDK) {
+  if (prm.kind == BPC_TOPK || prm.kind == BPC_TOPK16 || prm.kind == BPC_RANDK) {
     hipError_t e = fill_zero(out, sizeof(float) * g.D, stream);
     if (e != hipSuccess) return e;
     return scatter_add_sparse(g, prm, payload, out, stream);

@@ -59,7 +59,7 @@ inline bool params_valid(const bpc_params_t *p) {
   if (p->part_elems == 0 || p->part_elems % 1024 != 0 || p->part_elems > (1ull << 31)) return false;
   switch (p->kind) {
     case BPC_IDENTITY: case BPC_SIGN: case BPC_FP16: return true;
-    case BPC_TOPK: case BPC_RANDK: return p->k_ratio > 0.0 && p->k_ratio <= 1.0;
+    case BPC_TOPK: case BPC_TOPK16: case BPC_RANDK: return p->k_ratio > 0.0 && p->k_ratio <= 1.0;
     case BPC_DITHER:
       return p->levels >= 1 && p->levels <= 63 && (p->norm == BPC_NORM_L2 || p->norm == BPC_NORM_LINF);
     case BPC_NATDITHER:
@@ -86,6 +86,7 @@ inline size_t stride_of(const bpc_params_t *p) {
     case BPC_DITHER:   words = ru4(cdiv(d, 8)) + dither_planes(p->levels) * ru4(cdiv(d, 32)); break;
     case BPC_NATDITHER: words = ru4(cdiv(d, 8)); break;
     case BPC_TOPK:     words = 2 * ru4(k_rule(p->k_ratio, d)); break;
+    case BPC_TOPK16:   words = ru4(k_rule(p->k_ratio, d)) + ru4(cdiv(k_rule(p->k_ratio, d), 2)); break;
     case BPC_RANDK:    words = ru4(k_rule(p->k_ratio, d)); break;
     case BPC_FP16:     words = ru4(cdiv(d, 2)); break;
   }
@@ -100,7 +101,7 @@ inline Geo make_geo(const bpc_params_t *p, uint64_t D) {
   g.tiles_per_part = (uint32_t)cdiv(p->part_elems, kTile);
   uint64_t last = D - (uint64_t)(g.P ? g.P - 1 : 0) * p->part_elems;
   g.n_tiles = g.P ? (g.P - 1) * g.tiles_per_part + (uint32_t)cdiv(last, kTile) : 0;
-  g.k_cap = (p->kind == BPC_TOPK || p->kind == BPC_RANDK) ? (uint32_t)k_rule(p->k_ratio, p->part_elems) : 0;
+  g.k_cap = (p->kind == BPC_TOPK || p->kind == BPC_TOPK16 || p->kind == BPC_RANDK) ? (uint32_t)k_rule(p->k_ratio, p->part_elems) : 0;
   g.stride = stride_of(p);
   g.k_ratio = p->k_ratio;
   g.part0 = 0;
@@ -128,12 +129,13 @@ inline WsLayout ws_layout(const bpc_params_t *p, uint64_t D) {
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off += (bytes + 255) / 256 * 256; return o; };
   // kinds whose update reads a dense decode of the message from the workspace
-  bool sparse = p->kind == BPC_TOPK || p->kind == BPC_RANDK || (p->kind == BPC_DITHER && dither_planes(p->levels) > 0);
+  const bool topk = p->kind == BPC_TOPK || p->kind == BPC_TOPK16;
+  bool sparse = topk || p->kind == BPC_RANDK || (p->kind == BPC_DITHER && dither_planes(p->levels) > 0);
   w.partials = take(sizeof(double) * (size_t)g.n_tiles);
   w.dense = take(sparse ? sizeof(float) * (size_t)D : 0);
-  w.hist = take(p->kind == BPC_TOPK ? sizeof(uint32_t) * 4096 * (size_t)g.P : 0);
-  w.state = take(p->kind == BPC_TOPK ? sizeof(uint32_t) * 8 * (size_t)g.P : 0);
-  w.tilecnt = take(p->kind == BPC_TOPK ? sizeof(uint32_t) * 2 * (size_t)g.n_tiles : 0);
+  w.hist = take(topk ? sizeof(uint32_t) * 4096 * (size_t)g.P : 0);
+  w.state = take(topk ? sizeof(uint32_t) * 8 * (size_t)g.P : 0);
+  w.tilecnt = take(topk ? sizeof(uint32_t) * 2 * (size_t)g.n_tiles : 0);
   w.slots = take(sizeof(double) * 3 * ((size_t)g.P * cdiv(g.part_elems, kSTile)));
   w.status = take(256);
   w.norms = take(sizeof(double) * 3 * (size_t)g.P);

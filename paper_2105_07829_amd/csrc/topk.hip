@@ -154,7 +154,7 @@ __global__ __launch_bounds__(kThreads) void topk_count_kernel(Geo g, const float
 }
 
 // One workgroup per partition: exclusive scan of the tile counts in place, and the header.
-__global__ __launch_bounds__(kThreads) void topk_scan_kernel(Geo g, uint32_t *tilecnt, uint8_t *payload) {
+__global__ __launch_bounds__(kThreads) void topk_scan_kernel(Geo g, uint32_t *tilecnt, uint8_t *payload, int half_values) {
   __shared__ uint32_t scan[kThreads];
   const uint32_t p = blockIdx.x;
   const uint32_t d = g.part_size(p);
@@ -177,13 +177,23 @@ __global__ __launch_bounds__(kThreads) void topk_scan_kernel(Geo g, uint32_t *ti
   }
   if (threadIdx.x == 0) {
     uint32_t *hdr = reinterpret_cast<uint32_t *>(payload + (uint64_t)p * g.stride);
-    hdr[0] = (uint32_t)k_of_device(g, p);
+    const uint32_t k = (uint32_t)k_of_device(g, p);
+    hdr[0] = k;
     hdr[1] = 0; hdr[2] = 0; hdr[3] = 0;
+    // half-precision values: the format wants zeros from value k to the end of its last
+    // group of four words (emit writes values 0..k-1 only)
+    if (half_values) {
+      uint16_t *val = reinterpret_cast<uint16_t *>(payload + (uint64_t)p * g.stride + kHeaderBytes + 4 * ru4(g.k_cap));
+      for (uint32_t t = k; t < 2 * (uint32_t)ru4(cdiv(k, 2)); ++t) val[t] = 0;
+    }
   }
 }
 
 // Ordered compaction.  Thread t of a tile owns 16 consecutive elements, so positions follow
 // from an exclusive scan over threads.
+// HALF: values are sent as halves (round to nearest even) and a kept slot of the buffer keeps
+// what the rounding dropped instead of 0.
+template <bool HALF>
 __global__ __launch_bounds__(kThreads) void topk_emit_kernel(Geo g, float *buf, const uint32_t *state,
                                                              const uint32_t *tilecnt, uint8_t *payload,
                                                              int zero_selected) {
@@ -231,15 +241,22 @@ __global__ __launch_bounds__(kThreads) void topk_emit_kernel(Geo g, float *buf, 
     }
     if (take) {
       idx[pos] = j;
-      val[pos] = v[i];
+      if (HALF) {
+        const __half h = __float2half_rn(v[i]);
+        reinterpret_cast<__half *>(val)[pos] = h;
+        if (zero_selected) buf[base + j] = v[i] - __half2float(h);
+      } else {
+        val[pos] = v[i];
+        if (zero_selected) buf[base + j] = 0.0f;
+      }
       ++pos;
-      if (zero_selected) buf[base + j] = 0.0f;
     }
   }
 }
 
 // acc_j = acc_j + val for the entries of one worker's top-k message (indices are distinct
 // within a message, so plain read-modify-write suffices).
+template <bool HALF>
 __global__ __launch_bounds__(kThreads) void topk_accumulate_kernel(Geo g, const uint8_t *payload, float *acc) {
   const uint32_t p = blockIdx.y;
   const uint32_t d = g.part_size(p);
@@ -251,11 +268,11 @@ __global__ __launch_bounds__(kThreads) void topk_accumulate_kernel(Geo g, const 
   const uint64_t base = g.part_base(p);
   for (uint32_t t = blockIdx.x * kThreads + threadIdx.x; t < k; t += gridDim.x * kThreads) {
     uint32_t j = idx[t];
-    if (j < d) acc[base + j] = acc[base + j] + val[t];
+    if (j < d) acc[base + j] = acc[base + j] + (HALF ? __half2float(reinterpret_cast<const __half *>(val)[t]) : val[t]);
   }
 }
 
-hipError_t topk_encode(const Geo &g, const bpc_params_t &, const bpc_params_t *, const Source &src,
+hipError_t topk_encode(const Geo &g, const bpc_params_t &prm, const bpc_params_t *, const Source &src,
                        uint8_t *payload, const Workspace &ws, hipStream_t stream) {
   uint32_t *hist = ws.at<uint32_t>(ws.lay.hist);
   uint32_t *state = ws.at<uint32_t>(ws.lay.state);
@@ -263,14 +280,17 @@ hipError_t topk_encode(const Geo &g, const bpc_params_t &, const bpc_params_t *,
   float *dense = ws.at<float>(ws.lay.dense);
   // the vector being compressed ends up in the residual buffer (error feedback) or the workspace
   float *buf = src.residual ? src.residual : dense;
+  const bool half = prm.kind == BPC_TOPK16;
   hipError_t e;
   if (!src.grad) {
     // server: sum the n decoded messages into the workspace in worker order
     e = fill_zero(dense, sizeof(float) * g.D, stream);
     if (e != hipSuccess) return e;
     dim3 grid((uint32_t)cdiv(g.k_cap, kThreads), g.P);
-    for (int i = 0; i < src.msgs.n; ++i)
-      topk_accumulate_kernel<<<grid, kThreads, 0, stream>>>(g, src.msgs.ptr[i], dense);
+    for (int i = 0; i < src.msgs.n; ++i) {
+      if (half) topk_accumulate_kernel<true><<<grid, kThreads, 0, stream>>>(g, src.msgs.ptr[i], dense);
+      else topk_accumulate_kernel<false><<<grid, kThreads, 0, stream>>>(g, src.msgs.ptr[i], dense);
+    }
   }
   e = fill_zero(hist, sizeof(uint32_t) * kHistPerPart * (size_t)g.P, stream);
   if (e != hipSuccess) return e;
@@ -292,8 +312,9 @@ hipError_t topk_encode(const Geo &g, const bpc_params_t &, const bpc_params_t *,
   topk_hist_kernel<3><<<g.n_tiles, kThreads, 0, stream>>>(g, buf, state, hist);
   topk_pick_kernel<3><<<g.P, kThreads, 0, stream>>>(g, hist, state);
   topk_count_kernel<<<g.n_tiles, kThreads, 0, stream>>>(g, buf, state, tilecnt);
-  topk_scan_kernel<<<g.P, kThreads, 0, stream>>>(g, tilecnt, payload);
-  topk_emit_kernel<<<g.n_tiles, kThreads, 0, stream>>>(g, buf, state, tilecnt, payload, src.residual != nullptr);
+  topk_scan_kernel<<<g.P, kThreads, 0, stream>>>(g, tilecnt, payload, half ? 1 : 0);
+  if (half) topk_emit_kernel<true><<<g.n_tiles, kThreads, 0, stream>>>(g, buf, state, tilecnt, payload, src.residual != nullptr);
+  else topk_emit_kernel<false><<<g.n_tiles, kThreads, 0, stream>>>(g, buf, state, tilecnt, payload, src.residual != nullptr);
   return hipGetLastError();
 }
 

@@ -45,6 +45,9 @@ WORKLOADS = {
     "bert_large_natural": dict(D=336_000_000, dtype="f16", dist="student_t3", kind="natdither", levels=4,
                                n_workers=16, ef=True, opt="adam"),
     # nor is this: the 5-bit form of linear dithering (15 levels: nibbles and one bit plane)
+    # nor this: BERT-base shape with the paper's own BERT setting, top-k of 0.1 % sent as 32-bit index + half value
+    "bert_base_topk16": dict(D=110_000_000, dtype="f16", dist="student_t3", kind="topk16", k_ratio=0.001,
+                             n_workers=16, ef=True, opt="adam"),
     # nor this: the FP32 -> FP16 conversion as the compressor
     "bert_large_fp16": dict(D=336_000_000, dtype="f16", dist="student_t3", kind="fp16",
                             n_workers=16, ef=True, opt="adam"),

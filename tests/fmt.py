@@ -35,6 +35,8 @@ def stride(kind, part_elems, k_ratio=0.0, levels=4):
         words = ru4((part_elems + 1) // 2)
     elif kind == "topk":
         words = 2 * ru4(k_of(k_ratio, part_elems))
+    elif kind == "topk16":
+        words = ru4(k_of(k_ratio, part_elems)) + ru4((k_of(k_ratio, part_elems) + 1) // 2)
     elif kind == "randk":
         words = ru4(k_of(k_ratio, part_elems))
     else:
@@ -104,6 +106,14 @@ def topk_entries(rec, k_cap):
     return k, idx, val
 
 
+def topk16_entries(rec, k_cap):
+    k = header_u32(rec)
+    idx = rec[16:16 + 4 * k].view(np.int32)
+    off = 16 + 4 * ru4(k_cap)
+    val = rec[off:off + 2 * k].view(np.float16)
+    return k, idx, val
+
+
 def randk_values(rec):
     k = header_u32(rec)
     return k, rec[16:16 + 4 * k].view(np.float32)
@@ -127,6 +137,9 @@ def defined_bytes(kind, d, k=0, k_cap=0, part_elems=0, levels=4):
     if kind == "topk":
         off = 16 + 4 * ru4(k_cap)
         return [(0, 16 + 4 * k), (off, off + 4 * k)]
+    if kind == "topk16":
+        off = 16 + 4 * ru4(k_cap)
+        return [(0, 16 + 4 * k), (off, off + 4 * ru4((k + 1) // 2))]
     if kind == "randk":
         return [(0, 16 + 4 * k)]
     raise ValueError(kind)

@@ -8,13 +8,13 @@ import paper_2105_07829_amd as bpc
 DEV = "cuda"
 
 KIND_B = {"identity": bpc.IDENTITY, "sign": bpc.SIGN, "topk": bpc.TOPK, "randk": bpc.RANDK, "dither": bpc.DITHER,
-          "natdither": bpc.NATDITHER, "fp16": bpc.FP16}
+          "natdither": bpc.NATDITHER, "fp16": bpc.FP16, "topk16": bpc.TOPK16}
 
 
 def both_params(orc, kind, pe, **kw):
     """The same compressor description for the oracle and for the library."""
     kind_o = {"identity": orc.IDENTITY, "sign": orc.SIGN, "topk": orc.TOPK, "randk": orc.RANDK,
-              "dither": orc.DITHER, "natdither": orc.NATDITHER, "fp16": orc.FP16}[kind]
+              "dither": orc.DITHER, "natdither": orc.NATDITHER, "fp16": orc.FP16, "topk16": orc.TOPK16}[kind]
     return orc.make_params(kind_o, pe, **kw), bpc.make_params(KIND_B[kind], pe, **kw)
 
 

@@ -26,6 +26,7 @@ def gu():
 KW = {
     "sign": {},
     "topk": dict(k_ratio=0.01),
+    "topk16": dict(k_ratio=0.01),
     "randk": dict(k_ratio=0.02, value_scale=1.0, seed=11, stream_id=(2 << 32) | 5),
     "dither": dict(levels=4, seed=0xFEED, stream_id=(7 << 32) | 1),
     "natdither": dict(levels=6, seed=0xBEEF, stream_id=(7 << 32) | 2),
@@ -36,7 +37,7 @@ KW = {
 
 def defined_equal(kind, pay_a, pay_b, po, orc, D, pe, kw):
     strd = orc.partition_stride(po)
-    k_cap = fmt.k_of(kw.get("k_ratio", 0.01), pe) if kind in ("topk", "randk") else 0
+    k_cap = fmt.k_of(kw.get("k_ratio", 0.01), pe) if kind in ("topk", "topk16", "randk") else 0
     for p, d in enumerate(fmt.part_sizes(D, pe)):
         k = fmt.k_of(kw.get("k_ratio", 0.01), d) if k_cap else 0
         ra, rb = fmt.record(pay_a, p, strd), fmt.record(pay_b, p, strd)
@@ -121,7 +122,7 @@ def test_dither_tiny_values_divide_per_element(gu, orc, norm, kind):
     assert np.array_equal(res_gpu.view(np.uint32), res_ref.view(np.uint32))
 
 
-@pytest.mark.parametrize("kind", ["sign", "dither", "natdither", "topk", "randk", "identity", "fp16"])
+@pytest.mark.parametrize("kind", ["sign", "dither", "natdither", "topk", "topk16", "randk", "identity", "fp16"])
 def test_server_with_the_most_workers(gu, orc, kind):
     n = gu.bpc.MAX_WORKERS
     D = PE + 1234
@@ -156,7 +157,7 @@ def test_server_with_the_most_workers(gu, orc, kind):
             assert kg == kr and gu.close(vg, vr, REL)
     else:
         assert defined_equal(kind, pay_gpu, pay_ref, out_o, orc, D, PE, kw)
-    if kind in ("identity", "topk", "fp16"):
+    if kind in ("identity", "topk", "topk16", "fp16"):
         assert np.array_equal(res_gpu.view(np.uint32), res_ref.view(np.uint32))
     else:
         assert gu.close(res_gpu, res_ref, REL)

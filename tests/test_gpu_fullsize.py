@@ -39,7 +39,7 @@ def record_equal(kind, rec_g, rec_o, d, k, k_cap, pe=0, levels=4):
 
 
 @pytest.mark.parametrize("name", ["sign_1m", "resnet50", "vgg16", "bert_base", "bert_large", "bert_large_natural",
-                                  "bert_large_5bit", "bert_large_fp16"])
+                                  "bert_large_5bit", "bert_large_fp16", "bert_base_topk16"])
 def test_full_size_pipeline(env, orc, name):
     gu, synth, torch = env
     bpc = gu.bpc
@@ -50,9 +50,9 @@ def test_full_size_pipeline(env, orc, name):
     kw = dict(k_ratio=w.get("k_ratio", 0.01), levels=w.get("levels", 4), value_scale=w.get("value_scale", 1.0),
               seed=synth.BASE_SEED)
     kind_o = {"sign": orc.SIGN, "topk": orc.TOPK, "randk": orc.RANDK, "dither": orc.DITHER,
-              "natdither": orc.NATDITHER, "fp16": orc.FP16}[kind]
+              "natdither": orc.NATDITHER, "fp16": orc.FP16, "topk16": orc.TOPK16}[kind]
     kind_b = gu.KIND_B[kind]
-    k_cap = fmt.k_of(kw["k_ratio"], pe) if kind in ("topk", "randk") else 0
+    k_cap = fmt.k_of(kw["k_ratio"], pe) if kind in ("topk", "topk16", "randk") else 0
     dev = gu.DEV
 
     def prm_b(stream):
@@ -99,7 +99,7 @@ def test_full_size_pipeline(env, orc, name):
                 res_o = e_host[p].copy()
                 rec_o = orc.compress(prm_o((1 << 32) | 0, p, norm=hg), g_host[p], res_o)
         assert record_equal(kind, rec_g, rec_o, d, k, k_cap, pe, kw["levels"]), (name, "worker", p)
-        if kind in ("topk", "fp16"):
+        if kind in ("topk", "topk16", "fp16"):
             assert np.array_equal(e_after[p].view(np.uint32), res_o.view(np.uint32))
         else:
             assert gu.close(e_after[p], res_o, REL), (name, "worker residual", p)
@@ -134,7 +134,7 @@ def test_full_size_pipeline(env, orc, name):
         else:
             assert record_equal(kind, rec_g, rec_o, d, k, k_cap, pe, kw["levels"]), (name, "server", p)
         got = sres[sl(p)].cpu().numpy()
-        if kind in ("topk", "fp16"):
+        if kind in ("topk", "topk16", "fp16"):
             assert np.array_equal(got.view(np.uint32), res_o.view(np.uint32))
         else:
             assert gu.close(got, res_o, REL), (name, "server residual", p)

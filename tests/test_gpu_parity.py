@@ -37,6 +37,7 @@ KW = {
     "fp16": {},
     "sign": {},
     "topk": dict(k_ratio=0.01),
+    "topk16": dict(k_ratio=0.013),
     "randk": dict(k_ratio=0.02, value_scale=1.0, seed=0x1234567890ABCDEF, stream_id=(2 << 32) | 5),
     "randk_scaled": dict(k_ratio=0.02, value_scale=-1.0, seed=99, stream_id=3),
     "dither": dict(levels=4, seed=0xFEEDFACECAFEBEEF, stream_id=(7 << 32) | 1),
@@ -65,7 +66,7 @@ def compare_payload(gu, orc, name, po, pay_gpu, pay_ref, D, pe, ref_fn):
         assert np.all(np.abs(hg.astype(np.float64) - hr) <= REL * np.abs(hr))
         if not np.array_equal(hg, hr):
             pay_ref = ref_fn(hg)
-    k_cap = fmt.k_of(KW[name].get("k_ratio", 0.0), pe) if kind in ("topk", "randk") else 0
+    k_cap = fmt.k_of(KW[name].get("k_ratio", 0.0), pe) if kind in ("topk", "topk16", "randk") else 0
     for p, d in enumerate(sizes):
         rg, rr = fmt.record(pay_gpu, p, strd), fmt.record(pay_ref, p, strd)
         k = fmt.k_of(KW[name]["k_ratio"], d) if k_cap else 0
@@ -96,7 +97,7 @@ def test_worker_stage(gu, orc, name, dtype, ef):
 
         compare_payload(gu, orc, name, po, pay_gpu, pay_ref, D, PE, redo)
         if ef:
-            if base_kind(name) in ("identity", "topk", "fp16"):
+            if base_kind(name) in ("identity", "topk", "topk16", "fp16"):
                 assert np.array_equal(res_gpu.view(np.uint32), res_ref.view(np.uint32))
             else:
                 assert gu.close(res_gpu, res_ref, REL), name
@@ -129,7 +130,7 @@ def test_worker_stage_large_partitions(gu, orc, name, dtype, ef):
 
         compare_payload(gu, orc, name, po, pay_gpu, pay_ref, D, BIG_PE, redo)
         if ef:
-            if base_kind(name) in ("identity", "topk", "fp16"):
+            if base_kind(name) in ("identity", "topk", "topk16", "fp16"):
                 assert np.array_equal(res_gpu.view(np.uint32), res_ref.view(np.uint32))
             else:
                 assert gu.close(res_gpu, res_ref, REL), name
@@ -173,7 +174,7 @@ def test_server_stage(gu, orc, name, ef, n):
         else:
             compare_payload(gu, orc, name, out_o, pay_gpu, pay_ref, D, PE, redo)
         if ef:
-            if base_kind(name) in ("identity", "topk", "fp16"):
+            if base_kind(name) in ("identity", "topk", "topk16", "fp16"):
                 assert np.array_equal(res_gpu.view(np.uint32), res_ref.view(np.uint32))
             else:
                 assert gu.close(res_gpu, res_ref, REL), name
@@ -257,7 +258,7 @@ def test_update_stage(gu, orc, name, opt_kind):
 def test_deterministic_bytes(gu, orc):
     """Same call twice gives identical bytes for the kinds whose arithmetic has a fixed order."""
     D = 2 * PE + 4137
-    for name in ("sign", "topk", "dither", "dither_7bit", "natdither", "identity", "fp16"):
+    for name in ("sign", "topk", "topk16", "dither", "dither_7bit", "natdither", "identity", "fp16"):
         po, pb = gu.both_params(orc, base_kind(name), PE, **KW[name])
         g = grads(D, np.float16, 8)
         e = (rng(9).standard_normal(D) * 3e-4).astype(np.float32)
@@ -272,7 +273,7 @@ def test_deterministic_bytes(gu, orc):
                 assert np.array_equal(fmt.record(a[0], p, strd)[lo:hi], fmt.record(b[0], p, strd)[lo:hi])
 
 
-@pytest.mark.parametrize("name", ["sign", "topk", "dither", "dither_5bit", "natdither", "randk", "identity", "fp16"])
+@pytest.mark.parametrize("name", ["sign", "topk", "dither", "dither_5bit", "natdither", "randk", "identity", "fp16", "topk16"])
 def test_chained_pipeline_three_steps(gu, orc, name):
     """Algorithm 4 + the Adam-style update chained on the GPU only (each stage consumes the GPU's
     own previous outputs) against the chained oracle."""

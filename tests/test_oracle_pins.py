@@ -350,6 +350,40 @@ def test_dither_bit_planes_take_the_high_level_bits_in_element_order(orc):
     assert orc.partition_stride(p7) == 16 + 4 * fmt.ru4(PE // 8)
 
 
+# ---------------------------------------------------------------- top-k with half-precision values
+def test_topk16_keeps_the_same_slots_and_sends_halves(orc):
+    """Same selection as top-k; values are the nearest halves; the residual of a kept slot is
+    the rounding error; the message is 6 bytes per kept element, which against 2-byte
+    (mixed-precision) gradients at k = 0.1 % is the compression rate of 333 the paper quotes
+    (Section 5.2)."""
+    d = PE - 97
+    x = (rng(31).standard_normal(d) * np.float32(0.01)).astype(np.float32)
+    p32 = orc.make_params(orc.TOPK, PE, k_ratio=0.02)
+    p16 = orc.make_params(orc.TOPK16, PE, k_ratio=0.02)
+    k_cap = fmt.k_of(0.02, PE)
+    r32, r16 = orc.encode_partition(p32, 0, x), orc.encode_partition(p16, 0, x)
+    k, idx, val = fmt.topk_entries(r32, k_cap)
+    k2, idx2, val2 = fmt.topk16_entries(r16, k_cap)
+    assert k == k2 == fmt.k_of(0.02, d) and np.array_equal(idx, idx2)
+    assert np.array_equal(val2.view(np.uint16), val.astype(np.float16).view(np.uint16))
+    assert orc.partition_stride(p16) == 16 + 4 * fmt.ru4(k_cap) + 4 * fmt.ru4((k_cap + 1) // 2) == fmt.stride("topk16", PE, 0.02)
+    dec = orc.decode_partition(p16, 0, r16, d)
+    want = np.zeros(d, np.float32)
+    want[idx] = val.astype(np.float16).astype(np.float32)
+    assert np.array_equal(dec, want)
+    res = np.zeros(d, np.float32)
+    orc.compress(p16, x, res)
+    exp = x.copy()
+    exp[idx] = x[idx] - want[idx]
+    assert np.array_equal(res, exp)
+    # bytes per kept element and the quoted rate
+    pk = orc.make_params(orc.TOPK16, 1 << 20, k_ratio=0.001)
+    kk = fmt.k_of(0.001, 1 << 20)
+    payload_per_elem = (4 * kk + 2 * kk) / float(1 << 20)
+    assert abs(2.0 / payload_per_elem - 333.3) < 1.0
+    assert orc.partition_stride(pk) <= 16 + 6 * kk + 24
+
+
 # ---------------------------------------------------------------- FP16 conversion
 def test_float_to_half_matches_an_independent_conversion(orc):
     """Round to nearest even, overflow to infinity, subnormal halves, signed zeros: against
@@ -490,7 +524,7 @@ def test_zero_vector_encodes_to_zero(orc):
 
 
 # ---------------------------------------------------------------- Algorithm 4 identities
-KINDS = ["identity", "sign", "topk", "randk", "randk_scaled", "dither", "natdither", "fp16"]
+KINDS = ["identity", "sign", "topk", "randk", "randk_scaled", "dither", "natdither", "fp16", "topk16"]
 
 
 def params_for(orc, name, pe=PE, seed=1, stream=0):
@@ -510,6 +544,8 @@ def params_for(orc, name, pe=PE, seed=1, stream=0):
         return orc.make_params(orc.NATDITHER, pe, levels=4, seed=seed, stream_id=stream)
     if name == "fp16":
         return orc.make_params(orc.FP16, pe)
+    if name == "topk16":
+        return orc.make_params(orc.TOPK16, pe, k_ratio=0.05)
     raise ValueError(name)
 
 
