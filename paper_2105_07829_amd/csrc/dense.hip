@@ -182,6 +182,35 @@ __global__ __launch_bounds__(kThreads) void decode_randk_kernel(Geo g, const uin
   }
 }
 
+// Random-k messages that share one index stream (same seed and stream id at every worker): the
+// n values of draw t are summed in worker order first, then added at idx_t once, i.e. one
+// random access per draw instead of n.
+__global__ __launch_bounds__(kThreads) void decode_randk_shared_kernel(Geo g, WorkerMsgs msgs, float *out,
+                                                                       float value_scale, uint64_t seed,
+                                                                       uint64_t stream_id) {
+  const uint32_t p = blockIdx.y;
+  const uint32_t d = g.part_size(p);
+  uint32_t k = *reinterpret_cast<const uint32_t *>(msgs.ptr[0] + (uint64_t)p * g.stride);
+  k = k > g.k_cap ? g.k_cap : k;
+  const float scale = value_scale >= 0.0f ? value_scale : (float)d / (float)k;
+  const uint64_t base = g.part_base(p);
+  const Philox rng(seed, stream_id, p);
+  for (uint32_t t = blockIdx.x * kThreads + threadIdx.x; t < k; t += gridDim.x * kThreads) {
+    float s = 0.0f;
+    for (int i = 0; i < msgs.n; ++i)
+      s = s + scale * reinterpret_cast<const float *>(msgs.ptr[i] + (uint64_t)p * g.stride + kHeaderBytes)[t];
+    const uint32_t j = (uint32_t)(((uint64_t)rng.word(t) * d) >> 32);
+    atomicAdd(out + base + j, s);
+  }
+}
+
+hipError_t scatter_add_randk_shared(const Geo &g, const bpc_params_t &prm, const WorkerMsgs &msgs, float *out,
+                                    hipStream_t stream) {
+  dim3 grid((uint32_t)cdiv(g.k_cap, kThreads), g.P);
+  decode_randk_shared_kernel<<<grid, kThreads, 0, stream>>>(g, msgs, out, prm.value_scale, prm.seed, prm.stream_id);
+  return hipGetLastError();
+}
+
 hipError_t scatter_add_sparse(const Geo &g, const bpc_params_t &prm, const uint8_t *payload, float *out,
                               hipStream_t stream) {
   dim3 grid((uint32_t)cdiv(g.k_cap, kThreads), g.P);

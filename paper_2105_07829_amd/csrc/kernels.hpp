@@ -59,6 +59,8 @@ hipError_t randk_encode(const Geo &g, const bpc_params_t &prm, const bpc_params_
                         uint8_t *payload, const Workspace &ws, hipStream_t stream);
 
 // out[idx] += decoded sparse entries (TOPK: plain store).  `out` holds the running sum.
+hipError_t scatter_add_randk_shared(const Geo &g, const bpc_params_t &prm, const WorkerMsgs &msgs, float *out,
+                                    hipStream_t stream);
 hipError_t scatter_add_sparse(const Geo &g, const bpc_params_t &prm, const uint8_t *payload, float *out,
                               hipStream_t stream);
 

@@ -100,9 +100,19 @@ hipError_t randk_encode(const Geo &g, const bpc_params_t &prm, const bpc_params_
   } else {
     hipError_t e = fill_zero(dense, sizeof(float) * g.D, stream);
     if (e != hipSuccess) return e;
-    for (int i = 0; i < src.msgs.n; ++i) {
-      e = scatter_add_sparse(g, in_prm[i], src.msgs.ptr[i], dense, stream);
+    // workers that drew from one stream sent values for the same indices
+    bool shared = src.msgs.n > 1;
+    for (int i = 1; i < src.msgs.n; ++i)
+      shared = shared && in_prm[i].seed == in_prm[0].seed && in_prm[i].stream_id == in_prm[0].stream_id &&
+               in_prm[i].value_scale == in_prm[0].value_scale;
+    if (shared) {
+      e = scatter_add_randk_shared(g, in_prm[0], src.msgs, dense, stream);
       if (e != hipSuccess) return e;
+    } else {
+      for (int i = 0; i < src.msgs.n; ++i) {
+        e = scatter_add_sparse(g, in_prm[i], src.msgs.ptr[i], dense, stream);
+        if (e != hipSuccess) return e;
+      }
     }
     randk_store_kernel<<<g.n_tiles, kThreads, 0, stream>>>(g, DenseSumSource{dense, src.residual, src.msgs.inv_n}, buf);
   }

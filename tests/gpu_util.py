@@ -15,6 +15,7 @@ def both_params(orc, kind, pe, **kw):
     """The same compressor description for the oracle and for the library."""
     kind_o = {"identity": orc.IDENTITY, "sign": orc.SIGN, "topk": orc.TOPK, "randk": orc.RANDK,
               "dither": orc.DITHER, "natdither": orc.NATDITHER, "fp16": orc.FP16, "topk16": orc.TOPK16}[kind]
+    kw = {k: v for k, v in kw.items() if not k.startswith("_")}     # "_..." keys are notes for the tests
     return orc.make_params(kind_o, pe, **kw), bpc.make_params(KIND_B[kind], pe, **kw)
 
 

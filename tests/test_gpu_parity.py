@@ -40,6 +40,8 @@ KW = {
     "topk16": dict(k_ratio=0.013),
     "randk": dict(k_ratio=0.02, value_scale=1.0, seed=0x1234567890ABCDEF, stream_id=(2 << 32) | 5),
     "randk_scaled": dict(k_ratio=0.02, value_scale=-1.0, seed=99, stream_id=3),
+    # every worker draws from the same stream: the server sums the value vectors before it scatters
+    "randk_shared": dict(k_ratio=0.02, value_scale=-1.0, seed=1234, stream_id=77, _shared=True),
     "dither": dict(levels=4, seed=0xFEEDFACECAFEBEEF, stream_id=(7 << 32) | 1),
     "dither_linf": dict(levels=7, norm=1, seed=5, stream_id=9),
     "dither_5bit": dict(levels=15, seed=0xC0FFEE, stream_id=(5 << 32) | 3),
@@ -144,7 +146,7 @@ def test_server_stage(gu, orc, name, ef, n):
         kw = dict(KW[name])
         ins = []
         for i in range(n):
-            if "stream_id" in kw:
+            if "stream_id" in kw and not kw.get("_shared"):
                 kw["stream_id"] = (1 << 32) | i
             ins.append(gu.both_params(orc, base_kind(name), PE, **kw))
         if "stream_id" in kw:
@@ -190,7 +192,7 @@ def test_server_stage_large_partitions(gu, orc, name, ef, n):
         kw = dict(KW[name])
         ins = []
         for i in range(n):
-            if "stream_id" in kw:
+            if "stream_id" in kw and not kw.get("_shared"):
                 kw["stream_id"] = (1 << 32) | i
             ins.append(gu.both_params(orc, base_kind(name), BIG_PE, **kw))
         if "stream_id" in kw:
@@ -290,7 +292,7 @@ def test_chained_pipeline_three_steps(gu, orc, name):
         ins, pay_o, pay_g = [], [], []
         for i in range(n):
             kw = dict(KW[name])
-            if "stream_id" in kw:
+            if "stream_id" in kw and not kw.get("_shared"):
                 kw["stream_id"] = (t << 32) | i
             po, pb = gu.both_params(orc, base_kind(name), PE, **kw)
             ins.append((po, pb))
