@@ -30,7 +30,18 @@ hipStream_t g_last_stream[kMaxDevices];
 bool g_have[kMaxDevices];
 }  // namespace
 
+// While `stream` is being captured into a graph nothing is chained: the graph orders its own
+// nodes, and an event recorded during capture is not one a later eager launch could wait for.
+// Keeping replays of such a graph apart from cluster kernels launched elsewhere at the same
+// time is then up to the caller.
+static bool is_capturing(hipStream_t stream) {
+  hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(stream, &st) != hipSuccess) return false;
+  return st != hipStreamCaptureStatusNone;
+}
+
 hipError_t cluster_launch_begin(hipStream_t stream) {
+  if (is_capturing(stream)) return hipSuccess;
   int dev = 0;
   hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return e;
@@ -41,6 +52,7 @@ hipError_t cluster_launch_begin(hipStream_t stream) {
 }
 
 hipError_t cluster_launch_end(hipStream_t stream) {
+  if (is_capturing(stream)) return hipSuccess;
   int dev = 0;
   hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return e;
