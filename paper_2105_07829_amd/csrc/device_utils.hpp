@@ -188,20 +188,22 @@ __device__ inline float block_max(float x, float *scratch) {
 // exclusive prefix of `x`; *total receives the sum over all threads.
 template <int THREADS>
 __device__ inline uint32_t block_exclusive_scan(uint32_t x, uint32_t *lds /*THREADS*/, uint32_t *total) {
-  int t = threadIdx.x;
+  // scan inside each wave with lane moves, then add the totals of the waves before
+  const uint32_t incl = wave_inclusive_scan_u32(x);
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   __syncthreads();
-  lds[t] = x;
+  if (lane == 63) lds[wave] = incl;
   __syncthreads();
-  for (int off = 1; off < THREADS; off <<= 1) {
-    uint32_t add = t >= off ? lds[t - off] : 0;
-    __syncthreads();
-    lds[t] += add;
-    __syncthreads();
+  uint32_t before = 0, all = 0;
+#pragma unroll
+  for (int w = 0; w < THREADS / 64; ++w) {
+    const uint32_t v = lds[w];
+    before += w < wave ? v : 0u;
+    all += v;
   }
-  uint32_t incl = lds[t];
-  *total = lds[THREADS - 1];
+  *total = all;
   __syncthreads();
-  return incl - x;
+  return before + incl - x;
 }
 
 }  // namespace bpc

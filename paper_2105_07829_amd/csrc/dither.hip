@@ -1,6 +1,8 @@
 // Dithering, multi-pass form (linear levels: the stochastic multi-level quantiser the paper
-// cites for its "dithering" compressors, Section 3.2; natural levels: powers of two): with a = s|v_j|/nu the level is floor(a)+1 with probability
-// a-floor(a), else floor(a).  Message: nu once, then one nibble (sign, level) per element.
+// cites for its dithering compressors, Section 3.2; natural levels: powers of two): with
+// a = s|v_j|/nu the level is floor(a)+1 with probability a-floor(a), else floor(a).  Message:
+// nu once, then one nibble (sign, low level bits) per element and, beyond 7 levels, one bit
+// plane per further level bit.
 // Residual update as in Algorithm 4.  Three launches per call:
 //   reduce : per-tile partial of sum v_j^2 (f64) or max |v_j|
 //   finish : nu per partition -> record header

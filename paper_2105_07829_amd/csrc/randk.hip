@@ -1,4 +1,4 @@
-// Random-k compressor ("random k elements of the gradient are sent", Section 3.2): k indices
+// Random-k compressor (Section 3.2: k randomly chosen entries of the gradient travel): k indices
 // drawn uniformly with replacement from a Philox stream that sender and receiver share, so
 // only the k values travel.  The decode multiplies by `value_scale` (d/k makes the operator
 // unbiased, Definition 1; 1 gives the plain zero-fill residual of Section 4.2).  Residual
