@@ -161,3 +161,25 @@ def test_server_with_the_most_workers(gu, orc, kind):
         assert np.array_equal(res_gpu.view(np.uint32), res_ref.view(np.uint32))
     else:
         assert gu.close(res_gpu, res_ref, REL)
+
+
+def test_fp16_conversion_at_the_ends_of_the_half_range(gu, orc):
+    """Round to nearest even on the card as in the oracle: ties, the subnormal halves, what
+    rounds up to infinity (its residual is then -inf / +inf on both sides)."""
+    D = PE + 517
+    rs = np.random.default_rng(12)
+    g = (rs.standard_normal(D) * 1e-3).astype(np.float32)
+    special = np.array([65504.0, 65519.9, 65520.0, -65520.0, 70000.0, -1e6, 2.0 ** -24, 2.0 ** -25,
+                        np.nextafter(np.float32(2.0 ** -25), np.float32(1)), -2.0 ** -26, 2.0 ** -14,
+                        np.nextafter(np.float32(2.0 ** -14), np.float32(0)), 1.0 + 2.0 ** -11, 1.0 + 3 * 2.0 ** -11,
+                        1e-45, -1e-45, 0.0, -0.0], dtype=np.float32)
+    g[100:100 + special.size] = special
+    g[PE - 3:PE + 3] = special[:6]                      # across the partition boundary
+    po, pb = gu.both_params(orc, "fp16", PE)
+    e = np.zeros(D, np.float32)
+    res_ref = e.copy()
+    pay_ref = orc.compress(po, g, res_ref)
+    pay_gpu, res_gpu = gu.gpu_compress(pb, g, e.copy())
+    assert defined_equal("fp16", pay_gpu, pay_ref, po, orc, D, PE, {})
+    assert np.array_equal(res_gpu.view(np.uint32), res_ref.view(np.uint32))
+    assert np.array_equal(gu.gpu_decompress(pb, pay_gpu, D).view(np.uint32), orc.decompress(po, pay_ref, D).view(np.uint32))
