@@ -110,6 +110,13 @@ class Pipeline:
         opt = self.bpc.make_opt(self.bpc.OPT_ADAM, 1e-3, 0.9, 0.999, 1e-8, 0.01, t)
         self.bpc.bpc_adaptive_update(self.params(1, 0), self.pay_out, self.x, self.m, self.v, opt, self.ws)
 
+    def stage_u_lans(self):
+        """The update as Algorithm 5 prints it (block-normalised, the partitions as blocks); timed
+        beside the Adam-style update of the step, on the same buffers."""
+        t = max(self.t, 1)
+        opt = self.bpc.make_opt(self.bpc.OPT_LANS, 1e-3, 0.9, 0.999, 1e-8, 0.01, t)
+        self.bpc.bpc_adaptive_update(self.params(1, 0), self.pay_out, self.x, self.m, self.v, opt, self.ws)
+
     def step(self):
         self.t += 1
         for i in range(self.n):
@@ -145,14 +152,16 @@ def run_workload(name, w, steps, warmup, torch, bpc, synth):
     ms_w = timed(torch, lambda: pipe.stage_w(0), reps)
     ms_s = timed(torch, pipe.stage_s, reps)
     ms_u = timed(torch, pipe.stage_u, reps)
+    ms_ul = timed(torch, pipe.stage_u_lans, reps)
     G = 4 if w["dtype"] == "f32" else 2
     D, n = w["D"], w["n_workers"]
     alg = algorithmic_bytes_per_elem(w)
     stages = {}
-    for key, ms in (("W", ms_w), ("S", ms_s), ("U", ms_u)):
+    for key, ms in (("W", ms_w), ("S", ms_s), ("U", ms_u), ("U_lans", ms_ul)):
+        a = alg[key[0]]
         stages[key] = {"ms": round(ms, 4), "gradient_GBps": round(D * G / ms / 1e6, 1),
-                       "algorithmic_GBps": round(D * alg[key] / ms / 1e6, 1),
-                       "frac_of_hbm_peak": round(D * alg[key] / ms / 1e6 / HBM_PEAK_GBPS, 4)}
+                       "algorithmic_GBps": round(D * a / ms / 1e6, 1),
+                       "frac_of_hbm_peak": round(D * a / ms / 1e6 / HBM_PEAK_GBPS, 4)}
     out = {"workload": name, "D": D, "dtype": w["dtype"], "compressor": w["kind"], "n_workers": n,
            "ms_per_step": round(ms_step, 4), "value_GBps": round(n * D * G / ms_step / 1e6, 1),
            "pipeline_GBps_one_worker": round(D * G / (ms_w + ms_s + ms_u) / 1e6, 1), "stages": stages}
