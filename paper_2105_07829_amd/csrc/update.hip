@@ -81,6 +81,54 @@ struct DitherDec {
     for (int c = 0; c < 4; ++c) out[c] = lds[(w >> (4 * c)) & 15u];
   }
 };
+// Linear dithering with bit planes (more than 7 levels).  Table index = plane bits << 4 | nibble,
+// i.e. (level bits 3..5, sign, level bits 0..2); entries beyond the levels in use are never read.
+struct DitherWideDec {
+  const uint8_t *payload; uint64_t stride; uint32_t levels; uint64_t part_elems;
+  __device__ const float *dense_base() const { return nullptr; }
+  static constexpr int kLdsFloats = 128;
+  __device__ float entry(float nu, uint32_t e) const {
+    const uint32_t level = (e & 7u) | ((e >> 4) << 3);
+    const float mag = level <= levels ? dither_mag(nu, level, levels, false) : 0.0f;
+    return (e & 8u) ? -mag : mag;
+  }
+  __device__ void begin(uint32_t p, float *lds) const {
+    if (threadIdx.x < 128) lds[threadIdx.x] = entry(*reinterpret_cast<const float *>(payload + (uint64_t)p * stride), threadIdx.x);
+    __syncthreads();
+  }
+  // the nibbles of 4 elements in bits 0..15, then 4 bits of each plane in bits 16.., 20.., 24..
+  using R4 = uint32_t;
+  __device__ float header(uint32_t p) const { return *reinterpret_cast<const float *>(payload + (uint64_t)p * stride); }
+  __device__ void table(float nu, float *lds) const {
+    if (threadIdx.x < 128) lds[threadIdx.x] = entry(nu, threadIdx.x);
+  }
+  __device__ R4 load4(const Geo &, uint32_t p, uint32_t j, const TileBuf &) const {
+    const uint8_t *rec = payload + (uint64_t)p * stride;
+    uint32_t r = reinterpret_cast<const uint16_t *>(rec + kHeaderBytes)[j >> 2];
+    const uint32_t planes = dither_planes(levels);
+    const uint8_t *plane = rec + dither_plane0(part_elems) + (j >> 3);
+    for (uint32_t t = 0; t < planes; ++t)
+      r |= (((uint32_t)plane[t * dither_plane_bytes(part_elems)] >> (j & 4)) & 15u) << (16 + 4 * t);
+    return r;
+  }
+  __device__ void decode4(R4 r, uint32_t, float, const float *lds, float out[4]) const {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const uint32_t nib = (r >> (4 * c)) & 15u;
+      const uint32_t hi = ((r >> (16 + c)) & 1u) | (((r >> (20 + c)) & 1u) << 1) | (((r >> (24 + c)) & 1u) << 2);
+      out[c] = lds[(hi << 4) | nib];
+    }
+  }
+  __device__ void at4(const Geo &g, uint32_t p, uint32_t j, const TileBuf &row, const float *lds, float out[4]) const {
+    decode4(load4(g, p, j, row), j, 0.0f, lds, out);
+  }
+  __device__ float at(const Geo &g, uint32_t p, uint32_t j, const float *lds) const {
+    float out[4];
+    at4(g, p, j & ~3u, TileBuf(nullptr, 0), lds, out);
+    const uint32_t c = j & 3u;
+    return c == 0 ? out[0] : c == 1 ? out[1] : c == 2 ? out[2] : out[3];
+  }
+};
 struct IdentityDec {
   const uint8_t *payload; uint64_t stride;
   __device__ const float *dense_base() const { return nullptr; }
@@ -575,7 +623,12 @@ hipError_t adaptive_update(const Geo &g, const bpc_params_t &prm, const uint8_t 
   switch (prm.kind) {
     case BPC_SIGN: return run_update(g, SignDec{payload, g.stride}, x, m, v, opt, norms, ws, stream);
     case BPC_DITHER: case BPC_NATDITHER:
-      if (prm.kind == BPC_DITHER && dither_planes(prm.levels) > 0) break;   // bit planes: through the dense decode below
+      if (prm.kind == BPC_DITHER && dither_planes(prm.levels) > 0) {
+        // bit planes: the Adam-style update decodes them itself; LANS, which is bound by its
+        // arithmetic, was faster reading a dense decode (below)
+        if (opt.kind == BPC_OPT_LANS) break;
+        return run_update(g, DitherWideDec{payload, g.stride, prm.levels, g.part_elems}, x, m, v, opt, norms, ws, stream);
+      }
       return run_update(g, DitherDec{payload, g.stride, prm.levels, prm.kind == BPC_NATDITHER}, x, m, v, opt, norms, ws, stream);
     case BPC_IDENTITY: return run_update(g, IdentityDec{payload, g.stride}, x, m, v, opt, norms, ws, stream);
     case BPC_FP16: return run_update(g, Fp16Dec{payload, g.stride}, x, m, v, opt, norms, ws, stream);
