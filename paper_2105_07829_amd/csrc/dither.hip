@@ -180,10 +180,10 @@ hipError_t dither_encode(const Geo &g_in, const bpc_params_t &prm_in, const Sour
   Geo g = g_in;
   Source src = src_in;
   bpc_params_t prm = prm_in;
-  // (the single-pass server reads and writes nibbles only: with more than 7 levels the server
+  // (the single-pass server handles up to 15 levels; beyond that it declines and the server
   // side takes the passes below)
   const bool wide = prm_in.kind == BPC_DITHER && dither_planes(prm_in.levels) > 0;
-  if ((!wide || src.grad) && sp.single_pass && sp.head.P > 0) {
+  if (sp.single_pass && sp.head.P > 0) {
     bool used = false;
     hipError_t e = src.grad ? dither_worker_single_pass(sp.head, prm, src, payload, ws, stream, &used)
                             : dither_server_single_pass(sp.head, prm, src, payload, ws, stream, &used);

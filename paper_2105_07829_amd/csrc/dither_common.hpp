@@ -51,21 +51,33 @@ __device__ inline void dither_fill_table(float nu, uint32_t levels, bool natural
 
 // One output row of 8 consecutive elements per thread: levels from two Philox blocks, the
 // packed word and the 8 residuals.  j0 is the partition-local index of the first element.
-template <int MODE, bool NAT>
+// WIDE: levels beyond 7; *plane0 receives bit 3 of the 8 levels (the caller has made sure the
+// levels need no further plane).
+template <int MODE, bool NAT, bool WIDE = false>
 __device__ inline uint32_t dither_row(const float q[8], float nu, float top_over_nu, float top, uint32_t levels,
-                                      const Philox &rng, uint32_t j0, const float *mag, float r[8]) {
-  uint32_t word = 0;
+                                      const Philox &rng, uint32_t j0, const float *mag, float r[8],
+                                      uint32_t *plane0 = nullptr) {
+  uint32_t word = 0, hi = 0;
   if (MODE == 0) {
 #pragma unroll
     for (int c = 0; c < 8; ++c) r[c] = q[c];
+    if (WIDE) *plane0 = 0;
     return 0;
   }
   uint32_t rnd[8];
   rng.block(j0 >> 2, rnd);
   rng.block((j0 >> 2) + 1, rnd + 4);
 #pragma unroll
-  for (int c = 0; c < 8; ++c)
-    word |= dither_quantise<MODE == 2, NAT>(q[c], nu, top_over_nu, top, levels, rnd[c], mag, &r[c]) << (4 * c);
+  for (int c = 0; c < 8; ++c) {
+    const uint32_t code = dither_quantise<MODE == 2, NAT, WIDE>(q[c], nu, top_over_nu, top, levels, rnd[c], mag, &r[c]);
+    if (WIDE) {
+      word |= (((code >> 6) << 3) | (code & 7u)) << (4 * c);
+      hi |= ((code >> 3) & 1u) << c;
+    } else {
+      word |= code << (4 * c);
+    }
+  }
+  if (WIDE) *plane0 = hi;
   return word;
 }
 

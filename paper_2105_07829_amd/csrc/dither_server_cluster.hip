@@ -41,7 +41,10 @@ __device__ inline uint32_t byte_and(uint32_t x, uint32_t mask) {
 }
 
 // NW > 0: number of workers known at compile time (unrolled); NW == 0: rolled loop.
-template <bool EF, bool LINF, int NW, bool NAT>
+// WIDE: linear levels 8..15 (the 5-bit form): one bit plane beside the nibbles, on the way in
+// and on the way out; a worker's table then has 32 entries, index = plane bit << 4 | nibble,
+// and the workers come in groups of four so that their words and plane bytes fit the registers.
+template <bool EF, bool LINF, int NW, bool NAT, bool WIDE = false>
 struct DitherServerOp {
   static constexpr int kThreads = NW > 0 ? 512 : kSThreads;
   static constexpr int kDSRows = kSTile / (kThreads * 8);   // 2 or 4
@@ -51,7 +54,9 @@ struct DitherServerOp {
   struct Ctx { float nu, top_over_nu; int mode; const float *mag; };
   static constexpr bool kMax = LINF;
   static constexpr int kRowsPerTile = kDSRows;
-  static constexpr int kTableFloats = kMaxWorkers * 16 + 8;   // decode tables, then the 8 output magnitudes
+  static constexpr int kLutStride = WIDE ? 32 : 16;
+  static constexpr int kTableFloats = kMaxWorkers * 16 + 16;   // decode tables (at most 1024 floats), then the output magnitudes
+  static_assert(!WIDE || (NW > 0 && NW * 32 <= kMaxWorkers * 16), "tables of the wide form must fit");
   static constexpr size_t kMaxDynLds = 0;
   static constexpr bool kPersistent = false;
 
@@ -91,14 +96,16 @@ struct DitherServerOp {
     raw.e[2 * u + 1] = eb.load16(threadIdx.x * 32 + 16, 0);
   }
 
-  // Decode tables of all workers for partition p: lut[i*16 + nibble].
+  // Decode tables of all workers for partition p: lut[i*16 + nibble], or (WIDE)
+  // lut[i*32 + (plane bit << 4 | nibble)].
   __device__ void fill_luts(uint32_t p, float *lut) const {
     __syncthreads();
-    for (int e = threadIdx.x; e < msgs.n * 16; e += kThreads) {
-      const int i = e >> 4, nib = e & 15;
+    for (int e = threadIdx.x; e < msgs.n * kLutStride; e += kThreads) {
+      const int i = e / kLutStride, code = e % kLutStride;
       const float nu = *reinterpret_cast<const float *>(msgs.ptr[i] + (uint64_t)p * g.stride);
-      const float mag = dither_mag(nu, nib & 7, levels, NAT);
-      lut[e] = (nib & 8) ? -mag : mag;
+      const uint32_t level = (code & 7) | ((code >> 4) << 3);
+      const float mag = level <= levels ? dither_mag(nu, level, levels, NAT) : 0.0f;
+      lut[e] = (code & 8) ? -mag : mag;
     }
     __syncthreads();
   }
@@ -109,6 +116,33 @@ struct DitherServerOp {
         msgs.ptr[i] + uniform_off((uint64_t)part_of(item) * g.stride + kHeaderBytes + (tile_off(item) >> 1)));
 #pragma unroll
     for (int u = 0; u < kDSRows; ++u) out[u] = nibs[u * kThreads + threadIdx.x];
+  }
+
+  // The byte of worker i's bit plane that covers this thread's 8 elements of each row.
+  __device__ void load_planes(uint32_t item, int i, uint32_t out[kDSRows]) const {
+    const uint8_t *plane = msgs.ptr[i] + uniform_off((uint64_t)part_of(item) * g.stride + dither_plane0(g.part_elems) + (tile_off(item) >> 3));
+#pragma unroll
+    for (int u = 0; u < kDSRows; ++u) out[u] = plane[u * kThreads + threadIdx.x];
+  }
+  // WIDE: table offset = (plane bit << 4 | nibble) * 4.
+  __device__ static void add_worker_wide(const uint32_t word[kDSRows], const uint32_t pb[kDSRows], const float *lut_i,
+                                         float acc[kPerThread]) {
+    const char *lut_b = reinterpret_cast<const char *>(lut_i);
+#pragma unroll
+    for (int u = 0; u < kDSRows; ++u) {
+      const uint32_t even = word[u] << 2, odd = word[u] >> 2;
+      const uint32_t hi = pb[u] << 6;   // bit c of the byte -> bit 6 + c
+      uint32_t off[8];
+      off[0] = byte_and<0>(even, 0x3cu); off[1] = byte_and<0>(odd, 0x3cu);
+      off[2] = byte_and<1>(even, 0x3cu); off[3] = byte_and<1>(odd, 0x3cu);
+      off[4] = byte_and<2>(even, 0x3cu); off[5] = byte_and<2>(odd, 0x3cu);
+      off[6] = byte_and<3>(even, 0x3cu); off[7] = byte_and<3>(odd, 0x3cu);
+      float v[8];
+#pragma unroll
+      for (int c = 0; c < 8; ++c) v[c] = *reinterpret_cast<const float *>(lut_b + (off[c] | ((hi >> c) & 0x40u)));
+#pragma unroll
+      for (int c = 0; c < 8; ++c) acc[8 * u + c] = acc[8 * u + c] + v[c];
+    }
   }
 
   // The byte offsets nibble*4 of a word's eight nibbles into a worker's table: after a shift
@@ -139,7 +173,23 @@ struct DitherServerOp {
     float acc[kPerThread];
 #pragma unroll
     for (int k = 0; k < kPerThread; ++k) acc[k] = 0.0f;
-    if (NW > 0) {
+    if (WIDE) {
+      // groups of four workers, each requested in one go (more in flight would not fit the
+      // registers next to the tile of the older partition)
+      constexpr int kGroup = NW > 4 ? 4 : (NW > 0 ? NW : 1);
+#pragma unroll 1   // (unrolled, the loads of all groups are hoisted to the front)
+      for (int i0 = 0; i0 < NW; i0 += kGroup) {
+        uint32_t word[kGroup][kDSRows], pb[kGroup][kDSRows];
+#pragma unroll
+        for (int k = 0; k < kGroup; ++k) {
+          load_words(item, i0 + k, word[k]);
+          load_planes(item, i0 + k, pb[k]);
+        }
+        if (i0 == 0) fill_luts(p, table);
+#pragma unroll
+        for (int k = 0; k < kGroup; ++k) add_worker_wide(word[k], pb[k], table + (i0 + k) * 32, acc);
+      }
+    } else if (NW > 0) {
       // every word of every worker is requested before the tables are built
       uint32_t word[NW > 0 ? NW : 1][kDSRows];
 #pragma unroll
@@ -204,9 +254,14 @@ struct DitherServerOp {
     const Philox rng(seed, stream_id, p);
     const uint32_t j0 = tile_off(item) + (u * kThreads + threadIdx.x) * 8;
     float r[8];
-    const uint32_t word = dither_row<MODE, NAT>(&h.delta[8 * u], ctx.nu, ctx.top_over_nu, dither_top(levels, NAT), levels, rng, j0, ctx.mag, r);
+    uint32_t hi = 0;
+    const uint32_t word = dither_row<MODE, NAT, WIDE>(&h.delta[8 * u], ctx.nu, ctx.top_over_nu, dither_top(levels, NAT), levels, rng, j0, ctx.mag, r, &hi);
     uint32_t *nibs = reinterpret_cast<uint32_t *>(payload + (uint64_t)p * g.stride + kHeaderBytes);
     (nibs + uniform_off((tile_off(item) + u * (kThreads * 8)) >> 3))[threadIdx.x] = word;
+    if (WIDE) {
+      uint8_t *plane = payload + (uint64_t)p * g.stride + dither_plane0(g.part_elems);
+      (plane + uniform_off((tile_off(item) + u * (kThreads * 8)) >> 3))[threadIdx.x] = (uint8_t)hi;
+    }
     if (EF) {
       const TileBuf ob = row_buf(res + base(item), valid_of(item), u * (kThreads * 8), kThreads * 8);
       ob.store16(as_u32x4(r[0], r[1], r[2], r[3]), threadIdx.x * 32);
@@ -221,21 +276,27 @@ struct DitherServerOp {
 
 };
 
-template <bool EF, bool LINF, bool NAT>
+template <bool EF, bool LINF, bool NAT, bool WIDE>
 static hipError_t launch_dither_server(const Geo &g, const ClusterGeo &cg, const bpc_params_t &prm,
                                        const Source &src, uint8_t *payload, double *slots, uint32_t *status,
                                        hipStream_t stream, bool *used) {
   const DMsgPtrs mp = dmsg_ptrs(src.msgs);
   float *res = src.residual;
 #define BPC_DS(NW)                                                                                          \
-  return launch_cluster(DitherServerOp<EF, LINF, NW, NAT>{g, cg, mp, res, payload, prm.norm_override, prm.levels, \
-                                                     prm.seed, prm.stream_id},                              \
+  return launch_cluster(DitherServerOp<EF, LINF, NW, NAT, WIDE>{g, cg, mp, res, payload, prm.norm_override, prm.levels, \
+                                                           prm.seed, prm.stream_id},                        \
                         cg, slots, status, stream, used)
   switch (mp.n) {
     case 4: BPC_DS(4);
     case 8: BPC_DS(8);
     case 16: BPC_DS(16);
-    default: BPC_DS(0);
+    default:
+      if constexpr (WIDE) {
+        *used = false;   // the wide form is built for 4, 8 and 16 workers; others take the passes
+        return hipSuccess;
+      } else {
+        BPC_DS(0);
+      }
   }
 #undef BPC_DS
 }
@@ -246,12 +307,19 @@ hipError_t dither_server_single_pass(const Geo &g, const bpc_params_t &prm, cons
   double *slots = ws.at<double>(ws.lay.slots);
   uint32_t *status = ws.at<uint32_t>(ws.lay.status);
   const bool linf = prm.norm == BPC_NORM_LINF, nat = prm.kind == BPC_NATDITHER;
+  const uint32_t planes = nat ? 0u : dither_planes(prm.levels);
+  if (planes > 1) {   // 6 and 7 bits: the multi-pass kernels
+    *used = false;
+    return hipSuccess;
+  }
 #define BPC_DSL(EF)                                                                                              \
   do {                                                                                                           \
-    if (linf && nat) return launch_dither_server<EF, true, true>(g, cg, prm, src, payload, slots, status, stream, used);   \
-    if (linf) return launch_dither_server<EF, true, false>(g, cg, prm, src, payload, slots, status, stream, used);         \
-    if (nat) return launch_dither_server<EF, false, true>(g, cg, prm, src, payload, slots, status, stream, used);          \
-    return launch_dither_server<EF, false, false>(g, cg, prm, src, payload, slots, status, stream, used);                  \
+    if (planes == 1 && linf) return launch_dither_server<EF, true, false, true>(g, cg, prm, src, payload, slots, status, stream, used);  \
+    if (planes == 1) return launch_dither_server<EF, false, false, true>(g, cg, prm, src, payload, slots, status, stream, used);         \
+    if (linf && nat) return launch_dither_server<EF, true, true, false>(g, cg, prm, src, payload, slots, status, stream, used);   \
+    if (linf) return launch_dither_server<EF, true, false, false>(g, cg, prm, src, payload, slots, status, stream, used);         \
+    if (nat) return launch_dither_server<EF, false, true, false>(g, cg, prm, src, payload, slots, status, stream, used);          \
+    return launch_dither_server<EF, false, false, false>(g, cg, prm, src, payload, slots, status, stream, used);                  \
   } while (0)
   if (src.residual) BPC_DSL(true);
   BPC_DSL(false);
