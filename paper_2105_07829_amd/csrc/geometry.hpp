@@ -21,6 +21,8 @@ constexpr int kSThreads = 256;       // workgroup size of the server-side kernel
 constexpr int kWTile = 16384;        // tile of the worker-side single-pass kernels (1024 threads x 16 elements)
 constexpr int kSTile = 8192;         // tile of the server-side single-pass kernels and of single-pass LANS
 constexpr uint32_t kHeaderBytes = 16;
+constexpr uint32_t kTopkListCap = 32768;  // entries of a partition's top-k short list
+constexpr uint32_t kTopkHistWords = 2048 + 1024 + 1024;  // top-k radix histograms of a partition
 
 BPC_HD inline uint64_t ru4(uint64_t x) { return (x + 3) / 4 * 4; }
 BPC_HD inline uint64_t cdiv(uint64_t a, uint64_t b) { return (a + b - 1) / b; }
@@ -113,8 +115,10 @@ inline Geo make_geo(const bpc_params_t *p, uint64_t D) {
 struct WsLayout {
   size_t partials;   // double[n_tiles]: per-tile partial norms
   size_t dense;      // float[D]: q / Delta / decoded message when no caller buffer can hold it
-  size_t hist;       // u32[P*4096]: top-k radix histograms (2048 + 1024 + 1024 bins)
+  size_t hist;       // u32[P*kTopkHistWords]: top-k radix histograms (2048 + 1024 + 1024 bins)
   size_t state;      // u32[P*8]: top-k selection state
+  size_t guess;      // u32[P]: top-k key from which elements go to a partition's short list
+  size_t cand;       // u32[P * kTopkListCap] indices, then as many value bits: top-k short lists of the partitions
   size_t tilecnt;    // u32[2*n_tiles]: per-tile (greater, equal) counts, then offsets
   size_t slots;      // double[3 * tiles of kSTile]: partition-wide reductions of the single-pass kernels
                      // (one per tile; three for the LANS block norms)
@@ -133,8 +137,10 @@ inline WsLayout ws_layout(const bpc_params_t *p, uint64_t D) {
   bool sparse = topk || p->kind == BPC_RANDK || (p->kind == BPC_DITHER && dither_planes(p->levels) > 0);
   w.partials = take(sizeof(double) * (size_t)g.n_tiles);
   w.dense = take(sparse ? sizeof(float) * (size_t)D : 0);
-  w.hist = take(topk ? sizeof(uint32_t) * 4096 * (size_t)g.P : 0);
+  w.hist = take(topk ? sizeof(uint32_t) * kTopkHistWords * (size_t)g.P : 0);
   w.state = take(topk ? sizeof(uint32_t) * 8 * (size_t)g.P : 0);
+  w.guess = take(topk ? sizeof(uint32_t) * (size_t)g.P : 0);
+  w.cand = take(topk ? 8 * (size_t)kTopkListCap * (size_t)g.P : 0);
   w.tilecnt = take(topk ? sizeof(uint32_t) * 2 * (size_t)g.n_tiles : 0);
   w.slots = take(sizeof(double) * 3 * ((size_t)g.P * cdiv(g.part_elems, kSTile)));
   w.status = take(256);

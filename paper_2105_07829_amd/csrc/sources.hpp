@@ -266,6 +266,23 @@ struct DenseSumSource {
     float mean = sum[i] * inv_n;
     return res ? mean + res[i] : mean;
   }
+  __device__ void at8(const Geo &g, uint32_t p, uint32_t j0, uint32_t d, const float *, float out[8]) const {
+    const uint64_t i0 = g.part_base(p) + j0;
+    if (j0 + 8 <= d) {
+      float x[8];
+      load8_aligned(sum + i0, x);
+      float r[8] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+      if (res) load8_aligned(res + i0, r);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float mean = x[e] * inv_n;
+        out[e] = res ? mean + r[e] : mean;
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) out[e] = j0 + e < d ? at(g, p, j0 + e, nullptr) : 0.0f;
+    }
+  }
 };
 
 // Run `fn(source)` with the source that matches `src` (worker f32 / f16 gradient, or the

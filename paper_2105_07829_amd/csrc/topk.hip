@@ -2,11 +2,27 @@
 // with the residual update of Algorithm 4 in its fused form (Section 4.2, operator fusion: the
 // residual is the vector itself with the k sent slots set to zero).
 //
-// Selection is an exact three-level radix select on the 31-bit magnitude key
-// bits(v) & 0x7fffffff (11 + 10 + 10 bits), followed by an ordered compaction in which
-// elements equal to the threshold key are admitted lowest index first.  Five passes:
-//   load+hist1 : v_j from the source -> dense buffer; histogram of key >> 20
-//   hist2      : bucket of level 1 that holds the k-th largest key, histogram inside it
+// Selection is exact: a three-level radix select on the 31-bit magnitude key
+// bits(v) & 0x7fffffff (11 + 10 + 10 bits); elements equal to the threshold key are admitted
+// lowest index first, and the record lists its entries by ascending index.
+//
+// Short-list form (k of a full partition at most half of kTopkListCap): one pass over the data.
+//   sample     : 4096 elements of each partition (512 evenly spread chunks of eight); the key G
+//                at a rank of the sample chosen so that, but for rare cases, at least k and
+//                at most about 2 k elements of the partition have keys >= G
+//   load+hist1 : v_j from the source -> dense buffer; histogram of key >> 20; the elements
+//                with key >= G go to the partition's short list
+//   select     : one workgroup per partition runs the radix select on the short list alone
+//                and writes the record; kept slots of the buffer zeroed
+// The sample only decides how much work the selection is, never its result: a partition whose
+// short list came out shorter than k or longer than kTopkListCap (the sample misled, or a
+// great many equal magnitudes, or fewer than k non-zeros) is taken by the long form below
+// instead, whose kernels are enqueued behind with a small grid and return at once if no
+// partition needs them.
+//
+// Long form, five passes over the dense buffer:
+//   load+hist1 : as above
+//   hist2      : bin of level 1 that holds the k-th largest key, histogram inside it
 //   hist3      : the same one level down
 //   count      : threshold key T and the number r of elements with key == T that are kept;
 //                per tile, how many keys are > T and == T
@@ -18,96 +34,282 @@
 namespace bpc {
 
 constexpr int kBins1 = 2048, kBins23 = 1024;
-constexpr int kHistPerPart = 4096;  // 2048 + 1024 + 1024
+constexpr int kHist1 = 0, kHist2 = kBins1, kHist3 = kHist2 + kBins23;
+static_assert(kHist3 + kBins23 == kTopkHistWords, "histogram words of a partition");
+constexpr int kShift1 = 20, kShift2 = 10;
+constexpr int kBits1 = 11, kBits23 = 10;
 // A workgroup of the histogram / count passes handles a few consecutive tiles of one partition
 // (template parameter TPG): its LDS histogram is merged into the partition's with one atomic
-// per non-empty bin, so more tiles a workgroup mean fewer of those (they were the larger part
-// of the level-2 pass), while fewer, longer workgroups hide less latency (8 tiles a workgroup
-// doubled the time of the passes that only read).
+// per non-empty bin, so more tiles a workgroup mean fewer of those (an atomic on global memory
+// costs some 11 ns of one memory channel's time; they were the larger part of the level-2
+// pass), while fewer, longer workgroups hide less latency (8 tiles a workgroup doubled the
+// time of the passes that only read).
 constexpr int kTpgLoad = 2, kTpgHist2 = 4, kTpgHist3 = 1, kTpgCount = 1;
+constexpr int kSelThreads = 1024;                       // workgroup of the select pass
+constexpr int kSelPer = kTopkListCap / kSelThreads;     // list entries a thread of it keeps
+constexpr uint32_t kGatedGrid = 1024;                   // grid of a long-form kernel that may have nothing to do
+constexpr int kSamplePer = 16;                          // sampled elements per thread of the sample pass
+constexpr uint32_t kSample = kThreads * kSamplePer;     // per partition: 4096
+constexpr uint32_t kNoGuess = 0xffffffffu;              // no key reaches it: nothing goes to the short list
 
 __device__ inline uint32_t key_of(float v) { return __float_as_uint(v) & 0x7fffffffu; }
 
-// state words per partition: words 2L, 2L + 1 hold (prefix, rank left) after level L = 1..3
+// state words per partition: words 2L, 2L + 1 hold (prefix, rank left) after level L = 1..3;
+// word 0 the length of the short list, word 1 non-zero if the partition is left to the long form
 enum { kStPrefix = 0, kStKRem = 1 };
+enum { kStListLen = 0, kStLong = 1 };
 
+// Whether partition p is left to the long form (uniform over the workgroup).
+__device__ inline bool long_form(const uint32_t *state, uint32_t p) {
+  return __builtin_amdgcn_readfirstlane(state[p * 8 + kStLong]) != 0;
+}
+
+// Group `blk` of TPG consecutive tiles of one partition.
 struct GroupOf {
   uint32_t p, tile_lo, tile_hi, d;
 };
 template <int TPG>
-__device__ inline GroupOf group_of(const Geo &g) {
+__device__ inline GroupOf group_of(const Geo &g, uint32_t blk) {
   constexpr uint32_t kTilesPerGroup = TPG;
   const uint32_t groups_per_part = (uint32_t)cdiv(g.tiles_per_part, kTilesPerGroup);
   GroupOf r;
-  r.p = blockIdx.x / groups_per_part;
+  r.p = blk / groups_per_part;
   r.d = g.part_size(r.p);
   const uint32_t n_tiles = (uint32_t)cdiv(r.d, kTile);
-  r.tile_lo = (blockIdx.x % groups_per_part) * kTilesPerGroup;
+  r.tile_lo = (blk % groups_per_part) * kTilesPerGroup;
   r.tile_hi = r.tile_lo + kTilesPerGroup < n_tiles ? r.tile_lo + kTilesPerGroup : n_tiles;
   return r;
 }
-inline uint32_t group_grid(const Geo &g, int tpg) { return g.P * (uint32_t)cdiv(g.tiles_per_part, tpg); }
+inline uint32_t group_count(const Geo &g, int tpg) { return g.P * (uint32_t)cdiv(g.tiles_per_part, tpg); }
 
-template <class SRC>
-__global__ __launch_bounds__(kThreads) void topk_load_hist1_kernel(Geo g, SRC src, float *buf, uint32_t *hist) {
-  __shared__ float lds[SRC::kLdsFloats];
-  __shared__ uint32_t h[kBins1];
-  const GroupOf w = group_of<kTpgLoad>(g);
-  for (int b = threadIdx.x; b < kBins1; b += kThreads) h[b] = 0;
-  src.begin(g, w.p, lds);
-  __syncthreads();
-  const uint64_t base = g.part_base(w.p);
-  for (uint32_t tile = w.tile_lo; tile < w.tile_hi; ++tile) {
-#pragma unroll
-    for (int c = 0; c < kTile / kThreads; ++c) {
-      uint32_t j = tile * kTile + c * kThreads + threadIdx.x;
-      if (j < w.d) {
-        float v = src.at(g, w.p, j, lds);
-        buf[base + j] = v;
-        atomicAdd(&h[key_of(v) >> 20], 1u);
-      }
-    }
-  }
-  __syncthreads();
-  uint32_t *gh = hist + (uint64_t)w.p * kHistPerPart;
-  for (int b = threadIdx.x; b < kBins1; b += kThreads)
-    if (h[b]) atomicAdd(&gh[b], h[b]);
-}
-
-// All threads of a workgroup: walk the level's histogram of partition p from the highest bin
-// down and find the bin b with  count(bins above b) < k_rem <= count(bins above b) + count(b).
-// Returns the extended prefix and the rank left inside that bin through `sel` (LDS, 2 words).
+// All threads of a workgroup of THREADS: walk a histogram `h` of BINS bins (global or LDS)
+// from the highest bin down and find the bin b with
+//   count(bins above b) < k_rem <= count(bins above b) + count(b).
+// sel[0] = (prefix << BITS) | b (the extended prefix), sel[1] = the rank left inside b.
 // Every workgroup of the pass that follows a histogram pass does this for itself (a few
 // microseconds of L2 reads) instead of a launch of its own in between.
-template <int LEVEL>
-__device__ inline void pick_bin(const uint32_t *hist, uint32_t p, uint32_t k_rem, uint32_t prefix, uint32_t *scan,
-                                uint32_t *sel) {
-  constexpr int kBins = LEVEL == 1 ? kBins1 : kBins23;
-  constexpr int kPer = kBins / kThreads;
-  const uint32_t *gh = hist + (uint64_t)p * kHistPerPart + (LEVEL == 1 ? 0 : LEVEL == 2 ? kBins1 : kBins1 + kBins23);
-  // thread t owns bins [kBins-1 - t*kPer - (kPer-1), kBins-1 - t*kPer], highest first
+template <int BINS, int BITS, int THREADS>
+__device__ inline void pick_bin(const uint32_t *h, uint32_t k_rem, uint32_t prefix, uint32_t *scan, uint32_t *sel) {
+  constexpr int kPer = BINS / THREADS > 0 ? BINS / THREADS : 1;
+  // thread t owns bins BINS-1 - t*kPer - i, highest first; threads past the bins own none
   uint32_t cnt[kPer];
   uint32_t local = 0;
 #pragma unroll
   for (int i = 0; i < kPer; ++i) {
-    cnt[i] = gh[kBins - 1 - (threadIdx.x * kPer + i)];
+    const uint32_t b = threadIdx.x * kPer + i;
+    cnt[i] = b < (uint32_t)BINS ? h[BINS - 1 - b] : 0u;
     local += cnt[i];
   }
   uint32_t total;
-  uint32_t above = block_exclusive_scan<kThreads>(local, scan, &total);
+  const uint32_t above = block_exclusive_scan<THREADS>(local, scan, &total);
   if (above < k_rem && k_rem <= above + local) {
     uint32_t run = above;
 #pragma unroll
     for (int i = 0; i < kPer; ++i) {
       if (run < k_rem && k_rem <= run + cnt[i]) {
-        uint32_t bin = kBins - 1 - (threadIdx.x * kPer + i);
-        sel[0] = LEVEL == 1 ? bin : ((prefix << 10) | bin);
+        sel[0] = (prefix << BITS) | (BINS - 1 - (threadIdx.x * kPer + i));
         sel[1] = k_rem - run;
       }
       run += cnt[i];
     }
   }
   __syncthreads();
+}
+
+// Radix select, inside one workgroup of THREADS, among the keys of the values the threads hold
+// in registers (the low 31 bits of bits[i], i < cnt <= rounds, `rounds` the same for all
+// threads).  h: LDS, kBins1 words.
+// Level 1: the level-1 bin of the key of rank `rank` (1 = the largest) in sel[0], the rank left
+// inside it in sel[1].
+template <int PER, int THREADS>
+__device__ inline void level1_in_registers(const uint32_t (&bits)[PER], uint32_t cnt, uint32_t rounds, uint32_t rank,
+                                           uint32_t *h, uint32_t *scan, uint32_t *sel) {
+  for (int b = threadIdx.x; b < kBins1; b += THREADS) h[b] = 0;
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    if ((uint32_t)i >= rounds) break;
+    if ((uint32_t)i < cnt) atomicAdd(&h[(bits[i] & 0x7fffffffu) >> kShift1], 1u);
+  }
+  __syncthreads();
+  pick_bin<kBins1, kBits1, THREADS>(h, rank, 0, scan, sel);
+}
+// Levels 2 and 3, given level 1's (b1, k_rem1): the key in sel[0], the rank left among the keys
+// equal to it in sel[1].
+template <int PER, int THREADS>
+__device__ inline void levels23_in_registers(const uint32_t (&bits)[PER], uint32_t cnt, uint32_t rounds, uint32_t b1,
+                                             uint32_t k_rem1, uint32_t *h, uint32_t *scan, uint32_t *sel) {
+  for (int b = threadIdx.x; b < kBins23; b += THREADS) h[b] = 0;
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    if ((uint32_t)i >= rounds) break;
+    const uint32_t key = bits[i] & 0x7fffffffu;
+    if ((uint32_t)i < cnt && (key >> kShift1) == b1) atomicAdd(&h[(key >> kShift2) & (kBins23 - 1)], 1u);
+  }
+  __syncthreads();
+  pick_bin<kBins23, kBits23, THREADS>(h, k_rem1, b1, scan, sel);
+  const uint32_t prefix2 = sel[0], k_rem2 = sel[1];
+  __syncthreads();
+  for (int b = threadIdx.x; b < kBins23; b += THREADS) h[b] = 0;
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    if ((uint32_t)i >= rounds) break;
+    const uint32_t key = bits[i] & 0x7fffffffu;
+    if ((uint32_t)i < cnt && (key >> kShift2) == prefix2) atomicAdd(&h[key & (kBins23 - 1)], 1u);
+  }
+  __syncthreads();
+  pick_bin<kBins23, kBits23, THREADS>(h, k_rem2, prefix2, scan, sel);
+}
+
+// Chunk (of eight consecutive elements) number c of the sample of a partition sampled every
+// `stride` chunks: one of the c-th stretch of `stride` chunks, at a place that moves from
+// stretch to stretch (chunks at equal distances of a power of two would all come from the same
+// few memory channels).
+__device__ inline uint32_t sample_chunk(uint32_t c, uint32_t stride) { return c * stride + (c * 37u) % stride; }
+
+// Zeroes the histograms and the state words; with `sample`, workgroup p < P also works out
+// partition p's guess G from a sample of 512 chunks of eight consecutive elements (else the
+// guess is "none").  Random 64-byte reads cost about as much as 16 times as many sequential
+// ones, hence chunks rather than single elements.
+template <class SRC>
+__global__ __launch_bounds__(kThreads) void topk_sample_kernel(Geo g, SRC src, uint32_t *hist, uint32_t *state,
+                                                               uint32_t *guess, int sample) {
+  __shared__ float lds[SRC::kLdsFloats];
+  __shared__ uint32_t h[kBins1];
+  __shared__ uint32_t scan[kThreads];
+  __shared__ uint32_t sel[2];
+  {
+    const size_t i0 = (size_t)blockIdx.x * kThreads + threadIdx.x, step = (size_t)gridDim.x * kThreads;
+    uint4 *h16 = reinterpret_cast<uint4 *>(hist);
+    for (size_t q = i0; q < (size_t)kTopkHistWords * g.P / 4; q += step) h16[q] = make_uint4(0, 0, 0, 0);
+    for (size_t q = i0; q < 8ull * g.P; q += step) state[q] = 0;
+  }
+  const uint32_t p = blockIdx.x;
+  if (p >= g.P) return;
+  if (!sample) {
+    if (threadIdx.x == 0) guess[p] = kNoGuess;
+    return;
+  }
+  src.begin(g, p, lds);
+  __syncthreads();
+  static_assert(kSamplePer % 8 == 0, "whole chunks");
+  constexpr uint32_t kChunksPer = kSamplePer / 8, kChunks = kSample / 8;
+  const uint32_t d = g.part_size(p);
+  const uint32_t chunks = d / 8 < kChunks ? d / 8 : kChunks;   // chunks in the sample (whole chunks of the partition only)
+  const uint32_t m = 8 * chunks;                              // elements in the sample
+  // rank in the sample: the expected rank of the partition's k-th largest, four standard
+  // deviations of a count of twice that size further down (neighbours are not independent),
+  // and a little more
+  const double expect = (double)k_of_device(g, p) * (double)m / (double)d;
+  const uint32_t rank = (uint32_t)(expect + 4.0 * sqrt(2.0 * expect) + 3.0);
+  if (rank >= m) {   // (uniform) the whole partition would be listed
+    if (threadIdx.x == 0) guess[p] = 0;
+    return;
+  }
+  const uint32_t stride = (d / 8) / chunks;
+  uint32_t key[kSamplePer];
+  uint32_t cnt = 0;
+  // (every load is issued, with chunk 0 standing in past the end, so that none is waited for
+  // before the last is on its way)
+#pragma unroll
+  for (uint32_t i = 0; i < kChunksPer; ++i) {
+    const uint32_t c = i * kThreads + threadIdx.x;
+    float v[8];
+    source_at8(src, g, p, 8 * sample_chunk(c < chunks ? c : 0u, stride), d, lds, v);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) key[8 * i + e] = key_of(v[e]);
+    cnt += c < chunks ? 8 : 0;
+  }
+  level1_in_registers<kSamplePer, kThreads>(key, cnt, kSamplePer, rank, h, scan, sel);
+  const uint32_t b1 = sel[0], k_rem1 = sel[1];
+  __syncthreads();
+  levels23_in_registers<kSamplePer, kThreads>(key, cnt, kSamplePer, b1, k_rem1, h, scan, sel);
+  if (threadIdx.x == 0) guess[p] = sel[0];
+}
+
+// Load pass.  Besides the buffer and the histogram: the elements of the workgroup's tiles whose
+// key is at least the partition's guess go to its short list, together and in index order, at
+// the place one atomic add on the list length hands out; place and count are recorded per
+// group of tiles, so the select pass can walk the list in index order whatever order the
+// groups arrived in.
+template <class SRC>
+__global__ __launch_bounds__(kThreads) void topk_load_hist1_kernel(Geo g, SRC src, float *buf, uint32_t *hist, uint32_t *state,
+                                                                   const uint32_t *guess, uint32_t *groupcnt,
+                                                                   uint32_t *cand_idx, uint32_t *cand_val) {
+  __shared__ float lds[SRC::kLdsFloats];
+  __shared__ uint32_t h[kBins1];
+  __shared__ uint32_t scan[kThreads];
+  __shared__ uint32_t off_sh;
+  constexpr int kPieces = kTpgLoad * (kTile / (kThreads * 8));  // pieces of kThreads * 8 elements: 4
+  static_assert(kPieces == 4, "two scans of two 16-bit counts");
+  const GroupOf w = group_of<kTpgLoad>(g, blockIdx.x);
+  for (int b = threadIdx.x; b < kBins1; b += kThreads) h[b] = 0;
+  src.begin(g, w.p, lds);
+  __syncthreads();
+  if (w.tile_lo >= w.tile_hi) return;  // (uniform) past the end of a shorter last partition
+  const uint32_t G = guess[w.p];
+  const uint64_t base = g.part_base(w.p);
+  float v[kPieces][8];
+  uint32_t mask[kPieces];
+#pragma unroll
+  for (int c = 0; c < kPieces; ++c) {
+    const uint32_t j0 = w.tile_lo * kTile + c * (kThreads * 8) + threadIdx.x * 8;
+    mask[c] = 0;
+    if (j0 >= w.d) continue;
+    source_at8(src, g, w.p, j0, w.d, lds, v[c]);
+    if (j0 + 8 <= w.d) {
+      float4 *dst = reinterpret_cast<float4 *>(buf + base + j0);
+      dst[0] = make_float4(v[c][0], v[c][1], v[c][2], v[c][3]);
+      dst[1] = make_float4(v[c][4], v[c][5], v[c][6], v[c][7]);
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      if (j0 + e < w.d) {
+        if (j0 + 8 > w.d) buf[base + j0 + e] = v[c][e];
+        const uint32_t key = key_of(v[c][e]);
+        atomicAdd(&h[key >> kShift1], 1u);
+        mask[c] |= (uint32_t)(key >= G) << e;
+      }
+    }
+  }
+  if (G != kNoGuess) {
+    // positions in the group's run: pieces in order, threads in order within a piece
+    uint32_t tot01, tot23;
+    const uint32_t ex01 = block_exclusive_scan<kThreads>(__builtin_popcount(mask[0]) | (__builtin_popcount(mask[1]) << 16), scan, &tot01);
+    const uint32_t ex23 = block_exclusive_scan<kThreads>(__builtin_popcount(mask[2]) | (__builtin_popcount(mask[3]) << 16), scan, &tot23);
+    const uint32_t t0 = tot01 & 0xffffu, t1 = tot01 >> 16, t2 = tot23 & 0xffffu, t3 = tot23 >> 16;
+    const uint32_t total = t0 + t1 + t2 + t3;
+    if (threadIdx.x == 0) {
+      const uint32_t off = total ? atomicAdd(&state[w.p * 8 + kStListLen], total) : 0u;
+      off_sh = off;
+      groupcnt[2 * blockIdx.x] = off;
+      groupcnt[2 * blockIdx.x + 1] = total;
+    }
+    __syncthreads();
+    const uint32_t first[kPieces] = {ex01 & 0xffffu, t0 + (ex01 >> 16), t0 + t1 + (ex23 & 0xffffu), t0 + t1 + t2 + (ex23 >> 16)};
+    const uint64_t list = (uint64_t)w.p * kTopkListCap;
+#pragma unroll
+    for (int c = 0; c < kPieces; ++c) {
+      uint32_t pos = off_sh + first[c];
+      const uint32_t j0 = w.tile_lo * kTile + c * (kThreads * 8) + threadIdx.x * 8;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        if ((mask[c] >> e) & 1u) {
+          if (pos < kTopkListCap) {
+            cand_idx[list + pos] = j0 + e;
+            cand_val[list + pos] = __float_as_uint(v[c][e]);
+          }
+          ++pos;
+        }
+      }
+    }
+  }
+  __syncthreads();
+  uint32_t *gh = hist + (uint64_t)w.p * kTopkHistWords + kHist1;
+  for (int b = threadIdx.x; b < kBins1; b += kThreads)
+    if (h[b]) atomicAdd(&gh[b], h[b]);
 }
 
 // The selection state of partition p after `LEVEL` levels in sel[0] (prefix / threshold key)
@@ -117,8 +319,10 @@ __device__ inline void pick_bin(const uint32_t *hist, uint32_t p, uint32_t k_rem
 template <int LEVEL>
 __device__ inline void selection_after(const Geo &g, const uint32_t *hist, uint32_t *state, uint32_t p, bool first,
                                        uint32_t *scan, uint32_t *sel) {
-  if (LEVEL == 1) pick_bin<1>(hist, p, (uint32_t)k_of_device(g, p), 0, scan, sel);
-  else pick_bin<LEVEL>(hist, p, state[p * 8 + 2 * (LEVEL - 1) + kStKRem], state[p * 8 + 2 * (LEVEL - 1) + kStPrefix], scan, sel);
+  const uint32_t *gh = hist + (uint64_t)p * kTopkHistWords;
+  if (LEVEL == 1) pick_bin<kBins1, kBits1, kThreads>(gh + kHist1, (uint32_t)k_of_device(g, p), 0, scan, sel);
+  else pick_bin<kBins23, kBits23, kThreads>(gh + (LEVEL == 2 ? kHist2 : kHist3), state[p * 8 + 2 * (LEVEL - 1) + kStKRem],
+                                            state[p * 8 + 2 * (LEVEL - 1) + kStPrefix], scan, sel);
   // (state words 2L, 2L+1 hold the selection after level L; nobody reads the words this pass writes)
   if (first && threadIdx.x == 0) {
     state[p * 8 + 2 * LEVEL + kStPrefix] = sel[0];
@@ -140,178 +344,350 @@ __device__ inline void keys4(const float *part, uint32_t j, uint32_t d, uint32_t
   }
 }
 
+// The long-form kernels take their groups of tiles in a loop, so that they can be launched with
+// a small grid behind the short-list form (`gated`: only partitions left to the long form).
+
 // LEVEL 2: keys whose top 11 bits equal the prefix, histogram of the next 10 bits.
 // LEVEL 3: keys whose top 21 bits equal the prefix, histogram of the last 10 bits.
 template <int LEVEL>
-__global__ __launch_bounds__(kThreads) void topk_hist_kernel(Geo g, const float *buf, uint32_t *hist, uint32_t *state) {
+__global__ __launch_bounds__(kThreads) void topk_hist_kernel(Geo g, const float *buf, uint32_t *hist, uint32_t *state,
+                                                             uint32_t n_groups, int gated) {
   __shared__ uint32_t h[kBins23];
   __shared__ uint32_t scan[kThreads];
   __shared__ uint32_t sel[2];
-  const GroupOf w = group_of<LEVEL == 2 ? kTpgHist2 : kTpgHist3>(g);
-  for (int b = threadIdx.x; b < kBins23; b += kThreads) h[b] = 0;
-  selection_after<LEVEL - 1>(g, hist, state, w.p, w.tile_lo == 0, scan, sel);
-  const uint32_t prefix = sel[0];
-  constexpr int kHiShift = LEVEL == 2 ? 20 : 10;
-  constexpr int kLoShift = LEVEL == 2 ? 10 : 0;
-  const float *part = buf + g.part_base(w.p);
-  for (uint32_t tile = w.tile_lo; tile < w.tile_hi; ++tile) {
+  for (uint32_t blk = blockIdx.x; blk < n_groups; blk += gridDim.x) {
+    const GroupOf w = group_of<LEVEL == 2 ? kTpgHist2 : kTpgHist3>(g, blk);
+    if (gated && !long_form(state, w.p)) continue;
+    for (int b = threadIdx.x; b < kBins23; b += kThreads) h[b] = 0;
+    selection_after<LEVEL - 1>(g, hist, state, w.p, w.tile_lo == 0, scan, sel);
+    const uint32_t prefix = sel[0];
+    constexpr int kHiShift = LEVEL == 2 ? kShift1 : kShift2;
+    constexpr int kLoShift = LEVEL == 2 ? kShift2 : 0;
+    const float *part = buf + g.part_base(w.p);
+    for (uint32_t tile = w.tile_lo; tile < w.tile_hi; ++tile) {
 #pragma unroll
-    for (int c = 0; c < kTile / (kThreads * 4); ++c) {
-      uint32_t key[4], n;
-      keys4(part, tile * kTile + c * (kThreads * 4) + threadIdx.x * 4, w.d, key, &n);
+      for (int c = 0; c < kTile / (kThreads * 4); ++c) {
+        uint32_t key[4], n;
+        keys4(part, tile * kTile + c * (kThreads * 4) + threadIdx.x * 4, w.d, key, &n);
 #pragma unroll
-      for (int e = 0; e < 4; ++e)
-        if ((uint32_t)e < n && (key[e] >> kHiShift) == prefix) atomicAdd(&h[(key[e] >> kLoShift) & 1023u], 1u);
+        for (int e = 0; e < 4; ++e)
+          if ((uint32_t)e < n && (key[e] >> kHiShift) == prefix) atomicAdd(&h[(key[e] >> kLoShift) & (kBins23 - 1)], 1u);
+      }
     }
+    __syncthreads();
+    uint32_t *gh = hist + (uint64_t)w.p * kTopkHistWords + (LEVEL == 2 ? kHist2 : kHist3);
+    for (int b = threadIdx.x; b < kBins23; b += kThreads)
+      if (h[b]) atomicAdd(&gh[b], h[b]);
+    __syncthreads();
   }
-  __syncthreads();
-  uint32_t *gh = hist + (uint64_t)w.p * kHistPerPart + (LEVEL == 2 ? kBins1 : kBins1 + kBins23);
-  for (int b = threadIdx.x; b < kBins23; b += kThreads)
-    if (h[b]) atomicAdd(&gh[b], h[b]);
 }
 
 // Per tile: number of keys above the threshold and equal to it.  The first workgroup of a
 // partition also records the threshold key T and the number r of keys equal to T that are
 // kept, for the compaction.
 __global__ __launch_bounds__(kThreads) void topk_count_kernel(Geo g, const float *buf, const uint32_t *hist,
-                                                              uint32_t *state, uint32_t *tilecnt) {
+                                                              uint32_t *state, uint32_t *tilecnt, uint32_t n_groups,
+                                                              int gated) {
   __shared__ uint32_t red[2][kThreads / 64];
   __shared__ uint32_t scan[kThreads];
   __shared__ uint32_t sel[2];
-  const GroupOf w = group_of<kTpgCount>(g);
-  selection_after<3>(g, hist, state, w.p, w.tile_lo == 0, scan, sel);
-  const uint32_t T = sel[0];
-  const float *part = buf + g.part_base(w.p);
-  for (uint32_t tile = w.tile_lo; tile < w.tile_hi; ++tile) {
-    uint32_t n_gt = 0, n_eq = 0;
+  for (uint32_t blk = blockIdx.x; blk < n_groups; blk += gridDim.x) {
+    const GroupOf w = group_of<kTpgCount>(g, blk);
+    if (gated && !long_form(state, w.p)) continue;
+    selection_after<3>(g, hist, state, w.p, w.tile_lo == 0, scan, sel);
+    const uint32_t T = sel[0];
+    const float *part = buf + g.part_base(w.p);
+    for (uint32_t tile = w.tile_lo; tile < w.tile_hi; ++tile) {
+      uint32_t n_gt = 0, n_eq = 0;
 #pragma unroll
-    for (int c = 0; c < kTile / (kThreads * 4); ++c) {
-      uint32_t key[4], n;
-      keys4(part, tile * kTile + c * (kThreads * 4) + threadIdx.x * 4, w.d, key, &n);
+      for (int c = 0; c < kTile / (kThreads * 4); ++c) {
+        uint32_t key[4], n;
+        keys4(part, tile * kTile + c * (kThreads * 4) + threadIdx.x * 4, w.d, key, &n);
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        n_gt += (uint32_t)e < n && key[e] > T;
-        n_eq += (uint32_t)e < n && key[e] == T;
+        for (int e = 0; e < 4; ++e) {
+          n_gt += (uint32_t)e < n && key[e] > T;
+          n_eq += (uint32_t)e < n && key[e] == T;
+        }
+      }
+      n_gt = wave_sum_u32(n_gt);
+      n_eq = wave_sum_u32(n_eq);
+      __syncthreads();
+      if ((threadIdx.x & 63) == 0) {
+        red[0][threadIdx.x >> 6] = n_gt;
+        red[1][threadIdx.x >> 6] = n_eq;
+      }
+      __syncthreads();
+      if (threadIdx.x == 0) {
+        uint32_t a = 0, b = 0;
+        for (int v = 0; v < kThreads / 64; ++v) { a += red[0][v]; b += red[1][v]; }
+        const uint64_t t = (uint64_t)w.p * g.tiles_per_part + tile;
+        tilecnt[2 * t] = a;
+        tilecnt[2 * t + 1] = b;
       }
     }
-    n_gt = wave_sum_u32(n_gt);
-    n_eq = wave_sum_u32(n_eq);
     __syncthreads();
-    if ((threadIdx.x & 63) == 0) {
-      red[0][threadIdx.x >> 6] = n_gt;
-      red[1][threadIdx.x >> 6] = n_eq;
-    }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-      uint32_t a = 0, b = 0;
-      for (int v = 0; v < kThreads / 64; ++v) { a += red[0][v]; b += red[1][v]; }
-      const uint64_t t = (uint64_t)w.p * g.tiles_per_part + tile;
-      tilecnt[2 * t] = a;
-      tilecnt[2 * t + 1] = b;
-    }
   }
 }
 
-// Ordered compaction.  Thread t of a tile owns 16 consecutive elements, so positions follow
-// from an exclusive scan over threads, on top of the counts of the partition's earlier tiles
-// (at most a few hundred numbers, summed by every workgroup for itself).  The workgroup of
-// the first tile writes the record's header.
+// Header of partition p's record; for the half-value form also the zeros the format wants from
+// value k to the end of its last group of four words.
+template <bool HALF>
+__device__ inline void topk_write_header(const Geo &g, uint32_t p, uint8_t *payload) {
+  uint8_t *rec0 = payload + (uint64_t)p * g.stride;
+  uint32_t *hdr = reinterpret_cast<uint32_t *>(rec0);
+  const uint32_t k = (uint32_t)k_of_device(g, p);
+  hdr[0] = k;
+  hdr[1] = 0; hdr[2] = 0; hdr[3] = 0;
+  if (HALF) {
+    uint16_t *val16 = reinterpret_cast<uint16_t *>(rec0 + kHeaderBytes + 4 * ru4(g.k_cap));
+    for (uint32_t t = k; t < 2 * (uint32_t)ru4(cdiv(k, 2)); ++t) val16[t] = 0;
+  }
+}
+
+// Entry `pos` of partition p's record: element j with value v; the buffer keeps 0 there, or
+// what rounding to half dropped.
+template <bool HALF>
+__device__ inline void topk_write_entry(const Geo &g, uint8_t *rec, uint32_t pos, uint32_t j, float v, float *buf_part,
+                                        int zero_selected) {
+  uint32_t *idx = reinterpret_cast<uint32_t *>(rec + kHeaderBytes);
+  float *val = reinterpret_cast<float *>(rec + kHeaderBytes + 4 * ru4(g.k_cap));
+  idx[pos] = j;
+  if (HALF) {
+    const __half h = __float2half_rn(v);
+    reinterpret_cast<__half *>(val)[pos] = h;
+    if (zero_selected) buf_part[j] = v - __half2float(h);
+  } else {
+    val[pos] = v;
+    if (zero_selected) buf_part[j] = 0.0f;
+  }
+}
+
+// Select pass: the radix select on the short list of one partition, then the record.  The list
+// in index order is the groups' runs in group order.  Wave w owns a stretch of consecutive
+// entries of that order, lane l of it the entries l, l + 64, ... of the stretch (neighbouring
+// lanes read neighbouring words), and keeps their values in registers throughout; positions in
+// the record follow from the counts of the waves before, of the rounds before and of the lanes
+// before.  A list shorter than k or longer than its room leaves the partition to the long form.
+template <bool HALF>
+__global__ __launch_bounds__(kSelThreads) void topk_list_select_kernel(Geo g, float *buf, uint32_t *state,
+                                                                       const uint32_t *hist, const uint32_t *groupcnt,
+                                                                       const uint32_t *cand_idx, const uint32_t *cand_val,
+                                                                       uint8_t *payload, int zero_selected) {
+  constexpr int kWaves = kSelThreads / 64;
+  __shared__ uint32_t h[kBins23];
+  __shared__ uint32_t vstart[kSelThreads + 1];  // entries of the list before group t's run
+  __shared__ uint32_t goff[kSelThreads];        // where group t's run sits in the list
+  __shared__ uint32_t scan[kWaves];
+  __shared__ uint32_t sel[2];
+  __shared__ uint32_t wave_gt[kWaves], wave_eq[kWaves];
+  const uint32_t p = blockIdx.x;
+  const uint32_t n = __builtin_amdgcn_readfirstlane(state[p * 8 + kStListLen]);
+  const uint32_t k = (uint32_t)k_of_device(g, p);
+  if (n < k || n > kTopkListCap) {
+    if (threadIdx.x == 0) state[p * 8 + kStLong] = 1;
+    return;
+  }
+  const uint32_t groups_per_part = (uint32_t)cdiv(g.tiles_per_part, kTpgLoad);            // at most kSelThreads
+  const uint32_t n_groups_p = (uint32_t)cdiv(cdiv(g.part_size(p), kTile), kTpgLoad);
+  {
+    const uint64_t t = (uint64_t)p * groups_per_part + threadIdx.x;
+    const uint32_t c = threadIdx.x < n_groups_p ? groupcnt[2 * t + 1] : 0u;
+    goff[threadIdx.x] = threadIdx.x < n_groups_p ? groupcnt[2 * t] : 0u;
+    uint32_t total;
+    vstart[threadIdx.x] = block_exclusive_scan<kSelThreads>(c, scan, &total);
+    if (threadIdx.x == 0) vstart[kSelThreads] = n;
+  }
+  __syncthreads();
+  const uint32_t rounds = (uint32_t)cdiv(n, kSelThreads);  // at most kSelPer
+  const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const uint32_t first = wave * rounds * 64 + lane;        // the thread's entries: first + 64 i, i < rounds
+  const uint32_t cnt = first < n ? (uint32_t)cdiv(n - first, 64) < rounds ? (uint32_t)cdiv(n - first, 64) : rounds : 0u;
+  // the group whose run holds the first entry: the last one that starts at or before it
+  uint32_t group0 = 0;
+  if (cnt) {
+    uint32_t a = 0, b = kSelThreads;  // vstart[a] <= first < vstart[b] (vstart[kSelThreads] = n > first)
+    while (b - a > 1) {
+      const uint32_t m = (a + b) >> 1;
+      if (vstart[m] <= first) a = m; else b = m;
+    }
+    group0 = a;
+  }
+  const uint64_t list = (uint64_t)p * kTopkListCap;
+  // Place in the list of an entry of the order.  The run of the current group is kept in
+  // registers; LDS is read only when the walk crosses into a later group.
+  struct Walk {
+    uint32_t group, begin, end, off;  // entries [begin, end) of the order sit at off..
+  };
+  auto walk_to = [&](Walk &w, uint32_t entry) {
+    while (entry >= w.end) {
+      ++w.group;
+      w.begin = w.end;
+      w.end = vstart[w.group + 1];
+      w.off = goff[w.group];
+    }
+    return w.off + (entry - w.begin);
+  };
+  const Walk walk0{group0, vstart[group0], vstart[group0 + 1], goff[group0]};
+  // every load is issued whether or not the entry exists (entry 0 of the list stands in), so
+  // none of them is waited for before the last is on its way
+  uint32_t bits[kSelPer];
+  auto key = [&](int i) { return bits[i] & 0x7fffffffu; };
+  {
+    Walk w = walk0;
+#pragma unroll
+    for (int i = 0; i < kSelPer; ++i) {
+      bits[i] = 0;
+      if ((uint32_t)i >= rounds) continue;   // (the same for all threads)
+      const uint32_t at = (uint32_t)i < cnt ? walk_to(w, first + 64 * i) : 0u;
+      bits[i] = cand_val[list + at];
+    }
+  }
+  // level 1 is known from the histogram of the whole partition
+  pick_bin<kBins1, kBits1, kSelThreads>(hist + (uint64_t)p * kTopkHistWords + kHist1, k, 0, scan, sel);
+  const uint32_t b1 = sel[0], k_rem1 = sel[1];
+  __syncthreads();
+  levels23_in_registers<kSelPer, kSelThreads>(bits, cnt, rounds, b1, k_rem1, h, scan, sel);
+  const uint32_t T = sel[0], r = sel[1];
+  if (threadIdx.x == 0) topk_write_header<HALF>(g, p, payload);
+  // keys above T and equal to T in the waves before this one
+  {
+    uint32_t n_gt = 0, n_eq = 0;
+#pragma unroll
+    for (int i = 0; i < kSelPer; ++i) {
+      if ((uint32_t)i >= rounds) break;
+      n_gt += (uint32_t)i < cnt && key(i) > T;
+      n_eq += (uint32_t)i < cnt && key(i) == T;
+    }
+    n_gt = wave_sum_u32(n_gt);
+    n_eq = wave_sum_u32(n_eq);
+    if (lane == 0) { wave_gt[wave] = n_gt; wave_eq[wave] = n_eq; }
+  }
+  __syncthreads();
+  uint32_t gt_base = 0, eq_base = 0;
+#pragma unroll
+  for (int v = 0; v < kWaves; ++v) {
+    gt_base += (uint32_t)v < wave ? wave_gt[v] : 0u;
+    eq_base += (uint32_t)v < wave ? wave_eq[v] : 0u;
+  }
+  uint8_t *rec = payload + (uint64_t)p * g.stride;
+  float *buf_part = buf + g.part_base(p);
+  const uint64_t lanes_before = (1ull << lane) - 1ull;
+  // 16 rounds at a time: which entries are kept and where they go, the loads of their indices
+  // (entry 0 of the list stands in for an entry that is not kept), then the stores
+  constexpr int kChunk = 16;
+  Walk w = walk0;
+#pragma unroll
+  for (int c = 0; c < kSelPer / kChunk; ++c) {
+    if ((uint32_t)(kChunk * c) >= rounds) break;
+    uint32_t j[kChunk], pos[kChunk];
+    uint32_t take = 0;
+#pragma unroll
+    for (int e = 0; e < kChunk; ++e) {
+      const int i = kChunk * c + e;
+      j[e] = 0; pos[e] = 0;
+      if ((uint32_t)i >= rounds) continue;   // (the same for all threads)
+      const bool valid = (uint32_t)i < cnt;
+      const uint64_t gtm = __ballot(valid && key(i) > T), eqm = __ballot(valid && key(i) == T);
+      const uint32_t gt_before = gt_base + __popcll(gtm & lanes_before);
+      const uint32_t eq_before = eq_base + __popcll(eqm & lanes_before);
+      const bool t = valid && (key(i) > T || (key(i) == T && eq_before < r));
+      take |= (uint32_t)t << e;
+      pos[e] = gt_before + (eq_before < r ? eq_before : r);
+      gt_base += __popcll(gtm);
+      eq_base += __popcll(eqm);
+      const uint32_t at = t ? walk_to(w, first + 64 * i) : 0u;
+      j[e] = cand_idx[list + at];
+    }
+#pragma unroll
+    for (int e = 0; e < kChunk; ++e)
+      if ((take >> e) & 1u)
+        topk_write_entry<HALF>(g, rec, pos[e], j[e], __uint_as_float(bits[kChunk * c + e]), buf_part, zero_selected);
+  }
+}
+
+// Ordered compaction of the long form.  Thread t of a tile owns 16 consecutive elements, so
+// positions follow from an exclusive scan over threads, on top of the counts of the partition's
+// earlier tiles (at most a few hundred numbers, summed by every workgroup for itself).  The
+// workgroup of the first tile writes the record's header.
 // HALF: values are sent as halves (round to nearest even) and a kept slot of the buffer keeps
 // what the rounding dropped instead of 0.
 template <bool HALF>
 __global__ __launch_bounds__(kThreads) void topk_emit_kernel(Geo g, float *buf, const uint32_t *state,
                                                              const uint32_t *tilecnt, uint8_t *payload,
-                                                             int zero_selected) {
+                                                             int zero_selected, uint32_t n_items, int gated) {
   __shared__ uint32_t scan[kThreads];
-  constexpr int kPer = kTile / kThreads;
-  const uint32_t p = blockIdx.x / g.tiles_per_part;
-  const uint32_t tile = blockIdx.x % g.tiles_per_part;
-  const uint32_t d = g.part_size(p);
-  const uint32_t T = state[p * 8 + 6 + kStPrefix];   // the selection after level 3
-  const uint32_t r = state[p * 8 + 6 + kStKRem];
   __shared__ uint32_t before[2][kThreads / 64];
-  {
-    const uint32_t *tc = tilecnt + 2ull * p * g.tiles_per_part;
-    uint32_t a = 0, b = 0;
-    for (uint32_t t = threadIdx.x; t < tile; t += kThreads) { a += tc[2 * t]; b += tc[2 * t + 1]; }
-    a = wave_sum_u32(a);
-    b = wave_sum_u32(b);
-    if ((threadIdx.x & 63) == 0) { before[0][threadIdx.x >> 6] = a; before[1][threadIdx.x >> 6] = b; }
-    __syncthreads();
-  }
-  uint32_t gt_before = 0, eq_before = 0;
-#pragma unroll
-  for (int w = 0; w < kThreads / 64; ++w) { gt_before += before[0][w]; eq_before += before[1][w]; }
-  if (tile == 0 && threadIdx.x == 0) {
-    uint8_t *rec0 = payload + (uint64_t)p * g.stride;
-    uint32_t *hdr = reinterpret_cast<uint32_t *>(rec0);
-    const uint32_t k = (uint32_t)k_of_device(g, p);
-    hdr[0] = k;
-    hdr[1] = 0; hdr[2] = 0; hdr[3] = 0;
-    if (HALF) {
-      // the format wants zeros from value k to the end of its last group of four words
-      // (values 0..k-1 are written below, by whichever tiles hold them)
-      uint16_t *val16 = reinterpret_cast<uint16_t *>(rec0 + kHeaderBytes + 4 * ru4(g.k_cap));
-      for (uint32_t t = k; t < 2 * (uint32_t)ru4(cdiv(k, 2)); ++t) val16[t] = 0;
+  constexpr int kPer = kTile / kThreads;
+  for (uint32_t blk = blockIdx.x; blk < n_items; blk += gridDim.x) {
+    const uint32_t p = blk / g.tiles_per_part;
+    const uint32_t tile = blk % g.tiles_per_part;
+    if (gated && !long_form(state, p)) continue;
+    const uint32_t d = g.part_size(p);
+    if (tile >= (uint32_t)cdiv(d, kTile)) continue;
+    const uint32_t T = state[p * 8 + 6 + kStPrefix];   // the selection after level 3
+    const uint32_t r = state[p * 8 + 6 + kStKRem];
+    {
+      const uint32_t *tc = tilecnt + 2ull * p * g.tiles_per_part;
+      uint32_t a = 0, b = 0;
+      for (uint32_t t = threadIdx.x; t < tile; t += kThreads) { a += tc[2 * t]; b += tc[2 * t + 1]; }
+      a = wave_sum_u32(a);
+      b = wave_sum_u32(b);
+      if ((threadIdx.x & 63) == 0) { before[0][threadIdx.x >> 6] = a; before[1][threadIdx.x >> 6] = b; }
+      __syncthreads();
     }
-  }
-  const uint64_t base = g.part_base(p);
-  const uint32_t j0 = tile * kTile + threadIdx.x * kPer;
-  float v[kPer];
-  uint32_t n_gt = 0, n_eq = 0;
-  if (j0 + kPer <= d) {
-    // the thread's 16 elements start at a multiple of 16: four 16-byte loads
-    const float4 *src4 = reinterpret_cast<const float4 *>(buf + base + j0);
+    uint32_t gt_before = 0, eq_before = 0;
 #pragma unroll
-    for (int q = 0; q < kPer / 4; ++q) {
-      const float4 f = src4[q];
-      v[4 * q] = f.x; v[4 * q + 1] = f.y; v[4 * q + 2] = f.z; v[4 * q + 3] = f.w;
-    }
-  } else {
+    for (int w = 0; w < kThreads / 64; ++w) { gt_before += before[0][w]; eq_before += before[1][w]; }
+    if (tile == 0 && threadIdx.x == 0) topk_write_header<HALF>(g, p, payload);
+    const uint64_t base = g.part_base(p);
+    const uint32_t j0 = tile * kTile + threadIdx.x * kPer;
+    float v[kPer];
+    uint32_t n_gt = 0, n_eq = 0;
+    if (j0 + kPer <= d) {
+      // the thread's 16 elements start at a multiple of 16: four 16-byte loads
+      const float4 *src4 = reinterpret_cast<const float4 *>(buf + base + j0);
 #pragma unroll
-    for (int i = 0; i < kPer; ++i) v[i] = j0 + i < d ? buf[base + j0 + i] : 0.0f;
-  }
-#pragma unroll
-  for (int i = 0; i < kPer; ++i) {
-    uint32_t j = j0 + i;
-    uint32_t key = key_of(v[i]);
-    n_gt += (j < d) && key > T;
-    n_eq += (j < d) && key == T;
-  }
-  // one scan for both counts: a tile has 4096 elements, so each fits 16 bits
-  uint32_t tot;
-  const uint32_t ex_both = block_exclusive_scan<kThreads>(n_gt | (n_eq << 16), scan, &tot);
-  const uint32_t ex_gt = ex_both & 0xffffu, ex_eq = ex_both >> 16;
-  // ties admitted before this tile / before this thread
-  const uint32_t ties_tile = eq_before < r ? eq_before : r;
-  uint32_t eq_rank = eq_before + ex_eq;                 // rank of this thread's first tie
-  const uint32_t ties_thread = (eq_rank < r ? eq_rank : r) - ties_tile;
-  uint32_t pos = gt_before + ties_tile + ex_gt + ties_thread;
-  uint8_t *rec = payload + (uint64_t)p * g.stride;
-  uint32_t *idx = reinterpret_cast<uint32_t *>(rec + kHeaderBytes);
-  float *val = reinterpret_cast<float *>(rec + kHeaderBytes + 4 * ru4(g.k_cap));
-#pragma unroll
-  for (int i = 0; i < kPer; ++i) {
-    uint32_t j = j0 + i;
-    if (j >= d) continue;
-    uint32_t key = key_of(v[i]);
-    bool take = key > T;
-    if (key == T) {
-      take = eq_rank < r;
-      ++eq_rank;
-    }
-    if (take) {
-      idx[pos] = j;
-      if (HALF) {
-        const __half h = __float2half_rn(v[i]);
-        reinterpret_cast<__half *>(val)[pos] = h;
-        if (zero_selected) buf[base + j] = v[i] - __half2float(h);
-      } else {
-        val[pos] = v[i];
-        if (zero_selected) buf[base + j] = 0.0f;
+      for (int q = 0; q < kPer / 4; ++q) {
+        const float4 f = src4[q];
+        v[4 * q] = f.x; v[4 * q + 1] = f.y; v[4 * q + 2] = f.z; v[4 * q + 3] = f.w;
       }
-      ++pos;
+    } else {
+#pragma unroll
+      for (int i = 0; i < kPer; ++i) v[i] = j0 + i < d ? buf[base + j0 + i] : 0.0f;
     }
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) {
+      uint32_t j = j0 + i;
+      uint32_t key = key_of(v[i]);
+      n_gt += (j < d) && key > T;
+      n_eq += (j < d) && key == T;
+    }
+    // one scan for both counts: a tile has 4096 elements, so each fits 16 bits
+    uint32_t tot;
+    const uint32_t ex_both = block_exclusive_scan<kThreads>(n_gt | (n_eq << 16), scan, &tot);
+    const uint32_t ex_gt = ex_both & 0xffffu, ex_eq = ex_both >> 16;
+    // ties admitted before this tile / before this thread
+    const uint32_t ties_tile = eq_before < r ? eq_before : r;
+    uint32_t eq_rank = eq_before + ex_eq;                 // rank of this thread's first tie
+    const uint32_t ties_thread = (eq_rank < r ? eq_rank : r) - ties_tile;
+    uint32_t pos = gt_before + ties_tile + ex_gt + ties_thread;
+    uint8_t *rec = payload + (uint64_t)p * g.stride;
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) {
+      uint32_t j = j0 + i;
+      if (j >= d) continue;
+      uint32_t key = key_of(v[i]);
+      bool take = key > T;
+      if (key == T) {
+        take = eq_rank < r;
+        ++eq_rank;
+      }
+      if (take) {
+        topk_write_entry<HALF>(g, rec, pos, j, v[i], buf + base, zero_selected);
+        ++pos;
+      }
+    }
+    __syncthreads();
   }
 }
 
@@ -337,7 +713,8 @@ hipError_t topk_encode(const Geo &g, const bpc_params_t &prm, const bpc_params_t
                        uint8_t *payload, const Workspace &ws, hipStream_t stream) {
   uint32_t *hist = ws.at<uint32_t>(ws.lay.hist);
   uint32_t *state = ws.at<uint32_t>(ws.lay.state);
-  uint32_t *tilecnt = ws.at<uint32_t>(ws.lay.tilecnt);
+  uint32_t *guess = ws.at<uint32_t>(ws.lay.guess);
+  uint32_t *tilecnt = ws.at<uint32_t>(ws.lay.tilecnt);   // also the per-group (place, count) of the short lists
   float *dense = ws.at<float>(ws.lay.dense);
   // the vector being compressed ends up in the residual buffer (error feedback) or the workspace
   float *buf = src.residual ? src.residual : dense;
@@ -353,25 +730,36 @@ hipError_t topk_encode(const Geo &g, const bpc_params_t &prm, const bpc_params_t
       else topk_accumulate_kernel<false><<<grid, kThreads, 0, stream>>>(g, src.msgs.ptr[i], dense);
     }
   }
-  e = fill_zero(hist, sizeof(uint32_t) * kHistPerPart * (size_t)g.P, stream);
-  if (e != hipSuccess) return e;
+  uint32_t *cand_idx = ws.at<uint32_t>(ws.lay.cand);
+  uint32_t *cand_val = cand_idx + (size_t)kTopkListCap * g.P;
+  // the short-list form wants room for the k winners and as many again; the select pass gives
+  // each group of tiles of a partition one thread
+  const int short_list = g.k_cap <= kTopkListCap / 2 && cdiv(g.tiles_per_part, kTpgLoad) <= (uint64_t)kSelThreads;
+  const uint32_t sample_grid = g.P > 64 ? g.P : 64, load_grid = group_count(g, kTpgLoad);
+  auto first_two = [&](auto s) {
+    topk_sample_kernel<<<sample_grid, kThreads, 0, stream>>>(g, s, hist, state, guess, short_list);
+    topk_load_hist1_kernel<<<load_grid, kThreads, 0, stream>>>(g, s, buf, hist, state, guess, tilecnt, cand_idx, cand_val);
+  };
   if (src.grad) {
-    if (src.dtype == BPC_F16) {
-      GradSource<__half> s{(const __half *)src.grad, src.residual};
-      topk_load_hist1_kernel<<<group_grid(g, kTpgLoad), kThreads, 0, stream>>>(g, s, buf, hist);
-    } else {
-      GradSource<float> s{(const float *)src.grad, src.residual};
-      topk_load_hist1_kernel<<<group_grid(g, kTpgLoad), kThreads, 0, stream>>>(g, s, buf, hist);
-    }
+    if (src.dtype == BPC_F16) first_two(GradSource<__half>{(const __half *)src.grad, src.residual});
+    else first_two(GradSource<float>{(const float *)src.grad, src.residual});
   } else {
-    DenseSumSource s{dense, src.residual, src.msgs.inv_n};
-    topk_load_hist1_kernel<<<group_grid(g, kTpgLoad), kThreads, 0, stream>>>(g, s, buf, hist);
+    first_two(DenseSumSource{dense, src.residual, src.msgs.inv_n});
   }
-  topk_hist_kernel<2><<<group_grid(g, kTpgHist2), kThreads, 0, stream>>>(g, buf, hist, state);
-  topk_hist_kernel<3><<<group_grid(g, kTpgHist3), kThreads, 0, stream>>>(g, buf, hist, state);
-  topk_count_kernel<<<group_grid(g, kTpgCount), kThreads, 0, stream>>>(g, buf, hist, state, tilecnt);
-  if (half) topk_emit_kernel<true><<<g.n_tiles, kThreads, 0, stream>>>(g, buf, state, tilecnt, payload, src.residual != nullptr);
-  else topk_emit_kernel<false><<<g.n_tiles, kThreads, 0, stream>>>(g, buf, state, tilecnt, payload, src.residual != nullptr);
+  const int zero_selected = src.residual != nullptr;
+  const int gated = short_list;
+  if (short_list) {
+    if (half) topk_list_select_kernel<true><<<g.P, kSelThreads, 0, stream>>>(g, buf, state, hist, tilecnt, cand_idx, cand_val, payload, zero_selected);
+    else topk_list_select_kernel<false><<<g.P, kSelThreads, 0, stream>>>(g, buf, state, hist, tilecnt, cand_idx, cand_val, payload, zero_selected);
+  }
+  auto grid_of = [&](uint32_t n) { return gated && n > kGatedGrid ? kGatedGrid : n; };
+  const uint32_t n2 = group_count(g, kTpgHist2), n3 = group_count(g, kTpgHist3), nc = group_count(g, kTpgCount);
+  const uint32_t ne = g.P * g.tiles_per_part;
+  topk_hist_kernel<2><<<grid_of(n2), kThreads, 0, stream>>>(g, buf, hist, state, n2, gated);
+  topk_hist_kernel<3><<<grid_of(n3), kThreads, 0, stream>>>(g, buf, hist, state, n3, gated);
+  topk_count_kernel<<<grid_of(nc), kThreads, 0, stream>>>(g, buf, hist, state, tilecnt, nc, gated);
+  if (half) topk_emit_kernel<true><<<grid_of(ne), kThreads, 0, stream>>>(g, buf, state, tilecnt, payload, zero_selected, ne, gated);
+  else topk_emit_kernel<false><<<grid_of(ne), kThreads, 0, stream>>>(g, buf, state, tilecnt, payload, zero_selected, ne, gated);
   return hipGetLastError();
 }
 

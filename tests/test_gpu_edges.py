@@ -102,6 +102,66 @@ def test_topk_ties_take_the_lowest_indices(gu, orc, pe, dtype):
     assert np.array_equal(res_gpu.view(np.uint32), res_ref.view(np.uint32))
 
 
+@pytest.mark.parametrize("kind", ["topk", "topk16"])
+@pytest.mark.parametrize("case", ["short_list", "mixed", "many_duplicates", "sparse", "large_k"])
+def test_topk_selection_forms(gu, orc, kind, case):
+    """The selection runs on a short list of a partition's largest elements where that list
+    comes out between k and its capacity, and over the whole partition otherwise, partition by
+    partition: both give the oracle's record and residual.  short_list: continuous values; mixed: one partition of
+    equal magnitudes between two ordinary ones; many_duplicates: 16 distinct magnitudes;
+    sparse: fewer non-zeros than k; large_k: k beyond what a short list holds."""
+    pe = BIG_PE
+    D = 2 * pe + 70001
+    ratio = 0.3 if case == "large_k" else 0.011
+    po, pb = gu.both_params(orc, kind, pe, k_ratio=ratio)
+    rs = np.random.default_rng(17)
+    g = rs.standard_normal(D).astype(np.float32)
+    e = (0.3 * rs.standard_normal(D)).astype(np.float32)
+    if case == "mixed":
+        g[pe:2 * pe] = np.where(rs.random(pe) < 0.5, -0.5, 0.5)
+        e[pe:2 * pe] = 0.0
+        g[pe + 77] = 4.0
+    elif case == "many_duplicates":
+        g = (rs.integers(-8, 9, D) * 0.125).astype(np.float32)
+        e[:] = 0.0
+    elif case == "sparse":
+        keep = rs.random(D) < 0.004
+        g = np.where(keep, g, 0.0).astype(np.float32)
+        e[:] = 0.0
+    res_ref = e.copy()
+    pay_ref = orc.compress(po, g, res_ref)
+    pay_gpu, res_gpu = gu.gpu_compress(pb, g, e.copy())
+    assert defined_equal(kind, pay_gpu, pay_ref, po, orc, D, pe, dict(k_ratio=ratio))
+    assert np.array_equal(res_gpu.view(np.uint32), res_ref.view(np.uint32))
+
+
+def test_topk_sample_that_misleads(gu, orc):
+    """The short list is built from a guess taken from a sample of the partition (512 chunks of
+    eight elements; chunk c is chunk c*stride + (c*37) % stride of the partition, stride =
+    (d/8)/512).  Large values planted on 100 sampled elements only put the guess above all but
+    those 100, so the list comes out shorter than k and the selection has to fall back on the
+    whole partition; the record must be the oracle's all the same.  (Mirrors the sampling rule
+    of the kernel: if that changes, this test still passes but no longer takes that branch.)"""
+    pe = BIG_PE
+    D = 2 * pe
+    ratio = 0.011
+    po, pb = gu.both_params(orc, "topk", pe, k_ratio=ratio)
+    rs = np.random.default_rng(23)
+    g = (0.5 * rs.random(D) - 0.25).astype(np.float32)
+    e = np.zeros(D, np.float32)
+    stride = (pe // 8) // 512
+    c = np.arange(512)
+    chunk = c * stride + (c * 37) % stride
+    sampled = (8 * chunk[:, None] + np.arange(8)[None, :]).ravel()
+    planted = rs.choice(sampled, 100, replace=False)
+    g[planted] = (10.0 + rs.random(100)).astype(np.float32)          # partition 0 only
+    res_ref = e.copy()
+    pay_ref = orc.compress(po, g, res_ref)
+    pay_gpu, res_gpu = gu.gpu_compress(pb, g, e.copy())
+    assert defined_equal("topk", pay_gpu, pay_ref, po, orc, D, pe, dict(k_ratio=ratio))
+    assert np.array_equal(res_gpu.view(np.uint32), res_ref.view(np.uint32))
+
+
 @pytest.mark.parametrize("kind", ["dither", "natdither"])
 @pytest.mark.parametrize("norm", [0, 1])
 def test_dither_tiny_values_divide_per_element(gu, orc, norm, kind):
