@@ -6,7 +6,13 @@
 //   store  : v_j from the source -> dense buffer (the residual buffer under error feedback)
 //   gather : val_t = v[idx_t] -> message
 //   fixup  : residual[idx_t] -= scale * val_t   (atomic: an index may repeat)
+// Server: Delta is formed slice by slice in LDS (`randk_sum_kernel`): an atomic add on global
+// memory costs some 11 ns of a memory channel's time, so scattering the n messages into a dense
+// buffer in HBM (n k adds per partition) took half the server's time; a workgroup that keeps
+// 32768 elements of Delta in LDS regenerates every draw of its partition instead and keeps
+// those that fall into its slice.
 #include "sources.hpp"
+#include <hip/hip_runtime.h>
 
 namespace bpc {
 
@@ -23,9 +29,183 @@ __global__ __launch_bounds__(kThreads) void randk_store_kernel(Geo g, SRC src, f
   src.begin(g, p, lds);
   const uint64_t base = g.part_base(p);
 #pragma unroll
-  for (int c = 0; c < kTile / kThreads; ++c) {
-    uint32_t j = tile * kTile + c * kThreads + threadIdx.x;
-    if (j < d) buf[base + j] = src.at(g, p, j, lds);
+  for (int c = 0; c < kTile / (kThreads * 8); ++c) {
+    const uint32_t j0 = tile * kTile + c * (kThreads * 8) + threadIdx.x * 8;
+    if (j0 >= d) continue;
+    float v[8];
+    source_at8(src, g, p, j0, d, lds, v);
+    if (j0 + 8 <= d) {
+      float4 *dst = reinterpret_cast<float4 *>(buf + base + j0);
+      dst[0] = make_float4(v[0], v[1], v[2], v[3]);
+      dst[1] = make_float4(v[4], v[5], v[6], v[7]);
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e)
+        if (j0 + e < d) buf[base + j0 + e] = v[e];
+    }
+  }
+}
+
+// Server side: Delta_j = (sum_i decode(delta_i)_j) / n + e~_j for one slice of kRsSlice elements
+// of one partition, summed in LDS in worker order (a barrier between workers; within a message
+// repeated indices add equal values, so the order of its adds does not matter), then written to
+// `buf` with the mean and the residual applied.
+constexpr int kRsThreads = 1024;
+constexpr uint32_t kRsSlice = 32768;
+struct RandkScales { float value_scale[kMaxWorkers]; };
+
+__global__ __launch_bounds__(kRsThreads) void randk_sum_kernel(Geo g, WorkerMsgs msgs, RandkScales sc, const float *res,
+                                                               float *buf) {
+  extern __shared__ float acc[];  // kRsSlice
+  const uint32_t slices_per_part = (uint32_t)cdiv(g.part_elems, kRsSlice);
+  const uint32_t p = blockIdx.x / slices_per_part, lo = (blockIdx.x % slices_per_part) * kRsSlice;
+  const uint32_t d = g.part_size(p);
+  if (lo >= d) return;
+  const uint32_t len = d - lo < kRsSlice ? d - lo : kRsSlice;
+  for (uint32_t q = threadIdx.x; q < kRsSlice / 4; q += kRsThreads) reinterpret_cast<float4 *>(acc)[q] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+  __syncthreads();
+  for (int i = 0; i < msgs.n; ++i) {
+    const uint8_t *rec = msgs.ptr[i] + (uint64_t)p * g.stride;
+    uint32_t k = *reinterpret_cast<const uint32_t *>(rec);
+    k = k > g.k_cap ? g.k_cap : k;
+    const float *val = reinterpret_cast<const float *>(rec + kHeaderBytes);
+    const float scale = sc.value_scale[i] >= 0.0f ? sc.value_scale[i] : (float)d / (float)k;
+    const Philox rng(msgs.seed[i], msgs.stream_id[i], p);
+    for (uint32_t t4 = threadIdx.x; 4 * t4 < k; t4 += kRsThreads) {
+      uint32_t rnd[4];
+      rng.block(t4, rnd);
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const uint32_t t = 4 * t4 + c;
+        const uint32_t rel = (uint32_t)(((uint64_t)rnd[c] * d) >> 32) - lo;
+        if (t < k && rel < len) atomicAdd(&acc[rel], scale * val[t]);
+      }
+    }
+    __syncthreads();
+  }
+  const uint64_t at = g.part_base(p) + lo;
+  for (uint32_t q = threadIdx.x * 4; q < len; q += kRsThreads * 4) {
+    if (q + 4 <= len) {
+      const float4 a = *reinterpret_cast<const float4 *>(acc + q);
+      float4 r = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+      if (res) r = *reinterpret_cast<const float4 *>(res + at + q);
+      const float m0 = a.x * msgs.inv_n, m1 = a.y * msgs.inv_n, m2 = a.z * msgs.inv_n, m3 = a.w * msgs.inv_n;
+      *reinterpret_cast<float4 *>(buf + at + q) = res ? make_float4(m0 + r.x, m1 + r.y, m2 + r.z, m3 + r.w) : make_float4(m0, m1, m2, m3);
+    } else {
+      for (uint32_t e = q; e < len; ++e) {
+        const float mean = acc[e] * msgs.inv_n;
+        buf[at + e] = res ? mean + res[at + e] : mean;
+      }
+    }
+  }
+}
+
+// The same in two steps, for when the dense workspace is free to hold lists (the server has a
+// residual buffer for Delta and the lists fit): `randk_bin_kernel` writes each message's draws
+// as (index, scaled value) pairs grouped by slice, with a table of where each slice's group
+// starts; `randk_sum_binned_kernel` then adds up only the pairs of its own slice, so no draw is
+// regenerated more than twice and slices can be small (8192 elements: several workgroups a
+// compute unit, loads and stores of different slices overlap).
+constexpr int kRbThreads = 1024;
+constexpr uint32_t kRbMaxBins = 1024;   // slices of a partition, at most
+constexpr int kRbSumThreads = 256;
+
+__global__ __launch_bounds__(kRbThreads) void randk_bin_kernel(Geo g, WorkerMsgs msgs, RandkScales sc, uint32_t slice_shift,
+                                                               uint2 *lists, uint32_t *table) {
+  __shared__ uint32_t cnt[kRbMaxBins];
+  __shared__ uint32_t scan[kRbThreads / 64];
+  const uint32_t p = blockIdx.x, i = blockIdx.y;
+  const uint32_t d = g.part_size(p);
+  const uint8_t *rec = msgs.ptr[i] + (uint64_t)p * g.stride;
+  uint32_t k = *reinterpret_cast<const uint32_t *>(rec);
+  k = k > g.k_cap ? g.k_cap : k;
+  const float *val = reinterpret_cast<const float *>(rec + kHeaderBytes);
+  const float scale = sc.value_scale[i] >= 0.0f ? sc.value_scale[i] : (float)d / (float)k;
+  const Philox rng(msgs.seed[i], msgs.stream_id[i], p);
+  cnt[threadIdx.x] = 0;
+  __syncthreads();
+  for (uint32_t t4 = threadIdx.x; 4 * t4 < k; t4 += kRbThreads) {
+    uint32_t rnd[4];
+    rng.block(t4, rnd);
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+      if (4 * t4 + c < k) atomicAdd(&cnt[(uint32_t)(((uint64_t)rnd[c] * d) >> 32) >> slice_shift], 1u);
+  }
+  __syncthreads();
+  uint32_t total;
+  const uint32_t start = block_exclusive_scan<kRbThreads>(cnt[threadIdx.x], scan, &total);
+  uint32_t *tab = table + ((uint64_t)i * g.P + p) * (kRbMaxBins + 1);
+  tab[threadIdx.x] = start;
+  if (threadIdx.x == 0) tab[kRbMaxBins] = total;
+  cnt[threadIdx.x] = start;   // from here on: where the slice's next pair goes
+  __syncthreads();
+  uint2 *list = lists + ((uint64_t)i * g.P + p) * g.k_cap;
+  for (uint32_t t4 = threadIdx.x; 4 * t4 < k; t4 += kRbThreads) {
+    uint32_t rnd[4];
+    rng.block(t4, rnd);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const uint32_t t = 4 * t4 + c;
+      if (t < k) {
+        const uint32_t j = (uint32_t)(((uint64_t)rnd[c] * d) >> 32);
+        const uint32_t pos = atomicAdd(&cnt[j >> slice_shift], 1u);
+        list[pos] = make_uint2(j, __float_as_uint(scale * val[t]));
+      }
+    }
+  }
+}
+
+__global__ __launch_bounds__(kRbSumThreads) void randk_sum_binned_kernel(Geo g, int n, float inv_n, uint32_t slice_shift,
+                                                                         const uint2 *lists, const uint32_t *table,
+                                                                         const float *res, float *buf) {
+  extern __shared__ float acc[];  // 1 << slice_shift
+  __shared__ uint32_t from[kMaxWorkers], to[kMaxWorkers];
+  const uint32_t slice = 1u << slice_shift;
+  const uint32_t slices_per_part = (uint32_t)cdiv(g.part_elems, slice);
+  const uint32_t p = blockIdx.x / slices_per_part, s = blockIdx.x % slices_per_part, lo = s << slice_shift;
+  const uint32_t d = g.part_size(p);
+  if (lo >= d) return;
+  const uint32_t len = d - lo < slice ? d - lo : slice;
+  if (threadIdx.x < (uint32_t)n) {
+    const uint32_t *tab = table + ((uint64_t)threadIdx.x * g.P + p) * (kRbMaxBins + 1);
+    from[threadIdx.x] = tab[s];
+    to[threadIdx.x] = tab[s + 1];
+  }
+  for (uint32_t q = threadIdx.x; q < slice / 4; q += kRbSumThreads) reinterpret_cast<float4 *>(acc)[q] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+  __syncthreads();
+  // worker by worker (a barrier in between); the first pair a thread adds for the next worker
+  // is requested before the adds of this one
+  auto first_pair = [&](int i) {
+    const uint32_t q = from[i] + threadIdx.x;
+    return lists[((uint64_t)i * g.P + p) * g.k_cap + (q < to[i] ? q : from[i] < to[i] ? from[i] : 0u)];
+  };
+  uint2 next = first_pair(0);
+  for (int i = 0; i < n; ++i) {
+    const uint2 mine = next;
+    if (i + 1 < n) next = first_pair(i + 1);
+    const uint2 *list = lists + ((uint64_t)i * g.P + p) * g.k_cap;
+    const uint32_t b = from[i], e = to[i];
+    if (b + threadIdx.x < e) atomicAdd(&acc[mine.x - lo], __uint_as_float(mine.y));
+    for (uint32_t q = b + kRbSumThreads + threadIdx.x; q < e; q += kRbSumThreads) {
+      const uint2 ent = list[q];
+      atomicAdd(&acc[ent.x - lo], __uint_as_float(ent.y));
+    }
+    __syncthreads();
+  }
+  const uint64_t at = g.part_base(p) + lo;
+  for (uint32_t q = threadIdx.x * 4; q < len; q += kRbSumThreads * 4) {
+    if (q + 4 <= len) {
+      const float4 a = *reinterpret_cast<const float4 *>(acc + q);
+      float4 r = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+      if (res) r = *reinterpret_cast<const float4 *>(res + at + q);
+      const float m0 = a.x * inv_n, m1 = a.y * inv_n, m2 = a.z * inv_n, m3 = a.w * inv_n;
+      *reinterpret_cast<float4 *>(buf + at + q) = res ? make_float4(m0 + r.x, m1 + r.y, m2 + r.z, m3 + r.w) : make_float4(m0, m1, m2, m3);
+    } else {
+      for (uint32_t e = q; e < len; ++e) {
+        const float mean = acc[e] * inv_n;
+        buf[at + e] = res ? mean + res[at + e] : mean;
+      }
+    }
   }
 }
 
@@ -98,23 +278,56 @@ hipError_t randk_encode(const Geo &g, const bpc_params_t &prm, const bpc_params_
     else
       randk_store_kernel<<<g.n_tiles, kThreads, 0, stream>>>(g, GradSource<float>{(const float *)src.grad, src.residual}, buf);
   } else {
-    hipError_t e = fill_zero(dense, sizeof(float) * g.D, stream);
-    if (e != hipSuccess) return e;
     // workers that drew from one stream sent values for the same indices
     bool shared = src.msgs.n > 1;
     for (int i = 1; i < src.msgs.n; ++i)
       shared = shared && in_prm[i].seed == in_prm[0].seed && in_prm[i].stream_id == in_prm[0].stream_id &&
                in_prm[i].value_scale == in_prm[0].value_scale;
-    if (shared) {
-      e = scatter_add_randk_shared(g, in_prm[0], src.msgs, dense, stream);
+    static bool lds_ok = hipFuncSetAttribute(reinterpret_cast<const void *>(&randk_sum_kernel),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, kRsSlice * sizeof(float)) == hipSuccess;
+    if (shared || !lds_ok) {
+      hipError_t e = fill_zero(dense, sizeof(float) * g.D, stream);
       if (e != hipSuccess) return e;
-    } else {
-      for (int i = 0; i < src.msgs.n; ++i) {
-        e = scatter_add_sparse(g, in_prm[i], src.msgs.ptr[i], dense, stream);
+      if (shared) {
+        e = scatter_add_randk_shared(g, in_prm[0], src.msgs, dense, stream);
         if (e != hipSuccess) return e;
+      } else {
+        for (int i = 0; i < src.msgs.n; ++i) {
+          e = scatter_add_sparse(g, in_prm[i], src.msgs.ptr[i], dense, stream);
+          if (e != hipSuccess) return e;
+        }
       }
+      randk_store_kernel<<<g.n_tiles, kThreads, 0, stream>>>(g, DenseSumSource{dense, src.residual, src.msgs.inv_n}, buf);
+    } else {
+      RandkScales sc;
+      for (int i = 0; i < src.msgs.n; ++i) sc.value_scale[i] = in_prm[i].value_scale;
+      // slices of 8192 elements, larger (up to what LDS holds) if a partition would have more than kRbMaxBins of them
+      uint32_t slice_shift = 13;
+      while (slice_shift < 15 && cdiv(g.part_elems, 1ull << slice_shift) > kRbMaxBins) ++slice_shift;
+      const uint64_t np = (uint64_t)src.msgs.n * g.P;
+      const uint64_t list_bytes = np * g.k_cap * sizeof(uint2), table_bytes = np * (kRbMaxBins + 1) * sizeof(uint32_t);
+      const bool binned = src.residual != nullptr && cdiv(g.part_elems, 1ull << slice_shift) <= kRbMaxBins &&
+                          list_bytes + table_bytes + 256 <= sizeof(float) * g.D;
+      if (binned) {
+        // (Delta goes to the residual buffer, so the dense workspace is free)
+        uint2 *lists = reinterpret_cast<uint2 *>(dense);
+        uint32_t *table = reinterpret_cast<uint32_t *>(reinterpret_cast<uint8_t *>(dense) + (list_bytes + 255) / 256 * 256);
+        static bool lds2_ok = hipFuncSetAttribute(reinterpret_cast<const void *>(&randk_sum_binned_kernel),
+                                                  hipFuncAttributeMaxDynamicSharedMemorySize, (4u << 15)) == hipSuccess;
+        if (lds2_ok || slice_shift == 13) {
+          randk_bin_kernel<<<dim3(g.P, src.msgs.n), kRbThreads, 0, stream>>>(g, src.msgs, sc, slice_shift, lists, table);
+          const uint32_t slices = g.P * (uint32_t)cdiv(g.part_elems, 1ull << slice_shift);
+          randk_sum_binned_kernel<<<slices, kRbSumThreads, sizeof(float) << slice_shift, stream>>>(
+              g, src.msgs.n, src.msgs.inv_n, slice_shift, lists, table, src.residual, buf);
+          goto summed;
+        }
+      }
+      {
+        const uint32_t slices = g.P * (uint32_t)cdiv(g.part_elems, kRsSlice);
+        randk_sum_kernel<<<slices, kRsThreads, kRsSlice * sizeof(float), stream>>>(g, src.msgs, sc, src.residual, buf);
+      }
+    summed:;
     }
-    randk_store_kernel<<<g.n_tiles, kThreads, 0, stream>>>(g, DenseSumSource{dense, src.residual, src.msgs.inv_n}, buf);
   }
   randk_gather_kernel<<<grid, kThreads, 0, stream>>>(g, buf, payload, prm.seed, prm.stream_id);
   if (src.residual)
