@@ -118,6 +118,9 @@ struct WsLayout {
   size_t hist;       // u32[P*kTopkHistWords]: top-k radix histograms (2048 + 1024 + 1024 bins)
   size_t state;      // u32[P*8]: top-k selection state
   size_t guess;      // u32[P]: top-k key from which elements go to a partition's short list
+  size_t starts;     // u32[kMaxWorkers * P * (groups of 8192 elements per partition + 1)]: where each group's
+                     // entries start in each worker's top-k message (server side)
+  size_t samp;       // f32[P * 4096]: sums of the sampled chunks of Delta (top-k, server side)
   size_t cand;       // u32[P * kTopkListCap] indices, then as many value bits: top-k short lists of the partitions
   size_t tilecnt;    // u32[2*n_tiles]: per-tile (greater, equal) counts, then offsets
   size_t slots;      // double[3 * tiles of kSTile]: partition-wide reductions of the single-pass kernels
@@ -140,6 +143,8 @@ inline WsLayout ws_layout(const bpc_params_t *p, uint64_t D) {
   w.hist = take(topk ? sizeof(uint32_t) * kTopkHistWords * (size_t)g.P : 0);
   w.state = take(topk ? sizeof(uint32_t) * 8 * (size_t)g.P : 0);
   w.guess = take(topk ? sizeof(uint32_t) * (size_t)g.P : 0);
+  w.starts = take(topk ? sizeof(uint32_t) * kMaxWorkers * (size_t)g.P * (cdiv(p->part_elems, 8192) + 1) : 0);
+  w.samp = take(topk ? sizeof(float) * 4096 * (size_t)g.P : 0);
   w.cand = take(topk ? 8 * (size_t)kTopkListCap * (size_t)g.P : 0);
   w.tilecnt = take(topk ? sizeof(uint32_t) * 2 * (size_t)g.n_tiles : 0);
   w.slots = take(sizeof(double) * 3 * ((size_t)g.P * cdiv(g.part_elems, kSTile)));

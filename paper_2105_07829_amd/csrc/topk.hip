@@ -29,6 +29,12 @@
 //   emit       : (idx, val) in ascending index order; kept slots of the buffer zeroed
 // Each pass works out the selection so far from the histograms of the passes before it (every
 // workgroup for itself), so no launches sit between the passes.
+//
+// Server side the vector is Delta = (sum of the n decoded messages) / n + e~.  It is never
+// scattered into a dense buffer (n k read-modify-writes at random places of HBM per partition):
+// the messages list their entries by ascending index, so the load pass sums the stretch of each
+// message that falls into its group of 8192 elements in LDS, and the sample pass collects the
+// sums of the sampled chunks in one sweep over the messages.
 #include "sources.hpp"
 
 namespace bpc {
@@ -169,6 +175,166 @@ __device__ inline void levels23_in_registers(const uint32_t (&bits)[PER], uint32
 // few memory channels).
 __device__ inline uint32_t sample_chunk(uint32_t c, uint32_t stride) { return c * stride + (c * 37u) % stride; }
 
+// Sample chunks and their spacing for a partition of d elements.
+__device__ inline uint32_t sample_chunks(uint32_t d) { return d / 8 < kSample / 8 ? d / 8 : kSample / 8; }
+
+constexpr uint32_t kGroupElems = kTpgLoad * kTile;   // elements a workgroup of the load pass takes: 8192
+static_assert(kGroupElems == 8192, "the workspace is laid out for groups of 8192 elements");
+
+// Server side: Delta = (sum of the n decoded top-k messages) / n + e~ straight from the
+// messages.  A message lists its entries by ascending index, so the entries of a group of
+// 8192 elements are one stretch of it; `topk_starts_kernel` records where each stretch begins.
+struct TopkMsgs {
+  WorkerMsgs msgs;
+  const float *res;
+  const uint32_t *starts;   // [worker][partition][group .. groups_per_part]
+  uint32_t groups_per_part, k_cap;
+  uint64_t stride;
+  int half;
+  __device__ const uint8_t *rec(int i, uint32_t p) const { return msgs.ptr[i] + (uint64_t)p * stride; }
+  __device__ uint32_t k_of(int i, uint32_t p) const {
+    const uint32_t k = *reinterpret_cast<const uint32_t *>(rec(i, p));
+    return k > k_cap ? k_cap : k;
+  }
+  __device__ const uint32_t *idx(int i, uint32_t p) const { return reinterpret_cast<const uint32_t *>(rec(i, p) + kHeaderBytes); }
+  __device__ float value(int i, uint32_t p, uint32_t t) const {
+    const uint8_t *v = rec(i, p) + kHeaderBytes + 4 * ru4(k_cap);
+    return half ? __half2float(reinterpret_cast<const __half *>(v)[t]) : reinterpret_cast<const float *>(v)[t];
+  }
+  __device__ void finish8(const Geo &g, uint32_t p, uint32_t j0, uint32_t d, const float *sum, float out[8]) const {
+    const uint64_t i0 = g.part_base(p) + j0;
+    float r[8] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+    if (res) {
+      if (j0 + 8 <= d) load8_aligned(res + i0, r);
+      else
+        for (int e = 0; e < 8; ++e) r[e] = j0 + e < d ? res[i0 + e] : 0.0f;
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float mean = sum[e] * msgs.inv_n;
+      out[e] = j0 + e < d ? (res ? mean + r[e] : mean) : 0.0f;
+    }
+  }
+};
+
+// For t = 0 .. k: entry t is the first one of every group after the group of entry t - 1 up to
+// its own group (t = k: up to the end).  A message that is not in ascending order leaves
+// groups unset; readers clamp what they find to [0, k].
+// The same sweep adds the entries that fall into the chunks of the sample pass to `samp`
+// (zeroed before; about one entry in 250, so the global atomics do not matter, and the guess
+// needs no particular order of the sum).
+__global__ __launch_bounds__(kThreads) void topk_starts_kernel(Geo g, TopkMsgs m, uint32_t *starts, float *samp) {
+  const uint32_t p = blockIdx.y, i = blockIdx.z;
+  const uint32_t k = m.k_of(i, p);
+  const uint32_t *idx = m.idx(i, p);
+  uint32_t *tab = starts + ((uint64_t)i * g.P + p) * (m.groups_per_part + 1);
+  auto group = [&](uint32_t j) { const uint32_t q = j / kGroupElems; return q < m.groups_per_part ? q : m.groups_per_part - 1; };
+  const uint32_t d = g.part_size(p);
+  const uint32_t chunks = sample_chunks(d), stride = chunks ? (d / 8) / chunks : 1u;
+  for (uint32_t t = blockIdx.x * kThreads + threadIdx.x; t <= k; t += gridDim.x * kThreads) {
+    const uint32_t first = t == 0 ? 0u : group(idx[t - 1]) + 1;
+    const uint32_t last = t == k ? m.groups_per_part : group(idx[t]);
+    for (uint32_t q = first; q <= last && q <= m.groups_per_part; ++q) tab[q] = t;
+    if (t < k) {
+      const uint32_t j = idx[t], cj = j >> 3, c = cj / stride;
+      if (c < chunks && cj == sample_chunk(c, stride)) atomicAdd(&samp[(uint64_t)p * kSample + c * 8 + (j & 7u)], m.value(i, p, t));
+    }
+  }
+}
+
+// The load pass's view: the workgroup's group of 8192 elements summed in LDS, worker by worker
+// (a barrier in between: the order of the sum is the workers'), a thread's first entry of the
+// next worker requested before the adds of this one.
+struct TopkMsgsGroupSource : TopkMsgs {
+  static constexpr int kLdsFloats = kGroupElems + 3 * kMaxWorkers + 1;
+  __device__ void begin(const Geo &, uint32_t, float *) const {}
+  __device__ void begin_group(const Geo &g, uint32_t p, uint32_t grp, float *lds) const {
+    uint32_t *range = reinterpret_cast<uint32_t *>(lds + kGroupElems);
+    const uint32_t lo = grp * kGroupElems;
+    if (threadIdx.x < (uint32_t)msgs.n) {
+      const uint32_t *tab = starts + ((uint64_t)threadIdx.x * g.P + p) * (groups_per_part + 1);
+      const uint32_t k = k_of(threadIdx.x, p);
+      const uint32_t s = tab[grp] < k ? tab[grp] : k, e = tab[grp + 1] < k ? tab[grp + 1] : k;
+      range[2 * threadIdx.x] = s;
+      range[2 * threadIdx.x + 1] = e < s ? s : e;
+    }
+    for (uint32_t q = threadIdx.x; q < kGroupElems / 4; q += kThreads) reinterpret_cast<float4 *>(lds)[q] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    __syncthreads();
+    // entries of the group before worker i's, over all workers
+    uint32_t *cum = range + 2 * kMaxWorkers;
+    if (threadIdx.x < 64) {
+      const uint32_t c = threadIdx.x < (uint32_t)msgs.n ? range[2 * threadIdx.x + 1] - range[2 * threadIdx.x] : 0u;
+      const uint32_t incl = wave_inclusive_scan_u32(c);
+      cum[threadIdx.x + 1] = incl;
+      if (threadIdx.x == 0) cum[0] = 0;
+    }
+    __syncthreads();
+    const uint32_t total = cum[msgs.n];
+    constexpr int kMine = 4;   // entries a thread takes
+    if (total <= (uint32_t)(kMine * kThreads)) {
+      // all the group's entries are requested at once (worker-major, so a thread's entries come
+      // in worker order), then added worker by worker with a barrier in between
+      uint32_t rel[kMine], who[kMine];
+      float val[kMine];
+#pragma unroll
+      for (int r = 0; r < kMine; ++r) {
+        const uint32_t q = r * kThreads + threadIdx.x;
+        who[r] = 0xffffffffu;
+        rel[r] = 0;
+        val[r] = 0.0f;
+        if (q < total) {
+          uint32_t a = 0, b = msgs.n;   // cum[a] <= q < cum[b]
+          while (b - a > 1) {
+            const uint32_t mid = (a + b) >> 1;
+            if (cum[mid] <= q) a = mid; else b = mid;
+          }
+          const uint32_t t = range[2 * a] + (q - cum[a]);
+          who[r] = a;
+          rel[r] = idx(a, p)[t] - lo;
+          val[r] = value(a, p, t);
+        }
+      }
+      for (int i = 0; i < msgs.n; ++i) {
+        if (cum[i + 1] != cum[i]) {   // (uniform)
+#pragma unroll
+          for (int r = 0; r < kMine; ++r)
+            if (who[r] == (uint32_t)i && rel[r] < kGroupElems) lds[rel[r]] = lds[rel[r]] + val[r];
+          __syncthreads();
+        }
+      }
+    } else {
+      for (int i = 0; i < msgs.n; ++i) {
+        const uint32_t s = range[2 * i], e = range[2 * i + 1];
+        for (uint32_t q = s + threadIdx.x; q < e; q += kThreads) {
+          const uint32_t r = idx(i, p)[q] - lo;
+          if (r < kGroupElems) lds[r] = lds[r] + value(i, p, q);
+        }
+        __syncthreads();
+      }
+    }
+  }
+  __device__ void at8(const Geo &g, uint32_t p, uint32_t j0, uint32_t d, const float *lds, float out[8]) const {
+    float sum[8];
+    load8_aligned(lds + j0 % kGroupElems, sum);
+    finish8(g, p, j0, d, sum, out);
+  }
+};
+
+// The sample pass's view of the same: the sums of the sampled chunks, collected by the sweep of
+// `topk_starts_kernel`.
+struct TopkMsgsSampleSource : TopkMsgs {
+  const float *samp;
+  static constexpr int kLdsFloats = 1;
+  __device__ void begin(const Geo &, uint32_t, float *) const {}
+  // j0: the first element of a sampled chunk
+  __device__ void at8(const Geo &g, uint32_t p, uint32_t j0, uint32_t d, const float *, float out[8]) const {
+    const uint32_t chunks = sample_chunks(d), stride = (d / 8) / chunks;
+    float sum[8];
+    load8_aligned(samp + (uint64_t)p * kSample + 8 * ((j0 >> 3) / stride), sum);
+    finish8(g, p, j0, d, sum, out);
+  }
+};
+
 // Zeroes the histograms and the state words; with `sample`, workgroup p < P also works out
 // partition p's guess G from a sample of 512 chunks of eight consecutive elements (else the
 // guess is "none").  Random 64-byte reads cost about as much as 16 times as many sequential
@@ -192,12 +358,10 @@ __global__ __launch_bounds__(kThreads) void topk_sample_kernel(Geo g, SRC src, u
     if (threadIdx.x == 0) guess[p] = kNoGuess;
     return;
   }
-  src.begin(g, p, lds);
-  __syncthreads();
   static_assert(kSamplePer % 8 == 0, "whole chunks");
-  constexpr uint32_t kChunksPer = kSamplePer / 8, kChunks = kSample / 8;
+  constexpr uint32_t kChunksPer = kSamplePer / 8;
   const uint32_t d = g.part_size(p);
-  const uint32_t chunks = d / 8 < kChunks ? d / 8 : kChunks;   // chunks in the sample (whole chunks of the partition only)
+  const uint32_t chunks = sample_chunks(d);                   // chunks in the sample (whole chunks of the partition only)
   const uint32_t m = 8 * chunks;                              // elements in the sample
   // rank in the sample: the expected rank of the partition's k-th largest, four standard
   // deviations of a count of twice that size further down (neighbours are not independent),
@@ -209,6 +373,8 @@ __global__ __launch_bounds__(kThreads) void topk_sample_kernel(Geo g, SRC src, u
     return;
   }
   const uint32_t stride = (d / 8) / chunks;
+  src.begin(g, p, lds);
+  __syncthreads();
   uint32_t key[kSamplePer];
   uint32_t cnt = 0;
   // (every load is issued, with chunk 0 standing in past the end, so that none is waited for
@@ -228,6 +394,11 @@ __global__ __launch_bounds__(kThreads) void topk_sample_kernel(Geo g, SRC src, u
   levels23_in_registers<kSamplePer, kThreads>(key, cnt, kSamplePer, b1, k_rem1, h, scan, sel);
   if (threadIdx.x == 0) guess[p] = sel[0];
 }
+
+template <class SRC, class = void>
+struct has_begin_group : std::false_type {};
+template <class SRC>
+struct has_begin_group<SRC, std::void_t<decltype(&SRC::begin_group)>> : std::true_type {};
 
 // Load pass.  Besides the buffer and the histogram: the elements of the workgroup's tiles whose
 // key is at least the partition's guess go to its short list, together and in index order, at
@@ -249,6 +420,7 @@ __global__ __launch_bounds__(kThreads) void topk_load_hist1_kernel(Geo g, SRC sr
   src.begin(g, w.p, lds);
   __syncthreads();
   if (w.tile_lo >= w.tile_hi) return;  // (uniform) past the end of a shorter last partition
+  if constexpr (has_begin_group<SRC>::value) src.begin_group(g, w.p, w.tile_lo / kTpgLoad, lds);
   const uint32_t G = guess[w.p];
   const uint64_t base = g.part_base(w.p);
   float v[kPieces][8];
@@ -691,24 +863,6 @@ __global__ __launch_bounds__(kThreads) void topk_emit_kernel(Geo g, float *buf, 
   }
 }
 
-// acc_j = acc_j + val for the entries of one worker's top-k message (indices are distinct
-// within a message, so plain read-modify-write suffices).
-template <bool HALF>
-__global__ __launch_bounds__(kThreads) void topk_accumulate_kernel(Geo g, const uint8_t *payload, float *acc) {
-  const uint32_t p = blockIdx.y;
-  const uint32_t d = g.part_size(p);
-  const uint8_t *rec = payload + (uint64_t)p * g.stride;
-  uint32_t k = *reinterpret_cast<const uint32_t *>(rec);
-  k = k > g.k_cap ? g.k_cap : k;
-  const uint32_t *idx = reinterpret_cast<const uint32_t *>(rec + kHeaderBytes);
-  const float *val = reinterpret_cast<const float *>(rec + kHeaderBytes + 4 * ru4(g.k_cap));
-  const uint64_t base = g.part_base(p);
-  for (uint32_t t = blockIdx.x * kThreads + threadIdx.x; t < k; t += gridDim.x * kThreads) {
-    uint32_t j = idx[t];
-    if (j < d) acc[base + j] = acc[base + j] + (HALF ? __half2float(reinterpret_cast<const __half *>(val)[t]) : val[t]);
-  }
-}
-
 hipError_t topk_encode(const Geo &g, const bpc_params_t &prm, const bpc_params_t *, const Source &src,
                        uint8_t *payload, const Workspace &ws, hipStream_t stream) {
   uint32_t *hist = ws.at<uint32_t>(ws.lay.hist);
@@ -719,32 +873,33 @@ hipError_t topk_encode(const Geo &g, const bpc_params_t &prm, const bpc_params_t
   // the vector being compressed ends up in the residual buffer (error feedback) or the workspace
   float *buf = src.residual ? src.residual : dense;
   const bool half = prm.kind == BPC_TOPK16;
-  hipError_t e;
-  if (!src.grad) {
-    // server: sum the n decoded messages into the workspace in worker order
-    e = fill_zero(dense, sizeof(float) * g.D, stream);
-    if (e != hipSuccess) return e;
-    dim3 grid((uint32_t)cdiv(g.k_cap, kThreads), g.P);
-    for (int i = 0; i < src.msgs.n; ++i) {
-      if (half) topk_accumulate_kernel<true><<<grid, kThreads, 0, stream>>>(g, src.msgs.ptr[i], dense);
-      else topk_accumulate_kernel<false><<<grid, kThreads, 0, stream>>>(g, src.msgs.ptr[i], dense);
-    }
-  }
   uint32_t *cand_idx = ws.at<uint32_t>(ws.lay.cand);
   uint32_t *cand_val = cand_idx + (size_t)kTopkListCap * g.P;
   // the short-list form wants room for the k winners and as many again; the select pass gives
   // each group of tiles of a partition one thread
   const int short_list = g.k_cap <= kTopkListCap / 2 && cdiv(g.tiles_per_part, kTpgLoad) <= (uint64_t)kSelThreads;
   const uint32_t sample_grid = g.P > 64 ? g.P : 64, load_grid = group_count(g, kTpgLoad);
-  auto first_two = [&](auto s) {
-    topk_sample_kernel<<<sample_grid, kThreads, 0, stream>>>(g, s, hist, state, guess, short_list);
-    topk_load_hist1_kernel<<<load_grid, kThreads, 0, stream>>>(g, s, buf, hist, state, guess, tilecnt, cand_idx, cand_val);
+  auto first_two = [&](auto s_sample, auto s_load) {
+    topk_sample_kernel<<<sample_grid, kThreads, 0, stream>>>(g, s_sample, hist, state, guess, short_list);
+    topk_load_hist1_kernel<<<load_grid, kThreads, 0, stream>>>(g, s_load, buf, hist, state, guess, tilecnt, cand_idx, cand_val);
   };
   if (src.grad) {
-    if (src.dtype == BPC_F16) first_two(GradSource<__half>{(const __half *)src.grad, src.residual});
-    else first_two(GradSource<float>{(const float *)src.grad, src.residual});
+    if (src.dtype == BPC_F16) {
+      GradSource<__half> s{(const __half *)src.grad, src.residual};
+      first_two(s, s);
+    } else {
+      GradSource<float> s{(const float *)src.grad, src.residual};
+      first_two(s, s);
+    }
   } else {
-    first_two(DenseSumSource{dense, src.residual, src.msgs.inv_n});
+    // server: Delta straight from the n messages (they are taken to have the format of `prm`)
+    uint32_t *starts = ws.at<uint32_t>(ws.lay.starts);
+    const TopkMsgs m{src.msgs, src.residual, starts, (uint32_t)cdiv(g.tiles_per_part, kTpgLoad), g.k_cap, g.stride, half ? 1 : 0};
+    float *samp = ws.at<float>(ws.lay.samp);
+    const hipError_t e = fill_zero(samp, sizeof(float) * kSample * g.P, stream);
+    if (e != hipSuccess) return e;
+    topk_starts_kernel<<<dim3((uint32_t)cdiv(g.k_cap + 1, kThreads), g.P, src.msgs.n), kThreads, 0, stream>>>(g, m, starts, samp);
+    first_two(TopkMsgsSampleSource{m, samp}, TopkMsgsGroupSource{m});
   }
   const int zero_selected = src.residual != nullptr;
   const int gated = short_list;

@@ -135,6 +135,30 @@ def test_topk_selection_forms(gu, orc, kind, case):
     assert np.array_equal(res_gpu.view(np.uint32), res_ref.view(np.uint32))
 
 
+def test_randk_server_partition_of_many_slices(gu, orc):
+    """Random-k server on a partition of more than 1024 x 8192 elements: the sum of the decoded
+    messages is formed in LDS slices of 16384 elements instead of 8192 (values to 1e-6: the
+    order of the float adds inside a slice is free)."""
+    pe = 9 * 1024 * 1024
+    D = pe + 12345
+    n = 2
+    kw = dict(k_ratio=0.0005, value_scale=-1.0, seed=11)
+    ins = [gu.both_params(orc, "randk", pe, stream_id=(3 << 32) | i, **kw) for i in range(n)]
+    out_o, out_b = gu.both_params(orc, "randk", pe, stream_id=(3 << 32) | 99, **kw)
+    rs = np.random.default_rng(31)
+    payloads = [orc.compress(ins[i][0], (rs.standard_normal(D) * 1e-3).astype(np.float32), None) for i in range(n)]
+    et = (rs.standard_normal(D) * 2e-4).astype(np.float32)
+    res_ref = et.copy()
+    pay_ref = orc.server_aggregate([p[0] for p in ins], payloads, out_o, res_ref, D)
+    pay_gpu, res_gpu = gu.gpu_server([p[1] for p in ins], payloads, out_b, et, D)
+    strd = orc.partition_stride(out_o)
+    for p, d in enumerate(fmt.part_sizes(D, pe)):
+        kg, vg = fmt.randk_values(fmt.record(pay_gpu, p, strd))
+        kr, vr = fmt.randk_values(fmt.record(pay_ref, p, strd))
+        assert kg == kr and gu.close(vg, vr, REL)
+    assert gu.close(res_gpu, res_ref, REL)
+
+
 def test_topk_sample_that_misleads(gu, orc):
     """The short list is built from a guess taken from a sample of the partition (512 chunks of
     eight elements; chunk c is chunk c*stride + (c*37) % stride of the partition, stride =
