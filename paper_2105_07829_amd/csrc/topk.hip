@@ -191,6 +191,7 @@ struct TopkMsgs {
   uint32_t groups_per_part, k_cap;
   uint64_t stride;
   int half;
+  uint32_t group_shift;     // log2 of the elements of a group (13 for the load pass)
   __device__ const uint8_t *rec(int i, uint32_t p) const { return msgs.ptr[i] + (uint64_t)p * stride; }
   __device__ uint32_t k_of(int i, uint32_t p) const {
     const uint32_t k = *reinterpret_cast<const uint32_t *>(rec(i, p));
@@ -222,20 +223,20 @@ struct TopkMsgs {
 // groups unset; readers clamp what they find to [0, k].
 // The same sweep adds the entries that fall into the chunks of the sample pass to `samp`
 // (zeroed before; about one entry in 250, so the global atomics do not matter, and the guess
-// needs no particular order of the sum).
+// needs no particular order of the sum); `samp` may be null.
 __global__ __launch_bounds__(kThreads) void topk_starts_kernel(Geo g, TopkMsgs m, uint32_t *starts, float *samp) {
   const uint32_t p = blockIdx.y, i = blockIdx.z;
   const uint32_t k = m.k_of(i, p);
   const uint32_t *idx = m.idx(i, p);
   uint32_t *tab = starts + ((uint64_t)i * g.P + p) * (m.groups_per_part + 1);
-  auto group = [&](uint32_t j) { const uint32_t q = j / kGroupElems; return q < m.groups_per_part ? q : m.groups_per_part - 1; };
+  auto group = [&](uint32_t j) { const uint32_t q = j >> m.group_shift; return q < m.groups_per_part ? q : m.groups_per_part - 1; };
   const uint32_t d = g.part_size(p);
   const uint32_t chunks = sample_chunks(d), stride = chunks ? (d / 8) / chunks : 1u;
   for (uint32_t t = blockIdx.x * kThreads + threadIdx.x; t <= k; t += gridDim.x * kThreads) {
     const uint32_t first = t == 0 ? 0u : group(idx[t - 1]) + 1;
     const uint32_t last = t == k ? m.groups_per_part : group(idx[t]);
     for (uint32_t q = first; q <= last && q <= m.groups_per_part; ++q) tab[q] = t;
-    if (t < k) {
+    if (samp && t < k) {
       const uint32_t j = idx[t], cj = j >> 3, c = cj / stride;
       if (c < chunks && cj == sample_chunk(c, stride)) atomicAdd(&samp[(uint64_t)p * kSample + c * 8 + (j & 7u)], m.value(i, p, t));
     }
@@ -863,6 +864,22 @@ __global__ __launch_bounds__(kThreads) void topk_emit_kernel(Geo g, float *buf, 
   }
 }
 
+// table[p * (tiles_per_part + 1) + tile] = the first entry of partition p's record that lies in
+// tile `tile` (of kTile elements) or after it; entry tiles_per_part = the number of entries.
+hipError_t topk_tile_starts(const Geo &g, const uint8_t *payload, bool half, uint32_t *table, hipStream_t stream) {
+  static_assert(kTile == 4096, "group_shift");
+  TopkMsgs m{};
+  m.msgs.ptr[0] = payload;
+  m.msgs.n = 1;
+  m.groups_per_part = g.tiles_per_part;
+  m.k_cap = g.k_cap;
+  m.stride = g.stride;
+  m.half = half ? 1 : 0;
+  m.group_shift = 12;
+  topk_starts_kernel<<<dim3((uint32_t)cdiv(g.k_cap + 1, kThreads), g.P, 1), kThreads, 0, stream>>>(g, m, table, nullptr);
+  return hipGetLastError();
+}
+
 hipError_t topk_encode(const Geo &g, const bpc_params_t &prm, const bpc_params_t *, const Source &src,
                        uint8_t *payload, const Workspace &ws, hipStream_t stream) {
   uint32_t *hist = ws.at<uint32_t>(ws.lay.hist);
@@ -894,7 +911,7 @@ hipError_t topk_encode(const Geo &g, const bpc_params_t &prm, const bpc_params_t
   } else {
     // server: Delta straight from the n messages (they are taken to have the format of `prm`)
     uint32_t *starts = ws.at<uint32_t>(ws.lay.starts);
-    const TopkMsgs m{src.msgs, src.residual, starts, (uint32_t)cdiv(g.tiles_per_part, kTpgLoad), g.k_cap, g.stride, half ? 1 : 0};
+    const TopkMsgs m{src.msgs, src.residual, starts, (uint32_t)cdiv(g.tiles_per_part, kTpgLoad), g.k_cap, g.stride, half ? 1 : 0, 13};
     float *samp = ws.at<float>(ws.lay.samp);
     const hipError_t e = fill_zero(samp, sizeof(float) * kSample * g.P, stream);
     if (e != hipSuccess) return e;

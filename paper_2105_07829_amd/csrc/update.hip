@@ -6,6 +6,8 @@
 #include "cluster_launch.hpp"
 #include "sources.hpp"
 
+#include <type_traits>
+
 namespace bpc {
 
 struct SignDec {
@@ -198,6 +200,59 @@ struct DenseDec {
   }
 };
 
+// Top-k and random-k messages without a dense decode: the entries of a tile of kTile elements
+// are one stretch of a list (top-k: of the record itself, whose entries come by ascending
+// index; random-k: of the record's draws binned per tile beforehand), found through a table of
+// where each tile's stretch starts, and laid out in LDS by the workgroup that has the tile.
+struct SparseTileDec {
+  const uint8_t *payload;
+  uint64_t stride;
+  uint32_t k_cap;
+  int mode;                  // 0: top-k, f32 values; 1: top-k, half values; 2: random-k pairs
+  const uint32_t *table;     // [partition][tile .. ], `table_stride` words a partition
+  uint32_t table_stride;
+  const uint2 *pairs;        // random-k: [partition][k_cap]
+  __device__ const float *dense_base() const { return nullptr; }
+  static constexpr int kLdsFloats = kTile;
+  __device__ void begin(uint32_t, float *) const {}
+  __device__ void begin_tile(uint32_t p, uint32_t tile, float *lds) const {
+    for (uint32_t q = threadIdx.x; q < kTile / 4; q += kThreads) reinterpret_cast<float4 *>(lds)[q] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    const uint8_t *rec = payload + (uint64_t)p * stride;
+    uint32_t k = *reinterpret_cast<const uint32_t *>(rec);
+    k = k > k_cap ? k_cap : k;
+    const uint32_t *tab = table + (uint64_t)p * table_stride;
+    uint32_t s = tab[tile], e = tab[tile + 1];
+    s = s < k ? s : k;
+    e = e < k ? e : k;
+    const uint32_t lo = tile * kTile;
+    __syncthreads();
+    if (mode == 2) {
+      const uint2 *list = pairs + (uint64_t)p * k_cap;
+      for (uint32_t q = s + threadIdx.x; q < e; q += kThreads) {
+        const uint2 ent = list[q];
+        if (ent.x - lo < (uint32_t)kTile) atomicAdd(&lds[ent.x - lo], __uint_as_float(ent.y));   // an index may repeat
+      }
+    } else {
+      const uint32_t *idx = reinterpret_cast<const uint32_t *>(rec + kHeaderBytes);
+      const uint8_t *val = rec + kHeaderBytes + 4 * ru4(k_cap);
+      for (uint32_t q = s + threadIdx.x; q < e; q += kThreads) {
+        const uint32_t rel = idx[q] - lo;
+        const float v = mode == 1 ? __half2float(reinterpret_cast<const __half *>(val)[q]) : reinterpret_cast<const float *>(val)[q];
+        if (rel < (uint32_t)kTile) lds[rel] = v;
+      }
+    }
+    __syncthreads();
+  }
+  __device__ void at4(const Geo &, uint32_t, uint32_t j, const TileBuf &, const float *lds, float out[4]) const {
+    const float4 f = *reinterpret_cast<const float4 *>(lds + (j & (kTile - 1)));
+    out[0] = f.x; out[1] = f.y; out[2] = f.z; out[3] = f.w;
+  }
+};
+template <class DEC, class = void>
+struct has_begin_tile : std::false_type {};
+template <class DEC>
+struct has_begin_tile<DEC, std::void_t<decltype(&DEC::begin_tile)>> : std::true_type {};
+
 struct OptArgs {
   float lr, beta1, beta2, eps, wd, bc1, bc2, phi_lo, phi_hi;
   const uint64_t *block_offsets;  // device, or NULL: blocks are the partitions
@@ -314,12 +369,25 @@ __global__ __launch_bounds__(kThreads) void adam_update_kernel(Geo g, DEC dec, f
   const uint32_t valid = d - tile * kTile < (uint32_t)kTile ? d - tile * kTile : (uint32_t)kTile;
   const float omb1 = 1.0f - o.beta1, omb2 = 1.0f - o.beta2;
   u32x4 xr[kURows], mr[kURows], vr[kURows];
+  if constexpr (has_begin_tile<DEC>::value) {
+    // the loads of m, v, x are requested first, so they are under way while the tile of the
+    // message is laid out in LDS
+#pragma unroll
+    for (int u = 0; u < kURows; ++u) {
+      mr[u] = row_buf(m + tile_base, valid, u * kURow, kURow).load16<kNonTemporal>(threadIdx.x * 16, 0);
+      vr[u] = row_buf(v + tile_base, valid, u * kURow, kURow).load16<kNonTemporal>(threadIdx.x * 16, 0);
+      xr[u] = row_buf(x + tile_base, valid, u * kURow, kURow).load16<kNonTemporal>(threadIdx.x * 16, 0);
+    }
+    dec.begin_tile(p, tile, lds);
+  }
   float gr[kURows][4];
 #pragma unroll
   for (int u = 0; u < kURows; ++u) {
-    mr[u] = row_buf(m + tile_base, valid, u * kURow, kURow).load16<kNonTemporal>(threadIdx.x * 16, 0);
-    vr[u] = row_buf(v + tile_base, valid, u * kURow, kURow).load16<kNonTemporal>(threadIdx.x * 16, 0);
-    xr[u] = row_buf(x + tile_base, valid, u * kURow, kURow).load16<kNonTemporal>(threadIdx.x * 16, 0);
+    if constexpr (!has_begin_tile<DEC>::value) {
+      mr[u] = row_buf(m + tile_base, valid, u * kURow, kURow).load16<kNonTemporal>(threadIdx.x * 16, 0);
+      vr[u] = row_buf(v + tile_base, valid, u * kURow, kURow).load16<kNonTemporal>(threadIdx.x * 16, 0);
+      xr[u] = row_buf(x + tile_base, valid, u * kURow, kURow).load16<kNonTemporal>(threadIdx.x * 16, 0);
+    }
     const uint32_t j = tile * kTile + u * kURow + threadIdx.x * 4;
     dec.at4(g, p, j, row_buf(dec.dense_base() + tile_base, valid, u * kURow, kURow), lds, gr[u]);
   }
@@ -635,6 +703,30 @@ hipError_t adaptive_update(const Geo &g, const bpc_params_t &prm, const uint8_t 
     default: break;
   }
   float *dense = ws.at<float>(ws.lay.dense);
+  if (opt.kind == BPC_OPT_ADAM && (prm.kind == BPC_TOPK || prm.kind == BPC_TOPK16 || prm.kind == BPC_RANDK)) {
+    // no dense decode: the update kernel lays each tile of the message out in LDS itself
+    OptArgs o{opt.lr, opt.beta1, opt.beta2, opt.eps, opt.weight_decay, opt.bias_corr1, opt.bias_corr2,
+              opt.phi_lo, opt.phi_hi, opt.block_offsets, opt.n_blocks};
+    if (prm.kind == BPC_RANDK) {
+      const uint64_t list_bytes = ((uint64_t)g.P * g.k_cap * sizeof(uint2) + 255) / 256 * 256;
+      const uint64_t table_bytes = (uint64_t)g.P * kRandkTableStride * sizeof(uint32_t);
+      if (g.tiles_per_part <= 1024 && list_bytes + table_bytes <= sizeof(float) * g.D) {
+        uint2 *lists = reinterpret_cast<uint2 *>(dense);   // (the dense workspace is free on this path)
+        uint32_t *table = reinterpret_cast<uint32_t *>(reinterpret_cast<uint8_t *>(dense) + list_bytes);
+        hipError_t e = randk_bin_tiles(g, prm, payload, lists, table, stream);
+        if (e != hipSuccess) return e;
+        adam_update_kernel<<<g.n_tiles, kThreads, 0, stream>>>(g, SparseTileDec{payload, g.stride, g.k_cap, 2, table, kRandkTableStride, lists}, x, m, v, o);
+        return hipGetLastError();
+      }
+    } else {
+      uint32_t *table = ws.at<uint32_t>(ws.lay.starts);
+      const bool half = prm.kind == BPC_TOPK16;
+      hipError_t e = topk_tile_starts(g, payload, half, table, stream);
+      if (e != hipSuccess) return e;
+      adam_update_kernel<<<g.n_tiles, kThreads, 0, stream>>>(g, SparseTileDec{payload, g.stride, g.k_cap, half ? 1 : 0, table, g.tiles_per_part + 1, nullptr}, x, m, v, o);
+      return hipGetLastError();
+    }
+  }
   hipError_t e = decode_dense(g, prm, payload, dense, stream);
   if (e != hipSuccess) return e;
   return run_update(g, DenseDec{dense}, x, m, v, opt, norms, ws, stream);
