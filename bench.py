@@ -238,8 +238,8 @@ def cpu_baseline(name, w, n_parts, n_steps, synth):
 
 def recorded_traffic(workload, stage):
     """HBM bytes per launch of a stage as measured with rocprofv3 counters (profiles/), or None."""
-    path = os.path.join(ROOT, "profiles", f"bench_{workload}_dither.txt" if workload == "bert_large"
-                        else f"bench_{workload}.txt")
+    names = {"bert_large": "bench_bert_large_dither.txt", "resnet50": "bench_resnet50_topk.txt"}
+    path = os.path.join(ROOT, "profiles", names.get(workload, f"bench_{workload}.txt"))
     try:
         for line in open(path):
             f = line.split()
