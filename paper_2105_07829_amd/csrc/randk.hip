@@ -106,23 +106,27 @@ __global__ __launch_bounds__(kRsThreads) void randk_sum_kernel(Geo g, WorkerMsgs
 // starts; `randk_sum_binned_kernel` then adds up only the pairs of its own slice, so no draw is
 // regenerated more than twice and slices can be small (8192 elements: several workgroups a
 // compute unit, loads and stores of different slices overlap).
-constexpr int kRbThreads = 1024;
+constexpr int kRbThreads = 1024;    // (workgroups of 256, four bins a thread, took a third longer)
 constexpr uint32_t kRbMaxBins = 1024;   // slices of a partition, at most
 constexpr int kRbSumThreads = 256;
 
+// OUT: the draws of a message still to be written (stream i of `msgs`, k by the rule): the
+// pairs are (index, number of the draw).
+template <bool OUT>
 __global__ __launch_bounds__(kRbThreads) void randk_bin_kernel(Geo g, WorkerMsgs msgs, RandkScales sc, uint32_t slice_shift,
                                                                uint2 *lists, uint32_t *table) {
   __shared__ uint32_t cnt[kRbMaxBins];
-  __shared__ uint32_t scan[kRbThreads / 64];
+  __shared__ uint32_t scan[kRbThreads];
   const uint32_t p = blockIdx.x, i = blockIdx.y;
   const uint32_t d = g.part_size(p);
-  const uint8_t *rec = msgs.ptr[i] + (uint64_t)p * g.stride;
-  uint32_t k = *reinterpret_cast<const uint32_t *>(rec);
+  const uint8_t *rec = OUT ? nullptr : msgs.ptr[i] + (uint64_t)p * g.stride;
+  uint32_t k = OUT ? (uint32_t)k_of_device(g, p) : *reinterpret_cast<const uint32_t *>(rec);
   k = k > g.k_cap ? g.k_cap : k;
   const float *val = reinterpret_cast<const float *>(rec + kHeaderBytes);
   const float scale = sc.value_scale[i] >= 0.0f ? sc.value_scale[i] : (float)d / (float)k;
   const Philox rng(msgs.seed[i], msgs.stream_id[i], p);
-  cnt[threadIdx.x] = 0;
+  constexpr int kMine = kRbMaxBins / kRbThreads;   // bins a thread owns: 4 consecutive ones
+  for (int b = threadIdx.x; b < (int)kRbMaxBins; b += kRbThreads) cnt[b] = 0;
   __syncthreads();
   for (uint32_t t4 = threadIdx.x; 4 * t4 < k; t4 += kRbThreads) {
     uint32_t rnd[4];
@@ -132,12 +136,22 @@ __global__ __launch_bounds__(kRbThreads) void randk_bin_kernel(Geo g, WorkerMsgs
       if (4 * t4 + c < k) atomicAdd(&cnt[(uint32_t)(((uint64_t)rnd[c] * d) >> 32) >> slice_shift], 1u);
   }
   __syncthreads();
+  uint32_t mine[kMine], local = 0;
+#pragma unroll
+  for (int b = 0; b < kMine; ++b) {
+    mine[b] = cnt[threadIdx.x * kMine + b];
+    local += mine[b];
+  }
   uint32_t total;
-  const uint32_t start = block_exclusive_scan<kRbThreads>(cnt[threadIdx.x], scan, &total);
+  uint32_t start = block_exclusive_scan<kRbThreads>(local, scan, &total);
   uint32_t *tab = table + ((uint64_t)i * g.P + p) * (kRbMaxBins + 1);
-  tab[threadIdx.x] = start;
+#pragma unroll
+  for (int b = 0; b < kMine; ++b) {
+    tab[threadIdx.x * kMine + b] = start;
+    cnt[threadIdx.x * kMine + b] = start;   // from here on: where the slice's next pair goes
+    start += mine[b];
+  }
   if (threadIdx.x == 0) tab[kRbMaxBins] = total;
-  cnt[threadIdx.x] = start;   // from here on: where the slice's next pair goes
   __syncthreads();
   uint2 *list = lists + ((uint64_t)i * g.P + p) * g.k_cap;
   for (uint32_t t4 = threadIdx.x; 4 * t4 < k; t4 += kRbThreads) {
@@ -149,15 +163,88 @@ __global__ __launch_bounds__(kRbThreads) void randk_bin_kernel(Geo g, WorkerMsgs
       if (t < k) {
         const uint32_t j = (uint32_t)(((uint64_t)rnd[c] * d) >> 32);
         const uint32_t pos = atomicAdd(&cnt[j >> slice_shift], 1u);
-        list[pos] = make_uint2(j, __float_as_uint(scale * val[t]));
+        list[pos] = make_uint2(j, OUT ? t : __float_as_uint(scale * val[t]));
       }
+    }
+  }
+}
+
+// The message's draws that fall into the slice [lo, lo + len) of v, which the workgroup holds in
+// `acc` (LDS): val_t = v[idx_t] goes to the record, then every draw takes scale * val_t off its
+// element (all reads first: draws of one index read the same value).  `list`: (index, t) pairs,
+// those of this slice at [from, to).  All threads of the workgroup; leaves acc = the residual.
+template <int THREADS>
+__device__ inline void randk_apply_draws(float *acc, uint32_t lo, const uint2 *list, uint32_t from, uint32_t to, float scale,
+                                         float *val) {
+  __syncthreads();
+  const bool mine = from + threadIdx.x < to;
+  uint2 ent = make_uint2(lo, 0u);
+  float v = 0.0f;
+  if (mine) {
+    ent = list[from + threadIdx.x];
+    v = acc[ent.x - lo];
+    val[ent.y] = v;
+  }
+  for (uint32_t q = from + THREADS + threadIdx.x; q < to; q += THREADS) {   // (rare: more draws than threads)
+    const uint2 e2 = list[q];
+    val[e2.y] = acc[e2.x - lo];
+  }
+  __syncthreads();
+  if (mine) atomicAdd(&acc[ent.x - lo], -(scale * v));
+  for (uint32_t q = from + THREADS + threadIdx.x; q < to; q += THREADS) {
+    const uint2 e2 = list[q];
+    atomicAdd(&acc[e2.x - lo], -(scale * val[e2.y]));
+  }
+  __syncthreads();
+}
+
+// Worker with error feedback in one pass over the data: a workgroup forms its tile of q = g + e
+// in LDS, serves the draws that fall into it (binned per tile by `randk_bin_kernel<true>`) and
+// writes the tile of the residual.
+template <class SRC>
+__global__ __launch_bounds__(kThreads) void randk_tile_kernel(Geo g, SRC src, float *buf, uint8_t *payload, float value_scale,
+                                                              const uint2 *lists, const uint32_t *table) {
+  __shared__ float acc[kTile];
+  const uint32_t p = blockIdx.x / g.tiles_per_part, tile = blockIdx.x % g.tiles_per_part;
+  const uint32_t d = g.part_size(p);
+  const uint32_t lo = tile * kTile;
+  if (lo >= d) return;
+  const uint32_t k = (uint32_t)k_of_device(g, p);
+  if (tile == 0 && threadIdx.x == 0) {
+    uint32_t *hdr = reinterpret_cast<uint32_t *>(payload + (uint64_t)p * g.stride);
+    hdr[0] = k; hdr[1] = 0; hdr[2] = 0; hdr[3] = 0;
+  }
+  const uint32_t *tab = table + (uint64_t)p * (kRbMaxBins + 1);
+  const uint32_t from = tab[tile], to = tab[tile + 1];
+#pragma unroll
+  for (int c = 0; c < kTile / (kThreads * 8); ++c) {
+    const uint32_t r0 = c * (kThreads * 8) + threadIdx.x * 8;
+    float v[8] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+    if (lo + r0 < d) source_at8(src, g, p, lo + r0, d, nullptr, v);
+    reinterpret_cast<float4 *>(acc + r0)[0] = make_float4(v[0], v[1], v[2], v[3]);
+    reinterpret_cast<float4 *>(acc + r0)[1] = make_float4(v[4], v[5], v[6], v[7]);
+  }
+  const float scale = value_scale >= 0.0f ? value_scale : (float)d / (float)k;
+  float *val = reinterpret_cast<float *>(payload + (uint64_t)p * g.stride + kHeaderBytes);
+  randk_apply_draws<kThreads>(acc, lo, lists + (uint64_t)p * g.k_cap, from < k ? from : k, to < k ? to : k, scale, val);
+  const uint64_t base = g.part_base(p) + lo;
+#pragma unroll
+  for (int c = 0; c < kTile / (kThreads * 8); ++c) {
+    const uint32_t r0 = c * (kThreads * 8) + threadIdx.x * 8;
+    if (lo + r0 + 8 <= d) {
+      reinterpret_cast<float4 *>(buf + base + r0)[0] = reinterpret_cast<const float4 *>(acc + r0)[0];
+      reinterpret_cast<float4 *>(buf + base + r0)[1] = reinterpret_cast<const float4 *>(acc + r0)[1];
+    } else {
+      for (int e = 0; e < 8; ++e)
+        if (lo + r0 + e < d) buf[base + r0 + e] = acc[r0 + e];
     }
   }
 }
 
 __global__ __launch_bounds__(kRbSumThreads) void randk_sum_binned_kernel(Geo g, int n, float inv_n, uint32_t slice_shift,
                                                                          const uint2 *lists, const uint32_t *table,
-                                                                         const float *res, float *buf) {
+                                                                         const float *res, float *buf, uint8_t *payload,
+                                                                         float value_scale) {
   extern __shared__ float acc[];  // 1 << slice_shift
   __shared__ uint32_t from[kMaxWorkers], to[kMaxWorkers];
   const uint32_t slice = 1u << slice_shift;
@@ -193,18 +280,37 @@ __global__ __launch_bounds__(kRbSumThreads) void randk_sum_binned_kernel(Geo g, 
     __syncthreads();
   }
   const uint64_t at = g.part_base(p) + lo;
-  for (uint32_t q = threadIdx.x * 4; q < len; q += kRbSumThreads * 4) {
-    if (q + 4 <= len) {
-      const float4 a = *reinterpret_cast<const float4 *>(acc + q);
-      float4 r = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-      if (res) r = *reinterpret_cast<const float4 *>(res + at + q);
-      const float m0 = a.x * inv_n, m1 = a.y * inv_n, m2 = a.z * inv_n, m3 = a.w * inv_n;
-      *reinterpret_cast<float4 *>(buf + at + q) = res ? make_float4(m0 + r.x, m1 + r.y, m2 + r.z, m3 + r.w) : make_float4(m0, m1, m2, m3);
-    } else {
-      for (uint32_t e = q; e < len; ++e) {
-        const float mean = acc[e] * inv_n;
-        buf[at + e] = res ? mean + res[at + e] : mean;
+  {
+    // Delta in LDS, the recompression's draws served from there (list n is the output's),
+    // and what is left is the new residual
+    for (uint32_t q = threadIdx.x * 4; q < slice; q += kRbSumThreads * 4) {
+      float4 a = *reinterpret_cast<const float4 *>(acc + q);
+      float r[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+      if (res) {
+        if (q + 4 <= len) {
+          const float4 f = *reinterpret_cast<const float4 *>(res + at + q);
+          r[0] = f.x; r[1] = f.y; r[2] = f.z; r[3] = f.w;
+        } else {
+          for (uint32_t e = 0; e < 4; ++e) r[e] = q + e < len ? res[at + q + e] : 0.0f;
+        }
       }
+      const float m0 = a.x * inv_n, m1 = a.y * inv_n, m2 = a.z * inv_n, m3 = a.w * inv_n;
+      *reinterpret_cast<float4 *>(acc + q) = res ? make_float4(m0 + r[0], m1 + r[1], m2 + r[2], m3 + r[3]) : make_float4(m0, m1, m2, m3);
+    }
+    const uint32_t k = (uint32_t)k_of_device(g, p);
+    if (s == 0 && threadIdx.x == 0) {
+      uint32_t *hdr = reinterpret_cast<uint32_t *>(payload + (uint64_t)p * g.stride);
+      hdr[0] = k; hdr[1] = 0; hdr[2] = 0; hdr[3] = 0;
+    }
+    const uint32_t *tab = table + ((uint64_t)n * g.P + p) * (kRbMaxBins + 1);
+    const uint32_t f0 = tab[s] < k ? tab[s] : k, t0 = tab[s + 1] < k ? tab[s + 1] : k;
+    const float scale = value_scale >= 0.0f ? value_scale : (float)d / (float)k;
+    randk_apply_draws<kRbSumThreads>(acc, lo, lists + ((uint64_t)n * g.P + p) * g.k_cap, f0, t0, scale,
+                                     reinterpret_cast<float *>(payload + (uint64_t)p * g.stride + kHeaderBytes));
+    for (uint32_t q = threadIdx.x * 4; q < len; q += kRbSumThreads * 4) {
+      if (q + 4 <= len) *reinterpret_cast<float4 *>(buf + at + q) = *reinterpret_cast<const float4 *>(acc + q);
+      else
+        for (uint32_t e = q; e < len; ++e) buf[at + e] = acc[e];
     }
   }
 }
@@ -271,7 +377,7 @@ hipError_t randk_bin_tiles(const Geo &g, const bpc_params_t &prm, const uint8_t 
   msgs.n = 1;
   RandkScales sc{};
   sc.value_scale[0] = prm.value_scale;
-  randk_bin_kernel<<<dim3(g.P, 1), kRbThreads, 0, stream>>>(g, msgs, sc, 12, lists, table);
+  randk_bin_kernel<false><<<dim3(g.P, 1), kRbThreads, 0, stream>>>(g, msgs, sc, 12, lists, table);
   return hipGetLastError();
 }
 
@@ -280,6 +386,15 @@ hipError_t randk_encode(const Geo &g, const bpc_params_t &prm, const bpc_params_
   float *dense = ws.at<float>(ws.lay.dense);
   float *buf = src.residual ? src.residual : dense;
   dim3 grid((uint32_t)cdiv(g.k_cap, kThreads), g.P);
+  // the message's own draws, for the kernels that serve them from LDS
+  WorkerMsgs out_stream{};
+  out_stream.seed[0] = prm.seed;
+  out_stream.stream_id[0] = prm.stream_id;
+  out_stream.n = 1;
+  RandkScales out_scale{};
+  out_scale.value_scale[0] = prm.value_scale;
+  const uint64_t one_list = ((uint64_t)g.P * g.k_cap * sizeof(uint2) + 255) / 256 * 256;
+  const uint64_t one_table = ((uint64_t)g.P * (kRbMaxBins + 1) * sizeof(uint32_t) + 255) / 256 * 256;
   if (src.grad) {
     if (!src.residual) {
       if (src.dtype == BPC_F16)
@@ -288,6 +403,19 @@ hipError_t randk_encode(const Geo &g, const bpc_params_t &prm, const bpc_params_
       else
         randk_gather_src_kernel<<<grid, kThreads, 0, stream>>>(g, GradSource<float>{(const float *)src.grad, nullptr},
                                                                payload, prm.seed, prm.stream_id);
+      return hipGetLastError();
+    }
+    if (g.tiles_per_part <= kRbMaxBins && one_list + one_table <= sizeof(float) * g.D) {
+      // one pass over the data (q goes to the residual buffer, so the dense workspace is free for the list)
+      uint2 *lists = reinterpret_cast<uint2 *>(dense);
+      uint32_t *table = reinterpret_cast<uint32_t *>(reinterpret_cast<uint8_t *>(dense) + one_list);
+      randk_bin_kernel<true><<<dim3(g.P, 1), kRbThreads, 0, stream>>>(g, out_stream, out_scale, 12, lists, table);
+      if (src.dtype == BPC_F16)
+        randk_tile_kernel<<<g.n_tiles, kThreads, 0, stream>>>(g, GradSource<__half>{(const __half *)src.grad, src.residual}, buf,
+                                                              payload, prm.value_scale, lists, table);
+      else
+        randk_tile_kernel<<<g.n_tiles, kThreads, 0, stream>>>(g, GradSource<float>{(const float *)src.grad, src.residual}, buf,
+                                                              payload, prm.value_scale, lists, table);
       return hipGetLastError();
     }
     if (src.dtype == BPC_F16)
@@ -321,29 +449,27 @@ hipError_t randk_encode(const Geo &g, const bpc_params_t &prm, const bpc_params_
       // slices of 8192 elements, larger (up to what LDS holds) if a partition would have more than kRbMaxBins of them
       uint32_t slice_shift = 13;
       while (slice_shift < 15 && cdiv(g.part_elems, 1ull << slice_shift) > kRbMaxBins) ++slice_shift;
-      const uint64_t np = (uint64_t)src.msgs.n * g.P;
-      const uint64_t list_bytes = np * g.k_cap * sizeof(uint2), table_bytes = np * (kRbMaxBins + 1) * sizeof(uint32_t);
+      const int n = src.msgs.n;
+      // n lists and tables for the messages and one more for the output's draws, in the dense
+      // workspace (free: Delta goes to the residual buffer)
       const bool binned = src.residual != nullptr && cdiv(g.part_elems, 1ull << slice_shift) <= kRbMaxBins &&
-                          list_bytes + table_bytes + 256 <= sizeof(float) * g.D;
-      if (binned) {
-        // (Delta goes to the residual buffer, so the dense workspace is free)
+                          (n + 1) * (one_list + one_table) <= sizeof(float) * g.D;
+      static bool lds2_ok = hipFuncSetAttribute(reinterpret_cast<const void *>(&randk_sum_binned_kernel),
+                                                hipFuncAttributeMaxDynamicSharedMemorySize, (4u << 15)) == hipSuccess;
+      if (binned && (lds2_ok || slice_shift == 13)) {
         uint2 *lists = reinterpret_cast<uint2 *>(dense);
-        uint32_t *table = reinterpret_cast<uint32_t *>(reinterpret_cast<uint8_t *>(dense) + (list_bytes + 255) / 256 * 256);
-        static bool lds2_ok = hipFuncSetAttribute(reinterpret_cast<const void *>(&randk_sum_binned_kernel),
-                                                  hipFuncAttributeMaxDynamicSharedMemorySize, (4u << 15)) == hipSuccess;
-        if (lds2_ok || slice_shift == 13) {
-          randk_bin_kernel<<<dim3(g.P, src.msgs.n), kRbThreads, 0, stream>>>(g, src.msgs, sc, slice_shift, lists, table);
-          const uint32_t slices = g.P * (uint32_t)cdiv(g.part_elems, 1ull << slice_shift);
-          randk_sum_binned_kernel<<<slices, kRbSumThreads, sizeof(float) << slice_shift, stream>>>(
-              g, src.msgs.n, src.msgs.inv_n, slice_shift, lists, table, src.residual, buf);
-          goto summed;
-        }
+        uint32_t *table = reinterpret_cast<uint32_t *>(reinterpret_cast<uint8_t *>(dense) + (n + 1) * one_list);
+        randk_bin_kernel<false><<<dim3(g.P, n), kRbThreads, 0, stream>>>(g, src.msgs, sc, slice_shift, lists, table);
+        randk_bin_kernel<true><<<dim3(g.P, 1), kRbThreads, 0, stream>>>(g, out_stream, out_scale, slice_shift,
+                                                                         lists + (uint64_t)n * g.P * g.k_cap,
+                                                                         table + (uint64_t)n * g.P * (kRbMaxBins + 1));
+        const uint32_t slices = g.P * (uint32_t)cdiv(g.part_elems, 1ull << slice_shift);
+        randk_sum_binned_kernel<<<slices, kRbSumThreads, sizeof(float) << slice_shift, stream>>>(
+            g, n, src.msgs.inv_n, slice_shift, lists, table, src.residual, buf, payload, prm.value_scale);
+        return hipGetLastError();
       }
-      {
-        const uint32_t slices = g.P * (uint32_t)cdiv(g.part_elems, kRsSlice);
-        randk_sum_kernel<<<slices, kRsThreads, kRsSlice * sizeof(float), stream>>>(g, src.msgs, sc, src.residual, buf);
-      }
-    summed:;
+      const uint32_t slices = g.P * (uint32_t)cdiv(g.part_elems, kRsSlice);
+      randk_sum_kernel<<<slices, kRsThreads, kRsSlice * sizeof(float), stream>>>(g, src.msgs, sc, src.residual, buf);
     }
   }
   randk_gather_kernel<<<grid, kThreads, 0, stream>>>(g, buf, payload, prm.seed, prm.stream_id);
