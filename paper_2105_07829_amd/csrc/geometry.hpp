@@ -116,7 +116,7 @@ struct WsLayout {
   size_t partials;   // double[n_tiles]: per-tile partial norms
   size_t dense;      // float[D]: q / Delta / decoded message when no caller buffer can hold it
   size_t hist;       // u32[P*kTopkHistWords]: top-k radix histograms (2048 + 1024 + 1024 bins)
-  size_t state;      // u32[P*8]: top-k selection state
+  size_t state;      // u32[P*8 + 8]: top-k selection state; a barrier counter
   size_t guess;      // u32[P]: top-k key from which elements go to a partition's short list
   size_t starts;     // u32[kMaxWorkers * P * (groups of 8192 elements per partition + 1)]: where each group's
                      // entries start in each worker's top-k message (server side)
@@ -141,7 +141,7 @@ inline WsLayout ws_layout(const bpc_params_t *p, uint64_t D) {
   w.partials = take(sizeof(double) * (size_t)g.n_tiles);
   w.dense = take(sparse ? sizeof(float) * (size_t)D : 0);
   w.hist = take(topk ? sizeof(uint32_t) * kTopkHistWords * (size_t)g.P : 0);
-  w.state = take(topk ? sizeof(uint32_t) * 8 * (size_t)g.P : 0);
+  w.state = take(topk ? sizeof(uint32_t) * (8 * (size_t)g.P + 8) : 0);
   w.guess = take(topk ? sizeof(uint32_t) * (size_t)g.P : 0);
   w.starts = take(topk ? sizeof(uint32_t) * kMaxWorkers * (size_t)g.P * (cdiv(p->part_elems, 8192) + 1) : 0);
   w.samp = take(topk ? sizeof(float) * 4096 * (size_t)g.P : 0);

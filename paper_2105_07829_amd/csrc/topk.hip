@@ -35,6 +35,7 @@
 // the messages list their entries by ascending index, so the load pass sums the stretch of each
 // message that falls into its group of 8192 elements in LDS, and the sample pass collects the
 // sums of the sampled chunks in one sweep over the messages.
+#include "cluster.hpp"
 #include "sources.hpp"
 
 namespace bpc {
@@ -342,16 +343,17 @@ struct TopkMsgsSampleSource : TopkMsgs {
 // ones, hence chunks rather than single elements.
 template <class SRC>
 __global__ __launch_bounds__(kThreads) void topk_sample_kernel(Geo g, SRC src, uint32_t *hist, uint32_t *state,
-                                                               uint32_t *guess, int sample) {
+                                                               uint32_t *guess, int sample, uint32_t *status) {
   __shared__ float lds[SRC::kLdsFloats];
   __shared__ uint32_t h[kBins1];
+  if (blockIdx.x == 0 && threadIdx.x == 0) status[0] = 0;   // (set by a wait of the long form that gave up)
   __shared__ uint32_t scan[kThreads];
   __shared__ uint32_t sel[2];
   {
     const size_t i0 = (size_t)blockIdx.x * kThreads + threadIdx.x, step = (size_t)gridDim.x * kThreads;
     uint4 *h16 = reinterpret_cast<uint4 *>(hist);
     for (size_t q = i0; q < (size_t)kTopkHistWords * g.P / 4; q += step) h16[q] = make_uint4(0, 0, 0, 0);
-    for (size_t q = i0; q < 8ull * g.P; q += step) state[q] = 0;
+    for (size_t q = i0; q < 8ull * g.P + 8; q += step) state[q] = 0;   // (8 spare words: the long form's barrier counter)
   }
   const uint32_t p = blockIdx.x;
   if (p >= g.P) return;
@@ -523,8 +525,8 @@ __device__ inline void keys4(const float *part, uint32_t j, uint32_t d, uint32_t
 // LEVEL 2: keys whose top 11 bits equal the prefix, histogram of the next 10 bits.
 // LEVEL 3: keys whose top 21 bits equal the prefix, histogram of the last 10 bits.
 template <int LEVEL>
-__global__ __launch_bounds__(kThreads) void topk_hist_kernel(Geo g, const float *buf, uint32_t *hist, uint32_t *state,
-                                                             uint32_t n_groups, int gated) {
+__device__ inline void topk_hist_body(const Geo &g, const float *buf, uint32_t *hist, uint32_t *state, uint32_t n_groups,
+                                      int gated) {
   __shared__ uint32_t h[kBins23];
   __shared__ uint32_t scan[kThreads];
   __shared__ uint32_t sel[2];
@@ -555,12 +557,17 @@ __global__ __launch_bounds__(kThreads) void topk_hist_kernel(Geo g, const float 
   }
 }
 
+template <int LEVEL>
+__global__ __launch_bounds__(kThreads) void topk_hist_kernel(Geo g, const float *buf, uint32_t *hist, uint32_t *state,
+                                                             uint32_t n_groups) {
+  topk_hist_body<LEVEL>(g, buf, hist, state, n_groups, 0);
+}
+
 // Per tile: number of keys above the threshold and equal to it.  The first workgroup of a
 // partition also records the threshold key T and the number r of keys equal to T that are
 // kept, for the compaction.
-__global__ __launch_bounds__(kThreads) void topk_count_kernel(Geo g, const float *buf, const uint32_t *hist,
-                                                              uint32_t *state, uint32_t *tilecnt, uint32_t n_groups,
-                                                              int gated) {
+__device__ inline void topk_count_body(const Geo &g, const float *buf, const uint32_t *hist, uint32_t *state,
+                                       uint32_t *tilecnt, uint32_t n_groups, int gated) {
   __shared__ uint32_t red[2][kThreads / 64];
   __shared__ uint32_t scan[kThreads];
   __shared__ uint32_t sel[2];
@@ -600,6 +607,11 @@ __global__ __launch_bounds__(kThreads) void topk_count_kernel(Geo g, const float
     }
     __syncthreads();
   }
+}
+
+__global__ __launch_bounds__(kThreads) void topk_count_kernel(Geo g, const float *buf, const uint32_t *hist,
+                                                              uint32_t *state, uint32_t *tilecnt, uint32_t n_groups) {
+  topk_count_body(g, buf, hist, state, tilecnt, n_groups, 0);
 }
 
 // Header of partition p's record; for the half-value form also the zeros the format wants from
@@ -785,9 +797,8 @@ __global__ __launch_bounds__(kSelThreads) void topk_list_select_kernel(Geo g, fl
 // HALF: values are sent as halves (round to nearest even) and a kept slot of the buffer keeps
 // what the rounding dropped instead of 0.
 template <bool HALF>
-__global__ __launch_bounds__(kThreads) void topk_emit_kernel(Geo g, float *buf, const uint32_t *state,
-                                                             const uint32_t *tilecnt, uint8_t *payload,
-                                                             int zero_selected, uint32_t n_items, int gated) {
+__device__ inline void topk_emit_body(const Geo &g, float *buf, const uint32_t *state, const uint32_t *tilecnt,
+                                      uint8_t *payload, int zero_selected, uint32_t n_items, int gated) {
   __shared__ uint32_t scan[kThreads];
   __shared__ uint32_t before[2][kThreads / 64];
   constexpr int kPer = kTile / kThreads;
@@ -864,6 +875,60 @@ __global__ __launch_bounds__(kThreads) void topk_emit_kernel(Geo g, float *buf, 
   }
 }
 
+template <bool HALF>
+__global__ __launch_bounds__(kThreads) void topk_emit_kernel(Geo g, float *buf, const uint32_t *state,
+                                                             const uint32_t *tilecnt, uint8_t *payload,
+                                                             int zero_selected, uint32_t n_items) {
+  topk_emit_body<HALF>(g, buf, state, tilecnt, payload, zero_selected, n_items, 0);
+}
+
+// All workgroups of a grid that is resident as a whole meet here: what they wrote before is
+// visible to all of them after (release fence, one arrival each on a counter, acquire fence).
+// The wait is bounded like those of cluster.hpp: a workgroup that gives up sets the status word.
+__device__ inline void topk_grid_barrier(uint32_t *counter, uint32_t round, uint32_t *status) {
+  __threadfence();
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    atomicAdd(counter, 1u);
+    const uint32_t target = round * gridDim.x;
+    int spins = 0;
+    while (__hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+      if (++spins > kSpinLimit) {
+        atomicOr(status, 1u);
+        break;
+      }
+      __builtin_amdgcn_s_sleep(16);
+    }
+  }
+  __syncthreads();
+  __threadfence();
+}
+
+// The long form behind the short-list form, as one launch: returns at once unless some
+// partition was left to it (the usual case: one launch and one read instead of four of each),
+// else runs the four passes for those partitions with the whole grid meeting in between.
+// The grid is resident as a whole (the host sizes it by occupancy).  `counter`: zero at launch.
+template <bool HALF>
+__global__ __launch_bounds__(kThreads) void topk_long_form_kernel(Geo g, float *buf, uint32_t *hist, uint32_t *state,
+                                                                  uint32_t *tilecnt, uint8_t *payload, int zero_selected,
+                                                                  uint32_t n2, uint32_t n3, uint32_t nc, uint32_t ne,
+                                                                  uint32_t *counter, uint32_t *status) {
+  __shared__ uint32_t any;
+  if (threadIdx.x == 0) any = 0;
+  __syncthreads();
+  for (uint32_t p = threadIdx.x; p < g.P; p += kThreads)
+    if (state[p * 8 + kStLong]) any = 1;
+  __syncthreads();
+  if (!any) return;   // (the same answer in every workgroup: the flags were written by the kernel before)
+  topk_hist_body<2>(g, buf, hist, state, n2, 1);
+  topk_grid_barrier(counter, 1, status);
+  topk_hist_body<3>(g, buf, hist, state, n3, 1);
+  topk_grid_barrier(counter, 2, status);
+  topk_count_body(g, buf, hist, state, tilecnt, nc, 1);
+  topk_grid_barrier(counter, 3, status);
+  topk_emit_body<HALF>(g, buf, state, tilecnt, payload, zero_selected, ne, 1);
+}
+
 // table[p * (tiles_per_part + 1) + tile] = the first entry of partition p's record that lies in
 // tile `tile` (of kTile elements) or after it; entry tiles_per_part = the number of entries.
 hipError_t topk_tile_starts(const Geo &g, const uint8_t *payload, bool half, uint32_t *table, hipStream_t stream) {
@@ -894,10 +959,16 @@ hipError_t topk_encode(const Geo &g, const bpc_params_t &prm, const bpc_params_t
   uint32_t *cand_val = cand_idx + (size_t)kTopkListCap * g.P;
   // the short-list form wants room for the k winners and as many again; the select pass gives
   // each group of tiles of a partition one thread
-  const int short_list = g.k_cap <= kTopkListCap / 2 && cdiv(g.tiles_per_part, kTpgLoad) <= (uint64_t)kSelThreads;
+  // (and the long form behind it is one resident kernel: its grid comes from the occupancy query)
+  const void *long_fn = half ? reinterpret_cast<const void *>(&topk_long_form_kernel<true>)
+                             : reinterpret_cast<const void *>(&topk_long_form_kernel<false>);
+  static int capacity[2] = {0, 0};
+  if (capacity[half] == 0) capacity[half] = cluster_capacity(long_fn, kThreads, 0);
+  const int short_list = g.k_cap <= kTopkListCap / 2 && cdiv(g.tiles_per_part, kTpgLoad) <= (uint64_t)kSelThreads &&
+                         capacity[half] > 0;
   const uint32_t sample_grid = g.P > 64 ? g.P : 64, load_grid = group_count(g, kTpgLoad);
   auto first_two = [&](auto s_sample, auto s_load) {
-    topk_sample_kernel<<<sample_grid, kThreads, 0, stream>>>(g, s_sample, hist, state, guess, short_list);
+    topk_sample_kernel<<<sample_grid, kThreads, 0, stream>>>(g, s_sample, hist, state, guess, short_list, ws.at<uint32_t>(ws.lay.status));
     topk_load_hist1_kernel<<<load_grid, kThreads, 0, stream>>>(g, s_load, buf, hist, state, guess, tilecnt, cand_idx, cand_val);
   };
   if (src.grad) {
@@ -919,19 +990,30 @@ hipError_t topk_encode(const Geo &g, const bpc_params_t &prm, const bpc_params_t
     first_two(TopkMsgsSampleSource{m, samp}, TopkMsgsGroupSource{m});
   }
   const int zero_selected = src.residual != nullptr;
-  const int gated = short_list;
   if (short_list) {
     if (half) topk_list_select_kernel<true><<<g.P, kSelThreads, 0, stream>>>(g, buf, state, hist, tilecnt, cand_idx, cand_val, payload, zero_selected);
     else topk_list_select_kernel<false><<<g.P, kSelThreads, 0, stream>>>(g, buf, state, hist, tilecnt, cand_idx, cand_val, payload, zero_selected);
   }
-  auto grid_of = [&](uint32_t n) { return gated && n > kGatedGrid ? kGatedGrid : n; };
   const uint32_t n2 = group_count(g, kTpgHist2), n3 = group_count(g, kTpgHist3), nc = group_count(g, kTpgCount);
   const uint32_t ne = g.P * g.tiles_per_part;
-  topk_hist_kernel<2><<<grid_of(n2), kThreads, 0, stream>>>(g, buf, hist, state, n2, gated);
-  topk_hist_kernel<3><<<grid_of(n3), kThreads, 0, stream>>>(g, buf, hist, state, n3, gated);
-  topk_count_kernel<<<grid_of(nc), kThreads, 0, stream>>>(g, buf, hist, state, tilecnt, nc, gated);
-  if (half) topk_emit_kernel<true><<<grid_of(ne), kThreads, 0, stream>>>(g, buf, state, tilecnt, payload, zero_selected, ne, gated);
-  else topk_emit_kernel<false><<<grid_of(ne), kThreads, 0, stream>>>(g, buf, state, tilecnt, payload, zero_selected, ne, gated);
+  if (short_list) {
+    // the long form for the partitions the short list could not take: one resident kernel
+    const uint32_t grid = (uint32_t)capacity[half] < kGatedGrid ? (uint32_t)capacity[half] : kGatedGrid;
+    uint32_t *counter = state + 8ull * g.P;
+    uint32_t *status = ws.at<uint32_t>(ws.lay.status);
+    hipError_t e = cluster_launch_begin(stream);
+    if (e != hipSuccess) return e;
+    if (half) topk_long_form_kernel<true><<<grid, kThreads, 0, stream>>>(g, buf, hist, state, tilecnt, payload, zero_selected, n2, n3, nc, ne, counter, status);
+    else topk_long_form_kernel<false><<<grid, kThreads, 0, stream>>>(g, buf, hist, state, tilecnt, payload, zero_selected, n2, n3, nc, ne, counter, status);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    return cluster_launch_end(stream);
+  }
+  topk_hist_kernel<2><<<n2, kThreads, 0, stream>>>(g, buf, hist, state, n2);
+  topk_hist_kernel<3><<<n3, kThreads, 0, stream>>>(g, buf, hist, state, n3);
+  topk_count_kernel<<<nc, kThreads, 0, stream>>>(g, buf, hist, state, tilecnt, nc);
+  if (half) topk_emit_kernel<true><<<ne, kThreads, 0, stream>>>(g, buf, state, tilecnt, payload, zero_selected, ne);
+  else topk_emit_kernel<false><<<ne, kThreads, 0, stream>>>(g, buf, state, tilecnt, payload, zero_selected, ne);
   return hipGetLastError();
 }
 
