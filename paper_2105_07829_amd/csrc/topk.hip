@@ -203,19 +203,29 @@ struct TopkMsgs {
     const uint8_t *v = rec(i, p) + kHeaderBytes + 4 * ru4(k_cap);
     return half ? __half2float(reinterpret_cast<const __half *>(v)[t]) : reinterpret_cast<const float *>(v)[t];
   }
-  __device__ void finish8(const Geo &g, uint32_t p, uint32_t j0, uint32_t d, const float *sum, float out[8]) const {
+  // The residual's eight elements from j0 (zeros without a residual or past the end), and
+  // Delta from them and the sums of the decoded messages.
+  __device__ void load_res8(const Geo &g, uint32_t p, uint32_t j0, uint32_t d, float r[8]) const {
     const uint64_t i0 = g.part_base(p) + j0;
-    float r[8] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+    for (int e = 0; e < 8; ++e) r[e] = 0.0f;
     if (res) {
       if (j0 + 8 <= d) load8_aligned(res + i0, r);
       else
         for (int e = 0; e < 8; ++e) r[e] = j0 + e < d ? res[i0 + e] : 0.0f;
     }
+  }
+  __device__ void combine8(uint32_t j0, uint32_t d, const float *sum, const float r[8], float out[8]) const {
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       const float mean = sum[e] * msgs.inv_n;
       out[e] = j0 + e < d ? (res ? mean + r[e] : mean) : 0.0f;
     }
+  }
+  __device__ void finish8(const Geo &g, uint32_t p, uint32_t j0, uint32_t d, const float *sum, float out[8]) const {
+    float r[8];
+    load_res8(g, p, j0, d, r);
+    combine8(j0, d, sum, r, out);
   }
 };
 
@@ -248,12 +258,16 @@ __global__ __launch_bounds__(kThreads) void topk_starts_kernel(Geo g, TopkMsgs m
 // (a barrier in between: the order of the sum is the workers'), a thread's first entry of the
 // next worker requested before the adds of this one.
 struct TopkMsgsGroupSource : TopkMsgs {
-  static constexpr int kLdsFloats = kGroupElems + 3 * kMaxWorkers + 1;
+  static constexpr int kLdsFloats = kGroupElems + 5 * kMaxWorkers + 2;   // sums, ranges, counts before, record addresses
   __device__ void begin(const Geo &, uint32_t, float *) const {}
   __device__ void begin_group(const Geo &g, uint32_t p, uint32_t grp, float *lds) const {
     uint32_t *range = reinterpret_cast<uint32_t *>(lds + kGroupElems);
+    // (the records' addresses go to LDS: a thread's entries belong to workers it finds at run
+    // time, and indexing the kernel arguments by such a number is a memory access of its own)
+    const uint8_t **recs = reinterpret_cast<const uint8_t **>(lds + kGroupElems + 3 * kMaxWorkers + 2);
     const uint32_t lo = grp * kGroupElems;
     if (threadIdx.x < (uint32_t)msgs.n) {
+      recs[threadIdx.x] = rec(threadIdx.x, p);
       const uint32_t *tab = starts + ((uint64_t)threadIdx.x * g.P + p) * (groups_per_part + 1);
       const uint32_t k = k_of(threadIdx.x, p);
       const uint32_t s = tab[grp] < k ? tab[grp] : k, e = tab[grp + 1] < k ? tab[grp + 1] : k;
@@ -291,9 +305,11 @@ struct TopkMsgsGroupSource : TopkMsgs {
             if (cum[mid] <= q) a = mid; else b = mid;
           }
           const uint32_t t = range[2 * a] + (q - cum[a]);
+          const uint8_t *rc = recs[a];
           who[r] = a;
-          rel[r] = idx(a, p)[t] - lo;
-          val[r] = value(a, p, t);
+          rel[r] = reinterpret_cast<const uint32_t *>(rc + kHeaderBytes)[t] - lo;
+          const uint8_t *vp = rc + kHeaderBytes + 4 * ru4(k_cap);
+          val[r] = half ? __half2float(reinterpret_cast<const __half *>(vp)[t]) : reinterpret_cast<const float *>(vp)[t];
         }
       }
       for (int i = 0; i < msgs.n; ++i) {
@@ -320,6 +336,12 @@ struct TopkMsgsGroupSource : TopkMsgs {
     load8_aligned(lds + j0 % kGroupElems, sum);
     finish8(g, p, j0, d, sum, out);
   }
+  // the same with the residual's elements requested beforehand (load_res8)
+  __device__ void at8_with(uint32_t j0, uint32_t d, const float *lds, const float r[8], float out[8]) const {
+    float sum[8];
+    load8_aligned(lds + j0 % kGroupElems, sum);
+    combine8(j0, d, sum, r, out);
+  }
 };
 
 // The sample pass's view of the same: the sums of the sampled chunks, collected by the sweep of
@@ -344,7 +366,7 @@ struct TopkMsgsSampleSource : TopkMsgs {
 template <class SRC>
 __global__ __launch_bounds__(kThreads) void topk_sample_kernel(Geo g, SRC src, uint32_t *hist, uint32_t *state,
                                                                uint32_t *guess, int sample, uint32_t *status) {
-  __shared__ float lds[SRC::kLdsFloats];
+  __shared__ __align__(16) float lds[SRC::kLdsFloats];
   __shared__ uint32_t h[kBins1];
   if (blockIdx.x == 0 && threadIdx.x == 0) status[0] = 0;   // (set by a wait of the long form that gave up)
   __shared__ uint32_t scan[kThreads];
@@ -403,16 +425,19 @@ struct has_begin_group : std::false_type {};
 template <class SRC>
 struct has_begin_group<SRC, std::void_t<decltype(&SRC::begin_group)>> : std::true_type {};
 
-// Load pass.  Besides the buffer and the histogram: the elements of the workgroup's tiles whose
-// key is at least the partition's guess go to its short list, together and in index order, at
-// the place one atomic add on the list length hands out; place and count are recorded per
-// group of tiles, so the select pass can walk the list in index order whatever order the
-// groups arrived in.
+// Load pass.  Besides the buffer: the elements of the workgroup's tiles whose key is at least
+// the partition's guess go to its short list, together and in index order, at the place one
+// atomic add on the list length hands out; place and count are recorded per group of tiles, so
+// the select pass can walk the list in index order whatever order the groups arrived in.
+// The level-1 histogram takes those elements only (the bin of the k-th largest key and the rank
+// inside it come out the same as long as the list holds k elements; every non-empty bin of every
+// workgroup is one atomic on global memory, and with all elements counted those atomics were
+// most of this pass on the server side); without a guess it takes all elements.
 template <class SRC>
 __global__ __launch_bounds__(kThreads) void topk_load_hist1_kernel(Geo g, SRC src, float *buf, uint32_t *hist, uint32_t *state,
                                                                    const uint32_t *guess, uint32_t *groupcnt,
                                                                    uint32_t *cand_idx, uint32_t *cand_val) {
-  __shared__ float lds[SRC::kLdsFloats];
+  __shared__ __align__(16) float lds[SRC::kLdsFloats];
   __shared__ uint32_t h[kBins1];
   __shared__ uint32_t scan[kThreads];
   __shared__ uint32_t off_sh;
@@ -423,17 +448,33 @@ __global__ __launch_bounds__(kThreads) void topk_load_hist1_kernel(Geo g, SRC sr
   src.begin(g, w.p, lds);
   __syncthreads();
   if (w.tile_lo >= w.tile_hi) return;  // (uniform) past the end of a shorter last partition
-  if constexpr (has_begin_group<SRC>::value) src.begin_group(g, w.p, w.tile_lo / kTpgLoad, lds);
+  float v[kPieces][8];
+  if constexpr (has_begin_group<SRC>::value) {
+    // the residual's elements are requested first, so they are on their way while the group's
+    // sum is formed
+#pragma unroll
+    for (int c = 0; c < kPieces; ++c) {
+      const uint32_t j0 = w.tile_lo * kTile + c * (kThreads * 8) + threadIdx.x * 8;
+      src.load_res8(g, w.p, j0 < w.d ? j0 : 0u, w.d, v[c]);
+    }
+    src.begin_group(g, w.p, w.tile_lo / kTpgLoad, lds);
+  }
   const uint32_t G = guess[w.p];
   const uint64_t base = g.part_base(w.p);
-  float v[kPieces][8];
   uint32_t mask[kPieces];
 #pragma unroll
   for (int c = 0; c < kPieces; ++c) {
     const uint32_t j0 = w.tile_lo * kTile + c * (kThreads * 8) + threadIdx.x * 8;
     mask[c] = 0;
     if (j0 >= w.d) continue;
-    source_at8(src, g, w.p, j0, w.d, lds, v[c]);
+    if constexpr (has_begin_group<SRC>::value) {
+      float r[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) r[e] = v[c][e];
+      src.at8_with(j0, w.d, lds, r, v[c]);
+    } else {
+      source_at8(src, g, w.p, j0, w.d, lds, v[c]);
+    }
     if (j0 + 8 <= w.d) {
       float4 *dst = reinterpret_cast<float4 *>(buf + base + j0);
       dst[0] = make_float4(v[c][0], v[c][1], v[c][2], v[c][3]);
@@ -444,8 +485,9 @@ __global__ __launch_bounds__(kThreads) void topk_load_hist1_kernel(Geo g, SRC sr
       if (j0 + e < w.d) {
         if (j0 + 8 > w.d) buf[base + j0 + e] = v[c][e];
         const uint32_t key = key_of(v[c][e]);
-        atomicAdd(&h[key >> kShift1], 1u);
-        mask[c] |= (uint32_t)(key >= G) << e;
+        const bool listed = key >= G;
+        if (listed || G == kNoGuess) atomicAdd(&h[key >> kShift1], 1u);
+        mask[c] |= (uint32_t)listed << e;
       }
     }
   }
@@ -524,17 +566,41 @@ __device__ inline void keys4(const float *part, uint32_t j, uint32_t d, uint32_t
 
 // LEVEL 2: keys whose top 11 bits equal the prefix, histogram of the next 10 bits.
 // LEVEL 3: keys whose top 21 bits equal the prefix, histogram of the last 10 bits.
+// LEVEL 1 (long form behind the short-list form only): the keys below the partition's guess,
+// which the load pass left out of the level-1 histogram.
 template <int LEVEL>
 __device__ inline void topk_hist_body(const Geo &g, const float *buf, uint32_t *hist, uint32_t *state, uint32_t n_groups,
-                                      int gated) {
-  __shared__ uint32_t h[kBins23];
+                                      int gated, const uint32_t *guess = nullptr) {
+  constexpr int kBins = LEVEL == 1 ? kBins1 : kBins23;
+  __shared__ uint32_t h[kBins];
   __shared__ uint32_t scan[kThreads];
   __shared__ uint32_t sel[2];
   for (uint32_t blk = blockIdx.x; blk < n_groups; blk += gridDim.x) {
     const GroupOf w = group_of<LEVEL == 2 ? kTpgHist2 : kTpgHist3>(g, blk);
     if (gated && !long_form(state, w.p)) continue;
-    for (int b = threadIdx.x; b < kBins23; b += kThreads) h[b] = 0;
-    selection_after<LEVEL - 1>(g, hist, state, w.p, w.tile_lo == 0, scan, sel);
+    for (int b = threadIdx.x; b < kBins; b += kThreads) h[b] = 0;
+    if constexpr (LEVEL == 1) {
+      const uint32_t G = guess[w.p];
+      __syncthreads();
+      const float *part1 = buf + g.part_base(w.p);
+      for (uint32_t tile = w.tile_lo; tile < w.tile_hi; ++tile) {
+#pragma unroll
+        for (int c = 0; c < kTile / (kThreads * 4); ++c) {
+          uint32_t key[4], n;
+          keys4(part1, tile * kTile + c * (kThreads * 4) + threadIdx.x * 4, w.d, key, &n);
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if ((uint32_t)e < n && key[e] < G) atomicAdd(&h[key[e] >> kShift1], 1u);
+        }
+      }
+      __syncthreads();
+      uint32_t *gh1 = hist + (uint64_t)w.p * kTopkHistWords + kHist1;
+      for (int b = threadIdx.x; b < kBins; b += kThreads)
+        if (h[b]) atomicAdd(&gh1[b], h[b]);
+      __syncthreads();
+      continue;
+    }
+    selection_after<(LEVEL > 1 ? LEVEL - 1 : 1)>(g, hist, state, w.p, w.tile_lo == 0, scan, sel);
     const uint32_t prefix = sel[0];
     constexpr int kHiShift = LEVEL == 2 ? kShift1 : kShift2;
     constexpr int kLoShift = LEVEL == 2 ? kShift2 : 0;
@@ -906,13 +972,14 @@ __device__ inline void topk_grid_barrier(uint32_t *counter, uint32_t round, uint
 
 // The long form behind the short-list form, as one launch: returns at once unless some
 // partition was left to it (the usual case: one launch and one read instead of four of each),
-// else runs the four passes for those partitions with the whole grid meeting in between.
+// else completes their level-1 histograms and runs the four passes for those partitions, with
+// the whole grid meeting in between.
 // The grid is resident as a whole (the host sizes it by occupancy).  `counter`: zero at launch.
 template <bool HALF>
 __global__ __launch_bounds__(kThreads) void topk_long_form_kernel(Geo g, float *buf, uint32_t *hist, uint32_t *state,
                                                                   uint32_t *tilecnt, uint8_t *payload, int zero_selected,
                                                                   uint32_t n2, uint32_t n3, uint32_t nc, uint32_t ne,
-                                                                  uint32_t *counter, uint32_t *status) {
+                                                                  const uint32_t *guess, uint32_t *counter, uint32_t *status) {
   __shared__ uint32_t any;
   if (threadIdx.x == 0) any = 0;
   __syncthreads();
@@ -920,12 +987,14 @@ __global__ __launch_bounds__(kThreads) void topk_long_form_kernel(Geo g, float *
     if (state[p * 8 + kStLong]) any = 1;
   __syncthreads();
   if (!any) return;   // (the same answer in every workgroup: the flags were written by the kernel before)
-  topk_hist_body<2>(g, buf, hist, state, n2, 1);
+  topk_hist_body<1>(g, buf, hist, state, n3, 1, guess);   // (groups of one tile, as level 3)
   topk_grid_barrier(counter, 1, status);
-  topk_hist_body<3>(g, buf, hist, state, n3, 1);
+  topk_hist_body<2>(g, buf, hist, state, n2, 1);
   topk_grid_barrier(counter, 2, status);
-  topk_count_body(g, buf, hist, state, tilecnt, nc, 1);
+  topk_hist_body<3>(g, buf, hist, state, n3, 1);
   topk_grid_barrier(counter, 3, status);
+  topk_count_body(g, buf, hist, state, tilecnt, nc, 1);
+  topk_grid_barrier(counter, 4, status);
   topk_emit_body<HALF>(g, buf, state, tilecnt, payload, zero_selected, ne, 1);
 }
 
@@ -1003,8 +1072,8 @@ hipError_t topk_encode(const Geo &g, const bpc_params_t &prm, const bpc_params_t
     uint32_t *status = ws.at<uint32_t>(ws.lay.status);
     hipError_t e = cluster_launch_begin(stream);
     if (e != hipSuccess) return e;
-    if (half) topk_long_form_kernel<true><<<grid, kThreads, 0, stream>>>(g, buf, hist, state, tilecnt, payload, zero_selected, n2, n3, nc, ne, counter, status);
-    else topk_long_form_kernel<false><<<grid, kThreads, 0, stream>>>(g, buf, hist, state, tilecnt, payload, zero_selected, n2, n3, nc, ne, counter, status);
+    if (half) topk_long_form_kernel<true><<<grid, kThreads, 0, stream>>>(g, buf, hist, state, tilecnt, payload, zero_selected, n2, n3, nc, ne, guess, counter, status);
+    else topk_long_form_kernel<false><<<grid, kThreads, 0, stream>>>(g, buf, hist, state, tilecnt, payload, zero_selected, n2, n3, nc, ne, guess, counter, status);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     return cluster_launch_end(stream);
