@@ -79,9 +79,10 @@ hipError_t dither_worker_single_pass(const Geo &g, const bpc_params_t &prm, cons
 // out = decode(payload), dense.
 // Tables for the update kernel's sparse decoder (see update.hip).
 constexpr uint32_t kRandkTableStride = 1025;
-hipError_t topk_tile_starts(const Geo &g, const uint8_t *payload, bool half, uint32_t *table, hipStream_t stream);
+hipError_t topk_tile_starts(const Geo &g, const uint8_t *payload, bool half, uint32_t *table, uint32_t tile_shift,
+                            hipStream_t stream);
 hipError_t randk_bin_tiles(const Geo &g, const bpc_params_t &prm, const uint8_t *payload, uint2 *lists, uint32_t *table,
-                           hipStream_t stream);
+                           uint32_t tile_shift, hipStream_t stream);
 hipError_t decode_dense(const Geo &g, const bpc_params_t &prm, const uint8_t *payload, float *out,
                         hipStream_t stream);
 

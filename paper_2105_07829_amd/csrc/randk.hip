@@ -364,12 +364,12 @@ __global__ __launch_bounds__(kThreads) void randk_fixup_kernel(Geo g, float *buf
     atomicAdd(buf + base + randk_index(rng, t, d), -(scale * val[t]));
 }
 
-// One message's draws as (index, scaled value) pairs grouped by tile of kTile elements:
+// One message's draws as (index, scaled value) pairs grouped by tile of 1 << tile_shift elements:
 // lists[p * k_cap ..], table[p * kRandkTableStride + tile] = where the tile's pairs start.
-// Needs tiles_per_part <= 1024.
+// Needs at most 1024 tiles to a partition.
 hipError_t randk_bin_tiles(const Geo &g, const bpc_params_t &prm, const uint8_t *payload, uint2 *lists, uint32_t *table,
-                           hipStream_t stream) {
-  static_assert(kTile == 4096 && kRandkTableStride == kRbMaxBins + 1, "slice_shift, table layout");
+                           uint32_t tile_shift, hipStream_t stream) {
+  static_assert(kRandkTableStride == kRbMaxBins + 1, "table layout");
   WorkerMsgs msgs{};
   msgs.ptr[0] = payload;
   msgs.seed[0] = prm.seed;
@@ -377,7 +377,7 @@ hipError_t randk_bin_tiles(const Geo &g, const bpc_params_t &prm, const uint8_t 
   msgs.n = 1;
   RandkScales sc{};
   sc.value_scale[0] = prm.value_scale;
-  randk_bin_kernel<false><<<dim3(g.P, 1), kRbThreads, 0, stream>>>(g, msgs, sc, 12, lists, table);
+  randk_bin_kernel<false><<<dim3(g.P, 1), kRbThreads, 0, stream>>>(g, msgs, sc, tile_shift, lists, table);
   return hipGetLastError();
 }
 

@@ -998,18 +998,19 @@ __global__ __launch_bounds__(kThreads) void topk_long_form_kernel(Geo g, float *
   topk_emit_body<HALF>(g, buf, state, tilecnt, payload, zero_selected, ne, 1);
 }
 
-// table[p * (tiles_per_part + 1) + tile] = the first entry of partition p's record that lies in
-// tile `tile` (of kTile elements) or after it; entry tiles_per_part = the number of entries.
-hipError_t topk_tile_starts(const Geo &g, const uint8_t *payload, bool half, uint32_t *table, hipStream_t stream) {
-  static_assert(kTile == 4096, "group_shift");
+// With tiles of 1 << tile_shift elements, T of them to a full partition:
+// table[p * (T + 1) + tile] = the first entry of partition p's record that lies in tile `tile`
+// or after it; entry T = the number of entries.
+hipError_t topk_tile_starts(const Geo &g, const uint8_t *payload, bool half, uint32_t *table, uint32_t tile_shift,
+                            hipStream_t stream) {
   TopkMsgs m{};
   m.msgs.ptr[0] = payload;
   m.msgs.n = 1;
-  m.groups_per_part = g.tiles_per_part;
+  m.groups_per_part = (uint32_t)cdiv(g.part_elems, 1ull << tile_shift);
   m.k_cap = g.k_cap;
   m.stride = g.stride;
   m.half = half ? 1 : 0;
-  m.group_shift = 12;
+  m.group_shift = tile_shift;
   topk_starts_kernel<<<dim3((uint32_t)cdiv(g.k_cap + 1, kThreads), g.P, 1), kThreads, 0, stream>>>(g, m, table, nullptr);
   return hipGetLastError();
 }

@@ -204,47 +204,58 @@ struct DenseDec {
 // are one stretch of a list (top-k: of the record itself, whose entries come by ascending
 // index; random-k: of the record's draws binned per tile beforehand), found through a table of
 // where each tile's stretch starts, and laid out in LDS by the workgroup that has the tile.
+template <int TILE, int THREADS>
 struct SparseTileDec {
   const uint8_t *payload;
   uint64_t stride;
   uint32_t k_cap;
   int mode;                  // 0: top-k, f32 values; 1: top-k, half values; 2: random-k pairs
-  const uint32_t *table;     // [partition][tile .. ], `table_stride` words a partition
-  uint32_t table_stride;
+  const uint32_t *starts;    // [partition][tile .. ], `starts_stride` words a partition
+  uint32_t starts_stride;
   const uint2 *pairs;        // random-k: [partition][k_cap]
   __device__ const float *dense_base() const { return nullptr; }
-  static constexpr int kLdsFloats = kTile;
+  static constexpr int kLdsFloats = TILE;
   __device__ void begin(uint32_t, float *) const {}
   __device__ void begin_tile(uint32_t p, uint32_t tile, float *lds) const {
-    for (uint32_t q = threadIdx.x; q < kTile / 4; q += kThreads) reinterpret_cast<float4 *>(lds)[q] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    __syncthreads();   // (the tile before is done with)
+    for (uint32_t q = threadIdx.x; q < TILE / 4; q += THREADS) reinterpret_cast<float4 *>(lds)[q] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
     const uint8_t *rec = payload + (uint64_t)p * stride;
     uint32_t k = *reinterpret_cast<const uint32_t *>(rec);
     k = k > k_cap ? k_cap : k;
-    const uint32_t *tab = table + (uint64_t)p * table_stride;
+    const uint32_t *tab = starts + (uint64_t)p * starts_stride;
     uint32_t s = tab[tile], e = tab[tile + 1];
     s = s < k ? s : k;
     e = e < k ? e : k;
-    const uint32_t lo = tile * kTile;
+    const uint32_t lo = tile * TILE;
     __syncthreads();
     if (mode == 2) {
       const uint2 *list = pairs + (uint64_t)p * k_cap;
-      for (uint32_t q = s + threadIdx.x; q < e; q += kThreads) {
+      for (uint32_t q = s + threadIdx.x; q < e; q += THREADS) {
         const uint2 ent = list[q];
-        if (ent.x - lo < (uint32_t)kTile) atomicAdd(&lds[ent.x - lo], __uint_as_float(ent.y));   // an index may repeat
+        if (ent.x - lo < (uint32_t)TILE) atomicAdd(&lds[ent.x - lo], __uint_as_float(ent.y));   // an index may repeat
       }
     } else {
       const uint32_t *idx = reinterpret_cast<const uint32_t *>(rec + kHeaderBytes);
       const uint8_t *val = rec + kHeaderBytes + 4 * ru4(k_cap);
-      for (uint32_t q = s + threadIdx.x; q < e; q += kThreads) {
+      for (uint32_t q = s + threadIdx.x; q < e; q += THREADS) {
         const uint32_t rel = idx[q] - lo;
         const float v = mode == 1 ? __half2float(reinterpret_cast<const __half *>(val)[q]) : reinterpret_cast<const float *>(val)[q];
-        if (rel < (uint32_t)kTile) lds[rel] = v;
+        if (rel < (uint32_t)TILE) lds[rel] = v;
       }
     }
     __syncthreads();
   }
   __device__ void at4(const Geo &, uint32_t, uint32_t j, const TileBuf &, const float *lds, float out[4]) const {
-    const float4 f = *reinterpret_cast<const float4 *>(lds + (j & (kTile - 1)));
+    const float4 f = *reinterpret_cast<const float4 *>(lds + (j & (TILE - 1)));
+    out[0] = f.x; out[1] = f.y; out[2] = f.z; out[3] = f.w;
+  }
+  // (the forms the single-pass LANS kernel uses: nothing to request ahead, the tile is in LDS)
+  using R4 = uint32_t;
+  __device__ float header(uint32_t) const { return 0.0f; }
+  __device__ void table(float, float *) const {}
+  __device__ R4 load4(const Geo &, uint32_t, uint32_t, const TileBuf &) const { return 0u; }
+  __device__ void decode4(R4, uint32_t j, float, const float *lds, float out[4]) const {
+    const float4 f = *reinterpret_cast<const float4 *>(lds + (j & (TILE - 1)));
     out[0] = f.x; out[1] = f.y; out[2] = f.z; out[3] = f.w;
   }
 };
@@ -360,7 +371,7 @@ constexpr int kURow = kThreads * 4;
 constexpr int kURows = kTile / kURow;
 template <class DEC>
 __global__ __launch_bounds__(kThreads) void adam_update_kernel(Geo g, DEC dec, float *x, float *m, float *v, OptArgs o) {
-  __shared__ float lds[DEC::kLdsFloats];
+  __shared__ __align__(16) float lds[DEC::kLdsFloats];
   const uint32_t p = __builtin_amdgcn_readfirstlane(blockIdx.x / g.tiles_per_part);
   const uint32_t tile = __builtin_amdgcn_readfirstlane(blockIdx.x % g.tiles_per_part);
   const uint32_t d = g.part_size(p);
@@ -523,7 +534,7 @@ __device__ inline void lans_write_x(const Geo &g, const ClusterGeo &cg, const Op
 template <class DEC>
 __global__ __launch_bounds__(kLThreads) void lans_single_kernel(Geo g, ClusterGeo cg, DEC dec, float *x, float *m, float *v,
                                                                OptArgs o, double *slots, uint32_t *status) {
-  __shared__ float lds[DEC::kLdsFloats];
+  __shared__ __align__(16) float lds[DEC::kLdsFloats];
   __shared__ double red[kLThreads / 64];
   __shared__ double total_sh[3];
   constexpr uint32_t kNone = 0xffffffffu;
@@ -538,9 +549,13 @@ __global__ __launch_bounds__(kLThreads) void lans_single_kernel(Geo g, ClusterGe
   const float inv_bc1 = 1.0f / o.bc1, inv_bc2 = 1.0f / o.bc2;
   for (;;) {
     const LansTile t = lans_tile(g, cg, item);
-    __syncthreads();   // the table of the tile before
-    dec.table(raw.hdr, lds);
-    __syncthreads();
+    if constexpr (has_begin_tile<DEC>::value) {
+      dec.begin_tile(t.p, t.tile, lds);   // the tile of the message, laid out in LDS
+    } else {
+      __syncthreads();   // the table of the tile before
+      dec.table(raw.hdr, lds);
+      __syncthreads();
+    }
     LansHeld h;
     double s_x = 0.0, s_r = 0.0, s_c = 0.0;
 #pragma unroll
@@ -703,28 +718,45 @@ hipError_t adaptive_update(const Geo &g, const bpc_params_t &prm, const uint8_t 
     default: break;
   }
   float *dense = ws.at<float>(ws.lay.dense);
-  if (opt.kind == BPC_OPT_ADAM && (prm.kind == BPC_TOPK || prm.kind == BPC_TOPK16 || prm.kind == BPC_RANDK)) {
+  const bool lans_single = opt.kind == BPC_OPT_LANS && !opt.block_offsets && g.part_elems % kSTile == 0;
+  if ((opt.kind == BPC_OPT_ADAM || lans_single) && (prm.kind == BPC_TOPK || prm.kind == BPC_TOPK16 || prm.kind == BPC_RANDK)) {
     // no dense decode: the update kernel lays each tile of the message out in LDS itself
+    // (tiles of 4096 elements in the Adam-style kernel, of 8192 in the single-pass LANS kernel)
     OptArgs o{opt.lr, opt.beta1, opt.beta2, opt.eps, opt.weight_decay, opt.bias_corr1, opt.bias_corr2,
               opt.phi_lo, opt.phi_hi, opt.block_offsets, opt.n_blocks};
+    const uint32_t shift = lans_single ? 13 : 12;
+    const uint32_t tiles = (uint32_t)cdiv(g.part_elems, 1ull << shift);
+    const uint32_t *table = nullptr;
+    const uint2 *pairs = nullptr;
+    uint32_t table_stride = 0;
+    int mode = -1;
     if (prm.kind == BPC_RANDK) {
       const uint64_t list_bytes = ((uint64_t)g.P * g.k_cap * sizeof(uint2) + 255) / 256 * 256;
       const uint64_t table_bytes = (uint64_t)g.P * kRandkTableStride * sizeof(uint32_t);
-      if (g.tiles_per_part <= 1024 && list_bytes + table_bytes <= sizeof(float) * g.D) {
+      if (tiles <= 1024 && list_bytes + table_bytes <= sizeof(float) * g.D) {
         uint2 *lists = reinterpret_cast<uint2 *>(dense);   // (the dense workspace is free on this path)
-        uint32_t *table = reinterpret_cast<uint32_t *>(reinterpret_cast<uint8_t *>(dense) + list_bytes);
-        hipError_t e = randk_bin_tiles(g, prm, payload, lists, table, stream);
+        uint32_t *tab = reinterpret_cast<uint32_t *>(reinterpret_cast<uint8_t *>(dense) + list_bytes);
+        hipError_t e = randk_bin_tiles(g, prm, payload, lists, tab, shift, stream);
         if (e != hipSuccess) return e;
-        adam_update_kernel<<<g.n_tiles, kThreads, 0, stream>>>(g, SparseTileDec{payload, g.stride, g.k_cap, 2, table, kRandkTableStride, lists}, x, m, v, o);
-        return hipGetLastError();
+        table = tab; pairs = lists; table_stride = kRandkTableStride; mode = 2;
       }
     } else {
-      uint32_t *table = ws.at<uint32_t>(ws.lay.starts);
+      uint32_t *tab = ws.at<uint32_t>(ws.lay.starts);
       const bool half = prm.kind == BPC_TOPK16;
-      hipError_t e = topk_tile_starts(g, payload, half, table, stream);
+      hipError_t e = topk_tile_starts(g, payload, half, tab, shift, stream);
       if (e != hipSuccess) return e;
-      adam_update_kernel<<<g.n_tiles, kThreads, 0, stream>>>(g, SparseTileDec{payload, g.stride, g.k_cap, half ? 1 : 0, table, g.tiles_per_part + 1, nullptr}, x, m, v, o);
-      return hipGetLastError();
+      table = tab; table_stride = tiles + 1; mode = half ? 1 : 0;
+    }
+    if (mode >= 0) {
+      if (!lans_single) {
+        adam_update_kernel<<<g.n_tiles, kThreads, 0, stream>>>(g, SparseTileDec<kTile, kThreads>{payload, g.stride, g.k_cap, mode, table, table_stride, pairs}, x, m, v, o);
+        return hipGetLastError();
+      }
+      bool used = false;
+      hipError_t e = run_lans_single(g, SparseTileDec<kSTile, kLThreads>{payload, g.stride, g.k_cap, mode, table, table_stride, pairs},
+                                     x, m, v, o, ws, stream, &used);
+      if (e != hipSuccess || used) return e;
+      // (the single-pass kernel declined the shape: the dense decode below overwrites the lists)
     }
   }
   hipError_t e = decode_dense(g, prm, payload, dense, stream);
