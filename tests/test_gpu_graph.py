@@ -18,7 +18,8 @@ def gu():
 
 
 @pytest.mark.parametrize("kind,kw", [("sign", {}), ("dither", dict(levels=4, seed=5, stream_id=9)),
-                                     ("topk", dict(k_ratio=0.01))])
+                                     ("topk", dict(k_ratio=0.01)),
+                                     ("randk", dict(k_ratio=0.02, value_scale=-1.0, seed=3, stream_id=7))])
 def test_step_recorded_in_a_graph_replays_like_eager_calls(gu, kind, kw):
     import torch
     bpc = gu.bpc
@@ -81,7 +82,7 @@ def test_step_recorded_in_a_graph_replays_like_eager_calls(gu, kind, kw):
         got = snapshot()
         assert bpc.workspace_status(out_prm, D, ws) == 0
         for a, b in zip(got, ref):
-            if kind == "topk" and a is got[-2]:
+            if kind in ("topk", "randk") and a is got[-2]:
                 continue   # payload bytes past the defined fields are unspecified
             assert torch.equal(a, b), (kind, "replay", rep)
     # and the library still works eagerly afterwards, on the default stream
