@@ -781,16 +781,18 @@ __global__ __launch_bounds__(kSelThreads) void topk_list_select_kernel(Geo g, fl
   const Walk walk0{group0, vstart[group0], vstart[group0 + 1], goff[group0]};
   // every load is issued whether or not the entry exists (entry 0 of the list stands in), so
   // none of them is waited for before the last is on its way
-  uint32_t bits[kSelPer];
+  uint32_t bits[kSelPer], where[kSelPer];   // value and index of the thread's entries
   auto key = [&](int i) { return bits[i] & 0x7fffffffu; };
   {
     Walk w = walk0;
 #pragma unroll
     for (int i = 0; i < kSelPer; ++i) {
       bits[i] = 0;
+      where[i] = 0;
       if ((uint32_t)i >= rounds) continue;   // (the same for all threads)
       const uint32_t at = (uint32_t)i < cnt ? walk_to(w, first + 64 * i) : 0u;
       bits[i] = cand_val[list + at];
+      where[i] = cand_idx[list + at];
     }
   }
   // level 1 is known from the histogram of the whole partition
@@ -823,36 +825,19 @@ __global__ __launch_bounds__(kSelThreads) void topk_list_select_kernel(Geo g, fl
   uint8_t *rec = payload + (uint64_t)p * g.stride;
   float *buf_part = buf + g.part_base(p);
   const uint64_t lanes_before = (1ull << lane) - 1ull;
-  // 16 rounds at a time: which entries are kept and where they go, the loads of their indices
-  // (entry 0 of the list stands in for an entry that is not kept), then the stores
-  constexpr int kChunk = 16;
-  Walk w = walk0;
+  // which entries are kept and where they go
 #pragma unroll
-  for (int c = 0; c < kSelPer / kChunk; ++c) {
-    if ((uint32_t)(kChunk * c) >= rounds) break;
-    uint32_t j[kChunk], pos[kChunk];
-    uint32_t take = 0;
-#pragma unroll
-    for (int e = 0; e < kChunk; ++e) {
-      const int i = kChunk * c + e;
-      j[e] = 0; pos[e] = 0;
-      if ((uint32_t)i >= rounds) continue;   // (the same for all threads)
+  for (int i = 0; i < kSelPer; ++i) {
+    if ((uint32_t)i < rounds) {   // (the same for all threads)
       const bool valid = (uint32_t)i < cnt;
       const uint64_t gtm = __ballot(valid && key(i) > T), eqm = __ballot(valid && key(i) == T);
       const uint32_t gt_before = gt_base + __popcll(gtm & lanes_before);
       const uint32_t eq_before = eq_base + __popcll(eqm & lanes_before);
       const bool t = valid && (key(i) > T || (key(i) == T && eq_before < r));
-      take |= (uint32_t)t << e;
-      pos[e] = gt_before + (eq_before < r ? eq_before : r);
       gt_base += __popcll(gtm);
       eq_base += __popcll(eqm);
-      const uint32_t at = t ? walk_to(w, first + 64 * i) : 0u;
-      j[e] = cand_idx[list + at];
+      if (t) topk_write_entry<HALF>(g, rec, gt_before + (eq_before < r ? eq_before : r), where[i], __uint_as_float(bits[i]), buf_part, zero_selected);
     }
-#pragma unroll
-    for (int e = 0; e < kChunk; ++e)
-      if ((take >> e) & 1u)
-        topk_write_entry<HALF>(g, rec, pos[e], j[e], __uint_as_float(bits[kChunk * c + e]), buf_part, zero_selected);
   }
 }
 
