@@ -112,9 +112,13 @@ constexpr int kRbSumThreads = 256;
 
 // OUT: the draws of a message still to be written (stream i of `msgs`, k by the rule): the
 // pairs are (index, number of the draw).
-template <bool OUT>
+// STAGE: the pairs are put in order in LDS (k_cap * 8 bytes of dynamic LDS) and written out in
+// whole lines; else each pair is stored where it belongs directly (scattered 8-byte stores,
+// which were most of this kernel's time with eight messages of 10 K draws a partition).
+template <bool OUT, bool STAGE>
 __global__ __launch_bounds__(kRbThreads) void randk_bin_kernel(Geo g, WorkerMsgs msgs, RandkScales sc, uint32_t slice_shift,
                                                                uint2 *lists, uint32_t *table) {
+  extern __shared__ uint2 staged[];
   __shared__ uint32_t cnt[kRbMaxBins];
   __shared__ uint32_t scan[kRbThreads];
   const uint32_t p = blockIdx.x, i = blockIdx.y;
@@ -163,9 +167,15 @@ __global__ __launch_bounds__(kRbThreads) void randk_bin_kernel(Geo g, WorkerMsgs
       if (t < k) {
         const uint32_t j = (uint32_t)(((uint64_t)rnd[c] * d) >> 32);
         const uint32_t pos = atomicAdd(&cnt[j >> slice_shift], 1u);
-        list[pos] = make_uint2(j, OUT ? t : __float_as_uint(scale * val[t]));
+        const uint2 pair = make_uint2(j, OUT ? t : __float_as_uint(scale * val[t]));
+        if (STAGE) staged[pos] = pair;
+        else list[pos] = pair;
       }
     }
+  }
+  if (STAGE) {
+    __syncthreads();
+    for (uint32_t q = threadIdx.x; q < k; q += kRbThreads) list[q] = staged[q];
   }
 }
 
@@ -364,6 +374,22 @@ __global__ __launch_bounds__(kThreads) void randk_fixup_kernel(Geo g, float *buf
     atomicAdd(buf + base + randk_index(rng, t, d), -(scale * val[t]));
 }
 
+// Launches the binning kernel over P partitions x n streams, staged through LDS where the list of
+// a partition fits.
+template <bool OUT>
+static hipError_t launch_randk_bin(const Geo &g, const WorkerMsgs &msgs, const RandkScales &sc, int n, uint32_t slice_shift,
+                                   uint2 *lists, uint32_t *table, hipStream_t stream) {
+  const size_t lds = (size_t)g.k_cap * sizeof(uint2);
+  constexpr size_t kMaxStage = 96 * 1024;
+  static bool big_ok = hipFuncSetAttribute(reinterpret_cast<const void *>(&randk_bin_kernel<OUT, true>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxStage) == hipSuccess;
+  if (lds <= kMaxStage && (big_ok || lds <= 48 * 1024))
+    randk_bin_kernel<OUT, true><<<dim3(g.P, n), kRbThreads, lds, stream>>>(g, msgs, sc, slice_shift, lists, table);
+  else
+    randk_bin_kernel<OUT, false><<<dim3(g.P, n), kRbThreads, 0, stream>>>(g, msgs, sc, slice_shift, lists, table);
+  return hipGetLastError();
+}
+
 // One message's draws as (index, scaled value) pairs grouped by tile of 1 << tile_shift elements:
 // lists[p * k_cap ..], table[p * kRandkTableStride + tile] = where the tile's pairs start.
 // Needs at most 1024 tiles to a partition.
@@ -377,8 +403,7 @@ hipError_t randk_bin_tiles(const Geo &g, const bpc_params_t &prm, const uint8_t 
   msgs.n = 1;
   RandkScales sc{};
   sc.value_scale[0] = prm.value_scale;
-  randk_bin_kernel<false><<<dim3(g.P, 1), kRbThreads, 0, stream>>>(g, msgs, sc, tile_shift, lists, table);
-  return hipGetLastError();
+  return launch_randk_bin<false>(g, msgs, sc, 1, tile_shift, lists, table, stream);
 }
 
 hipError_t randk_encode(const Geo &g, const bpc_params_t &prm, const bpc_params_t *in_prm, const Source &src,
@@ -409,7 +434,8 @@ hipError_t randk_encode(const Geo &g, const bpc_params_t &prm, const bpc_params_
       // one pass over the data (q goes to the residual buffer, so the dense workspace is free for the list)
       uint2 *lists = reinterpret_cast<uint2 *>(dense);
       uint32_t *table = reinterpret_cast<uint32_t *>(reinterpret_cast<uint8_t *>(dense) + one_list);
-      randk_bin_kernel<true><<<dim3(g.P, 1), kRbThreads, 0, stream>>>(g, out_stream, out_scale, 12, lists, table);
+      hipError_t e = launch_randk_bin<true>(g, out_stream, out_scale, 1, 12, lists, table, stream);
+      if (e != hipSuccess) return e;
       if (src.dtype == BPC_F16)
         randk_tile_kernel<<<g.n_tiles, kThreads, 0, stream>>>(g, GradSource<__half>{(const __half *)src.grad, src.residual}, buf,
                                                               payload, prm.value_scale, lists, table);
@@ -459,10 +485,11 @@ hipError_t randk_encode(const Geo &g, const bpc_params_t &prm, const bpc_params_
       if (binned && (lds2_ok || slice_shift == 13)) {
         uint2 *lists = reinterpret_cast<uint2 *>(dense);
         uint32_t *table = reinterpret_cast<uint32_t *>(reinterpret_cast<uint8_t *>(dense) + (n + 1) * one_list);
-        randk_bin_kernel<false><<<dim3(g.P, n), kRbThreads, 0, stream>>>(g, src.msgs, sc, slice_shift, lists, table);
-        randk_bin_kernel<true><<<dim3(g.P, 1), kRbThreads, 0, stream>>>(g, out_stream, out_scale, slice_shift,
-                                                                         lists + (uint64_t)n * g.P * g.k_cap,
-                                                                         table + (uint64_t)n * g.P * (kRbMaxBins + 1));
+        hipError_t e = launch_randk_bin<false>(g, src.msgs, sc, n, slice_shift, lists, table, stream);
+        if (e != hipSuccess) return e;
+        e = launch_randk_bin<true>(g, out_stream, out_scale, 1, slice_shift, lists + (uint64_t)n * g.P * g.k_cap,
+                                   table + (uint64_t)n * g.P * (kRbMaxBins + 1), stream);
+        if (e != hipSuccess) return e;
         const uint32_t slices = g.P * (uint32_t)cdiv(g.part_elems, 1ull << slice_shift);
         randk_sum_binned_kernel<<<slices, kRbSumThreads, sizeof(float) << slice_shift, stream>>>(
             g, n, src.msgs.inv_n, slice_shift, lists, table, src.residual, buf, payload, prm.value_scale);
