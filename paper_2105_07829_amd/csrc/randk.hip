@@ -251,6 +251,9 @@ __global__ __launch_bounds__(kThreads) void randk_tile_kernel(Geo g, SRC src, fl
   }
 }
 
+// EARLY (slices of 8192 elements): the residual's elements of the slice are requested before
+// the sum is formed (32 registers a thread).
+template <bool EARLY>
 __global__ __launch_bounds__(kRbSumThreads) void randk_sum_binned_kernel(Geo g, int n, float inv_n, uint32_t slice_shift,
                                                                          const uint2 *lists, const uint32_t *table,
                                                                          const float *res, float *buf, uint8_t *payload,
@@ -267,6 +270,25 @@ __global__ __launch_bounds__(kRbSumThreads) void randk_sum_binned_kernel(Geo g, 
     const uint32_t *tab = table + ((uint64_t)threadIdx.x * g.P + p) * (kRbMaxBins + 1);
     from[threadIdx.x] = tab[s];
     to[threadIdx.x] = tab[s + 1];
+  }
+  constexpr int kEarly = 8192 / (kRbSumThreads * 4);   // 16-byte pieces of a slice of 8192 elements a thread
+  float4 early[kEarly];
+  if (EARLY) {
+    const uint64_t at0 = g.part_base(p) + lo;
+#pragma unroll
+    for (int c = 0; c < kEarly; ++c) {
+      const uint32_t q = (c * kRbSumThreads + threadIdx.x) * 4;
+      early[c] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+      if (res) {
+        if (q + 4 <= len) early[c] = *reinterpret_cast<const float4 *>(res + at0 + q);
+        else {
+          early[c].x = q < len ? res[at0 + q] : 0.0f;
+          early[c].y = q + 1 < len ? res[at0 + q + 1] : 0.0f;
+          early[c].z = q + 2 < len ? res[at0 + q + 2] : 0.0f;
+          early[c].w = 0.0f;   // (q + 3 < len would be the whole piece)
+        }
+      }
+    }
   }
   for (uint32_t q = threadIdx.x; q < slice / 4; q += kRbSumThreads) reinterpret_cast<float4 *>(acc)[q] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
   __syncthreads();
@@ -293,7 +315,17 @@ __global__ __launch_bounds__(kRbSumThreads) void randk_sum_binned_kernel(Geo g, 
   {
     // Delta in LDS, the recompression's draws served from there (list n is the output's),
     // and what is left is the new residual
-    for (uint32_t q = threadIdx.x * 4; q < slice; q += kRbSumThreads * 4) {
+    if (EARLY) {
+#pragma unroll
+      for (int c = 0; c < kEarly; ++c) {
+        const uint32_t q = (c * kRbSumThreads + threadIdx.x) * 4;
+        const float4 a = *reinterpret_cast<const float4 *>(acc + q);
+        const float m0 = a.x * inv_n, m1 = a.y * inv_n, m2 = a.z * inv_n, m3 = a.w * inv_n;
+        *reinterpret_cast<float4 *>(acc + q) = res ? make_float4(m0 + early[c].x, m1 + early[c].y, m2 + early[c].z, m3 + early[c].w)
+                                                    : make_float4(m0, m1, m2, m3);
+      }
+    }
+    for (uint32_t q = threadIdx.x * 4; !EARLY && q < slice; q += kRbSumThreads * 4) {
       float4 a = *reinterpret_cast<const float4 *>(acc + q);
       float r[4] = {0.0f, 0.0f, 0.0f, 0.0f};
       if (res) {
@@ -480,7 +512,7 @@ hipError_t randk_encode(const Geo &g, const bpc_params_t &prm, const bpc_params_
       // workspace (free: Delta goes to the residual buffer)
       const bool binned = src.residual != nullptr && cdiv(g.part_elems, 1ull << slice_shift) <= kRbMaxBins &&
                           (n + 1) * (one_list + one_table) <= sizeof(float) * g.D;
-      static bool lds2_ok = hipFuncSetAttribute(reinterpret_cast<const void *>(&randk_sum_binned_kernel),
+      static bool lds2_ok = hipFuncSetAttribute(reinterpret_cast<const void *>(&randk_sum_binned_kernel<false>),
                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (4u << 15)) == hipSuccess;
       if (binned && (lds2_ok || slice_shift == 13)) {
         uint2 *lists = reinterpret_cast<uint2 *>(dense);
@@ -491,8 +523,12 @@ hipError_t randk_encode(const Geo &g, const bpc_params_t &prm, const bpc_params_
                                    table + (uint64_t)n * g.P * (kRbMaxBins + 1), stream);
         if (e != hipSuccess) return e;
         const uint32_t slices = g.P * (uint32_t)cdiv(g.part_elems, 1ull << slice_shift);
-        randk_sum_binned_kernel<<<slices, kRbSumThreads, sizeof(float) << slice_shift, stream>>>(
-            g, n, src.msgs.inv_n, slice_shift, lists, table, src.residual, buf, payload, prm.value_scale);
+        if (slice_shift == 13)
+          randk_sum_binned_kernel<true><<<slices, kRbSumThreads, sizeof(float) << slice_shift, stream>>>(
+              g, n, src.msgs.inv_n, slice_shift, lists, table, src.residual, buf, payload, prm.value_scale);
+        else
+          randk_sum_binned_kernel<false><<<slices, kRbSumThreads, sizeof(float) << slice_shift, stream>>>(
+              g, n, src.msgs.inv_n, slice_shift, lists, table, src.residual, buf, payload, prm.value_scale);
         return hipGetLastError();
       }
       const uint32_t slices = g.P * (uint32_t)cdiv(g.part_elems, kRsSlice);
