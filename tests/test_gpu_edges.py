@@ -159,6 +159,28 @@ def test_randk_server_partition_of_many_slices(gu, orc):
     assert gu.close(res_gpu, res_ref, REL)
 
 
+@pytest.mark.parametrize("kind", ["topk", "topk16"])
+@pytest.mark.parametrize("ratio", [0.011, 0.3])
+def test_topk_server_both_forms(gu, orc, kind, ratio):
+    """Top-k server on partitions of several groups of 8192 elements, with a k the short list
+    takes and with one it does not (then the five passes run on Delta as a whole); several
+    workers keep the same coordinates, so sums of three terms occur and their order shows."""
+    pe = BIG_PE
+    D = 2 * pe + 70001
+    n = 3
+    ins = [gu.both_params(orc, kind, pe, k_ratio=ratio) for _ in range(n)]
+    out_o, out_b = gu.both_params(orc, kind, pe, k_ratio=ratio)
+    rs = np.random.default_rng(41)
+    common = rs.standard_normal(D).astype(np.float32)          # shared large coordinates
+    payloads = [orc.compress(ins[i][0], (common + 0.3 * rs.standard_normal(D)).astype(np.float32), None) for i in range(n)]
+    et = (0.05 * rs.standard_normal(D)).astype(np.float32)
+    res_ref = et.copy()
+    pay_ref = orc.server_aggregate([p[0] for p in ins], payloads, out_o, res_ref, D)
+    pay_gpu, res_gpu = gu.gpu_server([p[1] for p in ins], payloads, out_b, et, D)
+    assert defined_equal(kind, pay_gpu, pay_ref, out_o, orc, D, pe, dict(k_ratio=ratio))
+    assert np.array_equal(res_gpu.view(np.uint32), res_ref.view(np.uint32))
+
+
 def test_topk_sample_that_misleads(gu, orc):
     """The short list is built from a guess taken from a sample of the partition (512 chunks of
     eight elements; chunk c is chunk c*stride + (c*37) % stride of the partition, stride =
