@@ -557,7 +557,9 @@ __global__ __launch_bounds__(kLThreads) void lans_single_kernel(Geo g, ClusterGe
       __syncthreads();
     }
     LansHeld h;
-    double s_x = 0.0, s_r = 0.0, s_c = 0.0;
+    // a thread's eight squares are summed in f32 (a relative error of a few 1e-7 in its share,
+    // the same order as the reciprocals of `ratios_fast`), everything above that in f64
+    float f_x = 0.0f, f_r = 0.0f, f_c = 0.0f;
 #pragma unroll
     for (int u = 0; u < kLRows; ++u) {
       const uint32_t mi[4] = {raw.m[u].x, raw.m[u].y, raw.m[u].z, raw.m[u].w};
@@ -581,13 +583,14 @@ __global__ __launch_bounds__(kLThreads) void lans_single_kernel(Geo g, ClusterGe
         h.xs[4 * u + c] = xj;
         h.ur[4 * u + c] = u_r;
         h.uc[4 * u + c] = u_c;
-        s_x = in ? fma((double)xj, (double)xj, s_x) : s_x;
-        s_r = in ? fma((double)u_r, (double)u_r, s_r) : s_r;
-        s_c = in ? fma((double)u_c, (double)u_c, s_c) : s_c;
+        f_x = in ? fmaf(xj, xj, f_x) : f_x;
+        f_r = in ? fmaf(u_r, u_r, f_r) : f_r;
+        f_c = in ? fmaf(u_c, u_c, f_c) : f_c;
       }
       row_buf(m + t.base, t.valid, u * kLRow, kLRow).store16<kNonTemporal>(as_u32x4(mo[0], mo[1], mo[2], mo[3]), threadIdx.x * 16);
       row_buf(v + t.base, t.valid, u * kLRow, kLRow).store16<kNonTemporal>(as_u32x4(vo[0], vo[1], vo[2], vo[3]), threadIdx.x * 16);
     }
+    const double s_x = (double)f_x, s_r = (double)f_r, s_c = (double)f_c;
     const uint32_t next = __builtin_amdgcn_readfirstlane(item + gridDim.x);
     const bool have_next = next < cg.n_items;
     if (have_next) lans_issue(g, cg, dec, x, m, v, next, raw);
