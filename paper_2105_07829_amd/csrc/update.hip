@@ -535,7 +535,7 @@ template <class DEC>
 __global__ __launch_bounds__(kLThreads) void lans_single_kernel(Geo g, ClusterGeo cg, DEC dec, float *x, float *m, float *v,
                                                                OptArgs o, double *slots, uint32_t *status) {
   __shared__ __align__(16) float lds[DEC::kLdsFloats];
-  __shared__ double red[kLThreads / 64];
+  __shared__ double red3[3 * (kLThreads / 64)];
   __shared__ double total_sh[3];
   constexpr uint32_t kNone = 0xffffffffu;
   uint32_t item = __builtin_amdgcn_readfirstlane(blockIdx.x);
@@ -590,13 +590,34 @@ __global__ __launch_bounds__(kLThreads) void lans_single_kernel(Geo g, ClusterGe
       row_buf(m + t.base, t.valid, u * kLRow, kLRow).store16<kNonTemporal>(as_u32x4(mo[0], mo[1], mo[2], mo[3]), threadIdx.x * 16);
       row_buf(v + t.base, t.valid, u * kLRow, kLRow).store16<kNonTemporal>(as_u32x4(vo[0], vo[1], vo[2], vo[3]), threadIdx.x * 16);
     }
-    const double s_x = (double)f_x, s_r = (double)f_r, s_c = (double)f_c;
     const uint32_t next = __builtin_amdgcn_readfirstlane(item + gridDim.x);
     const bool have_next = next < cg.n_items;
     if (have_next) lans_issue(g, cg, dec, x, m, v, next, raw);
-    const double t_x = cluster_block_reduce<false, kLThreads>(s_x, red);
-    const double t_r = cluster_block_reduce<false, kLThreads>(s_r, red);
-    const double t_c = cluster_block_reduce<false, kLThreads>(s_c, red);
+    // the three sums over the workgroup: a tree in f32 inside each wave (six levels, the same
+    // order of error as the threads' own sums; shuffling doubles cost a tenth of the kernel's
+    // instructions), the 16 waves' sums in f64 in fixed order
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+      f_x = f_x + __shfl_xor(f_x, off, 64);
+      f_r = f_r + __shfl_xor(f_r, off, 64);
+      f_c = f_c + __shfl_xor(f_c, off, 64);
+    }
+    __syncthreads();   // (red3 of the tile before has been read)
+    if ((threadIdx.x & 63) == 0) {
+      red3[3 * (threadIdx.x >> 6) + 0] = (double)f_x;
+      red3[3 * (threadIdx.x >> 6) + 1] = (double)f_r;
+      red3[3 * (threadIdx.x >> 6) + 2] = (double)f_c;
+    }
+    __syncthreads();
+    double t_x = 0.0, t_r = 0.0, t_c = 0.0;
+    if (threadIdx.x == 0) {
+#pragma unroll
+      for (int w = 0; w < kLThreads / 64; ++w) {
+        t_x += red3[3 * w + 0];
+        t_r += red3[3 * w + 1];
+        t_c += red3[3 * w + 2];
+      }
+    }
     if (threadIdx.x == 0) {
       // slot 3*tile + k of the partition holds this tile's k-th partial
       double *ps = slots + 3ull * t.p * cg.tiles_per_part;
