@@ -479,7 +479,8 @@ __device__ inline void lans_issue(const Geo &g, const ClusterGeo &cg, const DEC 
 }
 
 // First wave: the three totals of a partition once all its tiles have published theirs.
-__device__ inline void lans_collect(const double *ps, uint32_t tiles_in_part, uint32_t *status, double *total_sh) {
+__device__ inline void lans_collect(const OptArgs &o, const double *ps, uint32_t tiles_in_part, uint32_t *status,
+                                    float *weights_sh) {
   const uint32_t lane = threadIdx.x;
   double a0, a1, a2;
   int spins = 0;
@@ -505,20 +506,26 @@ __device__ inline void lans_collect(const double *ps, uint32_t tiles_in_part, ui
   a0 = wave_sum(a0);
   a1 = wave_sum(a1);
   a2 = wave_sum(a2);
-  if (lane == 0) { total_sh[0] = a0; total_sh[1] = a1; total_sh[2] = a2; }
+  if (lane == 0) {
+    // phi(||x||) and the two weights beta1 / ||r + wd x||, (1 - beta1) / ||c + wd x||, once per tile
+    // (three square roots of doubles and two divisions: as much arithmetic as a thread's eight
+    // elements take, when every thread did them)
+    const float norm_x = (float)sqrt(a0);
+    const float norm_r = (float)sqrt(a1);
+    const float norm_c = (float)sqrt(a2);
+    float phi = norm_x < o.phi_lo ? o.phi_lo : norm_x;
+    phi = phi > o.phi_hi ? o.phi_hi : phi;
+    weights_sh[0] = phi;
+    weights_sh[1] = norm_r > 0.0f ? o.beta1 / norm_r : 0.0f;
+    weights_sh[2] = norm_c > 0.0f ? (1.0f - o.beta1) / norm_c : 0.0f;
+  }
 }
 
-// x of a tile whose partition's totals are in total_sh.
+// x of a tile whose partition's phi and weights are in weights_sh.
 __device__ inline void lans_write_x(const Geo &g, const ClusterGeo &cg, const OptArgs &o, float *x, uint32_t item,
-                                    const LansHeld &h, const double *total_sh) {
+                                    const LansHeld &h, const float *weights_sh) {
   const LansTile t = lans_tile(g, cg, item);
-  const float norm_x = (float)sqrt(total_sh[0]);
-  const float norm_r = (float)sqrt(total_sh[1]);
-  const float norm_c = (float)sqrt(total_sh[2]);
-  float phi = norm_x < o.phi_lo ? o.phi_lo : norm_x;
-  phi = phi > o.phi_hi ? o.phi_hi : phi;
-  const float w_r = norm_r > 0.0f ? o.beta1 / norm_r : 0.0f;
-  const float w_c = norm_c > 0.0f ? (1.0f - o.beta1) / norm_c : 0.0f;
+  const float phi = weights_sh[0], w_r = weights_sh[1], w_c = weights_sh[2];
 #pragma unroll
   for (int u = 0; u < kLRows; ++u) {
     float xo[4];
@@ -536,7 +543,7 @@ __global__ __launch_bounds__(kLThreads) void lans_single_kernel(Geo g, ClusterGe
                                                                OptArgs o, double *slots, uint32_t *status) {
   __shared__ __align__(16) float lds[DEC::kLdsFloats];
   __shared__ double red3[3 * (kLThreads / 64)];
-  __shared__ double total_sh[3];
+  __shared__ float total_sh[3];   // phi and the two weights of the tile being written
   constexpr uint32_t kNone = 0xffffffffu;
   uint32_t item = __builtin_amdgcn_readfirstlane(blockIdx.x);
   if (item >= cg.n_items) return;
@@ -627,7 +634,7 @@ __global__ __launch_bounds__(kLThreads) void lans_single_kernel(Geo g, ClusterGe
     }
     if (prev != kNone && threadIdx.x < 64) {
       const LansTile tp = lans_tile(g, cg, prev);
-      lans_collect(slots + 3ull * tp.p * cg.tiles_per_part, tp.tiles_in_part, status, total_sh);
+      lans_collect(o, slots + 3ull * tp.p * cg.tiles_per_part, tp.tiles_in_part, status, total_sh);
     }
     __syncthreads();
     if (prev != kNone) lans_write_x(g, cg, o, x, prev, prev_h, total_sh);
@@ -640,7 +647,7 @@ __global__ __launch_bounds__(kLThreads) void lans_single_kernel(Geo g, ClusterGe
   __syncthreads();
   if (threadIdx.x < 64) {
     const LansTile tp = lans_tile(g, cg, prev);
-    lans_collect(slots + 3ull * tp.p * cg.tiles_per_part, tp.tiles_in_part, status, total_sh);
+    lans_collect(o, slots + 3ull * tp.p * cg.tiles_per_part, tp.tiles_in_part, status, total_sh);
   }
   __syncthreads();
   lans_write_x(g, cg, o, x, prev, prev_h, total_sh);
