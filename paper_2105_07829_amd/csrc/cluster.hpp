@@ -210,7 +210,11 @@ __device__ inline double cluster_block_reduce(double x, double *red /*THREADS/64
 //   double phase1(item, Raw&, Held&, table) const;   consume the loads (ticketed: request them
 //                                                first), return the tile's partial
 //   void   early(item, Held&) const;             stores that do not need the norm
-//   Ctx    begin2(item, total, table) / row2(item, row, Held&, Ctx) const;   outputs of one row
+//   float  scale_of(item, total) const;         the partition's scale from the total (one thread
+//                                                forms it: a division or a root of doubles per
+//                                                thread and tile was a sixth of the sign kernels'
+//                                                instructions)
+//   Ctx    begin2(item, scale, table) / row2(item, row, Held&, Ctx) const;   outputs of one row
 //   void   slots_of(item, first, count)          the partition's slots
 //   static constexpr int kRowsPerTile; static constexpr bool kMax (maximum instead of sum)
 //   static constexpr int kTableFloats (LDS scratch, `table`)
@@ -223,7 +227,7 @@ __device__ inline void cluster_run_ticketed(const Op &op, float *table, double *
   constexpr int kT = Op::kThreads;
   constexpr uint32_t kNone = 0xffffffffu;
   __shared__ double red[kT / 64];
-  __shared__ double total_sh;
+  __shared__ float scale_sh;
   __shared__ uint32_t item_sh;
   const uint32_t n_items = op.n_items();
   typename Op::Held held_prev;
@@ -244,21 +248,21 @@ __device__ inline void cluster_run_ticketed(const Op &op, float *table, double *
     uint32_t ticket = kNone;
     // (reading the older tile's slots before phase 1, as the persistent driver does,
     // was slower here: phase 1 of these operators has no registers to spare for the values)
-    if (prev != kNone) {
-      if (threadIdx.x < 64 && op.needs_total()) {
+    if (prev != kNone && threadIdx.x < 64) {
+      double total = 0.0;
+      if (op.needs_total()) {
         uint32_t first, count;
         op.slots_of(prev, &first, &count);
-        double total = slots_collect<Op::kMax>(slots + first, count, status);
-        if (threadIdx.x == 0) total_sh = total;
+        total = slots_collect<Op::kMax>(slots + first, count, status);
       }
+      if (threadIdx.x == 0) scale_sh = op.scale_of(prev, total);
     }
     // the next ticket is on its way while the older tile is written out
     if (have && threadIdx.x == 0) ticket = atomicAdd(status + 1, 1u);
     if (have) op.early(item, held);
     __syncthreads();
     if (prev != kNone) {
-      const double total = total_sh;
-      const typename Op::Ctx ctx = op.begin2(prev, total, table);
+      const typename Op::Ctx ctx = op.begin2(prev, scale_sh, table);
 #pragma unroll
       for (int u = 0; u < Op::kRowsPerTile; ++u) op.row2(prev, u, held_prev, ctx);
     }
@@ -278,7 +282,7 @@ __device__ inline void cluster_run_persistent(const Op &op, float *table, double
   constexpr int kT = Op::kThreads;
   constexpr uint32_t kNone = 0xffffffffu;
   __shared__ double red[kT / 64];
-  __shared__ double total_sh;
+  __shared__ float scale_sh;
   const uint32_t n_items = op.n_items();
   uint32_t item = __builtin_amdgcn_readfirstlane(blockIdx.x);
   if (item >= n_items) return;
@@ -307,14 +311,15 @@ __device__ inline void cluster_run_persistent(const Op &op, float *table, double
     }
     part = cluster_block_reduce<Op::kMax, kT>(part, red);
     if (threadIdx.x == 0 && op.needs_total()) slot_publish(slots + item, part);
-    if (collects) {
-      double total = slots_finish<Op::kMax>(probe, slots + first, count, status);
-      if (threadIdx.x == 0) total_sh = total;
+    if (prev != kNone && threadIdx.x < 64) {
+      double total = 0.0;
+      if (collects) total = slots_finish<Op::kMax>(probe, slots + first, count, status);
+      if (threadIdx.x == 0) scale_sh = op.scale_of(prev, total);
     }
     op.early(item, held);
     __syncthreads();
     if (prev != kNone) {
-      const typename Op::Ctx ctx = op.begin2(prev, total_sh, table);
+      const typename Op::Ctx ctx = op.begin2(prev, scale_sh, table);
 #pragma unroll
       for (int u = 0; u < Op::kRowsPerTile; ++u) op.row2(prev, u, held_prev, ctx);
     }
@@ -326,14 +331,17 @@ __device__ inline void cluster_run_persistent(const Op &op, float *table, double
   }
   // the last tile
   __syncthreads();
-  if (threadIdx.x < 64 && op.needs_total()) {
-    uint32_t first, count;
-    op.slots_of(prev, &first, &count);
-    double total = slots_collect<Op::kMax>(slots + first, count, status);
-    if (threadIdx.x == 0) total_sh = total;
+  if (threadIdx.x < 64) {
+    double total = 0.0;
+    if (op.needs_total()) {
+      uint32_t first, count;
+      op.slots_of(prev, &first, &count);
+      total = slots_collect<Op::kMax>(slots + first, count, status);
+    }
+    if (threadIdx.x == 0) scale_sh = op.scale_of(prev, total);
   }
   __syncthreads();
-  const typename Op::Ctx ctx = op.begin2(prev, total_sh, table);
+  const typename Op::Ctx ctx = op.begin2(prev, scale_sh, table);
 #pragma unroll
   for (int u = 0; u < Op::kRowsPerTile; ++u) op.row2(prev, u, held_prev, ctx);
 }

@@ -117,9 +117,8 @@ struct DitherWorkerOp {
     }
   }
 
-  __device__ Ctx begin2(uint32_t item, double total, float *mag) const {
-    const uint32_t p = part_of(item);
-    const float nu = nu_of(p, total);
+  __device__ float scale_of(uint32_t item, double total) const { return nu_of(part_of(item), total); }
+  __device__ Ctx begin2(uint32_t item, float nu, float *mag) const {
     header(item, nu);
     dither_fill_table(nu, levels, NAT, mag);
     const float top_over_nu = dither_top(levels, NAT) / nu;

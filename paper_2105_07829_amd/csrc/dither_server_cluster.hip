@@ -249,9 +249,9 @@ struct DitherServerOp {
     if (override) return uniform_load(override + p);
     return LINF ? (float)total : (float)sqrt(total);
   }
-  __device__ Ctx begin2(uint32_t item, double total, float *table) const {
+  __device__ float scale_of(uint32_t item, double total) const { return nu_of(part_of(item), total); }
+  __device__ Ctx begin2(uint32_t item, float nu, float *table) const {
     const uint32_t p = part_of(item);
-    const float nu = nu_of(p, total);
     if (tile_off(item) == 0 && threadIdx.x == 0) {
       uint32_t *hdr = reinterpret_cast<uint32_t *>(payload + (uint64_t)p * g.stride);
       hdr[0] = __float_as_uint(nu);

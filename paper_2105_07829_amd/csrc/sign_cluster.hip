@@ -137,8 +137,8 @@ struct SignWorkerOp {
     }
   }
 
-  __device__ Ctx begin2(uint32_t item, double total, float *) const {
-    const float sigma = sigma_of(part_of(item), total);
+  __device__ float scale_of(uint32_t item, double total) const { return sigma_of(part_of(item), total); }
+  __device__ Ctx begin2(uint32_t item, float sigma, float *) const {
     header(item, sigma);
     return Ctx{sigma};
   }

@@ -233,8 +233,8 @@ struct SignServerOp {
       hdr[1] = 0; hdr[2] = 0; hdr[3] = 0;
     }
   }
-  __device__ Ctx begin2(uint32_t item, double total, float *) const {
-    const float sigma = sigma_of(part_of(item), total);
+  __device__ float scale_of(uint32_t item, double total) const { return sigma_of(part_of(item), total); }
+  __device__ Ctx begin2(uint32_t item, float sigma, float *) const {
     header(item, sigma);
     return Ctx{sigma};
   }
