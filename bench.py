@@ -238,7 +238,8 @@ def cpu_baseline(name, w, n_parts, n_steps, synth):
 
 def recorded_traffic(workload, stage):
     """HBM bytes per launch of a stage as measured with rocprofv3 counters (profiles/), or None."""
-    names = {"bert_large": "bench_bert_large_dither.txt", "resnet50": "bench_resnet50_topk.txt"}
+    names = {"bert_large": "bench_bert_large_dither.txt", "resnet50": "bench_resnet50_topk.txt",
+             "vgg16": "bench_vgg16_randk.txt"}
     path = os.path.join(ROOT, "profiles", names.get(workload, f"bench_{workload}.txt"))
     try:
         for line in open(path):
