@@ -40,6 +40,10 @@ static bool is_capturing(hipStream_t stream) {
   return st != hipStreamCaptureStatusNone;
 }
 
+// The event is recorded only when it is needed: when a launch comes on another stream than the
+// one before, on that earlier stream (it then covers the earlier kernel and whatever that
+// stream was given since, which is more than needed and never less).  Recording one after
+// every launch cost each call some microseconds of idle device time.
 hipError_t cluster_launch_begin(hipStream_t stream) {
   if (is_capturing(stream)) return hipSuccess;
   int dev = 0;
@@ -47,8 +51,19 @@ hipError_t cluster_launch_begin(hipStream_t stream) {
   if (e != hipSuccess) return e;
   if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
   std::lock_guard<std::mutex> lock(g_mu);
-  if (g_have[dev] && g_last_stream[dev] != stream) return hipStreamWaitEvent(stream, g_event[dev], 0);
-  return hipSuccess;
+  if (!g_have[dev] || g_last_stream[dev] == stream) return hipSuccess;
+  if (is_capturing(g_last_stream[dev])) return hipSuccess;   // (nothing can be recorded on it now)
+  if (!g_event[dev]) {
+    e = hipEventCreateWithFlags(&g_event[dev], hipEventDisableTiming);
+    if (e != hipSuccess) return e;
+  }
+  e = hipEventRecord(g_event[dev], g_last_stream[dev]);
+  if (e != hipSuccess) {
+    // the earlier stream is gone: wait for everything on the device instead
+    (void)hipGetLastError();
+    return hipDeviceSynchronize();
+  }
+  return hipStreamWaitEvent(stream, g_event[dev], 0);
 }
 
 hipError_t cluster_launch_end(hipStream_t stream) {
@@ -58,12 +73,6 @@ hipError_t cluster_launch_end(hipStream_t stream) {
   if (e != hipSuccess) return e;
   if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
   std::lock_guard<std::mutex> lock(g_mu);
-  if (!g_event[dev]) {
-    e = hipEventCreateWithFlags(&g_event[dev], hipEventDisableTiming);
-    if (e != hipSuccess) return e;
-  }
-  e = hipEventRecord(g_event[dev], stream);
-  if (e != hipSuccess) return e;
   g_last_stream[dev] = stream;
   g_have[dev] = true;
   return hipSuccess;

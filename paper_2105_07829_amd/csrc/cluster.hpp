@@ -91,7 +91,8 @@ inline SplitGeo split_geo(const Geo &g, uint32_t tile, bool ragged_ok) {
 
 // Host side: the arguments above count the resident workgroups of ONE kernel.  Two cluster
 // kernels running concurrently (different streams) would share the device, so launches are
-// chained: every launch records an event, and a launch on another stream first waits for it.
+// chained: a launch on another stream than the one before first waits for an event recorded
+// on that earlier stream.
 hipError_t cluster_launch_begin(hipStream_t stream);
 hipError_t cluster_launch_end(hipStream_t stream);
 // Number of workgroups of `kernel` (`threads` threads, `dyn_lds` bytes of dynamic LDS) resident at once.
