@@ -10,18 +10,19 @@
 //   sample     : 4096 elements of each partition (512 evenly spread chunks of eight); the key G
 //                at a rank of the sample chosen so that, but for rare cases, at least k and
 //                at most about 2 k elements of the partition have keys >= G
-//   load+hist1 : v_j from the source -> dense buffer; histogram of key >> 20; the elements
-//                with key >= G go to the partition's short list
+//   load+hist1 : v_j from the source -> dense buffer; the elements with key >= G go to the
+//                partition's short list and into the histogram of key >> 20
 //   select     : one workgroup per partition runs the radix select on the short list alone
 //                and writes the record; kept slots of the buffer zeroed
 // The sample only decides how much work the selection is, never its result: a partition whose
 // short list came out shorter than k or longer than kTopkListCap (the sample misled, or a
 // great many equal magnitudes, or fewer than k non-zeros) is taken by the long form below
-// instead, whose kernels are enqueued behind with a small grid and return at once if no
-// partition needs them.
+// instead: one more kernel, enqueued behind, which returns at once if no partition needs it
+// and else runs the long form's passes for those partitions (the rest of their level-1
+// histogram first) with its resident grid meeting between the passes.
 //
-// Long form, five passes over the dense buffer:
-//   load+hist1 : as above
+// Long form (a k too large for a short list), five passes over the dense buffer:
+//   load+hist1 : as above, every element counted
 //   hist2      : bin of level 1 that holds the k-th largest key, histogram inside it
 //   hist3      : the same one level down
 //   count      : threshold key T and the number r of elements with key == T that are kept;
@@ -54,7 +55,7 @@ constexpr int kBits1 = 11, kBits23 = 10;
 constexpr int kTpgLoad = 2, kTpgHist2 = 4, kTpgHist3 = 1, kTpgCount = 1;
 constexpr int kSelThreads = 1024;                       // workgroup of the select pass
 constexpr int kSelPer = kTopkListCap / kSelThreads;     // list entries a thread of it keeps
-constexpr uint32_t kGatedGrid = 1024;                   // grid of a long-form kernel that may have nothing to do
+constexpr uint32_t kGatedGrid = 1024;                   // grid of the long-form kernel behind the short-list form, at most
 constexpr int kSamplePer = 16;                          // sampled elements per thread of the sample pass
 constexpr uint32_t kSample = kThreads * kSamplePer;     // per partition: 4096
 constexpr uint32_t kNoGuess = 0xffffffffu;              // no key reaches it: nothing goes to the short list
