@@ -434,18 +434,24 @@ struct has_begin_group<SRC, std::void_t<decltype(&SRC::begin_group)>> : std::tru
 // inside it come out the same as long as the list holds k elements; every non-empty bin of every
 // workgroup is one atomic on global memory, and with all elements counted those atomics were
 // most of this pass on the server side); without a guess it takes all elements.
-template <class SRC>
+// LISTED (every partition has a guess): only the listed elements are counted, and their bins
+// start at the guess's, so the LDS histogram is kNearBins bins from there (8 KB less LDS a
+// workgroup: a fourth workgroup per compute unit on the server side); the rare key beyond them
+// goes to the partition's histogram directly.
+constexpr int kNearBins = 64;
+template <class SRC, bool LISTED>
 __global__ __launch_bounds__(kThreads) void topk_load_hist1_kernel(Geo g, SRC src, float *buf, uint32_t *hist, uint32_t *state,
                                                                    const uint32_t *guess, uint32_t *groupcnt,
                                                                    uint32_t *cand_idx, uint32_t *cand_val) {
   __shared__ __align__(16) float lds[SRC::kLdsFloats];
-  __shared__ uint32_t h[kBins1];
+  constexpr int kLocalBins = LISTED ? kNearBins : kBins1;
+  __shared__ uint32_t h[kLocalBins];
   __shared__ uint32_t scan[kThreads];
   __shared__ uint32_t off_sh;
   constexpr int kPieces = kTpgLoad * (kTile / (kThreads * 8));  // pieces of kThreads * 8 elements: 4
   static_assert(kPieces == 4, "two scans of two 16-bit counts");
   const GroupOf w = group_of<kTpgLoad>(g, blockIdx.x);
-  for (int b = threadIdx.x; b < kBins1; b += kThreads) h[b] = 0;
+  for (int b = threadIdx.x; b < kLocalBins; b += kThreads) h[b] = 0;
   src.begin(g, w.p, lds);
   __syncthreads();
   if (w.tile_lo >= w.tile_hi) return;  // (uniform) past the end of a shorter last partition
@@ -487,7 +493,15 @@ __global__ __launch_bounds__(kThreads) void topk_load_hist1_kernel(Geo g, SRC sr
         if (j0 + 8 > w.d) buf[base + j0 + e] = v[c][e];
         const uint32_t key = key_of(v[c][e]);
         const bool listed = key >= G;
-        if (listed || G == kNoGuess) atomicAdd(&h[key >> kShift1], 1u);
+        if (LISTED) {
+          if (listed) {
+            const uint32_t rel = (key >> kShift1) - (G >> kShift1);
+            if (rel < (uint32_t)kNearBins) atomicAdd(&h[rel], 1u);
+            else atomicAdd(&hist[(uint64_t)w.p * kTopkHistWords + kHist1 + (key >> kShift1)], 1u);
+          }
+        } else {
+          atomicAdd(&h[key >> kShift1], 1u);
+        }
         mask[c] |= (uint32_t)listed << e;
       }
     }
@@ -525,9 +539,9 @@ __global__ __launch_bounds__(kThreads) void topk_load_hist1_kernel(Geo g, SRC sr
     }
   }
   __syncthreads();
-  uint32_t *gh = hist + (uint64_t)w.p * kTopkHistWords + kHist1;
-  for (int b = threadIdx.x; b < kBins1; b += kThreads)
-    if (h[b]) atomicAdd(&gh[b], h[b]);
+  uint32_t *gh = hist + (uint64_t)w.p * kTopkHistWords + kHist1 + (LISTED ? (G >> kShift1) : 0u);
+  for (int b = threadIdx.x; b < kLocalBins; b += kThreads)
+    if (h[b]) atomicAdd(&gh[b], h[b]);   // (LISTED: bins past the last one hold nothing)
 }
 
 // The selection state of partition p after `LEVEL` levels in sel[0] (prefix / threshold key)
@@ -1025,7 +1039,9 @@ hipError_t topk_encode(const Geo &g, const bpc_params_t &prm, const bpc_params_t
   const uint32_t sample_grid = g.P > 64 ? g.P : 64, load_grid = group_count(g, kTpgLoad);
   auto first_two = [&](auto s_sample, auto s_load) {
     topk_sample_kernel<<<sample_grid, kThreads, 0, stream>>>(g, s_sample, hist, state, guess, short_list, ws.at<uint32_t>(ws.lay.status));
-    topk_load_hist1_kernel<<<load_grid, kThreads, 0, stream>>>(g, s_load, buf, hist, state, guess, tilecnt, cand_idx, cand_val);
+    using Load = decltype(s_load);
+    if (short_list) topk_load_hist1_kernel<Load, true><<<load_grid, kThreads, 0, stream>>>(g, s_load, buf, hist, state, guess, tilecnt, cand_idx, cand_val);
+    else topk_load_hist1_kernel<Load, false><<<load_grid, kThreads, 0, stream>>>(g, s_load, buf, hist, state, guess, tilecnt, cand_idx, cand_val);
   };
   if (src.grad) {
     if (src.dtype == BPC_F16) {
