@@ -181,6 +181,37 @@ def test_topk_server_both_forms(gu, orc, kind, ratio):
     assert np.array_equal(res_gpu.view(np.uint32), res_ref.view(np.uint32))
 
 
+@pytest.mark.parametrize("kind", ["topk", "topk16"])
+def test_topk_heavy_tail(gu, orc, kind):
+    """A few hundred coordinates four orders of magnitude above the rest (far more than the 64
+    eighth-octave bins above the guess that the load pass counts in LDS): worker and server
+    still give the oracle's record and residual."""
+    pe = BIG_PE
+    D = 2 * pe + 70001
+    ratio = 0.011
+    n = 3
+    ins = [gu.both_params(orc, kind, pe, k_ratio=ratio) for _ in range(n)]
+    out_o, out_b = gu.both_params(orc, kind, pe, k_ratio=ratio)
+    rs = np.random.default_rng(43)
+    common = rs.standard_normal(D).astype(np.float32)
+    tail = rs.choice(D, 300, replace=False)
+    common[tail] *= np.float32(3e4) if kind == "topk" else np.float32(2e3)   # (half-precision values: below 65504)
+    grads = [(common + 0.3 * rs.standard_normal(D)).astype(np.float32) for _ in range(n)]
+    e = (0.3 * rs.standard_normal(D)).astype(np.float32)
+    res_ref = e.copy()
+    pay_ref = orc.compress(ins[0][0], grads[0], res_ref)
+    pay_gpu, res_gpu = gu.gpu_compress(ins[0][1], grads[0], e.copy())
+    assert defined_equal(kind, pay_gpu, pay_ref, ins[0][0], orc, D, pe, dict(k_ratio=ratio))
+    assert np.array_equal(res_gpu.view(np.uint32), res_ref.view(np.uint32))
+    payloads = [orc.compress(ins[i][0], grads[i], None) for i in range(n)]
+    et = (0.05 * rs.standard_normal(D)).astype(np.float32)
+    res_ref = et.copy()
+    pay_ref = orc.server_aggregate([p[0] for p in ins], payloads, out_o, res_ref, D)
+    pay_gpu, res_gpu = gu.gpu_server([p[1] for p in ins], payloads, out_b, et, D)
+    assert defined_equal(kind, pay_gpu, pay_ref, out_o, orc, D, pe, dict(k_ratio=ratio))
+    assert np.array_equal(res_gpu.view(np.uint32), res_ref.view(np.uint32))
+
+
 def test_topk_sample_that_misleads(gu, orc):
     """The short list is built from a guess taken from a sample of the partition (512 chunks of
     eight elements; chunk c is chunk c*stride + (c*37) % stride of the partition, stride =
