@@ -98,31 +98,51 @@ struct DitherWideDec {
     if (threadIdx.x < 128) lds[threadIdx.x] = entry(*reinterpret_cast<const float *>(payload + (uint64_t)p * stride), threadIdx.x);
     __syncthreads();
   }
-  // the nibbles of 4 elements in bits 0..15, then 4 bits of each plane in bits 16.., 20.., 24..
-  using R4 = uint32_t;
+  // The nibbles of 4 elements and the byte of each plane that holds their bits, as loaded:
+  // nothing is combined here, so a caller that requests a tile ahead of its use does not wait
+  // for the loads at the request.
+  struct R4 { uint32_t nib, plane[3]; };
   __device__ float header(uint32_t p) const { return *reinterpret_cast<const float *>(payload + (uint64_t)p * stride); }
   __device__ void table(float nu, float *lds) const {
     if (threadIdx.x < 128) lds[threadIdx.x] = entry(nu, threadIdx.x);
   }
   __device__ R4 load4(const Geo &, uint32_t p, uint32_t j, const TileBuf &) const {
     const uint8_t *rec = payload + (uint64_t)p * stride;
+    R4 r;
+    r.nib = reinterpret_cast<const uint16_t *>(rec + kHeaderBytes)[j >> 2];
+    const uint32_t planes = dither_planes(levels);
+    const uint8_t *plane = rec + dither_plane0(part_elems) + (j >> 3);
+    r.plane[0] = plane[0];
+    r.plane[1] = planes > 1 ? plane[dither_plane_bytes(part_elems)] : 0u;
+    r.plane[2] = planes > 2 ? plane[2 * dither_plane_bytes(part_elems)] : 0u;
+    return r;
+  }
+  __device__ void decode4(R4 r, uint32_t j, float, const float *lds, float out[4]) const {
+    uint32_t bits[3];
+#pragma unroll
+    for (uint32_t t = 0; t < 3; ++t) bits[t] = (r.plane[t] >> (j & 4u)) & 15u;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const uint32_t nib = (r.nib >> (4 * c)) & 15u;
+      const uint32_t hi = ((bits[0] >> c) & 1u) | (((bits[1] >> c) & 1u) << 1) | (((bits[2] >> c) & 1u) << 2);
+      out[c] = lds[(hi << 4) | nib];
+    }
+  }
+  // Load and decode in one place: the nibbles of 4 elements in bits 0..15, then 4 bits of each
+  // plane in bits 16.., 20.., 24..
+  __device__ void at4(const Geo &, uint32_t p, uint32_t j, const TileBuf &, const float *lds, float out[4]) const {
+    const uint8_t *rec = payload + (uint64_t)p * stride;
     uint32_t r = reinterpret_cast<const uint16_t *>(rec + kHeaderBytes)[j >> 2];
     const uint32_t planes = dither_planes(levels);
     const uint8_t *plane = rec + dither_plane0(part_elems) + (j >> 3);
     for (uint32_t t = 0; t < planes; ++t)
       r |= (((uint32_t)plane[t * dither_plane_bytes(part_elems)] >> (j & 4)) & 15u) << (16 + 4 * t);
-    return r;
-  }
-  __device__ void decode4(R4 r, uint32_t, float, const float *lds, float out[4]) const {
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
       const uint32_t nib = (r >> (4 * c)) & 15u;
       const uint32_t hi = ((r >> (16 + c)) & 1u) | (((r >> (20 + c)) & 1u) << 1) | (((r >> (24 + c)) & 1u) << 2);
       out[c] = lds[(hi << 4) | nib];
     }
-  }
-  __device__ void at4(const Geo &g, uint32_t p, uint32_t j, const TileBuf &row, const float *lds, float out[4]) const {
-    decode4(load4(g, p, j, row), j, 0.0f, lds, out);
   }
   __device__ float at(const Geo &g, uint32_t p, uint32_t j, const float *lds) const {
     float out[4];
@@ -738,9 +758,6 @@ hipError_t adaptive_update(const Geo &g, const bpc_params_t &prm, const uint8_t 
     case BPC_SIGN: return run_update(g, SignDec{payload, g.stride}, x, m, v, opt, norms, ws, stream);
     case BPC_DITHER: case BPC_NATDITHER:
       if (prm.kind == BPC_DITHER && dither_planes(prm.levels) > 0) {
-        // bit planes: the Adam-style update decodes them itself; LANS, which is bound by its
-        // arithmetic, was faster reading a dense decode (below)
-        if (opt.kind == BPC_OPT_LANS) break;
         return run_update(g, DitherWideDec{payload, g.stride, prm.levels, g.part_elems}, x, m, v, opt, norms, ws, stream);
       }
       return run_update(g, DitherDec{payload, g.stride, prm.levels, prm.kind == BPC_NATDITHER}, x, m, v, opt, norms, ws, stream);
