@@ -156,5 +156,20 @@ def test_full_size_pipeline(env, orc, name):
                             orc.make_opt(orc.OPT_ADAM, 1e-3, 0.9, 0.999, 1e-8, 0.01, step))
         for got, ref in ((x, xo), (m, mo), (v, vo)):
             assert np.array_equal(got[sl(p)].cpu().numpy().view(np.uint32), ref.view(np.uint32)), (name, "update", p)
+    # ---------------- and a LANS step (the partitions are the blocks) on the state that step left
+    before = {p: tuple(t[sl(p)].cpu().numpy() for t in (x, m, v)) for p in parts}
+    step = 4
+    bpc.bpc_adaptive_update(prm_b(out_stream), out_pay, x, m, v,
+                            bpc.make_opt(bpc.OPT_LANS, 1e-3, 0.9, 0.999, 1e-8, 0.01, step), ws)
+    torch.cuda.synchronize()
+    for p in parts:
+        d = sl(p).stop - sl(p).start
+        xo, mo, vo = (a.copy() for a in before[p])
+        rec = out_pay[p * strd:(p + 1) * strd].cpu().numpy()
+        orc.adaptive_update(prm_o(out_stream, p), rec, d, xo, mo, vo,
+                            orc.make_opt(orc.OPT_LANS, 1e-3, 0.9, 0.999, 1e-8, 0.01, step))
+        for got, ref in ((m, mo), (v, vo)):
+            assert np.array_equal(got[sl(p)].cpu().numpy().view(np.uint32), ref.view(np.uint32)), (name, "lans", p)
+        assert gu.close(x[sl(p)].cpu().numpy(), xo, REL), (name, "lans x", p)
     del pays, sres, out_pay, x, m, v, ws
     torch.cuda.empty_cache()

@@ -257,6 +257,34 @@ def test_update_stage(gu, orc, name, opt_kind):
         assert gu.close(xg, x, REL)
 
 
+@pytest.mark.parametrize("name", sorted(KW))
+@pytest.mark.parametrize("opt_kind", ["adam", "lans"])
+def test_update_stage_large_partitions(gu, orc, name, opt_kind):
+    """Partitions of several tiles of the update kernels (16 tiles of the single-pass LANS kernel,
+    whose workgroups exchange their parts of the three block norms), a last partition of full
+    tiles and a ragged one, and a gradient of less than a tile."""
+    bpc = gu.bpc
+    for D in (BIG_D, 4137):
+        po, pb = gu.both_params(orc, base_kind(name), BIG_PE, **KW[name])
+        payload = orc.compress(po, grads(D, np.float32, 23, scale=1e-2), None)
+        x0 = (rng(4).standard_normal(D) * 0.02).astype(np.float32)
+        m0 = (rng(5).standard_normal(D) * 1e-3).astype(np.float32)
+        v0 = (rng(6).random(D) * 1e-5).astype(np.float32)
+        ko = orc.OPT_ADAM if opt_kind == "adam" else orc.OPT_LANS
+        kb = bpc.OPT_ADAM if opt_kind == "adam" else bpc.OPT_LANS
+        oo = orc.make_opt(ko, 1e-3, 0.9, 0.999, 1e-8, 0.01, 5)
+        ob = bpc.make_opt(kb, 1e-3, 0.9, 0.999, 1e-8, 0.01, 5)
+        x, m, v = x0.copy(), m0.copy(), v0.copy()
+        orc.adaptive_update(po, payload, D, x, m, v, oo)
+        xg, mg, vg = gu.gpu_update(pb, payload, x0, m0, v0, ob)
+        assert np.array_equal(mg.view(np.uint32), m.view(np.uint32)), (name, D)
+        assert np.array_equal(vg.view(np.uint32), v.view(np.uint32)), (name, D)
+        if opt_kind == "adam":
+            assert np.array_equal(xg.view(np.uint32), x.view(np.uint32)), (name, D)
+        else:
+            assert gu.close(xg, x, REL), (name, D)
+
+
 def test_deterministic_bytes(gu, orc):
     """Same call twice gives identical bytes for the kinds whose arithmetic has a fixed order."""
     D = 2 * PE + 4137
