@@ -258,11 +258,12 @@ def test_update_stage(gu, orc, name, opt_kind):
 
 
 @pytest.mark.parametrize("name", sorted(KW))
-@pytest.mark.parametrize("opt_kind", ["adam", "lans"])
+@pytest.mark.parametrize("opt_kind", ["adam", "lans", "lans_blocks"])
 def test_update_stage_large_partitions(gu, orc, name, opt_kind):
     """Partitions of several tiles of the update kernels (16 tiles of the single-pass LANS kernel,
     whose workgroups exchange their parts of the three block norms), a last partition of full
     tiles and a ragged one, and a gradient of less than a tile."""
+    import torch
     bpc = gu.bpc
     for D in (BIG_D, 4137):
         po, pb = gu.both_params(orc, base_kind(name), BIG_PE, **KW[name])
@@ -272,8 +273,12 @@ def test_update_stage_large_partitions(gu, orc, name, opt_kind):
         v0 = (rng(6).random(D) * 1e-5).astype(np.float32)
         ko = orc.OPT_ADAM if opt_kind == "adam" else orc.OPT_LANS
         kb = bpc.OPT_ADAM if opt_kind == "adam" else bpc.OPT_LANS
-        oo = orc.make_opt(ko, 1e-3, 0.9, 0.999, 1e-8, 0.01, 5)
-        ob = bpc.make_opt(kb, 1e-3, 0.9, 0.999, 1e-8, 0.01, 5)
+        # caller-defined blocks: inside a tile, across tiles and across a partition boundary
+        blocks = np.array(sorted({0, min(1000, D), min(BIG_PE + 3, D), min(2 * BIG_PE, D), D}), dtype=np.uint64) \
+            if opt_kind == "lans_blocks" else None
+        blocks_dev = None if blocks is None else torch.from_numpy(blocks.astype(np.int64)).to(gu.DEV)
+        oo = orc.make_opt(ko, 1e-3, 0.9, 0.999, 1e-8, 0.01, 5, block_offsets=blocks)
+        ob = bpc.make_opt(kb, 1e-3, 0.9, 0.999, 1e-8, 0.01, 5, block_offsets=blocks_dev)
         x, m, v = x0.copy(), m0.copy(), v0.copy()
         orc.adaptive_update(po, payload, D, x, m, v, oo)
         xg, mg, vg = gu.gpu_update(pb, payload, x0, m0, v0, ob)
