@@ -219,8 +219,8 @@ def test_server_stage_large_partitions(gu, orc, name, ef, n):
 
 @pytest.mark.parametrize("name", sorted(KW))
 def test_decompress(gu, orc, name):
-    for D in SHAPES:
-        po, pb = gu.both_params(orc, base_kind(name), PE, **KW[name])
+    for pe, D in [(PE, D) for D in SHAPES] + [(BIG_PE, BIG_D)]:
+        po, pb = gu.both_params(orc, base_kind(name), pe, **KW[name])
         payload = orc.compress(po, grads(D, np.float32, 3 + D), None)
         ref = orc.decompress(po, payload, D)
         got = gu.gpu_decompress(pb, payload, D)
