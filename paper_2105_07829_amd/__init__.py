@@ -21,14 +21,14 @@ IDENTITY, SIGN, TOPK, RANDK, DITHER, NATDITHER, FP16, TOPK16 = 0, 1, 2, 3, 4, 5,
 F32, F16 = 0, 1
 NORM_L2, NORM_LINF = 0, 1
 OPT_LANS, OPT_ADAM = 0, 1
-OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_ALIGNMENT, ERR_HIP = range(6)
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_ALIGNMENT, ERR_HIP, ERR_WAIT = range(7)
 MAX_WORKERS = 64
 
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-ffp-contract=off",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-fPIC", "-shared"]
 
 EXPORTS = ["bpc_partition_k", "bpc_partition_stride", "bpc_payload_bytes", "bpc_workspace_bytes",
-           "bpc_workspace_status_offset", "bpc_compress", "bpc_decompress", "bpc_server_aggregate", "bpc_adaptive_update",
+           "bpc_update_workspace_bytes", "bpc_workspace_status_offset", "bpc_workspace_check", "bpc_compress", "bpc_decompress", "bpc_server_aggregate", "bpc_adaptive_update",
            "bpc_status_string", "bpc_last_hip_error"]
 
 
@@ -90,6 +90,10 @@ def lib():
         L.bpc_workspace_bytes.restype = C.c_size_t
         L.bpc_workspace_status_offset.argtypes = [PP, C.c_uint64]
         L.bpc_workspace_status_offset.restype = C.c_size_t
+        L.bpc_update_workspace_bytes.argtypes = [PP, C.c_uint64, C.c_uint64]
+        L.bpc_update_workspace_bytes.restype = C.c_size_t
+        L.bpc_workspace_check.argtypes = [PP, C.c_uint64, C.c_void_p, C.c_void_p]
+        L.bpc_workspace_check.restype = C.c_int
         L.bpc_compress.argtypes = [PP, C.c_void_p, C.c_int, C.c_void_p, C.c_uint64, C.c_void_p,
                                    C.c_void_p, C.c_size_t, C.c_void_p]
         L.bpc_compress.restype = C.c_int
@@ -179,10 +183,20 @@ def workspace_bytes(p: Params, D: int, n: int = 1) -> int:
     return int(lib().bpc_workspace_bytes(C.byref(p), D, n))
 
 
+def update_workspace_bytes(p: Params, D: int, n_blocks: int = 0) -> int:
+    return int(lib().bpc_update_workspace_bytes(C.byref(p), D, n_blocks))
+
+
 def workspace_status(p: Params, D: int, ws) -> int:
     """Value of the workspace status word (synchronises the device); 0 means no wait timed out."""
     off = int(lib().bpc_workspace_status_offset(C.byref(p), D))
     return int(ws[off:off + 4].view(dtype=__import__("torch").int32).item())
+
+
+def workspace_check(p: Params, D: int, ws, stream=None) -> None:
+    """Waits for the stream and raises BpcError(ERR_WAIT) if a device-side wait of the last call
+    on ``ws`` gave up (its outputs are then undefined)."""
+    _check(lib().bpc_workspace_check(C.byref(p), D, _ptr(ws), _stream(stream)), "bpc_workspace_check")
 
 
 def _dtype_code(grad):

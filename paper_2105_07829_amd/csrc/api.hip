@@ -1,5 +1,5 @@
 // C ABI (include/bpc.h): argument validation on the host, then dispatch to the kernel
-// launchers.  Nothing here allocates or synchronises.
+// launchers.  Nothing here allocates, and only bpc_workspace_check() synchronises.
 #include <hip/hip_runtime.h>
 #include "kernels.hpp"
 
@@ -47,9 +47,41 @@ size_t bpc_workspace_status_offset(const bpc_params_t *params, uint64_t D) {
   return ws_layout(params, D).status;
 }
 
-static bpc_status_t check_size(uint64_t D) {
+// Workspace of an update call: LANS with caller-defined blocks keeps three f64 sums per block
+// where the layout has room for three per partition.
+static size_t update_ws_bytes(const WsLayout &lay, bool caller_blocks, uint64_t n_blocks) {
+  size_t need = lay.total;
+  if (caller_blocks) {
+    size_t with_blocks = lay.norms + (sizeof(double) * 3 * (size_t)n_blocks + 255) / 256 * 256;
+    if (with_blocks > need) need = with_blocks;
+  }
+  return need;
+}
+
+size_t bpc_update_workspace_bytes(const bpc_params_t *params, uint64_t D, uint64_t n_blocks) {
+  if (!params_valid(params) || n_blocks > (1ull << 40)) return 0;
+  if (D == 0) return 256;
+  return update_ws_bytes(ws_layout(params, D), n_blocks != 0, n_blocks);
+}
+
+bpc_status_t bpc_workspace_check(const bpc_params_t *params, uint64_t D, const void *ws, void *hip_stream) {
+  if (!params_valid(params) || (D != 0 && !ws)) return BPC_ERR_INVALID_ARG;
+  hipError_t e = hipStreamSynchronize((hipStream_t)hip_stream);
+  if (e != hipSuccess) return hip_status(e);
+  if (D == 0) return BPC_OK;
+  uint32_t word = 0;
+  e = hipMemcpy(&word, (const uint8_t *)ws + ws_layout(params, D).status, sizeof(word), hipMemcpyDeviceToHost);
+  if (e != hipSuccess) return hip_status(e);
+  return word == 0 ? BPC_OK : BPC_ERR_WAIT;
+}
+
+static bpc_status_t check_size(const bpc_params_t *p, uint64_t D) {
   // element offsets inside kernels are 64 bit, tile and partition counts 32 bit
-  return D / kTile >= 0x7fffffffull ? BPC_ERR_UNSUPPORTED : BPC_OK;
+  if (D / kTile >= 0x7fffffffull) return BPC_ERR_UNSUPPORTED;
+  // the sparse kinds have launches with the partition number in the second grid dimension
+  const bool sparse = p->kind == BPC_TOPK || p->kind == BPC_TOPK16 || p->kind == BPC_RANDK;
+  if (sparse && cdiv(D, p->part_elems) > 65535) return BPC_ERR_UNSUPPORTED;
+  return BPC_OK;
 }
 
 static hipError_t encode(const Geo &g, const bpc_params_t &prm, const bpc_params_t *in_prm, const Source &src,
@@ -70,7 +102,7 @@ bpc_status_t bpc_compress(const bpc_params_t *params, const void *grad, bpc_dtyp
   if (dtype != BPC_F32 && dtype != BPC_F16) return BPC_ERR_INVALID_ARG;
   if (D == 0) return BPC_OK;
   if (!grad || !payload) return BPC_ERR_INVALID_ARG;
-  if (check_size(D) != BPC_OK) return BPC_ERR_UNSUPPORTED;
+  if (check_size(params, D) != BPC_OK) return BPC_ERR_UNSUPPORTED;
   if (!aligned16(grad) || !aligned16(residual) || !aligned16(payload) || !aligned16(ws) ||
       !aligned16(params->norm_override))
     return BPC_ERR_ALIGNMENT;
@@ -90,7 +122,7 @@ bpc_status_t bpc_decompress(const bpc_params_t *params, const void *payload, uin
   if (!params_valid(params)) return BPC_ERR_INVALID_ARG;
   if (D == 0) return BPC_OK;
   if (!payload || !out) return BPC_ERR_INVALID_ARG;
-  if (check_size(D) != BPC_OK) return BPC_ERR_UNSUPPORTED;
+  if (check_size(params, D) != BPC_OK) return BPC_ERR_UNSUPPORTED;
   if (!aligned16(payload) || !aligned16(out)) return BPC_ERR_ALIGNMENT;
   Geo g = make_geo(params, D);
   return hip_status(decode_dense(g, *params, (const uint8_t *)payload, out, (hipStream_t)hip_stream));
@@ -112,7 +144,7 @@ bpc_status_t bpc_server_aggregate(const bpc_params_t *in, const void *const *pay
   if (!payloads || !out_payload) return BPC_ERR_INVALID_ARG;
   for (int i = 0; i < n; ++i)
     if (!payloads[i]) return BPC_ERR_INVALID_ARG;
-  if (check_size(D) != BPC_OK) return BPC_ERR_UNSUPPORTED;
+  if (check_size(out, D) != BPC_OK) return BPC_ERR_UNSUPPORTED;
   if (!aligned16(server_residual) || !aligned16(out_payload) || !aligned16(ws) || !aligned16(out->norm_override))
     return BPC_ERR_ALIGNMENT;
   for (int i = 0; i < n; ++i)
@@ -146,16 +178,12 @@ bpc_status_t bpc_adaptive_update(const bpc_params_t *params, const void *payload
   if (opt->kind == BPC_OPT_LANS && opt->block_offsets && opt->n_blocks == 0) return BPC_ERR_INVALID_ARG;
   if (D == 0) return BPC_OK;
   if (!payload || !param || !m || !v) return BPC_ERR_INVALID_ARG;
-  if (check_size(D) != BPC_OK) return BPC_ERR_UNSUPPORTED;
+  if (check_size(params, D) != BPC_OK) return BPC_ERR_UNSUPPORTED;
   if (!aligned16(payload) || !aligned16(param) || !aligned16(m) || !aligned16(v) || !aligned16(ws) ||
       !aligned16(opt->block_offsets))
     return BPC_ERR_ALIGNMENT;
   WsLayout lay = ws_layout(params, D);
-  size_t need = lay.total;
-  if (opt->kind == BPC_OPT_LANS && opt->block_offsets) {
-    size_t with_blocks = lay.norms + sizeof(double) * 3 * (size_t)opt->n_blocks;
-    if (with_blocks > need) need = with_blocks;
-  }
+  const size_t need = update_ws_bytes(lay, opt->kind == BPC_OPT_LANS && opt->block_offsets, opt->n_blocks);
   if (!ws || ws_bytes < need) return BPC_ERR_WORKSPACE;
   Geo g = make_geo(params, D);
   Workspace w{(uint8_t *)ws, lay};
@@ -171,6 +199,7 @@ const char *bpc_status_string(bpc_status_t status) {
     case BPC_ERR_WORKSPACE: return "workspace missing or too small";
     case BPC_ERR_ALIGNMENT: return "device pointer not 16-byte aligned";
     case BPC_ERR_HIP: return "HIP call failed";
+    case BPC_ERR_WAIT: return "a device-side wait gave up: outputs of the call are undefined";
     default: return "unknown status";
   }
 }

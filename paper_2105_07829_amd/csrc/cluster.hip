@@ -22,8 +22,13 @@ int cluster_capacity(const void *kernel, int threads, size_t dyn_lds) {
   return cus * per_cu;
 }
 
+int lds_limit_raised(const void *kernel, size_t bytes) {
+  if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) == hipSuccess) return 1;
+  (void)hipGetLastError();
+  return 0;
+}
+
 namespace {
-constexpr int kMaxDevices = 64;
 std::mutex g_mu;
 hipEvent_t g_event[kMaxDevices];
 hipStream_t g_last_stream[kMaxDevices];

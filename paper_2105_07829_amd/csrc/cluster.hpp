@@ -95,8 +95,30 @@ inline SplitGeo split_geo(const Geo &g, uint32_t tile, bool ragged_ok) {
 // on that earlier stream.
 hipError_t cluster_launch_begin(hipStream_t stream);
 hipError_t cluster_launch_end(hipStream_t stream);
-// Number of workgroups of `kernel` (`threads` threads, `dyn_lds` bytes of dynamic LDS) resident at once.
+// Number of workgroups of `kernel` (`threads` threads, `dyn_lds` bytes of dynamic LDS) resident at once
+// on the current device; 0 if the query failed.
 int cluster_capacity(const void *kernel, int threads, size_t dyn_lds = 0);
+
+// 1 if `kernel` may now be launched with up to `bytes` of dynamic LDS on the current device, else 0.
+int lds_limit_raised(const void *kernel, size_t bytes);
+
+// A positive integer per device that is found out once (an occupancy figure, "this function
+// attribute is set").  One zero-initialised static instance per kernel.  Answers <= 0 (a failed
+// query) are handed back but never kept, so the next call asks again.
+constexpr int kMaxDevices = 64;
+struct PerDevice {
+  int v[kMaxDevices];
+  template <class F>
+  int get(F query) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return query();
+    int cur = __atomic_load_n(&v[dev], __ATOMIC_ACQUIRE);
+    if (cur > 0) return cur;
+    cur = query();
+    if (cur > 0) __atomic_store_n(&v[dev], cur, __ATOMIC_RELEASE);
+    return cur;
+  }
+};
 
 #if defined(__HIPCC__)
 // Presets the slots to "not published", clears the status word and the ticket counter.

@@ -40,14 +40,15 @@ static hipError_t launch_cluster(const Op &op, const ClusterGeo &cg, double *slo
                                  hipStream_t stream, bool *used, size_t dyn_lds = 0) {
   const void *fn = dyn_lds ? reinterpret_cast<const void *>(&cluster_kernel_dyn<Op>)
                            : reinterpret_cast<const void *>(&cluster_kernel<Op>);
-  static int capacity = 0;  // resident workgroups; per kernel instantiation, a property of the device and the code object
-  if (capacity == 0) {
-    if (dyn_lds && hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)Op::kMaxDynLds) != hipSuccess) {
-      *used = false;
-      return hipSuccess;
+  static PerDevice cache;  // resident workgroups of this kernel on each device
+  const size_t max_dyn = dyn_lds ? (size_t)Op::kMaxDynLds : 0;
+  const int capacity = cache.get([&]() -> int {
+    if (max_dyn && hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)max_dyn) != hipSuccess) {
+      (void)hipGetLastError();
+      return 0;
     }
-    capacity = cluster_capacity(fn, Op::kThreads, dyn_lds ? Op::kMaxDynLds : 0);
-  }
+    return cluster_capacity(fn, Op::kThreads, max_dyn);
+  });
   *used = false;
   if (capacity <= 0) return hipSuccess;
   if (cg.tiles_per_part > (uint32_t)capacity) return hipSuccess;

@@ -51,7 +51,8 @@ __device__ inline uint64_t uniform_off(uint64_t v) {
 // A window of memory addressed through a buffer descriptor: accesses are "descriptor (scalar
 // registers) + 32-bit lane offset + scalar offset", so a tile's rows need no per-row address
 // registers.  `base` must be the same in every lane; `bytes` bounds the window (reads past it
-// return 0 and writes past it are dropped by the hardware, which the callers never rely on).
+// return 0 and writes past it are dropped by the hardware).  store16 deliberately has no
+// scalar-offset parameter (see there): keep 16-byte stores unable to take one.
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 // AUX is the cache policy of an access: 0 = default, kNonTemporal = data used once.

@@ -12,6 +12,7 @@
 // 32768 elements of Delta in LDS regenerates every draw of its partition instead and keeps
 // those that fall into its slice.
 #include "sources.hpp"
+#include "cluster.hpp"
 #include <hip/hip_runtime.h>
 
 namespace bpc {
@@ -413,8 +414,8 @@ static hipError_t launch_randk_bin(const Geo &g, const WorkerMsgs &msgs, const R
                                    uint2 *lists, uint32_t *table, hipStream_t stream) {
   const size_t lds = (size_t)g.k_cap * sizeof(uint2);
   constexpr size_t kMaxStage = 96 * 1024;
-  static bool big_ok = hipFuncSetAttribute(reinterpret_cast<const void *>(&randk_bin_kernel<OUT, true>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxStage) == hipSuccess;
+  static PerDevice attr;
+  const bool big_ok = attr.get([] { return lds_limit_raised(reinterpret_cast<const void *>(&randk_bin_kernel<OUT, true>), kMaxStage); }) > 0;
   if (lds <= kMaxStage && (big_ok || lds <= 48 * 1024))
     randk_bin_kernel<OUT, true><<<dim3(g.P, n), kRbThreads, lds, stream>>>(g, msgs, sc, slice_shift, lists, table);
   else
@@ -486,8 +487,8 @@ hipError_t randk_encode(const Geo &g, const bpc_params_t &prm, const bpc_params_
     for (int i = 1; i < src.msgs.n; ++i)
       shared = shared && in_prm[i].seed == in_prm[0].seed && in_prm[i].stream_id == in_prm[0].stream_id &&
                in_prm[i].value_scale == in_prm[0].value_scale;
-    static bool lds_ok = hipFuncSetAttribute(reinterpret_cast<const void *>(&randk_sum_kernel),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, kRsSlice * sizeof(float)) == hipSuccess;
+    static PerDevice attr1;
+    const bool lds_ok = attr1.get([] { return lds_limit_raised(reinterpret_cast<const void *>(&randk_sum_kernel), kRsSlice * sizeof(float)); }) > 0;
     if (shared || !lds_ok) {
       hipError_t e = fill_zero(dense, sizeof(float) * g.D, stream);
       if (e != hipSuccess) return e;
@@ -512,8 +513,8 @@ hipError_t randk_encode(const Geo &g, const bpc_params_t &prm, const bpc_params_
       // workspace (free: Delta goes to the residual buffer)
       const bool binned = src.residual != nullptr && cdiv(g.part_elems, 1ull << slice_shift) <= kRbMaxBins &&
                           (n + 1) * (one_list + one_table) <= sizeof(float) * g.D;
-      static bool lds2_ok = hipFuncSetAttribute(reinterpret_cast<const void *>(&randk_sum_binned_kernel<false>),
-                                                hipFuncAttributeMaxDynamicSharedMemorySize, (4u << 15)) == hipSuccess;
+      static PerDevice attr2;
+      const bool lds2_ok = attr2.get([] { return lds_limit_raised(reinterpret_cast<const void *>(&randk_sum_binned_kernel<false>), 4u << 15); }) > 0;
       if (binned && (lds2_ok || slice_shift == 13)) {
         uint2 *lists = reinterpret_cast<uint2 *>(dense);
         uint32_t *table = reinterpret_cast<uint32_t *>(reinterpret_cast<uint8_t *>(dense) + (n + 1) * one_list);

@@ -1032,8 +1032,9 @@ hipError_t topk_encode(const Geo &g, const bpc_params_t &prm, const bpc_params_t
   // (and the long form behind it is one resident kernel: its grid comes from the occupancy query)
   const void *long_fn = half ? reinterpret_cast<const void *>(&topk_long_form_kernel<true>)
                              : reinterpret_cast<const void *>(&topk_long_form_kernel<false>);
-  static int capacity[2] = {0, 0};
-  if (capacity[half] == 0) capacity[half] = cluster_capacity(long_fn, kThreads, 0);
+  static PerDevice cache[2];
+  int capacity[2] = {0, 0};
+  capacity[half] = cache[half].get([&] { return cluster_capacity(long_fn, kThreads, 0); });
   const int short_list = g.k_cap <= kTopkListCap / 2 && cdiv(g.tiles_per_part, kTpgLoad) <= (uint64_t)kSelThreads &&
                          capacity[half] > 0;
   const uint32_t sample_grid = g.P > 64 ? g.P : 64, load_grid = group_count(g, kTpgLoad);

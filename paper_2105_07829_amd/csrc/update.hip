@@ -712,8 +712,8 @@ static hipError_t run_lans_single(const Geo &g, DEC dec, float *x, float *m, flo
   *used = false;
   if (g.part_elems % kSTile != 0) return hipSuccess;
   const ClusterGeo cg = make_cluster_geo(g, kSTile);
-  static int capacity = 0;
-  if (capacity == 0) capacity = cluster_capacity(reinterpret_cast<const void *>(&lans_single_kernel<DEC>), kLThreads, 0);
+  static PerDevice cache;
+  const int capacity = cache.get([] { return cluster_capacity(reinterpret_cast<const void *>(&lans_single_kernel<DEC>), kLThreads, 0); });
   if (capacity <= 0 || cg.tiles_per_part > (uint32_t)capacity) return hipSuccess;
   *used = true;
   double *slots = ws.at<double>(ws.lay.slots);

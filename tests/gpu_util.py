@@ -71,8 +71,10 @@ def gpu_server(in_pbs, payloads_np, out_pb, res_np, D):
 def gpu_update(pb, payload_np, x_np, m_np, v_np, opt_b):
     x, m, v = to_dev(x_np), to_dev(m_np), to_dev(v_np)
     D = x_np.size
-    ws = torch.empty(bpc.workspace_bytes(pb, D, 1) + 24 * int(opt_b.n_blocks) + 256, dtype=torch.uint8, device=DEV)
+    ws = torch.empty(max(bpc.update_workspace_bytes(pb, D, int(opt_b.n_blocks)), 256), dtype=torch.uint8, device=DEV)
     bpc.bpc_adaptive_update(pb, to_dev(payload_np), x, m, v, opt_b, ws)
+    if D:
+        bpc.workspace_check(pb, D, ws)      # waits for the stream; raises if a device-side wait gave up
     torch.cuda.synchronize()
     return to_host(x), to_host(m), to_host(v)
 

@@ -124,10 +124,54 @@ def test_argument_errors_come_before_any_device_work(bpc):
     assert L.bpc_adaptive_update(C.byref(p), PL, 0, X, M, V, C.byref(o), WS, ws, None) == bpc.OK
 
 
+def test_update_workspace_covers_more_blocks_than_partitions(bpc):
+    """LANS blocks are layers: a gradient has far more of them than partitions.  The sizing call
+    must then ask for more than the common workspace, and the update must refuse anything less."""
+    L = bpc.lib()
+    p = bpc.make_params(bpc.SIGN, 1 << 20)
+    D = 3 * (1 << 20) + 5
+    common = bpc.workspace_bytes(p, D, 1)
+    assert bpc.update_workspace_bytes(p, D, 0) == common
+    assert bpc.update_workspace_bytes(p, D, 2) == common      # fits the room kept for the partitions
+    many = 400
+    need = bpc.update_workspace_bytes(p, D, many)
+    assert need >= common - 256 + 24 * many    # (the room kept for the partitions is one 256-byte unit here)
+    assert need % 256 == 0
+    o = bpc.make_opt(bpc.OPT_LANS, 1e-3, 0.9, 0.999, 1e-8, 0.01, 1)
+    o.block_offsets, o.n_blocks = 0x80000, many          # fake device address: never dereferenced here
+    PL, WS, X, M, V = 0x30000, 0x40000, 0x50000, 0x60000, 0x70000
+    assert L.bpc_adaptive_update(C.byref(p), PL, D, X, M, V, C.byref(o), WS, common, None) == bpc.ERR_WORKSPACE
+    assert L.bpc_adaptive_update(C.byref(p), PL, D, X, M, V, C.byref(o), WS, need - 1, None) == bpc.ERR_WORKSPACE
+    assert bpc.update_workspace_bytes(bpc.make_params(bpc.SIGN, 1000), D, 3) == 0
+
+
+def test_sparse_kinds_refuse_more_partitions_than_a_grid_dimension_holds(bpc):
+    """Some top-k / random-k launches carry the partition number in the second grid dimension
+    (at most 65535): such a shape is refused before anything is enqueued."""
+    L = bpc.lib()
+    G, R, PL, WS = 0x10000, 0x20000, 0x30000, 0x40000
+    D = 65536 * 1024
+    for kind in (bpc.TOPK, bpc.TOPK16, bpc.RANDK):
+        p = bpc.make_params(kind, 1024, k_ratio=0.01)
+        assert L.bpc_compress(C.byref(p), G, bpc.F32, R, D, PL, WS, 1 << 40, None) == bpc.ERR_UNSUPPORTED
+        assert L.bpc_decompress(C.byref(p), PL, D, R, None) == bpc.ERR_UNSUPPORTED
+        arr = (bpc.Params * 1)(p)
+        ptrs = (C.c_void_p * 1)(PL)
+        assert L.bpc_server_aggregate(arr, ptrs, 1, C.byref(p), R, D, PL, WS, 1 << 40, None) == bpc.ERR_UNSUPPORTED
+        o = bpc.make_opt(bpc.OPT_ADAM, 1e-3, 0.9, 0.999, 1e-8, 0.01, 1)
+        assert L.bpc_adaptive_update(C.byref(p), PL, D, R, R, R, C.byref(o), WS, 1 << 40, None) == bpc.ERR_UNSUPPORTED
+
+
+def test_workspace_check_validates_its_arguments(bpc):
+    L = bpc.lib()
+    assert L.bpc_workspace_check(None, 100, 0x1000, None) == bpc.ERR_INVALID_ARG
+    assert L.bpc_workspace_check(C.byref(bpc.make_params(bpc.SIGN, 1024)), 100, None, None) == bpc.ERR_INVALID_ARG
+
+
 def test_status_strings(bpc):
     L = bpc.lib()
-    seen = {L.bpc_status_string(i).decode() for i in range(6)}
-    assert len(seen) == 6 and "ok" in seen
+    seen = {L.bpc_status_string(i).decode() for i in range(7)}
+    assert len(seen) == 7 and "ok" in seen
     assert L.bpc_status_string(99).decode() == "unknown status"
     assert L.bpc_last_hip_error() == 0
 
