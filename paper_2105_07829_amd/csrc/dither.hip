@@ -60,7 +60,9 @@ __global__ __launch_bounds__(kThreads) void dither_reduce_kernel(Geo g, SRC src,
 }
 
 __global__ __launch_bounds__(64) void dither_finish_kernel(Geo g, const double *partials, const float *override,
-                                                           int linf, uint8_t *payload) {
+                                                           int linf, uint8_t *payload, uint32_t *status) {
+  // (status: NULL when a single-pass kernel of the same call may have set the word)
+  if (status && blockIdx.x == 0 && threadIdx.x == 0) status[0] = 0;
   const uint32_t p = blockIdx.x;
   const uint32_t d = g.part_size(p);
   const uint32_t n_tiles = (uint32_t)cdiv(d, kTile);
@@ -180,6 +182,7 @@ hipError_t dither_encode(const Geo &g_in, const bpc_params_t &prm_in, const Sour
   Geo g = g_in;
   Source src = src_in;
   bpc_params_t prm = prm_in;
+  uint32_t *status = ws.at<uint32_t>(ws.lay.status);
   // (the single-pass server handles up to 15 levels; beyond that it declines and the server
   // side takes the passes below)
   const bool wide = prm_in.kind == BPC_DITHER && dither_planes(prm_in.levels) > 0;
@@ -192,6 +195,7 @@ hipError_t dither_encode(const Geo &g_in, const bpc_params_t &prm_in, const Sour
       if (sp.tail.D == 0) return hipSuccess;
       advance_to_tail(sp.head.P, g_in, &src, &payload, &prm);
       g = sp.tail;
+      status = nullptr;
     }
   }
   double *partials = ws.at<double>(ws.lay.partials);
@@ -200,7 +204,7 @@ hipError_t dither_encode(const Geo &g_in, const bpc_params_t &prm_in, const Sour
   auto run = [&](auto s) -> hipError_t {
     using S = decltype(s);
     if (!prm.norm_override) dither_reduce_kernel<S><<<g.n_tiles, kThreads, 0, stream>>>(g, s, partials, linf);
-    dither_finish_kernel<<<g.P, 64, 0, stream>>>(g, partials, prm.norm_override, linf, payload);
+    dither_finish_kernel<<<g.P, 64, 0, stream>>>(g, partials, prm.norm_override, linf, payload, status);
     dither_apply_kernel<S><<<g.n_tiles, kThreads, 0, stream>>>(g, s, payload, src.residual, prm.levels, natural, prm.seed,
                                                                prm.stream_id);
     return hipGetLastError();

@@ -118,8 +118,10 @@ constexpr int kRbSumThreads = 256;
 // which were most of this kernel's time with eight messages of 10 K draws a partition).
 template <bool OUT, bool STAGE>
 __global__ __launch_bounds__(kRbThreads) void randk_bin_kernel(Geo g, WorkerMsgs msgs, RandkScales sc, uint32_t slice_shift,
-                                                               uint2 *lists, uint32_t *table) {
+                                                               uint2 *lists, uint32_t *table, uint32_t *status) {
   extern __shared__ uint2 staged[];
+  // (status, where given: the workspace's status word; random-k has no waits, so it reads "none gave up")
+  if (status && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) status[0] = 0;
   __shared__ uint32_t cnt[kRbMaxBins];
   __shared__ uint32_t scan[kRbThreads];
   const uint32_t p = blockIdx.x, i = blockIdx.y;
@@ -411,15 +413,15 @@ __global__ __launch_bounds__(kThreads) void randk_fixup_kernel(Geo g, float *buf
 // a partition fits.
 template <bool OUT>
 static hipError_t launch_randk_bin(const Geo &g, const WorkerMsgs &msgs, const RandkScales &sc, int n, uint32_t slice_shift,
-                                   uint2 *lists, uint32_t *table, hipStream_t stream) {
+                                   uint2 *lists, uint32_t *table, hipStream_t stream, uint32_t *status = nullptr) {
   const size_t lds = (size_t)g.k_cap * sizeof(uint2);
   constexpr size_t kMaxStage = 96 * 1024;
   static PerDevice attr;
   const bool big_ok = attr.get([] { return lds_limit_raised(reinterpret_cast<const void *>(&randk_bin_kernel<OUT, true>), kMaxStage); }) > 0;
   if (lds <= kMaxStage && (big_ok || lds <= 48 * 1024))
-    randk_bin_kernel<OUT, true><<<dim3(g.P, n), kRbThreads, lds, stream>>>(g, msgs, sc, slice_shift, lists, table);
+    randk_bin_kernel<OUT, true><<<dim3(g.P, n), kRbThreads, lds, stream>>>(g, msgs, sc, slice_shift, lists, table, status);
   else
-    randk_bin_kernel<OUT, false><<<dim3(g.P, n), kRbThreads, 0, stream>>>(g, msgs, sc, slice_shift, lists, table);
+    randk_bin_kernel<OUT, false><<<dim3(g.P, n), kRbThreads, 0, stream>>>(g, msgs, sc, slice_shift, lists, table, status);
   return hipGetLastError();
 }
 
@@ -453,8 +455,12 @@ hipError_t randk_encode(const Geo &g, const bpc_params_t &prm, const bpc_params_
   out_scale.value_scale[0] = prm.value_scale;
   const uint64_t one_list = ((uint64_t)g.P * g.k_cap * sizeof(uint2) + 255) / 256 * 256;
   const uint64_t one_table = ((uint64_t)g.P * (kRbMaxBins + 1) * sizeof(uint32_t) + 255) / 256 * 256;
+  // the status word: cleared by the binning kernel on the paths that start with it, by a fill elsewhere
+  uint32_t *status = ws.at<uint32_t>(ws.lay.status);
   if (src.grad) {
     if (!src.residual) {
+      hipError_t e0 = fill_zero(status, 16, stream);
+      if (e0 != hipSuccess) return e0;
       if (src.dtype == BPC_F16)
         randk_gather_src_kernel<<<grid, kThreads, 0, stream>>>(g, GradSource<__half>{(const __half *)src.grad, nullptr},
                                                                payload, prm.seed, prm.stream_id);
@@ -467,7 +473,7 @@ hipError_t randk_encode(const Geo &g, const bpc_params_t &prm, const bpc_params_
       // one pass over the data (q goes to the residual buffer, so the dense workspace is free for the list)
       uint2 *lists = reinterpret_cast<uint2 *>(dense);
       uint32_t *table = reinterpret_cast<uint32_t *>(reinterpret_cast<uint8_t *>(dense) + one_list);
-      hipError_t e = launch_randk_bin<true>(g, out_stream, out_scale, 1, 12, lists, table, stream);
+      hipError_t e = launch_randk_bin<true>(g, out_stream, out_scale, 1, 12, lists, table, stream, status);
       if (e != hipSuccess) return e;
       if (src.dtype == BPC_F16)
         randk_tile_kernel<<<g.n_tiles, kThreads, 0, stream>>>(g, GradSource<__half>{(const __half *)src.grad, src.residual}, buf,
@@ -477,6 +483,8 @@ hipError_t randk_encode(const Geo &g, const bpc_params_t &prm, const bpc_params_
                                                               payload, prm.value_scale, lists, table);
       return hipGetLastError();
     }
+    hipError_t e0 = fill_zero(status, 16, stream);
+    if (e0 != hipSuccess) return e0;
     if (src.dtype == BPC_F16)
       randk_store_kernel<<<g.n_tiles, kThreads, 0, stream>>>(g, GradSource<__half>{(const __half *)src.grad, src.residual}, buf);
     else
@@ -490,7 +498,9 @@ hipError_t randk_encode(const Geo &g, const bpc_params_t &prm, const bpc_params_
     static PerDevice attr1;
     const bool lds_ok = attr1.get([] { return lds_limit_raised(reinterpret_cast<const void *>(&randk_sum_kernel), kRsSlice * sizeof(float)); }) > 0;
     if (shared || !lds_ok) {
-      hipError_t e = fill_zero(dense, sizeof(float) * g.D, stream);
+      hipError_t e = fill_zero(status, 16, stream);
+      if (e != hipSuccess) return e;
+      e = fill_zero(dense, sizeof(float) * g.D, stream);
       if (e != hipSuccess) return e;
       if (shared) {
         e = scatter_add_randk_shared(g, in_prm[0], src.msgs, dense, stream);
@@ -518,7 +528,7 @@ hipError_t randk_encode(const Geo &g, const bpc_params_t &prm, const bpc_params_
       if (binned && (lds2_ok || slice_shift == 13)) {
         uint2 *lists = reinterpret_cast<uint2 *>(dense);
         uint32_t *table = reinterpret_cast<uint32_t *>(reinterpret_cast<uint8_t *>(dense) + (n + 1) * one_list);
-        hipError_t e = launch_randk_bin<false>(g, src.msgs, sc, n, slice_shift, lists, table, stream);
+        hipError_t e = launch_randk_bin<false>(g, src.msgs, sc, n, slice_shift, lists, table, stream, status);
         if (e != hipSuccess) return e;
         e = launch_randk_bin<true>(g, out_stream, out_scale, 1, slice_shift, lists + (uint64_t)n * g.P * g.k_cap,
                                    table + (uint64_t)n * g.P * (kRbMaxBins + 1), stream);
@@ -533,6 +543,8 @@ hipError_t randk_encode(const Geo &g, const bpc_params_t &prm, const bpc_params_
         return hipGetLastError();
       }
       const uint32_t slices = g.P * (uint32_t)cdiv(g.part_elems, kRsSlice);
+      hipError_t e = fill_zero(status, 16, stream);
+      if (e != hipSuccess) return e;
       randk_sum_kernel<<<slices, kRsThreads, kRsSlice * sizeof(float), stream>>>(g, src.msgs, sc, src.residual, buf);
     }
   }

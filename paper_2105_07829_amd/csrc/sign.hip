@@ -46,7 +46,9 @@ __global__ __launch_bounds__(kThreads) void sign_reduce_kernel(Geo g, SRC src, u
 
 // One wave per partition: sum the tile partials in a fixed order and write the header.
 __global__ __launch_bounds__(64) void sign_finish_kernel(Geo g, const double *partials, const float *override,
-                                                         uint8_t *payload) {
+                                                         uint8_t *payload, uint32_t *status) {
+  // (status: NULL when a single-pass kernel of the same call may have set the word)
+  if (status && blockIdx.x == 0 && threadIdx.x == 0) status[0] = 0;
   const uint32_t p = blockIdx.x;
   const uint32_t d = g.part_size(p);
   const uint32_t n_tiles = (uint32_t)cdiv(d, kTile);
@@ -97,6 +99,7 @@ hipError_t sign_encode(const Geo &g_in, const bpc_params_t &prm_in, const Source
   Geo g = g_in;
   Source src = src_in;
   bpc_params_t prm = prm_in;
+  uint32_t *status = ws.at<uint32_t>(ws.lay.status);
   if (sp.single_pass && sp.head.P > 0) {
     bool used = false;
     hipError_t e = src.grad ? sign_worker_single_pass(sp.head, prm, src, payload, ws, stream, &used)
@@ -106,6 +109,7 @@ hipError_t sign_encode(const Geo &g_in, const bpc_params_t &prm_in, const Source
       if (sp.tail.D == 0) return hipSuccess;
       advance_to_tail(sp.head.P, g_in, &src, &payload, &prm);
       g = sp.tail;
+      status = nullptr;
     }
   }
   double *partials = ws.at<double>(ws.lay.partials);
@@ -113,7 +117,7 @@ hipError_t sign_encode(const Geo &g_in, const bpc_params_t &prm_in, const Source
   return with_source(src, make_server, [&](auto s) -> hipError_t {
     using S = decltype(s);
     sign_reduce_kernel<S><<<g.n_tiles, kThreads, 0, stream>>>(g, s, payload, partials, prm.norm_override == nullptr);
-    sign_finish_kernel<<<g.P, 64, 0, stream>>>(g, partials, prm.norm_override, payload);
+    sign_finish_kernel<<<g.P, 64, 0, stream>>>(g, partials, prm.norm_override, payload, status);
     if (src.residual) sign_apply_kernel<S><<<g.n_tiles, kThreads, 0, stream>>>(g, s, payload, src.residual);
     return hipGetLastError();
   });

@@ -288,6 +288,7 @@ struct OptArgs {
   float lr, beta1, beta2, eps, wd, bc1, bc2, phi_lo, phi_hi;
   const uint64_t *block_offsets;  // device, or NULL: blocks are the partitions
   uint64_t n_blocks;
+  uint32_t *status;               // the workspace's status word (cleared by kernels that have no waits)
 };
 
 // r + wd*x and c + wd*x from the updated moments.
@@ -328,6 +329,7 @@ __global__ __launch_bounds__(kThreads) void update_moments_kernel(Geo g, DEC dec
                                                                   OptArgs o, double *norms) {
   __shared__ float lds[DEC::kLdsFloats];
   __shared__ double red[kThreads / 64];
+  if (blockIdx.x == 0 && threadIdx.x == 0) o.status[0] = 0;   // no wait in this call
   const uint32_t p = blockIdx.x / g.tiles_per_part;
   const uint32_t tile = blockIdx.x % g.tiles_per_part;
   const uint32_t d = g.part_size(p);
@@ -392,6 +394,7 @@ constexpr int kURows = kTile / kURow;
 template <class DEC>
 __global__ __launch_bounds__(kThreads) void adam_update_kernel(Geo g, DEC dec, float *x, float *m, float *v, OptArgs o) {
   __shared__ __align__(16) float lds[DEC::kLdsFloats];
+  if (blockIdx.x == 0 && threadIdx.x == 0) o.status[0] = 0;   // no wait in this call
   const uint32_t p = __builtin_amdgcn_readfirstlane(blockIdx.x / g.tiles_per_part);
   const uint32_t tile = __builtin_amdgcn_readfirstlane(blockIdx.x % g.tiles_per_part);
   const uint32_t d = g.part_size(p);
@@ -733,7 +736,7 @@ template <class DEC>
 static hipError_t run_update(const Geo &g, DEC dec, float *x, float *m, float *v, const bpc_opt_t &opt,
                              double *norms, const Workspace &ws, hipStream_t stream) {
   OptArgs o{opt.lr, opt.beta1, opt.beta2, opt.eps, opt.weight_decay, opt.bias_corr1, opt.bias_corr2,
-            opt.phi_lo, opt.phi_hi, opt.block_offsets, opt.n_blocks};
+            opt.phi_lo, opt.phi_hi, opt.block_offsets, opt.n_blocks, ws.at<uint32_t>(ws.lay.status)};
   if (opt.kind == BPC_OPT_ADAM) {
     adam_update_kernel<DEC><<<g.n_tiles, kThreads, 0, stream>>>(g, dec, x, m, v, o);
     return hipGetLastError();
@@ -771,7 +774,7 @@ hipError_t adaptive_update(const Geo &g, const bpc_params_t &prm, const uint8_t 
     // no dense decode: the update kernel lays each tile of the message out in LDS itself
     // (tiles of 4096 elements in the Adam-style kernel, of 8192 in the single-pass LANS kernel)
     OptArgs o{opt.lr, opt.beta1, opt.beta2, opt.eps, opt.weight_decay, opt.bias_corr1, opt.bias_corr2,
-              opt.phi_lo, opt.phi_hi, opt.block_offsets, opt.n_blocks};
+              opt.phi_lo, opt.phi_hi, opt.block_offsets, opt.n_blocks, ws.at<uint32_t>(ws.lay.status)};
     const uint32_t shift = lans_single ? 13 : 12;
     const uint32_t tiles = (uint32_t)cdiv(g.part_elems, 1ull << shift);
     const uint32_t *table = nullptr;
