@@ -28,7 +28,7 @@ HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-ffp-contract=off"
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-fPIC", "-shared"]
 
 EXPORTS = ["bpc_partition_k", "bpc_partition_stride", "bpc_payload_bytes", "bpc_workspace_bytes",
-           "bpc_update_workspace_bytes", "bpc_workspace_status_offset", "bpc_workspace_check", "bpc_compress", "bpc_decompress", "bpc_server_aggregate", "bpc_adaptive_update",
+           "bpc_update_workspace_bytes", "bpc_workspace_status_offset", "bpc_workspace_check", "bpc_compress", "bpc_compress_static_ws", "bpc_decompress", "bpc_server_aggregate", "bpc_adaptive_update",
            "bpc_status_string", "bpc_last_hip_error"]
 
 
@@ -97,6 +97,8 @@ def lib():
         L.bpc_compress.argtypes = [PP, C.c_void_p, C.c_int, C.c_void_p, C.c_uint64, C.c_void_p,
                                    C.c_void_p, C.c_size_t, C.c_void_p]
         L.bpc_compress.restype = C.c_int
+        L.bpc_compress_static_ws.argtypes = [PP, C.c_void_p, C.c_int, C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p]
+        L.bpc_compress_static_ws.restype = C.c_int
         L.bpc_decompress.argtypes = [PP, C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p]
         L.bpc_decompress.restype = C.c_int
         L.bpc_server_aggregate.argtypes = [PP, C.POINTER(C.c_void_p), C.c_int, PP, C.c_void_p,
@@ -214,6 +216,16 @@ def bpc_compress(p: Params, grad, residual, payload, ws, stream=None) -> None:
     st = lib().bpc_compress(C.byref(p), _ptr(grad), _dtype_code(grad), _ptr(residual), grad.numel(),
                             _ptr(payload), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream))
     _check(st, "bpc_compress")
+
+
+STATIC_WS_BYTES = 4 << 20
+
+
+def bpc_compress_static_ws(p: Params, grad, residual, payload, stream=None) -> None:
+    """bpc_compress on the library's static device workspace (no workspace argument)."""
+    st = lib().bpc_compress_static_ws(C.byref(p), _ptr(grad), _dtype_code(grad), _ptr(residual), grad.numel(),
+                                      _ptr(payload), _stream(stream))
+    _check(st, "bpc_compress_static_ws")
 
 
 def bpc_decompress(p: Params, payload, out, stream=None) -> None:

@@ -1,11 +1,16 @@
 // C ABI (include/bpc.h): argument validation on the host, then dispatch to the kernel
 // launchers.  Nothing here allocates, and only bpc_workspace_check() synchronises.
 #include <hip/hip_runtime.h>
+#include <mutex>
+#include "cluster.hpp"
 #include "kernels.hpp"
 
-
-
 using namespace bpc;
+
+// Workspace of bpc_compress_static_ws(): each device the library runs on holds this array until
+// the process ends.  In host code the array's name is only a handle for hipGetSymbolAddress();
+// the address kernels and copies are given is the one that call returned for the device.
+static __device__ __align__(256) unsigned char scratch[BPC_STATIC_WS_BYTES];
 
 static thread_local int g_last_hip_error = 0;
 
@@ -16,6 +21,29 @@ static bpc_status_t hip_status(hipError_t e) {
 }
 
 static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Device address of `scratch` on the current device, looked up once per device (together with
+// the event that orders single-pass kernels across streams, so that no later call creates one).
+static hipError_t static_workspace(uint8_t **ptr) {
+  static std::mutex mu;
+  static uint8_t *addr[kMaxDevices];
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!addr[dev]) {
+    void *p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    e = cluster_prepare_device();
+    if (e != hipSuccess) return e;
+    addr[dev] = static_cast<uint8_t *>(p);
+  }
+  *ptr = addr[dev];
+  return hipSuccess;
+}
 
 extern "C" {
 
@@ -65,7 +93,15 @@ size_t bpc_update_workspace_bytes(const bpc_params_t *params, uint64_t D, uint64
 }
 
 bpc_status_t bpc_workspace_check(const bpc_params_t *params, uint64_t D, const void *ws, void *hip_stream) {
-  if (!params_valid(params) || (D != 0 && !ws)) return BPC_ERR_INVALID_ARG;
+  if (!params_valid(params)) return BPC_ERR_INVALID_ARG;
+  if (D != 0 && !ws) {
+    // the static workspace of the current device
+    if (ws_layout(params, D).total > BPC_STATIC_WS_BYTES) return BPC_ERR_WORKSPACE;
+    uint8_t *st = nullptr;
+    hipError_t e0 = static_workspace(&st);
+    if (e0 != hipSuccess) return hip_status(e0);
+    ws = st;
+  }
   hipError_t e = hipStreamSynchronize((hipStream_t)hip_stream);
   if (e != hipSuccess) return hip_status(e);
   if (D == 0) return BPC_OK;
@@ -115,6 +151,24 @@ bpc_status_t bpc_compress(const bpc_params_t *params, const void *grad, bpc_dtyp
   src.residual = residual;
   Workspace w{(uint8_t *)ws, lay};
   return hip_status(encode(g, *params, nullptr, src, (uint8_t *)payload, w, (hipStream_t)hip_stream));
+}
+
+bpc_status_t bpc_compress_static_ws(const bpc_params_t *params, const void *grad, bpc_dtype_t dtype, float *residual,
+                                    uint64_t D, void *payload, void *hip_stream) {
+  if (!params_valid(params)) return BPC_ERR_INVALID_ARG;
+  if (dtype != BPC_F32 && dtype != BPC_F16) return BPC_ERR_INVALID_ARG;
+  if (D == 0) return BPC_OK;
+  if (!grad || !payload) return BPC_ERR_INVALID_ARG;
+  if (check_size(params, D) != BPC_OK) return BPC_ERR_UNSUPPORTED;
+  if (!aligned16(grad) || !aligned16(residual) || !aligned16(payload) || !aligned16(params->norm_override))
+    return BPC_ERR_ALIGNMENT;
+  if (ws_layout(params, D).total > BPC_STATIC_WS_BYTES) return BPC_ERR_WORKSPACE;
+  uint8_t *ws = nullptr;
+  hipError_t e = static_workspace(&ws);
+  if (e != hipSuccess) return hip_status(e);
+  // from here on the call is bpc_compress on that workspace (whose kernels clear the parts of it
+  // that must start from a known value: slots, status word, histograms)
+  return bpc_compress(params, grad, dtype, residual, D, payload, ws, BPC_STATIC_WS_BYTES, hip_stream);
 }
 
 bpc_status_t bpc_decompress(const bpc_params_t *params, const void *payload, uint64_t D, float *out,

@@ -71,6 +71,16 @@ hipError_t cluster_launch_begin(hipStream_t stream) {
   return hipStreamWaitEvent(stream, g_event[dev], 0);
 }
 
+hipError_t cluster_prepare_device() {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_mu);
+  if (g_event[dev]) return hipSuccess;
+  return hipEventCreateWithFlags(&g_event[dev], hipEventDisableTiming);
+}
+
 hipError_t cluster_launch_end(hipStream_t stream) {
   if (is_capturing(stream)) return hipSuccess;
   int dev = 0;

@@ -95,6 +95,8 @@ inline SplitGeo split_geo(const Geo &g, uint32_t tile, bool ragged_ok) {
 // on that earlier stream.
 hipError_t cluster_launch_begin(hipStream_t stream);
 hipError_t cluster_launch_end(hipStream_t stream);
+// Creates the current device's event now rather than at the first launch that needs it.
+hipError_t cluster_prepare_device();
 // Number of workgroups of `kernel` (`threads` threads, `dyn_lds` bytes of dynamic LDS) resident at once
 // on the current device; 0 if the query failed.
 int cluster_capacity(const void *kernel, int threads, size_t dyn_lds = 0);

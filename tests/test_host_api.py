@@ -165,7 +165,37 @@ def test_sparse_kinds_refuse_more_partitions_than_a_grid_dimension_holds(bpc):
 def test_workspace_check_validates_its_arguments(bpc):
     L = bpc.lib()
     assert L.bpc_workspace_check(None, 100, 0x1000, None) == bpc.ERR_INVALID_ARG
-    assert L.bpc_workspace_check(C.byref(bpc.make_params(bpc.SIGN, 1024)), 100, None, None) == bpc.ERR_INVALID_ARG
+    # no workspace pointer = the library's static one, which is too small for this shape
+    p = bpc.make_params(bpc.TOPK, 1 << 20, k_ratio=0.01)
+    assert L.bpc_workspace_check(C.byref(p), 1 << 24, None, None) == bpc.ERR_WORKSPACE
+
+
+def test_static_workspace_entry_point_validates_before_any_device_work(bpc):
+    """bpc_compress_static_ws: the argument checks of bpc_compress, then the size limit, all on
+    the host (fake pointers below)."""
+    L = bpc.lib()
+    G, R, PL = 0x10000, 0x20000, 0x30000
+    p = bpc.make_params(bpc.SIGN, 1 << 20)
+    f = L.bpc_compress_static_ws
+    assert f(None, G, bpc.F32, R, 4096, PL, None) == bpc.ERR_INVALID_ARG
+    assert f(C.byref(p), None, bpc.F32, R, 4096, PL, None) == bpc.ERR_INVALID_ARG
+    assert f(C.byref(p), G, 5, R, 4096, PL, None) == bpc.ERR_INVALID_ARG
+    assert f(C.byref(p), G, bpc.F32, R, 4096, None, None) == bpc.ERR_INVALID_ARG
+    assert f(C.byref(p), G + 8, bpc.F32, R, 4096, PL, None) == bpc.ERR_ALIGNMENT
+    assert f(C.byref(p), G, bpc.F32, R, 0, PL, None) == bpc.OK
+    # beyond the static array: refused, and the limit is where the sizing call says it is
+    big = 1 << 31
+    assert bpc.workspace_bytes(p, big, 1) > bpc.STATIC_WS_BYTES
+    assert f(C.byref(p), G, bpc.F32, R, big, PL, None) == bpc.ERR_WORKSPACE
+    t = bpc.make_params(bpc.TOPK, 1 << 20, k_ratio=0.01)
+    assert bpc.workspace_bytes(t, 1 << 21, 1) > bpc.STATIC_WS_BYTES
+    assert f(C.byref(t), G, bpc.F32, R, 1 << 21, PL, None) == bpc.ERR_WORKSPACE
+    header = open(os.path.join(ROOT, "include", "bpc.h")).read()
+    assert re.search(r"#define\s+BPC_STATIC_WS_BYTES\s+\(4u << 20\)", header) and bpc.STATIC_WS_BYTES == 4 << 20
+    # the shapes the header names as covered do fit
+    for kind, D in ((bpc.SIGN, 800_000_000), (bpc.DITHER, 800_000_000), (bpc.TOPK, 500_000)):
+        q = bpc.make_params(kind, 1 << 21 if kind != bpc.TOPK else 1 << 20, k_ratio=0.01)
+        assert bpc.workspace_bytes(q, D, 1) <= bpc.STATIC_WS_BYTES, (kind, D)
 
 
 def test_status_strings(bpc):
