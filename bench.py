@@ -8,6 +8,11 @@ the pulled message fused with the moment / parameter update).  Inputs are reside
 before the clock starts.  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-others] [--no-cpu]
+                  [--no-stream-probe]
+
+Stage times are medians over per-call HIP event pairs on the launch stream; after every timed
+region the workspace's status word is checked (a device-side wait that gave up would make the
+numbers meaningless, so it aborts the run).
 """
 from __future__ import annotations
 
@@ -35,6 +40,10 @@ def parse():
     ap.add_argument("--cpu-steps", type=int, default=6, help="pipeline steps the CPU sample runs")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy a few times (reference for hardware counters)")
+    ap.add_argument("--no-stream-probe", action="store_true",
+                    help="skip the plain streaming kernels that measure the achievable bandwidth")
+    ap.add_argument("--cpu-single-partitions", type=int, default=3,
+                    help="partitions in the single-threaded CPU sample (one step)")
     return ap.parse_args()
 
 
@@ -89,7 +98,10 @@ class Pipeline:
         pb = bpc.payload_bytes(p0, self.D)
         self.pay = [torch.zeros(pb, dtype=torch.uint8, device=dev) for _ in range(self.n)]
         self.pay_out = torch.zeros(pb, dtype=torch.uint8, device=dev)
-        self.ws = torch.empty(bpc.workspace_bytes(p0, self.D, self.n), dtype=torch.uint8, device=dev)
+        blocks = synth.layer_blocks(self.D, 768 if name.startswith("bert_base") else 1024)
+        self.blocks = torch.from_numpy(blocks.astype("int64")).to(dev)
+        self.ws = torch.empty(max(bpc.workspace_bytes(p0, self.D, self.n),
+                                  bpc.update_workspace_bytes(p0, self.D, len(blocks) - 1)), dtype=torch.uint8, device=dev)
         self.x = synth.device_params(self.D, device=dev)
         self.m = torch.zeros(self.D, dtype=torch.float32, device=dev)
         self.v = torch.zeros(self.D, dtype=torch.float32, device=dev)
@@ -117,6 +129,13 @@ class Pipeline:
         opt = self.bpc.make_opt(self.bpc.OPT_LANS, 1e-3, 0.9, 0.999, 1e-8, 0.01, t)
         self.bpc.bpc_adaptive_update(self.params(1, 0), self.pay_out, self.x, self.m, self.v, opt, self.ws)
 
+    def stage_u_lans_layers(self):
+        """The same update with the blocks Algorithm 5 means: layers (offsets shaped like the
+        tensors of a BERT encoder stack, synth.layer_blocks), not partitions."""
+        t = max(self.t, 1)
+        opt = self.bpc.make_opt(self.bpc.OPT_LANS, 1e-3, 0.9, 0.999, 1e-8, 0.01, t, block_offsets=self.blocks)
+        self.bpc.bpc_adaptive_update(self.params(1, 0), self.pay_out, self.x, self.m, self.v, opt, self.ws)
+
     def step(self):
         self.t += 1
         for i in range(self.n):
@@ -124,17 +143,28 @@ class Pipeline:
         self.stage_s()
         self.stage_u()
 
+    def check(self, where):
+        """Waits for the stream; raises if a device-side wait of the last call gave up."""
+        try:
+            self.bpc.workspace_check(self.params(0, 0), self.D, self.ws)
+        except self.bpc.BpcError as err:
+            raise SystemExit(f"bench.py: {self.name}, {where}: {err}")
+
 
 def timed(torch, fn, reps):
-    """Average milliseconds of fn() over reps calls, HIP events on the stream fn launches on."""
-    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    """Median milliseconds of fn() over reps calls: one HIP event before each call and one after
+    the last, on the stream fn launches on (torch's current stream, which the binding passes to
+    the library)."""
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
     torch.cuda.synchronize()
-    a.record()
-    for _ in range(reps):
+    for i in range(reps):
+        ev[i].record()
         fn()
-    b.record()
+    ev[reps].record()
     torch.cuda.synchronize()
-    return a.elapsed_time(b) / reps
+    per_call = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(reps))
+    mid = reps // 2
+    return per_call[mid] if reps % 2 else 0.5 * (per_call[mid - 1] + per_call[mid])
 
 
 def run_workload(name, w, steps, warmup, torch, bpc, synth):
@@ -147,17 +177,24 @@ def run_workload(name, w, steps, warmup, torch, bpc, synth):
         pipe.step()
     torch.cuda.synchronize()
     ms_step = (time.perf_counter() - t0) * 1e3 / steps
-    # per-stage averages, steady state (non-zero residuals)
+    pipe.check("timed steps")
+    # per-stage medians, steady state (non-zero residuals)
     reps = max(steps, 5)
     ms_w = timed(torch, lambda: pipe.stage_w(0), reps)
+    pipe.check("worker stage")
     ms_s = timed(torch, pipe.stage_s, reps)
+    pipe.check("server stage")
     ms_u = timed(torch, pipe.stage_u, reps)
+    pipe.check("update stage")
     ms_ul = timed(torch, pipe.stage_u_lans, reps)
+    pipe.check("LANS update stage")
+    ms_ulb = timed(torch, pipe.stage_u_lans_layers, reps)
+    pipe.check("LANS update stage, layer blocks")
     G = 4 if w["dtype"] == "f32" else 2
     D, n = w["D"], w["n_workers"]
     alg = algorithmic_bytes_per_elem(w)
     stages = {}
-    for key, ms in (("W", ms_w), ("S", ms_s), ("U", ms_u), ("U_lans", ms_ul)):
+    for key, ms in (("W", ms_w), ("S", ms_s), ("U", ms_u), ("U_lans", ms_ul), ("U_lans_layers", ms_ulb)):
         a = alg[key[0]]
         stages[key] = {"ms": round(ms, 4), "gradient_GBps": round(D * G / ms / 1e6, 1),
                        "algorithmic_GBps": round(D * a / ms / 1e6, 1),
@@ -178,7 +215,41 @@ def run_workload(name, w, steps, warmup, torch, bpc, synth):
     return out
 
 
-def cpu_baseline(name, w, n_parts, n_steps, synth):
+def stream_probe(torch, bpc, D):
+    """What the memory system of this device delivers for the stages' access patterns: plain
+    streaming kernels of the library (bpc_stream_probe: the traffic of a stage, none of its
+    arithmetic) over D elements, GB/s from the median of HIP-event timings."""
+    dev = "cuda"
+    a16 = torch.zeros(D, dtype=torch.float16, device=dev)
+    a, b, c = (torch.zeros(D, dtype=torch.float32, device=dev) for _ in range(3))
+    out = {"elements": D}
+    for key, mix, args in (("copy_GBps", bpc.PROBE_COPY, (a, None, c)),
+                           ("worker_mix_GBps", bpc.PROBE_WORKER_MIX, (a16, b, c)),
+                           ("update_mix_GBps", bpc.PROBE_UPDATE_MIX, (a, b, c))):
+        for _ in range(3):
+            bpc.bpc_stream_probe(mix, *args)
+        ms = timed(torch, lambda: bpc.bpc_stream_probe(mix, *args), 15)
+        out[key] = round(D * bpc.PROBE_BYTES_PER_ELEMENT[mix] / ms / 1e6, 1)
+    del a16, a, b, c
+    torch.cuda.empty_cache()
+    return out
+
+
+def sources_digest():
+    """sha256 over the kernel sources: the profile summaries record the digest they were measured
+    at, so a stored traffic figure can be told from one that predates a change to a kernel."""
+    import hashlib
+
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2105_07829_amd", "csrc")
+    for f in sorted(os.listdir(csrc)):
+        if f.endswith((".hip", ".hpp")):
+            h.update(f.encode())
+            h.update(open(os.path.join(csrc, f), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def cpu_baseline(name, w, n_parts, n_steps, synth, threads=None):
     """The CPU oracle as it stands, on `n_parts` full partitions of the same workload (all n
     workers, server, update) for `n_steps` steps, partitions spread over the host cores with a
     thread pool."""
@@ -191,7 +262,7 @@ def cpu_baseline(name, w, n_parts, n_steps, synth):
     pe = synth.part_elems(w["dtype"])
     n = w["n_workers"]
     D = pe * n_parts
-    cores = min(os.cpu_count() or 1, 16)
+    cores = threads or min(os.cpu_count() or 1, 16)
     kind = {"sign": oracle.SIGN, "topk": oracle.TOPK, "randk": oracle.RANDK, "dither": oracle.DITHER,
             "natdither": oracle.NATDITHER, "fp16": oracle.FP16, "topk16": oracle.TOPK16}[w["kind"]]
     kw = dict(k_ratio=w.get("k_ratio", 0.01), levels=w.get("levels", 4), value_scale=w.get("value_scale", 1.0),
@@ -237,18 +308,22 @@ def cpu_baseline(name, w, n_parts, n_steps, synth):
 
 
 def recorded_traffic(workload, stage):
-    """HBM bytes per launch of a stage as measured with rocprofv3 counters (profiles/), or None."""
+    """(HBM bytes per launch of a stage as measured with rocprofv3 counters and recorded under
+    profiles/, digest of the kernel sources it was measured at), or (None, None)."""
     names = {"bert_large": "bench_bert_large_dither.txt", "resnet50": "bench_resnet50_topk.txt",
-             "vgg16": "bench_vgg16_randk.txt"}
+             "vgg16": "bench_vgg16_randk.txt", "bert_base": "bench_bert_base_sign.txt"}
     path = os.path.join(ROOT, "profiles", names.get(workload, f"bench_{workload}.txt"))
+    total, digest = None, None
     try:
         for line in open(path):
             f = line.split()
             if len(f) >= 9 and f[0] == "TRAFFIC" and f[1] == workload and f[2] == stage:
-                return float(f[f.index("total_bytes") + 1])
+                total = float(f[f.index("total_bytes") + 1])
+            if len(f) >= 2 and f[0] == "SOURCES":
+                digest = f[1]
     except OSError:
         pass
-    return None
+    return total, digest
 
 
 def main():
@@ -279,6 +354,10 @@ def main():
     alg = algorithmic_bytes_per_elem(w)[dom]
     ach = head["stages"][dom]["algorithmic_GBps"]
     call = {"W": "bpc_compress", "S": "bpc_server_aggregate", "U": "bpc_adaptive_update"}[dom]
+    traffic, traffic_digest = recorded_traffic(args.workload, dom)
+    if traffic is not None and traffic_digest != sources_digest():
+        print(f"bench.py: the traffic figure under profiles/ was measured at kernel sources {traffic_digest}, "
+              f"these are {sources_digest()}", file=sys.stderr)
     result = {
         "metric": "GB/s of gradient compressed+EF+decompressed, % of HBM peak, per compressor",
         "value": head["value_GBps"], "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -288,7 +367,8 @@ def main():
                    "compressor": w["kind"], "n_workers": w["n_workers"], "partition_bytes": synth.PART_BYTES,
                    "error_feedback": "two-way", "update": "adam-style"},
         "roofline": {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": recorded_traffic(args.workload, dom),
+                     "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": traffic,
+                     "traffic_measured_at_sources": traffic_digest, "sources": sources_digest(),
                      "kernel": f"{call} ({w['kind']})", "algorithmic_bytes_per_element": alg,
                      "elements_per_launch": w["D"]},
         "stages": head["stages"],
@@ -302,8 +382,13 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         result["copy_calibration"] = {"bytes_read": src.numel() * 4, "bytes_written": src.numel() * 4, "launches": 3}
+    if not args.no_stream_probe:
+        # the ceiling the 8 TB/s figure has to be read against: plain streams of the same shapes
+        result["roofline"]["achieved_stream"] = stream_probe(torch, bpc, w["D"])
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(args.workload, w, args.cpu_partitions, args.cpu_steps, synth)
+        single = cpu_baseline(args.workload, w, args.cpu_single_partitions, 1, synth, threads=1)
+        result["cpu_baseline"]["single_thread"] = {"value": single["value"], "unit": "GB/s", "sample": single["sample"]}
     print(json.dumps(result))
 
 

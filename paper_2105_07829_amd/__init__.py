@@ -29,7 +29,7 @@ HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-ffp-contract=off"
 
 EXPORTS = ["bpc_partition_k", "bpc_partition_stride", "bpc_payload_bytes", "bpc_workspace_bytes",
            "bpc_update_workspace_bytes", "bpc_workspace_status_offset", "bpc_workspace_check", "bpc_compress", "bpc_compress_static_ws", "bpc_decompress", "bpc_server_aggregate", "bpc_adaptive_update",
-           "bpc_status_string", "bpc_last_hip_error"]
+           "bpc_stream_probe", "bpc_status_string", "bpc_last_hip_error"]
 
 
 def build(verbose: bool = False) -> str:
@@ -107,6 +107,8 @@ def lib():
         L.bpc_adaptive_update.argtypes = [PP, C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p,
                                           C.POINTER(Opt), C.c_void_p, C.c_size_t, C.c_void_p]
         L.bpc_adaptive_update.restype = C.c_int
+        L.bpc_stream_probe.argtypes = [C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p]
+        L.bpc_stream_probe.restype = C.c_int
         L.bpc_status_string.argtypes = [C.c_int]
         L.bpc_status_string.restype = C.c_char_p
         L.bpc_last_hip_error.argtypes = []
@@ -216,6 +218,15 @@ def bpc_compress(p: Params, grad, residual, payload, ws, stream=None) -> None:
     st = lib().bpc_compress(C.byref(p), _ptr(grad), _dtype_code(grad), _ptr(residual), grad.numel(),
                             _ptr(payload), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream))
     _check(st, "bpc_compress")
+
+
+PROBE_COPY, PROBE_WORKER_MIX, PROBE_UPDATE_MIX = 0, 1, 2
+PROBE_BYTES_PER_ELEMENT = {PROBE_COPY: 8, PROBE_WORKER_MIX: 10, PROBE_UPDATE_MIX: 24}
+
+
+def bpc_stream_probe(mix: int, a, b, c, stream=None) -> None:
+    """One streaming kernel with a stage's memory traffic and none of its arithmetic (see bpc.h)."""
+    _check(lib().bpc_stream_probe(mix, _ptr(a), _ptr(b), _ptr(c), c.numel(), _stream(stream)), "bpc_stream_probe")
 
 
 STATIC_WS_BYTES = 4 << 20

@@ -245,6 +245,15 @@ bpc_status_t bpc_adaptive_update(const bpc_params_t *params, const void *payload
                                     (hipStream_t)hip_stream));
 }
 
+bpc_status_t bpc_stream_probe(bpc_probe_t mix, const void *a, const void *b, void *c, uint64_t n, void *hip_stream) {
+  if (mix != BPC_PROBE_COPY && mix != BPC_PROBE_WORKER_MIX && mix != BPC_PROBE_UPDATE_MIX) return BPC_ERR_INVALID_ARG;
+  if (n == 0) return BPC_OK;
+  if (!a || !c || (mix != BPC_PROBE_COPY && !b)) return BPC_ERR_INVALID_ARG;
+  if (n / kTile >= 0x7fffffffull) return BPC_ERR_UNSUPPORTED;
+  if (!aligned16(a) || !aligned16(b) || !aligned16(c)) return BPC_ERR_ALIGNMENT;
+  return hip_status(stream_probe((int)mix, a, b, c, n, (hipStream_t)hip_stream));
+}
+
 const char *bpc_status_string(bpc_status_t status) {
   switch (status) {
     case BPC_OK: return "ok";

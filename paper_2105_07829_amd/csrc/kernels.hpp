@@ -31,6 +31,8 @@ struct Workspace {
 };
 
 hipError_t fill_zero(void *ptr, size_t bytes, hipStream_t stream);
+// Streaming kernels with a stage's memory traffic and no arithmetic (bpc_stream_probe).
+hipError_t stream_probe(int mix, const void *a, const void *b, void *c, uint64_t n, hipStream_t stream);
 
 // The same call restricted to the ragged last partition: every pointer advanced past the
 // `full_parts` full partitions that another kernel has taken.

@@ -123,8 +123,10 @@ def device_gradient(dist: str, D: int, dtype: str = "f32", worker: int = 0, step
                 idx = (torch.arange(lo, lo + n, device=device) // pe)
                 x = x * scales[idx]
         elif dist == "laplace":
+            # inverse CDF; |u| is kept below 1/2 (rand() can return exactly 0, which would map to
+            # an infinite gradient: about eight a worker at this size)
             u = torch.rand(n, generator=g, device=device) - 0.5
-            x = -1e-3 * torch.sign(u) * torch.log1p(-2.0 * u.abs())
+            x = -1e-3 * torch.sign(u) * torch.log1p(-(2.0 * u.abs()).clamp(max=1.0 - 2.0 ** -24))
         elif dist == "student_t3":
             z = torch.randn(n, generator=g, device=device)
             w = torch.randn(3, n, generator=g, device=device)
@@ -133,6 +135,26 @@ def device_gradient(dist: str, D: int, dtype: str = "f32", worker: int = 0, step
             raise ValueError(dist)
         out[lo:lo + n] = x.to(out_dtype)
     return out
+
+
+def layer_blocks(D: int, hidden: int = 1024, vocab: int = 30522) -> np.ndarray:
+    """Ascending element offsets (first 0, last D) that cut a flat gradient of D elements into
+    blocks sized like the parameter tensors of a BERT encoder stack: the embedding tables and
+    their layer norm, then per layer four hidden x hidden projections with biases, a layer norm,
+    the two feed-forward matrices with biases and another layer norm, repeated until D is used
+    up (the last block is cut short).  These are the layers that LANS normalises over; sizes
+    range from `hidden` elements to tens of millions, and most boundaries fall inside a
+    partition."""
+    h = hidden
+    sizes = [vocab * h, 512 * h, 2 * h, h, h]
+    layer = [h * h, h] * 4 + [h, h] + [4 * h * h, 4 * h, 4 * h * h, h] + [h, h]
+    offs, at, i = [0], 0, 0
+    while at < D:
+        size = sizes[i] if i < len(sizes) else layer[(i - len(sizes)) % len(layer)]
+        at = min(D, at + size)
+        offs.append(at)
+        i += 1
+    return np.asarray(offs, dtype=np.uint64)
 
 
 def device_params(D: int, seed: int = BASE_SEED, device="cuda"):

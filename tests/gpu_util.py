@@ -84,3 +84,26 @@ def close(a, b, rel):
     a64, b64 = a.astype(np.float64), b.astype(np.float64)
     scale = np.abs(b64) + (np.abs(b64).mean() if b64.size else 0.0)
     return bool(np.all(np.abs(a64 - b64) <= rel * scale + 1e-45))
+
+
+def lans_step_close(x_gpu, x_ref, x_before, blocks=None, rel=2e-6):
+    """The LANS step x_before - x_after of the library against the oracle's.
+
+    The single-pass LANS kernel forms the ratios r and c with the hardware's reciprocal and
+    square root (each within 1 ulp, four of them in a row: 4 * 2^-24 = 2.4e-7 relative) and its
+    block norms from f32 partial sums of 512 squares (a few 1e-7 relative), so an element of the
+    step lr * phi * (beta1 * u_r / |u_r| + (1 - beta1) * u_c / |u_c|) is off by at most about
+    2.4e-7 + 2 * 4e-7 + a few roundings < 2e-6 of its terms; where the two terms cancel the
+    bound is relative to their size, taken here as the mean |step| of the element's block.
+    On top comes the one rounding of x - step to f32 on either side (2^-24 |x| each).
+    `blocks`: ascending offsets of the LANS blocks (None: one block)."""
+    xb = x_before.astype(np.float64)
+    sg, sr = xb - x_gpu.astype(np.float64), xb - x_ref.astype(np.float64)
+    if blocks is None:
+        blocks = np.array([0, x_ref.size])
+    blocks = np.asarray(blocks, dtype=np.int64)
+    sizes = np.diff(blocks)
+    sums = np.add.reduceat(np.abs(sr), blocks[:-1][sizes > 0]) if x_ref.size else np.zeros(0)
+    mean = np.repeat(sums / sizes[sizes > 0], sizes[sizes > 0])
+    tol = rel * (np.abs(sr) + mean) + 2.0 ** -23 * np.abs(x_ref.astype(np.float64)) + 1e-45
+    return bool(np.all(np.abs(sg - sr) <= tol))

@@ -2,11 +2,18 @@
 
 For each workload of the benchmark spec the whole pipeline runs on the GPU (n workers with non-zero
 residuals, server aggregate, update) on seeded synthetic gradients generated on the card.
-Partitions are independent units of the method, so the oracle recomputes a sample of them
-(first, a middle one, the ragged last one) from exactly the bytes the GPU consumed: the
-gradient / residual slices for the worker stage, the GPU's own n worker records for the
-server stage, the GPU's own pulled record for the update.  Same bars as the small tests.
+Partitions are independent units of the method, so the oracle recomputes them one by one
+from exactly the bytes the GPU consumed: the gradient / residual slices for the worker stage,
+the GPU's own n worker records for the server stage, the GPU's own pulled record for the
+update.  On the two shapes that carry the throughput target (bert_base, bert_large) EVERY
+partition of worker 0, of the server and of the update is compared, and a second worker (the
+last one: another Philox stream id, another set of input buffers) on a sample; on the other
+shapes a sample of partitions (first, a middle one, the ragged last one).  A LANS step over
+layer-shaped caller-defined blocks, which cross partitions, is compared over the whole
+gradient.  Same bars as the small tests.
 """
+from concurrent.futures import ThreadPoolExecutor
+
 import numpy as np
 import pytest
 
@@ -27,8 +34,18 @@ def env():
     return gpu_util, synth, torch
 
 
+EVERY_PARTITION = ("bert_base", "bert_large")
+
+
 def sample_partitions(P):
     return sorted({0, P // 2, P - 1})
+
+
+def for_each(parts, check):
+    """check(p) for every partition, spread over host threads (the oracle is plain C called
+    through ctypes, which releases the interpreter lock).  Assertion errors surface here."""
+    with ThreadPoolExecutor(16) as pool:
+        list(pool.map(check, parts))
 
 
 def record_equal(kind, rec_g, rec_o, d, k, k_cap, pe=0, levels=4):
@@ -65,44 +82,52 @@ def test_full_size_pipeline(env, orc, name):
     p0 = prm_b(0)
     strd = bpc.partition_stride(p0)
     ws = torch.zeros(bpc.workspace_bytes(p0, D, n), dtype=torch.uint8, device=dev)
-    parts = sample_partitions(P)
+    parts = list(range(P)) if name in EVERY_PARTITION else sample_partitions(P)
+    sampled = sample_partitions(P)
 
     def sl(p):
         return slice(p * pe, min(D, (p + 1) * pe))
 
-    # ---------------- worker stage, every worker on the GPU, worker 0 checked
-    pays = []
+    # ---------------- worker stage, every worker on the GPU; worker 0 checked on `parts`, the
+    # last worker on the sample
+    checked = {0: parts, n - 1: sampled} if n > 1 else {0: parts}
+    pays, g_host, e_host, e_after = [], {}, {}, {}
     for i in range(n):
         g = synth.device_gradient(w["dist"], D, w["dtype"], worker=i, device=dev)
         e = synth.device_gradient("normal", D, "f32", worker=100 + i, device=dev) * 0.3
-        if i == 0:
-            g_host = {p: g[sl(p)].cpu().numpy() for p in parts}
-            e_host = {p: e[sl(p)].cpu().numpy() for p in parts}
+        if i in checked:
+            g_host[i] = {p: g[sl(p)].cpu().numpy() for p in checked[i]}
+            e_host[i] = {p: e[sl(p)].cpu().numpy() for p in checked[i]}
         pay = torch.zeros(bpc.payload_bytes(p0, D), dtype=torch.uint8, device=dev)
         bpc.bpc_compress(prm_b((1 << 32) | i), g, e, pay, ws)
+        bpc.workspace_check(p0, D, ws)
         pays.append(pay)
-        if i == 0:
-            e_after = {p: e[sl(p)].cpu().numpy() for p in parts}
+        if i in checked:
+            e_after[i] = {p: e[sl(p)].cpu().numpy() for p in checked[i]}
         del g, e
-    torch.cuda.synchronize()
-    assert bpc.workspace_status(p0, D, ws) == 0
-    for p in parts:
-        d = sl(p).stop - sl(p).start
-        k = fmt.k_of(kw["k_ratio"], d) if k_cap else 0
-        rec_g = pays[0][p * strd:(p + 1) * strd].cpu().numpy()
-        res_o = e_host[p].copy()
-        rec_o = orc.compress(prm_o((1 << 32) | 0, p), g_host[p], res_o)
-        if kind in ("sign", "dither", "natdither"):
-            hg, ho = fmt.header_f32(rec_g), fmt.header_f32(rec_o)
-            assert abs(float(hg) - float(ho)) <= REL * abs(float(ho))
-            if hg != ho:       # packed bits on equal terms: oracle with the GPU's scale
-                res_o = e_host[p].copy()
-                rec_o = orc.compress(prm_o((1 << 32) | 0, p, norm=hg), g_host[p], res_o)
-        assert record_equal(kind, rec_g, rec_o, d, k, k_cap, pe, kw["levels"]), (name, "worker", p)
-        if kind in ("topk", "topk16", "fp16"):
-            assert np.array_equal(e_after[p].view(np.uint32), res_o.view(np.uint32))
-        else:
-            assert gu.close(e_after[p], res_o, REL), (name, "worker residual", p)
+    for i in checked:
+        pay_host = pays[i].cpu().numpy()
+
+        def check_worker(p, i=i, pay_host=pay_host):
+            d = sl(p).stop - sl(p).start
+            k = fmt.k_of(kw["k_ratio"], d) if k_cap else 0
+            rec_g = pay_host[p * strd:(p + 1) * strd]
+            res_o = e_host[i][p].copy()
+            rec_o = orc.compress(prm_o((1 << 32) | i, p), g_host[i][p], res_o)
+            if kind in ("sign", "dither", "natdither"):
+                hg, ho = fmt.header_f32(rec_g), fmt.header_f32(rec_o)
+                assert abs(float(hg) - float(ho)) <= REL * abs(float(ho)), (name, "worker", i, "scale", p)
+                if hg != ho:       # packed bits on equal terms: oracle with the GPU's scale
+                    res_o = e_host[i][p].copy()
+                    rec_o = orc.compress(prm_o((1 << 32) | i, p, norm=hg), g_host[i][p], res_o)
+            assert record_equal(kind, rec_g, rec_o, d, k, k_cap, pe, kw["levels"]), (name, "worker", i, p)
+            if kind in ("topk", "topk16", "fp16"):
+                assert np.array_equal(e_after[i][p].view(np.uint32), res_o.view(np.uint32)), (name, "worker", i, p)
+            else:
+                assert gu.close(e_after[i][p], res_o, REL), (name, "worker residual", i, p)
+
+        for_each(checked[i], check_worker)
+    del g_host, e_host, e_after
 
     # ---------------- server stage on the GPU's own worker messages
     sres = synth.device_gradient("normal", D, "f32", worker=999, device=dev) * 0.2
@@ -111,65 +136,123 @@ def test_full_size_pipeline(env, orc, name):
     ins_b = [prm_b((1 << 32) | i) for i in range(n)]
     out_stream = (1 << 32) | (1 << 16)
     bpc.bpc_server_aggregate(ins_b, pays, prm_b(out_stream), sres, D, out_pay, ws)
-    torch.cuda.synchronize()
-    assert bpc.workspace_status(p0, D, ws) == 0
-    for p in parts:
+    bpc.workspace_check(p0, D, ws)
+    pays_host = [pay.cpu().numpy() for pay in pays]
+    out_host = out_pay.cpu().numpy()
+    sres_host = sres.cpu().numpy()
+
+    def check_server(p):
         d = sl(p).stop - sl(p).start
         k = fmt.k_of(kw["k_ratio"], d) if k_cap else 0
-        recs = [pays[i][p * strd:(p + 1) * strd].cpu().numpy() for i in range(n)]
+        recs = [pays_host[i][p * strd:(p + 1) * strd] for i in range(n)]
         ins_o = [prm_o((1 << 32) | i, p) for i in range(n)]
-        rec_g = out_pay[p * strd:(p + 1) * strd].cpu().numpy()
+        rec_g = out_host[p * strd:(p + 1) * strd]
         res_o = s_host[p].copy()
         rec_o = orc.server_aggregate(ins_o, recs, prm_o(out_stream, p), res_o, d)
         if kind in ("sign", "dither", "natdither"):
             hg, ho = fmt.header_f32(rec_g), fmt.header_f32(rec_o)
-            assert abs(float(hg) - float(ho)) <= REL * abs(float(ho))
+            assert abs(float(hg) - float(ho)) <= REL * abs(float(ho)), (name, "server scale", p)
             if hg != ho:
                 res_o = s_host[p].copy()
                 rec_o = orc.server_aggregate(ins_o, recs, prm_o(out_stream, p, norm=hg), res_o, d)
         if kind == "randk":      # values of Delta come through float atomics: tolerance
             kg, vg = fmt.randk_values(rec_g)
             ko, vo = fmt.randk_values(rec_o)
-            assert kg == ko and gu.close(vg, vo, REL)
+            assert kg == ko and gu.close(vg, vo, REL), (name, "server values", p)
         else:
             assert record_equal(kind, rec_g, rec_o, d, k, k_cap, pe, kw["levels"]), (name, "server", p)
-        got = sres[sl(p)].cpu().numpy()
+        got = sres_host[sl(p)]
         if kind in ("topk", "topk16", "fp16"):
-            assert np.array_equal(got.view(np.uint32), res_o.view(np.uint32))
+            assert np.array_equal(got.view(np.uint32), res_o.view(np.uint32)), (name, "server residual", p)
         else:
             assert gu.close(got, res_o, REL), (name, "server residual", p)
+
+    for_each(parts, check_server)
+    del pays, pays_host, sres, sres_host, s_host
 
     # ---------------- update stage on the GPU's own pulled message
     x = synth.device_params(D, device=dev)
     m = synth.device_gradient("normal", D, "f32", worker=777, device=dev)
     v = synth.device_gradient("normal", D, "f32", worker=778, device=dev).abs() * 1e-3
-    before = {p: tuple(t[sl(p)].cpu().numpy() for t in (x, m, v)) for p in parts}
+    before = [t.cpu().numpy() for t in (x, m, v)]
     step = 3
     bpc.bpc_adaptive_update(prm_b(out_stream), out_pay, x, m, v,
                             bpc.make_opt(bpc.OPT_ADAM, 1e-3, 0.9, 0.999, 1e-8, 0.01, step), ws)
-    torch.cuda.synchronize()
-    for p in parts:
+    bpc.workspace_check(p0, D, ws)
+    after = [t.cpu().numpy() for t in (x, m, v)]
+
+    def check_adam(p):
         d = sl(p).stop - sl(p).start
-        xo, mo, vo = (a.copy() for a in before[p])
-        rec = out_pay[p * strd:(p + 1) * strd].cpu().numpy()
+        xo, mo, vo = (a[sl(p)].copy() for a in before)
+        rec = out_host[p * strd:(p + 1) * strd]
         orc.adaptive_update(prm_o(out_stream, p), rec, d, xo, mo, vo,
                             orc.make_opt(orc.OPT_ADAM, 1e-3, 0.9, 0.999, 1e-8, 0.01, step))
-        for got, ref in ((x, xo), (m, mo), (v, vo)):
-            assert np.array_equal(got[sl(p)].cpu().numpy().view(np.uint32), ref.view(np.uint32)), (name, "update", p)
+        for got, ref in zip(after, (xo, mo, vo)):
+            assert np.array_equal(got[sl(p)].view(np.uint32), ref.view(np.uint32)), (name, "update", p)
+
+    for_each(parts, check_adam)
     # ---------------- and a LANS step (the partitions are the blocks) on the state that step left
-    before = {p: tuple(t[sl(p)].cpu().numpy() for t in (x, m, v)) for p in parts}
+    before = after
     step = 4
     bpc.bpc_adaptive_update(prm_b(out_stream), out_pay, x, m, v,
                             bpc.make_opt(bpc.OPT_LANS, 1e-3, 0.9, 0.999, 1e-8, 0.01, step), ws)
-    torch.cuda.synchronize()
-    for p in parts:
+    bpc.workspace_check(p0, D, ws)
+    after = [t.cpu().numpy() for t in (x, m, v)]
+
+    def check_lans(p):
         d = sl(p).stop - sl(p).start
-        xo, mo, vo = (a.copy() for a in before[p])
-        rec = out_pay[p * strd:(p + 1) * strd].cpu().numpy()
+        xo, mo, vo = (a[sl(p)].copy() for a in before)
+        rec = out_host[p * strd:(p + 1) * strd]
         orc.adaptive_update(prm_o(out_stream, p), rec, d, xo, mo, vo,
                             orc.make_opt(orc.OPT_LANS, 1e-3, 0.9, 0.999, 1e-8, 0.01, step))
-        for got, ref in ((m, mo), (v, vo)):
-            assert np.array_equal(got[sl(p)].cpu().numpy().view(np.uint32), ref.view(np.uint32)), (name, "lans", p)
-        assert gu.close(x[sl(p)].cpu().numpy(), xo, REL), (name, "lans x", p)
-    del pays, sres, out_pay, x, m, v, ws
+        for got, ref in zip(after[1:], (mo, vo)):
+            assert np.array_equal(got[sl(p)].view(np.uint32), ref.view(np.uint32)), (name, "lans", p)
+        assert gu.lans_step_close(after[0][sl(p)], xo, before[0][sl(p)]), (name, "lans x", p)
+
+    for_each(parts, check_lans)
+    del out_pay, x, m, v, ws
+    torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("name,hidden", [("bert_base", 768), ("bert_large", 1024)])
+@pytest.mark.parametrize("lr", [1e-3, 0.5])
+def test_full_size_lans_step_over_layer_blocks(env, orc, name, hidden, lr):
+    """Algorithm 5 normalises over layers, not partitions: one LANS step with caller-defined
+    blocks sized like the tensors of a BERT encoder stack (synth.layer_blocks: a few hundred
+    blocks from `hidden` to tens of millions of elements, most boundaries inside a partition),
+    on the whole gradient, against the oracle over the whole gradient.  The learning rate of 0.5
+    makes a step as large as x, so that its error is not hidden behind the rounding of x."""
+    gu, synth, torch = env
+    bpc = gu.bpc
+    w = synth.WORKLOADS[name]
+    D, kind = w["D"], w["kind"]
+    pe = synth.part_elems(w["dtype"])
+    kw = dict(levels=w.get("levels", 4), seed=synth.BASE_SEED, stream_id=(1 << 32) | (1 << 16))
+    kind_o = {"sign": orc.SIGN, "dither": orc.DITHER}[kind]
+    pb, po = bpc.make_params(gu.KIND_B[kind], pe, **kw), orc.make_params(kind_o, pe, **kw)
+    dev = gu.DEV
+    blocks = synth.layer_blocks(D, hidden)
+    # a pulled message: the worker-side call on a synthetic Delta
+    delta = synth.device_gradient(w["dist"], D, "f32", worker=5, device=dev)
+    pay = torch.zeros(bpc.payload_bytes(pb, D), dtype=torch.uint8, device=dev)
+    ws = torch.zeros(bpc.update_workspace_bytes(pb, D, len(blocks) - 1), dtype=torch.uint8, device=dev)
+    bpc.bpc_compress(pb, delta, None, pay, ws)
+    bpc.workspace_check(pb, D, ws)
+    del delta
+    x = synth.device_params(D, device=dev)
+    m = synth.device_gradient("normal", D, "f32", worker=777, device=dev)
+    v = synth.device_gradient("normal", D, "f32", worker=778, device=dev).abs() * 1e-3
+    xo, mo, vo = (t.cpu().numpy() for t in (x, m, v))
+    x_before = xo.copy()
+    step = 2
+    blocks_dev = torch.from_numpy(blocks.astype(np.int64)).to(dev)
+    bpc.bpc_adaptive_update(pb, pay, x, m, v,
+                            bpc.make_opt(bpc.OPT_LANS, lr, 0.9, 0.999, 1e-8, 0.01, step, block_offsets=blocks_dev), ws)
+    bpc.workspace_check(pb, D, ws)
+    orc.adaptive_update(po, pay.cpu().numpy(), D, xo, mo, vo,
+                        orc.make_opt(orc.OPT_LANS, lr, 0.9, 0.999, 1e-8, 0.01, step, block_offsets=blocks))
+    assert np.array_equal(m.cpu().numpy().view(np.uint32), mo.view(np.uint32))
+    assert np.array_equal(v.cpu().numpy().view(np.uint32), vo.view(np.uint32))
+    assert gu.lans_step_close(x.cpu().numpy(), xo, x_before, blocks)
+    del x, m, v, pay, ws
     torch.cuda.empty_cache()

@@ -515,6 +515,56 @@ def test_natural_dither_probability_is_the_distance_to_the_lower_level(orc):
     assert np.all(np.abs(freq - p_up) <= 4.5 * np.sqrt(np.maximum(p_up * (1 - p_up), 1e-12) / trials) + 1e-12)
 
 
+def test_given_scale_takes_the_place_of_the_reduction(orc):
+    """A scale handed in (the hand-off the GPU tests use to decide packed bits on equal terms)
+    is used exactly where the partition's own norm would be: the closed form of the scaled sign
+    with sigma replaced, the draw-by-draw level rule with nu replaced, exact levels on the grid
+    of the given nu, and -- handed the value the reduction itself finds -- the same bytes."""
+    d, part_no = 777, 2
+    q = rng(31).standard_normal(d).astype(np.float32)
+    # scaled sign: bits do not depend on the scale; decode and residual use the given one
+    p0 = orc.make_params(orc.SIGN, PE)
+    own = fmt.header_f32(orc.encode_partition(p0, part_no, q))
+    for given in (np.float32(own), np.float32(0.3), np.float32(own * 1.0000001)):
+        rec = orc.encode_partition(p0, part_no, q, norm=given)
+        sigma, bits, _ = fmt.sign_bits(rec, d)
+        assert sigma == given and np.array_equal(bits, q < 0)
+        assert np.array_equal(orc.decode_partition(p0, part_no, rec, d), np.where(q < 0, -given, given).astype(np.float32))
+        res = np.zeros(d, np.float32)
+        pay = orc.compress(orc.make_params(orc.SIGN, PE, norm_override=np.array([given], np.float32)), q, res)
+        assert np.array_equal(pay[:rec.size], rec)
+        assert np.array_equal(res, q - np.where(q < 0, -given, given).astype(np.float32))
+    assert np.array_equal(orc.encode_partition(p0, part_no, q, norm=own), orc.encode_partition(p0, part_no, q))
+    # linear dithering: every level recomputed from its draw with the given nu
+    s, seed, stream = 4, 42, (9 << 32) | 1
+    pd = orc.make_params(orc.DITHER, PE, levels=s, seed=seed, stream_id=stream)
+    own = fmt.header_f32(orc.encode_partition(pd, part_no, q))
+    assert np.array_equal(orc.encode_partition(pd, part_no, q, norm=own), orc.encode_partition(pd, part_no, q))
+    given = np.float32(own * 1.37)
+    rec = orc.encode_partition(pd, part_no, q, norm=given)
+    nu, sgn, lvl, _ = fmt.dither_nibbles(rec, d)
+    assert nu == given and np.array_equal(sgn, q < 0)
+    for j in range(d):
+        blk = orc.philox4x32_10([j // 4, part_no, stream & 0xFFFFFFFF, stream >> 32], [seed, 0])
+        u = np.float32(int(blk[j % 4]) >> 8) * np.float32(2.0 ** -24)
+        a = np.float32(abs(q[j])) * (np.float32(s) / given)
+        l = np.floor(a)
+        assert lvl[j] == min(s, int(l) + int(u < np.float32(a - l)))
+    # grid points of a given nu that is not the vector's norm: nothing to round
+    lv = np.array([0, 1, 2, 3, 4, 1, 2, 0], dtype=np.float32)
+    sg = np.array([1, -1, 1, -1, 1, -1, -1, 1], dtype=np.float32)
+    x = sg * lv * np.float32(0.25)                       # grid of nu = 1, while ||x||_2 = 1.5
+    for kind, xs, levels in ((orc.DITHER, x, 4),
+                             (orc.NATDITHER, sg * np.where(lv == 0, 0, 2.0 ** (lv - 4)).astype(np.float32), 4)):
+        for seed in range(10):
+            pk = orc.make_params(kind, PE, levels=levels, seed=seed)
+            rec = orc.encode_partition(pk, 0, xs, norm=np.float32(1.0))
+            nu, _, lvl, _ = fmt.dither_nibbles(rec, xs.size)
+            assert nu == 1.0 and np.array_equal(lvl, lv.astype(np.uint8))
+            assert np.array_equal(orc.decode_partition(pk, 0, rec, xs.size), xs)
+            assert fmt.header_f32(orc.encode_partition(pk, 0, xs)) != 1.0     # (its own norm is another number)
+
+
 def test_zero_vector_encodes_to_zero(orc):
     z = np.zeros(100, dtype=np.float32)
     for kind in (orc.SIGN, orc.DITHER, orc.NATDITHER, orc.TOPK, orc.RANDK, orc.IDENTITY):
