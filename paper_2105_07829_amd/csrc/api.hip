@@ -77,10 +77,13 @@ size_t bpc_workspace_status_offset(const bpc_params_t *params, uint64_t D) {
 
 // Workspace of an update call: LANS with caller-defined blocks keeps three f64 sums per block
 // where the layout has room for three per partition.
-static size_t update_ws_bytes(const WsLayout &lay, bool caller_blocks, uint64_t n_blocks) {
+static size_t update_ws_bytes(const WsLayout &lay, bool caller_blocks, uint64_t n_blocks, uint64_t D) {
   size_t need = lay.total;
   if (caller_blocks) {
+    // three f64 sums per block (the two-launch form) or the tables of the one-pass form
     size_t with_blocks = lay.norms + (sizeof(double) * 3 * (size_t)n_blocks + 255) / 256 * 256;
+    const size_t one_pass = lay.norms + block_ws(nullptr, n_blocks, cdiv(D, kSTile)).bytes;
+    if (one_pass > with_blocks) with_blocks = one_pass;
     if (with_blocks > need) need = with_blocks;
   }
   return need;
@@ -89,7 +92,7 @@ static size_t update_ws_bytes(const WsLayout &lay, bool caller_blocks, uint64_t 
 size_t bpc_update_workspace_bytes(const bpc_params_t *params, uint64_t D, uint64_t n_blocks) {
   if (!params_valid(params) || n_blocks > (1ull << 40)) return 0;
   if (D == 0) return 256;
-  return update_ws_bytes(ws_layout(params, D), n_blocks != 0, n_blocks);
+  return update_ws_bytes(ws_layout(params, D), n_blocks != 0, n_blocks, D);
 }
 
 bpc_status_t bpc_workspace_check(const bpc_params_t *params, uint64_t D, const void *ws, void *hip_stream) {
@@ -237,7 +240,7 @@ bpc_status_t bpc_adaptive_update(const bpc_params_t *params, const void *payload
       !aligned16(opt->block_offsets))
     return BPC_ERR_ALIGNMENT;
   WsLayout lay = ws_layout(params, D);
-  const size_t need = update_ws_bytes(lay, opt->kind == BPC_OPT_LANS && opt->block_offsets, opt->n_blocks);
+  const size_t need = update_ws_bytes(lay, opt->kind == BPC_OPT_LANS && opt->block_offsets, opt->n_blocks, D);
   if (!ws || ws_bytes < need) return BPC_ERR_WORKSPACE;
   Geo g = make_geo(params, D);
   Workspace w{(uint8_t *)ws, lay};

@@ -154,6 +154,30 @@ inline WsLayout ws_layout(const bpc_params_t *p, uint64_t D) {
   return w;
 }
 
+// Extra workspace of LANS with caller-defined blocks (update.hip), placed where the block norms
+// of the default blocks go (WsLayout::norms).  `tiles` = tiles of kSTile elements.
+struct BlockWs {
+  uint32_t *tot;      // [4 * n_blocks]: bits of phi, w_r, w_c of every block that reaches beyond a tile
+  uint32_t *cnt;      // [n_blocks]: tiles of the block that have published their share
+  double *tslots;     // [6 * tiles]: slots A and B of every tile, three sums each
+  uint32_t *first;    // [tiles]: the block that holds the first element of the tile
+  uint32_t *list;     // [1 + tiles]: number of deferred tiles, then their numbers
+  size_t bytes;       // of all of the above
+};
+inline BlockWs block_ws(uint8_t *base, uint64_t n_blocks, uint64_t tiles) {
+  BlockWs w;
+  size_t off = 0;
+  const uintptr_t at = reinterpret_cast<uintptr_t>(base);   // (base may be NULL when only the size is asked for)
+  auto take = [&](size_t bytes) { uintptr_t q = at + off; off += (bytes + 255) / 256 * 256; return q; };
+  w.tot = reinterpret_cast<uint32_t *>(take(16 * (size_t)n_blocks));
+  w.cnt = reinterpret_cast<uint32_t *>(take(4 * (size_t)n_blocks));
+  w.tslots = reinterpret_cast<double *>(take(48 * (size_t)tiles));
+  w.first = reinterpret_cast<uint32_t *>(take(4 * (size_t)tiles));
+  w.list = reinterpret_cast<uint32_t *>(take(4 * ((size_t)tiles + 1)));
+  w.bytes = off;
+  return w;
+}
+
 BPC_HD inline uint64_t k_of_device(const Geo &g, uint32_t p) { return k_rule(g.k_ratio, g.part_size(p)); }
 
 }  // namespace bpc

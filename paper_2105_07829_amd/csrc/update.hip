@@ -708,6 +708,561 @@ __global__ __launch_bounds__(kThreads) void lans_apply_kernel(Geo g, DEC dec, fl
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// LANS with caller-defined blocks (Algorithm 5 normalises over layers G_b), one pass over the
+// data where the blocks allow it.
+//
+// The tile structure, the lagged exchange and the arithmetic are those of lans_single_kernel;
+// what changes is whose sums a tile needs.  A tile of 8192 elements meets its blocks as
+//   * blocks that lie inside it ("interior"): their three sums are complete in the workgroup;
+//   * at most two blocks that reach beyond it: the one that holds its first element and the
+//     one that holds its last.  The tile's share of the first goes to slot A of the tile, its
+//     share of the last (if that is another block) to slot B, and the tile counts itself in
+//     at the block (one atomic add).  The tile that finds itself the last of a block's
+//     t1 - t0 + 1 tiles adds up the shares in tile order (first tile: slot A if the block
+//     starts on the tile's first element, else B; every later tile: slot A), which makes the
+//     totals independent of timing, and publishes phi and the two weights of the block.  Tiles
+//     wait for those three words in their lagged phase 2, not for slots.
+// A workgroup that holds a tile cannot take its next one before the tile's x is written.  With
+// G workgroups taking tiles w, w + G, ... (round i = tiles iG .. iG + G - 1), a workgroup writes
+// the x of its round-(i-1) tile after phase 1 of its round-i tile; so a wait for a block whose
+// tiles lie in at most two consecutive rounds is for tiles of rounds <= i, and by induction over
+// the rounds (phase 1 never waits for a tile that has not counted itself in) every such wait
+// ends.  A block that reaches over three rounds or more could stall the grid, and a tile with
+// more blocks than the kernel keeps weights for does not fit either.  Such tiles are
+// "deferred": they update their moments, publish their shares and count in like all others,
+// but leave x alone and put their number on a list; lans_deferred_kernel, launched after this
+// one (when every block's totals are known), recomputes r + wd x and c + wd x from the
+// updated moments and writes their x (16.5 more bytes per element, for those tiles only).
+constexpr int kLMaxLocal = 32;                  // blocks of a tile the one-pass kernel keeps weights for
+constexpr uint32_t kTotUnset = 0xffffffffu;     // a block total not yet published (never the bits of a result:
+                                                // a NaN that arithmetic produces is 0x7fc00000 or carries a payload of its input)
+
+__global__ void lans_blocks_prepare_kernel(BlockWs w, const uint64_t *offs, uint64_t n_blocks, uint32_t tiles, uint32_t *status) {
+  const uint64_t step = (uint64_t)gridDim.x * blockDim.x;
+  const uint64_t i0 = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  for (uint64_t i = i0; i < 4 * n_blocks; i += step) w.tot[i] = kTotUnset;
+  for (uint64_t i = i0; i < n_blocks; i += step) w.cnt[i] = 0;
+  for (uint64_t i = i0; i < 6ull * tiles; i += step) w.tslots[i] = -1.0;
+  for (uint64_t i = i0; i < tiles; i += step) w.first[i] = find_block(offs, n_blocks, i * kSTile);
+  if (i0 == 0) {
+    w.list[0] = 0;
+    status[0] = 0;
+    status[1] = 0;
+  }
+}
+
+// A thread's three sums of squares over those of its eight elements whose position in the tile
+// lies in [lo, hi) (f32, elements in index order), then over the wave (a tree in f32).
+__device__ __forceinline__ void lans_wave_sums(const LansHeld &h, uint32_t lo, uint32_t hi, float out[3]) {
+  float f_x = 0.0f, f_r = 0.0f, f_c = 0.0f;
+#pragma unroll
+  for (int u = 0; u < kLRows; ++u) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const uint32_t pos = (uint32_t)(u * kLRow) + threadIdx.x * 4 + c;
+      const bool in = pos >= lo && pos < hi;
+      f_x = in ? fmaf(h.xs[4 * u + c], h.xs[4 * u + c], f_x) : f_x;
+      f_r = in ? fmaf(h.ur[4 * u + c], h.ur[4 * u + c], f_r) : f_r;
+      f_c = in ? fmaf(h.uc[4 * u + c], h.uc[4 * u + c], f_c) : f_c;
+    }
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    f_x = f_x + __shfl_xor(f_x, off, 64);
+    f_r = f_r + __shfl_xor(f_r, off, 64);
+    f_c = f_c + __shfl_xor(f_c, off, 64);
+  }
+  out[0] = f_x; out[1] = f_r; out[2] = f_c;
+}
+
+// phi(||x||) and the two weights from a block's three sums.
+__device__ __forceinline__ void lans_weights(const OptArgs &o, double s_x, double s_r, double s_c, float w[3]) {
+  const float norm_x = (float)sqrt(s_x);
+  const float norm_r = (float)sqrt(s_r);
+  const float norm_c = (float)sqrt(s_c);
+  float phi = norm_x < o.phi_lo ? o.phi_lo : norm_x;
+  phi = phi > o.phi_hi ? o.phi_hi : phi;
+  w[0] = phi;
+  w[1] = norm_r > 0.0f ? o.beta1 / norm_r : 0.0f;
+  w[2] = norm_c > 0.0f ? (1.0f - o.beta1) / norm_c : 0.0f;
+}
+
+// What a workgroup knows about the blocks of a tile (LDS; two of them: the tile in phase 1
+// and the tile whose x is still to be written).
+struct TileBlocks {
+  uint64_t bound[kLMaxLocal + 1];    // bound[q] = first element of the tile's q-th block (bound[nloc] = end of the last)
+  uint32_t rel[kLMaxLocal + 1];      // the same relative to the tile, clamped to [0, 8192]
+  float wts[kLMaxLocal][3];          // phi, w_r, w_c of the tile's q-th block
+  // the blocks that reach beyond the tile: side 0 holds its first element, side 1 its last
+  double share[2][3];                // the tile's own sums over its part of that block
+  uint64_t far_lo[2], far_hi[2];     // the block's elements [lo, hi)
+  uint32_t far_b[2];                 // its number, or kNoBlock
+  uint32_t far_q[2];                 // its index in the tile's block list
+  uint32_t nloc;                     // blocks of the tile (kLMaxLocal + 1: more than the kernel keeps weights for)
+  uint32_t fb;                       // number of the tile's first block
+  uint32_t deferred;
+};
+constexpr uint32_t kNoBlock = 0xffffffffu;
+
+// Index in the tile's block list of the block that holds tile-relative position `pos`.
+__device__ __forceinline__ uint32_t lans_block_of(const TileBlocks &tb, uint32_t pos) {
+  uint32_t q = 0;
+  for (uint32_t k = 1; k < tb.nloc; ++k) q += tb.rel[k] <= pos ? 1u : 0u;
+  return q;
+}
+
+// First wave: the three words of block b's totals once they are published.
+__device__ __forceinline__ void lans_wait_block(const uint32_t *tot, uint32_t *status, float w[3]) {
+  uint32_t a, b, c;
+  int spins = 0;
+  for (;;) {
+    a = __hip_atomic_load(tot + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    b = __hip_atomic_load(tot + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    c = __hip_atomic_load(tot + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (a != kTotUnset && b != kTotUnset && c != kTotUnset) break;
+    if (++spins > kSpinLimit) {
+      if ((threadIdx.x & 63) == 0) atomicOr(status, 1u);
+      break;
+    }
+    __builtin_amdgcn_s_sleep(16);
+  }
+  w[0] = __uint_as_float(a); w[1] = __uint_as_float(b); w[2] = __uint_as_float(c);
+}
+
+// One wave: the tile `item` has the share `share` of block b, which covers tiles t0..t1.
+// Publishes the share, counts the tile in, and if it is the block's last tile adds up all
+// shares in tile order and publishes the block's totals.
+__device__ __forceinline__ void lans_publish_share(const OptArgs &o, const BlockWs &w, uint32_t item, int side, uint32_t b,
+                                          uint64_t lo, uint64_t hi, const double share[3], uint32_t *status) {
+  const uint32_t lane = threadIdx.x & 63;
+  const uint32_t t0 = (uint32_t)(lo / kSTile), t1 = (uint32_t)((hi - 1) / kSTile);
+  uint32_t arrived = 0;
+  if (lane == 0) {
+    double *ps = w.tslots + 6ull * item + 3 * side;
+    slot_publish(ps + 0, share[0]);
+    slot_publish(ps + 1, share[1]);
+    slot_publish(ps + 2, share[2]);
+    arrived = __hip_atomic_fetch_add(w.cnt + b, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1;
+  }
+  arrived = __builtin_amdgcn_readfirstlane(arrived);
+  if (arrived != t1 - t0 + 1) return;
+  // the last tile of the block: every other tile has issued the stores of its share
+  const bool starts_on_tile = lo % kSTile == 0;
+  double a0 = 0.0, a1 = 0.0, a2 = 0.0;
+  for (uint32_t idx = lane; idx <= t1 - t0; idx += 64) {
+    const double *ps = w.tslots + 6ull * (t0 + idx) + ((idx == 0 && !starts_on_tile) ? 3 : 0);
+    double q0, q1, q2;
+    int spins = 0;
+    for (;;) {
+      q0 = __hip_atomic_load(ps + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      q1 = __hip_atomic_load(ps + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      q2 = __hip_atomic_load(ps + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (slot_published(q0) && slot_published(q1) && slot_published(q2)) break;
+      if (++spins > kSpinLimit) {
+        atomicOr(status, 1u);
+        break;
+      }
+      __builtin_amdgcn_s_sleep(4);
+    }
+    a0 += q0; a1 += q1; a2 += q2;
+  }
+  a0 = wave_sum(a0);
+  a1 = wave_sum(a1);
+  a2 = wave_sum(a2);
+  if (lane == 0) {
+    float wt[3];
+    lans_weights(o, a0, a1, a2, wt);
+#pragma unroll
+    for (int k = 0; k < 3; ++k) {
+      uint32_t bits = __float_as_uint(wt[k]);
+      bits = bits == kTotUnset ? 0x7fc00000u : bits;
+      __hip_atomic_store(w.tot + 4ull * b + k, bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+  }
+}
+
+// Phase 1, block part: from the tile's held values and its block bounds (already in tb.bound /
+// tb.rel / tb.nloc / tb.fb) to the weights of the interior blocks, the published shares of the
+// far-reaching ones and the decision whether the tile is deferred.  `red` holds
+// kLMaxLocal x waves x 3 doubles.  All threads; contains barriers.
+__device__ __forceinline__ void lans_tile_blocks(const OptArgs &o, const BlockWs &w, uint32_t item, uint32_t n_items, const LansTile &t,
+                                        const LansHeld &h, TileBlocks &tb, double *red, uint32_t span_limit, uint64_t D,
+                                        uint32_t *status) {
+  const uint32_t nloc = tb.nloc;
+  const bool many = nloc > (uint32_t)kLMaxLocal;
+  const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  constexpr int kWaves = kLThreads / 64;
+  const uint64_t tile_first = (uint64_t)item * kSTile;
+  const uint64_t tile_end = tile_first + t.valid;
+  // a tile with more blocks than weights are kept for: only its first and last block can matter
+  // to other tiles; the last one is the block that holds the next tile's first element, if
+  // that block starts inside this tile
+  uint32_t last_b = kNoBlock;
+  uint64_t last_lo = 0, last_hi = 0;
+  if (many && item + 1 < n_items) {
+    last_b = __builtin_amdgcn_readfirstlane(w.first[item + 1]);
+    last_lo = uniform_off(o.block_offsets[last_b]);
+    last_hi = uniform_off(o.block_offsets[last_b + 1]);
+    if (last_lo >= tile_end) last_b = kNoBlock;
+  }
+  const uint32_t n_sums = many ? 2u : nloc;
+#pragma unroll 1
+  for (uint32_t q = 0; q < n_sums; ++q) {
+    // positions of the tile that belong to the q-th sum (past the partition's end: to none)
+    uint32_t lo, hi;
+    if (many) {
+      lo = q == 0 ? 0u : (last_b != kNoBlock ? (uint32_t)(last_lo - tile_first) : t.valid);
+      hi = q == 0 ? tb.rel[1] : t.valid;
+    } else {
+      lo = tb.rel[q];
+      hi = tb.rel[q + 1];
+    }
+    float f[3];
+    lans_wave_sums(h, lo, hi, f);
+    if (lane == 0) {
+      red[(q * kWaves + wave) * 3 + 0] = (double)f[0];
+      red[(q * kWaves + wave) * 3 + 1] = (double)f[1];
+      red[(q * kWaves + wave) * 3 + 2] = (double)f[2];
+    }
+  }
+  if (threadIdx.x == 0) {
+    tb.far_b[0] = kNoBlock;
+    tb.far_b[1] = kNoBlock;
+    tb.deferred = many ? 1u : 0u;
+  }
+  __syncthreads();
+  if (threadIdx.x < n_sums) {
+    const uint32_t q = threadIdx.x;
+    double s0 = 0.0, s1 = 0.0, s2 = 0.0;
+    // (not unrolled: sixteen waves' sums in flight at once would need a hundred registers)
+#pragma unroll 2
+    for (int wv = 0; wv < kWaves; ++wv) {
+      s0 += red[(q * kWaves + wv) * 3 + 0];
+      s1 += red[(q * kWaves + wv) * 3 + 1];
+      s2 += red[(q * kWaves + wv) * 3 + 2];
+    }
+    uint64_t lo, hi;
+    uint32_t b;
+    if (many) {
+      lo = q == 0 ? tb.bound[0] : last_lo;
+      hi = q == 0 ? tb.bound[1] : last_hi;
+      b = q == 0 ? tb.fb : last_b;
+    } else {
+      lo = tb.bound[q];
+      hi = tb.bound[q + 1];
+      b = tb.fb + q;
+    }
+    const bool interior = lo >= tile_first && hi <= tile_end;
+    if (!interior && b != kNoBlock) {
+      const int side = q == 0 ? 0 : 1;     // (only the first and the last block of a tile can reach beyond it)
+      tb.share[side][0] = s0; tb.share[side][1] = s1; tb.share[side][2] = s2;
+      tb.far_b[side] = b;
+      tb.far_q[side] = q;
+      tb.far_lo[side] = lo;
+      tb.far_hi[side] = hi;
+    } else if (!many) {
+      float wt[3];
+      lans_weights(o, s0, s1, s2, wt);
+      tb.wts[q][0] = wt[0]; tb.wts[q][1] = wt[1]; tb.wts[q][2] = wt[2];
+    }
+  }
+  __syncthreads();
+  if (wave < 2) {
+    const int side = (int)wave;
+    const uint32_t b = __builtin_amdgcn_readfirstlane(tb.far_b[side]);
+    if (b != kNoBlock) {
+      const uint64_t lo = uniform_off(tb.far_lo[side]), hi = uniform_off(tb.far_hi[side]);
+      const double share[3] = {tb.share[side][0], tb.share[side][1], tb.share[side][2]};
+      // (rounds: workgroup w of G takes tiles w, w + G, ...; the tiles w + iG form round i)
+      if ((hi - 1) / kSTile / span_limit - lo / kSTile / span_limit > 1 && lane == 0) tb.deferred = 1u;
+      lans_publish_share(o, w, item, side, b, lo, hi, share, status);
+    }
+  }
+}
+
+// x of a tile whose blocks' weights are all in tb.wts.
+__device__ __forceinline__ void lans_write_x_blocks(const Geo &g, const ClusterGeo &cg, const OptArgs &o, float *x, uint32_t item,
+                                           const LansHeld &h, const TileBlocks &tb) {
+  const LansTile t = lans_tile(g, cg, item);
+  const uint32_t nloc = tb.nloc;
+#pragma unroll
+  for (int u = 0; u < kLRows; ++u) {
+    float xo[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const uint32_t q = nloc == 1 ? 0u : lans_block_of(tb, (uint32_t)(u * kLRow) + threadIdx.x * 4 + c);
+      const float phi = tb.wts[q][0], w_r = tb.wts[q][1], w_c = tb.wts[q][2];
+      const float dir = phi * (w_r * h.ur[4 * u + c] + w_c * h.uc[4 * u + c]);
+      xo[c] = h.xs[4 * u + c] - o.lr * dir;
+    }
+    row_buf(x + t.base, t.valid, u * kLRow, kLRow).store16<kNonTemporal>(as_u32x4(xo[0], xo[1], xo[2], xo[3]), threadIdx.x * 16);
+  }
+}
+
+template <class DEC>
+__global__ __launch_bounds__(kLThreads) void lans_blocks_kernel(Geo g, ClusterGeo cg, DEC dec, float *x, float *m, float *v,
+                                                               OptArgs o, BlockWs w, uint32_t span_limit /* = gridDim.x */) {
+  __shared__ __align__(16) float lds[DEC::kLdsFloats];
+  __shared__ double red[kLMaxLocal * (kLThreads / 64) * 3];
+  __shared__ TileBlocks tbs[2];
+  constexpr uint32_t kNone = 0xffffffffu;
+  uint32_t *status = o.status;
+  uint32_t item = __builtin_amdgcn_readfirstlane(blockIdx.x);
+  if (item >= cg.n_items) return;
+  LansRaw<DEC> raw;
+  lans_issue(g, cg, dec, x, m, v, item, raw);
+  uint32_t fb_raw = w.first[item];
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the loop is entered with nothing in flight
+  LansHeld prev_h;
+  uint32_t prev = kNone;
+  int cur = 0;
+  const float omb1 = 1.0f - o.beta1, omb2 = 1.0f - o.beta2;
+  const float inv_bc1 = 1.0f / o.bc1, inv_bc2 = 1.0f / o.bc2;
+  for (;;) {
+    const LansTile t = lans_tile(g, cg, item);
+    TileBlocks &tb = tbs[cur];
+    // the bounds of the tile's blocks: thread k asks for the first element of block fb + k
+    const uint32_t fb = __builtin_amdgcn_readfirstlane(fb_raw);
+    uint64_t my_bound = 0;
+    if (threadIdx.x <= (uint32_t)kLMaxLocal) {
+      const uint64_t k = (uint64_t)fb + threadIdx.x;
+      my_bound = o.block_offsets[k < o.n_blocks ? k : o.n_blocks];
+    }
+    if constexpr (has_begin_tile<DEC>::value) {
+      dec.begin_tile(t.p, t.tile, lds);
+    } else {
+      __syncthreads();
+      dec.table(raw.hdr, lds);
+      __syncthreads();
+    }
+    LansHeld h;
+#pragma unroll
+    for (int u = 0; u < kLRows; ++u) {
+      const uint32_t mi[4] = {raw.m[u].x, raw.m[u].y, raw.m[u].z, raw.m[u].w};
+      const uint32_t vi[4] = {raw.v[u].x, raw.v[u].y, raw.v[u].z, raw.v[u].w};
+      const uint32_t xi[4] = {raw.x[u].x, raw.x[u].y, raw.x[u].z, raw.x[u].w};
+      float gr[4];
+      dec.decode4(raw.g[u], t.tile * kSTile + u * kLRow + threadIdx.x * 4, raw.hdr, lds, gr);
+      float mo[4], vo[4];
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const float gj = gr[c];
+        const float mj = o.beta1 * __uint_as_float(mi[c]) + omb1 * gj;
+        const float vj = o.beta2 * __uint_as_float(vi[c]) + omb2 * (gj * gj);
+        const float xj = __uint_as_float(xi[c]);
+        float u_r, u_c;
+        ratios_fast(o, inv_bc1, inv_bc2, gj, mj, vj, xj, &u_r, &u_c);
+        mo[c] = mj;
+        vo[c] = vj;
+        h.xs[4 * u + c] = xj;
+        h.ur[4 * u + c] = u_r;
+        h.uc[4 * u + c] = u_c;
+      }
+      row_buf(m + t.base, t.valid, u * kLRow, kLRow).store16<kNonTemporal>(as_u32x4(mo[0], mo[1], mo[2], mo[3]), threadIdx.x * 16);
+      row_buf(v + t.base, t.valid, u * kLRow, kLRow).store16<kNonTemporal>(as_u32x4(vo[0], vo[1], vo[2], vo[3]), threadIdx.x * 16);
+    }
+    const uint32_t next = __builtin_amdgcn_readfirstlane(item + gridDim.x);
+    const bool have_next = next < cg.n_items;
+    if (have_next) {
+      lans_issue(g, cg, dec, x, m, v, next, raw);
+      fb_raw = w.first[next];
+    }
+    // the tile's block list: bounds, their positions in the tile, the number of blocks
+    const uint64_t tile_first = (uint64_t)item * kSTile;
+    const uint64_t tile_end = tile_first + t.valid;
+    if (threadIdx.x < 64) {
+      const bool inside = threadIdx.x >= 1 && threadIdx.x <= (uint32_t)kLMaxLocal && my_bound < tile_end;
+      const uint32_t n_inside = (uint32_t)__popcll(__ballot(inside));     // (bounds ascend: these are lanes 1..n_inside)
+      if (threadIdx.x <= (uint32_t)kLMaxLocal) {
+        tb.bound[threadIdx.x] = my_bound;
+        const uint64_t c = my_bound < tile_first ? tile_first : (my_bound > tile_end ? tile_end : my_bound);
+        tb.rel[threadIdx.x] = (uint32_t)(c - tile_first);
+      }
+      if (threadIdx.x == 0) {
+        tb.nloc = n_inside + 1;
+        tb.fb = fb;
+      }
+    }
+    __syncthreads();
+    lans_tile_blocks(o, w, item, cg.n_items, t, h, tb, red, span_limit, g.D, status);
+    __syncthreads();
+    if (threadIdx.x == 0 && tb.deferred) {
+      const uint32_t at = __hip_atomic_fetch_add(w.list, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      w.list[1 + at] = item;
+    }
+    // the older tile: totals of its far-reaching blocks, then its x
+    if (prev != kNone) {
+      TileBlocks &tp = tbs[cur ^ 1];
+      if (!tp.deferred) {
+        if (threadIdx.x < 128) {
+          const int side = (int)(threadIdx.x >> 6);
+          const uint32_t b = __builtin_amdgcn_readfirstlane(tp.far_b[side]);
+          if (b != kNoBlock) {
+            const uint32_t q = tp.far_q[side];
+            float wt[3];
+            lans_wait_block(w.tot + 4ull * b, status, wt);
+            if ((threadIdx.x & 63) == 0) { tp.wts[q][0] = wt[0]; tp.wts[q][1] = wt[1]; tp.wts[q][2] = wt[2]; }
+          }
+        }
+        __syncthreads();
+        lans_write_x_blocks(g, cg, o, x, prev, prev_h, tp);
+      }
+    }
+    prev_h = h;
+    prev = item;
+    cur ^= 1;
+    if (!have_next) break;
+    item = next;
+    __syncthreads();
+  }
+  // the last tile
+  __syncthreads();
+  TileBlocks &tp = tbs[cur ^ 1];
+  if (!tp.deferred) {
+    if (threadIdx.x < 128) {
+      const int side = (int)(threadIdx.x >> 6);
+      const uint32_t b = __builtin_amdgcn_readfirstlane(tp.far_b[side]);
+      if (b != kNoBlock) {
+        const uint32_t q = tp.far_q[side];
+        float wt[3];
+        lans_wait_block(w.tot + 4ull * b, status, wt);
+        if ((threadIdx.x & 63) == 0) { tp.wts[q][0] = wt[0]; tp.wts[q][1] = wt[1]; tp.wts[q][2] = wt[2]; }
+      }
+    }
+    __syncthreads();
+    lans_write_x_blocks(g, cg, o, x, prev, prev_h, tp);
+  }
+}
+
+// x of the deferred tiles, after lans_blocks_kernel: every block's totals are known by now.
+// Workgroup i takes entries i, i + grid, ... of the list.  The moments in memory are the
+// updated ones, so r + wd x and c + wd x come out as in the first kernel; the sums of blocks
+// inside the tile are formed again the same way (same order, same bits), block by block, which
+// needs no table and so handles any number of blocks in a tile.
+template <class DEC>
+__global__ __launch_bounds__(kLThreads) void lans_deferred_kernel(Geo g, ClusterGeo cg, DEC dec, float *x, const float *m,
+                                                                 const float *v, OptArgs o, BlockWs w) {
+  __shared__ __align__(16) float lds[DEC::kLdsFloats];
+  __shared__ double red[(kLThreads / 64) * 3];
+  __shared__ float wts_sh[3];
+  constexpr int kWaves = kLThreads / 64;
+  const uint32_t n_list = __builtin_amdgcn_readfirstlane(w.list[0]);
+  const float inv_bc1 = 1.0f / o.bc1, inv_bc2 = 1.0f / o.bc2;
+  for (uint32_t at = blockIdx.x; at < n_list; at += gridDim.x) {
+    const uint32_t item = __builtin_amdgcn_readfirstlane(w.list[1 + at]);
+    const LansTile t = lans_tile(g, cg, item);
+    LansRaw<DEC> raw;
+    lans_issue(g, cg, dec, x, m, v, item, raw);
+    if constexpr (has_begin_tile<DEC>::value) {
+      dec.begin_tile(t.p, t.tile, lds);
+    } else {
+      __syncthreads();
+      dec.table(raw.hdr, lds);
+      __syncthreads();
+    }
+    LansHeld h;
+#pragma unroll
+    for (int u = 0; u < kLRows; ++u) {
+      const uint32_t mi[4] = {raw.m[u].x, raw.m[u].y, raw.m[u].z, raw.m[u].w};
+      const uint32_t vi[4] = {raw.v[u].x, raw.v[u].y, raw.v[u].z, raw.v[u].w};
+      const uint32_t xi[4] = {raw.x[u].x, raw.x[u].y, raw.x[u].z, raw.x[u].w};
+      float gr[4];
+      dec.decode4(raw.g[u], t.tile * kSTile + u * kLRow + threadIdx.x * 4, raw.hdr, lds, gr);
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const float xj = __uint_as_float(xi[c]);
+        float u_r, u_c;
+        ratios_fast(o, inv_bc1, inv_bc2, gr[c], __uint_as_float(mi[c]), __uint_as_float(vi[c]), xj, &u_r, &u_c);
+        h.xs[4 * u + c] = xj;
+        h.ur[4 * u + c] = u_r;
+        h.uc[4 * u + c] = u_c;
+      }
+    }
+    const uint64_t tile_first = (uint64_t)item * kSTile;
+    const uint64_t tile_end = tile_first + t.valid;
+    float xo[kLPer];
+#pragma unroll
+    for (int e = 0; e < kLPer; ++e) xo[e] = h.xs[e];
+#pragma unroll 1
+    for (uint64_t b = __builtin_amdgcn_readfirstlane(w.first[item]); b < o.n_blocks; ++b) {
+      const uint64_t lo = uniform_off(o.block_offsets[b]), hi = uniform_off(o.block_offsets[b + 1]);
+      if (lo >= tile_end) break;
+      const uint32_t rlo = (uint32_t)((lo > tile_first ? lo : tile_first) - tile_first);
+      const uint32_t rhi = (uint32_t)((hi < tile_end ? hi : tile_end) - tile_first);
+      float phi, w_r, w_c;
+      if (lo < tile_first || hi > tile_end) {
+        phi = __uint_as_float(w.tot[4 * b + 0]);
+        w_r = __uint_as_float(w.tot[4 * b + 1]);
+        w_c = __uint_as_float(w.tot[4 * b + 2]);
+      } else {
+        float f[3];
+        lans_wave_sums(h, rlo, rhi, f);
+        __syncthreads();   // (red and wts_sh of the block before have been read)
+        if ((threadIdx.x & 63) == 0) {
+          red[(threadIdx.x >> 6) * 3 + 0] = (double)f[0];
+          red[(threadIdx.x >> 6) * 3 + 1] = (double)f[1];
+          red[(threadIdx.x >> 6) * 3 + 2] = (double)f[2];
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+          double s0 = 0.0, s1 = 0.0, s2 = 0.0;
+#pragma unroll
+          for (int wv = 0; wv < kWaves; ++wv) {
+            s0 += red[wv * 3 + 0];
+            s1 += red[wv * 3 + 1];
+            s2 += red[wv * 3 + 2];
+          }
+          float wt[3];
+          lans_weights(o, s0, s1, s2, wt);
+          wts_sh[0] = wt[0]; wts_sh[1] = wt[1]; wts_sh[2] = wt[2];
+        }
+        __syncthreads();
+        phi = wts_sh[0]; w_r = wts_sh[1]; w_c = wts_sh[2];
+      }
+#pragma unroll
+      for (int u = 0; u < kLRows; ++u)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          const uint32_t pos = (uint32_t)(u * kLRow) + threadIdx.x * 4 + c;
+          const float dir = phi * (w_r * h.ur[4 * u + c] + w_c * h.uc[4 * u + c]);
+          xo[4 * u + c] = pos >= rlo && pos < rhi ? h.xs[4 * u + c] - o.lr * dir : xo[4 * u + c];
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < kLRows; ++u)
+      row_buf(x + t.base, t.valid, u * kLRow, kLRow).store16<kNonTemporal>(as_u32x4(xo[4 * u], xo[4 * u + 1], xo[4 * u + 2], xo[4 * u + 3]), threadIdx.x * 16);
+    __syncthreads();   // (lds of this tile has been read)
+  }
+}
+
+// LANS with caller-defined blocks in one pass (plus the pass over the deferred tiles).
+// *used = false: shape not supported, nothing enqueued.
+template <class DEC>
+static hipError_t run_lans_blocks(const Geo &g, DEC dec, float *x, float *m, float *v, const OptArgs &o,
+                                  const Workspace &ws, hipStream_t stream, bool *used) {
+  *used = false;
+  if (g.part_elems % kSTile != 0) return hipSuccess;
+  const ClusterGeo cg = make_cluster_geo(g, kSTile);
+  static PerDevice cache;
+  const int capacity = cache.get([] { return cluster_capacity(reinterpret_cast<const void *>(&lans_blocks_kernel<DEC>), kLThreads, 0); });
+  if (capacity <= 0) return hipSuccess;
+  *used = true;
+  const BlockWs w = block_ws(ws.base + ws.lay.norms, o.n_blocks, cg.n_items);
+  hipError_t e = cluster_launch_begin(stream);
+  if (e != hipSuccess) return e;
+  const uint64_t most = 6ull * cg.n_items > 4 * o.n_blocks ? 6ull * cg.n_items : 4 * o.n_blocks;
+  const uint32_t prep_grid = (uint32_t)(cdiv(most, 256) < 4096 ? cdiv(most, 256) : 4096);
+  lans_blocks_prepare_kernel<<<prep_grid, 256, 0, stream>>>(w, o.block_offsets, o.n_blocks, cg.n_items, o.status);
+  const uint32_t grid = cg.n_items > (uint32_t)capacity ? (uint32_t)capacity : cg.n_items;
+  lans_blocks_kernel<DEC><<<grid, kLThreads, 0, stream>>>(g, cg, dec, x, m, v, o, w, grid);
+  const uint32_t sweep_grid = cg.n_items < 1024u ? cg.n_items : 1024u;
+  lans_deferred_kernel<DEC><<<sweep_grid, kLThreads, 0, stream>>>(g, cg, dec, x, m, v, o, w);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  return cluster_launch_end(stream);
+}
+
 // LANS with the partitions as blocks, one pass.  *used = false: shape not supported.
 template <class DEC>
 static hipError_t run_lans_single(const Geo &g, DEC dec, float *x, float *m, float *v, const OptArgs &o,
@@ -741,9 +1296,10 @@ static hipError_t run_update(const Geo &g, DEC dec, float *x, float *m, float *v
     adam_update_kernel<DEC><<<g.n_tiles, kThreads, 0, stream>>>(g, dec, x, m, v, o);
     return hipGetLastError();
   }
-  if (!opt.block_offsets) {
+  {
     bool used = false;
-    hipError_t e1 = run_lans_single(g, dec, x, m, v, o, ws, stream, &used);
+    hipError_t e1 = opt.block_offsets ? run_lans_blocks(g, dec, x, m, v, o, ws, stream, &used)
+                                      : run_lans_single(g, dec, x, m, v, o, ws, stream, &used);
     if (e1 != hipSuccess || used) return e1;
   }
   uint64_t nb = opt.block_offsets ? opt.n_blocks : g.P;

@@ -324,3 +324,36 @@ def test_fp16_conversion_at_the_ends_of_the_half_range(gu, orc):
     assert defined_equal("fp16", pay_gpu, pay_ref, po, orc, D, PE, {})
     assert np.array_equal(res_gpu.view(np.uint32), res_ref.view(np.uint32))
     assert np.array_equal(gu.gpu_decompress(pb, pay_gpu, D).view(np.uint32), orc.decompress(po, pay_ref, D).view(np.uint32))
+
+
+@pytest.mark.parametrize("kind", ["sign", "dither", "topk", "identity"])
+@pytest.mark.parametrize("lr", [1e-3, 0.5])
+def test_lans_blocks_of_every_shape_in_one_call(gu, orc, kind, lr):
+    """Caller-defined LANS blocks (Algorithm 5's layers) that stress every path of the one-pass
+    kernel: ninety small blocks inside one tile of 8192 elements (more than it keeps weights
+    for), blocks of one element, empty blocks, a block that starts exactly on a tile, blocks that
+    start and end inside tiles and span several of them, across partition boundaries, and a
+    block that runs to the ragged end."""
+    import torch
+    bpc = gu.bpc
+    pe = 65536
+    D = 5 * pe + 12345
+    offs = [0] + list(range(100, 9001, 100)) + [9001, 9001, 9002, 8192 * 2, 8192 * 2 + 1, 8192 * 4 + 77,
+                                                pe + 8192 * 3, pe + 8192 * 3, 3 * pe - 5, 3 * pe + 8192, 5 * pe + 7, D]
+    blocks = np.array(offs, dtype=np.uint64)
+    assert np.all(np.diff(blocks.astype(np.int64)) >= 0)
+    po, pb = gu.both_params(orc, kind, pe, **KW[kind])
+    rs = np.random.default_rng(77)
+    payload = orc.compress(po, (rs.standard_t(3.0, D) * 1e-2).astype(np.float32), None)
+    x0 = (rs.standard_normal(D) * 0.02).astype(np.float32)
+    m0 = (rs.standard_normal(D) * 1e-3).astype(np.float32)
+    v0 = (rs.random(D) * 1e-5).astype(np.float32)
+    oo = orc.make_opt(orc.OPT_LANS, lr, 0.9, 0.999, 1e-8, 0.01, 4, block_offsets=blocks)
+    ob = bpc.make_opt(bpc.OPT_LANS, lr, 0.9, 0.999, 1e-8, 0.01, 4,
+                      block_offsets=torch.from_numpy(blocks.astype(np.int64)).to(gu.DEV))
+    x, m, v = x0.copy(), m0.copy(), v0.copy()
+    orc.adaptive_update(po, payload, D, x, m, v, oo)
+    xg, mg, vg = gu.gpu_update(pb, payload, x0, m0, v0, ob)
+    assert np.array_equal(mg.view(np.uint32), m.view(np.uint32))
+    assert np.array_equal(vg.view(np.uint32), v.view(np.uint32))
+    assert gu.lans_step_close(xg, x, x0, blocks)
