@@ -102,6 +102,15 @@ class Pipeline:
         self.blocks = torch.from_numpy(blocks.astype("int64")).to(dev)
         self.ws = torch.empty(max(bpc.workspace_bytes(p0, self.D, self.n),
                                   bpc.update_workspace_bytes(p0, self.D, len(blocks) - 1)), dtype=torch.uint8, device=dev)
+        # Workers whose call does not fill the device (the sparse kinds: the selection pass of
+        # top-k runs on one workgroup per partition) take turns on two streams, each with a
+        # workspace of its own, so that one worker's selection overlaps the next one's streaming
+        # pass; the server call joins them.  (The single-pass kernels of the other kinds fill the
+        # device and are kept apart by the library anyway.)
+        self.side = []
+        if w["kind"] in ("topk", "topk16", "randk") and self.n > 1:
+            self.side = [torch.cuda.Stream(), torch.cuda.Stream()]
+            self.ws_side = [torch.empty_like(self.ws) for _ in self.side]
         self.x = synth.device_params(self.D, device=dev)
         self.m = torch.zeros(self.D, dtype=torch.float32, device=dev)
         self.v = torch.zeros(self.D, dtype=torch.float32, device=dev)
@@ -110,8 +119,25 @@ class Pipeline:
     def params(self, role, worker):
         return self.bpc.make_params(self.kind, self.pe, stream_id=(self.t << 32) | (role << 16) | worker, **self.kw)
 
-    def stage_w(self, i):
-        self.bpc.bpc_compress(self.params(0, i), self.grads[i], self.res[i], self.pay[i], self.ws)
+    def stage_w(self, i, ws=None):
+        self.bpc.bpc_compress(self.params(0, i), self.grads[i], self.res[i], self.pay[i], self.ws if ws is None else ws)
+
+    def workers(self):
+        """All n worker calls of a step: one after the other, or alternating over two streams."""
+        if not self.side:
+            for i in range(self.n):
+                self.stage_w(i)
+            return
+        torch = self.torch
+        main = torch.cuda.current_stream()
+        for s in self.side:
+            s.wait_stream(main)
+        for i in range(self.n):
+            k = i % len(self.side)
+            with torch.cuda.stream(self.side[k]):
+                self.stage_w(i, ws=self.ws_side[k])
+        for s in self.side:
+            main.wait_stream(s)
 
     def stage_s(self):
         ins = [self.params(0, i) for i in range(self.n)]
@@ -138,15 +164,15 @@ class Pipeline:
 
     def step(self):
         self.t += 1
-        for i in range(self.n):
-            self.stage_w(i)
+        self.workers()
         self.stage_s()
         self.stage_u()
 
     def check(self, where):
         """Waits for the stream; raises if a device-side wait of the last call gave up."""
         try:
-            self.bpc.workspace_check(self.params(0, 0), self.D, self.ws)
+            for ws in [self.ws] + (self.ws_side if self.side else []):
+                self.bpc.workspace_check(self.params(0, 0), self.D, ws)
         except self.bpc.BpcError as err:
             raise SystemExit(f"bench.py: {self.name}, {where}: {err}")
 
@@ -200,6 +226,7 @@ def run_workload(name, w, steps, warmup, torch, bpc, synth):
                        "algorithmic_GBps": round(D * a / ms / 1e6, 1),
                        "frac_of_hbm_peak": round(D * a / ms / 1e6 / HBM_PEAK_GBPS, 4)}
     out = {"workload": name, "D": D, "dtype": w["dtype"], "compressor": w["kind"], "n_workers": n,
+           "worker_streams": max(1, len(pipe.side)),
            "ms_per_step": round(ms_step, 4), "value_GBps": round(n * D * G / ms_step / 1e6, 1),
            "pipeline_GBps_one_worker": round(D * G / (ms_w + ms_s + ms_u) / 1e6, 1), "stages": stages}
     if D <= (1 << 25):
