@@ -222,3 +222,68 @@ def decode_partition(p: Params, part_no: int, rec: np.ndarray, d: int) -> np.nda
     out = np.zeros(d, dtype=np.float32)
     lib().orc_decode_partition(C.byref(p), part_no, _ptr(rec), d, _ptr(out))
     return out
+
+
+# ---------------------------------------------------------------------------------------------
+# The size threshold of Section 4.2: tensors under a threshold are not compressed.  Here the
+# unit is the partition: `mask[p]` non-zero means partition p is carried as it is (an IDENTITY
+# record, residual 0), the others go through the compressor.  Written partition by partition,
+# each through the plain functions above, so the records simply follow each other.
+def _part_params(p: Params, part: int, bypassed: bool) -> Params:
+    q = Params()
+    C.memmove(C.byref(q), C.byref(p), C.sizeof(Params))
+    q.first_partition = p.first_partition + part
+    if bypassed:
+        q.kind = IDENTITY
+    if p.norm_override:
+        q.norm_override = p.norm_override + 4 * part
+        q._keep = getattr(p, "_keep", None)
+    return q
+
+
+def _parts(p: Params, D: int):
+    pe = int(p.part_elems)
+    return [(k, k * pe, min(D, (k + 1) * pe)) for k in range((D + pe - 1) // pe)]
+
+
+def record_sizes_bypass(p: Params, mask, D: int):
+    """Bytes of every partition's record: the kind's stride, or that of an IDENTITY record of
+    part_elems elements for a bypassed partition (records follow each other directly)."""
+    ident = _part_params(p, 0, True)
+    return [partition_stride(ident) if mask[k] else partition_stride(p) for k, _, _ in _parts(p, D)]
+
+
+def compress_bypass(p: Params, mask, grad: np.ndarray, residual) -> np.ndarray:
+    recs = []
+    for k, lo, hi in _parts(p, grad.size):
+        res = None if residual is None else residual[lo:hi]
+        recs.append(compress(_part_params(p, k, bool(mask[k])), grad[lo:hi], res))
+    return np.concatenate(recs) if recs else np.zeros(0, np.uint8)
+
+
+def decompress_bypass(p: Params, mask, payload: np.ndarray, D: int) -> np.ndarray:
+    out = np.zeros(D, dtype=np.float32)
+    offs = np.concatenate([[0], np.cumsum(record_sizes_bypass(p, mask, D))]).astype(np.int64)
+    for k, lo, hi in _parts(p, D):
+        out[lo:hi] = decompress(_part_params(p, k, bool(mask[k])), payload[offs[k]:offs[k + 1]], hi - lo)
+    return out
+
+
+def server_aggregate_bypass(in_params, payloads, out_params: Params, mask, server_residual, D: int) -> np.ndarray:
+    offs = np.concatenate([[0], np.cumsum(record_sizes_bypass(out_params, mask, D))]).astype(np.int64)
+    recs = []
+    for k, lo, hi in _parts(out_params, D):
+        ins = [_part_params(q, k, bool(mask[k])) for q in in_params]
+        res = None if server_residual is None else server_residual[lo:hi]
+        recs.append(server_aggregate(ins, [np.ascontiguousarray(pl[offs[k]:offs[k + 1]]) for pl in payloads],
+                                     _part_params(out_params, k, bool(mask[k])), res, hi - lo))
+    return np.concatenate(recs) if recs else np.zeros(0, np.uint8)
+
+
+def adaptive_update_bypass(p: Params, mask, payload: np.ndarray, D: int, param, m, v, opt: Opt) -> None:
+    """Blocks of the update are the partitions (no caller-defined blocks here)."""
+    assert not opt.block_offsets
+    offs = np.concatenate([[0], np.cumsum(record_sizes_bypass(p, mask, D))]).astype(np.int64)
+    for k, lo, hi in _parts(p, D):
+        adaptive_update(_part_params(p, k, bool(mask[k])), np.ascontiguousarray(payload[offs[k]:offs[k + 1]]), hi - lo,
+                        param[lo:hi], m[lo:hi], v[lo:hi], opt)

@@ -27,7 +27,7 @@ MAX_WORKERS = 64
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-ffp-contract=off",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-fPIC", "-shared"]
 
-EXPORTS = ["bpc_partition_k", "bpc_partition_stride", "bpc_payload_bytes", "bpc_workspace_bytes",
+EXPORTS = ["bpc_partition_k", "bpc_partition_stride", "bpc_payload_bytes", "bpc_partition_offset", "bpc_workspace_bytes",
            "bpc_update_workspace_bytes", "bpc_workspace_status_offset", "bpc_workspace_check", "bpc_compress", "bpc_compress_static_ws", "bpc_decompress", "bpc_server_aggregate", "bpc_adaptive_update",
            "bpc_stream_probe", "bpc_status_string", "bpc_last_hip_error"]
 
@@ -58,7 +58,8 @@ class BpcError(RuntimeError):
 class Params(C.Structure):
     _fields_ = [("kind", C.c_int32), ("norm", C.c_int32), ("part_elems", C.c_uint64),
                 ("k_ratio", C.c_double), ("levels", C.c_uint32), ("value_scale", C.c_float),
-                ("seed", C.c_uint64), ("stream_id", C.c_uint64), ("norm_override", C.c_void_p)]
+                ("seed", C.c_uint64), ("stream_id", C.c_uint64), ("norm_override", C.c_void_p),
+                ("bypass", C.c_void_p)]
 
 
 class Opt(C.Structure):
@@ -86,6 +87,8 @@ def lib():
         L.bpc_partition_stride.restype = C.c_size_t
         L.bpc_payload_bytes.argtypes = [PP, C.c_uint64]
         L.bpc_payload_bytes.restype = C.c_size_t
+        L.bpc_partition_offset.argtypes = [PP, C.c_uint64, C.c_uint64]
+        L.bpc_partition_offset.restype = C.c_size_t
         L.bpc_workspace_bytes.argtypes = [PP, C.c_uint64, C.c_int]
         L.bpc_workspace_bytes.restype = C.c_size_t
         L.bpc_workspace_status_offset.argtypes = [PP, C.c_uint64]
@@ -118,8 +121,10 @@ def lib():
 
 
 def make_params(kind, part_elems, k_ratio=0.01, levels=4, norm=NORM_L2, value_scale=1.0, seed=0,
-                stream_id=0, norm_override=None) -> Params:
-    """``norm_override``: float32 GPU tensor with one value per partition, or None."""
+                stream_id=0, norm_override=None, bypass=None) -> Params:
+    """``norm_override``: float32 GPU tensor with one value per partition, or None.
+    ``bypass``: numpy uint8 array (host) with one byte per partition, or None: partitions whose
+    byte is non-zero are carried uncompressed."""
     p = Params()
     p.kind, p.norm, p.part_elems, p.k_ratio = int(kind), int(norm), int(part_elems), float(k_ratio)
     p.levels, p.value_scale, p.seed, p.stream_id = int(levels), float(value_scale), int(seed), int(stream_id)
@@ -128,6 +133,14 @@ def make_params(kind, part_elems, k_ratio=0.01, levels=4, norm=NORM_L2, value_sc
         p.norm_override = norm_override.data_ptr()
     else:
         p.norm_override = None
+    if bypass is not None:
+        import numpy as np
+
+        mask = np.ascontiguousarray(bypass, dtype=np.uint8)
+        p._keep_mask = mask
+        p.bypass = mask.ctypes.data
+    else:
+        p.bypass = None
     return p
 
 
@@ -177,6 +190,10 @@ def partition_k(p: Params, d: int) -> int:
 
 def partition_stride(p: Params) -> int:
     return int(lib().bpc_partition_stride(C.byref(p)))
+
+
+def partition_offset(p: Params, D: int, part: int) -> int:
+    return int(lib().bpc_partition_offset(C.byref(p), D, part))
 
 
 def payload_bytes(p: Params, D: int) -> int:

@@ -45,6 +45,69 @@ static hipError_t static_workspace(uint8_t **ptr) {
   return hipSuccess;
 }
 
+// A call whose params carry a bypass mask (Section 4.2: tensors under a size threshold are not
+// compressed) is carried out run by run: a run is a maximal stretch of partitions of one class,
+// compressed by the params' kind or carried as they are (identity records).  Without a mask
+// the whole gradient is one run.
+struct Run {
+  uint32_t p0, n_parts;   // partitions [p0, p0 + n_parts)
+  bool bypass;
+  uint64_t elem0, elems;  // their elements [elem0, elem0 + elems)
+  size_t pay_off;         // byte offset of record p0 in a payload
+};
+struct Runs {
+  int n;
+  Run r[kMaxRuns];
+  size_t payload_bytes;
+};
+static size_t identity_stride(uint64_t part_elems) { return kHeaderBytes + 4 * ru4(part_elems); }
+// false: more runs than a call accepts.
+static bool make_runs(const bpc_params_t *prm, uint64_t D, Runs *out) {
+  const uint64_t P = cdiv(D, prm->part_elems);
+  out->n = 0;
+  size_t off = 0;
+  for (uint64_t p = 0; p < P;) {
+    const bool by = prm->bypass && prm->bypass[p] != 0;
+    uint64_t q = p + 1;
+    while (q < P && (prm->bypass && prm->bypass[q] != 0) == by) ++q;
+    if (out->n == kMaxRuns) return false;
+    Run &r = out->r[out->n++];
+    r.p0 = (uint32_t)p;
+    r.n_parts = (uint32_t)(q - p);
+    r.bypass = by;
+    r.elem0 = p * prm->part_elems;
+    r.elems = (q * prm->part_elems < D ? q * prm->part_elems : D) - r.elem0;
+    r.pay_off = off;
+    off += (size_t)(q - p) * (by ? identity_stride(prm->part_elems) : stride_of(prm));
+    p = q;
+  }
+  out->payload_bytes = off;
+  return true;
+}
+// The params of one run as a call of its own.
+static bpc_params_t run_params(const bpc_params_t *prm, const Run &r) {
+  bpc_params_t s = *prm;
+  s.bypass = nullptr;
+  if (r.bypass) s.kind = BPC_IDENTITY;
+  if (s.norm_override) s.norm_override += r.p0;
+  return s;
+}
+static Geo run_geo(const bpc_params_t &sub, const Run &r) {
+  Geo g = make_geo(&sub, r.elems);
+  g.part0 = r.p0;
+  return g;
+}
+
+// Every run's own workspace layout fits in ws_bytes (they all do when ws_bytes covers the layout
+// of the whole call, which is what the entry points ask for; checked all the same).
+static bool runs_fit(const bpc_params_t *prm, const Runs &runs, size_t ws_bytes) {
+  for (int k = 0; k < runs.n; ++k) {
+    const bpc_params_t sub = run_params(prm, runs.r[k]);
+    if (ws_layout(&sub, runs.r[k].elems).total > ws_bytes) return false;
+  }
+  return true;
+}
+
 extern "C" {
 
 uint64_t bpc_partition_k(const bpc_params_t *params, uint64_t d) {
@@ -60,7 +123,21 @@ size_t bpc_partition_stride(const bpc_params_t *params) {
 
 size_t bpc_payload_bytes(const bpc_params_t *params, uint64_t D) {
   if (!params_valid(params) || D == 0) return 0;
-  return (size_t)cdiv(D, params->part_elems) * stride_of(params);
+  Runs runs;
+  if (!make_runs(params, D, &runs)) return 0;
+  return runs.payload_bytes;
+}
+
+size_t bpc_partition_offset(const bpc_params_t *params, uint64_t D, uint64_t p) {
+  if (!params_valid(params) || p >= cdiv(D, params->part_elems)) return (size_t)-1;
+  Runs runs;
+  if (!make_runs(params, D, &runs)) return (size_t)-1;
+  for (int k = 0; k < runs.n; ++k) {
+    const Run &r = runs.r[k];
+    if (p < (uint64_t)r.p0 + r.n_parts)
+      return r.pay_off + (size_t)(p - r.p0) * (r.bypass ? identity_stride(params->part_elems) : stride_of(params));
+  }
+  return (size_t)-1;
 }
 
 size_t bpc_workspace_bytes(const bpc_params_t *params, uint64_t D, int n) {
@@ -105,13 +182,19 @@ bpc_status_t bpc_workspace_check(const bpc_params_t *params, uint64_t D, const v
     if (e0 != hipSuccess) return hip_status(e0);
     ws = st;
   }
+  Runs runs;
+  runs.n = 1;
+  if (D != 0 && !make_runs(params, D, &runs)) return BPC_ERR_UNSUPPORTED;
   hipError_t e = hipStreamSynchronize((hipStream_t)hip_stream);
   if (e != hipSuccess) return hip_status(e);
   if (D == 0) return BPC_OK;
-  uint32_t word = 0;
-  e = hipMemcpy(&word, (const uint8_t *)ws + ws_layout(params, D).status, sizeof(word), hipMemcpyDeviceToHost);
+  // one slot of four words per run; word 0 of a slot is the run's flag
+  uint32_t words[4 * kMaxRuns];
+  e = hipMemcpy(words, (const uint8_t *)ws + ws_layout(params, D).status, 16 * (size_t)runs.n, hipMemcpyDeviceToHost);
   if (e != hipSuccess) return hip_status(e);
-  return word == 0 ? BPC_OK : BPC_ERR_WAIT;
+  for (int k = 0; k < runs.n; ++k)
+    if (words[4 * k] != 0) return BPC_ERR_WAIT;
+  return BPC_OK;
 }
 
 static bpc_status_t check_size(const bpc_params_t *p, uint64_t D) {
@@ -147,13 +230,23 @@ bpc_status_t bpc_compress(const bpc_params_t *params, const void *grad, bpc_dtyp
     return BPC_ERR_ALIGNMENT;
   WsLayout lay = ws_layout(params, D);
   if (!ws || ws_bytes < lay.total) return BPC_ERR_WORKSPACE;
-  Geo g = make_geo(params, D);
-  Source src{};
-  src.grad = grad;
-  src.dtype = (int)dtype;
-  src.residual = residual;
-  Workspace w{(uint8_t *)ws, lay};
-  return hip_status(encode(g, *params, nullptr, src, (uint8_t *)payload, w, (hipStream_t)hip_stream));
+  Runs runs;
+  if (!make_runs(params, D, &runs)) return BPC_ERR_UNSUPPORTED;
+  if (!runs_fit(params, runs, ws_bytes)) return BPC_ERR_WORKSPACE;
+  const size_t gbytes = dtype == BPC_F16 ? 2 : 4;
+  for (int k = 0; k < runs.n; ++k) {
+    const Run &r = runs.r[k];
+    const bpc_params_t sub = run_params(params, r);
+    const WsLayout sub_lay = ws_layout(&sub, r.elems);
+    Source src{};
+    src.grad = (const uint8_t *)grad + r.elem0 * gbytes;
+    src.dtype = (int)dtype;
+    src.residual = residual ? residual + r.elem0 : nullptr;
+    Workspace w{(uint8_t *)ws, sub_lay, (uint32_t)k};
+    const hipError_t e = encode(run_geo(sub, r), sub, nullptr, src, (uint8_t *)payload + r.pay_off, w, (hipStream_t)hip_stream);
+    if (e != hipSuccess) return hip_status(e);
+  }
+  return BPC_OK;
 }
 
 bpc_status_t bpc_compress_static_ws(const bpc_params_t *params, const void *grad, bpc_dtype_t dtype, float *residual,
@@ -181,8 +274,16 @@ bpc_status_t bpc_decompress(const bpc_params_t *params, const void *payload, uin
   if (!payload || !out) return BPC_ERR_INVALID_ARG;
   if (check_size(params, D) != BPC_OK) return BPC_ERR_UNSUPPORTED;
   if (!aligned16(payload) || !aligned16(out)) return BPC_ERR_ALIGNMENT;
-  Geo g = make_geo(params, D);
-  return hip_status(decode_dense(g, *params, (const uint8_t *)payload, out, (hipStream_t)hip_stream));
+  Runs runs;
+  if (!make_runs(params, D, &runs)) return BPC_ERR_UNSUPPORTED;
+  for (int k = 0; k < runs.n; ++k) {
+    const Run &r = runs.r[k];
+    const bpc_params_t sub = run_params(params, r);
+    const hipError_t e = decode_dense(run_geo(sub, r), sub, (const uint8_t *)payload + r.pay_off, out + r.elem0,
+                                      (hipStream_t)hip_stream);
+    if (e != hipSuccess) return hip_status(e);
+  }
+  return BPC_OK;
 }
 
 bpc_status_t bpc_server_aggregate(const bpc_params_t *in, const void *const *payloads, int n,
@@ -208,19 +309,37 @@ bpc_status_t bpc_server_aggregate(const bpc_params_t *in, const void *const *pay
     if (!aligned16(payloads[i])) return BPC_ERR_ALIGNMENT;
   WsLayout lay = ws_layout(out, D);
   if (!ws || ws_bytes < lay.total) return BPC_ERR_WORKSPACE;
-  Geo g = make_geo(out, D);
-  Source src{};
-  src.grad = nullptr;
-  src.residual = server_residual;
-  src.msgs.n = n;
-  src.msgs.inv_n = 1.0f / (float)n;
+  Runs runs;
+  if (!make_runs(out, D, &runs)) return BPC_ERR_UNSUPPORTED;
+  if (!runs_fit(out, runs, ws_bytes)) return BPC_ERR_WORKSPACE;
+  // the workers' messages have the layout of the outgoing one: the same partitions bypass
+  const uint64_t P = cdiv(D, out->part_elems);
   for (int i = 0; i < n; ++i) {
-    src.msgs.ptr[i] = (const uint8_t *)payloads[i];
-    src.msgs.seed[i] = in[i].seed;
-    src.msgs.stream_id[i] = in[i].stream_id;
+    if ((in[i].bypass != nullptr) != (out->bypass != nullptr)) return BPC_ERR_INVALID_ARG;
+    if (out->bypass && in[i].bypass != out->bypass)
+      for (uint64_t p = 0; p < P; ++p)
+        if ((in[i].bypass[p] != 0) != (out->bypass[p] != 0)) return BPC_ERR_INVALID_ARG;
   }
-  Workspace w{(uint8_t *)ws, lay};
-  return hip_status(encode(g, *out, in, src, (uint8_t *)out_payload, w, (hipStream_t)hip_stream));
+  for (int k = 0; k < runs.n; ++k) {
+    const Run &r = runs.r[k];
+    const bpc_params_t sub = run_params(out, r);
+    bpc_params_t sub_in[kMaxWorkers];
+    Source src{};
+    src.grad = nullptr;
+    src.residual = server_residual ? server_residual + r.elem0 : nullptr;
+    src.msgs.n = n;
+    src.msgs.inv_n = 1.0f / (float)n;
+    for (int i = 0; i < n; ++i) {
+      sub_in[i] = run_params(&in[i], r);
+      src.msgs.ptr[i] = (const uint8_t *)payloads[i] + r.pay_off;
+      src.msgs.seed[i] = in[i].seed;
+      src.msgs.stream_id[i] = in[i].stream_id;
+    }
+    Workspace w{(uint8_t *)ws, ws_layout(&sub, r.elems), (uint32_t)k};
+    const hipError_t e = encode(run_geo(sub, r), sub, sub_in, src, (uint8_t *)out_payload + r.pay_off, w, (hipStream_t)hip_stream);
+    if (e != hipSuccess) return hip_status(e);
+  }
+  return BPC_OK;
 }
 
 bpc_status_t bpc_adaptive_update(const bpc_params_t *params, const void *payload, uint64_t D, float *param,
@@ -242,10 +361,20 @@ bpc_status_t bpc_adaptive_update(const bpc_params_t *params, const void *payload
   WsLayout lay = ws_layout(params, D);
   const size_t need = update_ws_bytes(lay, opt->kind == BPC_OPT_LANS && opt->block_offsets, opt->n_blocks, D);
   if (!ws || ws_bytes < need) return BPC_ERR_WORKSPACE;
-  Geo g = make_geo(params, D);
-  Workspace w{(uint8_t *)ws, lay};
-  return hip_status(adaptive_update(g, *params, (const uint8_t *)payload, param, m, v, *opt, w,
-                                    (hipStream_t)hip_stream));
+  Runs runs;
+  if (!make_runs(params, D, &runs)) return BPC_ERR_UNSUPPORTED;
+  // (caller-defined LANS blocks may reach from one run into the next: not built)
+  if (runs.n > 1 && opt->kind == BPC_OPT_LANS && opt->block_offsets) return BPC_ERR_UNSUPPORTED;
+  if (!runs_fit(params, runs, ws_bytes)) return BPC_ERR_WORKSPACE;
+  for (int k = 0; k < runs.n; ++k) {
+    const Run &r = runs.r[k];
+    const bpc_params_t sub = run_params(params, r);
+    Workspace w{(uint8_t *)ws, ws_layout(&sub, r.elems), (uint32_t)k};
+    const hipError_t e = adaptive_update(run_geo(sub, r), sub, (const uint8_t *)payload + r.pay_off, param + r.elem0, m + r.elem0,
+                                         v + r.elem0, *opt, w, (hipStream_t)hip_stream);
+    if (e != hipSuccess) return hip_status(e);
+  }
+  return BPC_OK;
 }
 
 bpc_status_t bpc_stream_probe(bpc_probe_t mix, const void *a, const void *b, void *c, uint64_t n, void *hip_stream) {

@@ -57,7 +57,7 @@ hipError_t fp16_encode(const Geo &g, const bpc_params_t &, const Source &src, ui
                        hipStream_t stream) {
   auto make_server = [&] { return Fp16MsgSource{src.msgs, src.residual, g.stride}; };
   return with_source(src, make_server, [&](auto s) -> hipError_t {
-    fp16_encode_kernel<decltype(s)><<<g.n_tiles, kThreads, 0, stream>>>(g, s, payload, src.residual, ws.at<uint32_t>(ws.lay.status));
+    fp16_encode_kernel<decltype(s)><<<g.n_tiles, kThreads, 0, stream>>>(g, s, payload, src.residual, ws.status());
     return hipGetLastError();
   });
 }

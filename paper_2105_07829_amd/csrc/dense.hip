@@ -51,7 +51,7 @@ hipError_t identity_encode(const Geo &g, const bpc_params_t &, const Source &src
                            const Workspace &ws, hipStream_t stream) {
   auto make_server = [&] { return IdentityMsgSource{src.msgs, src.residual, g.stride}; };
   return with_source(src, make_server, [&](auto s) -> hipError_t {
-    identity_encode_kernel<decltype(s)><<<g.n_tiles, kThreads, 0, stream>>>(g, s, payload, src.residual, ws.at<uint32_t>(ws.lay.status));
+    identity_encode_kernel<decltype(s)><<<g.n_tiles, kThreads, 0, stream>>>(g, s, payload, src.residual, ws.status());
     return hipGetLastError();
   });
 }
@@ -176,7 +176,7 @@ __global__ __launch_bounds__(kThreads) void decode_randk_kernel(Geo g, const uin
   const float *val = reinterpret_cast<const float *>(rec + kHeaderBytes);
   const float scale = value_scale >= 0.0f ? value_scale : (float)d / (float)k;
   const uint64_t base = g.part_base(p);
-  const Philox rng(seed, stream_id, p);
+  const Philox rng(seed, stream_id, p + g.part0);
   for (uint32_t t = blockIdx.x * kThreads + threadIdx.x; t < k; t += gridDim.x * kThreads) {
     uint32_t j = (uint32_t)(((uint64_t)rng.word(t) * d) >> 32);
     atomicAdd(out + base + j, scale * val[t]);
@@ -195,7 +195,7 @@ __global__ __launch_bounds__(kThreads) void decode_randk_shared_kernel(Geo g, Wo
   k = k > g.k_cap ? g.k_cap : k;
   const float scale = value_scale >= 0.0f ? value_scale : (float)d / (float)k;
   const uint64_t base = g.part_base(p);
-  const Philox rng(seed, stream_id, p);
+  const Philox rng(seed, stream_id, p + g.part0);
   for (uint32_t t = blockIdx.x * kThreads + threadIdx.x; t < k; t += gridDim.x * kThreads) {
     float s = 0.0f;
     for (int i = 0; i < msgs.n; ++i)

@@ -182,7 +182,7 @@ hipError_t dither_encode(const Geo &g_in, const bpc_params_t &prm_in, const Sour
   Geo g = g_in;
   Source src = src_in;
   bpc_params_t prm = prm_in;
-  uint32_t *status = ws.at<uint32_t>(ws.lay.status);
+  uint32_t *status = ws.status();
   // (the single-pass server handles up to 15 levels; beyond that it declines and the server
   // side takes the passes below)
   const bool wide = prm_in.kind == BPC_DITHER && dither_planes(prm_in.levels) > 0;

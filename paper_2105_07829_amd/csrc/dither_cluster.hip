@@ -135,7 +135,7 @@ struct DitherWorkerOp {
     const float nu = ctx.nu, top_over_nu = ctx.top_over_nu, top = dither_top(levels, NAT);
     const float *mag = ctx.mag;
     const uint32_t p = part_of(item);
-    const Philox rng(seed, stream_id, p);
+    const Philox rng(seed, stream_id, p + g.part0);
     const uint64_t b = base(item);
     uint32_t *nibs = reinterpret_cast<uint32_t *>(payload + (uint64_t)p * g.stride + kHeaderBytes);
     const uint32_t off = (u * kDWThreads + threadIdx.x) * 8;  // within the tile
@@ -210,7 +210,7 @@ hipError_t dither_worker_single_pass(const Geo &g, const bpc_params_t &prm, cons
                                      const Workspace &ws, hipStream_t stream, bool *used) {
   ClusterGeo cg = make_cluster_geo(g, kDWTile);
   double *slots = ws.at<double>(ws.lay.slots);
-  uint32_t *status = ws.at<uint32_t>(ws.lay.status);
+  uint32_t *status = ws.status();
   const bool f16 = src.dtype == BPC_F16;
   if (src.residual)
     return f16 ? launch_dither<__half, true>(g, cg, prm, src, payload, slots, status, stream, used)

@@ -266,7 +266,7 @@ struct DitherServerOp {
   template <int MODE>
   __device__ void row2_body(uint32_t item, int u, Held &h, const Ctx &ctx) const {
     const uint32_t p = part_of(item);
-    const Philox rng(seed, stream_id, p);
+    const Philox rng(seed, stream_id, p + g.part0);
     const uint32_t j0 = tile_off(item) + (u * kThreads + threadIdx.x) * 8;
     float r[8];
     uint32_t hi = 0;
@@ -320,7 +320,7 @@ hipError_t dither_server_single_pass(const Geo &g, const bpc_params_t &prm, cons
                                      const Workspace &ws, hipStream_t stream, bool *used) {
   ClusterGeo cg = make_cluster_geo(g, kSTile);
   double *slots = ws.at<double>(ws.lay.slots);
-  uint32_t *status = ws.at<uint32_t>(ws.lay.status);
+  uint32_t *status = ws.status();
   const bool linf = prm.norm == BPC_NORM_LINF, nat = prm.kind == BPC_NATDITHER;
   const uint32_t planes = nat ? 0u : dither_planes(prm.levels);
   if (planes > 1) {   // 6 and 7 bits: the multi-pass kernels

@@ -21,6 +21,7 @@ constexpr int kSThreads = 256;       // workgroup size of the server-side kernel
 constexpr int kWTile = 16384;        // tile of the worker-side single-pass kernels (1024 threads x 16 elements)
 constexpr int kSTile = 8192;         // tile of the server-side single-pass kernels and of single-pass LANS
 constexpr uint32_t kHeaderBytes = 16;
+constexpr int kMaxRuns = 64;         // most runs of partitions of one class (compressed / carried as they are) a call accepts
 constexpr uint32_t kTopkListCap = 32768;  // entries of a partition's top-k short list
 constexpr uint32_t kTopkHistWords = 2048 + 1024 + 1024;  // top-k radix histograms of a partition
 
@@ -113,6 +114,9 @@ inline Geo make_geo(const bpc_params_t *p, uint64_t D) {
 // Device workspace of one call.  Offsets in bytes from the workspace base, each
 // a multiple of 256.  Regions a kind does not use have size 0.
 struct WsLayout {
+  size_t status;     // u32[4 * kMaxRuns], at offset 0 whatever the shape: one slot of four words for every run of
+                     // partitions a call is split into (one run unless partitions bypass compression).  Word 0 of a
+                     // slot is non-zero if a single-pass kernel of that run gave up waiting, word 1 is its ticket counter
   size_t partials;   // double[n_tiles]: per-tile partial norms
   size_t dense;      // float[D]: q / Delta / decoded message when no caller buffer can hold it
   size_t hist;       // u32[P*kTopkHistWords]: top-k radix histograms (2048 + 1024 + 1024 bins)
@@ -125,7 +129,6 @@ struct WsLayout {
   size_t tilecnt;    // u32[2*n_tiles]: per-tile (greater, equal) counts, then offsets
   size_t slots;      // double[3 * tiles of kSTile]: partition-wide reductions of the single-pass kernels
                      // (one per tile; three for the LANS block norms)
-  size_t status;     // u32[64]: word 0 is non-zero if a single-pass kernel gave up waiting, word 1 is its ticket counter
   size_t norms;      // double[3*P]: LANS block norms when blocks are the partitions
   size_t total;
 };
@@ -138,6 +141,7 @@ inline WsLayout ws_layout(const bpc_params_t *p, uint64_t D) {
   // kinds whose update reads a dense decode of the message from the workspace
   const bool topk = p->kind == BPC_TOPK || p->kind == BPC_TOPK16;
   bool sparse = topk || p->kind == BPC_RANDK || (p->kind == BPC_DITHER && dither_planes(p->levels) > 0);
+  w.status = take(16 * kMaxRuns);
   w.partials = take(sizeof(double) * (size_t)g.n_tiles);
   w.dense = take(sparse ? sizeof(float) * (size_t)D : 0);
   w.hist = take(topk ? sizeof(uint32_t) * kTopkHistWords * (size_t)g.P : 0);
@@ -148,7 +152,6 @@ inline WsLayout ws_layout(const bpc_params_t *p, uint64_t D) {
   w.cand = take(topk ? 8 * (size_t)kTopkListCap * (size_t)g.P : 0);
   w.tilecnt = take(topk ? sizeof(uint32_t) * 2 * (size_t)g.n_tiles : 0);
   w.slots = take(sizeof(double) * 3 * ((size_t)g.P * cdiv(g.part_elems, kSTile)));
-  w.status = take(256);
   w.norms = take(sizeof(double) * 3 * (size_t)g.P);
   w.total = off;
   return w;

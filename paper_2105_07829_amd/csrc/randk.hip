@@ -71,7 +71,7 @@ __global__ __launch_bounds__(kRsThreads) void randk_sum_kernel(Geo g, WorkerMsgs
     k = k > g.k_cap ? g.k_cap : k;
     const float *val = reinterpret_cast<const float *>(rec + kHeaderBytes);
     const float scale = sc.value_scale[i] >= 0.0f ? sc.value_scale[i] : (float)d / (float)k;
-    const Philox rng(msgs.seed[i], msgs.stream_id[i], p);
+    const Philox rng(msgs.seed[i], msgs.stream_id[i], p + g.part0);
     for (uint32_t t4 = threadIdx.x; 4 * t4 < k; t4 += kRsThreads) {
       uint32_t rnd[4];
       rng.block(t4, rnd);
@@ -131,7 +131,7 @@ __global__ __launch_bounds__(kRbThreads) void randk_bin_kernel(Geo g, WorkerMsgs
   k = k > g.k_cap ? g.k_cap : k;
   const float *val = reinterpret_cast<const float *>(rec + kHeaderBytes);
   const float scale = sc.value_scale[i] >= 0.0f ? sc.value_scale[i] : (float)d / (float)k;
-  const Philox rng(msgs.seed[i], msgs.stream_id[i], p);
+  const Philox rng(msgs.seed[i], msgs.stream_id[i], p + g.part0);
   constexpr int kMine = kRbMaxBins / kRbThreads;   // bins a thread owns: 4 consecutive ones
   for (int b = threadIdx.x; b < (int)kRbMaxBins; b += kRbThreads) cnt[b] = 0;
   __syncthreads();
@@ -376,7 +376,7 @@ __global__ __launch_bounds__(kThreads) void randk_gather_kernel(Geo g, const flo
   randk_header(g, p, k, payload);
   float *val = reinterpret_cast<float *>(payload + (uint64_t)p * g.stride + kHeaderBytes);
   const uint64_t base = g.part_base(p);
-  const Philox rng(seed, stream_id, p);
+  const Philox rng(seed, stream_id, p + g.part0);
   for (uint32_t t = blockIdx.x * kThreads + threadIdx.x; t < k; t += gridDim.x * kThreads)
     val[t] = buf[base + randk_index(rng, t, d)];
 }
@@ -390,7 +390,7 @@ __global__ __launch_bounds__(kThreads) void randk_gather_src_kernel(Geo g, SRC s
   const uint32_t k = (uint32_t)k_of_device(g, p);
   randk_header(g, p, k, payload);
   float *val = reinterpret_cast<float *>(payload + (uint64_t)p * g.stride + kHeaderBytes);
-  const Philox rng(seed, stream_id, p);
+  const Philox rng(seed, stream_id, p + g.part0);
   for (uint32_t t = blockIdx.x * kThreads + threadIdx.x; t < k; t += gridDim.x * kThreads)
     val[t] = src.at(g, p, randk_index(rng, t, d), nullptr);
 }
@@ -404,7 +404,7 @@ __global__ __launch_bounds__(kThreads) void randk_fixup_kernel(Geo g, float *buf
   const float *val = reinterpret_cast<const float *>(payload + (uint64_t)p * g.stride + kHeaderBytes);
   const float scale = value_scale >= 0.0f ? value_scale : (float)d / (float)k;
   const uint64_t base = g.part_base(p);
-  const Philox rng(seed, stream_id, p);
+  const Philox rng(seed, stream_id, p + g.part0);
   for (uint32_t t = blockIdx.x * kThreads + threadIdx.x; t < k; t += gridDim.x * kThreads)
     atomicAdd(buf + base + randk_index(rng, t, d), -(scale * val[t]));
 }
@@ -456,7 +456,7 @@ hipError_t randk_encode(const Geo &g, const bpc_params_t &prm, const bpc_params_
   const uint64_t one_list = ((uint64_t)g.P * g.k_cap * sizeof(uint2) + 255) / 256 * 256;
   const uint64_t one_table = ((uint64_t)g.P * (kRbMaxBins + 1) * sizeof(uint32_t) + 255) / 256 * 256;
   // the status word: cleared by the binning kernel on the paths that start with it, by a fill elsewhere
-  uint32_t *status = ws.at<uint32_t>(ws.lay.status);
+  uint32_t *status = ws.status();
   if (src.grad) {
     if (!src.residual) {
       hipError_t e0 = fill_zero(status, 16, stream);

@@ -99,7 +99,7 @@ hipError_t sign_encode(const Geo &g_in, const bpc_params_t &prm_in, const Source
   Geo g = g_in;
   Source src = src_in;
   bpc_params_t prm = prm_in;
-  uint32_t *status = ws.at<uint32_t>(ws.lay.status);
+  uint32_t *status = ws.status();
   if (sp.single_pass && sp.head.P > 0) {
     bool used = false;
     hipError_t e = src.grad ? sign_worker_single_pass(sp.head, prm, src, payload, ws, stream, &used)

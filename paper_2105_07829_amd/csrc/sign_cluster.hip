@@ -160,7 +160,7 @@ hipError_t sign_worker_single_pass(const Geo &g, const bpc_params_t &prm, const 
                                    const Workspace &ws, hipStream_t stream, bool *used) {
   ClusterGeo cg = make_cluster_geo(g, kSWTile);
   double *slots = ws.at<double>(ws.lay.slots);
-  uint32_t *status = ws.at<uint32_t>(ws.lay.status);
+  uint32_t *status = ws.status();
   const bool f16 = src.dtype == BPC_F16;
   if (src.residual) {
     if (f16)

@@ -269,7 +269,7 @@ hipError_t sign_server_single_pass(const Geo &g, const bpc_params_t &prm, const 
                                    const Workspace &ws, hipStream_t stream, bool *used) {
   ClusterGeo cg = make_cluster_geo(g, kSSTile);
   double *slots = ws.at<double>(ws.lay.slots);
-  uint32_t *status = ws.at<uint32_t>(ws.lay.status);
+  uint32_t *status = ws.status();
   if (src.residual) return launch_sign_server<true>(g, cg, prm, src, payload, slots, status, stream, used);
   return launch_sign_server<false>(g, cg, prm, src, payload, slots, status, stream, used);
 }

@@ -1039,7 +1039,7 @@ hipError_t topk_encode(const Geo &g, const bpc_params_t &prm, const bpc_params_t
                          capacity[half] > 0;
   const uint32_t sample_grid = g.P > 64 ? g.P : 64, load_grid = group_count(g, kTpgLoad);
   auto first_two = [&](auto s_sample, auto s_load) {
-    topk_sample_kernel<<<sample_grid, kThreads, 0, stream>>>(g, s_sample, hist, state, guess, short_list, ws.at<uint32_t>(ws.lay.status));
+    topk_sample_kernel<<<sample_grid, kThreads, 0, stream>>>(g, s_sample, hist, state, guess, short_list, ws.status());
     using Load = decltype(s_load);
     if (short_list) topk_load_hist1_kernel<Load, true><<<load_grid, kThreads, 0, stream>>>(g, s_load, buf, hist, state, guess, tilecnt, cand_idx, cand_val);
     else topk_load_hist1_kernel<Load, false><<<load_grid, kThreads, 0, stream>>>(g, s_load, buf, hist, state, guess, tilecnt, cand_idx, cand_val);
@@ -1073,7 +1073,7 @@ hipError_t topk_encode(const Geo &g, const bpc_params_t &prm, const bpc_params_t
     // the long form for the partitions the short list could not take: one resident kernel
     const uint32_t grid = (uint32_t)capacity[half] < kGatedGrid ? (uint32_t)capacity[half] : kGatedGrid;
     uint32_t *counter = state + 8ull * g.P;
-    uint32_t *status = ws.at<uint32_t>(ws.lay.status);
+    uint32_t *status = ws.status();
     hipError_t e = cluster_launch_begin(stream);
     if (e != hipSuccess) return e;
     if (half) topk_long_form_kernel<true><<<grid, kThreads, 0, stream>>>(g, buf, hist, state, tilecnt, payload, zero_selected, n2, n3, nc, ne, guess, counter, status);

@@ -1275,7 +1275,7 @@ static hipError_t run_lans_single(const Geo &g, DEC dec, float *x, float *m, flo
   if (capacity <= 0 || cg.tiles_per_part > (uint32_t)capacity) return hipSuccess;
   *used = true;
   double *slots = ws.at<double>(ws.lay.slots);
-  uint32_t *status = ws.at<uint32_t>(ws.lay.status);
+  uint32_t *status = ws.status();
   hipError_t e = cluster_launch_begin(stream);
   if (e != hipSuccess) return e;
   const uint32_t n_slots = 3 * g.P * cg.tiles_per_part;
@@ -1291,7 +1291,7 @@ template <class DEC>
 static hipError_t run_update(const Geo &g, DEC dec, float *x, float *m, float *v, const bpc_opt_t &opt,
                              double *norms, const Workspace &ws, hipStream_t stream) {
   OptArgs o{opt.lr, opt.beta1, opt.beta2, opt.eps, opt.weight_decay, opt.bias_corr1, opt.bias_corr2,
-            opt.phi_lo, opt.phi_hi, opt.block_offsets, opt.n_blocks, ws.at<uint32_t>(ws.lay.status)};
+            opt.phi_lo, opt.phi_hi, opt.block_offsets, opt.n_blocks, ws.status()};
   if (opt.kind == BPC_OPT_ADAM) {
     adam_update_kernel<DEC><<<g.n_tiles, kThreads, 0, stream>>>(g, dec, x, m, v, o);
     return hipGetLastError();
@@ -1330,7 +1330,7 @@ hipError_t adaptive_update(const Geo &g, const bpc_params_t &prm, const uint8_t 
     // no dense decode: the update kernel lays each tile of the message out in LDS itself
     // (tiles of 4096 elements in the Adam-style kernel, of 8192 in the single-pass LANS kernel)
     OptArgs o{opt.lr, opt.beta1, opt.beta2, opt.eps, opt.weight_decay, opt.bias_corr1, opt.bias_corr2,
-              opt.phi_lo, opt.phi_hi, opt.block_offsets, opt.n_blocks, ws.at<uint32_t>(ws.lay.status)};
+              opt.phi_lo, opt.phi_hi, opt.block_offsets, opt.n_blocks, ws.status()};
     const uint32_t shift = lans_single ? 13 : 12;
     const uint32_t tiles = (uint32_t)cdiv(g.part_elems, 1ull << shift);
     const uint32_t *table = nullptr;

@@ -16,7 +16,11 @@ def both_params(orc, kind, pe, **kw):
     kind_o = {"identity": orc.IDENTITY, "sign": orc.SIGN, "topk": orc.TOPK, "randk": orc.RANDK,
               "dither": orc.DITHER, "natdither": orc.NATDITHER, "fp16": orc.FP16, "topk16": orc.TOPK16}[kind]
     kw = {k: v for k, v in kw.items() if not k.startswith("_")}     # "_..." keys are notes for the tests
-    return orc.make_params(kind_o, pe, **kw), bpc.make_params(KIND_B[kind], pe, **kw)
+    kw_o, kw_b = dict(kw), dict(kw)
+    kw_o.pop("bypass", None)                      # the oracle takes the mask per call, not in its params
+    if isinstance(kw.get("norm_override"), np.ndarray):
+        kw_b["norm_override"] = to_dev(kw["norm_override"])     # the library reads the scales on the card
+    return orc.make_params(kind_o, pe, **kw_o), bpc.make_params(KIND_B[kind], pe, **kw_b)
 
 
 def to_dev(a):

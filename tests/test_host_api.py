@@ -199,6 +199,57 @@ def test_static_workspace_entry_point_validates_before_any_device_work(bpc):
         assert bpc.workspace_bytes(q, D, 1) <= bpc.STATIC_WS_BYTES, (kind, D)
 
 
+def test_bypass_mask_sizes_and_limits(bpc, orc):
+    """Partitions under the size threshold travel as identity records: record offsets and the
+    payload size follow from the mask (and agree with the oracle's record sizes); more than 64
+    runs of one class are refused; the masks of one server call must mark the same partitions."""
+    import numpy as np
+    L = bpc.lib()
+    pe = 1024
+    D = 6 * pe + 100
+    mask = np.array([0, 1, 1, 0, 1, 0, 1], dtype=np.uint8)
+    for kind_b, kind_o, kw in [(bpc.SIGN, orc.SIGN, {}), (bpc.TOPK, orc.TOPK, dict(k_ratio=0.05)),
+                               (bpc.DITHER, orc.DITHER, dict(levels=15))]:
+        plain = bpc.make_params(kind_b, pe, **kw)
+        p = bpc.make_params(kind_b, pe, bypass=mask, **kw)
+        sizes = orc.record_sizes_bypass(orc.make_params(kind_o, pe, **kw), mask, D)
+        ident = bpc.partition_stride(bpc.make_params(bpc.IDENTITY, pe))
+        assert sizes == [ident if b else bpc.partition_stride(plain) for b in mask]
+        offs = np.concatenate([[0], np.cumsum(sizes)])
+        assert bpc.payload_bytes(p, D) == offs[-1]
+        for k in range(7):
+            assert bpc.partition_offset(p, D, k) == offs[k]
+            assert bpc.partition_offset(plain, D, k) == k * bpc.partition_stride(plain)
+        assert bpc.partition_offset(p, D, 7) == 2 ** 64 - 1            # no such partition
+        # a mask of zeros is no mask
+        zeros = bpc.make_params(kind_b, pe, bypass=np.zeros(7, np.uint8), **kw)
+        assert bpc.payload_bytes(zeros, D) == bpc.payload_bytes(plain, D)
+    # 65 runs: refused by every entry point before any device work
+    many = np.arange(65, dtype=np.uint8) & 1
+    p = bpc.make_params(bpc.SIGN, pe, bypass=many)
+    D2 = 65 * pe
+    assert bpc.payload_bytes(p, D2) == 0 and bpc.partition_offset(p, D2, 0) == 2 ** 64 - 1
+    G, R, PL, WS = 0x10000, 0x20000, 0x30000, 0x40000
+    assert L.bpc_compress(C.byref(p), G, bpc.F32, R, D2, PL, WS, 1 << 30, None) == bpc.ERR_UNSUPPORTED
+    assert L.bpc_decompress(C.byref(p), PL, D2, R, None) == bpc.ERR_UNSUPPORTED
+    o = bpc.make_opt(bpc.OPT_ADAM, 1e-3, 0.9, 0.999, 1e-8, 0.01, 1)
+    assert L.bpc_adaptive_update(C.byref(p), PL, D2, R, R, R, C.byref(o), WS, 1 << 30, None) == bpc.ERR_UNSUPPORTED
+    ok64 = bpc.make_params(bpc.SIGN, pe, bypass=np.arange(64, dtype=np.uint8) & 1)
+    assert bpc.payload_bytes(ok64, 64 * pe) > 0
+    # server: every worker's mask must mark the partitions the outgoing one marks
+    a = bpc.make_params(bpc.SIGN, pe, bypass=mask)
+    b = bpc.make_params(bpc.SIGN, pe, bypass=np.array([0, 1, 1, 0, 0, 0, 1], dtype=np.uint8))
+    c = bpc.make_params(bpc.SIGN, pe)
+    ptrs = (C.c_void_p * 2)(PL, PL + 0x100000)
+    for pair in ((a, b), (a, c)):
+        arr = (bpc.Params * 2)(*pair)
+        assert L.bpc_server_aggregate(arr, ptrs, 2, C.byref(a), R, D, PL, WS, 1 << 30, None) == bpc.ERR_INVALID_ARG
+    # LANS with caller-defined blocks takes no mask with more than one run
+    lo = bpc.make_opt(bpc.OPT_LANS, 1e-3, 0.9, 0.999, 1e-8, 0.01, 1)
+    lo.block_offsets, lo.n_blocks = 0x80000, 3
+    assert L.bpc_adaptive_update(C.byref(a), PL, D, R, R, R, C.byref(lo), WS, 1 << 30, None) == bpc.ERR_UNSUPPORTED
+
+
 def test_status_strings(bpc):
     L = bpc.lib()
     seen = {L.bpc_status_string(i).decode() for i in range(7)}

@@ -565,6 +565,69 @@ def test_given_scale_takes_the_place_of_the_reduction(orc):
             assert fmt.header_f32(orc.encode_partition(pk, 0, xs)) != 1.0     # (its own norm is another number)
 
 
+@pytest.mark.parametrize("name", ["sign", "topk", "randk", "dither"])
+def test_partitions_under_the_size_threshold_are_carried_as_they_are(orc, name):
+    """Section 4.2: what is too small to be worth compressing is sent uncompressed.  With the
+    partition as the unit: a bypassed partition's record is its values, its residual stays 0 on
+    both sides, the server's result there is the plain average of Algorithm 1, and the update
+    sees that average; every other partition's record, residual and draws (the Philox
+    partition number) are exactly what a call without a mask gives."""
+    kw = {"sign": {}, "topk": dict(k_ratio=0.05), "randk": dict(k_ratio=0.05, seed=4, stream_id=6),
+          "dither": dict(levels=4, seed=9, stream_id=(1 << 32) | 2)}[name]
+    kind = {"sign": orc.SIGN, "topk": orc.TOPK, "randk": orc.RANDK, "dither": orc.DITHER}[name]
+    pe, n = PE, 3
+    D = 5 * pe + 321
+    mask = np.array([0, 1, 1, 0, 1, 0], dtype=np.uint8)
+    prm = [orc.make_params(kind, pe, stream_id=kw.get("stream_id", 0) + i, **{k: v for k, v in kw.items() if k != "stream_id"})
+           for i in range(n)]
+    out = orc.make_params(kind, pe, stream_id=99, **{k: v for k, v in kw.items() if k != "stream_id"})
+    gs = [(rng(40 + i).standard_normal(D) * 1e-3).astype(np.float32) for i in range(n)]
+    es = [(rng(50 + i).standard_normal(D) * 1e-4).astype(np.float32) for i in range(n)]
+    strd, ident = orc.partition_stride(prm[0]), 16 + 4 * pe
+    sizes = orc.record_sizes_bypass(prm[0], mask, D)
+    assert sizes == [ident if b else strd for b in mask]
+    offs = np.concatenate([[0], np.cumsum(sizes)])
+    pays, plain = [], []
+    for i in range(n):
+        e_mask, e_plain = es[i].copy(), es[i].copy()
+        pays.append(orc.compress_bypass(prm[i], mask, gs[i], e_mask))
+        plain.append(orc.compress(prm[i], gs[i], e_plain))
+        assert pays[i].size == offs[-1]
+        for k in range(6):
+            lo, hi = k * pe, min(D, (k + 1) * pe)
+            rec = pays[i][offs[k]:offs[k + 1]]
+            if mask[k]:
+                q = gs[i][lo:hi] + es[i][lo:hi]
+                assert not rec[:16].any() and np.array_equal(rec[16:16 + 4 * (hi - lo)].view(np.float32), q)
+                assert not e_mask[lo:hi].any()
+            else:
+                assert np.array_equal(rec, plain[i][k * strd:(k + 1) * strd])
+                assert np.array_equal(e_mask[lo:hi], e_plain[lo:hi])
+        es[i] = e_mask
+    sres = np.zeros(D, np.float32)
+    p_out = orc.server_aggregate_bypass(prm, pays, out, mask, sres, D)
+    dec = orc.decompress_bypass(out, mask, p_out, D)
+    qs = [gs[i] + (rng(50 + i).standard_normal(D) * 1e-4).astype(np.float32) for i in range(n)]
+    for k in range(6):
+        lo, hi = k * pe, min(D, (k + 1) * pe)
+        if mask[k]:
+            acc = np.zeros(hi - lo, np.float32)
+            for i in range(n):
+                acc = acc + qs[i][lo:hi]
+            mean = acc * np.float32(1.0 / n)
+            assert np.array_equal(dec[lo:hi], mean) and not sres[lo:hi].any()
+            assert np.allclose(dec[lo:hi], np.mean([q[lo:hi].astype(np.float64) for q in qs], axis=0), rtol=1e-6, atol=1e-9)
+    # the update consumes the mixed message: same as updating with the decoded vector
+    x = (rng(60).standard_normal(D) * 0.02).astype(np.float32)
+    m, v = np.zeros(D, np.float32), np.zeros(D, np.float32)
+    x2, m2, v2 = x.copy(), m.copy(), v.copy()
+    opt = orc.make_opt(orc.OPT_ADAM, 1e-3, 0.9, 0.999, 1e-8, 0.01, 1)
+    orc.adaptive_update_bypass(out, mask, p_out, D, x, m, v, opt)
+    ident_p = orc.make_params(orc.IDENTITY, pe)
+    orc.adaptive_update(ident_p, orc.compress(ident_p, dec, None), D, x2, m2, v2, opt)
+    assert np.array_equal(x, x2) and np.array_equal(m, m2) and np.array_equal(v, v2)
+
+
 def test_zero_vector_encodes_to_zero(orc):
     z = np.zeros(100, dtype=np.float32)
     for kind in (orc.SIGN, orc.DITHER, orc.NATDITHER, orc.TOPK, orc.RANDK, orc.IDENTITY):
