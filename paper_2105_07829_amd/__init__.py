@@ -25,17 +25,14 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_ALIGNMENT, ERR_HIP, ERR
 MAX_WORKERS = 64
 
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-ffp-contract=off",
-               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-fPIC", "-shared"]
+               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-fPIC"]
 
 EXPORTS = ["bpc_partition_k", "bpc_partition_stride", "bpc_payload_bytes", "bpc_partition_offset", "bpc_workspace_bytes",
            "bpc_update_workspace_bytes", "bpc_workspace_status_offset", "bpc_workspace_check", "bpc_compress", "bpc_compress_static_ws", "bpc_decompress", "bpc_server_aggregate", "bpc_adaptive_update",
            "bpc_stream_probe", "bpc_status_string", "bpc_last_hip_error"]
 
 
-def build(verbose: bool = False) -> str:
-    """Compile csrc/*.hip for gfx950 into libbpc.so (in-tree)."""
-    srcs = sorted(os.path.join(_CSRC, f) for f in os.listdir(_CSRC) if f.endswith(".hip"))
-    cmd = ["hipcc", *HIPCC_FLAGS, "-o", LIB_PATH, *srcs]
+def _hipcc(cmd, verbose):
     res = subprocess.run(cmd, capture_output=True, text=True)
     noise = "is not a recognized feature for this target"
     err = "\n".join(l for l in res.stderr.splitlines() if noise not in l)
@@ -43,6 +40,22 @@ def build(verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed:\n" + err)
     if verbose and err.strip():
         print(err)
+
+
+def build(verbose: bool = False, jobs: int = 8) -> str:
+    """Compile csrc/*.hip for gfx950 into libbpc.so (in-tree): one object per source file, the
+    files compiled side by side (no kernel calls across files, so no relocatable device code),
+    then one link.  Every call compiles every file."""
+    from concurrent.futures import ThreadPoolExecutor
+
+    srcs = sorted(f for f in os.listdir(_CSRC) if f.endswith(".hip"))
+    obj_dir = os.path.join(_HERE, "_build")
+    os.makedirs(obj_dir, exist_ok=True)
+    objs = [os.path.join(obj_dir, f[:-4] + ".o") for f in srcs]
+    with ThreadPoolExecutor(max_workers=max(1, jobs)) as pool:
+        list(pool.map(lambda so: _hipcc(["hipcc", *HIPCC_FLAGS, "-c", os.path.join(_CSRC, so[0]), "-o", so[1]], verbose),
+                      zip(srcs, objs)))
+    _hipcc(["hipcc", "--offload-arch=gfx950", "-fPIC", "-shared", "-o", LIB_PATH, *objs], verbose)
     return LIB_PATH
 
 

@@ -5,13 +5,11 @@
 
 namespace bpc {
 
-__global__ void slots_reset_kernel(double *slots, uint32_t n, uint32_t *status) {
+__global__ void slots_reset_kernel(double *slots, uint32_t n, uint32_t *status, uint32_t *tickets) {
   uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) slots[i] = -1.0;
-  if (i == 0) {
-    status[0] = 0;  // no wait has given up
-    status[1] = 0;  // next ticket
-  }
+  if (i == 0) status[0] = 0;  // no wait has given up
+  if (tickets && i < (uint32_t)kTicketClasses) tickets[i * (kTicketStride / 4)] = 0;  // next ticket of every class
 }
 
 int cluster_capacity(const void *kernel, int threads, size_t dyn_lds) {

@@ -27,7 +27,16 @@
 //     side (two input streams per tile, one large workgroup per compute unit).
 //   TICKETED (cluster_run_ticketed): a workgroup takes the number of its next tile from a
 //     counter, so tiles are handed out in the order in which workgroups become free, and phase
-//     1 issues its own loads.  Used on the server side (n + 1 input streams and n-term sums
+//     1 issues its own loads.  There are C = min(kTicketClasses, grid) counters: workgroup w
+//     draws from counter c = w % C, whose ticket t stands for tile t * C + c.  (Atomics on one
+//     address are served one after the other, about 11 ns each: with a single counter the
+//     13 K tiles of a 110 M element gradient were 0.15 ms of that unit's time, which a kernel
+//     with little else to do -- few workers, no residual -- then took: 0.17 against 0.10 ms.)
+//     Within a class tiles are taken in index order, and every class has at least
+//     floor(grid / C) workgroups, so the argument below holds class by class: the lowest tile
+//     never published would belong to a class all of whose workgroups hold two earlier tiles
+//     of that class each, which puts it 2 C floor(grid / C) tiles past the oldest of them,
+//     further than a partition reaches.  Used on the server side (n + 1 input streams and n-term sums
 //     per tile): several workgroups per compute unit overlap each other's loads and
 //     arithmetic, with no prefetch to keep in registers.
 //   (Launching one workgroup per tile instead of a resident grid would tie each workgroup to
@@ -123,8 +132,8 @@ struct PerDevice {
 };
 
 #if defined(__HIPCC__)
-// Presets the slots to "not published", clears the status word and the ticket counter.
-__global__ void slots_reset_kernel(double *slots, uint32_t n, uint32_t *status);
+// Presets the slots to "not published", clears the status word and (if given) the ticket counters.
+__global__ void slots_reset_kernel(double *slots, uint32_t n, uint32_t *status, uint32_t *tickets);
 
 // A slot is unpublished while it holds exactly the preset -1.0.  Partials are sums of
 // magnitudes or squares, so no published value has that bit pattern, whatever the inputs
@@ -246,9 +255,9 @@ __device__ inline double cluster_block_reduce(double x, double *red /*THREADS/64
 // The operator is passed by value in the kernel arguments and never modified, so it stays in
 // the kernel-argument segment (a modified copy would live in scratch memory).
 
-// Ticketed driver.  `status[1]` is the ticket counter.
+// Ticketed driver.
 template <class Op>
-__device__ inline void cluster_run_ticketed(const Op &op, float *table, double *slots, uint32_t *status) {
+__device__ inline void cluster_run_ticketed(const Op &op, float *table, double *slots, uint32_t *status, uint32_t *tickets) {
   constexpr int kT = Op::kThreads;
   constexpr uint32_t kNone = 0xffffffffu;
   __shared__ double red[kT / 64];
@@ -257,7 +266,10 @@ __device__ inline void cluster_run_ticketed(const Op &op, float *table, double *
   const uint32_t n_items = op.n_items();
   typename Op::Held held_prev;
   uint32_t prev = kNone;
-  if (threadIdx.x == 0) item_sh = atomicAdd(status + 1, 1u);
+  const uint32_t n_classes = gridDim.x < (uint32_t)kTicketClasses ? gridDim.x : (uint32_t)kTicketClasses;
+  const uint32_t cls = blockIdx.x % n_classes;
+  uint32_t *counter = tickets + cls * (kTicketStride / 4);
+  if (threadIdx.x == 0) item_sh = atomicAdd(counter, 1u) * n_classes + cls;
   __syncthreads();
   uint32_t item = __builtin_amdgcn_readfirstlane(item_sh);
   for (;;) {
@@ -283,7 +295,7 @@ __device__ inline void cluster_run_ticketed(const Op &op, float *table, double *
       if (threadIdx.x == 0) scale_sh = op.scale_of(prev, total);
     }
     // the next ticket is on its way while the older tile is written out
-    if (have && threadIdx.x == 0) ticket = atomicAdd(status + 1, 1u);
+    if (have && threadIdx.x == 0) ticket = atomicAdd(counter, 1u) * n_classes + cls;
     if (have) op.early(item, held);
     __syncthreads();
     if (prev != kNone) {
@@ -303,7 +315,7 @@ __device__ inline void cluster_run_ticketed(const Op &op, float *table, double *
 // Persistent driver.  The older tile's slots are read before phase 1 of the current tile and
 // looked at after it, so that read is off the critical path as well.
 template <class Op>
-__device__ inline void cluster_run_persistent(const Op &op, float *table, double *slots, uint32_t *status) {
+__device__ inline void cluster_run_persistent(const Op &op, float *table, double *slots, uint32_t *status, uint32_t *) {
   constexpr int kT = Op::kThreads;
   constexpr uint32_t kNone = 0xffffffffu;
   __shared__ double red[kT / 64];

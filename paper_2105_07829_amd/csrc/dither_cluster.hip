@@ -181,18 +181,18 @@ struct DitherWorkerOp {
 
 template <class G, bool EF>
 static hipError_t launch_dither(const Geo &g, const ClusterGeo &cg, const bpc_params_t &prm, const Source &src,
-                                uint8_t *payload, double *slots, uint32_t *status, hipStream_t stream,
+                                uint8_t *payload, double *slots, uint32_t *status, uint32_t *tickets, hipStream_t stream,
                                 bool *used) {
 #define BPC_DW(LINF, NAT)                                                                                  \
   return launch_cluster(DitherWorkerOp<G, EF, LINF, NAT>{g, cg, (const G *)src.grad, src.residual, payload, \
                                                          prm.norm_override, prm.levels, prm.seed, prm.stream_id}, \
-                        cg, slots, status, stream, used)
+                        cg, slots, status, tickets, stream, used)
   const bool nat = prm.kind == BPC_NATDITHER;
   if (!nat && dither_planes(prm.levels) > 0) {
 #define BPC_DWW(LINF)                                                                                             \
   return launch_cluster(DitherWorkerOp<G, EF, LINF, false, true>{g, cg, (const G *)src.grad, src.residual, payload, \
                                                                  prm.norm_override, prm.levels, prm.seed, prm.stream_id}, \
-                        cg, slots, status, stream, used)
+                        cg, slots, status, tickets, stream, used)
     if (prm.norm == BPC_NORM_LINF) BPC_DWW(true);
     BPC_DWW(false);
 #undef BPC_DWW
@@ -211,12 +211,13 @@ hipError_t dither_worker_single_pass(const Geo &g, const bpc_params_t &prm, cons
   ClusterGeo cg = make_cluster_geo(g, kDWTile);
   double *slots = ws.at<double>(ws.lay.slots);
   uint32_t *status = ws.status();
+  uint32_t *tickets = ws.tickets();
   const bool f16 = src.dtype == BPC_F16;
   if (src.residual)
-    return f16 ? launch_dither<__half, true>(g, cg, prm, src, payload, slots, status, stream, used)
-               : launch_dither<float, true>(g, cg, prm, src, payload, slots, status, stream, used);
-  return f16 ? launch_dither<__half, false>(g, cg, prm, src, payload, slots, status, stream, used)
-             : launch_dither<float, false>(g, cg, prm, src, payload, slots, status, stream, used);
+    return f16 ? launch_dither<__half, true>(g, cg, prm, src, payload, slots, status, tickets, stream, used)
+               : launch_dither<float, true>(g, cg, prm, src, payload, slots, status, tickets, stream, used);
+  return f16 ? launch_dither<__half, false>(g, cg, prm, src, payload, slots, status, tickets, stream, used)
+             : launch_dither<float, false>(g, cg, prm, src, payload, slots, status, tickets, stream, used);
 }
 
 }  // namespace bpc

@@ -293,14 +293,14 @@ struct DitherServerOp {
 
 template <bool EF, bool LINF, bool NAT, bool WIDE>
 static hipError_t launch_dither_server(const Geo &g, const ClusterGeo &cg, const bpc_params_t &prm,
-                                       const Source &src, uint8_t *payload, double *slots, uint32_t *status,
+                                       const Source &src, uint8_t *payload, double *slots, uint32_t *status, uint32_t *tickets,
                                        hipStream_t stream, bool *used) {
   const DMsgPtrs mp = dmsg_ptrs(src.msgs);
   float *res = src.residual;
 #define BPC_DS(NW)                                                                                          \
   return launch_cluster(DitherServerOp<EF, LINF, NW, NAT, WIDE>{g, cg, mp, res, payload, prm.norm_override, prm.levels, \
                                                            prm.seed, prm.stream_id},                        \
-                        cg, slots, status, stream, used)
+                        cg, slots, status, tickets, stream, used)
   switch (mp.n) {
     case 4: BPC_DS(4);
     case 8: BPC_DS(8);
@@ -321,6 +321,7 @@ hipError_t dither_server_single_pass(const Geo &g, const bpc_params_t &prm, cons
   ClusterGeo cg = make_cluster_geo(g, kSTile);
   double *slots = ws.at<double>(ws.lay.slots);
   uint32_t *status = ws.status();
+  uint32_t *tickets = ws.tickets();
   const bool linf = prm.norm == BPC_NORM_LINF, nat = prm.kind == BPC_NATDITHER;
   const uint32_t planes = nat ? 0u : dither_planes(prm.levels);
   if (planes > 1) {   // 6 and 7 bits: the multi-pass kernels
@@ -329,12 +330,12 @@ hipError_t dither_server_single_pass(const Geo &g, const bpc_params_t &prm, cons
   }
 #define BPC_DSL(EF)                                                                                              \
   do {                                                                                                           \
-    if (planes == 1 && linf) return launch_dither_server<EF, true, false, true>(g, cg, prm, src, payload, slots, status, stream, used);  \
-    if (planes == 1) return launch_dither_server<EF, false, false, true>(g, cg, prm, src, payload, slots, status, stream, used);         \
-    if (linf && nat) return launch_dither_server<EF, true, true, false>(g, cg, prm, src, payload, slots, status, stream, used);   \
-    if (linf) return launch_dither_server<EF, true, false, false>(g, cg, prm, src, payload, slots, status, stream, used);         \
-    if (nat) return launch_dither_server<EF, false, true, false>(g, cg, prm, src, payload, slots, status, stream, used);          \
-    return launch_dither_server<EF, false, false, false>(g, cg, prm, src, payload, slots, status, stream, used);                  \
+    if (planes == 1 && linf) return launch_dither_server<EF, true, false, true>(g, cg, prm, src, payload, slots, status, tickets, stream, used);  \
+    if (planes == 1) return launch_dither_server<EF, false, false, true>(g, cg, prm, src, payload, slots, status, tickets, stream, used);         \
+    if (linf && nat) return launch_dither_server<EF, true, true, false>(g, cg, prm, src, payload, slots, status, tickets, stream, used);   \
+    if (linf) return launch_dither_server<EF, true, false, false>(g, cg, prm, src, payload, slots, status, tickets, stream, used);         \
+    if (nat) return launch_dither_server<EF, false, true, false>(g, cg, prm, src, payload, slots, status, tickets, stream, used);          \
+    return launch_dither_server<EF, false, false, false>(g, cg, prm, src, payload, slots, status, tickets, stream, used);                  \
   } while (0)
   if (src.residual) BPC_DSL(true);
   BPC_DSL(false);

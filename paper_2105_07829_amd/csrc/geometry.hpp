@@ -21,6 +21,8 @@ constexpr int kSThreads = 256;       // workgroup size of the server-side kernel
 constexpr int kWTile = 16384;        // tile of the worker-side single-pass kernels (1024 threads x 16 elements)
 constexpr int kSTile = 8192;         // tile of the server-side single-pass kernels and of single-pass LANS
 constexpr uint32_t kHeaderBytes = 16;
+constexpr int kTicketClasses = 16;   // counters the ticketed single-pass kernels draw their tiles from (workgroup w uses counter w % 16)
+constexpr int kTicketStride = 4096;  // bytes between two of them, so that they lie in different memory channels
 constexpr int kMaxRuns = 64;         // most runs of partitions of one class (compressed / carried as they are) a call accepts
 constexpr uint32_t kTopkListCap = 32768;  // entries of a partition's top-k short list
 constexpr uint32_t kTopkHistWords = 2048 + 1024 + 1024;  // top-k radix histograms of a partition
@@ -116,7 +118,9 @@ inline Geo make_geo(const bpc_params_t *p, uint64_t D) {
 struct WsLayout {
   size_t status;     // u32[4 * kMaxRuns], at offset 0 whatever the shape: one slot of four words for every run of
                      // partitions a call is split into (one run unless partitions bypass compression).  Word 0 of a
-                     // slot is non-zero if a single-pass kernel of that run gave up waiting, word 1 is its ticket counter
+                     // slot is non-zero if a single-pass kernel of that run gave up waiting
+  size_t tickets;    // u32 at every kTicketStride bytes, kTicketClasses of them: the ticket counters of the
+                     // ticketed single-pass kernels
   size_t partials;   // double[n_tiles]: per-tile partial norms
   size_t dense;      // float[D]: q / Delta / decoded message when no caller buffer can hold it
   size_t hist;       // u32[P*kTopkHistWords]: top-k radix histograms (2048 + 1024 + 1024 bins)
@@ -142,6 +146,7 @@ inline WsLayout ws_layout(const bpc_params_t *p, uint64_t D) {
   const bool topk = p->kind == BPC_TOPK || p->kind == BPC_TOPK16;
   bool sparse = topk || p->kind == BPC_RANDK || (p->kind == BPC_DITHER && dither_planes(p->levels) > 0);
   w.status = take(16 * kMaxRuns);
+  w.tickets = take((size_t)kTicketClasses * kTicketStride);
   w.partials = take(sizeof(double) * (size_t)g.n_tiles);
   w.dense = take(sparse ? sizeof(float) * (size_t)D : 0);
   w.hist = take(topk ? sizeof(uint32_t) * kTopkHistWords * (size_t)g.P : 0);

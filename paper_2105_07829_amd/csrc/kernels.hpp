@@ -30,6 +30,7 @@ struct Workspace {
   uint32_t run = 0;   // which run of partitions of the call this is: selects the status slot
   template <class T> T *at(size_t off) const { return reinterpret_cast<T *>(base + off); }
   uint32_t *status() const { return reinterpret_cast<uint32_t *>(base + lay.status) + 4 * run; }
+  uint32_t *tickets() const { return reinterpret_cast<uint32_t *>(base + lay.tickets); }
 };
 
 hipError_t fill_zero(void *ptr, size_t bytes, hipStream_t stream);

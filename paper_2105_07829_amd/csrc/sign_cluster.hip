@@ -161,19 +161,20 @@ hipError_t sign_worker_single_pass(const Geo &g, const bpc_params_t &prm, const 
   ClusterGeo cg = make_cluster_geo(g, kSWTile);
   double *slots = ws.at<double>(ws.lay.slots);
   uint32_t *status = ws.status();
+  uint32_t *tickets = ws.tickets();
   const bool f16 = src.dtype == BPC_F16;
   if (src.residual) {
     if (f16)
       return launch_cluster(SignWorkerOp<__half, true>{g, cg, (const __half *)src.grad, src.residual, payload, prm.norm_override},
-                            cg, slots, status, stream, used);
+                            cg, slots, status, tickets, stream, used);
     return launch_cluster(SignWorkerOp<float, true>{g, cg, (const float *)src.grad, src.residual, payload, prm.norm_override},
-                          cg, slots, status, stream, used);
+                          cg, slots, status, tickets, stream, used);
   }
   if (f16)
     return launch_cluster(SignWorkerOp<__half, false>{g, cg, (const __half *)src.grad, nullptr, payload, prm.norm_override},
-                          cg, slots, status, stream, used);
+                          cg, slots, status, tickets, stream, used);
   return launch_cluster(SignWorkerOp<float, false>{g, cg, (const float *)src.grad, nullptr, payload, prm.norm_override},
-                        cg, slots, status, stream, used);
+                        cg, slots, status, tickets, stream, used);
 }
 
 }  // namespace bpc

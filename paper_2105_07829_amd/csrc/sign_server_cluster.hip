@@ -253,15 +253,15 @@ struct SignServerOp {
 
 template <bool EF>
 static hipError_t launch_sign_server(const Geo &g, const ClusterGeo &cg, const bpc_params_t &prm, const Source &src,
-                                     uint8_t *payload, double *slots, uint32_t *status, hipStream_t stream,
+                                     uint8_t *payload, double *slots, uint32_t *status, uint32_t *tickets, hipStream_t stream,
                                      bool *used) {
   const MsgPtrs mp = msg_ptrs(src.msgs);
   float *res = src.residual;
   switch (mp.n) {
-    case 4: return launch_cluster(SignServerOp<EF, 4>{g, cg, mp, res, payload, prm.norm_override}, cg, slots, status, stream, used);
-    case 8: return launch_cluster(SignServerOp<EF, 8>{g, cg, mp, res, payload, prm.norm_override}, cg, slots, status, stream, used);
-    case 16: return launch_cluster(SignServerOp<EF, 16>{g, cg, mp, res, payload, prm.norm_override}, cg, slots, status, stream, used);
-    default: return launch_cluster(SignServerOp<EF, 0>{g, cg, mp, res, payload, prm.norm_override}, cg, slots, status, stream, used);
+    case 4: return launch_cluster(SignServerOp<EF, 4>{g, cg, mp, res, payload, prm.norm_override}, cg, slots, status, tickets, stream, used);
+    case 8: return launch_cluster(SignServerOp<EF, 8>{g, cg, mp, res, payload, prm.norm_override}, cg, slots, status, tickets, stream, used);
+    case 16: return launch_cluster(SignServerOp<EF, 16>{g, cg, mp, res, payload, prm.norm_override}, cg, slots, status, tickets, stream, used);
+    default: return launch_cluster(SignServerOp<EF, 0>{g, cg, mp, res, payload, prm.norm_override}, cg, slots, status, tickets, stream, used);
   }
 }
 
@@ -270,8 +270,9 @@ hipError_t sign_server_single_pass(const Geo &g, const bpc_params_t &prm, const 
   ClusterGeo cg = make_cluster_geo(g, kSSTile);
   double *slots = ws.at<double>(ws.lay.slots);
   uint32_t *status = ws.status();
-  if (src.residual) return launch_sign_server<true>(g, cg, prm, src, payload, slots, status, stream, used);
-  return launch_sign_server<false>(g, cg, prm, src, payload, slots, status, stream, used);
+  uint32_t *tickets = ws.tickets();
+  if (src.residual) return launch_sign_server<true>(g, cg, prm, src, payload, slots, status, tickets, stream, used);
+  return launch_sign_server<false>(g, cg, prm, src, payload, slots, status, tickets, stream, used);
 }
 
 }  // namespace bpc

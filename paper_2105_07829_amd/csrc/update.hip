@@ -1279,7 +1279,7 @@ static hipError_t run_lans_single(const Geo &g, DEC dec, float *x, float *m, flo
   hipError_t e = cluster_launch_begin(stream);
   if (e != hipSuccess) return e;
   const uint32_t n_slots = 3 * g.P * cg.tiles_per_part;
-  slots_reset_kernel<<<(uint32_t)cdiv(n_slots, 256), 256, 0, stream>>>(slots, n_slots, status);
+  slots_reset_kernel<<<(uint32_t)cdiv(n_slots, 256), 256, 0, stream>>>(slots, n_slots, status, nullptr);
   const uint32_t grid = cg.n_items > (uint32_t)capacity ? (uint32_t)capacity : cg.n_items;
   lans_single_kernel<DEC><<<grid, kLThreads, 0, stream>>>(g, cg, dec, x, m, v, o, slots, status);
   e = hipGetLastError();
