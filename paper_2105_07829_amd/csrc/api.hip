@@ -335,6 +335,8 @@ bpc_status_t bpc_server_aggregate(const bpc_params_t *in, const void *const *pay
       src.msgs.seed[i] = in[i].seed;
       src.msgs.stream_id[i] = in[i].stream_id;
     }
+    src.msgs.shared_scale = in[0].norm_override != nullptr;
+    for (int i = 1; i < n; ++i) src.msgs.shared_scale = src.msgs.shared_scale && in[i].norm_override == in[0].norm_override;
     Workspace w{(uint8_t *)ws, ws_layout(&sub, r.elems), (uint32_t)k};
     const hipError_t e = encode(run_geo(sub, r), sub, sub_in, src, (uint8_t *)out_payload + r.pay_off, w, (hipStream_t)hip_stream);
     if (e != hipSuccess) return hip_status(e);

@@ -13,6 +13,8 @@ struct WorkerMsgs {
   uint64_t stream_id[kMaxWorkers];
   int n;
   float inv_n;
+  bool shared_scale;    // every worker's params name the same scale array (norm_override): the caller's
+                        // statement that the workers compressed with one common scale per partition
 };
 
 // Where the worker-side q = g + e or the server-side Delta comes from.

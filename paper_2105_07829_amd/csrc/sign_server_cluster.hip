@@ -40,9 +40,22 @@ __device__ inline float pick_sign(uint32_t byte, uint32_t mag) {
   return __builtin_copysignf(__uint_as_float(mag), __uint_as_float(byte << (31 - C)));
 }
 
+// The n-term sum of +-sigma_i can be had from bit counts when every worker sent the SAME
+// scale and that scale is short: with the low six bits of its significand clear (and the scale
+// positive, normal and far from overflow) every partial sum m * sigma, |m| <= 64, is exactly
+// representable, so the f32 sum in worker order is exact and equals sigma * (n - 2 c), c = the
+// number of workers whose bit is set -- bit for bit the same result, without the n additions.
+// (Workers get such a scale by agreeing on one, e.g. through bpc_params_t::norm_override.)
+__device__ inline bool scale_is_short(uint32_t bits) {
+  const uint32_t ex = bits >> 23;   // (a set sign bit makes this 256 or more)
+  return (bits & 0x3fu) == 0u && ex >= 1u && ex <= 240u;
+}
+
 // NW > 0: the number of workers is known at compile time and the worker loop is unrolled, so
 // the byte loads can be scheduled ahead of their use; NW == 0: any number, rolled loop.
-template <bool EF, int NW>
+// COUNT: the caller stated that the workers share a scale array; the counting form is compiled in
+// and taken for the partitions where it is exact.
+template <bool EF, int NW, bool COUNT = false>
 struct SignServerOp {
   // loads of a tile: its rows of e~, this wave's share of the workers' bits, a worker's scale
   struct Raw {
@@ -55,7 +68,11 @@ struct SignServerOp {
   static constexpr int kRowsPerTile = kSRows;
   // LDS: the n scales, then (NW > 0) the tile's sign bits of every worker, 1 KiB each
   static constexpr int kBitsPerWorker = kSSTile / 8;   // bytes
-  static constexpr int kTableFloats = kMaxWorkers + (NW > 0 ? NW * kBitsPerWorker / 4 : 0);
+  static constexpr int kSpreadWords = COUNT ? 256 : 0;   // byte -> its 8 bits as 8 nibbles (the counting form of the sum)
+  static constexpr int kTableFloats = kMaxWorkers + (NW > 0 ? NW * kBitsPerWorker / 4 : 0) + kSpreadWords;
+  // Workers per nibble counter of the counting form: a nibble counts up to 15.
+  static constexpr int kCountGroup = 8;
+  static constexpr int kCountGroups = NW > 0 ? (NW + kCountGroup - 1) / kCountGroup : 1;
   static constexpr int kThreads = kSSThreads;
   static constexpr int kWavesPerSimd = 6;   // 80 registers a lane, three workgroups a CU
   static constexpr bool kPersistent = false;
@@ -93,6 +110,7 @@ struct SignServerOp {
   // A worker's bits of a tile are fetched in pieces of 1 KiB (16 bytes a lane, 8192 elements);
   // piece j = (worker j / kPieces, part j % kPieces) is fetched by wave j % kSSWaves.
   static constexpr int kPieces = kSSTile / 8192;
+  static_assert(!COUNT || NW > 0, "the counting form is built for fixed numbers of workers");
   static_assert(kSSTile % 8192 == 0, "tile must be whole pieces");
   // Row u of e~; with row 0 also the scale of worker threadIdx.x and (NW > 0) the tile's sign
   // bits, all in one round trip.
@@ -158,21 +176,60 @@ struct SignServerOp {
       uint8_t *staged = reinterpret_cast<uint8_t *>(sig + kMaxWorkers);
       const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
       const u32x4 *fetched = raw.fetched;
+      uint32_t *spread = reinterpret_cast<uint32_t *>(sig + kMaxWorkers + NW * kBitsPerWorker / 4);
       __syncthreads();   // the LDS scratch may still be in use by the caller
       if ((int)threadIdx.x < msgs.n) sig[threadIdx.x] = my_sigma;
+      if (COUNT && threadIdx.x < 256u) {
+        // bit c of the byte value -> nibble c
+        const uint32_t b = threadIdx.x;
+        spread[b] = (b & 1u) | ((b & 2u) << 3) | ((b & 4u) << 6) | ((b & 8u) << 9) | ((b & 16u) << 12) | ((b & 32u) << 15) |
+                    ((b & 64u) << 18) | ((b & 128u) << 21);
+      }
 #pragma unroll
       for (int j = 0; j < NW * kPieces; ++j)
         if ((uint32_t)(j % kSSWaves) == wave)
           reinterpret_cast<u32x4 *>(staged + (j / kPieces) * kBitsPerWorker + (j % kPieces) * 1024)[lane] = fetched[j / kSSWaves];
       __syncthreads();
-      // four workers per trip: unrolled further, the LDS reads of all workers would be in
-      // flight at once and cost more registers than a lane has at this occupancy
-#pragma unroll 4
-      for (int i = 0; i < NW; ++i) {
-        uint32_t byte[kSRows];
+      // every wave for itself: do all workers carry worker 0's scale, and is it short?
+      bool counting = false;
+      uint32_t first_bits = 0;
+      if (COUNT) {
+        first_bits = __float_as_uint(sig[0]);
+        const bool same = lane >= (uint32_t)NW || __float_as_uint(sig[lane < (uint32_t)NW ? lane : 0u]) == first_bits;
+        counting = __all(same) && scale_is_short(first_bits);
+      }
+      if (COUNT && counting) {
+        // counting form: a byte's bits spread to nibbles, added up over the workers as integers
+        uint32_t cnt[kSRows][kCountGroups];
 #pragma unroll
-        for (int u = 0; u < kSRows; ++u) byte[u] = staged[i * kBitsPerWorker + u * kSSThreads + threadIdx.x];
-        add_worker(byte, sig[i], acc);
+        for (int u = 0; u < kSRows; ++u)
+#pragma unroll
+          for (int q = 0; q < kCountGroups; ++q) cnt[u][q] = 0;
+#pragma unroll 4
+        for (int i = 0; i < NW; ++i)
+#pragma unroll
+          for (int u = 0; u < kSRows; ++u)
+            cnt[u][i / kCountGroup] += spread[staged[i * kBitsPerWorker + u * kSSThreads + threadIdx.x]];
+        const float sigma = __uint_as_float(first_bits);
+#pragma unroll
+        for (int u = 0; u < kSRows; ++u)
+#pragma unroll
+          for (int c = 0; c < 8; ++c) {
+            uint32_t neg = 0;
+#pragma unroll
+            for (int q = 0; q < kCountGroups; ++q) neg += (cnt[u][q] >> (4 * c)) & 0xfu;
+            acc[8 * u + c] = sigma * (float)(NW - 2 * (int)neg);   // exact (see scale_is_short)
+          }
+      } else {
+        // four workers per trip: unrolled further, the LDS reads of all workers would be in
+        // flight at once and cost more registers than a lane has at this occupancy
+#pragma unroll 4
+        for (int i = 0; i < NW; ++i) {
+          uint32_t byte[kSRows];
+#pragma unroll
+          for (int u = 0; u < kSRows; ++u) byte[u] = staged[i * kBitsPerWorker + u * kSSThreads + threadIdx.x];
+          add_worker(byte, sig[i], acc);
+        }
       }
     } else {
       __syncthreads();
@@ -257,6 +314,11 @@ static hipError_t launch_sign_server(const Geo &g, const ClusterGeo &cg, const b
                                      bool *used) {
   const MsgPtrs mp = msg_ptrs(src.msgs);
   float *res = src.residual;
+  // The counting form pays from about 16 workers on (110 M elements: 0.283 against 0.291 ms at
+  // n = 16, 0.224 against 0.204 ms at n = 4: with few workers the additions it replaces are
+  // fewer than the instructions that take the counts apart again).
+  if (src.msgs.shared_scale && mp.n == 16)
+    return launch_cluster(SignServerOp<EF, 16, true>{g, cg, mp, res, payload, prm.norm_override}, cg, slots, status, tickets, stream, used);
   switch (mp.n) {
     case 4: return launch_cluster(SignServerOp<EF, 4>{g, cg, mp, res, payload, prm.norm_override}, cg, slots, status, tickets, stream, used);
     case 8: return launch_cluster(SignServerOp<EF, 8>{g, cg, mp, res, payload, prm.norm_override}, cg, slots, status, tickets, stream, used);

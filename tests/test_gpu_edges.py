@@ -304,6 +304,44 @@ def test_server_with_the_most_workers(gu, orc, kind):
         assert gu.close(res_gpu, res_ref, REL)
 
 
+@pytest.mark.parametrize("n", [4, 8, 16, 3])
+@pytest.mark.parametrize("scale_bits", [0x3A83F1C0, 0x3A83126F, 0x3A83F1C0 | (1 << 31)])
+def test_sign_server_with_a_shared_scale(gu, orc, n, scale_bits):
+    """Scaled-sign messages that all carry one scale: with a short, positive scale (low six bits
+    of the significand clear) the server may form the n-term sum from bit counts, which is then
+    exact and so the plain sum; a scale with a full significand or a negative one must take the
+    additions in worker order (as do fewer than 16 workers, where counting does not pay).  Either
+    way every bit of the outgoing message and the residual are the oracle's.
+    Partitions of several tiles with a ragged last one, with and without a server residual."""
+    sigma = np.uint32(scale_bits).view(np.float32)
+    for pe, D in ((PE, 2 * PE + 4137), (BIG_PE, 2 * BIG_PE + 70000)):
+        scales = np.full(len(fmt.part_sizes(D, pe)), sigma, np.float32)
+        ins = [gu.both_params(orc, "sign", pe, norm_override=scales) for _ in range(n)]
+        rs = np.random.default_rng(33 + n)
+        payloads = [orc.compress(ins[i][0], (rs.standard_normal(D) * 1e-3).astype(np.float32), None) for i in range(n)]
+        out_o, out_b = gu.both_params(orc, "sign", pe)
+        # the library is told that the workers shared their scales by params that all name one array
+        shared = gu.to_dev(scales)
+        plain = [gu.bpc.make_params(gu.bpc.SIGN, pe, norm_override=shared) for _ in range(n)]
+        for ef in (True, False):
+            et = (rs.standard_normal(D) * 2e-4).astype(np.float32) if ef else None
+            res_ref = None if et is None else et.copy()
+            pay_ref = orc.server_aggregate([p[0] for p in ins], payloads, out_o, res_ref, D)
+            pay_gpu, res_gpu = gu.gpu_server(plain, payloads, out_b, None if et is None else et.copy(), D)
+            strd = orc.partition_stride(out_o)
+            n_parts = len(fmt.part_sizes(D, pe))
+            hg = np.array([fmt.header_f32(fmt.record(pay_gpu, p, strd)) for p in range(n_parts)], dtype=np.float32)
+            ho = np.array([fmt.header_f32(fmt.record(pay_ref, p, strd)) for p in range(n_parts)], dtype=np.float32)
+            assert np.all(np.abs(hg.astype(np.float64) - ho) <= REL * np.abs(ho))
+            if not np.array_equal(hg, ho):
+                o2, _ = gu.both_params(orc, "sign", pe, norm_override=hg)
+                res_ref = None if et is None else et.copy()
+                pay_ref = orc.server_aggregate([p[0] for p in ins], payloads, o2, res_ref, D)
+            assert defined_equal("sign", pay_gpu, pay_ref, out_o, orc, D, pe, {})
+            if ef:
+                assert gu.close(res_gpu, res_ref, REL)
+
+
 def test_fp16_conversion_at_the_ends_of_the_half_range(gu, orc):
     """Round to nearest even on the card as in the oracle: ties, the subnormal halves, what
     rounds up to infinity (its residual is then -inf / +inf on both sides)."""

@@ -565,6 +565,44 @@ def test_given_scale_takes_the_place_of_the_reduction(orc):
             assert fmt.header_f32(orc.encode_partition(pk, 0, xs)) != 1.0     # (its own norm is another number)
 
 
+def test_shared_short_scale_makes_the_sign_sum_exact(orc):
+    """Aggregating scaled-sign messages by counting bits (the compressed-domain shortcut for the
+    server) is the plain algorithm of Algorithm 4 whenever it is exact: if all n workers sent the
+    same scale sigma and the low six bits of sigma's significand are clear, every partial sum of
+    the n-term sum in worker order is an integer multiple m * sigma with |m| <= 64 and therefore
+    representable, so the f32 sum equals sigma * (n - 2 c) (c = workers whose bit is set) to the
+    bit.  Checked on the sum itself (float64 product against the sequential f32 sum; the same
+    check fails for a scale with a full significand, which is why the condition is there) and on
+    the oracle's server: its message and residual are those of compressing
+    Delta = sigma (n - 2 c) / n + residual formed from the counts."""
+    pe, D = PE, PE + 333
+    short = np.uint32(0x3A83F1C0).view(np.float32)          # about 1.0e-3, 18 significant bits
+    assert int(np.float32(short).view(np.uint32)) & 0x3F == 0 and int(np.float32(0.001).view(np.uint32)) & 0x3F != 0
+    for n in (2, 4, 16, 64):
+        gs = [(rng(90 + i).standard_normal(D) * 1e-3).astype(np.float32) for i in range(n)]
+        neg = np.sum([g < 0 for g in gs], axis=0)
+        for sigma, exact in ((np.float32(short), True), (np.float32(0.001), False)):
+            acc = np.zeros(D, np.float32)
+            for g in gs:                                     # the n-term sum as Algorithm 4 writes it
+                acc = acc + np.where(g < 0, -sigma, sigma).astype(np.float32)
+            product = np.float64(sigma) * (n - 2 * neg)      # exact in float64
+            if exact:
+                assert np.array_equal(acc.astype(np.float64), product), n
+            elif n >= 4:
+                assert not np.array_equal(acc.astype(np.float64), product), n
+        sigma = np.float32(short)
+        scales = np.full((D + pe - 1) // pe, sigma, np.float32)
+        ins = [orc.make_params(orc.SIGN, pe, norm_override=scales) for _ in range(n)]
+        pays = [orc.compress(ins[i], gs[i], None) for i in range(n)]
+        out = orc.make_params(orc.SIGN, pe)
+        et = (rng(7).standard_normal(D) * 2e-4).astype(np.float32)
+        res = et.copy()
+        p_out = orc.server_aggregate(ins, pays, out, res, D)
+        delta = (np.float64(sigma) * (n - 2 * neg)).astype(np.float32) * (np.float32(1.0) / np.float32(n)) + et
+        res2 = np.zeros(D, np.float32)                       # compress(delta, 0): q = delta + 0 = delta
+        assert np.array_equal(p_out, orc.compress(out, delta, res2)) and np.array_equal(res, res2), n
+
+
 @pytest.mark.parametrize("name", ["sign", "topk", "randk", "dither"])
 def test_partitions_under_the_size_threshold_are_carried_as_they_are(orc, name):
     """Section 4.2: what is too small to be worth compressing is sent uncompressed.  With the
