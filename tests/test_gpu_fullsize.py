@@ -256,3 +256,123 @@ def test_full_size_lans_step_over_layer_blocks(env, orc, name, hidden, lr):
     assert gu.lans_step_close(x.cpu().numpy(), xo, x_before, blocks)
     del x, m, v, pay, ws
     torch.cuda.empty_cache()
+
+
+def test_full_size_masked_pipeline_with_a_shared_scale(env, orc):
+    """The bert_base shape (scaled sign, f16 gradients, 16 workers) with what a deployment adds
+    to it (Section 4.2 size threshold; Section 3.2 scaled sign with one scale for all workers):
+    a few partitions bypass compression and the workers all quantise with one short scale per
+    partition, so the server takes the counting form of the sum between runs of bypassed
+    partitions.  Worker 0 and the last worker, the server and an Adam step are compared on
+    every partition with the oracle, partition by partition."""
+    gu, synth, torch = env
+    bpc = gu.bpc
+    w = synth.WORKLOADS["bert_base"]
+    D, n = w["D"], w["n_workers"]
+    assert w["kind"] == "sign" and n == 16
+    pe = synth.part_elems(w["dtype"])
+    P = (D + pe - 1) // pe
+    dev = gu.DEV
+    mask = np.zeros(P, np.uint8)
+    mask[[3, 4, P // 2, P - 1]] = 1
+    # one scale per partition, all short (low six significand bits clear) and different
+    scales = (np.uint32(0x3A83F1C0) + np.arange(P, dtype=np.uint32) * 64).view(np.float32)
+    shared = gu.to_dev(scales)
+
+    def prm_b(stream, shared_scale):
+        return bpc.make_params(bpc.SIGN, pe, stream_id=stream, seed=synth.BASE_SEED, bypass=mask,
+                               norm_override=shared if shared_scale else None)
+
+    def prm_o(stream, part, norm=None):
+        return orc.make_params(orc.IDENTITY if mask[part] else orc.SIGN, pe, stream_id=stream, seed=synth.BASE_SEED,
+                               first_partition=part,
+                               norm_override=None if norm is None else np.array([norm], np.float32))
+
+    p_in = [prm_b((1 << 32) | i, True) for i in range(n)]
+    out_stream = (1 << 32) | (1 << 16)
+    p_out = prm_b(out_stream, False)
+    offs = [bpc.partition_offset(p_out, D, p) for p in range(P)] + [bpc.payload_bytes(p_out, D)]
+    assert offs == sorted(offs) and offs[P] - offs[P - 1] == 16 + 4 * pe      # the last one is bypassed
+    ws = torch.zeros(bpc.workspace_bytes(p_out, D, n), dtype=torch.uint8, device=dev)
+    parts = list(range(P))
+
+    def sl(p):
+        return slice(p * pe, min(D, (p + 1) * pe))
+
+    def defined(p):
+        d = sl(p).stop - sl(p).start
+        return fmt.defined_bytes("identity" if mask[p] else "sign", d)
+
+    def same_record(a, b, p):
+        return all(np.array_equal(a[lo:hi], b[lo:hi]) for lo, hi in defined(p))
+
+    checked = (0, n - 1)
+    pays, g_host, e_host, e_after = [], {}, {}, {}
+    for i in range(n):
+        g = synth.device_gradient(w["dist"], D, w["dtype"], worker=i, device=dev)
+        e = synth.device_gradient("normal", D, "f32", worker=100 + i, device=dev) * 0.3
+        if i in checked:
+            g_host[i], e_host[i] = g.cpu().numpy(), e.cpu().numpy()
+        pay = torch.zeros(offs[P], dtype=torch.uint8, device=dev)
+        bpc.bpc_compress(p_in[i], g, e, pay, ws)
+        bpc.workspace_check(p_out, D, ws)
+        pays.append(pay)
+        if i in checked:
+            e_after[i] = e.cpu().numpy()
+        del g, e
+    pays_host = [pay.cpu().numpy() for pay in pays]
+    for i in checked:
+        def check_worker(p, i=i):
+            res_o = e_host[i][sl(p)].copy()
+            rec_o = orc.compress(prm_o((1 << 32) | i, p, norm=scales[p]), g_host[i][sl(p)], res_o)
+            assert same_record(pays_host[i][offs[p]:offs[p + 1]], rec_o, p), ("worker", i, p)
+            assert np.array_equal(e_after[i][sl(p)].view(np.uint32), res_o.view(np.uint32)), ("worker residual", i, p)
+
+        for_each(parts, check_worker)
+    del g_host, e_host, e_after
+
+    sres = synth.device_gradient("normal", D, "f32", worker=999, device=dev) * 0.2
+    s_host = sres.cpu().numpy()
+    out_pay = torch.zeros(offs[P], dtype=torch.uint8, device=dev)
+    bpc.bpc_server_aggregate(p_in, pays, p_out, sres, D, out_pay, ws)
+    bpc.workspace_check(p_out, D, ws)
+    out_host, sres_host = out_pay.cpu().numpy(), sres.cpu().numpy()
+
+    def check_server(p):
+        d = sl(p).stop - sl(p).start
+        recs = [np.ascontiguousarray(pays_host[i][offs[p]:offs[p + 1]]) for i in range(n)]
+        ins_o = [prm_o((1 << 32) | i, p, norm=scales[p]) for i in range(n)]
+        rec_g = out_host[offs[p]:offs[p + 1]]
+        res_o = s_host[sl(p)].copy()
+        rec_o = orc.server_aggregate(ins_o, recs, prm_o(out_stream, p), res_o, d)
+        if not mask[p]:
+            hg, ho = fmt.header_f32(rec_g), fmt.header_f32(rec_o)
+            assert abs(float(hg) - float(ho)) <= REL * abs(float(ho)), ("server scale", p)
+            if hg != ho:
+                res_o = s_host[sl(p)].copy()
+                rec_o = orc.server_aggregate(ins_o, recs, prm_o(out_stream, p, norm=hg), res_o, d)
+        assert same_record(rec_g, rec_o, p), ("server", p)
+        assert gu.close(sres_host[sl(p)], res_o, REL), ("server residual", p)
+
+    for_each(parts, check_server)
+    del pays, pays_host, sres
+
+    x = synth.device_params(D, device=dev)
+    m = synth.device_gradient("normal", D, "f32", worker=777, device=dev)
+    v = synth.device_gradient("normal", D, "f32", worker=778, device=dev).abs() * 1e-3
+    before = [t.cpu().numpy() for t in (x, m, v)]
+    bpc.bpc_adaptive_update(p_out, out_pay, x, m, v, bpc.make_opt(bpc.OPT_ADAM, 1e-3, 0.9, 0.999, 1e-8, 0.01, 3), ws)
+    bpc.workspace_check(p_out, D, ws)
+    after = [t.cpu().numpy() for t in (x, m, v)]
+
+    def check_adam(p):
+        d = sl(p).stop - sl(p).start
+        xo, mo, vo = (a[sl(p)].copy() for a in before)
+        orc.adaptive_update(prm_o(out_stream, p), np.ascontiguousarray(out_host[offs[p]:offs[p + 1]]), d, xo, mo, vo,
+                            orc.make_opt(orc.OPT_ADAM, 1e-3, 0.9, 0.999, 1e-8, 0.01, 3))
+        for got, ref in zip(after, (xo, mo, vo)):
+            assert np.array_equal(got[sl(p)].view(np.uint32), ref.view(np.uint32)), ("update", p)
+
+    for_each(parts, check_adam)
+    del out_pay, x, m, v, ws
+    torch.cuda.empty_cache()
