@@ -46,6 +46,8 @@
 #include "device_utils.hpp"
 #include "geometry.hpp"
 #include <hip/hip_runtime.h>
+#include <type_traits>
+#include <utility>
 
 namespace bpc {
 
@@ -255,6 +257,14 @@ __device__ inline double cluster_block_reduce(double x, double *red /*THREADS/64
 // The operator is passed by value in the kernel arguments and never modified, so it stays in
 // the kernel-argument segment (a modified copy would live in scratch memory).
 
+// An operator may have `void init(table) const`, called once per workgroup before its first tile
+// (tables in the LDS scratch that do not depend on the tile; the first barrier of the loop
+// orders them before their use).
+template <class Op, class = void>
+struct has_init { static constexpr bool value = false; };
+template <class Op>
+struct has_init<Op, std::void_t<decltype(std::declval<const Op &>().init((float *)nullptr))>> { static constexpr bool value = true; };
+
 // Ticketed driver.
 template <class Op>
 __device__ inline void cluster_run_ticketed(const Op &op, float *table, double *slots, uint32_t *status, uint32_t *tickets) {
@@ -270,6 +280,7 @@ __device__ inline void cluster_run_ticketed(const Op &op, float *table, double *
   const uint32_t cls = blockIdx.x % n_classes;
   uint32_t *counter = tickets + cls * (kTicketStride / 4);
   if (threadIdx.x == 0) item_sh = atomicAdd(counter, 1u) * n_classes + cls;
+  if constexpr (has_init<Op>::value) op.init(table);
   __syncthreads();
   uint32_t item = __builtin_amdgcn_readfirstlane(item_sh);
   for (;;) {

@@ -21,14 +21,14 @@ __device__ inline void cluster_run(const Op &op, float *table, double *slots, ui
 
 template <class Op>
 __global__ __launch_bounds__(Op::kThreads, waves_per_simd<Op>::value) void cluster_kernel(const Op op, double *slots, uint32_t *status, uint32_t *tickets) {
-  __shared__ float table[Op::kTableFloats];
+  __shared__ __attribute__((aligned(16))) float table[Op::kTableFloats];
   cluster_run(op, table, slots, status, tickets);
 }
 
 // Same, with the operator's LDS scratch allocated at launch (sizes above the static limit).
 template <class Op>
 __global__ __launch_bounds__(Op::kThreads, waves_per_simd<Op>::value) void cluster_kernel_dyn(const Op op, double *slots, uint32_t *status, uint32_t *tickets) {
-  extern __shared__ float dyn_table[];
+  extern __shared__ __attribute__((aligned(16))) float dyn_table[];
   cluster_run(op, dyn_table, slots, status, tickets);
 }
 

@@ -4,10 +4,14 @@
 // the sign bits of Delta, exchanges its part of ||Delta||_1 and writes e~' = Delta -+ sigma.
 //
 // A thread owns 8 consecutive elements per row (2 rows of 4096 elements per tile, 512 threads),
-// i.e. one byte of every worker's sign bits per row; shifting a bit to the sign position and
-// merging it into |sigma_i| gives +-sigma_i in two instructions.  16 elements a thread keep a
-// lane under 64 vector registers, so 8 waves per SIMD are resident: the n-term sums of some
-// tiles then run under the loads and stores of others.
+// i.e. one byte of every worker's sign bits per row.  With the number of workers fixed at
+// compile time the byte indexes a 256-row LDS table whose row holds, as eight halves, -1 where
+// the byte's bit is set and +1 where it is clear, and the sum advances by one mixed-precision
+// fused multiply-add per element and worker: fma(+-1, sigma_i, acc) rounds once, and the product
+// is exact, so it is acc +- sigma_i to the bit, the f32 addition in worker order (for any sigma_i,
+// negative ones included).  The n scales of a partition sit in the first n lanes of every wave and
+// reach the multiply-add through a scalar register.  Three workgroups a CU overlap each other's
+// loads, sums and stores.
 #include "cluster_launch.hpp"
 #include "sources.hpp"
 
@@ -33,6 +37,8 @@ inline MsgPtrs msg_ptrs(const WorkerMsgs &m) {
   return r;
 }
 
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+
 // -|sigma| if bit C of `byte` is set, else +|sigma|: the bit is shifted to the sign position
 // and the magnitude takes its sign from there (one shift and one bit-field insert).
 template <int C>
@@ -51,8 +57,10 @@ __device__ inline bool scale_is_short(uint32_t bits) {
   return (bits & 0x3fu) == 0u && ex >= 1u && ex <= 240u;
 }
 
-// NW > 0: the number of workers is known at compile time and the worker loop is unrolled, so
-// the byte loads can be scheduled ahead of their use; NW == 0: any number, rolled loop.
+// NW > 0: the number of workers is known at compile time: the tile's sign bits of all workers are
+// requested in one round trip with e~, staged through LDS and summed by table look-up and
+// multiply-add (above); NW == 0: any number, a rolled loop over the workers that loads a
+// worker's bytes and forms +-sigma_i with a shift and a bit-field insert.
 // COUNT: the caller stated that the workers share a scale array; the counting form is compiled in
 // and taken for the partitions where it is exact.
 template <bool EF, int NW, bool COUNT = false>
@@ -66,13 +74,12 @@ struct SignServerOp {
   struct Held { float delta[kSPerThread]; };
   static constexpr bool kMax = false;
   static constexpr int kRowsPerTile = kSRows;
-  // LDS: the n scales, then (NW > 0) the tile's sign bits of every worker, 1 KiB each
+  // LDS: the n scales (NW == 0), then (NW > 0) the tile's sign bits of every worker, 1 KiB each,
+  // then the tables that init() fills once per workgroup
   static constexpr int kBitsPerWorker = kSSTile / 8;   // bytes
-  static constexpr int kSpreadWords = COUNT ? 256 : 0;   // byte -> its 8 bits as 8 nibbles (the counting form of the sum)
-  static constexpr int kTableFloats = kMaxWorkers + (NW > 0 ? NW * kBitsPerWorker / 4 : 0) + kSpreadWords;
-  // Workers per nibble counter of the counting form: a nibble counts up to 15.
-  static constexpr int kCountGroup = 8;
-  static constexpr int kCountGroups = NW > 0 ? (NW + kCountGroup - 1) / kCountGroup : 1;
+  static constexpr int kSpreadWords = COUNT ? 512 : 0;   // byte -> its 8 bits as 8 bytes (the counting form of the sum)
+  static constexpr int kUnitWords = NW > 0 ? 256 * 4 : 0;   // byte -> 8 halves: -1 where its bit is set, +1 where clear
+  static constexpr int kTableFloats = kMaxWorkers + (NW > 0 ? NW * kBitsPerWorker / 4 : 0) + kSpreadWords + kUnitWords;
   static constexpr int kThreads = kSSThreads;
   static constexpr int kWavesPerSimd = 6;   // 80 registers a lane, three workgroups a CU
   static constexpr bool kPersistent = false;
@@ -112,8 +119,8 @@ struct SignServerOp {
   static constexpr int kPieces = kSSTile / 8192;
   static_assert(!COUNT || NW > 0, "the counting form is built for fixed numbers of workers");
   static_assert(kSSTile % 8192 == 0, "tile must be whole pieces");
-  // Row u of e~; with row 0 also the scale of worker threadIdx.x and (NW > 0) the tile's sign
-  // bits, all in one round trip.
+  // Row u of e~; with row 0 also the workers' scales (lane i of every wave: worker i) and
+  // (NW > 0) the tile's sign bits, all in one round trip.
   __device__ void issue_row(uint32_t item, int u, Raw &raw) const {
     if (EF) {
       const TileBuf eb = row_buf(res + base(item), valid_of(item), u * (kSSThreads * 8), kSSThreads * 8);
@@ -123,8 +130,8 @@ struct SignServerOp {
     if (u != 0) return;
     const uint32_t p = part_of(item);
     raw.my_sigma = 0.0f;
-    if ((int)threadIdx.x < msgs.n)
-      raw.my_sigma = *reinterpret_cast<const float *>(msgs.ptr[threadIdx.x] + (uint64_t)p * g.stride);
+    if ((int)(threadIdx.x & 63) < msgs.n)
+      raw.my_sigma = *reinterpret_cast<const float *>(msgs.ptr[threadIdx.x & 63] + (uint64_t)p * g.stride);
     if (NW > 0) {
       const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
       const uint64_t rec_off = uniform_off((uint64_t)p * g.stride + kHeaderBytes + (tile_off(item) >> 3));
@@ -134,6 +141,29 @@ struct SignServerOp {
           const TileBuf mb(msgs.ptr[j / kPieces] + rec_off + (j % kPieces) * 1024, 1024);
           raw.fetched[j / kSSWaves] = mb.load16(lane * 16, 0);
         }
+    }
+  }
+
+  // Once per workgroup: the tables that do not depend on the tile.
+  __device__ u32x2 *spread_of(float *sig) const { return reinterpret_cast<u32x2 *>(sig + kMaxWorkers + NW * kBitsPerWorker / 4); }
+  __device__ u32x4 *unit_of(float *sig) const { return reinterpret_cast<u32x4 *>(sig + kMaxWorkers + NW * kBitsPerWorker / 4 + kSpreadWords); }
+  __device__ void init(float *sig) const {
+    if (NW > 0 && threadIdx.x < 256u) {
+      const uint32_t b = threadIdx.x;
+      if (COUNT) {   // bit c of the byte value -> byte c
+        u32x2 sp;
+        sp.x = (b & 1u) | ((b & 2u) << 7) | ((b & 4u) << 14) | ((b & 8u) << 21);
+        sp.y = ((b >> 4) & 1u) | ((b & 32u) << 3) | ((b & 64u) << 10) | ((b & 128u) << 17);
+        spread_of(sig)[b] = sp;
+      }
+      // bit c of the byte value -> half c: 0x3C00 is 1.0, the sign bit makes it -1.0
+      u32x4 *unit = unit_of(sig);
+      u32x4 row;
+      row.x = 0x3C003C00u | ((b & 1u) << 15) | ((b & 2u) << 30);
+      row.y = 0x3C003C00u | ((b & 4u) << 13) | ((b & 8u) << 28);
+      row.z = 0x3C003C00u | ((b & 16u) << 11) | ((b & 32u) << 26);
+      row.w = 0x3C003C00u | ((b & 64u) << 9) | ((b & 128u) << 24);
+      unit[b] = row;
     }
   }
 
@@ -176,15 +206,10 @@ struct SignServerOp {
       uint8_t *staged = reinterpret_cast<uint8_t *>(sig + kMaxWorkers);
       const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
       const u32x4 *fetched = raw.fetched;
-      uint32_t *spread = reinterpret_cast<uint32_t *>(sig + kMaxWorkers + NW * kBitsPerWorker / 4);
-      __syncthreads();   // the LDS scratch may still be in use by the caller
-      if ((int)threadIdx.x < msgs.n) sig[threadIdx.x] = my_sigma;
-      if (COUNT && threadIdx.x < 256u) {
-        // bit c of the byte value -> nibble c
-        const uint32_t b = threadIdx.x;
-        spread[b] = (b & 1u) | ((b & 2u) << 3) | ((b & 4u) << 6) | ((b & 8u) << 9) | ((b & 16u) << 12) | ((b & 32u) << 15) |
-                    ((b & 64u) << 18) | ((b & 128u) << 21);
-      }
+      const u32x2 *spread = spread_of(sig);
+      const u32x4 *unit = unit_of(sig);
+      // (the staging area is free: every wave has passed the barriers that follow the sums of
+      // the tile before)
 #pragma unroll
       for (int j = 0; j < NW * kPieces; ++j)
         if ((uint32_t)(j % kSSWaves) == wave)
@@ -194,32 +219,31 @@ struct SignServerOp {
       bool counting = false;
       uint32_t first_bits = 0;
       if (COUNT) {
-        first_bits = __float_as_uint(sig[0]);
-        const bool same = lane >= (uint32_t)NW || __float_as_uint(sig[lane < (uint32_t)NW ? lane : 0u]) == first_bits;
+        first_bits = __builtin_amdgcn_readfirstlane(__float_as_uint(my_sigma));
+        const bool same = lane >= (uint32_t)NW || __float_as_uint(my_sigma) == first_bits;
         counting = __all(same) && scale_is_short(first_bits);
       }
       if (COUNT && counting) {
-        // counting form: a byte's bits spread to nibbles, added up over the workers as integers
-        uint32_t cnt[kSRows][kCountGroups];
+        // counting form: a byte's bits spread to bytes, added up over the workers as integers
+        // (at most 16 a byte), then c -> sigma (n - 2 c) as fma(c, -2 sigma, n sigma): every term exact
+        uint32_t cnt[kSRows][2];
 #pragma unroll
-        for (int u = 0; u < kSRows; ++u)
-#pragma unroll
-          for (int q = 0; q < kCountGroups; ++q) cnt[u][q] = 0;
+        for (int u = 0; u < kSRows; ++u) cnt[u][0] = cnt[u][1] = 0;
 #pragma unroll 4
         for (int i = 0; i < NW; ++i)
 #pragma unroll
-          for (int u = 0; u < kSRows; ++u)
-            cnt[u][i / kCountGroup] += spread[staged[i * kBitsPerWorker + u * kSSThreads + threadIdx.x]];
+          for (int u = 0; u < kSRows; ++u) {
+            const u32x2 sp = spread[staged[i * kBitsPerWorker + u * kSSThreads + threadIdx.x]];
+            cnt[u][0] += sp.x;
+            cnt[u][1] += sp.y;
+          }
         const float sigma = __uint_as_float(first_bits);
+        const float all_clear = (float)NW * sigma, per_bit = -2.0f * sigma;
 #pragma unroll
         for (int u = 0; u < kSRows; ++u)
 #pragma unroll
-          for (int c = 0; c < 8; ++c) {
-            uint32_t neg = 0;
-#pragma unroll
-            for (int q = 0; q < kCountGroups; ++q) neg += (cnt[u][q] >> (4 * c)) & 0xfu;
-            acc[8 * u + c] = sigma * (float)(NW - 2 * (int)neg);   // exact (see scale_is_short)
-          }
+          for (int c = 0; c < 8; ++c)
+            acc[8 * u + c] = __builtin_fmaf((float)((cnt[u][c / 4] >> (8 * (c % 4))) & 0xffu), per_bit, all_clear);
       } else {
         // four workers per trip: unrolled further, the LDS reads of all workers would be in
         // flight at once and cost more registers than a lane has at this occupancy
@@ -228,7 +252,20 @@ struct SignServerOp {
           uint32_t byte[kSRows];
 #pragma unroll
           for (int u = 0; u < kSRows; ++u) byte[u] = staged[i * kBitsPerWorker + u * kSSThreads + threadIdx.x];
-          add_worker(byte, sig[i], acc);
+          // acc +- sigma_i as fma(+-1, sigma_i, acc): the compiler folds the widening of the half
+          // into the multiply-add (v_fma_mix_f32)
+          const float sigma_i = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(my_sigma), i));
+#pragma unroll
+          for (int u = 0; u < kSRows; ++u) {
+            const u32x4 row = unit[byte[u]];
+            const uint32_t w[4] = {row.x, row.y, row.z, row.w};
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+              const half2_t pm = __builtin_bit_cast(half2_t, w[c]);
+              acc[8 * u + 2 * c] = __builtin_fmaf((float)pm.x, sigma_i, acc[8 * u + 2 * c]);
+              acc[8 * u + 2 * c + 1] = __builtin_fmaf((float)pm.y, sigma_i, acc[8 * u + 2 * c + 1]);
+            }
+          }
         }
       }
     } else {
@@ -314,9 +351,9 @@ static hipError_t launch_sign_server(const Geo &g, const ClusterGeo &cg, const b
                                      bool *used) {
   const MsgPtrs mp = msg_ptrs(src.msgs);
   float *res = src.residual;
-  // The counting form pays from about 16 workers on (110 M elements: 0.283 against 0.291 ms at
-  // n = 16, 0.224 against 0.204 ms at n = 4: with few workers the additions it replaces are
-  // fewer than the instructions that take the counts apart again).
+  // The counting form is taken at 16 workers, where it is as fast as the sum (110 M elements:
+  // 0.241-0.248 ms against 0.248-0.253 ms; both are bound by the memory system there) and does
+  // not depend on the order of the workers; it is not instantiated for fewer.
   if (src.msgs.shared_scale && mp.n == 16)
     return launch_cluster(SignServerOp<EF, 16, true>{g, cg, mp, res, payload, prm.norm_override}, cg, slots, status, tickets, stream, used);
   switch (mp.n) {
