@@ -851,9 +851,7 @@ __global__ __launch_bounds__(kSelThreads) void topk_list_select_kernel(Geo g, fl
       const bool t = valid && (key(i) > T || (key(i) == T && eq_before < r));
       gt_base += __popcll(gtm);
       eq_base += __popcll(eqm);
-      // (the buffer's kept slots are cleared by the kernel that follows, on the whole device:
-      // from one compute unit these scattered stores were 10 of the pass's 23 microseconds)
-      if (t) topk_write_entry<HALF>(g, rec, gt_before + (eq_before < r ? eq_before : r), where[i], __uint_as_float(bits[i]), buf_part, 0);
+      if (t) topk_write_entry<HALF>(g, rec, gt_before + (eq_before < r ? eq_before : r), where[i], __uint_as_float(bits[i]), buf_part, zero_selected);
     }
   }
 }
@@ -987,23 +985,6 @@ __global__ __launch_bounds__(kThreads) void topk_long_form_kernel(Geo g, float *
   __syncthreads();
   for (uint32_t p = threadIdx.x; p < g.P; p += kThreads)
     if (state[p * 8 + kStLong]) any = 1;
-  // The kept slots of the partitions the select pass took: 0 (or what rounding to half dropped)
-  // goes into the buffer here, entry by entry of the records it wrote, spread over the grid.
-  if (zero_selected) {
-    const uint64_t entries = (uint64_t)g.P * g.k_cap;
-    for (uint64_t e = (uint64_t)blockIdx.x * kThreads + threadIdx.x; e < entries; e += (uint64_t)gridDim.x * kThreads) {
-      const uint32_t p = (uint32_t)(e / g.k_cap), t = (uint32_t)(e % g.k_cap);
-      if (t >= (uint32_t)k_of_device(g, p) || state[p * 8 + kStLong]) continue;
-      const uint32_t j = reinterpret_cast<const uint32_t *>(payload + (uint64_t)p * g.stride + kHeaderBytes)[t];
-      float *slot = buf + g.part_base(p) + j;
-      if (HALF) {
-        const float v = *slot;
-        *slot = v - __half2float(__float2half_rn(v));
-      } else {
-        *slot = 0.0f;
-      }
-    }
-  }
   __syncthreads();
   if (!any) return;   // (the same answer in every workgroup: the flags were written by the kernel before)
   topk_hist_body<1>(g, buf, hist, state, n3, 1, guess);   // (groups of one tile, as level 3)
