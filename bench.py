@@ -35,6 +35,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="bert_large")
     ap.add_argument("--no-others", action="store_true", help="skip the secondary workloads")
+    ap.add_argument("--worker-streams", type=int, default=2, choices=(1, 2),
+                    help="streams the workers of the sparse kinds take turns on")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--cpu-partitions", type=int, default=8, help="partitions in the CPU sample")
     ap.add_argument("--cpu-steps", type=int, default=6, help="pipeline steps the CPU sample runs")
@@ -80,7 +82,7 @@ def algorithmic_bytes_per_elem(w):
 class Pipeline:
     """Device state of one workload and the three stage calls."""
 
-    def __init__(self, name, w, torch, bpc, synth):
+    def __init__(self, name, w, torch, bpc, synth, worker_streams=2):
         self.name, self.w, self.torch, self.bpc = name, w, torch, bpc
         dev = "cuda"
         self.D, self.n = w["D"], w["n_workers"]
@@ -108,7 +110,7 @@ class Pipeline:
         # pass; the server call joins them.  (The single-pass kernels of the other kinds fill the
         # device and are kept apart by the library anyway.)
         self.side = []
-        if w["kind"] in ("topk", "topk16", "randk") and self.n > 1:
+        if w["kind"] in ("topk", "topk16", "randk") and self.n > 1 and worker_streams > 1:
             self.side = [torch.cuda.Stream(), torch.cuda.Stream()]
             self.ws_side = [torch.empty_like(self.ws) for _ in self.side]
         self.x = synth.device_params(self.D, device=dev)
@@ -193,8 +195,8 @@ def timed(torch, fn, reps):
     return per_call[mid] if reps % 2 else 0.5 * (per_call[mid - 1] + per_call[mid])
 
 
-def run_workload(name, w, steps, warmup, torch, bpc, synth):
-    pipe = Pipeline(name, w, torch, bpc, synth)
+def run_workload(name, w, steps, warmup, torch, bpc, synth, worker_streams=2):
+    pipe = Pipeline(name, w, torch, bpc, synth, worker_streams)
     for _ in range(warmup):
         pipe.step()
     torch.cuda.synchronize()
@@ -369,12 +371,13 @@ def main():
         sys.exit(2)
     bpc.lib()   # raises if the HIP library was not built: there is no fallback
     torch.cuda.set_device(0)
-    head = run_workload(args.workload, synth.WORKLOADS[args.workload], args.steps, args.warmup, torch, bpc, synth)
+    head = run_workload(args.workload, synth.WORKLOADS[args.workload], args.steps, args.warmup, torch, bpc, synth,
+                        args.worker_streams)
     others = []
     if not args.no_others:
         for name, w in synth.WORKLOADS.items():
             if name != args.workload:
-                others.append(run_workload(name, w, max(3, args.steps // 2), 2, torch, bpc, synth))
+                others.append(run_workload(name, w, max(3, args.steps // 2), 2, torch, bpc, synth, args.worker_streams))
     w = synth.WORKLOADS[args.workload]
     # dominant stage of the step: the worker compress call runs n times per step
     dom = max(("W", "S", "U"), key=lambda k: head["stages"][k]["ms"] * (w["n_workers"] if k == "W" else 1))
