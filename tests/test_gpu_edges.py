@@ -342,6 +342,41 @@ def test_sign_server_with_a_shared_scale(gu, orc, n, scale_bits):
                 assert gu.close(res_gpu, res_ref, REL)
 
 
+@pytest.mark.parametrize("n", [16, 8, 3])
+@pytest.mark.parametrize("case", ["subnormal", "mixed", "huge", "zero_and_negative"])
+def test_sign_server_scales_at_the_ends_of_the_float_range(gu, orc, n, case):
+    """The n-term sum of +-sigma_i with scales that are subnormal, zero, negative, or so large that
+    the sum comes near the end of the range: the card's sum (a fused multiply-add by +-1 per worker
+    for 4, 8 and 16 workers; a rolled loop of additions for other n) must give what the oracle's
+    additions in worker order give, subnormal results and signed zeros included.  The outgoing
+    scale is handed to both sides, so the message and the residual are compared bit for bit."""
+    D = 2 * PE + 4137
+    n_parts = len(fmt.part_sizes(D, PE))
+    rs = np.random.default_rng(5 + n)
+    pick = {"subnormal": [1e-40, 3e-39, 7e-45, 1.1e-38],
+            "mixed": [1e-40, 2.5e-3, 1e-38, 3.0, 1e-20],
+            "huge": [1e37, 2e37, 5e36],
+            "zero_and_negative": [0.0, -0.0, -1e-3, 2e-3, -3e-40]}[case]
+    ins, payloads = [], []
+    for i in range(n):
+        scales = np.full(n_parts, pick[i % len(pick)], np.float32)
+        po, pb = gu.both_params(orc, "sign", PE, norm_override=scales)
+        ins.append((po, pb))
+        payloads.append(orc.compress(po, (rs.standard_normal(D) * 1e-3).astype(np.float32), None))
+    mag = {"subnormal": 1e-40, "mixed": 1e-3, "huge": 1e36, "zero_and_negative": 1e-4}[case]
+    out_scale = np.full(n_parts, mag, np.float32)
+    out_o, out_b = gu.both_params(orc, "sign", PE, norm_override=out_scale)
+    plain = [gu.bpc.make_params(gu.bpc.SIGN, PE) for _ in range(n)]
+    for ef in (True, False):
+        et = (rs.standard_normal(D) * mag).astype(np.float32) if ef else None
+        res_ref = None if et is None else et.copy()
+        pay_ref = orc.server_aggregate([p[0] for p in ins], payloads, out_o, res_ref, D)
+        pay_gpu, res_gpu = gu.gpu_server(plain, payloads, out_b, None if et is None else et.copy(), D)
+        assert defined_equal("sign", pay_gpu, pay_ref, out_o, orc, D, PE, {})
+        if ef:
+            assert np.array_equal(res_gpu.view(np.uint32), res_ref.view(np.uint32))
+
+
 def test_fp16_conversion_at_the_ends_of_the_half_range(gu, orc):
     """Round to nearest even on the card as in the oracle: ties, the subnormal halves, what
     rounds up to infinity (its residual is then -inf / +inf on both sides)."""
