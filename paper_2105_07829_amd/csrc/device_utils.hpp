@@ -89,6 +89,10 @@ struct TileBuf {
     __builtin_amdgcn_raw_buffer_store_b8((uint8_t)v, r, (int)lane_off, (int)row_off, AUX);
   }
   template <int AUX = 0>
+  __device__ void store2(uint32_t v, uint32_t lane_off, uint32_t row_off) const {
+    __builtin_amdgcn_raw_buffer_store_b16((uint16_t)v, r, (int)lane_off, (int)row_off, AUX);
+  }
+  template <int AUX = 0>
   __device__ void store4(uint32_t v, uint32_t lane_off, uint32_t row_off) const {
     __builtin_amdgcn_raw_buffer_store_b32(v, r, (int)lane_off, (int)row_off, AUX);
   }

@@ -1,48 +1,32 @@
 // Linear-dithering worker, single pass (Algorithm 4 worker lines with the stochastic
-// multi-level quantiser): a workgroup reads a tile (16384 elements) of g and e once, keeps
+// multi-level quantiser): a workgroup reads a tile (8192 elements) of g and e once, keeps
 // q = g + e in registers, publishes its part of ||q||_2^2 (or max |q|), waits for the
 // partition's norm, then draws the levels, writes the packed nibbles and e' = q - decode.
 #include "dither_common.hpp"
+#include "tile_rows.hpp"
 
 namespace bpc {
 
-// 1024 threads (one workgroup a CU) and 16 elements a thread, as in the scaled-sign worker.
-constexpr int kDWThreads = 1024;
+// 512 threads (two workgroups a CU) and 16 elements a thread, laid out as in the scaled-sign
+// worker: 4 rows of 2048 elements, a thread owns 4 consecutive elements per row -- one Philox
+// block -- so every 16-byte access of a wave covers whole cache lines and is marked
+// non-temporal.  The four nibbles of a thread and row are two bytes of the record, which every
+// lane stores for itself with a plain store (small stores with the non-temporal hint slow the
+// whole kernel down).  With one workgroup of 1024 threads a CU the quantiser (2.7 us of vector
+// instructions a tile) ran between the workgroup's memory phases; two workgroups run it under
+// each other's (336 M f16 elements: 0.712 -> 0.668 ms; with 8 consecutive elements a thread,
+// i.e. two 16-byte halves per 32 bytes, the access pattern set the time: 0.69 ms with or
+// without the arithmetic).
+constexpr int kDWThreads = 512;
 constexpr int kDWPer = 16;
 constexpr int kDWTile = kDWThreads * kDWPer;
-constexpr int kDRows = kDWPer / 8;  // rows of kDWThreads * 8 elements; a thread owns 8 consecutive per row
-
-struct F32x8 { u32x4 a, b; };
-template <class G> struct Vec8Of;
-template <> struct Vec8Of<float> { using type = F32x8; };
-template <> struct Vec8Of<__half> { using type = u32x4; };
-
-__device__ inline void widen8(const F32x8 &g, float out[8]) {
-  out[0] = __uint_as_float(g.a.x); out[1] = __uint_as_float(g.a.y); out[2] = __uint_as_float(g.a.z); out[3] = __uint_as_float(g.a.w);
-  out[4] = __uint_as_float(g.b.x); out[5] = __uint_as_float(g.b.y); out[6] = __uint_as_float(g.b.z); out[7] = __uint_as_float(g.b.w);
-}
-__device__ inline void widen8(const u32x4 &g, float out[8]) {
-  const uint32_t w[4] = {g.x, g.y, g.z, g.w};
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    float2 f = __half22float2(*reinterpret_cast<const __half2 *>(&w[i]));
-    out[2 * i] = f.x;
-    out[2 * i + 1] = f.y;
-  }
-}
-// 8 consecutive gradient elements of thread t in row u of a tile window
-__device__ inline F32x8 tile_load8(const TileBuf &b, int u, const float *) {
-  return {b.load16(threadIdx.x * 32, u * (kDWThreads * 32)), b.load16(threadIdx.x * 32 + 16, u * (kDWThreads * 32))};
-}
-__device__ inline u32x4 tile_load8(const TileBuf &b, int u, const __half *) {
-  return b.load16(threadIdx.x * 16, u * (kDWThreads * 16));
-}
+constexpr int kDRows = kDWPer / 4;  // rows of kDWThreads * 4 elements; a thread owns 4 consecutive per row
 
 // WIDE: linear levels beyond 7, whose upper level bits go to the record's bit planes.
 template <class G, bool EF, bool LINF, bool NAT, bool WIDE = false>
 struct DitherWorkerOp {
-  using GV = typename Vec8Of<G>::type;
-  struct Raw { GV g[kDRows]; F32x8 e[kDRows]; };
+  using GV = typename Vec4Of<G>::type;
+  struct Raw { GV g[kDRows]; u32x4 e[kDRows]; };
   struct Held { float q[kDWPer]; };
   static constexpr bool kMax = LINF;
   static constexpr int kRowsPerTile = kDRows;
@@ -80,8 +64,12 @@ struct DitherWorkerOp {
     return __builtin_amdgcn_readfirstlane(left < (uint32_t)kDWTile ? left : (uint32_t)kDWTile);
   }
   __device__ void issue_row(uint32_t item, int u, Raw &raw) const {
-    raw.g[u] = tile_load8(TileBuf(grad + base(item), valid_of(item) * sizeof(G)), u, grad);
-    if (EF) raw.e[u] = tile_load8(TileBuf(res + base(item), valid_of(item) * 4), u, (const float *)nullptr);
+    const TileBuf gb(grad + base(item), valid_of(item) * sizeof(G));
+    raw.g[u] = tile_load4(gb, threadIdx.x * (4 * sizeof(G)), u * (kDWThreads * 4 * sizeof(G)), grad);
+    if (EF) {
+      const TileBuf eb(res + base(item), valid_of(item) * 4);
+      raw.e[u] = eb.load16<kNonTemporal>(threadIdx.x * 16, u * (kDWThreads * 16));
+    }
   }
 
   __device__ double phase1(uint32_t, Raw &raw, Held &h, float *) const {
@@ -89,14 +77,14 @@ struct DitherWorkerOp {
     float mx = 0.0f;
 #pragma unroll
     for (int u = 0; u < kDRows; ++u) {
-      float w[8];
-      widen8(raw.g[u], w);
-      float e[8];
-      widen8(raw.e[u], e);
+      float w[4];
+      widen4(raw.g[u], w);
+      float e[4];
+      widen4(raw.e[u], e);
 #pragma unroll
-      for (int c = 0; c < 8; ++c) {
+      for (int c = 0; c < 4; ++c) {
         float q = EF ? w[c] + e[c] : w[c];
-        h.q[8 * u + c] = q;
+        h.q[4 * u + c] = q;
         if (LINF) mx = fmaxf(mx, fabsf(q));
         else acc = fma((double)q, (double)q, acc);
       }
@@ -136,44 +124,45 @@ struct DitherWorkerOp {
     const float *mag = ctx.mag;
     const uint32_t p = part_of(item);
     const Philox rng(seed, stream_id, p + g.part0);
-    const uint64_t b = base(item);
-    uint32_t *nibs = reinterpret_cast<uint32_t *>(payload + (uint64_t)p * g.stride + kHeaderBytes);
-    const uint32_t off = (u * kDWThreads + threadIdx.x) * 8;  // within the tile
-    const uint32_t j0 = tile_off(item) + off;                // within the partition
-    uint32_t word = 0, hi[3] = {0, 0, 0};
-    float r[8];
+    const uint32_t t = threadIdx.x;
+    const uint32_t j0 = tile_off(item) + (u * kDWThreads + t) * 4;   // within the partition: one Philox block
+    uint32_t nibs = 0, hi[3] = {0, 0, 0};
+    float r[4];
     if (MODE == 0) {
 #pragma unroll
-      for (int c = 0; c < 8; ++c) r[c] = h.q[8 * u + c];
+      for (int c = 0; c < 4; ++c) r[c] = h.q[4 * u + c];
     } else {
-      uint32_t rnd[8];
+      uint32_t rnd[4];
       rng.block(j0 >> 2, rnd);
-      rng.block((j0 >> 2) + 1, rnd + 4);
 #pragma unroll
-      for (int c = 0; c < 8; ++c) {
-        const uint32_t code = dither_quantise<MODE == 2, NAT, WIDE>(h.q[8 * u + c], nu, top_over_nu, top, levels, rnd[c], mag, &r[c]);
+      for (int c = 0; c < 4; ++c) {
+        const uint32_t code = dither_quantise<MODE == 2, NAT, WIDE>(h.q[4 * u + c], nu, top_over_nu, top, levels, rnd[c], mag, &r[c]);
         if (WIDE) {
-          word |= (((code >> 6) << 3) | (code & 7u)) << (4 * c);
+          nibs |= (((code >> 6) << 3) | (code & 7u)) << (4 * c);
 #pragma unroll
-          for (int t = 0; t < 3; ++t) hi[t] |= ((code >> (3 + t)) & 1u) << c;
+          for (int k = 0; k < 3; ++k) hi[k] |= ((code >> (3 + k)) & 1u) << c;
         } else {
-          word |= code << (4 * c);
+          nibs |= code << (4 * c);
         }
       }
     }
-    TileBuf(nibs + (tile_off(item) >> 3), kDWTile / 2).store4(word, threadIdx.x * 4, u * (kDWThreads * 4));
+    // the four nibbles of this lane: two bytes of the record (a plain store: marked non-temporal,
+    // stores this small slow the whole kernel down)
+    uint8_t *rec = payload + (uint64_t)p * g.stride;
+    const TileBuf nb(rec + kHeaderBytes + (tile_off(item) >> 1), kDWTile / 2);
+    nb.store2(nibs, t * 2, u * (kDWThreads * 2));
     if (WIDE) {
-      // one byte per thread and plane: bit c = bit 3 + t of the level of the thread's element c
-      const uint8_t *rec = payload + (uint64_t)p * g.stride;
+      // a plane holds one bit per element: eight lanes make a word, which lane 8w stores
       const uint32_t planes = dither_planes(levels);
-      for (uint32_t t = 0; t < planes; ++t)
-        TileBuf(rec + dither_plane0(g.part_elems) + t * dither_plane_bytes(g.part_elems) + (tile_off(item) >> 3), kDWTile / 8)
-            .store1(hi[t], threadIdx.x, u * kDWThreads);
+      for (uint32_t k = 0; k < planes; ++k) {
+        const uint32_t pw = merge8(hi[k]);
+        const TileBuf pb(rec + dither_plane0(g.part_elems) + k * dither_plane_bytes(g.part_elems) + (tile_off(item) >> 3), kDWTile / 8);
+        if ((t & 7) == 0) pb.store4(pw, (t >> 3) * 4, u * (kDWThreads * 4 / 8));
+      }
     }
     if (EF) {
-      const TileBuf ob = row_buf(res + b, valid_of(item), u * (kDWThreads * 8), kDWThreads * 8);
-      ob.store16(as_u32x4(r[0], r[1], r[2], r[3]), threadIdx.x * 32);
-      ob.store16(as_u32x4(r[4], r[5], r[6], r[7]), threadIdx.x * 32 + 16);
+      const TileBuf ob = row_buf(res + base(item), valid_of(item), u * (kDWThreads * 4), kDWThreads * 4);
+      ob.store16<kNonTemporal>(as_u32x4(r[0], r[1], r[2], r[3]), t * 16);
     }
   }
 
