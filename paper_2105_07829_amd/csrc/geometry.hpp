@@ -18,7 +18,7 @@ constexpr int kMaxWorkers = 64;      // most worker messages one aggregate call 
 constexpr int kTile = 4096;          // elements one workgroup handles in the streaming kernels
 constexpr int kThreads = 256;        // workgroup size of the streaming kernels
 constexpr int kSThreads = 256;       // workgroup size of the server-side kernels when the number of workers is not one they are compiled for
-constexpr int kWTile = 16384;        // tile of the worker-side single-pass kernels (1024 threads x 16 elements)
+constexpr int kWTile = 8192;         // tile of the worker-side single-pass kernels (512 threads x 16 elements)
 constexpr int kSTile = 8192;         // tile of the server-side single-pass kernels and of single-pass LANS
 constexpr uint32_t kHeaderBytes = 16;
 constexpr int kTicketClasses = 16;   // counters the ticketed single-pass kernels draw their tiles from (workgroup w uses counter w % 16)

@@ -1,5 +1,5 @@
 // Scaled-sign worker, single pass (Algorithm 4 worker lines with C(v) = ||v||_1/d sign(v)):
-// each workgroup reads a tile (16384 elements) of g and e once, keeps q = g + e in registers,
+// each workgroup reads a tile (8192 elements) of g and e once, keeps q = g + e in registers,
 // writes the sign bits, publishes its part of ||q||_1, waits for the partition's sum and then
 // writes e' = q -+ sigma.  HBM traffic is the algorithmic minimum: g and e read once, e' and
 // the bits written once.
@@ -7,9 +7,11 @@
 
 namespace bpc {
 
-// 1024 threads (one workgroup a CU) and 16 elements a thread: q of two tiles (the current one
-// and the one awaiting its total) and the loads of a third fit the registers.
-constexpr int kSWThreads = 1024;
+// 512 threads (two workgroups a CU) and 16 elements a thread: q of two tiles (the current one
+// and the one awaiting its total) and the loads of a third fit the registers.  (One workgroup of
+// 1024 threads a CU took as long at 336 M f16 elements and 2-6 % longer at 110 M and with f32
+// gradients.)
+constexpr int kSWThreads = 512;
 constexpr int kSWPer = 16;
 constexpr int kSWTile = kSWThreads * kSWPer;
 constexpr int kRows = kSWPer / 4;  // rows of kSWThreads * 4 elements; a thread owns 4 consecutive per row
