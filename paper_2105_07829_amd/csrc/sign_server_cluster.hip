@@ -3,16 +3,20 @@
 // tile of e~ and the matching bits of the n messages once, keeps Delta in registers, writes
 // the sign bits of Delta, exchanges its part of ||Delta||_1 and writes e~' = Delta -+ sigma.
 //
-// A thread owns 8 consecutive elements per row (2 rows of 4096 elements per tile, 512 threads),
-// i.e. one byte of every worker's sign bits per row.  With the number of workers fixed at
-// compile time the byte indexes a 256-row LDS table whose row holds, as eight halves, -1 where
-// the byte's bit is set and +1 where it is clear, and the sum advances by one mixed-precision
-// fused multiply-add per element and worker: fma(+-1, sigma_i, acc) rounds once, and the product
-// is exact, so it is acc +- sigma_i to the bit, the f32 addition in worker order (for any sigma_i,
-// negative ones included).  The n scales of a partition sit in the first n lanes of every wave and
-// reach the multiply-add through a scalar register.  Three workgroups a CU overlap each other's
-// loads, sums and stores.
-#include "cluster_launch.hpp"
+// A thread owns 8 elements per row (2 rows of 4096 elements per tile, 512 threads): a wave takes
+// 512 consecutive elements of a row, lane l the four elements from 4 l and the four from
+// 256 + 4 l, so that every 16-byte access of a wave to e~ covers whole cache lines and is marked
+// non-temporal.  Its share of a worker's sign bits is then two nibbles 32 bytes apart; when the
+// tile's bits are staged in LDS they are interleaved (4 instructions per 8 bytes) so that the two
+// nibbles of a thread are one byte again.  With the number of workers fixed at compile time that
+// byte indexes a 256-row LDS table whose row holds, as eight halves, -1 where the byte's bit is
+// set and +1 where it is clear, and the sum advances by one mixed-precision fused multiply-add
+// per element and worker: fma(+-1, sigma_i, acc) rounds once, and the product is exact, so it
+// is acc +- sigma_i to the bit, the f32 addition in worker order (for any sigma_i, negative ones
+// included).  The n scales of a partition sit in the first n lanes of every wave and reach the
+// multiply-add through a scalar register.  Three workgroups a CU overlap each other's loads,
+// sums and stores.
+#include "tile_rows.hpp"
 #include "sources.hpp"
 
 namespace bpc {
@@ -114,6 +118,12 @@ struct SignServerOp {
     const uint32_t left = g.part_size(part_of(item)) - tile_off(item);
     return __builtin_amdgcn_readfirstlane(left < (uint32_t)kSSTile ? left : (uint32_t)kSSTile);
   }
+  // Within a row: byte offset in e~ of the thread's first four elements (the other four lie
+  // 1024 bytes on), and the elements' numbers.
+  __device__ static uint32_t first_byte() { return (threadIdx.x >> 6) * 2048 + (threadIdx.x & 63) * 16; }
+  __device__ static uint32_t element_of(int u, int c) {
+    return u * (kSSThreads * 8) + (threadIdx.x >> 6) * 512 + (threadIdx.x & 63) * 4 + (c < 4 ? c : 252 + c);
+  }
   // A worker's bits of a tile are fetched in pieces of 1 KiB (16 bytes a lane, 8192 elements);
   // piece j = (worker j / kPieces, part j % kPieces) is fetched by wave j % kSSWaves.
   static constexpr int kPieces = kSSTile / 8192;
@@ -124,8 +134,8 @@ struct SignServerOp {
   __device__ void issue_row(uint32_t item, int u, Raw &raw) const {
     if (EF) {
       const TileBuf eb = row_buf(res + base(item), valid_of(item), u * (kSSThreads * 8), kSSThreads * 8);
-      raw.e[2 * u] = eb.load16(threadIdx.x * 32, 0);
-      raw.e[2 * u + 1] = eb.load16(threadIdx.x * 32 + 16, 0);
+      raw.e[2 * u] = eb.load16<kNonTemporal>(first_byte(), 0);
+      raw.e[2 * u + 1] = eb.load16<kNonTemporal>(first_byte() + 1024, 0);
     }
     if (u != 0) return;
     const uint32_t p = part_of(item);
@@ -167,11 +177,16 @@ struct SignServerOp {
     }
   }
 
-  // The byte of worker i's sign bits that covers this thread's 8 elements of each row.
+  // The two nibbles of worker i's sign bits that cover this thread's 4 + 4 elements of each row,
+  // as one byte.
   __device__ void load_bytes(uint32_t item, int i, uint32_t out[kSRows]) const {
     const uint8_t *bits = msgs.ptr[i] + uniform_off((uint64_t)part_of(item) * g.stride + kHeaderBytes + (tile_off(item) >> 3));
+    const uint32_t at = (threadIdx.x >> 6) * 64 + ((threadIdx.x & 63) >> 1), shift = (threadIdx.x & 1u) * 4u;
 #pragma unroll
-    for (int u = 0; u < kSRows; ++u) out[u] = bits[u * kSSThreads + threadIdx.x];
+    for (int u = 0; u < kSRows; ++u) {
+      const uint32_t a = bits[u * kSSThreads + at], b = bits[u * kSSThreads + at + 32];
+      out[u] = ((a >> shift) & 0xfu) | (((b >> shift) & 0xfu) << 4);
+    }
   }
 
   __device__ void add_worker(const uint32_t byte[kSRows], float sigma_i, float acc[kSPerThread]) const {
@@ -210,10 +225,33 @@ struct SignServerOp {
       const u32x4 *unit = unit_of(sig);
       // (the staging area is free: every wave has passed the barriers that follow the sums of
       // the tile before)
+      // Four lanes hold the 64 bytes of bits of a wave's 512 elements of a row: lanes 0 and 1 of
+      // the four the bytes of the lanes' first elements, lanes 2 and 3 those of their second.
+      // Nibble k of the first 32 bytes and nibble k of the second become byte k: lanes 0 and 1
+      // fetch the words of the lane two up and write 32 bytes each.
 #pragma unroll
       for (int j = 0; j < NW * kPieces; ++j)
-        if ((uint32_t)(j % kSSWaves) == wave)
-          reinterpret_cast<u32x4 *>(staged + (j / kPieces) * kBitsPerWorker + (j % kPieces) * 1024)[lane] = fetched[j / kSSWaves];
+        if ((uint32_t)(j % kSSWaves) == wave) {
+          const u32x4 a = fetched[j / kSSWaves];
+          const uint32_t aw[4] = {a.x, a.y, a.z, a.w};
+          uint32_t out[8];
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {
+            const uint32_t b = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)aw[k], 0x4E, 0xf, 0xf, true);   // quad_perm [2,3,0,1]
+            const uint32_t lo = (aw[k] & 0x0F0F0F0Fu) | ((b & 0x0F0F0F0Fu) << 4);
+            const uint32_t hi = ((aw[k] >> 4) & 0x0F0F0F0Fu) | (b & 0xF0F0F0F0u);
+            out[2 * k] = __builtin_amdgcn_perm(hi, lo, 0x05010400u);
+            out[2 * k + 1] = __builtin_amdgcn_perm(hi, lo, 0x07030602u);
+          }
+          if ((lane & 2) == 0) {
+            u32x4 *dst = reinterpret_cast<u32x4 *>(staged + (j / kPieces) * kBitsPerWorker + (j % kPieces) * 1024 + (lane >> 2) * 64 + (lane & 1) * 32);
+            u32x4 o0, o1;
+            o0.x = out[0]; o0.y = out[1]; o0.z = out[2]; o0.w = out[3];
+            o1.x = out[4]; o1.y = out[5]; o1.z = out[6]; o1.w = out[7];
+            dst[0] = o0;
+            dst[1] = o1;
+          }
+        }
       __syncthreads();
       // every wave for itself: do all workers carry worker 0's scale, and is it short?
       bool counting = false;
@@ -285,14 +323,11 @@ struct SignServerOp {
       const u32x4 ea = raw.e[2 * u], eb = raw.e[2 * u + 1];
       const float e[8] = {__uint_as_float(ea.x), __uint_as_float(ea.y), __uint_as_float(ea.z), __uint_as_float(ea.w),
                           __uint_as_float(eb.x), __uint_as_float(eb.y), __uint_as_float(eb.z), __uint_as_float(eb.w)};
-      // elements of this thread's row segment that exist
-      const uint32_t seg0 = (u * kSSThreads + threadIdx.x) * 8;
-      const uint32_t have = valid > seg0 ? valid - seg0 : 0u;
 #pragma unroll
       for (int c = 0; c < 8; ++c) {
         float mean = acc[8 * u + c] * msgs.inv_n;
         float d = EF ? mean + e[c] : mean;
-        d = (uint32_t)c < have ? d : 0.0f;
+        d = element_of(u, c) < valid ? d : 0.0f;   // (elements past a shorter last partition)
         h.delta[8 * u + c] = d;
         sum += (double)fabsf(d);
       }
@@ -300,19 +335,25 @@ struct SignServerOp {
     return sum;
   }
 
-  // Sign bits of Delta: a byte per thread and row, four neighbouring threads make a word.
+  // Sign bits of Delta: two nibbles per thread and row, each merged with those of the seven lanes
+  // above into a word (32 consecutive elements); the words of the second nibbles lie 8 words on.
   __device__ void early(uint32_t item, Held &h) const {
     uint32_t *bits = reinterpret_cast<uint32_t *>(payload + (uint64_t)part_of(item) * g.stride + kHeaderBytes);
 #pragma unroll
     for (int u = 0; u < kSRows; ++u) {
-      uint32_t byte = 0;
+      uint32_t na = 0, nb = 0;
 #pragma unroll
-      for (int c = 0; c < 8; ++c) byte |= (h.delta[8 * u + c] < 0.0f ? 1u : 0u) << c;
-      // DPP row_shl:n reads lane i+n of the 16-lane row (0 past its end)
-      byte |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)byte, 0x101, 0xf, 0xf, true) << 8;
-      byte |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)byte, 0x102, 0xf, 0xf, true) << 16;
+      for (int c = 0; c < 4; ++c) {
+        na |= (h.delta[8 * u + c] < 0.0f ? 1u : 0u) << c;
+        nb |= (h.delta[8 * u + 4 + c] < 0.0f ? 1u : 0u) << c;
+      }
+      const uint32_t wa = merge8(na), wb = merge8(nb);
       uint32_t *row_words = bits + uniform_off((tile_off(item) >> 5) + u * (kSSThreads * 8 / 32));
-      if ((threadIdx.x & 3) == 0) row_words[threadIdx.x >> 2] = byte;
+      if ((threadIdx.x & 7) == 0) {
+        const uint32_t at = (threadIdx.x >> 6) * 16 + ((threadIdx.x & 63) >> 3);
+        row_words[at] = wa;
+        row_words[at + 8] = wb;
+      }
     }
   }
 
@@ -339,8 +380,8 @@ struct SignServerOp {
     float r[8];
 #pragma unroll
     for (int c = 0; c < 8; ++c) r[c] = h.delta[8 * u + c] - (h.delta[8 * u + c] < 0.0f ? -sigma : sigma);
-    ob.store16(as_u32x4(r[0], r[1], r[2], r[3]), threadIdx.x * 32);
-    ob.store16(as_u32x4(r[4], r[5], r[6], r[7]), threadIdx.x * 32 + 16);
+    ob.store16<kNonTemporal>(as_u32x4(r[0], r[1], r[2], r[3]), first_byte());
+    ob.store16<kNonTemporal>(as_u32x4(r[4], r[5], r[6], r[7]), first_byte() + 1024);
   }
 
 };
