@@ -2,64 +2,223 @@
 // anything heavier would not pay; Section 5.1 lists the half-precision method): every element of
 // q = g + e (worker) or Delta (server) is rounded to the nearest half, ties to even, and the
 // residual is what the rounding dropped (Algorithm 4).  No partition-wide quantity is needed,
-// so one streaming launch does it: 8 consecutive elements a thread and row, one 16-byte store
-// of halves and two of the residual.
+// so one streaming launch does it.  A workgroup takes a tile of 4096 elements as rows of 1024,
+// 4 consecutive elements a thread and row: every access of a wave to the gradient and the
+// residual covers whole cache lines and is marked non-temporal, and all loads of a tile (worker)
+// or of two rows (server: the n messages' halves) are requested before the first is used.
+// Everything goes through buffer descriptors sized to what exists of the tile: elements past a
+// shorter last partition read as zero, encode as zero halves (the record is zero up to the next
+// 16-byte boundary) and are not written to the residual.
 #include "sources.hpp"
+#include "tile_rows.hpp"
 
 namespace bpc {
 
-template <class SRC>
-__global__ __launch_bounds__(kThreads) void fp16_encode_kernel(Geo g, SRC src, uint8_t *payload, float *residual,
+constexpr int kCRowElems = kThreads * 4;
+constexpr int kCRows = kTile / kCRowElems;
+
+// Where a tile lies: its partition, the elements of it that exist, its first element in the flat
+// arrays, and the bytes of the record's halves that belong to it (whole 16-byte chunks).
+struct CastTile {
+  uint32_t p, j0, valid, half_bytes;
+  uint64_t base;
+};
+__device__ inline CastTile cast_tile(const Geo &g) {
+  CastTile t;
+  t.p = __builtin_amdgcn_readfirstlane(blockIdx.x / g.tiles_per_part);
+  t.j0 = __builtin_amdgcn_readfirstlane((blockIdx.x % g.tiles_per_part) * kTile);
+  const uint32_t d = g.part_size(t.p);
+  const uint32_t left = d - t.j0;
+  t.valid = __builtin_amdgcn_readfirstlane(left < (uint32_t)kTile ? left : (uint32_t)kTile);
+  const uint32_t rec_bytes = 4 * (uint32_t)ru4(cdiv(d, 2)) - 2 * t.j0;
+  t.half_bytes = __builtin_amdgcn_readfirstlane(rec_bytes < 2u * kTile ? rec_bytes : 2u * kTile);
+  t.base = uniform_off(g.part_base(t.p) + t.j0);
+  return t;
+}
+
+// Rounds the four values of a thread and row, stores the halves and (EF) what the rounding dropped.
+template <bool EF>
+__device__ inline void cast_store_row(const CastTile &t, int u, const float q[4], uint8_t *halves, float *residual) {
+  uint32_t packed[2];
+  float r[4];
+#pragma unroll
+  for (int c = 0; c < 4; c += 2) {
+    const __half lo = __float2half_rn(q[c]), hi = __float2half_rn(q[c + 1]);
+    packed[c / 2] = (uint32_t)__half_as_ushort(lo) | ((uint32_t)__half_as_ushort(hi) << 16);
+    r[c] = q[c] - __half2float(lo);
+    r[c + 1] = q[c + 1] - __half2float(hi);
+  }
+  const uint32_t row_bytes = u * kCRowElems * 2;
+  const uint32_t in_row = t.half_bytes > row_bytes ? t.half_bytes - row_bytes : 0u;
+  const TileBuf hb(halves + row_bytes, in_row < 2u * kCRowElems ? in_row : 2u * kCRowElems);
+  u32x2 w;
+  w.x = packed[0]; w.y = packed[1];
+  hb.store8(w, threadIdx.x * 8);   // (the rows start 16 bytes off a line: not marked non-temporal)
+  if (EF) row_buf(residual + t.base, t.valid, u * kCRowElems, kCRowElems).store16<kNonTemporal>(as_u32x4(r[0], r[1], r[2], r[3]), threadIdx.x * 16);
+}
+
+template <class GT, bool EF>
+__global__ __launch_bounds__(kThreads) void fp16_worker_kernel(Geo g, const GT *grad, float *residual, uint8_t *payload,
                                                                uint32_t *status) {
   if (blockIdx.x == 0 && threadIdx.x == 0) status[0] = 0;   // no wait in this call: the word reads "none gave up"
-  __shared__ float lds[SRC::kLdsFloats];
-  constexpr int kRowElems = kThreads * 8, kRows = kTile / kRowElems;
-  const uint32_t p = blockIdx.x / g.tiles_per_part;
-  const uint32_t tile = blockIdx.x % g.tiles_per_part;
-  const uint32_t d = g.part_size(p);
-  src.begin(g, p, lds);
-  uint8_t *rec = payload + (uint64_t)p * g.stride;
-  if (tile == 0 && threadIdx.x < 4) reinterpret_cast<uint32_t *>(rec)[threadIdx.x] = 0;
-  uint4 *chunks = reinterpret_cast<uint4 *>(rec + kHeaderBytes);
-  const uint32_t n_chunks = (uint32_t)(ru4(cdiv(d, 2)) / 4);   // the record's half-words, zero past d
-  const uint64_t base = g.part_base(p);
+  const CastTile t = cast_tile(g);
+  uint8_t *rec = payload + (uint64_t)t.p * g.stride;
+  if (t.j0 == 0 && threadIdx.x < 4) reinterpret_cast<uint32_t *>(rec)[threadIdx.x] = 0;
+  const TileBuf gb(grad + t.base, t.valid * (uint32_t)sizeof(GT));
+  const TileBuf eb(residual + (EF ? t.base : 0), EF ? t.valid * 4 : 0);
+  typename Vec4Of<GT>::type gr[kCRows];
+  u32x4 er[kCRows];
 #pragma unroll
-  for (int row = 0; row < kRows; ++row) {
-    const uint32_t j0 = tile * kTile + row * kRowElems + threadIdx.x * 8;
-    if ((j0 >> 3) >= n_chunks) continue;
-    float v[8];
-    source_at8(src, g, p, j0, d, lds, v);
-    uint32_t packed[4];
-    float r[8];
+  for (int u = 0; u < kCRows; ++u) {
+    gr[u] = tile_load4(gb, threadIdx.x * 4 * (uint32_t)sizeof(GT), u * kCRowElems * (uint32_t)sizeof(GT), (const GT *)nullptr);
+    if (EF) er[u] = eb.load16<kNonTemporal>(threadIdx.x * 16, u * kCRowElems * 4);
+  }
+  if constexpr (sizeof(GT) == 2) {
+    // An odd number of halves (the end of the gradient): the descriptor's range check works on
+    // whole dwords, so the last half came back as zero; the lane that owns it fetches it alone.
+    if (t.valid & 1u) {
+      const uint32_t last = t.valid - 1;   // even: the low half of its dword
+      const uint32_t mine = last - threadIdx.x * 4;
 #pragma unroll
-    for (int e = 0; e < 8; e += 2) {
-      const __half lo = __float2half_rn(v[e]), hi = __float2half_rn(v[e + 1]);
-      packed[e / 2] = (uint32_t)__half_as_ushort(lo) | ((uint32_t)__half_as_ushort(hi) << 16);
-      r[e] = v[e] - __half2float(lo);
-      r[e + 1] = v[e + 1] - __half2float(hi);
-    }
-    chunks[j0 >> 3] = make_uint4(packed[0], packed[1], packed[2], packed[3]);
-    if (residual) {
-      if (j0 + 8 <= d) {
-        float4 *out = reinterpret_cast<float4 *>(residual + base + j0);
-        out[0] = make_float4(r[0], r[1], r[2], r[3]);
-        out[1] = make_float4(r[4], r[5], r[6], r[7]);
-      } else {
-#pragma unroll
-        for (int e = 0; e < 8; ++e)
-          if (j0 + e < d) residual[base + j0 + e] = r[e];
+      for (int u = 0; u < kCRows; ++u) {
+        const uint32_t c = mine - u * kCRowElems;
+        if (c < 4u) {
+          const uint32_t h = gb.load2(last * 2, 0);
+          if (c == 0) gr[u].x = h; else gr[u].y = h;
+        }
       }
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < kCRows; ++u) {
+    float q[4];
+    widen4(gr[u], q);
+    if (EF) {
+      float e[4];
+      widen4(er[u], e);
+#pragma unroll
+      for (int c = 0; c < 4; ++c) q[c] = q[c] + e[c];
+    }
+    cast_store_row<EF>(t, u, q, rec + kHeaderBytes + 2 * t.j0, residual);
+  }
+}
+
+struct CastMsgs {
+  const uint8_t *ptr[kMaxWorkers];
+  int n;
+  float inv_n;
+};
+
+// NW > 0: number of workers known at compile time; NW == 0: any number, four at a time.
+template <bool EF, int NW>
+__global__ __launch_bounds__(kThreads) void fp16_server_kernel(Geo g, CastMsgs msgs, float *residual, uint8_t *payload,
+                                                               uint32_t *status) {
+  if (blockIdx.x == 0 && threadIdx.x == 0) status[0] = 0;
+  const CastTile t = cast_tile(g);
+  uint8_t *rec = payload + (uint64_t)t.p * g.stride;
+  if (t.j0 == 0 && threadIdx.x < 4) reinterpret_cast<uint32_t *>(rec)[threadIdx.x] = 0;
+  const uint64_t rec_off = uniform_off((uint64_t)t.p * g.stride + kHeaderBytes + 2 * t.j0);
+  const TileBuf eb(residual + (EF ? t.base : 0), EF ? t.valid * 4 : 0);
+  constexpr int kPair = 2;   // rows whose loads are in flight together
+#pragma unroll 1
+  for (int u0 = 0; u0 < kCRows; u0 += kPair) {
+    float acc[kPair][4];
+    u32x4 er[kPair];
+#pragma unroll
+    for (int k = 0; k < kPair; ++k) {
+      if (EF) er[k] = eb.load16<kNonTemporal>(threadIdx.x * 16, (u0 + k) * kCRowElems * 4);
+#pragma unroll
+      for (int c = 0; c < 4; ++c) acc[k][c] = 0.0f;
+    }
+    if (NW > 0) {
+      u32x2 h[NW > 0 ? NW : 1][kPair];
+#pragma unroll
+      for (int i = 0; i < NW; ++i) {
+        const TileBuf mb(msgs.ptr[i] + rec_off, t.half_bytes);
+#pragma unroll
+        for (int k = 0; k < kPair; ++k) h[i][k] = mb.load8(threadIdx.x * 8, (u0 + k) * kCRowElems * 2);
+      }
+#pragma unroll
+      for (int i = 0; i < NW; ++i) {
+#pragma unroll
+        for (int k = 0; k < kPair; ++k) {
+          float v[4];
+          widen4(h[i][k], v);
+#pragma unroll
+          for (int c = 0; c < 4; ++c) acc[k][c] = acc[k][c] + v[c];
+        }
+      }
+    } else {
+      for (int i0 = 0; i0 < msgs.n; i0 += 4) {
+        u32x2 h[4][kPair];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          if (i0 + i < msgs.n) {
+            const TileBuf mb(msgs.ptr[i0 + i] + rec_off, t.half_bytes);
+#pragma unroll
+            for (int k = 0; k < kPair; ++k) h[i][k] = mb.load8(threadIdx.x * 8, (u0 + k) * kCRowElems * 2);
+          }
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          if (i0 + i < msgs.n) {
+#pragma unroll
+            for (int k = 0; k < kPair; ++k) {
+              float v[4];
+              widen4(h[i][k], v);
+#pragma unroll
+              for (int c = 0; c < 4; ++c) acc[k][c] = acc[k][c] + v[c];
+            }
+          }
+        }
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < kPair; ++k) {
+      float q[4];
+#pragma unroll
+      for (int c = 0; c < 4; ++c) q[c] = acc[k][c] * msgs.inv_n;
+      if (EF) {
+        float e[4];
+        widen4(er[k], e);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) q[c] = q[c] + e[c];
+      }
+      cast_store_row<EF>(t, u0 + k, q, rec + kHeaderBytes + 2 * t.j0, residual);
     }
   }
 }
 
+template <bool EF>
+static hipError_t launch_fp16_server(const Geo &g, const Source &src, uint8_t *payload, uint32_t *status, hipStream_t stream) {
+  CastMsgs m;
+  for (int i = 0; i < kMaxWorkers; ++i) m.ptr[i] = i < src.msgs.n ? src.msgs.ptr[i] : nullptr;
+  m.n = src.msgs.n;
+  m.inv_n = src.msgs.inv_n;
+  switch (m.n) {
+    case 4: fp16_server_kernel<EF, 4><<<g.n_tiles, kThreads, 0, stream>>>(g, m, src.residual, payload, status); break;
+    case 8: fp16_server_kernel<EF, 8><<<g.n_tiles, kThreads, 0, stream>>>(g, m, src.residual, payload, status); break;
+    case 16: fp16_server_kernel<EF, 16><<<g.n_tiles, kThreads, 0, stream>>>(g, m, src.residual, payload, status); break;
+    default: fp16_server_kernel<EF, 0><<<g.n_tiles, kThreads, 0, stream>>>(g, m, src.residual, payload, status); break;
+  }
+  return hipGetLastError();
+}
+
 hipError_t fp16_encode(const Geo &g, const bpc_params_t &, const Source &src, uint8_t *payload, const Workspace &ws,
                        hipStream_t stream) {
-  auto make_server = [&] { return Fp16MsgSource{src.msgs, src.residual, g.stride}; };
-  return with_source(src, make_server, [&](auto s) -> hipError_t {
-    fp16_encode_kernel<decltype(s)><<<g.n_tiles, kThreads, 0, stream>>>(g, s, payload, src.residual, ws.status());
-    return hipGetLastError();
-  });
+  uint32_t *status = ws.status();
+  float *res = src.residual;
+  if (!src.grad) return res ? launch_fp16_server<true>(g, src, payload, status, stream) : launch_fp16_server<false>(g, src, payload, status, stream);
+  if (src.dtype == BPC_F16) {
+    const __half *gr = (const __half *)src.grad;
+    if (res) fp16_worker_kernel<__half, true><<<g.n_tiles, kThreads, 0, stream>>>(g, gr, res, payload, status);
+    else fp16_worker_kernel<__half, false><<<g.n_tiles, kThreads, 0, stream>>>(g, gr, res, payload, status);
+  } else {
+    const float *gr = (const float *)src.grad;
+    if (res) fp16_worker_kernel<float, true><<<g.n_tiles, kThreads, 0, stream>>>(g, gr, res, payload, status);
+    else fp16_worker_kernel<float, false><<<g.n_tiles, kThreads, 0, stream>>>(g, gr, res, payload, status);
+  }
+  return hipGetLastError();
 }
 
 }  // namespace bpc

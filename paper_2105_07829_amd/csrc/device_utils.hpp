@@ -74,6 +74,10 @@ struct TileBuf {
     return __builtin_amdgcn_raw_buffer_load_b32(r, (int)lane_off, (int)row_off, AUX);
   }
   template <int AUX = 0>
+  __device__ uint32_t load2(uint32_t lane_off, uint32_t row_off) const {
+    return (uint32_t)__builtin_amdgcn_raw_buffer_load_b16(r, (int)lane_off, (int)row_off, AUX);
+  }
+  template <int AUX = 0>
   __device__ uint32_t load1(uint32_t lane_off, uint32_t row_off) const {
     return (uint32_t)__builtin_amdgcn_raw_buffer_load_b8(r, (int)lane_off, (int)row_off, AUX);
   }
@@ -83,6 +87,10 @@ struct TileBuf {
   template <int AUX = 0>
   __device__ void store16(u32x4 v, uint32_t lane_off) const {
     __builtin_amdgcn_raw_buffer_store_b128(v, r, (int)lane_off, 0, AUX);
+  }
+  template <int AUX = 0>
+  __device__ void store8(u32x2 v, uint32_t lane_off) const {
+    __builtin_amdgcn_raw_buffer_store_b64(v, r, (int)lane_off, 0, AUX);
   }
   template <int AUX = 0>
   __device__ void store1(uint32_t v, uint32_t lane_off, uint32_t row_off) const {

@@ -195,47 +195,6 @@ __device__ inline void source_at8(const SRC &src, const Geo &g, uint32_t p, uint
   }
 }
 
-// Delta from n FP16 messages.
-struct Fp16MsgSource {
-  WorkerMsgs msgs;
-  const float *res;
-  uint64_t stride;
-  static constexpr int kLdsFloats = 1;
-  __device__ void begin(const Geo &, uint32_t, float *) const {}
-  __device__ float at(const Geo &g, uint32_t p, uint32_t j, const float *) const {
-    float acc = 0.0f;
-    for (int i = 0; i < msgs.n; ++i) {
-      const __half *vals = reinterpret_cast<const __half *>(msgs.ptr[i] + (uint64_t)p * stride + kHeaderBytes);
-      acc = acc + __half2float(vals[j]);
-    }
-    float mean = acc * msgs.inv_n;
-    return res ? mean + res[g.part_base(p) + j] : mean;
-  }
-  // j0 a multiple of 8: one 16-byte load per worker (the record is padded to whole words and
-  // its tail is zero, so reading the 8 halves of the last chunk stays inside it)
-  __device__ void at8(const Geo &g, uint32_t p, uint32_t j0, uint32_t d, const float *, float out[8]) const {
-    float acc[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) acc[e] = 0.0f;
-    for (int i = 0; i < msgs.n; ++i) {
-      float v[8];
-      load8_aligned(reinterpret_cast<const __half *>(msgs.ptr[i] + (uint64_t)p * stride + kHeaderBytes) + j0, v);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) acc[e] = acc[e] + v[e];
-    }
-    const uint64_t base = g.part_base(p);
-    float r[8];
-    if (res && j0 + 8 <= d) load8_aligned(res + base + j0, r);
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const float mean = acc[e] * msgs.inv_n;
-      if (j0 + e >= d) out[e] = 0.0f;
-      else if (!res) out[e] = mean;
-      else out[e] = mean + (j0 + 8 <= d ? r[e] : res[base + j0 + e]);
-    }
-  }
-};
-
 // Delta from n identity messages (plain averaging, Algorithm 1).
 struct IdentityMsgSource {
   WorkerMsgs msgs;
