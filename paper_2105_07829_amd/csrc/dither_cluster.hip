@@ -127,22 +127,30 @@ struct DitherWorkerOp {
     const uint32_t t = threadIdx.x;
     const uint32_t j0 = tile_off(item) + (u * kDWThreads + t) * 4;   // within the partition: one Philox block
     uint32_t nibs = 0, hi[3] = {0, 0, 0};
+    const uint32_t planes = WIDE ? dither_planes(levels) : 0u;
     float r[4];
     if (MODE == 0) {
 #pragma unroll
       for (int c = 0; c < 4; ++c) r[c] = h.q[4 * u + c];
     } else {
-      uint32_t rnd[4];
+      uint32_t rnd[4], code[4];
       rng.block(j0 >> 2, rnd);
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
-        const uint32_t code = dither_quantise<MODE == 2, NAT, WIDE>(h.q[4 * u + c], nu, top_over_nu, top, levels, rnd[c], mag, &r[c]);
-        if (WIDE) {
-          nibs |= (((code >> 6) << 3) | (code & 7u)) << (4 * c);
+        code[c] = dither_quantise<MODE == 2, NAT, WIDE>(h.q[4 * u + c], nu, top_over_nu, top, levels, rnd[c], mag, &r[c]);
+        if (WIDE) nibs |= (((code[c] >> 6) << 3) | (code[c] & 7u)) << (4 * c);
+        else nibs |= code[c] << (4 * c);
+      }
+      if (WIDE) {
+        // bit 3 + k of the levels goes to plane k; most records have one plane (up to 15 levels)
 #pragma unroll
-          for (int k = 0; k < 3; ++k) hi[k] |= ((code >> (3 + k)) & 1u) << c;
-        } else {
-          nibs |= code << (4 * c);
+        for (int c = 0; c < 4; ++c) hi[0] |= ((code[c] >> 3) & 1u) << c;
+        if (planes > 1) {
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            hi[1] |= ((code[c] >> 4) & 1u) << c;
+            hi[2] |= ((code[c] >> 5) & 1u) << c;
+          }
         }
       }
     }
@@ -153,7 +161,6 @@ struct DitherWorkerOp {
     nb.store2(nibs, t * 2, u * (kDWThreads * 2));
     if (WIDE) {
       // a plane holds one bit per element: eight lanes make a word, which lane 8w stores
-      const uint32_t planes = dither_planes(levels);
       for (uint32_t k = 0; k < planes; ++k) {
         const uint32_t pw = merge8(hi[k]);
         const TileBuf pb(rec + dither_plane0(g.part_elems) + k * dither_plane_bytes(g.part_elems) + (tile_off(item) >> 3), kDWTile / 8);
