@@ -55,7 +55,12 @@ struct DitherServerOp {
   static constexpr bool kMax = LINF;
   static constexpr int kRowsPerTile = kDSRows;
   static constexpr int kLutStride = WIDE ? 32 : 16;
-  static constexpr int kTableFloats = kMaxWorkers * 16 + 16;   // decode tables (at most 1024 floats), then the output magnitudes
+  // decode tables (at most 1024 floats), the output magnitudes, and (WIDE) the spread table:
+  // for each value of a plane byte, its even bits at bit 6 of the four bytes of one word and its
+  // odd bits likewise in a second word, i.e. where the "plane bit << 4" of a table index falls
+  // once a word's nibbles sit at bits 2..5 of its bytes
+  static constexpr int kSpreadAt = kMaxWorkers * 16 + 16;
+  static constexpr int kTableFloats = kSpreadAt + (WIDE ? 512 : 0);
   static_assert(!WIDE || (NW > 0 && NW * 32 <= kMaxWorkers * 16), "tables of the wide form must fit");
   static constexpr size_t kMaxDynLds = 0;
   static constexpr bool kPersistent = false;
@@ -125,22 +130,40 @@ struct DitherServerOp {
 #pragma unroll
     for (int u = 0; u < kDSRows; ++u) out[u] = plane[u * kThreads + threadIdx.x];
   }
-  // WIDE: table offset = (plane bit << 4 | nibble) * 4.
+  // WIDE, once per workgroup: the spread table.
+  template <bool W = WIDE, std::enable_if_t<W, int> = 0>
+  __device__ void init(float *table) const {
+    if (threadIdx.x < 256) {
+      uint32_t even = 0, odd = 0;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        even |= ((threadIdx.x >> (2 * k)) & 1u) << (8 * k + 6);
+        odd |= ((threadIdx.x >> (2 * k + 1)) & 1u) << (8 * k + 6);
+      }
+      u32x2 e;
+      e.x = even; e.y = odd;
+      reinterpret_cast<u32x2 *>(table + kSpreadAt)[threadIdx.x] = e;
+    }
+  }
+  // WIDE: table offset = (plane bit << 4 | nibble) * 4: the nibbles at bits 2..5 of the bytes of
+  // two words as in add_worker, the plane bits or-ed in at bit 6 through the spread table.
   __device__ static void add_worker_wide(const uint32_t word[kDSRows], const uint32_t pb[kDSRows], const float *lut_i,
-                                         float acc[kPerThread]) {
+                                         const float *table, float acc[kPerThread]) {
     const char *lut_b = reinterpret_cast<const char *>(lut_i);
+    const u32x2 *spread = reinterpret_cast<const u32x2 *>(table + kSpreadAt);
 #pragma unroll
     for (int u = 0; u < kDSRows; ++u) {
-      const uint32_t even = word[u] << 2, odd = word[u] >> 2;
-      const uint32_t hi = pb[u] << 6;   // bit c of the byte -> bit 6 + c
-      uint32_t off[8];
-      off[0] = byte_and<0>(even, 0x3cu); off[1] = byte_and<0>(odd, 0x3cu);
-      off[2] = byte_and<1>(even, 0x3cu); off[3] = byte_and<1>(odd, 0x3cu);
-      off[4] = byte_and<2>(even, 0x3cu); off[5] = byte_and<2>(odd, 0x3cu);
-      off[6] = byte_and<3>(even, 0x3cu); off[7] = byte_and<3>(odd, 0x3cu);
+      const u32x2 bits = spread[pb[u]];
+      const uint32_t even = ((word[u] << 2) & 0x3c3c3c3cu) | bits.x, odd = ((word[u] >> 2) & 0x3c3c3c3cu) | bits.y;
       float v[8];
-#pragma unroll
-      for (int c = 0; c < 8; ++c) v[c] = *reinterpret_cast<const float *>(lut_b + (off[c] | ((hi >> c) & 0x40u)));
+      v[0] = *reinterpret_cast<const float *>(lut_b + byte_and<0>(even, 0x7cu));
+      v[1] = *reinterpret_cast<const float *>(lut_b + byte_and<0>(odd, 0x7cu));
+      v[2] = *reinterpret_cast<const float *>(lut_b + byte_and<1>(even, 0x7cu));
+      v[3] = *reinterpret_cast<const float *>(lut_b + byte_and<1>(odd, 0x7cu));
+      v[4] = *reinterpret_cast<const float *>(lut_b + byte_and<2>(even, 0x7cu));
+      v[5] = *reinterpret_cast<const float *>(lut_b + byte_and<2>(odd, 0x7cu));
+      v[6] = *reinterpret_cast<const float *>(lut_b + byte_and<3>(even, 0x7cu));
+      v[7] = *reinterpret_cast<const float *>(lut_b + byte_and<3>(odd, 0x7cu));
 #pragma unroll
       for (int c = 0; c < 8; ++c) acc[8 * u + c] = acc[8 * u + c] + v[c];
     }
@@ -188,7 +211,7 @@ struct DitherServerOp {
         }
         if (i0 == 0) fill_luts(p, table);
 #pragma unroll
-        for (int k = 0; k < kGroup; ++k) add_worker_wide(word[k], pb[k], table + (i0 + k) * 32, acc);
+        for (int k = 0; k < kGroup; ++k) add_worker_wide(word[k], pb[k], table + (i0 + k) * 32, table, acc);
       }
     } else if (NW > 8) {
       // many workers: groups of four, so that a lane stays within 80 registers and three
