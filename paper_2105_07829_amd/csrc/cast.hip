@@ -40,13 +40,22 @@ __device__ inline CastTile cast_tile(const Geo &g) {
 template <bool EF>
 __device__ inline void cast_store_row(const CastTile &t, int u, const float q[4], uint8_t *halves, float *residual) {
   uint32_t packed[2];
-  float r[4];
+  float r[4], v[4];
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    // q as an f32 value in a register: left to itself the compiler folds the multiplication by
+    // 1/n that produced it into the conversion (one mixed-precision instruction that rounds the
+    // exact product to a half once), and a mean over 3 workers then differs from the f32 mean
+    // rounded to a half
+    v[c] = q[c];
+    asm("" : "+v"(v[c]));
+  }
 #pragma unroll
   for (int c = 0; c < 4; c += 2) {
-    const __half lo = __float2half_rn(q[c]), hi = __float2half_rn(q[c + 1]);
+    const __half lo = __float2half_rn(v[c]), hi = __float2half_rn(v[c + 1]);
     packed[c / 2] = (uint32_t)__half_as_ushort(lo) | ((uint32_t)__half_as_ushort(hi) << 16);
-    r[c] = q[c] - __half2float(lo);
-    r[c + 1] = q[c + 1] - __half2float(hi);
+    r[c] = v[c] - __half2float(lo);
+    r[c + 1] = v[c + 1] - __half2float(hi);
   }
   const uint32_t row_bytes = u * kCRowElems * 2;
   const uint32_t in_row = t.half_bytes > row_bytes ? t.half_bytes - row_bytes : 0u;

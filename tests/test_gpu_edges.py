@@ -399,6 +399,38 @@ def test_fp16_conversion_at_the_ends_of_the_half_range(gu, orc):
     assert np.array_equal(gu.gpu_decompress(pb, pay_gpu, D).view(np.uint32), orc.decompress(po, pay_ref, D).view(np.uint32))
 
 
+@pytest.mark.parametrize("n", [2, 3, 4, 5, 8, 16])
+@pytest.mark.parametrize("ef", [True, False])
+def test_fp16_server_forms_and_ragged_ends(gu, orc, n, ef):
+    """The FP16 server with its unrolled (4, 8, 16 workers) and its rolled form, on a gradient
+    whose last partition ends inside a row of a tile and on an odd element, with signed zeros
+    among the messages (the sum starts from +0 and runs in worker order, so -0 survives only
+    where it must); then the worker on f16 gradients of the same odd length."""
+    for D in (2 * PE + 4101, PE + 1, 3):
+        po, pb = gu.both_params(orc, "fp16", PE)
+        rs = np.random.default_rng(1000 * n + D)
+        payloads = []
+        for i in range(n):
+            g = (rs.standard_t(3.0, D) * 1e-3).astype(np.float32)
+            g[::7] = -0.0 if i % 2 else 0.0
+            payloads.append(orc.compress(po, g, None))
+        et = (rs.standard_normal(D) * 2e-4).astype(np.float32) if ef else None
+        res_ref = None if et is None else et.copy()
+        pay_ref = orc.server_aggregate([po] * n, payloads, po, res_ref, D)
+        pay_gpu, res_gpu = gu.gpu_server([pb] * n, payloads, pb, et, D)
+        assert defined_equal("fp16", pay_gpu, pay_ref, po, orc, D, PE, {}), (n, D)
+        if ef:
+            assert np.array_equal(res_gpu.view(np.uint32), res_ref.view(np.uint32))
+        g16 = (rs.standard_t(3.0, D) * 1e-3).astype(np.float16)
+        e = (rs.standard_normal(D) * 3e-4).astype(np.float32) if ef else None
+        res_ref = None if e is None else e.copy()
+        pay_ref = orc.compress(po, g16, res_ref)
+        pay_gpu, res_gpu = gu.gpu_compress(pb, g16, e)
+        assert defined_equal("fp16", pay_gpu, pay_ref, po, orc, D, PE, {}), ("worker", D)
+        if ef:
+            assert np.array_equal(res_gpu.view(np.uint32), res_ref.view(np.uint32))
+
+
 @pytest.mark.parametrize("kind", ["sign", "dither", "topk", "identity"])
 @pytest.mark.parametrize("lr", [1e-3, 0.5])
 def test_lans_blocks_of_every_shape_in_one_call(gu, orc, kind, lr):

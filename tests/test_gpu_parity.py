@@ -140,7 +140,7 @@ def test_worker_stage_large_partitions(gu, orc, name, dtype, ef):
 
 @pytest.mark.parametrize("name", sorted(KW))
 @pytest.mark.parametrize("ef", [True, False])
-@pytest.mark.parametrize("n", [1, 4, 16])
+@pytest.mark.parametrize("n", [1, 3, 4, 16])     # (3: a mean that rounds)
 def test_server_stage(gu, orc, name, ef, n):
     for D in SHAPES[:3]:
         kw = dict(KW[name])
