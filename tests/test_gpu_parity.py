@@ -184,7 +184,7 @@ def test_server_stage(gu, orc, name, ef, n):
 
 @pytest.mark.parametrize("name", [k for k in sorted(KW) if base_kind(k) in ("sign", "dither", "natdither")])
 @pytest.mark.parametrize("ef", [True, False])
-@pytest.mark.parametrize("n", [3, 16])
+@pytest.mark.parametrize("n", [3, 8, 16])
 def test_server_stage_large_partitions(gu, orc, name, ef, n):
     """Server stage on partitions that span several tiles of the single-pass kernel, with and
     without a ragged last partition."""
