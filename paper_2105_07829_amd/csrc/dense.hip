@@ -1,5 +1,4 @@
-// Identity "compressor" (with it Algorithms 3 and 4 reduce to plain gradient averaging,
-// Algorithm 1), the dense decode of every message kind, and a zero-fill kernel.
+// The dense decode of every message kind, and a zero-fill kernel.
 #include "sources.hpp"
 
 namespace bpc {
@@ -21,39 +20,6 @@ hipError_t fill_zero(void *ptr, size_t bytes, hipStream_t stream) {
   if (blocks > 4096) blocks = 4096;
   fill_zero_kernel<<<(uint32_t)blocks, kThreads, 0, stream>>>((uint32_t *)ptr, n_words);
   return hipGetLastError();
-}
-
-template <class SRC>
-__global__ __launch_bounds__(kThreads) void identity_encode_kernel(Geo g, SRC src, uint8_t *payload,
-                                                                   float *residual, uint32_t *status) {
-  __shared__ float lds[SRC::kLdsFloats];
-  if (blockIdx.x == 0 && threadIdx.x == 0) status[0] = 0;   // no wait in this call: the word reads "none gave up"
-  const uint32_t p = blockIdx.x / g.tiles_per_part;
-  const uint32_t tile = blockIdx.x % g.tiles_per_part;
-  const uint32_t d = g.part_size(p);
-  src.begin(g, p, lds);
-  uint8_t *rec = payload + (uint64_t)p * g.stride;
-  float *vals = reinterpret_cast<float *>(rec + kHeaderBytes);
-  if (tile == 0 && threadIdx.x < 4) reinterpret_cast<uint32_t *>(rec)[threadIdx.x] = 0;
-  const uint64_t base = g.part_base(p);
-#pragma unroll
-  for (int c = 0; c < kTile / kThreads; ++c) {
-    uint32_t j = tile * kTile + c * kThreads + threadIdx.x;
-    if (j < d) {
-      float v = src.at(g, p, j, lds);
-      vals[j] = v;
-      if (residual) residual[base + j] = v - v;
-    }
-  }
-}
-
-hipError_t identity_encode(const Geo &g, const bpc_params_t &, const Source &src, uint8_t *payload,
-                           const Workspace &ws, hipStream_t stream) {
-  auto make_server = [&] { return IdentityMsgSource{src.msgs, src.residual, g.stride}; };
-  return with_source(src, make_server, [&](auto s) -> hipError_t {
-    identity_encode_kernel<decltype(s)><<<g.n_tiles, kThreads, 0, stream>>>(g, s, payload, src.residual, ws.status());
-    return hipGetLastError();
-  });
 }
 
 // Decode of the bit-packed kinds and of the identity record.  A thread owns 4 consecutive

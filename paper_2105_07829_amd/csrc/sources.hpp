@@ -195,24 +195,6 @@ __device__ inline void source_at8(const SRC &src, const Geo &g, uint32_t p, uint
   }
 }
 
-// Delta from n identity messages (plain averaging, Algorithm 1).
-struct IdentityMsgSource {
-  WorkerMsgs msgs;
-  const float *res;
-  uint64_t stride;
-  static constexpr int kLdsFloats = 1;
-  __device__ void begin(const Geo &, uint32_t, float *) const {}
-  __device__ float at(const Geo &g, uint32_t p, uint32_t j, const float *) const {
-    float acc = 0.0f;
-    for (int i = 0; i < msgs.n; ++i) {
-      const float *vals = reinterpret_cast<const float *>(msgs.ptr[i] + (uint64_t)p * stride + kHeaderBytes);
-      acc = acc + vals[j];
-    }
-    float mean = acc * msgs.inv_n;
-    return res ? mean + res[g.part_base(p) + j] : mean;
-  }
-};
-
 // Delta for the sparse kinds: the decoded messages were summed into a dense f32 buffer first.
 struct DenseSumSource {
   const float *sum;
