@@ -47,8 +47,8 @@ __device__ inline CastTile cast_tile(const Geo &g) {
   const uint32_t left = d - t.j0;
   t.valid = __builtin_amdgcn_readfirstlane(left < (uint32_t)kTile ? left : (uint32_t)kTile);
   if (FMT::kBytes == 2) {
-    const uint32_t rec_bytes = 4 * (uint32_t)ru4(cdiv(d, 2)) - 2 * t.j0;
-    t.rec_bytes = __builtin_amdgcn_readfirstlane(rec_bytes < 2u * kTile ? rec_bytes : 2u * kTile);
+    const uint64_t rec_bytes = 4 * ru4(cdiv(d, 2)) - 2 * (uint64_t)t.j0;   // (a partition may have 2^31 elements)
+    t.rec_bytes = __builtin_amdgcn_readfirstlane(rec_bytes < 2u * kTile ? (uint32_t)rec_bytes : 2u * kTile);
   } else {
     t.rec_bytes = t.valid * 4;
   }
@@ -134,7 +134,7 @@ __global__ __launch_bounds__(kThreads) void cast_worker_kernel(Geo g, const GT *
 #pragma unroll
       for (int c = 0; c < 4; ++c) q[c] = q[c] + e[c];
     }
-    cast_store_row<EF, FMT>(t, u, q, rec + kHeaderBytes + FMT::kBytes * t.j0, residual);
+    cast_store_row<EF, FMT>(t, u, q, rec + kHeaderBytes + (uint64_t)FMT::kBytes * t.j0, residual);
   }
 }
 
@@ -152,7 +152,7 @@ __global__ __launch_bounds__(kThreads) void cast_server_kernel(Geo g, CastMsgs m
   const CastTile t = cast_tile<FMT>(g);
   uint8_t *rec = payload + (uint64_t)t.p * g.stride;
   if (t.j0 == 0 && threadIdx.x < 4) reinterpret_cast<uint32_t *>(rec)[threadIdx.x] = 0;
-  const uint64_t rec_off = uniform_off((uint64_t)t.p * g.stride + kHeaderBytes + FMT::kBytes * t.j0);
+  const uint64_t rec_off = uniform_off((uint64_t)t.p * g.stride + kHeaderBytes + (uint64_t)FMT::kBytes * t.j0);
   const TileBuf eb(residual + (EF ? t.base : 0), EF ? t.valid * 4 : 0);
   constexpr int kPair = FMT::kPair;   // rows whose loads are in flight together
   using Vec = typename FMT::Vec;
@@ -220,7 +220,7 @@ __global__ __launch_bounds__(kThreads) void cast_server_kernel(Geo g, CastMsgs m
 #pragma unroll
         for (int c = 0; c < 4; ++c) q[c] = q[c] + e[c];
       }
-      cast_store_row<EF, FMT>(t, u0 + k, q, rec + kHeaderBytes + FMT::kBytes * t.j0, residual);
+      cast_store_row<EF, FMT>(t, u0 + k, q, rec + kHeaderBytes + (uint64_t)FMT::kBytes * t.j0, residual);
     }
   }
 }

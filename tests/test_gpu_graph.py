@@ -19,7 +19,8 @@ def gu():
 
 @pytest.mark.parametrize("kind,kw", [("sign", {}), ("dither", dict(levels=4, seed=5, stream_id=9)),
                                      ("topk", dict(k_ratio=0.01)),
-                                     ("randk", dict(k_ratio=0.02, value_scale=-1.0, seed=3, stream_id=7))])
+                                     ("randk", dict(k_ratio=0.02, value_scale=-1.0, seed=3, stream_id=7)),
+                                     ("fp16", {}), ("identity", {})])
 def test_step_recorded_in_a_graph_replays_like_eager_calls(gu, kind, kw):
     import torch
     bpc = gu.bpc
