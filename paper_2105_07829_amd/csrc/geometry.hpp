@@ -61,7 +61,8 @@ struct Geo {
 
 inline bool params_valid(const bpc_params_t *p) {
   if (!p) return false;
-  if (p->part_elems == 0 || p->part_elems % 1024 != 0 || p->part_elems > (1ull << 31)) return false;
+  // (2^28 elements at most: byte offsets inside a partition's record and arrays fit 32 bits everywhere)
+  if (p->part_elems == 0 || p->part_elems % 1024 != 0 || p->part_elems > (1ull << 28)) return false;
   switch (p->kind) {
     case BPC_IDENTITY: case BPC_SIGN: case BPC_FP16: return true;
     case BPC_TOPK: case BPC_TOPK16: case BPC_RANDK: return p->k_ratio > 0.0 && p->k_ratio <= 1.0;

@@ -63,6 +63,7 @@ def test_sizes_agree_with_the_oracle(bpc, orc):
 
 def test_invalid_params_are_rejected(bpc):
     bad = [bpc.make_params(bpc.SIGN, 0), bpc.make_params(bpc.SIGN, 1000), bpc.make_params(9, 1024),
+           bpc.make_params(bpc.SIGN, (1 << 28) + 1024),
            bpc.make_params(bpc.TOPK, 1024, k_ratio=0.0), bpc.make_params(bpc.TOPK, 1024, k_ratio=1.5),
            bpc.make_params(bpc.RANDK, 1024, k_ratio=-1.0), bpc.make_params(bpc.DITHER, 1024, levels=0),
            bpc.make_params(bpc.DITHER, 1024, levels=64), bpc.make_params(bpc.NATDITHER, 1024, levels=8),
