@@ -437,6 +437,31 @@ def test_fp16_compressor_is_the_cast_and_its_residual_is_the_rounding_error(orc)
     assert np.array_equal(res, q - orc.decompress(p, pay, d))
 
 
+def test_fp16_server_rounds_the_f32_mean_not_the_exact_one(orc):
+    """Algorithm 4's Delta is an f32 vector and C rounds each of its elements to a half: with a
+    number of workers that is no power of two the mean sum * (1/n) is rounded to f32 first and to
+    a half then.  Against numpy's own two casts, on inputs where rounding the exact product to a
+    half in one go (what a fused multiply-convert does) would give another half: such elements
+    must be in the sample, else the pin would not tell the two readings apart."""
+    n, d = 3, 64 * 4096
+    r = rng(2024)
+    # halves of mixed exponents: their sums carry up to 24 significant bits, and about one product
+    # in 2^13 lies so close to the middle between two halves that the f32 rounding decides
+    msgs = [(r.standard_normal(d) * 1e-3).astype(np.float16) for _ in range(n)]
+    p = orc.make_params(orc.FP16, PE)
+    pays = [orc.compress(p, m.astype(np.float32), None) for m in msgs]
+    acc = np.zeros(d, np.float32)
+    for m in msgs:
+        acc = acc + m.astype(np.float32)
+    two_step = (acc * np.float32(1.0 / n)).astype(np.float16)
+    one_step = (acc.astype(np.float64) * np.float64(np.float32(1.0 / n))).astype(np.float16)   # the product, rounded once
+    assert np.count_nonzero(one_step.view(np.uint16) != two_step.view(np.uint16)) > 0
+    out = orc.server_aggregate([p] * n, pays, p, None, d)
+    strd = orc.partition_stride(p)
+    got = np.concatenate([fmt.fp16_values(fmt.record(out, k, strd), dk) for k, dk in enumerate(fmt.part_sizes(d, PE))])
+    assert np.array_equal(got.view(np.uint16), two_step.view(np.uint16))
+
+
 # ---------------------------------------------------------------- natural dithering
 @pytest.mark.parametrize("norm", ["l2", "linf"])
 def test_natural_dither_unbiased_on_power_of_two_levels(orc, norm):
