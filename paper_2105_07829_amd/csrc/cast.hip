@@ -108,22 +108,7 @@ __global__ __launch_bounds__(kThreads) void cast_worker_kernel(Geo g, const GT *
     gr[u] = tile_load4(gb, threadIdx.x * 4 * (uint32_t)sizeof(GT), u * kCRowElems * (uint32_t)sizeof(GT), (const GT *)nullptr);
     if (EF) er[u] = eb.load16<kNonTemporal>(threadIdx.x * 16, u * kCRowElems * 4);
   }
-  if constexpr (sizeof(GT) == 2) {
-    // An odd number of halves (the end of the gradient): the descriptor's range check works on
-    // whole dwords, so the last half came back as zero; the lane that owns it fetches it alone.
-    if (t.valid & 1u) {
-      const uint32_t last = t.valid - 1;   // even: the low half of its dword
-      const uint32_t mine = last - threadIdx.x * 4;
-#pragma unroll
-      for (int u = 0; u < kCRows; ++u) {
-        const uint32_t c = mine - u * kCRowElems;
-        if (c < 4u) {
-          const uint32_t h = gb.load2(last * 2, 0);
-          if (c == 0) gr[u].x = h; else gr[u].y = h;
-        }
-      }
-    }
-  }
+  patch_last_half<kCRows, kCRowElems>(gb, t.valid, gr);   // (f16 gradients of odd length)
 #pragma unroll
   for (int u = 0; u < kCRows; ++u) {
     float q[4];

@@ -29,6 +29,7 @@ __device__ inline void load8_aligned(const __half *p, float out[8]) {
 // q = g + e, or g alone without error feedback (Algorithm 3).
 template <class T>
 struct GradSource {
+  using Elem = T;
   const T *grad;
   const float *res;
   static constexpr int kLdsFloats = 1;

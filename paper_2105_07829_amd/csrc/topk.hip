@@ -38,6 +38,7 @@
 // sums of the sampled chunks in one sweep over the messages.
 #include "cluster.hpp"
 #include "sources.hpp"
+#include "tile_rows.hpp"
 
 namespace bpc {
 
@@ -439,59 +440,89 @@ struct has_begin_group<SRC, std::void_t<decltype(&SRC::begin_group)>> : std::tru
 // workgroup: a fourth workgroup per compute unit on the server side); the rare key beyond them
 // goes to the partition's histogram directly.
 constexpr int kNearBins = 64;
+// The group is taken as 8 rows of 1024 elements, 4 consecutive elements a thread and row: every
+// 16-byte access of a wave to the gradient, the residual and the buffer covers whole cache lines
+// and is marked non-temporal; everything goes through descriptors of the elements that exist
+// (the rest read as zero and are not written).  All loads of the group are requested before the
+// first is used.  Index order in the list is row, thread, element: a thread's place in its
+// row comes from the wave's ballots, the places of the rows and waves from one scan of their
+// 32 counts.
+constexpr int kLoadRowElems = kThreads * 4;
+constexpr int kLoadRows = kGroupElems / kLoadRowElems;
 template <class SRC, bool LISTED>
 __global__ __launch_bounds__(kThreads) void topk_load_hist1_kernel(Geo g, SRC src, float *buf, uint32_t *hist, uint32_t *state,
                                                                    const uint32_t *guess, uint32_t *groupcnt,
                                                                    uint32_t *cand_idx, uint32_t *cand_val) {
   __shared__ __align__(16) float lds[SRC::kLdsFloats];
   constexpr int kLocalBins = LISTED ? kNearBins : kBins1;
+  constexpr int kWaves = kThreads / 64;
+  static_assert(kLoadRows * kWaves <= 64, "one wave scans the counts of all rows and waves");
   __shared__ uint32_t h[kLocalBins];
-  __shared__ uint32_t scan[kThreads];
+  __shared__ uint32_t run_cnt[kLoadRows * kWaves];   // listed elements per row and wave, then how many come before them
   __shared__ uint32_t off_sh;
-  constexpr int kPieces = kTpgLoad * (kTile / (kThreads * 8));  // pieces of kThreads * 8 elements: 4
-  static_assert(kPieces == 4, "two scans of two 16-bit counts");
   const GroupOf w = group_of<kTpgLoad>(g, blockIdx.x);
   for (int b = threadIdx.x; b < kLocalBins; b += kThreads) h[b] = 0;
   src.begin(g, w.p, lds);
   __syncthreads();
   if (w.tile_lo >= w.tile_hi) return;  // (uniform) past the end of a shorter last partition
-  float v[kPieces][8];
+  const uint32_t j_lo = __builtin_amdgcn_readfirstlane(w.tile_lo * kTile);
+  const uint32_t left = w.d - j_lo;
+  const uint32_t valid = __builtin_amdgcn_readfirstlane(left < kGroupElems ? left : kGroupElems);
+  const uint64_t base = uniform_off(g.part_base(w.p) + j_lo);
+  const bool ef = src.res != nullptr;
+  const TileBuf eb(ef ? src.res + base : nullptr, ef ? valid * 4 : 0);
+  float v[kLoadRows][4];
   if constexpr (has_begin_group<SRC>::value) {
     // the residual's elements are requested first, so they are on their way while the group's
     // sum is formed
+    u32x4 er[kLoadRows];
 #pragma unroll
-    for (int c = 0; c < kPieces; ++c) {
-      const uint32_t j0 = w.tile_lo * kTile + c * (kThreads * 8) + threadIdx.x * 8;
-      src.load_res8(g, w.p, j0 < w.d ? j0 : 0u, w.d, v[c]);
-    }
+    for (int u = 0; u < kLoadRows; ++u) er[u] = eb.load16<kNonTemporal>(threadIdx.x * 16, u * kLoadRowElems * 4);
     src.begin_group(g, w.p, w.tile_lo / kTpgLoad, lds);
+#pragma unroll
+    for (int u = 0; u < kLoadRows; ++u) {
+      const float4 sum = reinterpret_cast<const float4 *>(lds)[u * kThreads + threadIdx.x];
+      const float sv[4] = {sum.x, sum.y, sum.z, sum.w};
+      float e[4];
+      widen4(er[u], e);
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const float mean = sv[c] * src.msgs.inv_n;
+        const float delta = ef ? mean + e[c] : mean;
+        v[u][c] = (uint32_t)(u * kLoadRowElems + c) + threadIdx.x * 4 < valid ? delta : 0.0f;
+      }
+    }
+  } else {
+    using T = typename SRC::Elem;
+    const TileBuf gb(src.grad + base, valid * (uint32_t)sizeof(T));
+    typename Vec4Of<T>::type gr[kLoadRows];
+    u32x4 er[kLoadRows];
+#pragma unroll
+    for (int u = 0; u < kLoadRows; ++u) {
+      gr[u] = tile_load4(gb, threadIdx.x * 4 * (uint32_t)sizeof(T), u * kLoadRowElems * (uint32_t)sizeof(T), (const T *)nullptr);
+      er[u] = eb.load16<kNonTemporal>(threadIdx.x * 16, u * kLoadRowElems * 4);
+    }
+    if constexpr (sizeof(T) == 2) patch_last_half<kLoadRows, kLoadRowElems>(gb, valid, gr);
+#pragma unroll
+    for (int u = 0; u < kLoadRows; ++u) {
+      float x[4], e[4];
+      widen4(gr[u], x);
+      widen4(er[u], e);
+#pragma unroll
+      for (int c = 0; c < 4; ++c) v[u][c] = ef ? x[c] + e[c] : x[c];
+    }
   }
+#pragma unroll
+  for (int u = 0; u < kLoadRows; ++u)
+    row_buf(buf + base, valid, u * kLoadRowElems, kLoadRowElems).store16<kNonTemporal>(as_u32x4(v[u][0], v[u][1], v[u][2], v[u][3]), threadIdx.x * 16);
   const uint32_t G = guess[w.p];
-  const uint64_t base = g.part_base(w.p);
-  uint32_t mask[kPieces];
+  uint32_t mask = 0;   // bit 4 u + c: element c of row u goes to the list
 #pragma unroll
-  for (int c = 0; c < kPieces; ++c) {
-    const uint32_t j0 = w.tile_lo * kTile + c * (kThreads * 8) + threadIdx.x * 8;
-    mask[c] = 0;
-    if (j0 >= w.d) continue;
-    if constexpr (has_begin_group<SRC>::value) {
-      float r[8];
+  for (int u = 0; u < kLoadRows; ++u) {
 #pragma unroll
-      for (int e = 0; e < 8; ++e) r[e] = v[c][e];
-      src.at8_with(j0, w.d, lds, r, v[c]);
-    } else {
-      source_at8(src, g, w.p, j0, w.d, lds, v[c]);
-    }
-    if (j0 + 8 <= w.d) {
-      float4 *dst = reinterpret_cast<float4 *>(buf + base + j0);
-      dst[0] = make_float4(v[c][0], v[c][1], v[c][2], v[c][3]);
-      dst[1] = make_float4(v[c][4], v[c][5], v[c][6], v[c][7]);
-    }
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      if (j0 + e < w.d) {
-        if (j0 + 8 > w.d) buf[base + j0 + e] = v[c][e];
-        const uint32_t key = key_of(v[c][e]);
+    for (int c = 0; c < 4; ++c) {
+      if ((uint32_t)(u * kLoadRowElems + c) + threadIdx.x * 4 < valid) {
+        const uint32_t key = key_of(v[u][c]);
         const bool listed = key >= G;
         if (LISTED) {
           if (listed) {
@@ -502,36 +533,50 @@ __global__ __launch_bounds__(kThreads) void topk_load_hist1_kernel(Geo g, SRC sr
         } else {
           atomicAdd(&h[key >> kShift1], 1u);
         }
-        mask[c] |= (uint32_t)listed << e;
+        mask |= (uint32_t)listed << (4 * u + c);
       }
     }
   }
   if (G != kNoGuess) {
-    // positions in the group's run: pieces in order, threads in order within a piece
-    uint32_t tot01, tot23;
-    const uint32_t ex01 = block_exclusive_scan<kThreads>(__builtin_popcount(mask[0]) | (__builtin_popcount(mask[1]) << 16), scan, &tot01);
-    const uint32_t ex23 = block_exclusive_scan<kThreads>(__builtin_popcount(mask[2]) | (__builtin_popcount(mask[3]) << 16), scan, &tot23);
-    const uint32_t t0 = tot01 & 0xffffu, t1 = tot01 >> 16, t2 = tot23 & 0xffffu, t3 = tot23 >> 16;
-    const uint32_t total = t0 + t1 + t2 + t3;
-    if (threadIdx.x == 0) {
-      const uint32_t off = total ? atomicAdd(&state[w.p * 8 + kStListLen], total) : 0u;
-      off_sh = off;
-      groupcnt[2 * blockIdx.x] = off;
-      groupcnt[2 * blockIdx.x + 1] = total;
+    const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    uint32_t before[kLoadRows];   // listed elements of the row in the wave's lanes below this one
+#pragma unroll
+    for (int u = 0; u < kLoadRows; ++u) {
+      uint32_t mine = 0, all = 0;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const unsigned long long m = __ballot((mask >> (4 * u + c)) & 1u);
+        mine += __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+        all += (uint32_t)__popcll(m);
+      }
+      before[u] = mine;
+      if (lane == 0) run_cnt[u * kWaves + wave] = all;
     }
     __syncthreads();
-    const uint32_t first[kPieces] = {ex01 & 0xffffu, t0 + (ex01 >> 16), t0 + t1 + (ex23 & 0xffffu), t0 + t1 + t2 + (ex23 >> 16)};
+    if (threadIdx.x < 64) {
+      const uint32_t x = threadIdx.x < (uint32_t)(kLoadRows * kWaves) ? run_cnt[threadIdx.x] : 0u;
+      const uint32_t incl = wave_inclusive_scan_u32(x);
+      if (threadIdx.x < (uint32_t)(kLoadRows * kWaves)) run_cnt[threadIdx.x] = incl - x;
+      if (threadIdx.x == 63) {
+        const uint32_t total = incl;
+        const uint32_t off = total ? atomicAdd(&state[w.p * 8 + kStListLen], total) : 0u;
+        off_sh = off;
+        groupcnt[2 * blockIdx.x] = off;
+        groupcnt[2 * blockIdx.x + 1] = total;
+      }
+    }
+    __syncthreads();
     const uint64_t list = (uint64_t)w.p * kTopkListCap;
 #pragma unroll
-    for (int c = 0; c < kPieces; ++c) {
-      uint32_t pos = off_sh + first[c];
-      const uint32_t j0 = w.tile_lo * kTile + c * (kThreads * 8) + threadIdx.x * 8;
+    for (int u = 0; u < kLoadRows; ++u) {
+      uint32_t pos = off_sh + run_cnt[u * kWaves + wave] + before[u];
+      const uint32_t j0 = j_lo + u * kLoadRowElems + threadIdx.x * 4;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        if ((mask[c] >> e) & 1u) {
+      for (int c = 0; c < 4; ++c) {
+        if ((mask >> (4 * u + c)) & 1u) {
           if (pos < kTopkListCap) {
-            cand_idx[list + pos] = j0 + e;
-            cand_val[list + pos] = __float_as_uint(v[c][e]);
+            cand_idx[list + pos] = j0 + c;
+            cand_val[list + pos] = __float_as_uint(v[u][c]);
           }
           ++pos;
         }
