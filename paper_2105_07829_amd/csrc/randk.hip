@@ -12,6 +12,7 @@
 // 32768 elements of Delta in LDS regenerates every draw of its partition instead and keeps
 // those that fall into its slice.
 #include "sources.hpp"
+#include "tile_rows.hpp"
 #include "cluster.hpp"
 #include <hip/hip_runtime.h>
 
@@ -229,28 +230,41 @@ __global__ __launch_bounds__(kThreads) void randk_tile_kernel(Geo g, SRC src, fl
   }
   const uint32_t *tab = table + (uint64_t)p * (kRbMaxBins + 1);
   const uint32_t from = tab[tile], to = tab[tile + 1];
+  // the tile as rows of 1024 elements, 4 consecutive a thread, through descriptors of the
+  // elements that exist: whole-line non-temporal accesses, all loads requested before the first
+  // is used (elements past a shorter last partition read as zero and are not written back)
+  using T = typename SRC::Elem;
+  constexpr int kRowElems = kThreads * 4, kRows = kTile / kRowElems;
+  const uint32_t valid = __builtin_amdgcn_readfirstlane(d - lo < (uint32_t)kTile ? d - lo : (uint32_t)kTile);
+  const uint64_t base = uniform_off(g.part_base(p) + lo);
+  {
+    const bool ef = src.res != nullptr;
+    const TileBuf gb(src.grad + base, valid * (uint32_t)sizeof(T));
+    const TileBuf eb(ef ? src.res + base : nullptr, ef ? valid * 4 : 0);
+    typename Vec4Of<T>::type gr[kRows];
+    u32x4 er[kRows];
 #pragma unroll
-  for (int c = 0; c < kTile / (kThreads * 8); ++c) {
-    const uint32_t r0 = c * (kThreads * 8) + threadIdx.x * 8;
-    float v[8] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
-    if (lo + r0 < d) source_at8(src, g, p, lo + r0, d, nullptr, v);
-    reinterpret_cast<float4 *>(acc + r0)[0] = make_float4(v[0], v[1], v[2], v[3]);
-    reinterpret_cast<float4 *>(acc + r0)[1] = make_float4(v[4], v[5], v[6], v[7]);
+    for (int u = 0; u < kRows; ++u) {
+      gr[u] = tile_load4(gb, threadIdx.x * 4 * (uint32_t)sizeof(T), u * kRowElems * (uint32_t)sizeof(T), (const T *)nullptr);
+      er[u] = eb.load16<kNonTemporal>(threadIdx.x * 16, u * kRowElems * 4);
+    }
+    if constexpr (sizeof(T) == 2) patch_last_half<kRows, kRowElems>(gb, valid, gr);
+#pragma unroll
+    for (int u = 0; u < kRows; ++u) {
+      float x[4], e[4];
+      widen4(gr[u], x);
+      widen4(er[u], e);
+      reinterpret_cast<float4 *>(acc)[u * kThreads + threadIdx.x] =
+          ef ? make_float4(x[0] + e[0], x[1] + e[1], x[2] + e[2], x[3] + e[3]) : make_float4(x[0], x[1], x[2], x[3]);
+    }
   }
   const float scale = value_scale >= 0.0f ? value_scale : (float)d / (float)k;
   float *val = reinterpret_cast<float *>(payload + (uint64_t)p * g.stride + kHeaderBytes);
   randk_apply_draws<kThreads>(acc, lo, lists + (uint64_t)p * g.k_cap, from < k ? from : k, to < k ? to : k, scale, val);
-  const uint64_t base = g.part_base(p) + lo;
 #pragma unroll
-  for (int c = 0; c < kTile / (kThreads * 8); ++c) {
-    const uint32_t r0 = c * (kThreads * 8) + threadIdx.x * 8;
-    if (lo + r0 + 8 <= d) {
-      reinterpret_cast<float4 *>(buf + base + r0)[0] = reinterpret_cast<const float4 *>(acc + r0)[0];
-      reinterpret_cast<float4 *>(buf + base + r0)[1] = reinterpret_cast<const float4 *>(acc + r0)[1];
-    } else {
-      for (int e = 0; e < 8; ++e)
-        if (lo + r0 + e < d) buf[base + r0 + e] = acc[r0 + e];
-    }
+  for (int u = 0; u < kRows; ++u) {
+    const float4 a = reinterpret_cast<const float4 *>(acc)[u * kThreads + threadIdx.x];
+    row_buf(buf + base, valid, u * kRowElems, kRowElems).store16<kNonTemporal>(as_u32x4(a.x, a.y, a.z, a.w), threadIdx.x * 16);
   }
 }
 
@@ -275,23 +289,15 @@ __global__ __launch_bounds__(kRbSumThreads) void randk_sum_binned_kernel(Geo g, 
     to[threadIdx.x] = tab[s + 1];
   }
   constexpr int kEarly = 8192 / (kRbSumThreads * 4);   // 16-byte pieces of a slice of 8192 elements a thread
-  float4 early[kEarly];
+  // the residual and the buffer through descriptors of the slice's elements that exist (what lies
+  // past them reads as zero and is not written): 4 consecutive elements a thread and access,
+  // whole lines a wave, non-temporal
+  const uint64_t at = uniform_off(g.part_base(p) + lo);
+  const TileBuf rb(res ? res + at : nullptr, res ? len * 4 : 0);
+  u32x4 early[kEarly];
   if (EARLY) {
-    const uint64_t at0 = g.part_base(p) + lo;
 #pragma unroll
-    for (int c = 0; c < kEarly; ++c) {
-      const uint32_t q = (c * kRbSumThreads + threadIdx.x) * 4;
-      early[c] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-      if (res) {
-        if (q + 4 <= len) early[c] = *reinterpret_cast<const float4 *>(res + at0 + q);
-        else {
-          early[c].x = q < len ? res[at0 + q] : 0.0f;
-          early[c].y = q + 1 < len ? res[at0 + q + 1] : 0.0f;
-          early[c].z = q + 2 < len ? res[at0 + q + 2] : 0.0f;
-          early[c].w = 0.0f;   // (q + 3 < len would be the whole piece)
-        }
-      }
-    }
+    for (int c = 0; c < kEarly; ++c) early[c] = rb.load16<kNonTemporal>((c * kRbSumThreads + threadIdx.x) * 16, 0);
   }
   for (uint32_t q = threadIdx.x; q < slice / 4; q += kRbSumThreads) reinterpret_cast<float4 *>(acc)[q] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
   __syncthreads();
@@ -314,7 +320,6 @@ __global__ __launch_bounds__(kRbSumThreads) void randk_sum_binned_kernel(Geo g, 
     }
     __syncthreads();
   }
-  const uint64_t at = g.part_base(p) + lo;
   {
     // Delta in LDS, the recompression's draws served from there (list n is the output's),
     // and what is left is the new residual
@@ -324,21 +329,16 @@ __global__ __launch_bounds__(kRbSumThreads) void randk_sum_binned_kernel(Geo g, 
         const uint32_t q = (c * kRbSumThreads + threadIdx.x) * 4;
         const float4 a = *reinterpret_cast<const float4 *>(acc + q);
         const float m0 = a.x * inv_n, m1 = a.y * inv_n, m2 = a.z * inv_n, m3 = a.w * inv_n;
-        *reinterpret_cast<float4 *>(acc + q) = res ? make_float4(m0 + early[c].x, m1 + early[c].y, m2 + early[c].z, m3 + early[c].w)
+        float r[4];
+        widen4(early[c], r);
+        *reinterpret_cast<float4 *>(acc + q) = res ? make_float4(m0 + r[0], m1 + r[1], m2 + r[2], m3 + r[3])
                                                     : make_float4(m0, m1, m2, m3);
       }
     }
     for (uint32_t q = threadIdx.x * 4; !EARLY && q < slice; q += kRbSumThreads * 4) {
       float4 a = *reinterpret_cast<const float4 *>(acc + q);
-      float r[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-      if (res) {
-        if (q + 4 <= len) {
-          const float4 f = *reinterpret_cast<const float4 *>(res + at + q);
-          r[0] = f.x; r[1] = f.y; r[2] = f.z; r[3] = f.w;
-        } else {
-          for (uint32_t e = 0; e < 4; ++e) r[e] = q + e < len ? res[at + q + e] : 0.0f;
-        }
-      }
+      float r[4];
+      widen4(rb.load16<kNonTemporal>(q * 4, 0), r);
       const float m0 = a.x * inv_n, m1 = a.y * inv_n, m2 = a.z * inv_n, m3 = a.w * inv_n;
       *reinterpret_cast<float4 *>(acc + q) = res ? make_float4(m0 + r[0], m1 + r[1], m2 + r[2], m3 + r[3]) : make_float4(m0, m1, m2, m3);
     }
@@ -352,10 +352,10 @@ __global__ __launch_bounds__(kRbSumThreads) void randk_sum_binned_kernel(Geo g, 
     const float scale = value_scale >= 0.0f ? value_scale : (float)d / (float)k;
     randk_apply_draws<kRbSumThreads>(acc, lo, lists + ((uint64_t)n * g.P + p) * g.k_cap, f0, t0, scale,
                                      reinterpret_cast<float *>(payload + (uint64_t)p * g.stride + kHeaderBytes));
+    const TileBuf ob(buf + at, len * 4);
     for (uint32_t q = threadIdx.x * 4; q < len; q += kRbSumThreads * 4) {
-      if (q + 4 <= len) *reinterpret_cast<float4 *>(buf + at + q) = *reinterpret_cast<const float4 *>(acc + q);
-      else
-        for (uint32_t e = q; e < len; ++e) buf[at + e] = acc[e];
+      const float4 a = *reinterpret_cast<const float4 *>(acc + q);
+      ob.store16<kNonTemporal>(as_u32x4(a.x, a.y, a.z, a.w), q * 4);
     }
   }
 }
