@@ -333,17 +333,6 @@ struct TopkMsgsGroupSource : TopkMsgs {
       }
     }
   }
-  __device__ void at8(const Geo &g, uint32_t p, uint32_t j0, uint32_t d, const float *lds, float out[8]) const {
-    float sum[8];
-    load8_aligned(lds + j0 % kGroupElems, sum);
-    finish8(g, p, j0, d, sum, out);
-  }
-  // the same with the residual's elements requested beforehand (load_res8)
-  __device__ void at8_with(uint32_t j0, uint32_t d, const float *lds, const float r[8], float out[8]) const {
-    float sum[8];
-    load8_aligned(lds + j0 % kGroupElems, sum);
-    combine8(j0, d, sum, r, out);
-  }
 };
 
 // The sample pass's view of the same: the sums of the sampled chunks, collected by the sweep of
