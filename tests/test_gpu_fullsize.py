@@ -10,7 +10,9 @@ partition of worker 0, of the server and of the update is compared, and a second
 last one: another Philox stream id, another set of input buffers) on a sample; on the other
 shapes a sample of partitions (first, a middle one, the ragged last one).  A LANS step over
 layer-shaped caller-defined blocks, which cross partitions, is compared over the whole
-gradient.  Same bars as the small tests.
+gradient.  The same pipeline also runs on f32 arrays of more than 4 GiB (sign, dithering, top-k,
+random-k, FP16; the partitions around the 4 GiB offset and the last ones are compared).  Same bars
+as the small tests.
 """
 from concurrent.futures import ThreadPoolExecutor
 
@@ -58,9 +60,29 @@ def record_equal(kind, rec_g, rec_o, d, k, k_cap, pe=0, levels=4):
 @pytest.mark.parametrize("name", ["sign_1m", "resnet50", "vgg16", "bert_base", "bert_large", "bert_large_natural",
                                   "bert_large_5bit", "bert_large_fp16", "bert_base_topk16"])
 def test_full_size_pipeline(env, orc, name):
+    run_pipeline(env, orc, name, env[1].WORKLOADS[name])
+
+
+# Shapes whose f32 arrays (gradient, residuals, parameters, moments) are larger than 4 GiB: every
+# offset beyond 2^32 bytes has to come out of 64-bit arithmetic.  Partition 1024 starts exactly at
+# 4 GiB; the sample takes it, its neighbour below and the last two (the last one ragged).
+BEYOND_4GIB_D = (1 << 30) + 3 * (1 << 20) + 4321
+BEYOND_4GIB = {
+    "sign": dict(kind="sign"), "dither": dict(kind="dither", levels=4), "topk": dict(kind="topk", k_ratio=0.001),
+    "randk": dict(kind="randk", k_ratio=0.001, value_scale=-1.0), "fp16": dict(kind="fp16"),
+}
+
+
+@pytest.mark.parametrize("name", sorted(BEYOND_4GIB))
+def test_arrays_beyond_4_gib(env, orc, name):
+    w = dict(D=BEYOND_4GIB_D, dtype="f32", dist="normal", n_workers=2, ef=True, opt="adam", **BEYOND_4GIB[name])
+    P = (w["D"] + env[1].part_elems("f32") - 1) // env[1].part_elems("f32")
+    run_pipeline(env, orc, name + "_beyond_4gib", w, sample=[0, 1023, 1024, P - 2, P - 1])
+
+
+def run_pipeline(env, orc, name, w, sample=None):
     gu, synth, torch = env
     bpc = gu.bpc
-    w = synth.WORKLOADS[name]
     D, n, kind = w["D"], w["n_workers"], w["kind"]
     pe = synth.part_elems(w["dtype"])
     P = (D + pe - 1) // pe
@@ -82,8 +104,8 @@ def test_full_size_pipeline(env, orc, name):
     p0 = prm_b(0)
     strd = bpc.partition_stride(p0)
     ws = torch.zeros(bpc.workspace_bytes(p0, D, n), dtype=torch.uint8, device=dev)
-    parts = list(range(P)) if name in EVERY_PARTITION else sample_partitions(P)
-    sampled = sample_partitions(P)
+    sampled = sample_partitions(P) if sample is None else sorted(set(sample))
+    parts = list(range(P)) if name in EVERY_PARTITION else sampled
 
     def sl(p):
         return slice(p * pe, min(D, (p + 1) * pe))
