@@ -102,6 +102,56 @@ def test_topk_ties_take_the_lowest_indices(gu, orc, pe, dtype):
     assert np.array_equal(res_gpu.view(np.uint32), res_ref.view(np.uint32))
 
 
+@pytest.mark.parametrize("kind", ["topk", "topk16", "randk"])
+@pytest.mark.parametrize("pe", [PE, BIG_PE])
+def test_sparse_kinds_that_keep_everything(gu, orc, kind, pe):
+    """k_ratio = 1, the largest k there is: top-k then keeps every element (its residual is all
+    zeros, or the half-rounding error), random-k makes d draws with replacement.  Worker, server
+    with two workers, decode and an Adam-style step against the oracle."""
+    kw = dict(k_ratio=1.0)
+    if kind == "randk":
+        kw.update(value_scale=1.0, seed=21, stream_id=(4 << 32) | 9)
+    D = pe + 1234
+    rs = np.random.default_rng(5 + pe)
+    po, pb = gu.both_params(orc, kind, pe, **kw)
+    pays = []
+    for i in range(2):
+        g = (rs.standard_normal(D) * 1e-2).astype(np.float32)
+        e = (rs.standard_normal(D) * 1e-3).astype(np.float32)
+        res_ref = e.copy()
+        pay_ref = orc.compress(po, g, res_ref)
+        pay_gpu, res_gpu = gu.gpu_compress(pb, g, e.copy())
+        assert defined_equal(kind, pay_gpu, pay_ref, po, orc, D, pe, kw), ("worker", i)
+        if kind == "randk":   # (an element drawn three times: q - 3q against ((q - q) - q) - q)
+            assert gu.close(res_gpu, res_ref, 1e-6)
+        else:
+            assert np.array_equal(res_gpu.view(np.uint32), res_ref.view(np.uint32))
+        pays.append(pay_ref)
+    et = (rs.standard_normal(D) * 1e-3).astype(np.float32)
+    res_ref = et.copy()
+    out_ref = orc.server_aggregate([po, po], pays, po, res_ref, D)
+    out_gpu, res_gpu = gu.gpu_server([pb, pb], pays, pb, et, D)
+    if kind == "randk":       # (values of Delta pass through float atomics whose order is free)
+        strd = orc.partition_stride(po)
+        for p, d in enumerate(fmt.part_sizes(D, pe)):
+            kg, vg = fmt.randk_values(fmt.record(out_gpu, p, strd))
+            kr, vr = fmt.randk_values(fmt.record(out_ref, p, strd))
+            assert kg == kr and gu.close(vg, vr, 1e-6)
+        assert gu.close(res_gpu, res_ref, 1e-6)
+    else:
+        assert defined_equal(kind, out_gpu, out_ref, po, orc, D, pe, kw), "server"
+        assert np.array_equal(res_gpu.view(np.uint32), res_ref.view(np.uint32))
+    assert np.array_equal(gu.gpu_decompress(pb, out_ref, D).view(np.uint32), orc.decompress(po, out_ref, D).view(np.uint32))
+    x0 = (rs.standard_normal(D) * 0.02).astype(np.float32)
+    m0 = (rs.standard_normal(D) * 1e-3).astype(np.float32)
+    v0 = (rs.random(D) * 1e-5).astype(np.float32)
+    x, m, v = x0.copy(), m0.copy(), v0.copy()
+    orc.adaptive_update(po, out_ref, D, x, m, v, orc.make_opt(orc.OPT_ADAM, 1e-3, 0.9, 0.999, 1e-8, 0.01, 2))
+    xg, mg, vg = gu.gpu_update(pb, out_ref, x0, m0, v0, gu.bpc.make_opt(gu.bpc.OPT_ADAM, 1e-3, 0.9, 0.999, 1e-8, 0.01, 2))
+    for a, b in ((xg, x), (mg, m), (vg, v)):
+        assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+
+
 @pytest.mark.parametrize("kind", ["topk", "topk16"])
 @pytest.mark.parametrize("case", ["short_list", "mixed", "many_duplicates", "sparse", "large_k"])
 def test_topk_selection_forms(gu, orc, kind, case):
