@@ -265,6 +265,89 @@ def test_update_stage(gu, orc, name, opt_kind):
 
 
 @pytest.mark.parametrize("name", sorted(KW))
+@pytest.mark.parametrize("pe", [1024, 3072, 12288])
+def test_partitions_that_are_no_multiple_of_a_tile(gu, orc, name, pe):
+    """Partition sizes the single-pass kernels do not take (their tiles are 8192 elements): the
+    smallest one, one below a tile of the streaming kernels, one and a half tiles.  Every stage
+    against the oracle: worker (both gradient types), server with three workers, decode, an
+    Adam-style and a LANS step."""
+    bpc = gu.bpc
+    kw = dict(KW[name])
+    kind = base_kind(name)
+    D = 3 * pe + 517
+    ins = []
+    for i in range(3):
+        if "stream_id" in kw and not kw.get("_shared"):
+            kw["stream_id"] = (1 << 32) | i
+        ins.append(gu.both_params(orc, kind, pe, **kw))
+    if "stream_id" in kw:
+        kw["stream_id"] = (1 << 32) | (1 << 16)
+    po, pb = gu.both_params(orc, kind, pe, **kw)
+
+    def with_norms(call):
+        def redo(norms):
+            return call(gu.both_params(orc, kind, pe, norm_override=norms, **kw)[0])
+        return redo
+
+    for dtype in (np.float32, np.float16):
+        g = grads(D, dtype, 31 + pe)
+        e = (rng(7 + pe).standard_normal(D) * 3e-4).astype(np.float32)
+        res_ref = e.copy()
+        pay_ref = orc.compress(po, g, res_ref)
+        pay_gpu, res_gpu = gu.gpu_compress(pb, g, e.copy())
+
+        def again(p2, g=g, e=e, res_ref=res_ref):
+            r2 = e.copy()
+            out = orc.compress(p2, g, r2)
+            res_ref[:] = r2
+            return out
+
+        compare_payload(gu, orc, name, po, pay_gpu, pay_ref, D, pe, with_norms(again))
+        if kind in ("identity", "topk", "topk16", "fp16"):
+            assert np.array_equal(res_gpu.view(np.uint32), res_ref.view(np.uint32))
+        else:
+            assert gu.close(res_gpu, res_ref, REL), (name, dtype)
+    payloads = [orc.compress(ins[i][0], grads(D, np.float32, 100 * i + pe), None) for i in range(3)]
+    et = (rng(78 + pe).standard_normal(D) * 2e-4).astype(np.float32)
+    res_ref = et.copy()
+    pay_ref = orc.server_aggregate([p[0] for p in ins], payloads, po, res_ref, D)
+    pay_gpu, res_gpu = gu.gpu_server([p[1] for p in ins], payloads, pb, et.copy(), D)
+
+    def again_s(p2):
+        r2 = et.copy()
+        out = orc.server_aggregate([p[0] for p in ins], payloads, p2, r2, D)
+        res_ref[:] = r2
+        return out
+
+    if kind == "randk":
+        strd = orc.partition_stride(po)
+        for p, d in enumerate(fmt.part_sizes(D, pe)):
+            kg, vg = fmt.randk_values(fmt.record(pay_gpu, p, strd))
+            kr, vr = fmt.randk_values(fmt.record(pay_ref, p, strd))
+            assert kg == kr and gu.close(vg, vr, REL)
+    else:
+        pay_ref = compare_payload(gu, orc, name, po, pay_gpu, pay_ref, D, pe, with_norms(again_s))
+    if kind in ("identity", "topk", "topk16", "fp16"):
+        assert np.array_equal(res_gpu.view(np.uint32), res_ref.view(np.uint32))
+    else:
+        assert gu.close(res_gpu, res_ref, REL), name
+    assert np.array_equal(gu.gpu_decompress(pb, pay_ref, D).view(np.uint32), orc.decompress(po, pay_ref, D).view(np.uint32))
+    x0 = (rng(1).standard_normal(D) * 0.02).astype(np.float32)
+    m0 = (rng(2).standard_normal(D) * 1e-3).astype(np.float32)
+    v0 = (rng(3).random(D) * 1e-5).astype(np.float32)
+    for ko, kb in ((orc.OPT_ADAM, bpc.OPT_ADAM), (orc.OPT_LANS, bpc.OPT_LANS)):
+        x, m, v = x0.copy(), m0.copy(), v0.copy()
+        orc.adaptive_update(po, pay_ref, D, x, m, v, orc.make_opt(ko, 1e-3, 0.9, 0.999, 1e-8, 0.01, 3))
+        xg, mg, vg = gu.gpu_update(pb, pay_ref, x0, m0, v0, bpc.make_opt(kb, 1e-3, 0.9, 0.999, 1e-8, 0.01, 3))
+        assert np.array_equal(mg.view(np.uint32), m.view(np.uint32))
+        assert np.array_equal(vg.view(np.uint32), v.view(np.uint32))
+        if ko == orc.OPT_ADAM:
+            assert np.array_equal(xg.view(np.uint32), x.view(np.uint32))
+        else:
+            assert gu.lans_step_close(xg, x, x0, np.array([0, pe, 2 * pe, 3 * pe, D]))
+
+
+@pytest.mark.parametrize("name", sorted(KW))
 @pytest.mark.parametrize("opt_kind", ["adam", "lans", "lans_blocks", "lans_long_step", "lans_blocks_long_step"])
 def test_update_stage_large_partitions(gu, orc, name, opt_kind):
     """Partitions of several tiles of the update kernels (16 tiles of the single-pass LANS kernel,
