@@ -23,8 +23,8 @@ constexpr int kCRows = kTile / kCRowElems;
 
 // The two record formats: what a thread holds of a row (4 values), bytes a value, and how many
 // rows of the n messages the server requests at once (registers: 2 or 4 a worker and row).
-struct HalfFmt { using Vec = u32x2; using Elem = __half; static constexpr int kBytes = 2, kPair = 2; };
-struct FloatFmt { using Vec = u32x4; using Elem = float; static constexpr int kBytes = 4, kPair = 1; };
+struct HalfFmt { using Vec = u32x2; static constexpr int kBytes = 2, kPair = 2; };
+struct FloatFmt { using Vec = u32x4; static constexpr int kBytes = 4, kPair = 1; };
 template <class FMT>
 __device__ inline typename FMT::Vec msg_load4(const TileBuf &b, uint32_t row_off) {
   // (default cache policy: the rows of a record start 16 bytes off a line)
@@ -47,7 +47,7 @@ __device__ inline CastTile cast_tile(const Geo &g) {
   const uint32_t left = d - t.j0;
   t.valid = __builtin_amdgcn_readfirstlane(left < (uint32_t)kTile ? left : (uint32_t)kTile);
   if (FMT::kBytes == 2) {
-    const uint64_t rec_bytes = 4 * ru4(cdiv(d, 2)) - 2 * (uint64_t)t.j0;   // (a partition may have 2^31 elements)
+    const uint64_t rec_bytes = 4 * ru4(cdiv(d, 2)) - 2 * (uint64_t)t.j0;
     t.rec_bytes = __builtin_amdgcn_readfirstlane(rec_bytes < 2u * kTile ? (uint32_t)rec_bytes : 2u * kTile);
   } else {
     t.rec_bytes = t.valid * 4;
